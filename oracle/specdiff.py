@@ -1,0 +1,148 @@
+"""One SpecDiff round -- Algorithm 1 of the paper -- as plain fp64 numpy / Python loops.
+Test infrastructure only.
+
+Algorithm 1 in the paper's order: (1) start the gamma-slot block from noise, (2) T reverse
+diffusion steps t = T..1, each one evaluation of M_q on prefix o block, (3) the draft
+tokens are sampled from q and q is kept, (4) M_p scores the gamma+1 prefixes in parallel,
+(5) uniforms r are drawn and n = number of leading accepted tokens (reject when
+r > p(x)/q(x)), (6) p' = p_{n+1}, replaced by norm(max(0, p_{n+1} - q_{n+1})) when a
+rejection happened, (7) one token from p', return n draft tokens + that token.
+
+Readings where the paper is silent or inconsistent (each also listed in the design notes):
+  * the drafter is a *masked* diffusion model (Section 4.1), so the start state is an
+    all-[MASK] block, not Gaussian noise;
+  * reverse step j (time t = j/T, linear schedule alpha_t = 1 - t): every still-masked slot
+    is revealed with probability 1/j, independently; a revealed slot draws its token from
+    the softmax row M_q gives it at that step; revealed slots never change again
+    (absorbing-state reverse process of masked diffusion); step j = 1 reveals all;
+  * q_k is the row token k was drawn from (so that x_k ~ q_k, which the acceptance
+    identity needs); q crosses the draft/verify boundary as fp32;
+  * indices are relative: P[0..gamma], n in [0, gamma], residual iff n < gamma;
+  * accept iff r * q(x) <= p(x), the product and the comparison in fp32;
+  * sampling = inverse CDF over ascending token id with a strict '>' crossing;
+  * a residual whose mass is zero (impossible in exact arithmetic) falls back to p.
+"""
+import numpy as np
+
+from . import philox
+from .transformer import softmax_rows
+
+
+def invcdf(w, u):
+    """Smallest v with sum_{v'<=v} w[v'] > u * sum(w).  Returns (v, margin): margin is the
+    distance of u*sum(w) from the nearer edge of v's CDF interval, divided by sum(w) --
+    how far the decision is from flipping to a neighbouring token."""
+    c = np.cumsum(np.asarray(w, dtype=np.float64))
+    total = c[-1]
+    target = u * total
+    v = int(np.searchsorted(c, target, side="right"))     # first index with c[v] > target
+    if v >= c.size:                                        # rounding only
+        v = int(np.flatnonzero(np.asarray(w) > 0)[-1])
+    lo = c[v - 1] if v > 0 else 0.0
+    margin = min(target - lo, c[v] - target) / total
+    return v, float(margin)
+
+
+def draft_with_uniforms(drafter_logits, prefix, gamma, T, ua, ub, mask_id, skip_when_done=True):
+    """Steps (1)-(3).  drafter_logits(tokens, t) -> [gamma, V] logits of the block rows for the
+    sequence prefix o block.  ua, ub: [T+1, gamma] uniforms indexed [j, k] (row 0 unused).
+    Returns (z int64[gamma], q fp32[gamma, V], margins fp64[gamma], n_forwards)."""
+    prefix = np.asarray(prefix, dtype=np.int64)
+    z = np.full(gamma, mask_id, dtype=np.int64)
+    q = None
+    margins = np.zeros(gamma)
+    n_forwards = 0
+    for j in range(T, 0, -1):
+        masked = np.flatnonzero(z == mask_id)
+        if masked.size == 0 and skip_when_done:
+            continue                                   # nothing left to reveal: the step is a no-op
+        logits = np.asarray(drafter_logits(np.concatenate([prefix, z]), j / T), dtype=np.float64)
+        n_forwards += 1
+        if q is None:
+            q = np.zeros((gamma, logits.shape[1]), dtype=np.float64)
+        for k in masked:
+            if j == 1 or ua[j, k] * j < 1.0:           # reveal with probability 1/j
+                pi = softmax_rows(logits[k])
+                z[k], margins[k] = invcdf(pi, ub[j, k])
+                q[k] = pi
+    return z, q.astype(np.float32), margins, n_forwards
+
+
+def accept_flags(P, q, draft, r):
+    """Step (5), per position: accept iff fl32(r * q_k(x_k)) <= fl32(p_k(x_k))."""
+    gamma = len(draft)
+    flags = np.zeros(gamma, dtype=bool)
+    for k in range(gamma):
+        px = np.float32(P[k][draft[k]])
+        qx = np.float32(q[k][draft[k]])
+        flags[k] = (np.float32(r[k]) * qx) <= px
+    return flags
+
+
+def accept_margins(P, q, draft, r):
+    """Relative distance |r*q(x) - p(x)| / p(x) of every acceptance test from flipping."""
+    out = np.zeros(len(draft))
+    for k in range(len(draft)):
+        px, qx = float(P[k][draft[k]]), float(q[k][draft[k]])
+        out[k] = abs(r[k] * qx - px) / px if px > 0 else np.inf
+    return out
+
+
+def residual(p_row, q_row):
+    """Step (6): unnormalised max(0, p - q); falls back to p if nothing is left."""
+    R = np.maximum(0.0, np.asarray(p_row, dtype=np.float64) - np.asarray(q_row, dtype=np.float64))
+    return (R, False) if R.sum() > 0.0 else (np.asarray(p_row, dtype=np.float64), True)
+
+
+def verify_with_uniforms(P, q, draft, r, u_final):
+    """Steps (5)-(7).  P: [gamma+1, V] target probabilities (row k = next-token law after
+    prefix o draft[:k]); q: [gamma, V]; r: [gamma]; u_final: [gamma+1], entry n is used.
+    Returns (n, token, margin, fell_back)."""
+    gamma = len(draft)
+    flags = accept_flags(P, q, draft, r)
+    rejected = np.flatnonzero(~flags)
+    n = int(rejected[0]) if rejected.size else gamma
+    if n < gamma:
+        w, fell_back = residual(P[n], q[n])
+    else:
+        w, fell_back = np.asarray(P[gamma], dtype=np.float64), False
+    tok, margin = invcdf(w, u_final[n])
+    return n, tok, margin, fell_back
+
+
+# ---------------------------------------------------------------------------------------
+# The two boundary calls, with uniforms taken from the counter-based generator.
+# ---------------------------------------------------------------------------------------
+def draft_uniforms(seed, batch, gamma, T):
+    ua = np.zeros((T + 1, gamma))
+    ub = np.zeros((T + 1, gamma))
+    for j in range(1, T + 1):
+        ua[j], ub[j] = philox.uniforms(seed, philox.STREAM_DRAFT, batch, j, np.arange(gamma))
+    return ua, ub
+
+
+def verify_uniforms(seed, batch, gamma):
+    r, u = philox.uniforms(seed, philox.STREAM_VERIFY, batch, 0, np.arange(gamma + 1))
+    return r[:gamma], u
+
+
+def oracle_draft(drafter_logits, prefix, gamma, T, seed, mask_id, batch=0):
+    ua, ub = draft_uniforms(seed, batch, gamma, T)
+    return draft_with_uniforms(drafter_logits, prefix, gamma, T, ua, ub, mask_id)
+
+
+def oracle_verify(target_logits, prefix, draft, q, seed, batch=0):
+    """target_logits(tokens, rows) -> logits [len(rows), V] of the causal model at those
+    positions of `tokens`.  Rows L-1 .. L-1+gamma of prefix o draft give P[0..gamma]."""
+    prefix = np.asarray(prefix, dtype=np.int64)
+    draft = np.asarray(draft, dtype=np.int64)
+    L, gamma = prefix.size, draft.size
+    rows = np.arange(L - 1, L + gamma)
+    P = softmax_rows(np.asarray(target_logits(np.concatenate([prefix, draft]), rows), dtype=np.float64))
+    r, u = verify_uniforms(seed, batch, gamma)
+    return verify_with_uniforms(P, q, draft, r, u)
+
+
+def expected_tokens(alpha, gamma):
+    """Appendix A, Eq. (2): expected tokens per round for i.i.d. acceptance rate alpha."""
+    return (1.0 - alpha ** (gamma + 1)) / (1.0 - alpha) if alpha < 1.0 else gamma + 1.0
