@@ -1,0 +1,167 @@
+/*
+ * specdiff.h -- C ABI of the MI355X (gfx950) implementation of one Speculative Diffusion
+ * Decoding round (arxiv 2408.05636, Algorithm 1).
+ *
+ * Conventions
+ *   - Every function returns an sd_status (0 = SD_OK) unless stated; nothing aborts or throws.
+ *   - "host" pointers are ordinary CPU memory owned by the caller; "device" pointers are HIP
+ *     device memory of the current device, owned by the caller unless stated otherwise.
+ *   - Token ids are int32.  The output vocabulary is [0, vocab); the diffusion drafter's
+ *     absorbing [MASK] state has id == vocab and is never an output class.
+ *   - Logit / probability rows have a leading dimension ld = sd_vocab_pad(vocab) floats
+ *     (vocab rounded up to 256); columns >= vocab are undefined.
+ *   - Batches are ragged: sequence b has prefix_len[b] tokens, stored back to back in `prefix`.
+ *   - All work is enqueued on the HIP stream given at creation (or per call for the
+ *     stand-alone kernels); calls that return host data synchronise that stream.
+ *   - Random draws come from Philox4x32-10 keyed by `seed`, counter =
+ *     (position k, step j, sequence b, stream) with stream 1 = draft (word 0: reveal decision,
+ *     word 1: token sample) and stream 2 = verify (word 0: acceptance, word 1: final token);
+ *     a uniform is (word >> 8) * 2^-24.
+ */
+#ifndef SPECDIFF_H
+#define SPECDIFF_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum sd_status {
+    SD_OK = 0,
+    SD_ERR_ARG = 1,       /* NULL pointer, non-positive size, unknown enum                         */
+    SD_ERR_SHAPE = 2,     /* batch / gamma / length beyond what the handle or the model allows     */
+    SD_ERR_TOKEN = 3,     /* a token id outside the vocabulary                                      */
+    SD_ERR_STATE = 4,     /* call needs state that is missing (e.g. q of a previous sd_draft)       */
+    SD_ERR_WORKSPACE = 5, /* workspace too small or misaligned                                      */
+    SD_ERR_HIP = 6        /* a HIP runtime call failed; see sd_last_error                           */
+} sd_status;
+
+enum { SD_ARCH_GPT2 = 0, SD_ARCH_LLAMA = 1 };
+enum { SD_DTYPE_F32 = 0, SD_DTYPE_BF16 = 1 };
+
+/* Shape of one transformer.  The paper names the model families (Evaluation, Experimental
+ * Setup: GPT-2 XL / GPT-Neo / Vicuna targets, MDLM drafter) but not their arithmetic; see
+ * the weight inventory below for what each field selects. */
+typedef struct sd_model_config {
+    int32_t arch;          /* SD_ARCH_GPT2: LayerNorm, biases, tanh-GELU MLP, learned positions
+                              SD_ARCH_LLAMA: RMSNorm, no biases, SwiGLU, rotary positions, GQA  */
+    int32_t dtype;         /* storage type of matrices / embeddings and of the KV cache         */
+    int32_t n_layer, d_model, n_head, n_kv_head, d_ff, vocab, n_ctx;
+    int32_t bidirectional; /* 1 = diffusion drafter M_q: non-causal attention, an extra embedding
+                              row for [MASK], additive timestep embedding; 0 = causal target M_p */
+    float norm_eps;
+    float rope_theta;
+} sd_model_config;
+
+typedef struct sd_handle sd_handle;
+
+int32_t sd_vocab_pad(int32_t vocab);
+
+/* ---- weight buffer layout (host logic only; no GPU needed) -----------------------------
+ * A model's parameters live in ONE device buffer.  Tensor i of sd_weight_count() sits at
+ * byte offset `offset` (256-byte aligned), row-major [rows, cols] (cols contiguous; linear
+ * layers are stored [out_features, in_features]).  elem_bytes is 4 for gains and biases
+ * (always fp32) and 4 or 2 for matrices and embeddings according to dtype (bf16 = upper 16
+ * bits of the fp32 pattern).  Names: wte, wpe, t_w1, t_b1, t_w2, t_b2, l<i>.ln1_g, l<i>.ln1_b,
+ * l<i>.w_qkv, l<i>.b_qkv, l<i>.w_o, l<i>.b_o, l<i>.ln2_g, l<i>.ln2_b, l<i>.w_fc, l<i>.b_fc,
+ * l<i>.w_gate, l<i>.w_up, l<i>.w_proj, l<i>.b_proj, lnf_g, lnf_b, w_head. */
+int32_t sd_weight_count(const sd_model_config *cfg);
+int32_t sd_weight_desc(const sd_model_config *cfg, int32_t index, char *name, int32_t name_cap,
+                       int64_t *rows, int64_t *cols, int32_t *elem_bytes, int64_t *offset);
+int64_t sd_weight_bytes(const sd_model_config *cfg);
+
+/* Bytes of device workspace sd_create needs for these models and limits (0 on bad input). */
+int64_t sd_workspace_bytes(const sd_model_config *target, const sd_model_config *drafter,
+                           int32_t max_batch, int32_t gamma_max);
+
+/* Create a decoder.  target_w / drafter_w: device weight buffers in the layout above,
+ * borrowed -- the caller keeps them alive and unchanged.  workspace: device memory,
+ * 256-byte aligned, at least sd_workspace_bytes(); borrowed for the handle's lifetime and
+ * holding every activation, the target's KV cache and q.  hip_stream: a hipStream_t (NULL =
+ * default stream).  The library itself allocates only small pinned host staging buffers. */
+int32_t sd_create(const sd_model_config *target, const sd_model_config *drafter,
+                  const void *target_w, const void *drafter_w, int32_t max_batch, int32_t gamma_max,
+                  void *workspace, int64_t workspace_bytes, void *hip_stream, sd_handle **out);
+void sd_destroy(sd_handle *h);
+/* Library-owned message describing the last failure on this handle (never NULL). */
+const char *sd_last_error(const sd_handle *h);
+
+/* Fill the target's KV cache for tokens [0, prefix_len[b]-1) of every sequence (prompt
+ * processing; Table 1 of the paper costs a round "following the initial prompt", so this is
+ * outside the timed round).  prefix, prefix_len: host. */
+int32_t sd_prefill(sd_handle *h, int32_t batch, const int32_t *prefix, const int32_t *prefix_len);
+
+/* Algorithm 1, drafting part: start from gamma [MASK] slots, run T reverse-diffusion steps
+ * j = T..1 (time j/T), each one bidirectional forward of the drafter over prefix o block,
+ * a vocabulary softmax on the block rows and the reveal / categorical-sampling step: a
+ * masked slot is revealed at step j with probability 1/j (always at j = 1), its token is
+ * drawn by inverse CDF from that step's softmax row, which becomes q_k.
+ *   draft_out: host [batch, gamma]; qtok_out: host [batch, gamma] = q_k(x_k), may be NULL;
+ *   q_dev_out: receives a device pointer to q, fp32 [batch, gamma, ld], library-owned,
+ *   valid until the next sd_draft / sd_round on this handle. */
+int32_t sd_draft(sd_handle *h, int32_t batch, const int32_t *prefix, const int32_t *prefix_len,
+                 int32_t gamma, int32_t T, uint64_t seed, int32_t *draft_out, float *qtok_out,
+                 const float **q_dev_out);
+
+/* Algorithm 1, verification part: one causal forward of the target over the last prefix
+ * token and the gamma draft tokens against its KV cache (prefilled on demand when the cache
+ * does not hold this prefix), giving gamma+1 next-token laws P[0..gamma]; token k is accepted
+ * iff r_k * q_k(x_k) <= P[k](x_k) (fp32 product); n = number of leading accepted tokens; the
+ * extra token is drawn from norm(max(0, P[n] - q_n)) if n < gamma, else from P[gamma].
+ *   draft: host [batch, gamma]; q_dev: device fp32 [batch, gamma, ld];
+ *   n_accepted_out, token_out: host [batch]. */
+int32_t sd_verify(sd_handle *h, int32_t batch, const int32_t *prefix, const int32_t *prefix_len,
+                  int32_t gamma, const int32_t *draft, const float *q_dev, uint64_t seed,
+                  int32_t *n_accepted_out, int32_t *token_out);
+
+/* sd_draft followed by sd_verify with the same seed, the draft and q handed over on the
+ * device and a single synchronisation at the end.  Same results as the two calls. */
+int32_t sd_round(sd_handle *h, int32_t batch, const int32_t *prefix, const int32_t *prefix_len,
+                 int32_t gamma, int32_t T, uint64_t seed, int32_t *draft_out,
+                 int32_t *n_accepted_out, int32_t *token_out);
+
+/* ---- single steps of the path, for parity checks and profiling --------------------------- */
+
+/* One drafter evaluation M_q(prefix o block, t = step/T) (Algorithm 1, loop body).
+ * tokens: host, sequences back to back, sequence b = its prefix followed by gamma block
+ * slots (ids in [0, vocab], vocab = [MASK]); seq_len[b] includes the gamma block slots.
+ * logits_dev_out: device fp32 [batch*gamma, ld], row b*gamma+k = slot k; library-owned. */
+int32_t sd_drafter_logits(sd_handle *h, int32_t batch, const int32_t *tokens, const int32_t *seq_len,
+                          int32_t gamma, int32_t step, int32_t T, const float **logits_dev_out);
+
+/* The target's parallel scoring M_p(x_{0:i}) .. M_p(x_{0:i+gamma}) (Algorithm 1).
+ * logits_dev_out: device fp32 [batch*(gamma+1), ld], row b*(gamma+1)+k = logits of P[k]. */
+int32_t sd_target_logits(sd_handle *h, int32_t batch, const int32_t *prefix, const int32_t *prefix_len,
+                         int32_t gamma, const int32_t *draft, const float **logits_dev_out);
+
+/* Stand-alone kernels on caller-provided device rows (all pointers device, asynchronous on
+ * hip_stream).  scratch: device, sd_sampling_scratch_bytes(rows, vocab) bytes. */
+int64_t sd_sampling_scratch_bytes(int32_t rows, int32_t vocab);
+
+/* Reveal / sample step j of the drafting loop on logits [batch*gamma, ld]:
+ * for every slot with z == vocab ([MASK]) that is revealed at this step, z <- token,
+ * q row <- softmax row, qtok <- its probability; other slots are left untouched. */
+int32_t sd_unmask_sample(const float *logits, int32_t batch, int32_t gamma, int32_t vocab,
+                         int32_t step, uint64_t seed, int32_t *z, float *q, float *qtok,
+                         void *scratch, int64_t scratch_bytes, void *hip_stream);
+
+/* Acceptance, first rejection and residual / bonus sampling on target logits
+ * [batch*(gamma+1), ld], q [batch*gamma, ld] and draft [batch, gamma];
+ * writes n_accepted[batch] and token[batch]. */
+int32_t sd_accept_resample(const float *p_logits, const float *q, const int32_t *draft,
+                           int32_t batch, int32_t gamma, int32_t vocab, uint64_t seed,
+                           int32_t *n_accepted, int32_t *token,
+                           void *scratch, int64_t scratch_bytes, void *hip_stream);
+
+/* y = epilogue(x W^T + bias): the dense contraction used by every QKV / MLP / LM-head layer.
+ * x: [m, k] (dtype), w: [n, k] (dtype), bias: fp32 [n] or NULL.
+ * epilogue 0: y (dtype) = acc; 1: y (dtype) = gelu_tanh(acc); 2: y (fp32) += acc (residual);
+ * 3: y (fp32) = acc.  ldy in elements of y. */
+int32_t sd_linear(int32_t dtype, const void *x, const void *w, const float *bias, void *y,
+                  int32_t m, int32_t n, int32_t k, int32_t ldy, int32_t epilogue, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPECDIFF_H */

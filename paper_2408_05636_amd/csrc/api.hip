@@ -1,0 +1,768 @@
+// C ABI of the SpecDiff round (see include/specdiff.h): weight layout, workspace carving, the two
+// forward passes and the draft / verify drivers.  Host code only enqueues kernels; every step of
+// Algorithm 1 runs on the device.
+#include <string.h>
+
+#include <string>
+#include <vector>
+
+#include "common.h"
+
+using namespace sd;
+
+namespace {
+
+constexpr int kMaxSteps = 256;   // upper limit of T
+
+// ------------------------------------------------------------------------------------------
+// weight layout
+// ------------------------------------------------------------------------------------------
+struct TensorDesc {
+    std::string name;
+    int64_t rows, cols;
+    int elem;
+    int64_t off;
+};
+
+bool config_ok(const sd_model_config* c) {
+    if (!c) return false;
+    if (c->arch != SD_ARCH_GPT2 && c->arch != SD_ARCH_LLAMA) return false;
+    if (c->dtype != SD_DTYPE_F32 && c->dtype != SD_DTYPE_BF16) return false;
+    if (c->n_layer <= 0 || c->d_model <= 0 || c->n_head <= 0 || c->n_kv_head <= 0 || c->d_ff <= 0 || c->vocab <= 0 ||
+        c->n_ctx <= 0)
+        return false;
+    if (c->d_model % c->n_head || c->n_head % c->n_kv_head) return false;
+    const int dh = c->d_model / c->n_head;
+    if (dh != 32 && dh != 64 && dh != 128) return false;
+    if (c->d_model % 16 || c->d_ff % 16) return false;
+    if (c->d_model > 8192) return false;
+    if (c->bidirectional && c->arch != SD_ARCH_GPT2) return false;
+    if (c->vocab > kChunk * 512) return false;
+    return true;
+}
+
+void build_layout(const sd_model_config& c, std::vector<TensorDesc>& out, int64_t& total) {
+    const int ew = c.dtype == SD_DTYPE_BF16 ? 2 : 4;
+    const int64_t d = c.d_model, F = c.d_ff, dkv = (int64_t)c.n_kv_head * (c.d_model / c.n_head);
+    int64_t off = 0;
+    auto add = [&](const std::string& name, int64_t rows, int64_t cols, int elem) {
+        out.push_back(TensorDesc{name, rows, cols, elem, off});
+        off = align_up(off + rows * cols * elem, 256);
+    };
+    add("wte", c.vocab + (c.bidirectional ? 1 : 0), d, ew);
+    if (c.arch == SD_ARCH_GPT2) add("wpe", c.n_ctx, d, ew);
+    if (c.bidirectional) {
+        add("t_w1", d, d, ew); add("t_b1", 1, d, 4);
+        add("t_w2", d, d, ew); add("t_b2", 1, d, 4);
+    }
+    for (int i = 0; i < c.n_layer; ++i) {
+        const std::string p = "l" + std::to_string(i) + ".";
+        if (c.arch == SD_ARCH_GPT2) {
+            add(p + "ln1_g", 1, d, 4); add(p + "ln1_b", 1, d, 4);
+            add(p + "w_qkv", d + 2 * dkv, d, ew); add(p + "b_qkv", 1, d + 2 * dkv, 4);
+            add(p + "w_o", d, d, ew); add(p + "b_o", 1, d, 4);
+            add(p + "ln2_g", 1, d, 4); add(p + "ln2_b", 1, d, 4);
+            add(p + "w_fc", F, d, ew); add(p + "b_fc", 1, F, 4);
+            add(p + "w_proj", d, F, ew); add(p + "b_proj", 1, d, 4);
+        } else {
+            add(p + "ln1_g", 1, d, 4);
+            add(p + "w_qkv", d + 2 * dkv, d, ew);
+            add(p + "w_o", d, d, ew);
+            add(p + "ln2_g", 1, d, 4);
+            add(p + "w_gate", F, d, ew);
+            add(p + "w_up", F, d, ew);
+            add(p + "w_proj", d, F, ew);
+        }
+    }
+    add("lnf_g", 1, d, 4);
+    if (c.arch == SD_ARCH_GPT2) add("lnf_b", 1, d, 4);
+    add("w_head", c.vocab, d, ew);
+    total = off;
+}
+
+struct Layer {
+    const float *ln1_g = nullptr, *ln1_b = nullptr, *b_qkv = nullptr, *b_o = nullptr, *ln2_g = nullptr, *ln2_b = nullptr,
+                *b_fc = nullptr, *b_proj = nullptr;
+    const void *w_qkv = nullptr, *w_o = nullptr, *w_fc = nullptr, *w_proj = nullptr;   // w_fc: [F,d] or gate|up [2F,d]
+};
+
+struct Model {
+    sd_model_config c;
+    int dh, dq, dkv, ld, ew;
+    const void *wte = nullptr, *wpe = nullptr, *t_w1 = nullptr, *t_w2 = nullptr, *w_head = nullptr;
+    const float *t_b1 = nullptr, *t_b2 = nullptr, *lnf_g = nullptr, *lnf_b = nullptr;
+    std::vector<Layer> L;
+};
+
+bool bind_model(Model& m, const sd_model_config& c, const void* base) {
+    m.c = c;
+    m.dh = c.d_model / c.n_head;
+    m.dq = c.d_model;
+    m.dkv = c.n_kv_head * m.dh;
+    m.ld = vocab_pad(c.vocab);
+    m.ew = c.dtype == SD_DTYPE_BF16 ? 2 : 4;
+    m.L.assign(c.n_layer, Layer());
+    std::vector<TensorDesc> t;
+    int64_t total;
+    build_layout(c, t, total);
+    const char* b = static_cast<const char*>(base);
+    for (const TensorDesc& d : t) {
+        const void* p = b + d.off;
+        const float* f = reinterpret_cast<const float*>(p);
+        const std::string& n = d.name;
+        if (n == "wte") m.wte = p;
+        else if (n == "wpe") m.wpe = p;
+        else if (n == "t_w1") m.t_w1 = p;
+        else if (n == "t_b1") m.t_b1 = f;
+        else if (n == "t_w2") m.t_w2 = p;
+        else if (n == "t_b2") m.t_b2 = f;
+        else if (n == "lnf_g") m.lnf_g = f;
+        else if (n == "lnf_b") m.lnf_b = f;
+        else if (n == "w_head") m.w_head = p;
+        else {
+            const size_t dot = n.find('.');
+            if (n[0] != 'l' || dot == std::string::npos) return false;
+            Layer& l = m.L[std::stoi(n.substr(1, dot - 1))];
+            const std::string s = n.substr(dot + 1);
+            if (s == "ln1_g") l.ln1_g = f;
+            else if (s == "ln1_b") l.ln1_b = f;
+            else if (s == "w_qkv") l.w_qkv = p;
+            else if (s == "b_qkv") l.b_qkv = f;
+            else if (s == "w_o") l.w_o = p;
+            else if (s == "b_o") l.b_o = f;
+            else if (s == "ln2_g") l.ln2_g = f;
+            else if (s == "ln2_b") l.ln2_b = f;
+            else if (s == "w_fc" || s == "w_gate") l.w_fc = p;     // w_up follows w_gate contiguously
+            else if (s == "w_up") {
+                if (static_cast<const char*>(p) != static_cast<const char*>(l.w_fc) + (int64_t)c.d_ff * c.d_model * m.ew)
+                    return false;
+            } else if (s == "b_fc") l.b_fc = f;
+            else if (s == "w_proj") l.w_proj = p;
+            else if (s == "b_proj") l.b_proj = f;
+            else return false;
+        }
+    }
+    return true;
+}
+
+// ------------------------------------------------------------------------------------------
+// workspace
+// ------------------------------------------------------------------------------------------
+struct Arena {
+    char* base;
+    int64_t off = 0;
+    explicit Arena(void* b) : base(static_cast<char*>(b)) {}
+    template <typename T> T* take(int64_t count, int64_t elem = sizeof(T)) {
+        T* p = base ? reinterpret_cast<T*>(base + off) : nullptr;
+        off = align_up(off + count * elem, 256);
+        return p;
+    }
+};
+
+struct Buffers {
+    float* h; void* xn; void* qkv; void* att; void* mlp; void* act; void* xf;
+    float *logits_d, *logits_t, *q, *qtok, *temb;
+    int32_t *z, *n_acc, *tok, *prefix, *row_src, *row_pos, *row_seq, *kv_len, *blk_idx;
+    int64_t* kv_off;
+    void* sample_scratch;
+    void *kcache, *vcache;
+};
+
+struct Limits { int64_t max_rows, rows_head, dmax, qkvmax, ffmax, ew; int64_t prefix_cap; };
+
+Limits limits_of(const sd_model_config& t, const sd_model_config& d, int max_batch, int gamma_max) {
+    Limits l;
+    l.max_rows = (int64_t)max_batch * (t.n_ctx > d.n_ctx ? t.n_ctx : d.n_ctx);
+    l.rows_head = (int64_t)max_batch * (gamma_max + 1);
+    l.dmax = t.d_model > d.d_model ? t.d_model : d.d_model;
+    auto qkvw = [](const sd_model_config& c) { return (int64_t)c.d_model + 2 * (int64_t)c.n_kv_head * (c.d_model / c.n_head); };
+    auto ffw = [](const sd_model_config& c) { return (int64_t)c.d_ff * (c.arch == SD_ARCH_LLAMA ? 2 : 1); };
+    l.qkvmax = qkvw(t) > qkvw(d) ? qkvw(t) : qkvw(d);
+    l.ffmax = ffw(t) > ffw(d) ? ffw(t) : ffw(d);
+    l.ew = (t.dtype == SD_DTYPE_F32 || d.dtype == SD_DTYPE_F32) ? 4 : 2;
+    l.prefix_cap = l.max_rows;
+    return l;
+}
+
+int64_t carve(Arena& a, Buffers& b, const sd_model_config& t, const sd_model_config& d, int max_batch, int gamma_max) {
+    const Limits l = limits_of(t, d, max_batch, gamma_max);
+    const int64_t ld = vocab_pad(t.vocab);
+    b.h = a.take<float>(l.max_rows * l.dmax);
+    b.xn = a.take<char>(l.max_rows * l.dmax, l.ew);
+    b.qkv = a.take<char>(l.max_rows * l.qkvmax, l.ew);
+    b.att = a.take<char>(l.max_rows * l.dmax, l.ew);
+    b.mlp = a.take<char>(l.max_rows * l.ffmax, l.ew);
+    b.act = a.take<char>(t.arch == SD_ARCH_LLAMA ? l.max_rows * t.d_ff : 1, l.ew);
+    b.xf = a.take<char>(l.rows_head * l.dmax, l.ew);
+    b.logits_d = a.take<float>((int64_t)max_batch * gamma_max * ld);
+    b.logits_t = a.take<float>(l.rows_head * ld);
+    b.q = a.take<float>((int64_t)max_batch * gamma_max * ld);
+    b.qtok = a.take<float>((int64_t)max_batch * gamma_max);
+    b.temb = a.take<float>((int64_t)kMaxSteps * d.d_model);
+    b.z = a.take<int32_t>((int64_t)max_batch * gamma_max);
+    b.n_acc = a.take<int32_t>(max_batch);
+    b.tok = a.take<int32_t>(max_batch);
+    b.prefix = a.take<int32_t>(l.prefix_cap);
+    b.row_src = a.take<int32_t>(l.max_rows);
+    b.row_pos = a.take<int32_t>(l.max_rows);
+    b.row_seq = a.take<int32_t>(l.max_rows);
+    b.kv_len = a.take<int32_t>(l.max_rows);
+    b.blk_idx = a.take<int32_t>((int64_t)max_batch * gamma_max);
+    b.kv_off = a.take<int64_t>(l.max_rows);
+    b.sample_scratch = a.take<char>(sampling_scratch_bytes((int)l.rows_head, t.vocab));
+    const int64_t cache = (int64_t)t.n_layer * max_batch * t.n_ctx * t.n_kv_head * (t.d_model / t.n_head);
+    b.kcache = a.take<char>(cache, t.dtype == SD_DTYPE_BF16 ? 2 : 4);
+    b.vcache = a.take<char>(cache, t.dtype == SD_DTYPE_BF16 ? 2 : 4);
+    return a.off;
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------------------------------
+// handle
+// ------------------------------------------------------------------------------------------
+struct sd_handle {
+    Model target, drafter;
+    Buffers buf;
+    Limits lim;
+    int max_batch, gamma_max;
+    hipStream_t st;
+    // pinned host staging
+    int32_t* stage_i = nullptr;   // row maps and token uploads
+    int64_t* stage_l = nullptr;
+    int32_t* stage_z = nullptr;   // block / draft tokens going to the device
+    int32_t* stage_out = nullptr; // results read back
+    float* stage_f = nullptr;
+    int64_t stage_cap = 0;
+    // KV-cache state per sequence: number of cached positions and a hash of their tokens
+    std::vector<int32_t> cached_len;
+    std::vector<uint64_t> cached_hash;
+    bool have_q = false;
+    int q_batch = 0, q_gamma = 0;
+    std::string err;
+};
+
+namespace {
+
+#define SD_HIP(h, expr)                                                                           \
+    do {                                                                                          \
+        hipError_t e_ = (expr);                                                                   \
+        if (e_ != hipSuccess) {                                                                   \
+            (h)->err = std::string(#expr) + ": " + hipGetErrorString(e_);                         \
+            return SD_ERR_HIP;                                                                    \
+        }                                                                                         \
+    } while (0)
+
+int fail(sd_handle* h, int code, const std::string& msg) {
+    if (h) h->err = msg;
+    return code;
+}
+
+uint64_t hash_tokens(const int32_t* t, int n) {
+    uint64_t x = 1469598103934665603ull;
+    for (int i = 0; i < n; ++i) { x ^= (uint32_t)t[i]; x *= 1099511628211ull; }
+    return x ^ (uint64_t)n;
+}
+
+// Validate a ragged batch; returns total token count through *total.
+int check_batch(sd_handle* h, int batch, const int32_t* tokens, const int32_t* len, int vocab_limit, int64_t* total) {
+    if (!h) return SD_ERR_ARG;
+    if (!tokens || !len) return fail(h, SD_ERR_ARG, "null token or length array");
+    if (batch <= 0 || batch > h->max_batch) return fail(h, SD_ERR_SHAPE, "batch outside [1, max_batch]");
+    int64_t n = 0;
+    for (int b = 0; b < batch; ++b) {
+        if (len[b] <= 0) return fail(h, SD_ERR_SHAPE, "sequence length must be positive");
+        n += len[b];
+    }
+    if (n > h->lim.prefix_cap) return fail(h, SD_ERR_SHAPE, "batch has more tokens than the workspace holds");
+    for (int64_t i = 0; i < n; ++i)
+        if (tokens[i] < 0 || tokens[i] >= vocab_limit) return fail(h, SD_ERR_TOKEN, "token id outside the vocabulary");
+    *total = n;
+    return SD_OK;
+}
+
+struct RowMaps { int rows = 0; int max_kv = 0; };
+
+// Upload prefix tokens and per-row maps.  mode 0: drafter over prefix o block; 1: target query rows
+// (last prefix token + gamma draft tokens); 2: target prefill rows [0, L-1).
+int upload_rows(sd_handle* h, int mode, int batch, const int32_t* tokens, const int32_t* len, int64_t n_tokens,
+                int gamma, RowMaps* out) {
+    const Model& m = mode == 0 ? h->drafter : h->target;
+    // One staging region per mode: a region is rewritten only by a later call of the same mode,
+    // and every exported call ends with a stream synchronisation, so no copy is still reading it.
+    const int64_t region = h->lim.prefix_cap + 4 * h->lim.max_rows + (int64_t)h->max_batch * h->gamma_max;
+    int32_t* s_tok = h->stage_i + mode * region;
+    int32_t* s_src = s_tok + h->lim.prefix_cap;
+    int32_t* s_pos = s_src + h->lim.max_rows;
+    int32_t* s_seq = s_pos + h->lim.max_rows;
+    int32_t* s_kvl = s_seq + h->lim.max_rows;
+    int32_t* s_blk = s_kvl + h->lim.max_rows;
+    int64_t* s_off = h->stage_l + mode * h->lim.max_rows;
+    memcpy(s_tok, tokens, n_tokens * sizeof(int32_t));
+    int64_t r = 0, tok_off = 0;
+    int max_kv = 0;
+    for (int b = 0; b < batch; ++b) {
+        const int L = len[b];
+        if (mode == 0) {
+            const int S = L + gamma;
+            const int64_t row0 = r;
+            for (int p = 0; p < S; ++p, ++r) {
+                s_src[r] = p < L ? (int32_t)(tok_off + p) : -(b * gamma + (p - L)) - 1;
+                s_pos[r] = p;
+                s_seq[r] = b;
+                s_kvl[r] = S;
+                s_off[r] = row0 * (int64_t)(m.dq + 2 * m.dkv);
+                if (p >= L) s_blk[b * gamma + (p - L)] = (int32_t)r;
+            }
+            if (S > max_kv) max_kv = S;
+        } else if (mode == 1) {
+            for (int k = 0; k <= gamma; ++k, ++r) {
+                s_src[r] = k == 0 ? (int32_t)(tok_off + L - 1) : -(b * gamma + k - 1) - 1;
+                s_pos[r] = L - 1 + k;
+                s_seq[r] = b;
+                s_kvl[r] = L + k;
+                s_off[r] = (int64_t)b * m.c.n_ctx * m.dkv;
+            }
+            if (L + gamma > max_kv) max_kv = L + gamma;
+        } else {
+            for (int p = 0; p < L - 1; ++p, ++r) {
+                s_src[r] = (int32_t)(tok_off + p);
+                s_pos[r] = p;
+                s_seq[r] = b;
+                s_kvl[r] = p + 1;
+                s_off[r] = (int64_t)b * m.c.n_ctx * m.dkv;
+            }
+            if (L - 1 > max_kv) max_kv = L - 1;
+        }
+        tok_off += L;
+    }
+    if (r > h->lim.max_rows) return fail(h, SD_ERR_SHAPE, "more rows than the workspace holds");
+    Buffers& B = h->buf;
+    SD_HIP(h, hipMemcpyAsync(B.prefix, s_tok, n_tokens * 4, hipMemcpyHostToDevice, h->st));
+    if (r > 0) {
+        SD_HIP(h, hipMemcpyAsync(B.row_src, s_src, r * 4, hipMemcpyHostToDevice, h->st));
+        SD_HIP(h, hipMemcpyAsync(B.row_pos, s_pos, r * 4, hipMemcpyHostToDevice, h->st));
+        SD_HIP(h, hipMemcpyAsync(B.row_seq, s_seq, r * 4, hipMemcpyHostToDevice, h->st));
+        SD_HIP(h, hipMemcpyAsync(B.kv_len, s_kvl, r * 4, hipMemcpyHostToDevice, h->st));
+        SD_HIP(h, hipMemcpyAsync(B.kv_off, s_off, r * 8, hipMemcpyHostToDevice, h->st));
+    }
+    if (mode == 0)
+        SD_HIP(h, hipMemcpyAsync(B.blk_idx, s_blk, (int64_t)batch * gamma * 4, hipMemcpyHostToDevice, h->st));
+    out->rows = (int)r;
+    out->max_kv = max_kv;
+    return SD_OK;
+}
+
+// Transformer layers over the rows described by the uploaded maps; residual stream in buf.h.
+int run_layers(sd_handle* h, const Model& m, const RowMaps& rm, const float* temb) {
+    Buffers& B = h->buf;
+    const sd_model_config& c = m.c;
+    const int rows = rm.rows, d = c.d_model, dt = c.dtype;
+    if (rows == 0) return SD_OK;
+    const bool cached = !c.bidirectional;
+    const int qkv_w = m.dq + 2 * m.dkv;
+    SD_HIP(h, launch_embed(dt, B.row_src, B.row_pos, B.prefix, B.z, m.wte, m.wpe, temb, B.h, rows, d, h->st));
+    for (int i = 0; i < c.n_layer; ++i) {
+        const Layer& l = m.L[i];
+        SD_HIP(h, launch_norm(dt, B.h, nullptr, l.ln1_g, l.ln1_b, B.xn, rows, d, c.norm_eps, h->st));
+        SD_HIP(h, launch_linear(dt, B.xn, l.w_qkv, l.b_qkv, B.qkv, rows, qkv_w, d, qkv_w, EPI_STORE, h->st));
+        if (c.arch == SD_ARCH_LLAMA)
+            SD_HIP(h, launch_rope(dt, B.qkv, B.row_pos, rows, c.n_head, c.n_kv_head, m.dh, c.rope_theta, h->st));
+        AttnArgs a;
+        a.q = B.qkv; a.q_ld = qkv_w;
+        a.kv_off = B.kv_off; a.kv_len = B.kv_len;
+        a.out = B.att; a.out_ld = d;
+        a.rows = rows; a.n_head = c.n_head; a.n_kv_head = c.n_kv_head; a.d_head = m.dh; a.max_kv = rm.max_kv;
+        if (cached) {
+            const int64_t per_layer = (int64_t)h->max_batch * c.n_ctx * m.dkv * m.ew;
+            char* kc = static_cast<char*>(B.kcache) + i * per_layer;
+            char* vc = static_cast<char*>(B.vcache) + i * per_layer;
+            SD_HIP(h, launch_kv_store(dt, B.qkv, B.row_seq, B.row_pos, kc, vc, rows, c.n_head, c.n_kv_head, m.dh, c.n_ctx, h->st));
+            a.k = kc; a.v = vc; a.kv_ld = m.dkv;
+        } else {
+            a.k = static_cast<char*>(B.qkv) + (int64_t)m.dq * m.ew;
+            a.v = static_cast<char*>(B.qkv) + (int64_t)(m.dq + m.dkv) * m.ew;
+            a.kv_ld = qkv_w;
+        }
+        SD_HIP(h, launch_attention(dt, a, h->st));
+        SD_HIP(h, launch_linear(dt, B.att, l.w_o, l.b_o, B.h, rows, d, d, d, EPI_RESID, h->st));
+        SD_HIP(h, launch_norm(dt, B.h, nullptr, l.ln2_g, l.ln2_b, B.xn, rows, d, c.norm_eps, h->st));
+        if (c.arch == SD_ARCH_GPT2) {
+            SD_HIP(h, launch_linear(dt, B.xn, l.w_fc, l.b_fc, B.mlp, rows, c.d_ff, d, c.d_ff, EPI_GELU, h->st));
+            SD_HIP(h, launch_linear(dt, B.mlp, l.w_proj, l.b_proj, B.h, rows, d, c.d_ff, d, EPI_RESID, h->st));
+        } else {
+            SD_HIP(h, launch_linear(dt, B.xn, l.w_fc, nullptr, B.mlp, rows, 2 * c.d_ff, d, 2 * c.d_ff, EPI_STORE, h->st));
+            SD_HIP(h, launch_swiglu(dt, B.mlp, B.act, rows, c.d_ff, h->st));
+            SD_HIP(h, launch_linear(dt, B.act, l.w_proj, nullptr, B.h, rows, d, c.d_ff, d, EPI_RESID, h->st));
+        }
+    }
+    return SD_OK;
+}
+
+// Final norm on selected rows + LM head -> fp32 logits [n_rows, ld].
+int run_head(sd_handle* h, const Model& m, const int32_t* idx, int n_rows, float* logits) {
+    Buffers& B = h->buf;
+    const sd_model_config& c = m.c;
+    SD_HIP(h, launch_norm(c.dtype, B.h, idx, m.lnf_g, m.lnf_b, B.xf, n_rows, c.d_model, c.norm_eps, h->st));
+    SD_HIP(h, launch_linear(c.dtype, B.xf, m.w_head, nullptr, logits, n_rows, c.vocab, c.d_model, m.ld, EPI_F32, h->st));
+    return SD_OK;
+}
+
+int check_round_shapes(sd_handle* h, int batch, const int32_t* len, int gamma) {
+    if (gamma <= 0 || gamma > h->gamma_max) return fail(h, SD_ERR_SHAPE, "gamma outside [1, gamma_max]");
+    for (int b = 0; b < batch; ++b) {
+        if (len[b] + gamma > h->drafter.c.n_ctx) return fail(h, SD_ERR_SHAPE, "prefix + gamma exceeds the drafter context");
+        if (len[b] + gamma > h->target.c.n_ctx) return fail(h, SD_ERR_SHAPE, "prefix + gamma exceeds the target context");
+    }
+    return SD_OK;
+}
+
+int do_prefill(sd_handle* h, int batch, const int32_t* prefix, const int32_t* len, int64_t n_tokens) {
+    RowMaps rm;
+    int rc = upload_rows(h, 2, batch, prefix, len, n_tokens, 0, &rm);
+    if (rc) return rc;
+    rc = run_layers(h, h->target, rm, nullptr);
+    if (rc) return rc;
+    int64_t off = 0;
+    for (int b = 0; b < batch; ++b) {
+        h->cached_len[b] = len[b] - 1;
+        h->cached_hash[b] = hash_tokens(prefix + off, len[b] - 1);
+        off += len[b];
+    }
+    return SD_OK;
+}
+
+bool cache_matches(sd_handle* h, int batch, const int32_t* prefix, const int32_t* len) {
+    int64_t off = 0;
+    for (int b = 0; b < batch; ++b) {
+        if (h->cached_len[b] != len[b] - 1 || h->cached_hash[b] != hash_tokens(prefix + off, len[b] - 1)) return false;
+        off += len[b];
+    }
+    return true;
+}
+
+// The T reverse-diffusion steps, device resident.  Leaves z (draft), q, qtok in the workspace.
+int enqueue_draft(sd_handle* h, int batch, const int32_t* prefix, const int32_t* len, int64_t n_tokens, int gamma,
+                  int T, uint64_t seed) {
+    Buffers& B = h->buf;
+    const Model& m = h->drafter;
+    RowMaps rm;
+    int rc = upload_rows(h, 0, batch, prefix, len, n_tokens, gamma, &rm);
+    if (rc) return rc;
+    // z <- [MASK]^gamma  (fill through the staging buffer: vocab is not a byte pattern)
+    for (int i = 0; i < batch * gamma; ++i) h->stage_z[i] = m.c.vocab;
+    SD_HIP(h, hipMemcpyAsync(B.z, h->stage_z, (int64_t)batch * gamma * 4, hipMemcpyHostToDevice, h->st));
+    SD_HIP(h, launch_timestep_embed(m.c.dtype, m.t_w1, m.t_b1, m.t_w2, m.t_b2, nullptr, B.temb, T, m.c.d_model, h->st));
+    const SampleScratch ss = sampling_scratch(B.sample_scratch, (int)h->lim.rows_head, m.c.vocab);
+    for (int j = T; j >= 1; --j) {
+        rc = run_layers(h, m, rm, B.temb + (int64_t)(j - 1) * m.c.d_model);
+        if (rc) return rc;
+        rc = run_head(h, m, B.blk_idx, batch * gamma, B.logits_d);
+        if (rc) return rc;
+        SD_HIP(h, launch_unmask_sample(B.logits_d, batch, gamma, m.c.vocab, j, seed, B.z, B.q, B.qtok, ss, h->st));
+    }
+    h->have_q = true;
+    h->q_batch = batch;
+    h->q_gamma = gamma;
+    return SD_OK;
+}
+
+// Target forward over the gamma+1 query rows (draft tokens taken from buf.z) -> buf.logits_t.
+int enqueue_target(sd_handle* h, int batch, const int32_t* prefix, const int32_t* len, int64_t n_tokens, int gamma) {
+    if (!cache_matches(h, batch, prefix, len)) {
+        int rc = do_prefill(h, batch, prefix, len, n_tokens);
+        if (rc) return rc;
+    }
+    RowMaps rm;
+    int rc = upload_rows(h, 1, batch, prefix, len, n_tokens, gamma, &rm);
+    if (rc) return rc;
+    rc = run_layers(h, h->target, rm, nullptr);
+    if (rc) return rc;
+    return run_head(h, h->target, nullptr, rm.rows, h->buf.logits_t);
+}
+
+int read_back(sd_handle* h, int32_t* dst, const int32_t* dev, int64_t n) {
+    SD_HIP(h, hipMemcpyAsync(h->stage_out, dev, n * 4, hipMemcpyDeviceToHost, h->st));
+    SD_HIP(h, hipStreamSynchronize(h->st));
+    memcpy(dst, h->stage_out, n * 4);
+    return SD_OK;
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------------------------------
+// exported functions
+// ------------------------------------------------------------------------------------------
+extern "C" {
+
+int32_t sd_vocab_pad(int32_t vocab) { return vocab_pad(vocab); }
+
+int32_t sd_weight_count(const sd_model_config* cfg) {
+    if (!config_ok(cfg)) return 0;
+    std::vector<TensorDesc> t;
+    int64_t total;
+    build_layout(*cfg, t, total);
+    return (int32_t)t.size();
+}
+
+int32_t sd_weight_desc(const sd_model_config* cfg, int32_t index, char* name, int32_t name_cap, int64_t* rows,
+                       int64_t* cols, int32_t* elem_bytes, int64_t* offset) {
+    if (!config_ok(cfg) || !name || name_cap <= 0 || !rows || !cols || !elem_bytes || !offset) return SD_ERR_ARG;
+    std::vector<TensorDesc> t;
+    int64_t total;
+    build_layout(*cfg, t, total);
+    if (index < 0 || index >= (int32_t)t.size()) return SD_ERR_ARG;
+    const TensorDesc& d = t[index];
+    if ((int32_t)d.name.size() + 1 > name_cap) return SD_ERR_ARG;
+    memcpy(name, d.name.c_str(), d.name.size() + 1);
+    *rows = d.rows; *cols = d.cols; *elem_bytes = d.elem; *offset = d.off;
+    return SD_OK;
+}
+
+int64_t sd_weight_bytes(const sd_model_config* cfg) {
+    if (!config_ok(cfg)) return 0;
+    std::vector<TensorDesc> t;
+    int64_t total;
+    build_layout(*cfg, t, total);
+    return total;
+}
+
+static bool pair_ok(const sd_model_config* t, const sd_model_config* d, int max_batch, int gamma_max) {
+    return config_ok(t) && config_ok(d) && !t->bidirectional && d->bidirectional && t->vocab == d->vocab &&
+           max_batch > 0 && max_batch <= 4096 && gamma_max > 0 && gamma_max <= 255 && gamma_max < t->n_ctx &&
+           gamma_max < d->n_ctx;
+}
+
+int64_t sd_workspace_bytes(const sd_model_config* target, const sd_model_config* drafter, int32_t max_batch,
+                           int32_t gamma_max) {
+    if (!pair_ok(target, drafter, max_batch, gamma_max)) return 0;
+    Arena a(nullptr);
+    Buffers b;
+    return carve(a, b, *target, *drafter, max_batch, gamma_max);
+}
+
+int32_t sd_create(const sd_model_config* target, const sd_model_config* drafter, const void* target_w,
+                  const void* drafter_w, int32_t max_batch, int32_t gamma_max, void* workspace,
+                  int64_t workspace_bytes, void* hip_stream, sd_handle** out) {
+    if (!out) return SD_ERR_ARG;
+    *out = nullptr;
+    if (!target_w || !drafter_w || !workspace) return SD_ERR_ARG;
+    if (!pair_ok(target, drafter, max_batch, gamma_max)) return SD_ERR_ARG;
+    if ((reinterpret_cast<uintptr_t>(workspace) & 255) || (reinterpret_cast<uintptr_t>(target_w) & 255) ||
+        (reinterpret_cast<uintptr_t>(drafter_w) & 255))
+        return SD_ERR_WORKSPACE;
+    sd_handle* h = new (std::nothrow) sd_handle();
+    if (!h) return SD_ERR_ARG;
+    Arena a(workspace);
+    const int64_t need = carve(a, h->buf, *target, *drafter, max_batch, gamma_max);
+    if (need > workspace_bytes) { delete h; return SD_ERR_WORKSPACE; }
+    if (!bind_model(h->target, *target, target_w) || !bind_model(h->drafter, *drafter, drafter_w)) { delete h; return SD_ERR_ARG; }
+    h->lim = limits_of(*target, *drafter, max_batch, gamma_max);
+    h->max_batch = max_batch;
+    h->gamma_max = gamma_max;
+    h->st = static_cast<hipStream_t>(hip_stream);
+    h->cached_len.assign(max_batch, -1);
+    h->cached_hash.assign(max_batch, 0);
+    const int64_t n_i = h->lim.prefix_cap + 4 * h->lim.max_rows + (int64_t)max_batch * gamma_max;
+    const int64_t n_out = (int64_t)max_batch * (gamma_max + 2) + 16;
+    if (hipHostMalloc(reinterpret_cast<void**>(&h->stage_i), 3 * n_i * 4, hipHostMallocDefault) != hipSuccess ||
+        hipHostMalloc(reinterpret_cast<void**>(&h->stage_l), 3 * h->lim.max_rows * 8, hipHostMallocDefault) != hipSuccess ||
+        hipHostMalloc(reinterpret_cast<void**>(&h->stage_z), n_out * 4, hipHostMallocDefault) != hipSuccess ||
+        hipHostMalloc(reinterpret_cast<void**>(&h->stage_out), n_out * 4, hipHostMallocDefault) != hipSuccess ||
+        hipHostMalloc(reinterpret_cast<void**>(&h->stage_f), n_out * 4, hipHostMallocDefault) != hipSuccess) {
+        sd_destroy(h);
+        return SD_ERR_HIP;
+    }
+    *out = h;
+    return SD_OK;
+}
+
+void sd_destroy(sd_handle* h) {
+    if (!h) return;
+    if (h->stage_i) (void)hipHostFree(h->stage_i);
+    if (h->stage_l) (void)hipHostFree(h->stage_l);
+    if (h->stage_z) (void)hipHostFree(h->stage_z);
+    if (h->stage_out) (void)hipHostFree(h->stage_out);
+    if (h->stage_f) (void)hipHostFree(h->stage_f);
+    delete h;
+}
+
+const char* sd_last_error(const sd_handle* h) { return h ? h->err.c_str() : "null handle"; }
+
+int32_t sd_prefill(sd_handle* h, int32_t batch, const int32_t* prefix, const int32_t* prefix_len) {
+    int64_t n;
+    int rc = check_batch(h, batch, prefix, prefix_len, h ? h->target.c.vocab : 0, &n);
+    if (rc) return rc;
+    for (int b = 0; b < batch; ++b)
+        if (prefix_len[b] > h->target.c.n_ctx) return fail(h, SD_ERR_SHAPE, "prefix exceeds the target context");
+    rc = do_prefill(h, batch, prefix, prefix_len, n);
+    if (rc) return rc;
+    SD_HIP(h, hipStreamSynchronize(h->st));
+    return SD_OK;
+}
+
+int32_t sd_draft(sd_handle* h, int32_t batch, const int32_t* prefix, const int32_t* prefix_len, int32_t gamma,
+                 int32_t T, uint64_t seed, int32_t* draft_out, float* qtok_out, const float** q_dev_out) {
+    int64_t n;
+    int rc = check_batch(h, batch, prefix, prefix_len, h ? h->drafter.c.vocab : 0, &n);
+    if (rc) return rc;
+    if (!draft_out) return fail(h, SD_ERR_ARG, "draft_out is null");
+    if (T <= 0 || T > kMaxSteps) return fail(h, SD_ERR_SHAPE, "T outside [1, 256]");
+    rc = check_round_shapes(h, batch, prefix_len, gamma);
+    if (rc) return rc;
+    rc = enqueue_draft(h, batch, prefix, prefix_len, n, gamma, T, seed);
+    if (rc) return rc;
+    const int64_t cnt = (int64_t)batch * gamma;
+    SD_HIP(h, hipMemcpyAsync(h->stage_out, h->buf.z, cnt * 4, hipMemcpyDeviceToHost, h->st));
+    SD_HIP(h, hipMemcpyAsync(h->stage_f, h->buf.qtok, cnt * 4, hipMemcpyDeviceToHost, h->st));
+    SD_HIP(h, hipStreamSynchronize(h->st));
+    memcpy(draft_out, h->stage_out, cnt * 4);
+    if (qtok_out) memcpy(qtok_out, h->stage_f, cnt * 4);
+    if (q_dev_out) *q_dev_out = h->buf.q;
+    return SD_OK;
+}
+
+int32_t sd_verify(sd_handle* h, int32_t batch, const int32_t* prefix, const int32_t* prefix_len, int32_t gamma,
+                  const int32_t* draft, const float* q_dev, uint64_t seed, int32_t* n_accepted_out,
+                  int32_t* token_out) {
+    int64_t n;
+    int rc = check_batch(h, batch, prefix, prefix_len, h ? h->target.c.vocab : 0, &n);
+    if (rc) return rc;
+    if (!draft || !q_dev || !n_accepted_out || !token_out) return fail(h, SD_ERR_ARG, "null argument");
+    rc = check_round_shapes(h, batch, prefix_len, gamma);
+    if (rc) return rc;
+    const int64_t cnt = (int64_t)batch * gamma;
+    for (int64_t i = 0; i < cnt; ++i)
+        if (draft[i] < 0 || draft[i] >= h->target.c.vocab) return fail(h, SD_ERR_TOKEN, "draft token outside the vocabulary");
+    memcpy(h->stage_z, draft, cnt * 4);
+    SD_HIP(h, hipMemcpyAsync(h->buf.z, h->stage_z, cnt * 4, hipMemcpyHostToDevice, h->st));
+    rc = enqueue_target(h, batch, prefix, prefix_len, n, gamma);
+    if (rc) return rc;
+    const SampleScratch ss = sampling_scratch(h->buf.sample_scratch, (int)h->lim.rows_head, h->target.c.vocab);
+    SD_HIP(h, launch_accept_resample(h->buf.logits_t, q_dev, h->buf.z, batch, gamma, h->target.c.vocab, seed,
+                                     h->buf.n_acc, h->buf.tok, ss, h->st));
+    rc = read_back(h, n_accepted_out, h->buf.n_acc, batch);
+    if (rc) return rc;
+    return read_back(h, token_out, h->buf.tok, batch);
+}
+
+int32_t sd_round(sd_handle* h, int32_t batch, const int32_t* prefix, const int32_t* prefix_len, int32_t gamma,
+                 int32_t T, uint64_t seed, int32_t* draft_out, int32_t* n_accepted_out, int32_t* token_out) {
+    int64_t n;
+    int rc = check_batch(h, batch, prefix, prefix_len, h ? h->target.c.vocab : 0, &n);
+    if (rc) return rc;
+    if (!draft_out || !n_accepted_out || !token_out) return fail(h, SD_ERR_ARG, "null argument");
+    if (T <= 0 || T > kMaxSteps) return fail(h, SD_ERR_SHAPE, "T outside [1, 256]");
+    rc = check_round_shapes(h, batch, prefix_len, gamma);
+    if (rc) return rc;
+    rc = enqueue_draft(h, batch, prefix, prefix_len, n, gamma, T, seed);
+    if (rc) return rc;
+    rc = enqueue_target(h, batch, prefix, prefix_len, n, gamma);
+    if (rc) return rc;
+    const SampleScratch ss = sampling_scratch(h->buf.sample_scratch, (int)h->lim.rows_head, h->target.c.vocab);
+    SD_HIP(h, launch_accept_resample(h->buf.logits_t, h->buf.q, h->buf.z, batch, gamma, h->target.c.vocab, seed,
+                                     h->buf.n_acc, h->buf.tok, ss, h->st));
+    const int64_t cnt = (int64_t)batch * gamma;
+    int32_t* so = h->stage_out;
+    SD_HIP(h, hipMemcpyAsync(so, h->buf.z, cnt * 4, hipMemcpyDeviceToHost, h->st));
+    SD_HIP(h, hipMemcpyAsync(so + cnt, h->buf.n_acc, batch * 4, hipMemcpyDeviceToHost, h->st));
+    SD_HIP(h, hipMemcpyAsync(so + cnt + batch, h->buf.tok, batch * 4, hipMemcpyDeviceToHost, h->st));
+    SD_HIP(h, hipStreamSynchronize(h->st));
+    memcpy(draft_out, so, cnt * 4);
+    memcpy(n_accepted_out, so + cnt, batch * 4);
+    memcpy(token_out, so + cnt + batch, batch * 4);
+    return SD_OK;
+}
+
+int32_t sd_drafter_logits(sd_handle* h, int32_t batch, const int32_t* tokens, const int32_t* seq_len, int32_t gamma,
+                          int32_t step, int32_t T, const float** logits_dev_out) {
+    int64_t n;
+    int rc = check_batch(h, batch, tokens, seq_len, h ? h->drafter.c.vocab + 1 : 0, &n);
+    if (rc) return rc;
+    if (!logits_dev_out) return fail(h, SD_ERR_ARG, "logits_dev_out is null");
+    if (T <= 0 || T > kMaxSteps || step < 1 || step > T) return fail(h, SD_ERR_SHAPE, "step / T out of range");
+    if (gamma <= 0 || gamma > h->gamma_max) return fail(h, SD_ERR_SHAPE, "gamma outside [1, gamma_max]");
+    std::vector<int32_t> plen(batch);
+    for (int b = 0; b < batch; ++b) {
+        if (seq_len[b] <= gamma || seq_len[b] > h->drafter.c.n_ctx)
+            return fail(h, SD_ERR_SHAPE, "sequence must hold a prefix and gamma slots within the drafter context");
+        plen[b] = seq_len[b] - gamma;
+    }
+    // Rows are described as prefix + gamma block slots; the block tokens are copied into z.
+    std::vector<int32_t> pre, blk((size_t)batch * gamma);
+    pre.reserve(n);
+    int64_t off = 0;
+    for (int b = 0; b < batch; ++b) {
+        pre.insert(pre.end(), tokens + off, tokens + off + plen[b]);
+        for (int k = 0; k < gamma; ++k) blk[(size_t)b * gamma + k] = tokens[off + plen[b] + k];
+        off += seq_len[b];
+    }
+    RowMaps rm;
+    rc = upload_rows(h, 0, batch, pre.data(), plen.data(), (int64_t)pre.size(), gamma, &rm);
+    if (rc) return rc;
+    memcpy(h->stage_z, blk.data(), blk.size() * 4);
+    SD_HIP(h, hipMemcpyAsync(h->buf.z, h->stage_z, blk.size() * 4, hipMemcpyHostToDevice, h->st));
+    const Model& m = h->drafter;
+    SD_HIP(h, launch_timestep_embed(m.c.dtype, m.t_w1, m.t_b1, m.t_w2, m.t_b2, nullptr, h->buf.temb, T, m.c.d_model, h->st));
+    rc = run_layers(h, m, rm, h->buf.temb + (int64_t)(step - 1) * m.c.d_model);
+    if (rc) return rc;
+    rc = run_head(h, m, h->buf.blk_idx, batch * gamma, h->buf.logits_d);
+    if (rc) return rc;
+    SD_HIP(h, hipStreamSynchronize(h->st));
+    *logits_dev_out = h->buf.logits_d;
+    return SD_OK;
+}
+
+int32_t sd_target_logits(sd_handle* h, int32_t batch, const int32_t* prefix, const int32_t* prefix_len,
+                         int32_t gamma, const int32_t* draft, const float** logits_dev_out) {
+    int64_t n;
+    int rc = check_batch(h, batch, prefix, prefix_len, h ? h->target.c.vocab : 0, &n);
+    if (rc) return rc;
+    if (!draft || !logits_dev_out) return fail(h, SD_ERR_ARG, "null argument");
+    rc = check_round_shapes(h, batch, prefix_len, gamma);
+    if (rc) return rc;
+    const int64_t cnt = (int64_t)batch * gamma;
+    for (int64_t i = 0; i < cnt; ++i)
+        if (draft[i] < 0 || draft[i] >= h->target.c.vocab) return fail(h, SD_ERR_TOKEN, "draft token outside the vocabulary");
+    memcpy(h->stage_z, draft, cnt * 4);
+    SD_HIP(h, hipMemcpyAsync(h->buf.z, h->stage_z, cnt * 4, hipMemcpyHostToDevice, h->st));
+    rc = enqueue_target(h, batch, prefix, prefix_len, n, gamma);
+    if (rc) return rc;
+    SD_HIP(h, hipStreamSynchronize(h->st));
+    *logits_dev_out = h->buf.logits_t;
+    return SD_OK;
+}
+
+int64_t sd_sampling_scratch_bytes(int32_t rows, int32_t vocab) { return sampling_scratch_bytes(rows, vocab); }
+
+int32_t sd_unmask_sample(const float* logits, int32_t batch, int32_t gamma, int32_t vocab, int32_t step,
+                         uint64_t seed, int32_t* z, float* q, float* qtok, void* scratch, int64_t scratch_bytes,
+                         void* hip_stream) {
+    if (!logits || !z || !q || !qtok || !scratch) return SD_ERR_ARG;
+    if (batch <= 0 || gamma <= 0 || vocab <= 0 || step < 1 || vocab > kChunk * 512) return SD_ERR_SHAPE;
+    if (scratch_bytes < sampling_scratch_bytes(batch * (gamma + 1), vocab) || (reinterpret_cast<uintptr_t>(scratch) & 255))
+        return SD_ERR_WORKSPACE;
+    const SampleScratch ss = sampling_scratch(scratch, batch * (gamma + 1), vocab);
+    return launch_unmask_sample(logits, batch, gamma, vocab, step, seed, z, q, qtok, ss, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? SD_OK : SD_ERR_HIP;
+}
+
+int32_t sd_accept_resample(const float* p_logits, const float* q, const int32_t* draft, int32_t batch, int32_t gamma,
+                           int32_t vocab, uint64_t seed, int32_t* n_accepted, int32_t* token, void* scratch,
+                           int64_t scratch_bytes, void* hip_stream) {
+    if (!p_logits || !q || !draft || !n_accepted || !token || !scratch) return SD_ERR_ARG;
+    if (batch <= 0 || gamma <= 0 || vocab <= 0 || vocab > kChunk * 512 || gamma > 4095) return SD_ERR_SHAPE;
+    if (scratch_bytes < sampling_scratch_bytes(batch * (gamma + 1), vocab) || (reinterpret_cast<uintptr_t>(scratch) & 255))
+        return SD_ERR_WORKSPACE;
+    const SampleScratch ss = sampling_scratch(scratch, batch * (gamma + 1), vocab);
+    return launch_accept_resample(p_logits, q, draft, batch, gamma, vocab, seed, n_accepted, token, ss, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? SD_OK : SD_ERR_HIP;
+}
+
+int32_t sd_linear(int32_t dtype, const void* x, const void* w, const float* bias, void* y, int32_t m, int32_t n,
+                  int32_t k, int32_t ldy, int32_t epilogue, void* hip_stream) {
+    if (!x || !w || !y) return SD_ERR_ARG;
+    if (dtype != SD_DTYPE_F32 && dtype != SD_DTYPE_BF16) return SD_ERR_ARG;
+    if (m <= 0 || n <= 0 || k <= 0 || ldy < n || epilogue < 0 || epilogue > 3 || k % 8) return SD_ERR_SHAPE;
+    return launch_linear(dtype, x, w, bias, y, m, n, k, ldy, epilogue, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? SD_OK : SD_ERR_HIP;
+}
+
+}  // extern "C"

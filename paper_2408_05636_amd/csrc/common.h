@@ -1,0 +1,90 @@
+// Shared declarations of the gfx950 SpecDiff library: element types, launch helpers and the
+// prototypes of the kernel launchers (one translation unit per kernel family).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/specdiff.h"
+
+namespace sd {
+
+typedef __bf16 bf16_t;
+
+constexpr int kWave = 64;            // CDNA wavefront
+constexpr int kChunk = 1024;         // vocabulary columns handled by one workgroup of the sampling kernels
+constexpr uint32_t STREAM_DRAFT = 1; // Philox counter word 3
+constexpr uint32_t STREAM_VERIFY = 2;
+
+__host__ __device__ inline int64_t align_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
+__host__ __device__ inline int vocab_pad(int v) { return (v + 255) / 256 * 256; }
+__host__ __device__ inline int n_chunks(int vocab) { return (vocab + kChunk - 1) / kChunk; }
+
+enum Epilogue { EPI_STORE = 0, EPI_GELU = 1, EPI_RESID = 2, EPI_F32 = 3 };
+
+// ---- launchers (all asynchronous on `st`; return hipGetLastError()) ------------------------
+
+// y = epilogue(x W^T + bias); see sd_linear in specdiff.h.
+hipError_t launch_linear(int dtype, const void* x, const void* w, const float* bias, void* y, int m, int n,
+                         int k, int ldy, int epilogue, hipStream_t st);
+
+// h[r, :] = wte[token(r)] + wpe[pos[r]] + temb, fp32 residual stream.  token(r) = src[r] >= 0 ?
+// prefix[src[r]] : block[-src[r] - 1].  wpe, temb may be NULL.
+hipError_t launch_embed(int dtype, const int32_t* src, const int32_t* pos, const int32_t* prefix,
+                        const int32_t* block, const void* wte, const void* wpe, const float* temb,
+                        float* h, int rows, int d, hipStream_t st);
+
+// temb[j-1, :] = W2 silu(W1 s(j/T) + b1) + b2 for j = 1..T  (sinusoidal s of 1000 t).
+hipError_t launch_timestep_embed(int dtype, const void* w1, const float* b1, const void* w2, const float* b2,
+                                 float* hidden, float* temb, int T, int d, hipStream_t st);
+
+// out[i, :] = norm(h[idx ? idx[i] : i, :]) * gain (+ bias): LayerNorm if bias != NULL else RMSNorm.
+hipError_t launch_norm(int dtype, const float* h, const int32_t* idx, const float* gain, const float* bias,
+                       void* out, int rows, int d, float eps, hipStream_t st);
+
+// In-place rotary embedding of the q and k parts of qkv rows (llama), positions pos[r].
+hipError_t launch_rope(int dtype, void* qkv, const int32_t* pos, int rows, int n_head, int n_kv_head, int d_head,
+                       float theta, hipStream_t st);
+
+// Copy the k and v parts of qkv rows into the cache at (seq[r], pos[r]).
+hipError_t launch_kv_store(int dtype, const void* qkv, const int32_t* seq, const int32_t* pos, void* kcache,
+                           void* vcache, int rows, int n_head, int n_kv_head, int d_head, int n_ctx, hipStream_t st);
+
+// out[r, h*dh:(h+1)*dh] = softmax(q_r k^T / sqrt(dh)) v over keys 0..kv_len[r]-1 of r's sequence.
+// Keys/values of sequence s start at kbase + kv_off[r] elements with row stride kv_ld.
+struct AttnArgs {
+    const void* q; int q_ld;                 // query rows, head h at column h*dh
+    const void* k; const void* v; int kv_ld; // key / value rows, kv head g at column g*dh
+    const int64_t* kv_off;                   // per query row: element offset of its sequence's key row 0
+    const int32_t* kv_len;                   // per query row: number of visible keys
+    void* out; int out_ld;
+    int rows, n_head, n_kv_head, d_head;
+    int max_kv;                              // upper bound of kv_len over the rows
+};
+hipError_t launch_attention(int dtype, const AttnArgs& a, hipStream_t st);
+hipError_t launch_attention_generic(int dtype, const AttnArgs& a, int max_kv, hipStream_t st);
+hipError_t launch_linear_generic(int dtype, const void* x, const void* w, const float* bias, void* y, int m, int n,
+                                 int k, int ldy, int epilogue, hipStream_t st);
+
+// act[r, c] = silu(gu[r, c]) * gu[r, F + c]
+hipError_t launch_swiglu(int dtype, const void* gu, void* act, int rows, int F, hipStream_t st);
+
+// ---- sampling family ------------------------------------------------------------------------
+struct SampleScratch {       // carved from one device buffer by sampling_scratch()
+    double* part_m;          // [rows, n_chunks] chunk maxima
+    double* part_s;          // [rows, n_chunks] chunk sums of exp(l - chunk max)
+    double* part_r;          // [batch, n_chunks] chunk sums of the residual / bonus weights
+    double* row_m;           // [batch] max of the row the final token is drawn from
+    double* row_z;           // [batch] its softmax normaliser
+    int32_t* active;         // [rows]
+};
+int64_t sampling_scratch_bytes(int rows, int vocab);
+SampleScratch sampling_scratch(void* base, int rows, int vocab);
+
+hipError_t launch_unmask_sample(const float* logits, int batch, int gamma, int vocab, int step, uint64_t seed,
+                                int32_t* z, float* q, float* qtok, const SampleScratch& s, hipStream_t st);
+hipError_t launch_accept_resample(const float* p_logits, const float* q, const int32_t* draft, int batch,
+                                  int gamma, int vocab, uint64_t seed, int32_t* n_acc, int32_t* token,
+                                  const SampleScratch& s, hipStream_t st);
+
+}  // namespace sd

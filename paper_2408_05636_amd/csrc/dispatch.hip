@@ -1,0 +1,15 @@
+// Shape-based choice between the kernel variants of one operation.
+#include "common.h"
+
+namespace sd {
+
+hipError_t launch_linear(int dtype, const void* x, const void* w, const float* bias, void* y, int m, int n, int k,
+                         int ldy, int epilogue, hipStream_t st) {
+    return launch_linear_generic(dtype, x, w, bias, y, m, n, k, ldy, epilogue, st);
+}
+
+hipError_t launch_attention(int dtype, const AttnArgs& a, hipStream_t st) {
+    return launch_attention_generic(dtype, a, a.max_kv, st);
+}
+
+}  // namespace sd

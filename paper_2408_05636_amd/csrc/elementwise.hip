@@ -1,0 +1,207 @@
+// Row-wise kernels around the contractions: token / position / timestep embedding, LayerNorm and
+// RMSNorm, rotary embedding, KV-cache append and the SwiGLU gate.  The residual stream is fp32
+// for every storage type; normalised activations are emitted in the storage type, ready to be the
+// A operand of the next contraction.
+#include "common.h"
+
+namespace sd {
+
+template <typename T> __device__ inline float to_f(T v) { return static_cast<float>(v); }
+template <typename T> __device__ inline T from_f(float v) { return static_cast<T>(v); }
+
+// ---------------------------------------------------------------- embedding
+// One workgroup per row; d floats.  The drafter adds the timestep embedding to every row.
+template <typename T>
+__global__ __launch_bounds__(256) void k_embed(const int32_t* __restrict__ src, const int32_t* __restrict__ pos,
+                                               const int32_t* __restrict__ prefix, const int32_t* __restrict__ block,
+                                               const T* __restrict__ wte, const T* __restrict__ wpe,
+                                               const float* __restrict__ temb, float* __restrict__ h, int d) {
+    const int r = blockIdx.x;
+    const int s = src[r];
+    const int tok = s >= 0 ? prefix[s] : block[-s - 1];
+    const T* e = wte + (size_t)tok * d;
+    const T* p = wpe ? wpe + (size_t)pos[r] * d : nullptr;
+    for (int i = threadIdx.x; i < d; i += blockDim.x) {
+        float v = to_f(e[i]);
+        if (p) v += to_f(p[i]);
+        if (temb) v += temb[i];
+        h[(size_t)r * d + i] = v;
+    }
+}
+
+// ---------------------------------------------------------------- timestep embedding (drafter)
+// grid (T): block j-1 computes temb(j/T).  s(t)_i = sin(1000 t f_i), s(t)_{i+d/2} = cos(1000 t f_i),
+// f_i = 10000^(-2i/d), evaluated in fp64 (T*d values per call); two d x d mat-vecs in fp32.
+template <typename T>
+__global__ __launch_bounds__(256) void k_timestep_embed(const T* __restrict__ w1, const float* __restrict__ b1,
+                                                        const T* __restrict__ w2, const float* __restrict__ b2,
+                                                        float* __restrict__ hidden, float* __restrict__ temb,
+                                                        int n_steps, int d) {
+    extern __shared__ float sm[];      // [d] sinusoid, then [d] hidden
+    float* s = sm;
+    float* hid = sm + d;
+    const int j = blockIdx.x + 1;
+    const double t = (double)j / (double)n_steps;
+    const int half = d / 2;
+    for (int i = threadIdx.x; i < half; i += blockDim.x) {
+        const double f = exp(-log(10000.0) * 2.0 * (double)i / (double)d);
+        s[i] = (float)sin(1000.0 * t * f);
+        s[i + half] = (float)cos(1000.0 * t * f);
+    }
+    __syncthreads();
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    for (int o = wv; o < d; o += nw) {            // one wave per output row, lanes over the reduction
+        float acc = 0.f;
+        for (int i = lane; i < d; i += 64) acc += to_f(w1[(size_t)o * d + i]) * s[i];
+        for (int off = 32; off > 0; off >>= 1) acc += __shfl_down(acc, off, 64);
+        if (lane == 0) {
+            const float x = acc + b1[o];
+            hid[o] = x / (1.f + expf(-x));
+        }
+    }
+    __syncthreads();
+    for (int o = wv; o < d; o += nw) {
+        float acc = 0.f;
+        for (int i = lane; i < d; i += 64) acc += to_f(w2[(size_t)o * d + i]) * hid[i];
+        for (int off = 32; off > 0; off >>= 1) acc += __shfl_down(acc, off, 64);
+        if (lane == 0) temb[(size_t)(j - 1) * d + o] = acc + b2[o];
+    }
+    (void)hidden;
+}
+
+// ---------------------------------------------------------------- LayerNorm / RMSNorm
+// One workgroup per output row; the row is held in registers (d <= 256 * 32).
+constexpr int kNormMaxPerThread = 32;
+template <typename T>
+__global__ __launch_bounds__(256) void k_norm(const float* __restrict__ h, const int32_t* __restrict__ idx,
+                                              const float* __restrict__ gain, const float* __restrict__ bias,
+                                              T* __restrict__ out, int d, float eps) {
+    __shared__ float sh[4];
+    const int r = blockIdx.x;
+    const float* x = h + (size_t)(idx ? idx[r] : r) * d;
+    float v[kNormMaxPerThread];
+    float s = 0.f;
+    int cnt = 0;
+    for (int i = threadIdx.x; i < d; i += 256) { v[cnt] = x[i]; s += v[cnt]; ++cnt; }
+    auto bsum = [&](float a) {
+        for (int off = 32; off > 0; off >>= 1) a += __shfl_xor(a, off, 64);
+        __syncthreads();
+        if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = a;
+        __syncthreads();
+        return (sh[0] + sh[1]) + (sh[2] + sh[3]);
+    };
+    float mean = 0.f;
+    if (bias) mean = bsum(s) / (float)d;           // LayerNorm centres; RMSNorm does not
+    float ss = 0.f;
+    for (int c = 0; c < cnt; ++c) { const float t = v[c] - mean; ss += t * t; }
+    const float rstd = rsqrtf(bsum(ss) / (float)d + eps);
+    cnt = 0;
+    for (int i = threadIdx.x; i < d; i += 256) {
+        float y = (v[cnt] - mean) * rstd * gain[i];
+        if (bias) y += bias[i];
+        out[(size_t)r * d + i] = from_f<T>(y);
+        ++cnt;
+    }
+}
+
+// ---------------------------------------------------------------- rotary embedding (llama)
+// One thread per (row, head, pair): rotates (x_i, x_{i+dh/2}) of q and k by pos * theta^(-2i/dh).
+template <typename T>
+__global__ __launch_bounds__(256) void k_rope(T* __restrict__ qkv, const int32_t* __restrict__ pos, int rows,
+                                              int n_head, int n_kv_head, int d_head, float theta) {
+    const int half = d_head / 2;
+    const int heads = n_head + n_kv_head;          // q heads then k heads are contiguous in a qkv row
+    const long total = (long)rows * heads * half;
+    const long t = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= total) return;
+    const int i = (int)(t % half);
+    const int hd = (int)((t / half) % heads);
+    const int r = (int)(t / ((long)half * heads));
+    const int ld = (n_head + 2 * n_kv_head) * d_head;
+    T* x = qkv + (size_t)r * ld + (size_t)hd * d_head;
+    const double inv = exp(-log((double)theta) * 2.0 * (double)i / (double)d_head);
+    const double ang = (double)pos[r] * inv;
+    const float c = (float)cos(ang), s = (float)sin(ang);
+    const float a = to_f(x[i]), b = to_f(x[i + half]);
+    x[i] = from_f<T>(a * c - b * s);
+    x[i + half] = from_f<T>(b * c + a * s);
+}
+
+// ---------------------------------------------------------------- KV-cache append
+// cache layout [max_batch, n_ctx, n_kv_head * d_head]; one workgroup per row.
+template <typename T>
+__global__ __launch_bounds__(256) void k_kv_store(const T* __restrict__ qkv, const int32_t* __restrict__ seq,
+                                                  const int32_t* __restrict__ pos, T* __restrict__ kc,
+                                                  T* __restrict__ vc, int dq, int dkv, int n_ctx) {
+    const int r = blockIdx.x;
+    const T* k = qkv + (size_t)r * (dq + 2 * dkv) + dq;
+    const T* v = k + dkv;
+    const size_t o = ((size_t)seq[r] * n_ctx + pos[r]) * dkv;
+    for (int i = threadIdx.x; i < dkv; i += blockDim.x) {
+        kc[o + i] = k[i];
+        vc[o + i] = v[i];
+    }
+}
+
+// ---------------------------------------------------------------- SwiGLU gate
+template <typename T>
+__global__ __launch_bounds__(256) void k_swiglu(const T* __restrict__ gu, T* __restrict__ act, long total, int F) {
+    const long t = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= total) return;
+    const long r = t / F;
+    const int c = (int)(t % F);
+    const float g = to_f(gu[r * 2 * F + c]), u = to_f(gu[r * 2 * F + F + c]);
+    act[t] = from_f<T>(g / (1.f + expf(-g)) * u);
+}
+
+// ---------------------------------------------------------------- launchers
+#define SD_DISPATCH(dtype, CALL)                   \
+    if ((dtype) == SD_DTYPE_F32) { using T = float; CALL; } else { using T = bf16_t; CALL; }
+
+hipError_t launch_embed(int dtype, const int32_t* src, const int32_t* pos, const int32_t* prefix,
+                        const int32_t* block, const void* wte, const void* wpe, const float* temb, float* h,
+                        int rows, int d, hipStream_t st) {
+    if (rows <= 0) return hipSuccess;
+    SD_DISPATCH(dtype, (k_embed<T><<<rows, 256, 0, st>>>(src, pos, prefix, block, (const T*)wte, (const T*)wpe, temb, h, d)));
+    return hipGetLastError();
+}
+
+hipError_t launch_timestep_embed(int dtype, const void* w1, const float* b1, const void* w2, const float* b2,
+                                 float* hidden, float* temb, int T_steps, int d, hipStream_t st) {
+    SD_DISPATCH(dtype, (k_timestep_embed<T><<<T_steps, 256, 2 * d * sizeof(float), st>>>((const T*)w1, b1, (const T*)w2, b2, hidden, temb, T_steps, d)));
+    return hipGetLastError();
+}
+
+hipError_t launch_norm(int dtype, const float* h, const int32_t* idx, const float* gain, const float* bias,
+                       void* out, int rows, int d, float eps, hipStream_t st) {
+    if (rows <= 0) return hipSuccess;
+    if (d > 256 * kNormMaxPerThread) return hipErrorInvalidValue;
+    SD_DISPATCH(dtype, (k_norm<T><<<rows, 256, 0, st>>>(h, idx, gain, bias, (T*)out, d, eps)));
+    return hipGetLastError();
+}
+
+hipError_t launch_rope(int dtype, void* qkv, const int32_t* pos, int rows, int n_head, int n_kv_head, int d_head,
+                       float theta, hipStream_t st) {
+    const long total = (long)rows * (n_head + n_kv_head) * (d_head / 2);
+    if (total <= 0) return hipSuccess;
+    const int grid = (int)((total + 255) / 256);
+    SD_DISPATCH(dtype, (k_rope<T><<<grid, 256, 0, st>>>((T*)qkv, pos, rows, n_head, n_kv_head, d_head, theta)));
+    return hipGetLastError();
+}
+
+hipError_t launch_kv_store(int dtype, const void* qkv, const int32_t* seq, const int32_t* pos, void* kcache,
+                           void* vcache, int rows, int n_head, int n_kv_head, int d_head, int n_ctx, hipStream_t st) {
+    if (rows <= 0) return hipSuccess;
+    SD_DISPATCH(dtype, (k_kv_store<T><<<rows, 256, 0, st>>>((const T*)qkv, seq, pos, (T*)kcache, (T*)vcache, n_head * d_head, n_kv_head * d_head, n_ctx)));
+    return hipGetLastError();
+}
+
+hipError_t launch_swiglu(int dtype, const void* gu, void* act, int rows, int F, hipStream_t st) {
+    const long total = (long)rows * F;
+    if (total <= 0) return hipSuccess;
+    const int grid = (int)((total + 255) / 256);
+    SD_DISPATCH(dtype, (k_swiglu<T><<<grid, 256, 0, st>>>((const T*)gu, (T*)act, total, F)));
+    return hipGetLastError();
+}
+
+}  // namespace sd

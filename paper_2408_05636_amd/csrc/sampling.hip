@@ -1,0 +1,399 @@
+// Vocabulary-row kernels of Algorithm 1: softmax statistics, the reveal / categorical-sampling
+// step of the diffusion drafter, and the acceptance test with residual resampling.
+//
+// All probability-space arithmetic is fp64 (exp, normalisers, CDF prefix sums): these kernels
+// stream fp32 rows from HBM/L2 and are nowhere near ALU-bound, and fp64 keeps every integer
+// decision (which token, how many accepted) independent of the summation tree.  No float
+// atomics anywhere: every reduction has a fixed order, so results are run-to-run identical.
+//
+// A row of `vocab` logits is cut into chunks of kChunk columns; one 256-thread workgroup owns
+// one chunk (4 consecutive columns per thread), so a single row is spread over many CUs.
+#include "common.h"
+#include "philox.hip.h"
+
+namespace sd {
+
+constexpr int kThreads = 256;
+constexpr int kMaxChunks = 512;   // vocab <= 524288
+
+// ---------------------------------------------------------------- block-wide primitives (256 threads)
+__device__ inline double wave_sum(double v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, 64);
+    return v;   // valid in lane 0
+}
+__device__ inline double wave_max(double v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmax(v, __shfl_xor(v, o, 64));
+    return v;   // all lanes
+}
+__device__ inline double block_sum(double v, double* sh /*[4]*/) {
+    v = wave_sum(v);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return (sh[0] + sh[1]) + (sh[2] + sh[3]);
+}
+__device__ inline double block_max(double v, double* sh) {
+    v = wave_max(v);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return fmax(fmax(sh[0], sh[1]), fmax(sh[2], sh[3]));
+}
+__device__ inline int block_min_int(int v, int* sh) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = min(v, __shfl_xor(v, o, 64));
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return min(min(sh[0], sh[1]), min(sh[2], sh[3]));
+}
+__device__ inline int block_max_int(int v, int* sh) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = max(v, __shfl_xor(v, o, 64));
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return max(max(sh[0], sh[1]), max(sh[2], sh[3]));
+}
+// exclusive prefix sum over the 256 threads, in thread order
+__device__ inline double block_excl_scan(double v, double* sh /*[4]*/) {
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    double inc = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const double t = __shfl_up(inc, o, 64);
+        if (lane >= o) inc += t;
+    }
+    __syncthreads();
+    if (lane == 63) sh[wv] = inc;
+    __syncthreads();
+    double base = 0.0;
+    for (int i = 0; i < wv; ++i) base += sh[i];
+    return base + (inc - v);
+}
+
+// 4 consecutive logits of this thread; columns >= vocab read as -inf
+__device__ inline void load4(const float* row, int col, int vocab, float (&l)[4]) {
+    if (col + 3 < vocab) {
+        const float4 t = *reinterpret_cast<const float4*>(row + col);
+        l[0] = t.x; l[1] = t.y; l[2] = t.z; l[3] = t.w;
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) l[i] = (col + i < vocab) ? row[col + i] : -INFINITY;
+    }
+}
+
+// Is slot (b, k) revealed at reverse step `step`?  Probability 1/step: u < 1/step with
+// u = m 2^-24, decided exactly in integers as m * step < 2^24.
+__device__ inline bool reveal_now(int k, int step, int b, uint64_t seed) {
+    if (step == 1) return true;
+    const Philox4 r = philox4x32_10((uint32_t)k, (uint32_t)step, (uint32_t)b, STREAM_DRAFT, seed);
+    return (uint64_t)uniform_bits(r.x) * (uint64_t)step < (1ull << 24);
+}
+
+// ---------------------------------------------------------------- chunk statistics
+// grid (n_chunks, rows).  z != NULL: drafter mode, rows that are not revealed at this step are skipped.
+__global__ __launch_bounds__(kThreads) void k_row_stats(const float* __restrict__ logits, int ld, int vocab,
+                                                        const int32_t* __restrict__ z, int gamma, int step,
+                                                        uint64_t seed, double* __restrict__ part_m,
+                                                        double* __restrict__ part_s, int32_t* __restrict__ active) {
+    __shared__ double sh[4];
+    const int row = blockIdx.y, c = blockIdx.x, nch = gridDim.x;
+    if (z != nullptr) {
+        const bool act = (z[row] == vocab) && reveal_now(row % gamma, step, row / gamma, seed);
+        if (c == 0 && threadIdx.x == 0) active[row] = act ? 1 : 0;
+        if (!act) return;
+    }
+    float l[4];
+    load4(logits + (size_t)row * ld, c * kChunk + threadIdx.x * 4, vocab, l);
+    const double m = block_max((double)fmaxf(fmaxf(l[0], l[1]), fmaxf(l[2], l[3])), sh);
+    double s = 0.0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) s += exp((double)l[i] - m);   // exp(-inf) = 0 for padding columns
+    s = block_sum(s, sh);
+    if (threadIdx.x == 0) {
+        part_m[(size_t)row * nch + c] = m;
+        part_s[(size_t)row * nch + c] = s;
+    }
+}
+
+// Combine a row's chunk statistics: m = max_c m_c, sS[c] = s_c exp(m_c - m).  Block-uniform result.
+__device__ inline double combine_chunks(const double* pm, const double* ps, int nch, double* sS, double* sh) {
+    double m = -INFINITY;
+    for (int i = threadIdx.x; i < nch; i += kThreads) m = fmax(m, pm[i]);
+    m = block_max(m, sh);
+    for (int i = threadIdx.x; i < nch; i += kThreads) sS[i] = ps[i] * exp(pm[i] - m);
+    __syncthreads();
+    return m;
+}
+
+// Thread 0: total of sS[0..nch) in chunk order, the chunk where the running sum first exceeds
+// u * total and the running sum before that chunk.
+struct ChunkPick { double total, target, before; int chunk; };
+__device__ inline ChunkPick pick_chunk(const double* sS, int nch, double u) {
+    ChunkPick p;
+    double tot = 0.0;
+    for (int i = 0; i < nch; ++i) tot += sS[i];
+    p.total = tot;
+    p.target = u * tot;
+    double run = 0.0;
+    p.chunk = -1;
+    p.before = 0.0;
+    int last_pos = 0;
+    for (int i = 0; i < nch; ++i) {
+        if (sS[i] > 0.0) last_pos = i;
+        if (run + sS[i] > p.target) { p.chunk = i; p.before = run; break; }
+        run += sS[i];
+    }
+    if (p.chunk < 0) {          // rounding only: last chunk that carries mass
+        p.chunk = last_pos;
+        double r2 = 0.0;
+        for (int i = 0; i < last_pos; ++i) r2 += sS[i];
+        p.before = r2;
+    }
+    return p;
+}
+
+// Within one chunk: smallest column whose inclusive running sum exceeds target; if none (rounding),
+// the last column of the chunk with positive weight.  w: this thread's 4 weights.  Block-uniform result.
+__device__ inline int select_in_chunk(const double (&w)[4], int col0, double before, double target, double* sh,
+                                      int* shi) {
+    const double mine = ((w[0] + w[1]) + w[2]) + w[3];
+    double run = before + block_excl_scan(mine, sh);
+    int cand = INT_MAX, lastpos = -1;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        run += w[i];
+        if (w[i] > 0.0) lastpos = col0 + i;
+        if (cand == INT_MAX && run > target && w[i] > 0.0) cand = col0 + i;
+    }
+    cand = block_min_int(cand, shi);
+    if (cand != INT_MAX) return cand;
+    return block_max_int(lastpos, shi);
+}
+
+// ---------------------------------------------------------------- reveal + sample (drafter)
+// grid (n_chunks, rows).  Writes the full q row of every revealed slot; the workgroup owning the
+// chunk where the CDF crosses u picks the token.
+__global__ __launch_bounds__(kThreads) void k_unmask_sample(const float* __restrict__ logits, int ld, int vocab,
+                                                            int gamma, int step, uint64_t seed,
+                                                            const double* __restrict__ part_m,
+                                                            const double* __restrict__ part_s,
+                                                            const int32_t* __restrict__ active, int32_t* __restrict__ z,
+                                                            float* __restrict__ q, float* __restrict__ qtok) {
+    __shared__ double sS[kMaxChunks];
+    __shared__ double sh[4];
+    __shared__ int shi[4];
+    __shared__ ChunkPick pick;
+    const int row = blockIdx.y, c = blockIdx.x, nch = gridDim.x;
+    if (!active[row]) return;
+    const double m = combine_chunks(part_m + (size_t)row * nch, part_s + (size_t)row * nch, nch, sS, sh);
+    if (threadIdx.x == 0) {
+        const Philox4 r = philox4x32_10((uint32_t)(row % gamma), (uint32_t)step, (uint32_t)(row / gamma),
+                                        STREAM_DRAFT, seed);
+        pick = pick_chunk(sS, nch, uniform_f64(r.y));
+    }
+    __syncthreads();
+    const double Z = pick.total;
+    const int col0 = c * kChunk + threadIdx.x * 4;
+    float l[4];
+    load4(logits + (size_t)row * ld, col0, vocab, l);
+    double w[4];
+    float qv[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        w[i] = exp((double)l[i] - m);
+        qv[i] = (float)(w[i] / Z);
+    }
+    if (col0 < ld) *reinterpret_cast<float4*>(q + (size_t)row * ld + col0) = make_float4(qv[0], qv[1], qv[2], qv[3]);
+    if (c != pick.chunk) return;
+    const int v = select_in_chunk(w, col0, pick.before, pick.target, sh, shi);
+    if (v >= col0 && v < col0 + 4) {
+        z[row] = v;
+        qtok[row] = qv[v - col0];
+    }
+}
+
+// ---------------------------------------------------------------- acceptance (target)
+// grid (batch).  Row statistics of P[0..gamma], the gamma acceptance tests, n = first rejection.
+__global__ __launch_bounds__(kThreads) void k_accept(const float* __restrict__ p_logits, const float* __restrict__ q,
+                                                     const int32_t* __restrict__ draft, int ld, int vocab, int gamma,
+                                                     int nch, uint64_t seed, const double* __restrict__ part_m,
+                                                     const double* __restrict__ part_s, int32_t* __restrict__ n_acc,
+                                                     double* __restrict__ row_m, double* __restrict__ row_z) {
+    extern __shared__ double dyn[];          // [gamma+1] maxima, [gamma+1] normalisers
+    __shared__ int shi[4];
+    double* rm = dyn;
+    double* rz = dyn + (gamma + 1);
+    const int b = blockIdx.x, lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    for (int k = wv; k <= gamma; k += kThreads / 64) {
+        const size_t o = ((size_t)b * (gamma + 1) + k) * nch;
+        double m = -INFINITY;
+        for (int i = lane; i < nch; i += 64) m = fmax(m, part_m[o + i]);
+        m = wave_max(m);
+        double s = 0.0;
+        for (int i = lane; i < nch; i += 64) s += part_s[o + i] * exp(part_m[o + i] - m);
+        s = wave_sum(s);
+        if (lane == 0) { rm[k] = m; rz[k] = s; }
+    }
+    __syncthreads();
+    int first_reject = gamma;
+    for (int k = threadIdx.x; k < gamma; k += kThreads) {
+        const int x = draft[b * gamma + k];
+        bool ok = false;
+        if ((unsigned)x < (unsigned)vocab) {
+            const size_t prow = (size_t)b * (gamma + 1) + k, qrow = (size_t)b * gamma + k;
+            const float px = (float)(exp((double)p_logits[prow * ld + x] - rm[k]) / rz[k]);
+            const float qx = q[qrow * ld + x];
+            const Philox4 r = philox4x32_10((uint32_t)k, 0u, (uint32_t)b, STREAM_VERIFY, seed);
+            ok = __fmul_rn(uniform_f32(r.x), qx) <= px;        // accept iff r q(x) <= p(x), fp32 product
+        }
+        if (!ok) first_reject = min(first_reject, k);
+    }
+    const int n = block_min_int(first_reject, shi);
+    if (threadIdx.x == 0) {
+        n_acc[b] = n;
+        row_m[b] = rm[n];
+        row_z[b] = rz[n];
+    }
+}
+
+// Weight of column i of the row the final token is drawn from: residual max(0, p - q) after a
+// rejection, p itself after full acceptance (or when the residual carries no mass).
+__device__ inline double final_weight(float l, float qv, double m, double Z, bool use_residual) {
+    const double p = exp((double)l - m) / Z;
+    return use_residual ? fmax(0.0, p - (double)qv) : p;
+}
+
+// grid (n_chunks, batch): chunk sums of the final-token weights.
+__global__ __launch_bounds__(kThreads) void k_final_partial(const float* __restrict__ p_logits,
+                                                            const float* __restrict__ q, int ld, int vocab, int gamma,
+                                                            const int32_t* __restrict__ n_acc,
+                                                            const double* __restrict__ row_m,
+                                                            const double* __restrict__ row_z,
+                                                            double* __restrict__ part_r) {
+    __shared__ double sh[4];
+    const int b = blockIdx.y, c = blockIdx.x, nch = gridDim.x;
+    const int n = n_acc[b];
+    const bool resid = n < gamma;
+    const int col0 = c * kChunk + threadIdx.x * 4;
+    float l[4], qv[4] = {0.f, 0.f, 0.f, 0.f};
+    load4(p_logits + ((size_t)b * (gamma + 1) + n) * ld, col0, vocab, l);
+    if (resid && col0 < ld) {
+        const float4 t = *reinterpret_cast<const float4*>(q + ((size_t)b * gamma + n) * ld + col0);
+        qv[0] = t.x; qv[1] = t.y; qv[2] = t.z; qv[3] = t.w;
+    }
+    const double m = row_m[b], Z = row_z[b];
+    double w[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) w[i] = (col0 + i < vocab) ? final_weight(l[i], qv[i], m, Z, resid) : 0.0;
+    const double s = block_sum(((w[0] + w[1]) + w[2]) + w[3], sh);
+    if (threadIdx.x == 0) part_r[(size_t)b * nch + c] = s;
+}
+
+// grid (batch): pick the chunk, then the token.
+__global__ __launch_bounds__(kThreads) void k_final_sample(const float* __restrict__ p_logits,
+                                                           const float* __restrict__ q, int ld, int vocab, int gamma,
+                                                           int nch, uint64_t seed, const int32_t* __restrict__ n_acc,
+                                                           const double* __restrict__ row_m,
+                                                           const double* __restrict__ row_z,
+                                                           const double* __restrict__ part_m,
+                                                           const double* __restrict__ part_s,
+                                                           const double* __restrict__ part_r,
+                                                           int32_t* __restrict__ token) {
+    __shared__ double sS[kMaxChunks];
+    __shared__ double sh[4];
+    __shared__ int shi[4];
+    __shared__ ChunkPick pick;
+    __shared__ int s_resid;
+    const int b = blockIdx.x;
+    const int n = n_acc[b];
+    const double m = row_m[b], Z = row_z[b];
+    for (int i = threadIdx.x; i < nch; i += kThreads) sS[i] = part_r[(size_t)b * nch + i];
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const Philox4 r = philox4x32_10((uint32_t)n, 0u, (uint32_t)b, STREAM_VERIFY, seed);
+        const double u = uniform_f64(r.y);
+        int resid = n < gamma;
+        if (resid) {
+            double tot = 0.0;
+            for (int i = 0; i < nch; ++i) tot += sS[i];
+            if (!(tot > 0.0)) {      // empty residual (cannot happen in exact arithmetic): draw from p
+                resid = 0;
+                const size_t o = ((size_t)b * (gamma + 1) + n) * nch;
+                for (int i = 0; i < nch; ++i) sS[i] = part_s[o + i] * exp(part_m[o + i] - m) / Z;
+            }
+        }
+        s_resid = resid;
+        pick = pick_chunk(sS, nch, u);
+    }
+    __syncthreads();
+    const bool resid = s_resid != 0;
+    const int col0 = pick.chunk * kChunk + threadIdx.x * 4;
+    float l[4], qv[4] = {0.f, 0.f, 0.f, 0.f};
+    load4(p_logits + ((size_t)b * (gamma + 1) + n) * ld, col0, vocab, l);
+    if (resid && col0 < ld) {
+        const float4 t = *reinterpret_cast<const float4*>(q + ((size_t)b * gamma + n) * ld + col0);
+        qv[0] = t.x; qv[1] = t.y; qv[2] = t.z; qv[3] = t.w;
+    }
+    double w[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) w[i] = (col0 + i < vocab) ? final_weight(l[i], qv[i], m, Z, resid) : 0.0;
+    const int v = select_in_chunk(w, col0, pick.before, pick.target, sh, shi);
+    if (threadIdx.x == 0) token[b] = v;
+}
+
+// ---------------------------------------------------------------- host side
+int64_t sampling_scratch_bytes(int rows, int vocab) {
+    if (rows <= 0 || vocab <= 0) return 0;
+    const int64_t nch = n_chunks(vocab);
+    int64_t b = 0;
+    b += align_up(rows * nch * 8, 256) * 3;   // part_m, part_s, part_r
+    b += align_up((int64_t)rows * 8, 256) * 2; // row_m, row_z
+    b += align_up((int64_t)rows * 4, 256);     // active
+    return b;
+}
+
+SampleScratch sampling_scratch(void* base, int rows, int vocab) {
+    const int64_t nch = n_chunks(vocab);
+    char* p = static_cast<char*>(base);
+    SampleScratch s;
+    const int64_t big = align_up(rows * nch * 8, 256), small = align_up((int64_t)rows * 8, 256);
+    s.part_m = reinterpret_cast<double*>(p); p += big;
+    s.part_s = reinterpret_cast<double*>(p); p += big;
+    s.part_r = reinterpret_cast<double*>(p); p += big;
+    s.row_m = reinterpret_cast<double*>(p); p += small;
+    s.row_z = reinterpret_cast<double*>(p); p += small;
+    s.active = reinterpret_cast<int32_t*>(p);
+    return s;
+}
+
+hipError_t launch_unmask_sample(const float* logits, int batch, int gamma, int vocab, int step, uint64_t seed,
+                                int32_t* z, float* q, float* qtok, const SampleScratch& s, hipStream_t st) {
+    const int rows = batch * gamma, nch = n_chunks(vocab), ld = vocab_pad(vocab);
+    const dim3 grid(nch, rows);
+    k_row_stats<<<grid, kThreads, 0, st>>>(logits, ld, vocab, z, gamma, step, seed, s.part_m, s.part_s, s.active);
+    k_unmask_sample<<<grid, kThreads, 0, st>>>(logits, ld, vocab, gamma, step, seed, s.part_m, s.part_s, s.active, z,
+                                               q, qtok);
+    return hipGetLastError();
+}
+
+hipError_t launch_accept_resample(const float* p_logits, const float* q, const int32_t* draft, int batch,
+                                  int gamma, int vocab, uint64_t seed, int32_t* n_acc, int32_t* token,
+                                  const SampleScratch& s, hipStream_t st) {
+    const int rows = batch * (gamma + 1), nch = n_chunks(vocab), ld = vocab_pad(vocab);
+    k_row_stats<<<dim3(nch, rows), kThreads, 0, st>>>(p_logits, ld, vocab, nullptr, gamma, 0, seed, s.part_m,
+                                                      s.part_s, s.active);
+    k_accept<<<batch, kThreads, 2 * (gamma + 1) * sizeof(double), st>>>(p_logits, q, draft, ld, vocab, gamma, nch,
+                                                                       seed, s.part_m, s.part_s, n_acc, s.row_m,
+                                                                       s.row_z);
+    k_final_partial<<<dim3(nch, batch), kThreads, 0, st>>>(p_logits, q, ld, vocab, gamma, n_acc, s.row_m, s.row_z,
+                                                           s.part_r);
+    k_final_sample<<<batch, kThreads, 0, st>>>(p_logits, q, ld, vocab, gamma, nch, seed, n_acc, s.row_m, s.row_z,
+                                               s.part_m, s.part_s, s.part_r, token);
+    return hipGetLastError();
+}
+
+}  // namespace sd
