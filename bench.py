@@ -1,0 +1,148 @@
+"""Benchmark of one SpecDiff draft-then-verify round on one MI355X.
+
+A step is one whole round (sd_round): T drafter evaluations with their vocabulary softmax and
+reveal/sampling step, one target evaluation against its KV cache, acceptance and residual
+resampling.  Inputs (weights, KV cache of the prefix, prefix tokens) are resident in HBM before
+the timed region; each step uploads ~1 KB of token ids / row maps and reads back gamma + 2 ints.
+
+Prints ONE JSON line: verified tokens/s of the whole job, the roofline fraction of the dominant
+kernel (HIP-event timing from an instrumented second pass over the same steps) and the CPU
+oracle's rate on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0
+PEAK_MFMA_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
+
+
+def prefixes_for(w, seed):
+    from paper_2408_05636_amd import synth
+    V = w["target"].vocab
+    if isinstance(w["prefix_len"], tuple):
+        lens = synth.gen_prefix_lengths(w["batch"], w["prefix_len"][0], w["prefix_len"][1], seed)
+    else:
+        lens = [w["prefix_len"]] * w["batch"]
+    return [synth.gen_prefix(V, int(L), seed + 1 + i) for i, L in enumerate(lens)]
+
+
+def cpu_baseline(w, Wt, Wd, prefixes, seed):
+    """The oracle as it stands, one round of sequence 0 of the same workload."""
+    from threadpoolctl import threadpool_info
+    from oracle import specdiff as osd
+    from oracle import transformer as otf
+    t, d, gamma, T = w["target"], w["drafter"], w["gamma"], w["T"]
+    p = prefixes[0]
+    t0 = time.perf_counter()
+    dl = lambda tokens, tt: otf.logits_at(Wd, d, tokens, np.arange(len(tokens) - gamma, len(tokens)), tt)
+    z, q, _, nf = osd.oracle_draft(dl, p, gamma, T, seed, t.vocab)
+    tl = lambda tokens, rows: otf.logits_at(Wt, t, tokens, rows)
+    n, tok, _, _ = osd.oracle_verify(tl, p, z, q, seed)
+    dt = time.perf_counter() - t0
+    threads = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
+    return {"value": (n + 1) / dt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"1 round of sequence 0 ({nf} drafter + 1 target fp64 forwards over {len(p) + gamma} tokens), "
+                      f"{dt:.1f} s, {n + 1} tokens"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=40)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="gpt2s")
+    ap.add_argument("--gamma", type=int, default=0)
+    ap.add_argument("--T", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-profile", action="store_true")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2408_05636_amd import binding, synth
+
+    w = synth.workload(a.workload)
+    if a.gamma:
+        w["gamma"] = a.gamma
+    if a.T:
+        w["T"] = a.T
+    t, d, gamma, T, B = w["target"], w["drafter"], w["gamma"], w["T"], w["batch"]
+    Wt, Wd = synth.gen_weights(t, 1), synth.gen_weights(d, 2)
+    sd = binding.SpecDiff(t, d, Wt, Wd, max_batch=B, gamma_max=gamma)
+    prefixes = prefixes_for(w, 3)
+    flat, lens = binding._ragged(prefixes)
+    sd.sd_prefill(prefixes)                       # prompt processing: outside the round
+
+    for i in range(a.warmup):
+        sd.sd_round_flat(flat, lens, gamma, T, 100 + i)
+    torch.cuda.synchronize()
+    tokens = accepted = 0
+    t0 = time.perf_counter()
+    for i in range(a.steps):
+        _, n, _ = sd.sd_round_flat(flat, lens, gamma, T, 1000 + i)
+        tokens += int(n.sum()) + B
+        accepted += int(n.sum())
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / a.steps * 1e3
+
+    roof = None
+    phases = None
+    if not a.no_profile:
+        sd.sd_profile_begin()
+        for i in range(a.steps):
+            sd.sd_round_flat(flat, lens, gamma, T, 1000 + i)
+        prof = sd.sd_profile_end()
+        prof.sort(key=lambda e: -e["ms"])
+        total = sum(e["ms"] for e in prof)
+        phases = [{"kernel": e["name"], "launches_per_step": e["launches"] / a.steps,
+                   "us_per_launch": round(1e3 * e["ms"] / e["launches"], 3), "share": round(e["ms"] / total, 4)} for e in prof]
+        e = prof[0]
+        us = 1e3 * e["ms"] / e["launches"]
+        gbs = e["bytes"] / e["launches"] / (us * 1e-6) / 1e9
+        tfl = e["flops"] / e["launches"] / (us * 1e-6) / 1e12
+        peak_f = PEAK_MFMA_TFLOPS[t.dtype]
+        if gbs / PEAK_HBM_GBS >= tfl / peak_f:
+            roof = {"kernel": e["name"], "bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                    "frac": gbs / PEAK_HBM_GBS, "traffic": None}
+        else:
+            roof = {"kernel": e["name"], "bound": "mfma", "achieved": tfl, "peak": peak_f, "unit": "TFLOP/s",
+                    "frac": tfl / peak_f, "traffic": None}
+        roof["us_per_launch"] = us
+        roof["algorithmic_bytes_per_launch"] = e["bytes"] / e["launches"]
+        roof["flops_per_launch"] = e["flops"] / e["launches"]
+        tr = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+        if os.path.exists(tr):
+            roof["traffic"] = json.load(open(tr)).get(a.workload, {}).get(e["name"])
+
+    cpu = None
+    if not a.no_cpu_baseline:
+        cpu = cpu_baseline(w, Wt, Wd, prefixes, 1000)
+
+    out = {
+        "metric": "verified tokens/s", "value": tokens / dt, "unit": "tokens/s", "n_gpus": 1, "steps": a.steps,
+        "warmup": a.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": t.dtype, "data": "synthetic",
+        "config": {"workload": f"{a.workload}: one SpecDiff round, target {t.n_layer}L d={t.d_model} V={t.vocab}, "
+                               f"drafter {d.n_layer}L d={d.d_model}, prefix {[int(x) for x in lens][:4]}, "
+                               f"gamma={gamma}, T={T}, batch={B}, random-init weights"},
+        "round_latency_us": ms_per_step * 1e3,
+        "mean_accepted_per_round": accepted / (a.steps * B),
+        "roofline": roof, "cpu_baseline": cpu, "kernels": phases,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -84,7 +84,8 @@ int32_t sd_create(const sd_model_config *target, const sd_model_config *drafter,
                   const void *target_w, const void *drafter_w, int32_t max_batch, int32_t gamma_max,
                   void *workspace, int64_t workspace_bytes, void *hip_stream, sd_handle **out);
 void sd_destroy(sd_handle *h);
-/* Library-owned message describing the last failure on this handle (never NULL). */
+/* Library-owned message describing the last failure on this handle (never NULL); with
+ * h == NULL, the reason the last sd_create failed. */
 const char *sd_last_error(const sd_handle *h);
 
 /* Fill the target's KV cache for tokens [0, prefix_len[b]-1) of every sequence (prompt
@@ -160,6 +161,18 @@ int32_t sd_accept_resample(const float *p_logits, const float *q, const int32_t 
  * 3: y (fp32) = acc.  ldy in elements of y. */
 int32_t sd_linear(int32_t dtype, const void *x, const void *w, const float *bias, void *y,
                   int32_t m, int32_t n, int32_t k, int32_t ldy, int32_t epilogue, void *hip_stream);
+
+/* ---- per-kernel timing ----------------------------------------------------------------------
+ * Between sd_profile_begin and sd_profile_end every kernel launch of the handle is bracketed by
+ * HIP events on its stream; entries accumulate, per kernel name, the launch count, the summed
+ * elapsed milliseconds and the summed algorithmic bytes and flops of those launches (operands
+ * read once, results written once).  The events cost a few microseconds per launch: time a
+ * round without profiling.  name: caller buffer of name_cap bytes. */
+int32_t sd_profile_begin(sd_handle *h);
+int32_t sd_profile_end(sd_handle *h);
+int32_t sd_profile_count(const sd_handle *h);
+int32_t sd_profile_entry(const sd_handle *h, int32_t index, char *name, int32_t name_cap, int64_t *launches,
+                         double *total_ms, double *bytes, double *flops);
 
 #ifdef __cplusplus
 }

@@ -22,7 +22,8 @@ STATUS_NAMES = {0: "SD_OK", 1: "SD_ERR_ARG", 2: "SD_ERR_SHAPE", 3: "SD_ERR_TOKEN
                 5: "SD_ERR_WORKSPACE", 6: "SD_ERR_HIP"}
 EXPORTS = ["sd_vocab_pad", "sd_weight_count", "sd_weight_desc", "sd_weight_bytes", "sd_workspace_bytes", "sd_create",
            "sd_destroy", "sd_last_error", "sd_prefill", "sd_draft", "sd_verify", "sd_round", "sd_drafter_logits",
-           "sd_target_logits", "sd_sampling_scratch_bytes", "sd_unmask_sample", "sd_accept_resample", "sd_linear"]
+           "sd_target_logits", "sd_sampling_scratch_bytes", "sd_unmask_sample", "sd_accept_resample", "sd_linear",
+           "sd_profile_begin", "sd_profile_end", "sd_profile_count", "sd_profile_entry"]
 
 
 class SdModelConfig(C.Structure):
@@ -46,6 +47,9 @@ def lib() -> C.CDLL:
         if not os.path.exists(LIB_PATH):
             raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2408_05636_amd.build` "
                                "(there is no fallback path)")
+        # torch ships its own HIP runtime (same soname): load it first so that the library binds to
+        # the runtime that owns torch's device memory and streams, whatever the import order.
+        import torch  # noqa: F401
         L = C.CDLL(LIB_PATH)
         i32, i64, u64, vp, ip, fp = C.c_int32, C.c_int64, C.c_uint64, C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_float)
         cfgp = C.POINTER(SdModelConfig)
@@ -72,6 +76,12 @@ def lib() -> C.CDLL:
         L.sd_accept_resample.argtypes = [vp, vp, vp, i32, i32, i32, u64, vp, vp, vp, i64, vp]
         L.sd_linear.restype = i32
         L.sd_linear.argtypes = [i32, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp]
+        L.sd_profile_begin.restype = i32; L.sd_profile_begin.argtypes = [vp]
+        L.sd_profile_end.restype = i32; L.sd_profile_end.argtypes = [vp]
+        L.sd_profile_count.restype = i32; L.sd_profile_count.argtypes = [vp]
+        L.sd_profile_entry.restype = i32
+        L.sd_profile_entry.argtypes = [vp, i32, C.c_char_p, i32, C.POINTER(i64), C.POINTER(C.c_double),
+                                       C.POINTER(C.c_double), C.POINTER(C.c_double)]
         _lib = L
     return _lib
 
@@ -158,7 +168,7 @@ class SpecDiff:
         rc = lib().sd_create(C.byref(self._ct), C.byref(self._cd), self.tw.data_ptr(), self.dw.data_ptr(), max_batch,
                              gamma_max, self.workspace.data_ptr(), nbytes, self.stream.cuda_stream, C.byref(h))
         if rc:
-            raise SdError(rc, "sd_create")
+            raise SdError(rc, "sd_create", lib().sd_last_error(None).decode())
         self.h = h
 
     def close(self):
@@ -178,6 +188,21 @@ class SpecDiff:
         off = ptr - self.workspace.data_ptr()
         assert 0 <= off and off + rows * self.ld * 4 <= self.workspace.numel()
         return self.workspace[off:off + rows * self.ld * 4].view(self.torch.float32).view(rows, self.ld)
+
+    def sd_profile_begin(self):
+        self._check(lib().sd_profile_begin(self.h), "sd_profile_begin")
+
+    def sd_profile_end(self):
+        """-> [dict(name, launches, ms, bytes, flops)] accumulated since sd_profile_begin."""
+        self._check(lib().sd_profile_end(self.h), "sd_profile_end")
+        out = []
+        for i in range(lib().sd_profile_count(self.h)):
+            name = C.create_string_buffer(128)
+            n, ms, by, fl = C.c_int64(), C.c_double(), C.c_double(), C.c_double()
+            self._check(lib().sd_profile_entry(self.h, i, name, 128, C.byref(n), C.byref(ms), C.byref(by), C.byref(fl)),
+                        "sd_profile_entry")
+            out.append(dict(name=name.value.decode(), launches=n.value, ms=ms.value, bytes=by.value, flops=fl.value))
+        return out
 
     def sd_prefill(self, prefixes):
         flat, lens = _ragged(prefixes)

@@ -219,9 +219,26 @@ int64_t carve(Arena& a, Buffers& b, const sd_model_config& t, const sd_model_con
 }  // namespace
 
 // ------------------------------------------------------------------------------------------
+// per-kernel timing with HIP events on the handle's stream (off unless sd_profile_begin was called)
+// ------------------------------------------------------------------------------------------
+struct ProfEntry {
+    std::string name;
+    int64_t launches = 0;
+    double ms = 0.0, bytes = 0.0, flops = 0.0;
+};
+struct Profiler {
+    bool on = false;
+    std::vector<hipEvent_t> events;      // pairs (start, stop)
+    size_t used = 0;
+    std::vector<int> pending;            // entry index per used pair
+    std::vector<ProfEntry> entries;
+};
+
+// ------------------------------------------------------------------------------------------
 // handle
 // ------------------------------------------------------------------------------------------
 struct sd_handle {
+    Profiler prof;
     Model target, drafter;
     Buffers buf;
     Limits lim;
@@ -253,6 +270,63 @@ namespace {
         }                                                                                         \
     } while (0)
 
+void prof_start(sd_handle* h) {
+    Profiler& p = h->prof;
+    if (!p.on) return;
+    if (p.used + 2 > p.events.size()) {
+        for (int i = 0; i < 2; ++i) {
+            hipEvent_t e;
+            if (hipEventCreate(&e) != hipSuccess) { p.on = false; return; }
+            p.events.push_back(e);
+        }
+    }
+    (void)hipEventRecord(p.events[p.used], h->st);
+}
+
+void prof_stop(sd_handle* h, const char* name, double bytes, double flops) {
+    Profiler& p = h->prof;
+    if (!p.on) return;
+    (void)hipEventRecord(p.events[p.used + 1], h->st);
+    int idx = -1;
+    for (size_t i = 0; i < p.entries.size(); ++i)
+        if (p.entries[i].name == name) { idx = (int)i; break; }
+    if (idx < 0) { p.entries.push_back(ProfEntry()); idx = (int)p.entries.size() - 1; p.entries[idx].name = name; }
+    p.entries[idx].launches += 1;
+    p.entries[idx].bytes += bytes;
+    p.entries[idx].flops += flops;
+    p.pending.push_back(idx);
+    p.used += 2;
+}
+
+// After a stream synchronisation: fold the elapsed times of the recorded pairs into the entries.
+void prof_flush(sd_handle* h) {
+    Profiler& p = h->prof;
+    for (size_t i = 0; i < p.pending.size(); ++i) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, p.events[2 * i], p.events[2 * i + 1]) == hipSuccess) p.entries[p.pending[i]].ms += ms;
+    }
+    p.pending.clear();
+    p.used = 0;
+}
+
+// Launch with optional event bracketing.  NAME may be assigned by the launcher (kernel variant).
+#define SD_LAUNCH(h, NAME, BYTES, FLOPS, expr)                                                    \
+    do {                                                                                          \
+        prof_start(h);                                                                            \
+        hipError_t e_ = (expr);                                                                   \
+        prof_stop(h, NAME, (double)(BYTES), (double)(FLOPS));                                     \
+        if (e_ != hipSuccess) {                                                                   \
+            (h)->err = std::string(#expr) + ": " + hipGetErrorString(e_);                         \
+            return SD_ERR_HIP;                                                                    \
+        }                                                                                         \
+    } while (0)
+
+int sync_stream(sd_handle* h) {
+    SD_HIP(h, hipStreamSynchronize(h->st));
+    if (h->prof.on || !h->prof.pending.empty()) prof_flush(h);
+    return SD_OK;
+}
+
 int fail(sd_handle* h, int code, const std::string& msg) {
     if (h) h->err = msg;
     return code;
@@ -281,7 +355,7 @@ int check_batch(sd_handle* h, int batch, const int32_t* tokens, const int32_t* l
     return SD_OK;
 }
 
-struct RowMaps { int rows = 0; int max_kv = 0; };
+struct RowMaps { int rows = 0; int max_kv = 0; double kv_sum = 0; double kv_rows = 0; };   // kv_sum: sum of kv_len; kv_rows: distinct key rows
 
 // Upload prefix tokens and per-row maps.  mode 0: drafter over prefix o block; 1: target query rows
 // (last prefix token + gamma draft tokens); 2: target prefill rows [0, L-1).
@@ -350,10 +424,26 @@ int upload_rows(sd_handle* h, int mode, int batch, const int32_t* tokens, const 
         SD_HIP(h, hipMemcpyAsync(B.blk_idx, s_blk, (int64_t)batch * gamma * 4, hipMemcpyHostToDevice, h->st));
     out->rows = (int)r;
     out->max_kv = max_kv;
+    out->kv_sum = 0;
+    out->kv_rows = 0;
+    for (int64_t i = 0; i < r; ++i) out->kv_sum += s_kvl[i];
+    for (int b = 0; b < batch; ++b) out->kv_rows += mode == 0 ? len[b] + gamma : (mode == 1 ? len[b] + gamma : len[b] - 1);
     return SD_OK;
 }
 
 // Transformer layers over the rows described by the uploaded maps; residual stream in buf.h.
+// The byte / flop figures passed to SD_LAUNCH are the algorithmic ones (operands read once,
+// results written once).
+int run_linear(sd_handle* h, int dt, const void* x, const void* w, const float* bias, void* y, int m, int n, int k,
+               int ldy, int epi) {
+    const double ew = dt == SD_DTYPE_BF16 ? 2 : 4;
+    const double out_b = epi == EPI_RESID ? 8.0 : (epi == EPI_F32 ? 4.0 : ew);
+    const double bytes = ((double)m * k + (double)n * k) * ew + (double)m * n * out_b;
+    const char* name = "linear";
+    SD_LAUNCH(h, name, bytes, 2.0 * m * n * k, launch_linear(dt, x, w, bias, y, m, n, k, ldy, epi, h->st, &name));
+    return SD_OK;
+}
+
 int run_layers(sd_handle* h, const Model& m, const RowMaps& rm, const float* temb) {
     Buffers& B = h->buf;
     const sd_model_config& c = m.c;
@@ -361,13 +451,15 @@ int run_layers(sd_handle* h, const Model& m, const RowMaps& rm, const float* tem
     if (rows == 0) return SD_OK;
     const bool cached = !c.bidirectional;
     const int qkv_w = m.dq + 2 * m.dkv;
-    SD_HIP(h, launch_embed(dt, B.row_src, B.row_pos, B.prefix, B.z, m.wte, m.wpe, temb, B.h, rows, d, h->st));
+    const double ew = m.ew, rd = (double)rows * d;
+    int rc;
+    SD_LAUNCH(h, "k_embed", rd * (4 + ew), 0, launch_embed(dt, B.row_src, B.row_pos, B.prefix, B.z, m.wte, m.wpe, temb, B.h, rows, d, h->st));
     for (int i = 0; i < c.n_layer; ++i) {
         const Layer& l = m.L[i];
-        SD_HIP(h, launch_norm(dt, B.h, nullptr, l.ln1_g, l.ln1_b, B.xn, rows, d, c.norm_eps, h->st));
-        SD_HIP(h, launch_linear(dt, B.xn, l.w_qkv, l.b_qkv, B.qkv, rows, qkv_w, d, qkv_w, EPI_STORE, h->st));
+        SD_LAUNCH(h, "k_norm", rd * (4 + ew), 0, launch_norm(dt, B.h, nullptr, l.ln1_g, l.ln1_b, B.xn, rows, d, c.norm_eps, h->st));
+        if ((rc = run_linear(h, dt, B.xn, l.w_qkv, l.b_qkv, B.qkv, rows, qkv_w, d, qkv_w, EPI_STORE))) return rc;
         if (c.arch == SD_ARCH_LLAMA)
-            SD_HIP(h, launch_rope(dt, B.qkv, B.row_pos, rows, c.n_head, c.n_kv_head, m.dh, c.rope_theta, h->st));
+            SD_LAUNCH(h, "k_rope", 2.0 * rows * (m.dq + m.dkv) * ew, 0, launch_rope(dt, B.qkv, B.row_pos, rows, c.n_head, c.n_kv_head, m.dh, c.rope_theta, h->st));
         AttnArgs a;
         a.q = B.qkv; a.q_ld = qkv_w;
         a.kv_off = B.kv_off; a.kv_len = B.kv_len;
@@ -377,23 +469,24 @@ int run_layers(sd_handle* h, const Model& m, const RowMaps& rm, const float* tem
             const int64_t per_layer = (int64_t)h->max_batch * c.n_ctx * m.dkv * m.ew;
             char* kc = static_cast<char*>(B.kcache) + i * per_layer;
             char* vc = static_cast<char*>(B.vcache) + i * per_layer;
-            SD_HIP(h, launch_kv_store(dt, B.qkv, B.row_seq, B.row_pos, kc, vc, rows, c.n_head, c.n_kv_head, m.dh, c.n_ctx, h->st));
+            SD_LAUNCH(h, "k_kv_store", 4.0 * rows * m.dkv * ew, 0, launch_kv_store(dt, B.qkv, B.row_seq, B.row_pos, kc, vc, rows, c.n_head, c.n_kv_head, m.dh, c.n_ctx, h->st));
             a.k = kc; a.v = vc; a.kv_ld = m.dkv;
         } else {
             a.k = static_cast<char*>(B.qkv) + (int64_t)m.dq * m.ew;
             a.v = static_cast<char*>(B.qkv) + (int64_t)(m.dq + m.dkv) * m.ew;
             a.kv_ld = qkv_w;
         }
-        SD_HIP(h, launch_attention(dt, a, h->st));
-        SD_HIP(h, launch_linear(dt, B.att, l.w_o, l.b_o, B.h, rows, d, d, d, EPI_RESID, h->st));
-        SD_HIP(h, launch_norm(dt, B.h, nullptr, l.ln2_g, l.ln2_b, B.xn, rows, d, c.norm_eps, h->st));
+        const char* aname = "attention";
+        SD_LAUNCH(h, aname, 2.0 * rd * ew + 2.0 * rm.kv_rows * m.dkv * ew, 4.0 * rm.kv_sum * d, launch_attention(dt, a, h->st, &aname));
+        if ((rc = run_linear(h, dt, B.att, l.w_o, l.b_o, B.h, rows, d, d, d, EPI_RESID))) return rc;
+        SD_LAUNCH(h, "k_norm", rd * (4 + ew), 0, launch_norm(dt, B.h, nullptr, l.ln2_g, l.ln2_b, B.xn, rows, d, c.norm_eps, h->st));
         if (c.arch == SD_ARCH_GPT2) {
-            SD_HIP(h, launch_linear(dt, B.xn, l.w_fc, l.b_fc, B.mlp, rows, c.d_ff, d, c.d_ff, EPI_GELU, h->st));
-            SD_HIP(h, launch_linear(dt, B.mlp, l.w_proj, l.b_proj, B.h, rows, d, c.d_ff, d, EPI_RESID, h->st));
+            if ((rc = run_linear(h, dt, B.xn, l.w_fc, l.b_fc, B.mlp, rows, c.d_ff, d, c.d_ff, EPI_GELU))) return rc;
+            if ((rc = run_linear(h, dt, B.mlp, l.w_proj, l.b_proj, B.h, rows, d, c.d_ff, d, EPI_RESID))) return rc;
         } else {
-            SD_HIP(h, launch_linear(dt, B.xn, l.w_fc, nullptr, B.mlp, rows, 2 * c.d_ff, d, 2 * c.d_ff, EPI_STORE, h->st));
-            SD_HIP(h, launch_swiglu(dt, B.mlp, B.act, rows, c.d_ff, h->st));
-            SD_HIP(h, launch_linear(dt, B.act, l.w_proj, nullptr, B.h, rows, d, c.d_ff, d, EPI_RESID, h->st));
+            if ((rc = run_linear(h, dt, B.xn, l.w_fc, nullptr, B.mlp, rows, 2 * c.d_ff, d, 2 * c.d_ff, EPI_STORE))) return rc;
+            SD_LAUNCH(h, "k_swiglu", 3.0 * rows * c.d_ff * ew, 0, launch_swiglu(dt, B.mlp, B.act, rows, c.d_ff, h->st));
+            if ((rc = run_linear(h, dt, B.act, l.w_proj, nullptr, B.h, rows, d, c.d_ff, d, EPI_RESID))) return rc;
         }
     }
     return SD_OK;
@@ -403,9 +496,8 @@ int run_layers(sd_handle* h, const Model& m, const RowMaps& rm, const float* tem
 int run_head(sd_handle* h, const Model& m, const int32_t* idx, int n_rows, float* logits) {
     Buffers& B = h->buf;
     const sd_model_config& c = m.c;
-    SD_HIP(h, launch_norm(c.dtype, B.h, idx, m.lnf_g, m.lnf_b, B.xf, n_rows, c.d_model, c.norm_eps, h->st));
-    SD_HIP(h, launch_linear(c.dtype, B.xf, m.w_head, nullptr, logits, n_rows, c.vocab, c.d_model, m.ld, EPI_F32, h->st));
-    return SD_OK;
+    SD_LAUNCH(h, "k_norm", (double)n_rows * c.d_model * (4 + m.ew), 0, launch_norm(c.dtype, B.h, idx, m.lnf_g, m.lnf_b, B.xf, n_rows, c.d_model, c.norm_eps, h->st));
+    return run_linear(h, c.dtype, B.xf, m.w_head, nullptr, logits, n_rows, c.vocab, c.d_model, m.ld, EPI_F32);
 }
 
 int check_round_shapes(sd_handle* h, int batch, const int32_t* len, int gamma) {
@@ -452,14 +544,16 @@ int enqueue_draft(sd_handle* h, int batch, const int32_t* prefix, const int32_t*
     // z <- [MASK]^gamma  (fill through the staging buffer: vocab is not a byte pattern)
     for (int i = 0; i < batch * gamma; ++i) h->stage_z[i] = m.c.vocab;
     SD_HIP(h, hipMemcpyAsync(B.z, h->stage_z, (int64_t)batch * gamma * 4, hipMemcpyHostToDevice, h->st));
-    SD_HIP(h, launch_timestep_embed(m.c.dtype, m.t_w1, m.t_b1, m.t_w2, m.t_b2, nullptr, B.temb, T, m.c.d_model, h->st));
+    SD_LAUNCH(h, "k_timestep_embed", 2.0 * m.c.d_model * m.c.d_model * m.ew, 4.0 * T * m.c.d_model * m.c.d_model,
+              launch_timestep_embed(m.c.dtype, m.t_w1, m.t_b1, m.t_w2, m.t_b2, nullptr, B.temb, T, m.c.d_model, h->st));
     const SampleScratch ss = sampling_scratch(B.sample_scratch, (int)h->lim.rows_head, m.c.vocab);
     for (int j = T; j >= 1; --j) {
         rc = run_layers(h, m, rm, B.temb + (int64_t)(j - 1) * m.c.d_model);
         if (rc) return rc;
         rc = run_head(h, m, B.blk_idx, batch * gamma, B.logits_d);
         if (rc) return rc;
-        SD_HIP(h, launch_unmask_sample(B.logits_d, batch, gamma, m.c.vocab, j, seed, B.z, B.q, B.qtok, ss, h->st));
+        SD_LAUNCH(h, "unmask_sample(k_row_stats+k_unmask_sample)", 3.0 * batch * gamma / T * m.ld * 4, 0,
+                  launch_unmask_sample(B.logits_d, batch, gamma, m.c.vocab, j, seed, B.z, B.q, B.qtok, ss, h->st));
     }
     h->have_q = true;
     h->q_batch = batch;
@@ -483,7 +577,7 @@ int enqueue_target(sd_handle* h, int batch, const int32_t* prefix, const int32_t
 
 int read_back(sd_handle* h, int32_t* dst, const int32_t* dev, int64_t n) {
     SD_HIP(h, hipMemcpyAsync(h->stage_out, dev, n * 4, hipMemcpyDeviceToHost, h->st));
-    SD_HIP(h, hipStreamSynchronize(h->st));
+    { const int rc_ = sync_stream(h); if (rc_) return rc_; }
     memcpy(dst, h->stage_out, n * 4);
     return SD_OK;
 }
@@ -493,6 +587,8 @@ int read_back(sd_handle* h, int32_t* dst, const int32_t* dev, int64_t n) {
 // ------------------------------------------------------------------------------------------
 // exported functions
 // ------------------------------------------------------------------------------------------
+static std::string g_create_error = "null handle";   // reported by sd_last_error(NULL)
+
 extern "C" {
 
 int32_t sd_vocab_pad(int32_t vocab) { return vocab_pad(vocab); }
@@ -565,13 +661,19 @@ int32_t sd_create(const sd_model_config* target, const sd_model_config* drafter,
     h->cached_hash.assign(max_batch, 0);
     const int64_t n_i = h->lim.prefix_cap + 4 * h->lim.max_rows + (int64_t)max_batch * gamma_max;
     const int64_t n_out = (int64_t)max_batch * (gamma_max + 2) + 16;
-    if (hipHostMalloc(reinterpret_cast<void**>(&h->stage_i), 3 * n_i * 4, hipHostMallocDefault) != hipSuccess ||
-        hipHostMalloc(reinterpret_cast<void**>(&h->stage_l), 3 * h->lim.max_rows * 8, hipHostMallocDefault) != hipSuccess ||
-        hipHostMalloc(reinterpret_cast<void**>(&h->stage_z), n_out * 4, hipHostMallocDefault) != hipSuccess ||
-        hipHostMalloc(reinterpret_cast<void**>(&h->stage_out), n_out * 4, hipHostMallocDefault) != hipSuccess ||
-        hipHostMalloc(reinterpret_cast<void**>(&h->stage_f), n_out * 4, hipHostMallocDefault) != hipSuccess) {
-        sd_destroy(h);
-        return SD_ERR_HIP;
+    struct { void** p; int64_t bytes; } pinned[] = {
+        {reinterpret_cast<void**>(&h->stage_i), 3 * n_i * 4},
+        {reinterpret_cast<void**>(&h->stage_l), 3 * h->lim.max_rows * 8},
+        {reinterpret_cast<void**>(&h->stage_z), n_out * 4},
+        {reinterpret_cast<void**>(&h->stage_out), n_out * 4},
+        {reinterpret_cast<void**>(&h->stage_f), n_out * 4}};
+    for (auto& a : pinned) {
+        const hipError_t e = hipHostMalloc(a.p, a.bytes, hipHostMallocDefault);
+        if (e != hipSuccess) {
+            g_create_error = std::string("hipHostMalloc(") + std::to_string(a.bytes) + "): " + hipGetErrorString(e);
+            sd_destroy(h);
+            return SD_ERR_HIP;
+        }
     }
     *out = h;
     return SD_OK;
@@ -579,6 +681,7 @@ int32_t sd_create(const sd_model_config* target, const sd_model_config* drafter,
 
 void sd_destroy(sd_handle* h) {
     if (!h) return;
+    for (hipEvent_t e : h->prof.events) (void)hipEventDestroy(e);
     if (h->stage_i) (void)hipHostFree(h->stage_i);
     if (h->stage_l) (void)hipHostFree(h->stage_l);
     if (h->stage_z) (void)hipHostFree(h->stage_z);
@@ -587,7 +690,7 @@ void sd_destroy(sd_handle* h) {
     delete h;
 }
 
-const char* sd_last_error(const sd_handle* h) { return h ? h->err.c_str() : "null handle"; }
+const char* sd_last_error(const sd_handle* h) { return h ? h->err.c_str() : g_create_error.c_str(); }
 
 int32_t sd_prefill(sd_handle* h, int32_t batch, const int32_t* prefix, const int32_t* prefix_len) {
     int64_t n;
@@ -597,7 +700,7 @@ int32_t sd_prefill(sd_handle* h, int32_t batch, const int32_t* prefix, const int
         if (prefix_len[b] > h->target.c.n_ctx) return fail(h, SD_ERR_SHAPE, "prefix exceeds the target context");
     rc = do_prefill(h, batch, prefix, prefix_len, n);
     if (rc) return rc;
-    SD_HIP(h, hipStreamSynchronize(h->st));
+    { const int rc_ = sync_stream(h); if (rc_) return rc_; }
     return SD_OK;
 }
 
@@ -615,7 +718,7 @@ int32_t sd_draft(sd_handle* h, int32_t batch, const int32_t* prefix, const int32
     const int64_t cnt = (int64_t)batch * gamma;
     SD_HIP(h, hipMemcpyAsync(h->stage_out, h->buf.z, cnt * 4, hipMemcpyDeviceToHost, h->st));
     SD_HIP(h, hipMemcpyAsync(h->stage_f, h->buf.qtok, cnt * 4, hipMemcpyDeviceToHost, h->st));
-    SD_HIP(h, hipStreamSynchronize(h->st));
+    { const int rc_ = sync_stream(h); if (rc_) return rc_; }
     memcpy(draft_out, h->stage_out, cnt * 4);
     if (qtok_out) memcpy(qtok_out, h->stage_f, cnt * 4);
     if (q_dev_out) *q_dev_out = h->buf.q;
@@ -639,7 +742,9 @@ int32_t sd_verify(sd_handle* h, int32_t batch, const int32_t* prefix, const int3
     rc = enqueue_target(h, batch, prefix, prefix_len, n, gamma);
     if (rc) return rc;
     const SampleScratch ss = sampling_scratch(h->buf.sample_scratch, (int)h->lim.rows_head, h->target.c.vocab);
-    SD_HIP(h, launch_accept_resample(h->buf.logits_t, q_dev, h->buf.z, batch, gamma, h->target.c.vocab, seed,
+    SD_LAUNCH(h, "accept_resample(k_row_stats+k_accept+k_final_partial+k_final_sample)",
+              ((double)batch * (gamma + 1) + 4.0 * batch) * h->target.ld * 4, 0,
+              launch_accept_resample(h->buf.logits_t, q_dev, h->buf.z, batch, gamma, h->target.c.vocab, seed,
                                      h->buf.n_acc, h->buf.tok, ss, h->st));
     rc = read_back(h, n_accepted_out, h->buf.n_acc, batch);
     if (rc) return rc;
@@ -660,14 +765,16 @@ int32_t sd_round(sd_handle* h, int32_t batch, const int32_t* prefix, const int32
     rc = enqueue_target(h, batch, prefix, prefix_len, n, gamma);
     if (rc) return rc;
     const SampleScratch ss = sampling_scratch(h->buf.sample_scratch, (int)h->lim.rows_head, h->target.c.vocab);
-    SD_HIP(h, launch_accept_resample(h->buf.logits_t, h->buf.q, h->buf.z, batch, gamma, h->target.c.vocab, seed,
+    SD_LAUNCH(h, "accept_resample(k_row_stats+k_accept+k_final_partial+k_final_sample)",
+              ((double)batch * (gamma + 1) + 4.0 * batch) * h->target.ld * 4, 0,
+              launch_accept_resample(h->buf.logits_t, h->buf.q, h->buf.z, batch, gamma, h->target.c.vocab, seed,
                                      h->buf.n_acc, h->buf.tok, ss, h->st));
     const int64_t cnt = (int64_t)batch * gamma;
     int32_t* so = h->stage_out;
     SD_HIP(h, hipMemcpyAsync(so, h->buf.z, cnt * 4, hipMemcpyDeviceToHost, h->st));
     SD_HIP(h, hipMemcpyAsync(so + cnt, h->buf.n_acc, batch * 4, hipMemcpyDeviceToHost, h->st));
     SD_HIP(h, hipMemcpyAsync(so + cnt + batch, h->buf.tok, batch * 4, hipMemcpyDeviceToHost, h->st));
-    SD_HIP(h, hipStreamSynchronize(h->st));
+    { const int rc_ = sync_stream(h); if (rc_) return rc_; }
     memcpy(draft_out, so, cnt * 4);
     memcpy(n_accepted_out, so + cnt, batch * 4);
     memcpy(token_out, so + cnt + batch, batch * 4);
@@ -708,7 +815,7 @@ int32_t sd_drafter_logits(sd_handle* h, int32_t batch, const int32_t* tokens, co
     if (rc) return rc;
     rc = run_head(h, m, h->buf.blk_idx, batch * gamma, h->buf.logits_d);
     if (rc) return rc;
-    SD_HIP(h, hipStreamSynchronize(h->st));
+    { const int rc_ = sync_stream(h); if (rc_) return rc_; }
     *logits_dev_out = h->buf.logits_d;
     return SD_OK;
 }
@@ -728,8 +835,37 @@ int32_t sd_target_logits(sd_handle* h, int32_t batch, const int32_t* prefix, con
     SD_HIP(h, hipMemcpyAsync(h->buf.z, h->stage_z, cnt * 4, hipMemcpyHostToDevice, h->st));
     rc = enqueue_target(h, batch, prefix, prefix_len, n, gamma);
     if (rc) return rc;
-    SD_HIP(h, hipStreamSynchronize(h->st));
+    { const int rc_ = sync_stream(h); if (rc_) return rc_; }
     *logits_dev_out = h->buf.logits_t;
+    return SD_OK;
+}
+
+int32_t sd_profile_begin(sd_handle* h) {
+    if (!h) return SD_ERR_ARG;
+    { const int rc_ = sync_stream(h); if (rc_) return rc_; }
+    h->prof.entries.clear();
+    h->prof.on = true;
+    return SD_OK;
+}
+
+int32_t sd_profile_end(sd_handle* h) {
+    if (!h) return SD_ERR_ARG;
+    { const int rc_ = sync_stream(h); if (rc_) return rc_; }
+    h->prof.on = false;
+    return (int32_t)SD_OK;
+}
+
+int32_t sd_profile_count(const sd_handle* h) { return h ? (int32_t)h->prof.entries.size() : 0; }
+
+int32_t sd_profile_entry(const sd_handle* h, int32_t index, char* name, int32_t name_cap, int64_t* launches,
+                         double* total_ms, double* bytes, double* flops) {
+    if (!h || !name || name_cap <= 0 || !launches || !total_ms || !bytes || !flops) return SD_ERR_ARG;
+    if (index < 0 || index >= (int32_t)h->prof.entries.size()) return SD_ERR_ARG;
+    const ProfEntry& e = h->prof.entries[index];
+    const size_t n = e.name.size() < (size_t)name_cap - 1 ? e.name.size() : (size_t)name_cap - 1;
+    memcpy(name, e.name.c_str(), n);
+    name[n] = 0;
+    *launches = e.launches; *total_ms = e.ms; *bytes = e.bytes; *flops = e.flops;
     return SD_OK;
 }
 
@@ -762,7 +898,7 @@ int32_t sd_linear(int32_t dtype, const void* x, const void* w, const float* bias
     if (!x || !w || !y) return SD_ERR_ARG;
     if (dtype != SD_DTYPE_F32 && dtype != SD_DTYPE_BF16) return SD_ERR_ARG;
     if (m <= 0 || n <= 0 || k <= 0 || ldy < n || epilogue < 0 || epilogue > 3 || k % 8) return SD_ERR_SHAPE;
-    return launch_linear(dtype, x, w, bias, y, m, n, k, ldy, epilogue, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? SD_OK : SD_ERR_HIP;
+    return launch_linear(dtype, x, w, bias, y, m, n, k, ldy, epilogue, static_cast<hipStream_t>(hip_stream), nullptr) == hipSuccess ? SD_OK : SD_ERR_HIP;
 }
 
 }  // extern "C"

@@ -25,8 +25,9 @@ enum Epilogue { EPI_STORE = 0, EPI_GELU = 1, EPI_RESID = 2, EPI_F32 = 3 };
 // ---- launchers (all asynchronous on `st`; return hipGetLastError()) ------------------------
 
 // y = epilogue(x W^T + bias); see sd_linear in specdiff.h.
+// *kernel_name (optional) receives the name of the kernel variant that was launched.
 hipError_t launch_linear(int dtype, const void* x, const void* w, const float* bias, void* y, int m, int n,
-                         int k, int ldy, int epilogue, hipStream_t st);
+                         int k, int ldy, int epilogue, hipStream_t st, const char** kernel_name);
 
 // h[r, :] = wte[token(r)] + wpe[pos[r]] + temb, fp32 residual stream.  token(r) = src[r] >= 0 ?
 // prefix[src[r]] : block[-src[r] - 1].  wpe, temb may be NULL.
@@ -61,7 +62,7 @@ struct AttnArgs {
     int rows, n_head, n_kv_head, d_head;
     int max_kv;                              // upper bound of kv_len over the rows
 };
-hipError_t launch_attention(int dtype, const AttnArgs& a, hipStream_t st);
+hipError_t launch_attention(int dtype, const AttnArgs& a, hipStream_t st, const char** kernel_name);
 hipError_t launch_attention_generic(int dtype, const AttnArgs& a, int max_kv, hipStream_t st);
 hipError_t launch_linear_generic(int dtype, const void* x, const void* w, const float* bias, void* y, int m, int n,
                                  int k, int ldy, int epilogue, hipStream_t st);

@@ -4,11 +4,13 @@
 namespace sd {
 
 hipError_t launch_linear(int dtype, const void* x, const void* w, const float* bias, void* y, int m, int n, int k,
-                         int ldy, int epilogue, hipStream_t st) {
+                         int ldy, int epilogue, hipStream_t st, const char** kernel_name) {
+    if (kernel_name) *kernel_name = "k_linear_generic";
     return launch_linear_generic(dtype, x, w, bias, y, m, n, k, ldy, epilogue, st);
 }
 
-hipError_t launch_attention(int dtype, const AttnArgs& a, hipStream_t st) {
+hipError_t launch_attention(int dtype, const AttnArgs& a, hipStream_t st, const char** kernel_name) {
+    if (kernel_name) *kernel_name = "k_attention_generic";
     return launch_attention_generic(dtype, a, a.max_kv, st);
 }
 
