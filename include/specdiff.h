@@ -162,6 +162,17 @@ int32_t sd_accept_resample(const float *p_logits, const float *q, const int32_t 
 int32_t sd_linear(int32_t dtype, const void *x, const void *w, const float *bias, void *y,
                   int32_t m, int32_t n, int32_t k, int32_t ldy, int32_t epilogue, void *hip_stream);
 
+/* Tuning hook for sd_linear and every contraction inside the forwards: force tile variant
+ * `variant` of the matrix-core kernel (0..5, see the kernel source), -1 = choose by shape (default).
+ * Process-wide; results do not depend on the variant beyond fp32 summation order. */
+int32_t sd_set_linear_variant(int32_t variant);
+
+/* The launch sequences of sd_draft / sd_verify / sd_round are captured into HIP graphs on first
+ * use (one per combination of batch, gamma, T and sequence lengths) and replayed afterwards; the
+ * results are identical to eager launches.  enable = 0 turns replay off (it is also off while
+ * profiling and when the handle runs on the NULL stream). */
+int32_t sd_set_graph_replay(sd_handle *h, int32_t enable);
+
 /* ---- per-kernel timing ----------------------------------------------------------------------
  * Between sd_profile_begin and sd_profile_end every kernel launch of the handle is bracketed by
  * HIP events on its stream; entries accumulate, per kernel name, the launch count, the summed

@@ -49,6 +49,12 @@ def softmax_rows(x):
     return e / e.sum(axis=-1, keepdims=True)
 
 
+def linear(x, W, bias=None):
+    """y = x W^T + bias with W stored [out_features, in_features]."""
+    y = f64(x) @ f64(W).T
+    return y if bias is None else y + f64(bias)
+
+
 def rope(x, positions, theta):
     """x: [S, n_head, d_head]; rotates the pair (i, i + d_head/2) by positions * theta^(-2i/d_head)."""
     half = x.shape[-1] // 2

@@ -23,7 +23,7 @@ STATUS_NAMES = {0: "SD_OK", 1: "SD_ERR_ARG", 2: "SD_ERR_SHAPE", 3: "SD_ERR_TOKEN
 EXPORTS = ["sd_vocab_pad", "sd_weight_count", "sd_weight_desc", "sd_weight_bytes", "sd_workspace_bytes", "sd_create",
            "sd_destroy", "sd_last_error", "sd_prefill", "sd_draft", "sd_verify", "sd_round", "sd_drafter_logits",
            "sd_target_logits", "sd_sampling_scratch_bytes", "sd_unmask_sample", "sd_accept_resample", "sd_linear",
-           "sd_profile_begin", "sd_profile_end", "sd_profile_count", "sd_profile_entry"]
+           "sd_profile_begin", "sd_profile_end", "sd_profile_count", "sd_profile_entry", "sd_set_graph_replay", "sd_set_linear_variant"]
 
 
 class SdModelConfig(C.Structure):
@@ -76,6 +76,8 @@ def lib() -> C.CDLL:
         L.sd_accept_resample.argtypes = [vp, vp, vp, i32, i32, i32, u64, vp, vp, vp, i64, vp]
         L.sd_linear.restype = i32
         L.sd_linear.argtypes = [i32, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp]
+        L.sd_set_graph_replay.restype = i32; L.sd_set_graph_replay.argtypes = [vp, i32]
+        L.sd_set_linear_variant.restype = i32; L.sd_set_linear_variant.argtypes = [i32]
         L.sd_profile_begin.restype = i32; L.sd_profile_begin.argtypes = [vp]
         L.sd_profile_end.restype = i32; L.sd_profile_end.argtypes = [vp]
         L.sd_profile_count.restype = i32; L.sd_profile_count.argtypes = [vp]
@@ -162,7 +164,10 @@ class SpecDiff:
         if nbytes <= 0:
             raise SdError(1, "sd_workspace_bytes", "configuration rejected")
         self.workspace = torch.zeros(nbytes, dtype=torch.uint8, device=self.device)
-        self.stream = torch.cuda.current_stream(self.device)
+        # A stream of its own (default priority): launch sequences are captured into HIP graphs,
+        # which the legacy default stream does not allow.
+        self.stream = torch.cuda.Stream(self.device)
+        torch.cuda.synchronize(self.device)       # weights and workspace are in place before the first call
         self._ct, self._cd = c_config(target), c_config(drafter)
         h = C.c_void_p()
         rc = lib().sd_create(C.byref(self._ct), C.byref(self._cd), self.tw.data_ptr(), self.dw.data_ptr(), max_batch,
@@ -188,6 +193,9 @@ class SpecDiff:
         off = ptr - self.workspace.data_ptr()
         assert 0 <= off and off + rows * self.ld * 4 <= self.workspace.numel()
         return self.workspace[off:off + rows * self.ld * 4].view(self.torch.float32).view(rows, self.ld)
+
+    def sd_set_graph_replay(self, enable: bool):
+        self._check(lib().sd_set_graph_replay(self.h, int(enable)), "sd_set_graph_replay")
 
     def sd_profile_begin(self):
         self._check(lib().sd_profile_begin(self.h), "sd_profile_begin")

@@ -4,6 +4,7 @@
 #include <string.h>
 
 #include <string>
+#include <unordered_map>
 #include <vector>
 
 #include "common.h"
@@ -161,14 +162,15 @@ struct Arena {
 
 struct Buffers {
     float* h; void* xn; void* qkv; void* att; void* mlp; void* act; void* xf;
-    float *logits_d, *logits_t, *q, *qtok, *temb;
-    int32_t *z, *n_acc, *tok, *prefix, *row_src, *row_pos, *row_seq, *kv_len, *blk_idx;
-    int64_t* kv_off;
+    float *logits_d, *logits_t, *q, *qtok, *temb, *temb_hidden;
+    int32_t *z, *n_acc, *tok;
+    char* maps[3];           // packed row maps: 0 drafter, 1 target query rows, 2 target prefill
+    uint64_t* seed;          // Philox key of the current call
     void* sample_scratch;
     void *kcache, *vcache;
 };
 
-struct Limits { int64_t max_rows, rows_head, dmax, qkvmax, ffmax, ew; int64_t prefix_cap; };
+struct Limits { int64_t max_rows, rows_head, dmax, qkvmax, ffmax, ew; int64_t prefix_cap; int64_t map_bytes; };
 
 Limits limits_of(const sd_model_config& t, const sd_model_config& d, int max_batch, int gamma_max) {
     Limits l;
@@ -181,6 +183,7 @@ Limits limits_of(const sd_model_config& t, const sd_model_config& d, int max_bat
     l.ffmax = ffw(t) > ffw(d) ? ffw(t) : ffw(d);
     l.ew = (t.dtype == SD_DTYPE_F32 || d.dtype == SD_DTYPE_F32) ? 4 : 2;
     l.prefix_cap = l.max_rows;
+    l.map_bytes = align_up((l.prefix_cap + 6 * l.max_rows + (int64_t)max_batch * gamma_max) * 4 + 8 + l.max_rows * 8, 256);
     return l;
 }
 
@@ -199,16 +202,12 @@ int64_t carve(Arena& a, Buffers& b, const sd_model_config& t, const sd_model_con
     b.q = a.take<float>((int64_t)max_batch * gamma_max * ld);
     b.qtok = a.take<float>((int64_t)max_batch * gamma_max);
     b.temb = a.take<float>((int64_t)kMaxSteps * d.d_model);
+    b.temb_hidden = a.take<float>((int64_t)kMaxSteps * d.d_model);
     b.z = a.take<int32_t>((int64_t)max_batch * gamma_max);
     b.n_acc = a.take<int32_t>(max_batch);
     b.tok = a.take<int32_t>(max_batch);
-    b.prefix = a.take<int32_t>(l.prefix_cap);
-    b.row_src = a.take<int32_t>(l.max_rows);
-    b.row_pos = a.take<int32_t>(l.max_rows);
-    b.row_seq = a.take<int32_t>(l.max_rows);
-    b.kv_len = a.take<int32_t>(l.max_rows);
-    b.blk_idx = a.take<int32_t>((int64_t)max_batch * gamma_max);
-    b.kv_off = a.take<int64_t>(l.max_rows);
+    for (int i = 0; i < 3; ++i) b.maps[i] = a.take<char>(l.map_bytes);
+    b.seed = a.take<uint64_t>(32);
     b.sample_scratch = a.take<char>(sampling_scratch_bytes((int)l.rows_head, t.vocab));
     const int64_t cache = (int64_t)t.n_layer * max_batch * t.n_ctx * t.n_kv_head * (t.d_model / t.n_head);
     b.kcache = a.take<char>(cache, t.dtype == SD_DTYPE_BF16 ? 2 : 4);
@@ -217,6 +216,18 @@ int64_t carve(Arena& a, Buffers& b, const sd_model_config& t, const sd_model_con
 }
 
 }  // namespace
+
+// Row maps of one forward pass, packed into one device buffer (one upload per call):
+// prefix tokens, per row: token source, position, sequence, visible key count, key offset;
+// per query tile: first row, row count; per block slot: its row.
+struct MapSet {
+    int32_t *tokens = nullptr, *src = nullptr, *pos = nullptr, *seq = nullptr, *kvl = nullptr, *t0 = nullptr,
+            *tn = nullptr, *blk = nullptr;
+    int64_t* kv_off = nullptr;
+    int rows = 0, n_tiles = 0, max_kv = 0;
+    double kv_sum = 0, kv_rows = 0;     // sum of kv_len over rows; distinct key rows
+    int64_t bytes = -1;
+};
 
 // ------------------------------------------------------------------------------------------
 // per-kernel timing with HIP events on the handle's stream (off unless sd_profile_begin was called)
@@ -245,17 +256,19 @@ struct sd_handle {
     int max_batch, gamma_max;
     hipStream_t st;
     // pinned host staging
-    int32_t* stage_i = nullptr;   // row maps and token uploads
-    int64_t* stage_l = nullptr;
+    char* stage_maps[3] = {nullptr, nullptr, nullptr};   // host images of the packed row maps
+    uint64_t* stage_seed = nullptr;
     int32_t* stage_z = nullptr;   // block / draft tokens going to the device
     int32_t* stage_out = nullptr; // results read back
     float* stage_f = nullptr;
-    int64_t stage_cap = 0;
+    MapSet maps[3];               // what each device map buffer currently holds
+    std::vector<char> map_shadow[3];
+    // captured launch sequences, keyed by everything that shapes them
+    std::unordered_map<uint64_t, hipGraphExec_t> graphs;
+    bool use_graphs = true;
     // KV-cache state per sequence: number of cached positions and a hash of their tokens
     std::vector<int32_t> cached_len;
     std::vector<uint64_t> cached_hash;
-    bool have_q = false;
-    int q_batch = 0, q_gamma = 0;
     std::string err;
 };
 
@@ -355,40 +368,55 @@ int check_batch(sd_handle* h, int batch, const int32_t* tokens, const int32_t* l
     return SD_OK;
 }
 
-struct RowMaps { int rows = 0; int max_kv = 0; double kv_sum = 0; double kv_rows = 0; };   // kv_sum: sum of kv_len; kv_rows: distinct key rows
-
-// Upload prefix tokens and per-row maps.  mode 0: drafter over prefix o block; 1: target query rows
-// (last prefix token + gamma draft tokens); 2: target prefill rows [0, L-1).
+// Build and upload the packed row maps of one forward.  mode 0: drafter over prefix o block;
+// 1: target query rows (last prefix token + gamma draft tokens); 2: target prefill rows [0, L-1).
+// The upload is skipped when the device buffer already holds exactly these maps (same prefix,
+// same shapes as the previous call of this mode).
 int upload_rows(sd_handle* h, int mode, int batch, const int32_t* tokens, const int32_t* len, int64_t n_tokens,
-                int gamma, RowMaps* out) {
+                int gamma) {
     const Model& m = mode == 0 ? h->drafter : h->target;
-    // One staging region per mode: a region is rewritten only by a later call of the same mode,
-    // and every exported call ends with a stream synchronisation, so no copy is still reading it.
-    const int64_t region = h->lim.prefix_cap + 4 * h->lim.max_rows + (int64_t)h->max_batch * h->gamma_max;
-    int32_t* s_tok = h->stage_i + mode * region;
-    int32_t* s_src = s_tok + h->lim.prefix_cap;
-    int32_t* s_pos = s_src + h->lim.max_rows;
-    int32_t* s_seq = s_pos + h->lim.max_rows;
-    int32_t* s_kvl = s_seq + h->lim.max_rows;
-    int32_t* s_blk = s_kvl + h->lim.max_rows;
-    int64_t* s_off = h->stage_l + mode * h->lim.max_rows;
+    int64_t rows = 0, n_tiles = 0;
+    for (int b = 0; b < batch; ++b) {
+        const int64_t rb = mode == 0 ? len[b] + gamma : (mode == 1 ? gamma + 1 : len[b] - 1);
+        rows += rb;
+        n_tiles += (rb + 31) / 32;
+    }
+    if (rows > h->lim.max_rows) return fail(h, SD_ERR_SHAPE, "more rows than the workspace holds");
+    const int64_t n_blk = mode == 0 ? (int64_t)batch * gamma : 0;
+    // packed layout
+    int64_t o = 0;
+    auto take = [&](int64_t n) { const int64_t at = o; o += n * 4; return at; };
+    const int64_t o_tok = take(n_tokens), o_src = take(rows), o_pos = take(rows), o_seq = take(rows), o_kvl = take(rows),
+                  o_t0 = take(n_tiles), o_tn = take(n_tiles), o_blk = take(n_blk);
+    o = align_up(o, 8);
+    const int64_t o_off = o;
+    o += rows * 8;
+    const int64_t bytes = o;
+    char* hb = h->stage_maps[mode];
+    int32_t *s_tok = (int32_t*)(hb + o_tok), *s_src = (int32_t*)(hb + o_src), *s_pos = (int32_t*)(hb + o_pos),
+            *s_seq = (int32_t*)(hb + o_seq), *s_kvl = (int32_t*)(hb + o_kvl), *s_t0 = (int32_t*)(hb + o_t0),
+            *s_tn = (int32_t*)(hb + o_tn), *s_blk = (int32_t*)(hb + o_blk);
+    int64_t* s_off = (int64_t*)(hb + o_off);
     memcpy(s_tok, tokens, n_tokens * sizeof(int32_t));
-    int64_t r = 0, tok_off = 0;
+    int64_t r = 0, tok_off = 0, nt = 0;
     int max_kv = 0;
+    double kv_sum = 0, kv_rows = 0;
     for (int b = 0; b < batch; ++b) {
         const int L = len[b];
+        const int64_t seq_row0 = r;
         if (mode == 0) {
             const int S = L + gamma;
-            const int64_t row0 = r;
             for (int p = 0; p < S; ++p, ++r) {
                 s_src[r] = p < L ? (int32_t)(tok_off + p) : -(b * gamma + (p - L)) - 1;
                 s_pos[r] = p;
                 s_seq[r] = b;
                 s_kvl[r] = S;
-                s_off[r] = row0 * (int64_t)(m.dq + 2 * m.dkv);
+                s_off[r] = seq_row0 * (int64_t)(m.dq + 2 * m.dkv);
                 if (p >= L) s_blk[b * gamma + (p - L)] = (int32_t)r;
             }
             if (S > max_kv) max_kv = S;
+            kv_sum += (double)S * S;
+            kv_rows += S;
         } else if (mode == 1) {
             for (int k = 0; k <= gamma; ++k, ++r) {
                 s_src[r] = k == 0 ? (int32_t)(tok_off + L - 1) : -(b * gamma + k - 1) - 1;
@@ -396,8 +424,10 @@ int upload_rows(sd_handle* h, int mode, int batch, const int32_t* tokens, const 
                 s_seq[r] = b;
                 s_kvl[r] = L + k;
                 s_off[r] = (int64_t)b * m.c.n_ctx * m.dkv;
+                kv_sum += L + k;
             }
             if (L + gamma > max_kv) max_kv = L + gamma;
+            kv_rows += L + gamma;
         } else {
             for (int p = 0; p < L - 1; ++p, ++r) {
                 s_src[r] = (int32_t)(tok_off + p);
@@ -405,30 +435,81 @@ int upload_rows(sd_handle* h, int mode, int batch, const int32_t* tokens, const 
                 s_seq[r] = b;
                 s_kvl[r] = p + 1;
                 s_off[r] = (int64_t)b * m.c.n_ctx * m.dkv;
+                kv_sum += p + 1;
             }
             if (L - 1 > max_kv) max_kv = L - 1;
+            kv_rows += L - 1;
+        }
+        for (int64_t t0 = seq_row0; t0 < r; t0 += 32) {      // query tiles never span two sequences
+            s_t0[nt] = (int32_t)t0;
+            s_tn[nt] = (int32_t)(r - t0 < 32 ? r - t0 : 32);
+            ++nt;
         }
         tok_off += L;
     }
-    if (r > h->lim.max_rows) return fail(h, SD_ERR_SHAPE, "more rows than the workspace holds");
-    Buffers& B = h->buf;
-    SD_HIP(h, hipMemcpyAsync(B.prefix, s_tok, n_tokens * 4, hipMemcpyHostToDevice, h->st));
-    if (r > 0) {
-        SD_HIP(h, hipMemcpyAsync(B.row_src, s_src, r * 4, hipMemcpyHostToDevice, h->st));
-        SD_HIP(h, hipMemcpyAsync(B.row_pos, s_pos, r * 4, hipMemcpyHostToDevice, h->st));
-        SD_HIP(h, hipMemcpyAsync(B.row_seq, s_seq, r * 4, hipMemcpyHostToDevice, h->st));
-        SD_HIP(h, hipMemcpyAsync(B.kv_len, s_kvl, r * 4, hipMemcpyHostToDevice, h->st));
-        SD_HIP(h, hipMemcpyAsync(B.kv_off, s_off, r * 8, hipMemcpyHostToDevice, h->st));
+    MapSet& ms = h->maps[mode];
+    std::vector<char>& shadow = h->map_shadow[mode];
+    const bool same = ms.bytes == bytes && (int64_t)shadow.size() == bytes && memcmp(shadow.data(), hb, bytes) == 0;
+    if (!same) {
+        if (bytes > 0) SD_HIP(h, hipMemcpyAsync(h->buf.maps[mode], hb, bytes, hipMemcpyHostToDevice, h->st));
+        shadow.assign(hb, hb + bytes);
     }
-    if (mode == 0)
-        SD_HIP(h, hipMemcpyAsync(B.blk_idx, s_blk, (int64_t)batch * gamma * 4, hipMemcpyHostToDevice, h->st));
-    out->rows = (int)r;
-    out->max_kv = max_kv;
-    out->kv_sum = 0;
-    out->kv_rows = 0;
-    for (int64_t i = 0; i < r; ++i) out->kv_sum += s_kvl[i];
-    for (int b = 0; b < batch; ++b) out->kv_rows += mode == 0 ? len[b] + gamma : (mode == 1 ? len[b] + gamma : len[b] - 1);
+    char* db = h->buf.maps[mode];
+    ms.tokens = (int32_t*)(db + o_tok); ms.src = (int32_t*)(db + o_src); ms.pos = (int32_t*)(db + o_pos);
+    ms.seq = (int32_t*)(db + o_seq); ms.kvl = (int32_t*)(db + o_kvl); ms.t0 = (int32_t*)(db + o_t0);
+    ms.tn = (int32_t*)(db + o_tn); ms.blk = (int32_t*)(db + o_blk); ms.kv_off = (int64_t*)(db + o_off);
+    ms.rows = (int)rows; ms.n_tiles = (int)n_tiles; ms.max_kv = max_kv; ms.kv_sum = kv_sum; ms.kv_rows = kv_rows;
+    ms.bytes = bytes;
     return SD_OK;
+}
+
+// Replay a launch sequence through a captured graph (capturing it on first use).  `key` must
+// identify everything that shapes the sequence: the call, batch, gamma, T, every sequence length
+// and every pointer argument.  Falls back to eager launches when profiling is on, when the handle
+// runs on the legacy default stream, or when capture is not possible.
+template <typename F>
+int replay(sd_handle* h, uint64_t key, F&& enqueue) {
+    if (!h->use_graphs || h->prof.on || h->st == nullptr) return enqueue();
+    auto it = h->graphs.find(key);
+    if (it == h->graphs.end()) {
+        if (h->graphs.size() >= 256) {
+            for (auto& g : h->graphs) (void)hipGraphExecDestroy(g.second);
+            h->graphs.clear();
+        }
+        if (hipStreamBeginCapture(h->st, hipStreamCaptureModeThreadLocal) != hipSuccess) {
+            (void)hipGetLastError();
+            h->use_graphs = false;
+            return enqueue();
+        }
+        const int rc = enqueue();
+        hipGraph_t graph = nullptr;
+        const hipError_t e1 = hipStreamEndCapture(h->st, &graph);
+        if (rc != SD_OK || e1 != hipSuccess || graph == nullptr) {
+            if (graph) (void)hipGraphDestroy(graph);
+            (void)hipGetLastError();
+            h->use_graphs = false;
+            return rc != SD_OK ? rc : enqueue();
+        }
+        hipGraphExec_t exec = nullptr;
+        const hipError_t e2 = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+        (void)hipGraphDestroy(graph);
+        if (e2 != hipSuccess || exec == nullptr) {
+            (void)hipGetLastError();
+            h->use_graphs = false;
+            return enqueue();
+        }
+        it = h->graphs.emplace(key, exec).first;
+    }
+    SD_HIP(h, hipGraphLaunch(it->second, h->st));
+    return SD_OK;
+}
+
+uint64_t shape_key(int call, int batch, int gamma, int T, const int32_t* len, const void* ptr) {
+    uint64_t x = 1469598103934665603ull;
+    auto mix = [&](uint64_t v) { x ^= v; x *= 1099511628211ull; };
+    mix((uint64_t)call); mix((uint64_t)batch); mix((uint64_t)gamma); mix((uint64_t)T); mix((uint64_t)(uintptr_t)ptr);
+    for (int b = 0; b < batch; ++b) mix((uint64_t)(uint32_t)len[b]);
+    return x;
 }
 
 // Transformer layers over the rows described by the uploaded maps; residual stream in buf.h.
@@ -444,7 +525,7 @@ int run_linear(sd_handle* h, int dt, const void* x, const void* w, const float* 
     return SD_OK;
 }
 
-int run_layers(sd_handle* h, const Model& m, const RowMaps& rm, const float* temb) {
+int run_layers(sd_handle* h, const Model& m, const MapSet& rm, const float* temb) {
     Buffers& B = h->buf;
     const sd_model_config& c = m.c;
     const int rows = rm.rows, d = c.d_model, dt = c.dtype;
@@ -453,23 +534,24 @@ int run_layers(sd_handle* h, const Model& m, const RowMaps& rm, const float* tem
     const int qkv_w = m.dq + 2 * m.dkv;
     const double ew = m.ew, rd = (double)rows * d;
     int rc;
-    SD_LAUNCH(h, "k_embed", rd * (4 + ew), 0, launch_embed(dt, B.row_src, B.row_pos, B.prefix, B.z, m.wte, m.wpe, temb, B.h, rows, d, h->st));
+    SD_LAUNCH(h, "k_embed", rd * (4 + ew), 0, launch_embed(dt, rm.src, rm.pos, rm.tokens, B.z, m.wte, m.wpe, temb, B.h, rows, d, h->st));
     for (int i = 0; i < c.n_layer; ++i) {
         const Layer& l = m.L[i];
         SD_LAUNCH(h, "k_norm", rd * (4 + ew), 0, launch_norm(dt, B.h, nullptr, l.ln1_g, l.ln1_b, B.xn, rows, d, c.norm_eps, h->st));
         if ((rc = run_linear(h, dt, B.xn, l.w_qkv, l.b_qkv, B.qkv, rows, qkv_w, d, qkv_w, EPI_STORE))) return rc;
         if (c.arch == SD_ARCH_LLAMA)
-            SD_LAUNCH(h, "k_rope", 2.0 * rows * (m.dq + m.dkv) * ew, 0, launch_rope(dt, B.qkv, B.row_pos, rows, c.n_head, c.n_kv_head, m.dh, c.rope_theta, h->st));
+            SD_LAUNCH(h, "k_rope", 2.0 * rows * (m.dq + m.dkv) * ew, 0, launch_rope(dt, B.qkv, rm.pos, rows, c.n_head, c.n_kv_head, m.dh, c.rope_theta, h->st));
         AttnArgs a;
         a.q = B.qkv; a.q_ld = qkv_w;
-        a.kv_off = B.kv_off; a.kv_len = B.kv_len;
+        a.kv_off = rm.kv_off; a.kv_len = rm.kvl;
         a.out = B.att; a.out_ld = d;
         a.rows = rows; a.n_head = c.n_head; a.n_kv_head = c.n_kv_head; a.d_head = m.dh; a.max_kv = rm.max_kv;
+        a.tile_row0 = rm.t0; a.tile_rows = rm.tn; a.n_tiles = rm.n_tiles;
         if (cached) {
             const int64_t per_layer = (int64_t)h->max_batch * c.n_ctx * m.dkv * m.ew;
             char* kc = static_cast<char*>(B.kcache) + i * per_layer;
             char* vc = static_cast<char*>(B.vcache) + i * per_layer;
-            SD_LAUNCH(h, "k_kv_store", 4.0 * rows * m.dkv * ew, 0, launch_kv_store(dt, B.qkv, B.row_seq, B.row_pos, kc, vc, rows, c.n_head, c.n_kv_head, m.dh, c.n_ctx, h->st));
+            SD_LAUNCH(h, "k_kv_store", 4.0 * rows * m.dkv * ew, 0, launch_kv_store(dt, B.qkv, rm.seq, rm.pos, kc, vc, rows, c.n_head, c.n_kv_head, m.dh, c.n_ctx, h->st));
             a.k = kc; a.v = vc; a.kv_ld = m.dkv;
         } else {
             a.k = static_cast<char*>(B.qkv) + (int64_t)m.dq * m.ew;
@@ -510,10 +592,9 @@ int check_round_shapes(sd_handle* h, int batch, const int32_t* len, int gamma) {
 }
 
 int do_prefill(sd_handle* h, int batch, const int32_t* prefix, const int32_t* len, int64_t n_tokens) {
-    RowMaps rm;
-    int rc = upload_rows(h, 2, batch, prefix, len, n_tokens, 0, &rm);
+    int rc = upload_rows(h, 2, batch, prefix, len, n_tokens, 0);
     if (rc) return rc;
-    rc = run_layers(h, h->target, rm, nullptr);
+    rc = run_layers(h, h->target, h->maps[2], nullptr);
     if (rc) return rc;
     int64_t off = 0;
     for (int b = 0; b < batch; ++b) {
@@ -533,46 +614,61 @@ bool cache_matches(sd_handle* h, int batch, const int32_t* prefix, const int32_t
     return true;
 }
 
-// The T reverse-diffusion steps, device resident.  Leaves z (draft), q, qtok in the workspace.
-int enqueue_draft(sd_handle* h, int batch, const int32_t* prefix, const int32_t* len, int64_t n_tokens, int gamma,
-                  int T, uint64_t seed) {
+// Everything a draft needs on the device before its launches: row maps and the seed.
+int prepare_draft(sd_handle* h, int batch, const int32_t* prefix, const int32_t* len, int64_t n_tokens, int gamma,
+                  uint64_t seed) {
+    const int rc = upload_rows(h, 0, batch, prefix, len, n_tokens, gamma);
+    if (rc) return rc;
+    h->stage_seed[0] = seed;
+    SD_HIP(h, hipMemcpyAsync(h->buf.seed, h->stage_seed, 8, hipMemcpyHostToDevice, h->st));
+    return SD_OK;
+}
+
+// The T reverse-diffusion steps (launches only: capturable).  Leaves z (draft), q, qtok in the workspace.
+int enqueue_draft(sd_handle* h, int batch, int gamma, int T) {
     Buffers& B = h->buf;
     const Model& m = h->drafter;
-    RowMaps rm;
-    int rc = upload_rows(h, 0, batch, prefix, len, n_tokens, gamma, &rm);
-    if (rc) return rc;
-    // z <- [MASK]^gamma  (fill through the staging buffer: vocab is not a byte pattern)
-    for (int i = 0; i < batch * gamma; ++i) h->stage_z[i] = m.c.vocab;
-    SD_HIP(h, hipMemcpyAsync(B.z, h->stage_z, (int64_t)batch * gamma * 4, hipMemcpyHostToDevice, h->st));
-    SD_LAUNCH(h, "k_timestep_embed", 2.0 * m.c.d_model * m.c.d_model * m.ew, 4.0 * T * m.c.d_model * m.c.d_model,
-              launch_timestep_embed(m.c.dtype, m.t_w1, m.t_b1, m.t_w2, m.t_b2, nullptr, B.temb, T, m.c.d_model, h->st));
+    const MapSet& rm = h->maps[0];
+    int rc;
+    SD_LAUNCH(h, "k_fill_i32", 4.0 * batch * gamma, 0, launch_fill_i32(B.z, batch * gamma, m.c.vocab, h->st));   // z <- [MASK]^gamma
+    SD_LAUNCH(h, "k_timestep_matvec(x2)", 2.0 * m.c.d_model * m.c.d_model * m.ew, 4.0 * T * m.c.d_model * m.c.d_model,
+              launch_timestep_embed(m.c.dtype, m.t_w1, m.t_b1, m.t_w2, m.t_b2, B.temb_hidden, B.temb, T, m.c.d_model, h->st));
     const SampleScratch ss = sampling_scratch(B.sample_scratch, (int)h->lim.rows_head, m.c.vocab);
     for (int j = T; j >= 1; --j) {
         rc = run_layers(h, m, rm, B.temb + (int64_t)(j - 1) * m.c.d_model);
         if (rc) return rc;
-        rc = run_head(h, m, B.blk_idx, batch * gamma, B.logits_d);
+        rc = run_head(h, m, rm.blk, batch * gamma, B.logits_d);
         if (rc) return rc;
         SD_LAUNCH(h, "unmask_sample(k_row_stats+k_unmask_sample)", 3.0 * batch * gamma / T * m.ld * 4, 0,
-                  launch_unmask_sample(B.logits_d, batch, gamma, m.c.vocab, j, seed, B.z, B.q, B.qtok, ss, h->st));
+                  launch_unmask_sample(B.logits_d, batch, gamma, m.c.vocab, j, B.seed, B.z, B.q, B.qtok, ss, h->st));
     }
-    h->have_q = true;
-    h->q_batch = batch;
-    h->q_gamma = gamma;
     return SD_OK;
 }
 
-// Target forward over the gamma+1 query rows (draft tokens taken from buf.z) -> buf.logits_t.
-int enqueue_target(sd_handle* h, int batch, const int32_t* prefix, const int32_t* len, int64_t n_tokens, int gamma) {
+// Prefill on demand and upload the maps of the gamma+1 query rows.
+int prepare_target(sd_handle* h, int batch, const int32_t* prefix, const int32_t* len, int64_t n_tokens, int gamma) {
     if (!cache_matches(h, batch, prefix, len)) {
-        int rc = do_prefill(h, batch, prefix, len, n_tokens);
+        const int rc = do_prefill(h, batch, prefix, len, n_tokens);
         if (rc) return rc;
     }
-    RowMaps rm;
-    int rc = upload_rows(h, 1, batch, prefix, len, n_tokens, gamma, &rm);
-    if (rc) return rc;
-    rc = run_layers(h, h->target, rm, nullptr);
+    return upload_rows(h, 1, batch, prefix, len, n_tokens, gamma);
+}
+
+// Target forward over the gamma+1 query rows (draft tokens taken from buf.z) -> buf.logits_t (capturable).
+int enqueue_target(sd_handle* h) {
+    const MapSet& rm = h->maps[1];
+    const int rc = run_layers(h, h->target, rm, nullptr);
     if (rc) return rc;
     return run_head(h, h->target, nullptr, rm.rows, h->buf.logits_t);
+}
+
+int enqueue_accept(sd_handle* h, int batch, int gamma, const float* q_dev) {
+    const SampleScratch ss = sampling_scratch(h->buf.sample_scratch, (int)h->lim.rows_head, h->target.c.vocab);
+    SD_LAUNCH(h, "accept_resample(k_row_stats+k_accept+k_final_partial+k_final_sample)",
+              ((double)batch * (gamma + 1) + 4.0 * batch) * h->target.ld * 4, 0,
+              launch_accept_resample(h->buf.logits_t, q_dev, h->buf.z, batch, gamma, h->target.c.vocab, h->buf.seed,
+                                     h->buf.n_acc, h->buf.tok, ss, h->st));
+    return SD_OK;
 }
 
 int read_back(sd_handle* h, int32_t* dst, const int32_t* dev, int64_t n) {
@@ -659,11 +755,12 @@ int32_t sd_create(const sd_model_config* target, const sd_model_config* drafter,
     h->st = static_cast<hipStream_t>(hip_stream);
     h->cached_len.assign(max_batch, -1);
     h->cached_hash.assign(max_batch, 0);
-    const int64_t n_i = h->lim.prefix_cap + 4 * h->lim.max_rows + (int64_t)max_batch * gamma_max;
     const int64_t n_out = (int64_t)max_batch * (gamma_max + 2) + 16;
     struct { void** p; int64_t bytes; } pinned[] = {
-        {reinterpret_cast<void**>(&h->stage_i), 3 * n_i * 4},
-        {reinterpret_cast<void**>(&h->stage_l), 3 * h->lim.max_rows * 8},
+        {reinterpret_cast<void**>(&h->stage_maps[0]), h->lim.map_bytes},
+        {reinterpret_cast<void**>(&h->stage_maps[1]), h->lim.map_bytes},
+        {reinterpret_cast<void**>(&h->stage_maps[2]), h->lim.map_bytes},
+        {reinterpret_cast<void**>(&h->stage_seed), 64},
         {reinterpret_cast<void**>(&h->stage_z), n_out * 4},
         {reinterpret_cast<void**>(&h->stage_out), n_out * 4},
         {reinterpret_cast<void**>(&h->stage_f), n_out * 4}};
@@ -682,8 +779,10 @@ int32_t sd_create(const sd_model_config* target, const sd_model_config* drafter,
 void sd_destroy(sd_handle* h) {
     if (!h) return;
     for (hipEvent_t e : h->prof.events) (void)hipEventDestroy(e);
-    if (h->stage_i) (void)hipHostFree(h->stage_i);
-    if (h->stage_l) (void)hipHostFree(h->stage_l);
+    for (auto& g : h->graphs) (void)hipGraphExecDestroy(g.second);
+    for (int i = 0; i < 3; ++i)
+        if (h->stage_maps[i]) (void)hipHostFree(h->stage_maps[i]);
+    if (h->stage_seed) (void)hipHostFree(h->stage_seed);
     if (h->stage_z) (void)hipHostFree(h->stage_z);
     if (h->stage_out) (void)hipHostFree(h->stage_out);
     if (h->stage_f) (void)hipHostFree(h->stage_f);
@@ -713,7 +812,9 @@ int32_t sd_draft(sd_handle* h, int32_t batch, const int32_t* prefix, const int32
     if (T <= 0 || T > kMaxSteps) return fail(h, SD_ERR_SHAPE, "T outside [1, 256]");
     rc = check_round_shapes(h, batch, prefix_len, gamma);
     if (rc) return rc;
-    rc = enqueue_draft(h, batch, prefix, prefix_len, n, gamma, T, seed);
+    rc = prepare_draft(h, batch, prefix, prefix_len, n, gamma, seed);
+    if (rc) return rc;
+    rc = replay(h, shape_key(1, batch, gamma, T, prefix_len, nullptr), [&] { return enqueue_draft(h, batch, gamma, T); });
     if (rc) return rc;
     const int64_t cnt = (int64_t)batch * gamma;
     SD_HIP(h, hipMemcpyAsync(h->stage_out, h->buf.z, cnt * 4, hipMemcpyDeviceToHost, h->st));
@@ -739,13 +840,15 @@ int32_t sd_verify(sd_handle* h, int32_t batch, const int32_t* prefix, const int3
         if (draft[i] < 0 || draft[i] >= h->target.c.vocab) return fail(h, SD_ERR_TOKEN, "draft token outside the vocabulary");
     memcpy(h->stage_z, draft, cnt * 4);
     SD_HIP(h, hipMemcpyAsync(h->buf.z, h->stage_z, cnt * 4, hipMemcpyHostToDevice, h->st));
-    rc = enqueue_target(h, batch, prefix, prefix_len, n, gamma);
+    h->stage_seed[0] = seed;
+    SD_HIP(h, hipMemcpyAsync(h->buf.seed, h->stage_seed, 8, hipMemcpyHostToDevice, h->st));
+    rc = prepare_target(h, batch, prefix, prefix_len, n, gamma);
     if (rc) return rc;
-    const SampleScratch ss = sampling_scratch(h->buf.sample_scratch, (int)h->lim.rows_head, h->target.c.vocab);
-    SD_LAUNCH(h, "accept_resample(k_row_stats+k_accept+k_final_partial+k_final_sample)",
-              ((double)batch * (gamma + 1) + 4.0 * batch) * h->target.ld * 4, 0,
-              launch_accept_resample(h->buf.logits_t, q_dev, h->buf.z, batch, gamma, h->target.c.vocab, seed,
-                                     h->buf.n_acc, h->buf.tok, ss, h->st));
+    rc = replay(h, shape_key(2, batch, gamma, 0, prefix_len, q_dev), [&] {
+        const int r2 = enqueue_target(h);
+        return r2 ? r2 : enqueue_accept(h, batch, gamma, q_dev);
+    });
+    if (rc) return rc;
     rc = read_back(h, n_accepted_out, h->buf.n_acc, batch);
     if (rc) return rc;
     return read_back(h, token_out, h->buf.tok, batch);
@@ -760,15 +863,16 @@ int32_t sd_round(sd_handle* h, int32_t batch, const int32_t* prefix, const int32
     if (T <= 0 || T > kMaxSteps) return fail(h, SD_ERR_SHAPE, "T outside [1, 256]");
     rc = check_round_shapes(h, batch, prefix_len, gamma);
     if (rc) return rc;
-    rc = enqueue_draft(h, batch, prefix, prefix_len, n, gamma, T, seed);
+    rc = prepare_draft(h, batch, prefix, prefix_len, n, gamma, seed);
     if (rc) return rc;
-    rc = enqueue_target(h, batch, prefix, prefix_len, n, gamma);
+    rc = prepare_target(h, batch, prefix, prefix_len, n, gamma);
     if (rc) return rc;
-    const SampleScratch ss = sampling_scratch(h->buf.sample_scratch, (int)h->lim.rows_head, h->target.c.vocab);
-    SD_LAUNCH(h, "accept_resample(k_row_stats+k_accept+k_final_partial+k_final_sample)",
-              ((double)batch * (gamma + 1) + 4.0 * batch) * h->target.ld * 4, 0,
-              launch_accept_resample(h->buf.logits_t, h->buf.q, h->buf.z, batch, gamma, h->target.c.vocab, seed,
-                                     h->buf.n_acc, h->buf.tok, ss, h->st));
+    rc = replay(h, shape_key(3, batch, gamma, T, prefix_len, nullptr), [&] {
+        int r2 = enqueue_draft(h, batch, gamma, T);
+        if (!r2) r2 = enqueue_target(h);
+        return r2 ? r2 : enqueue_accept(h, batch, gamma, h->buf.q);
+    });
+    if (rc) return rc;
     const int64_t cnt = (int64_t)batch * gamma;
     int32_t* so = h->stage_out;
     SD_HIP(h, hipMemcpyAsync(so, h->buf.z, cnt * 4, hipMemcpyDeviceToHost, h->st));
@@ -804,16 +908,15 @@ int32_t sd_drafter_logits(sd_handle* h, int32_t batch, const int32_t* tokens, co
         for (int k = 0; k < gamma; ++k) blk[(size_t)b * gamma + k] = tokens[off + plen[b] + k];
         off += seq_len[b];
     }
-    RowMaps rm;
-    rc = upload_rows(h, 0, batch, pre.data(), plen.data(), (int64_t)pre.size(), gamma, &rm);
+    rc = upload_rows(h, 0, batch, pre.data(), plen.data(), (int64_t)pre.size(), gamma);
     if (rc) return rc;
     memcpy(h->stage_z, blk.data(), blk.size() * 4);
     SD_HIP(h, hipMemcpyAsync(h->buf.z, h->stage_z, blk.size() * 4, hipMemcpyHostToDevice, h->st));
     const Model& m = h->drafter;
-    SD_HIP(h, launch_timestep_embed(m.c.dtype, m.t_w1, m.t_b1, m.t_w2, m.t_b2, nullptr, h->buf.temb, T, m.c.d_model, h->st));
-    rc = run_layers(h, m, rm, h->buf.temb + (int64_t)(step - 1) * m.c.d_model);
+    SD_HIP(h, launch_timestep_embed(m.c.dtype, m.t_w1, m.t_b1, m.t_w2, m.t_b2, h->buf.temb_hidden, h->buf.temb, T, m.c.d_model, h->st));
+    rc = run_layers(h, m, h->maps[0], h->buf.temb + (int64_t)(step - 1) * m.c.d_model);
     if (rc) return rc;
-    rc = run_head(h, m, h->buf.blk_idx, batch * gamma, h->buf.logits_d);
+    rc = run_head(h, m, h->maps[0].blk, batch * gamma, h->buf.logits_d);
     if (rc) return rc;
     { const int rc_ = sync_stream(h); if (rc_) return rc_; }
     *logits_dev_out = h->buf.logits_d;
@@ -833,10 +936,18 @@ int32_t sd_target_logits(sd_handle* h, int32_t batch, const int32_t* prefix, con
         if (draft[i] < 0 || draft[i] >= h->target.c.vocab) return fail(h, SD_ERR_TOKEN, "draft token outside the vocabulary");
     memcpy(h->stage_z, draft, cnt * 4);
     SD_HIP(h, hipMemcpyAsync(h->buf.z, h->stage_z, cnt * 4, hipMemcpyHostToDevice, h->st));
-    rc = enqueue_target(h, batch, prefix, prefix_len, n, gamma);
+    rc = prepare_target(h, batch, prefix, prefix_len, n, gamma);
+    if (rc) return rc;
+    rc = enqueue_target(h);
     if (rc) return rc;
     { const int rc_ = sync_stream(h); if (rc_) return rc_; }
     *logits_dev_out = h->buf.logits_t;
+    return SD_OK;
+}
+
+int32_t sd_set_graph_replay(sd_handle* h, int32_t enable) {
+    if (!h) return SD_ERR_ARG;
+    h->use_graphs = enable != 0;
     return SD_OK;
 }
 
@@ -879,7 +990,9 @@ int32_t sd_unmask_sample(const float* logits, int32_t batch, int32_t gamma, int3
     if (scratch_bytes < sampling_scratch_bytes(batch * (gamma + 1), vocab) || (reinterpret_cast<uintptr_t>(scratch) & 255))
         return SD_ERR_WORKSPACE;
     const SampleScratch ss = sampling_scratch(scratch, batch * (gamma + 1), vocab);
-    return launch_unmask_sample(logits, batch, gamma, vocab, step, seed, z, q, qtok, ss, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? SD_OK : SD_ERR_HIP;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (hipMemcpyAsync(ss.seed, &seed, 8, hipMemcpyHostToDevice, st) != hipSuccess) return SD_ERR_HIP;   // pageable source: staged before return
+    return launch_unmask_sample(logits, batch, gamma, vocab, step, ss.seed, z, q, qtok, ss, st) == hipSuccess ? SD_OK : SD_ERR_HIP;
 }
 
 int32_t sd_accept_resample(const float* p_logits, const float* q, const int32_t* draft, int32_t batch, int32_t gamma,
@@ -890,7 +1003,14 @@ int32_t sd_accept_resample(const float* p_logits, const float* q, const int32_t*
     if (scratch_bytes < sampling_scratch_bytes(batch * (gamma + 1), vocab) || (reinterpret_cast<uintptr_t>(scratch) & 255))
         return SD_ERR_WORKSPACE;
     const SampleScratch ss = sampling_scratch(scratch, batch * (gamma + 1), vocab);
-    return launch_accept_resample(p_logits, q, draft, batch, gamma, vocab, seed, n_accepted, token, ss, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? SD_OK : SD_ERR_HIP;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (hipMemcpyAsync(ss.seed, &seed, 8, hipMemcpyHostToDevice, st) != hipSuccess) return SD_ERR_HIP;   // pageable source: staged before return
+    return launch_accept_resample(p_logits, q, draft, batch, gamma, vocab, ss.seed, n_accepted, token, ss, st) == hipSuccess ? SD_OK : SD_ERR_HIP;
+}
+
+int32_t sd_set_linear_variant(int32_t variant) {
+    linear_mfma_set_variant(variant);
+    return SD_OK;
 }
 
 int32_t sd_linear(int32_t dtype, const void* x, const void* w, const float* bias, void* y, int32_t m, int32_t n,

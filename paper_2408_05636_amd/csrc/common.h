@@ -61,11 +61,23 @@ struct AttnArgs {
     void* out; int out_ld;
     int rows, n_head, n_kv_head, d_head;
     int max_kv;                              // upper bound of kv_len over the rows
+    // Query tiles for the matrix-core kernel: tile t = rows tile_row0[t] .. +tile_rows[t]-1 (<= 32 rows,
+    // all of one sequence).  NULL / 0 when not provided.
+    const int32_t* tile_row0 = nullptr;
+    const int32_t* tile_rows = nullptr;
+    int n_tiles = 0;
 };
+bool attention_mfma_supported(int dtype, const AttnArgs& a);
+hipError_t launch_attention_mfma(const AttnArgs& a, hipStream_t st, const char** kernel_name);
 hipError_t launch_attention(int dtype, const AttnArgs& a, hipStream_t st, const char** kernel_name);
 hipError_t launch_attention_generic(int dtype, const AttnArgs& a, int max_kv, hipStream_t st);
 hipError_t launch_linear_generic(int dtype, const void* x, const void* w, const float* bias, void* y, int m, int n,
                                  int k, int ldy, int epilogue, hipStream_t st);
+
+bool linear_mfma_supported(int dtype, int m, int n, int k, int ldy);
+void linear_mfma_set_variant(int v);   // tuning hook: force a tile variant (-1 = choose by shape)
+hipError_t launch_linear_mfma(const void* x, const void* w, const float* bias, void* y, int m, int n, int k, int ldy,
+                              int epilogue, hipStream_t st, const char** kernel_name);
 
 // act[r, c] = silu(gu[r, c]) * gu[r, F + c]
 hipError_t launch_swiglu(int dtype, const void* gu, void* act, int rows, int F, hipStream_t st);
@@ -78,14 +90,17 @@ struct SampleScratch {       // carved from one device buffer by sampling_scratc
     double* row_m;           // [batch] max of the row the final token is drawn from
     double* row_z;           // [batch] its softmax normaliser
     int32_t* active;         // [rows]
+    uint64_t* seed;          // Philox key of the current call (kernels read it from memory so that a
+                             // captured graph can be replayed with a new seed)
 };
 int64_t sampling_scratch_bytes(int rows, int vocab);
 SampleScratch sampling_scratch(void* base, int rows, int vocab);
 
-hipError_t launch_unmask_sample(const float* logits, int batch, int gamma, int vocab, int step, uint64_t seed,
+hipError_t launch_fill_i32(int32_t* p, int n, int v, hipStream_t st);
+hipError_t launch_unmask_sample(const float* logits, int batch, int gamma, int vocab, int step, const uint64_t* seed,
                                 int32_t* z, float* q, float* qtok, const SampleScratch& s, hipStream_t st);
 hipError_t launch_accept_resample(const float* p_logits, const float* q, const int32_t* draft, int batch,
-                                  int gamma, int vocab, uint64_t seed, int32_t* n_acc, int32_t* token,
+                                  int gamma, int vocab, const uint64_t* seed, int32_t* n_acc, int32_t* token,
                                   const SampleScratch& s, hipStream_t st);
 
 }  // namespace sd

@@ -30,43 +30,39 @@ __global__ __launch_bounds__(256) void k_embed(const int32_t* __restrict__ src, 
 }
 
 // ---------------------------------------------------------------- timestep embedding (drafter)
-// grid (T): block j-1 computes temb(j/T).  s(t)_i = sin(1000 t f_i), s(t)_{i+d/2} = cos(1000 t f_i),
-// f_i = 10000^(-2i/d), evaluated in fp64 (T*d values per call); two d x d mat-vecs in fp32.
-template <typename T>
-__global__ __launch_bounds__(256) void k_timestep_embed(const T* __restrict__ w1, const float* __restrict__ b1,
-                                                        const T* __restrict__ w2, const float* __restrict__ b2,
-                                                        float* __restrict__ hidden, float* __restrict__ temb,
-                                                        int n_steps, int d) {
-    extern __shared__ float sm[];      // [d] sinusoid, then [d] hidden
-    float* s = sm;
-    float* hid = sm + d;
-    const int j = blockIdx.x + 1;
-    const double t = (double)j / (double)n_steps;
-    const int half = d / 2;
-    for (int i = threadIdx.x; i < half; i += blockDim.x) {
-        const double f = exp(-log(10000.0) * 2.0 * (double)i / (double)d);
-        s[i] = (float)sin(1000.0 * t * f);
-        s[i + half] = (float)cos(1000.0 * t * f);
+// temb(j/T) = W2 silu(W1 s + b1) + b2 with s_i = sin(1000 t f_i), s_{i+d/2} = cos(1000 t f_i),
+// f_i = 10000^(-2i/d), the sinusoid evaluated in fp64.  Two launches of the same mat-vec kernel,
+// grid (d / 16, T): a workgroup produces 16 outputs of one timestep, one wave per 4 outputs.
+template <typename T, bool FIRST>
+__global__ __launch_bounds__(256) void k_timestep_matvec(const T* __restrict__ w, const float* __restrict__ b,
+                                                         const float* __restrict__ in, float* __restrict__ out,
+                                                         int n_steps, int d) {
+    extern __shared__ float s[];       // [d] input vector of this timestep
+    const int j = blockIdx.y + 1;
+    if (FIRST) {
+        const double t = (double)j / (double)n_steps;
+        const int half = d / 2;
+        for (int i = threadIdx.x; i < half; i += blockDim.x) {
+            const double f = exp(-log(10000.0) * 2.0 * (double)i / (double)d);
+            s[i] = (float)sin(1000.0 * t * f);
+            s[i + half] = (float)cos(1000.0 * t * f);
+        }
+    } else {
+        for (int i = threadIdx.x; i < d; i += blockDim.x) s[i] = in[(size_t)(j - 1) * d + i];
     }
     __syncthreads();
-    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6, nw = blockDim.x >> 6;
-    for (int o = wv; o < d; o += nw) {            // one wave per output row, lanes over the reduction
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    for (int q = 0; q < 4; ++q) {
+        const int o = blockIdx.x * 16 + wv * 4 + q;
+        if (o >= d) break;
         float acc = 0.f;
-        for (int i = lane; i < d; i += 64) acc += to_f(w1[(size_t)o * d + i]) * s[i];
+        for (int i = lane; i < d; i += 64) acc += to_f(w[(size_t)o * d + i]) * s[i];
         for (int off = 32; off > 0; off >>= 1) acc += __shfl_down(acc, off, 64);
         if (lane == 0) {
-            const float x = acc + b1[o];
-            hid[o] = x / (1.f + expf(-x));
+            const float x = acc + b[o];
+            out[(size_t)(j - 1) * d + o] = FIRST ? x / (1.f + expf(-x)) : x;
         }
     }
-    __syncthreads();
-    for (int o = wv; o < d; o += nw) {
-        float acc = 0.f;
-        for (int i = lane; i < d; i += 64) acc += to_f(w2[(size_t)o * d + i]) * hid[i];
-        for (int off = 32; off > 0; off >>= 1) acc += __shfl_down(acc, off, 64);
-        if (lane == 0) temb[(size_t)(j - 1) * d + o] = acc + b2[o];
-    }
-    (void)hidden;
 }
 
 // ---------------------------------------------------------------- LayerNorm / RMSNorm
@@ -168,7 +164,9 @@ hipError_t launch_embed(int dtype, const int32_t* src, const int32_t* pos, const
 
 hipError_t launch_timestep_embed(int dtype, const void* w1, const float* b1, const void* w2, const float* b2,
                                  float* hidden, float* temb, int T_steps, int d, hipStream_t st) {
-    SD_DISPATCH(dtype, (k_timestep_embed<T><<<T_steps, 256, 2 * d * sizeof(float), st>>>((const T*)w1, b1, (const T*)w2, b2, hidden, temb, T_steps, d)));
+    const dim3 grid((d + 15) / 16, T_steps);
+    SD_DISPATCH(dtype, (k_timestep_matvec<T, true><<<grid, 256, d * sizeof(float), st>>>((const T*)w1, b1, nullptr, hidden, T_steps, d)));
+    SD_DISPATCH(dtype, (k_timestep_matvec<T, false><<<grid, 256, d * sizeof(float), st>>>((const T*)w2, b2, hidden, temb, T_steps, d)));
     return hipGetLastError();
 }
 

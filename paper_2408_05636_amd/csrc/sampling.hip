@@ -97,12 +97,12 @@ __device__ inline bool reveal_now(int k, int step, int b, uint64_t seed) {
 // grid (n_chunks, rows).  z != NULL: drafter mode, rows that are not revealed at this step are skipped.
 __global__ __launch_bounds__(kThreads) void k_row_stats(const float* __restrict__ logits, int ld, int vocab,
                                                         const int32_t* __restrict__ z, int gamma, int step,
-                                                        uint64_t seed, double* __restrict__ part_m,
+                                                        const uint64_t* __restrict__ seed_p, double* __restrict__ part_m,
                                                         double* __restrict__ part_s, int32_t* __restrict__ active) {
     __shared__ double sh[4];
     const int row = blockIdx.y, c = blockIdx.x, nch = gridDim.x;
     if (z != nullptr) {
-        const bool act = (z[row] == vocab) && reveal_now(row % gamma, step, row / gamma, seed);
+        const bool act = (z[row] == vocab) && reveal_now(row % gamma, step, row / gamma, *seed_p);
         if (c == 0 && threadIdx.x == 0) active[row] = act ? 1 : 0;
         if (!act) return;
     }
@@ -178,7 +178,7 @@ __device__ inline int select_in_chunk(const double (&w)[4], int col0, double bef
 // grid (n_chunks, rows).  Writes the full q row of every revealed slot; the workgroup owning the
 // chunk where the CDF crosses u picks the token.
 __global__ __launch_bounds__(kThreads) void k_unmask_sample(const float* __restrict__ logits, int ld, int vocab,
-                                                            int gamma, int step, uint64_t seed,
+                                                            int gamma, int step, const uint64_t* __restrict__ seed_p,
                                                             const double* __restrict__ part_m,
                                                             const double* __restrict__ part_s,
                                                             const int32_t* __restrict__ active, int32_t* __restrict__ z,
@@ -192,7 +192,7 @@ __global__ __launch_bounds__(kThreads) void k_unmask_sample(const float* __restr
     const double m = combine_chunks(part_m + (size_t)row * nch, part_s + (size_t)row * nch, nch, sS, sh);
     if (threadIdx.x == 0) {
         const Philox4 r = philox4x32_10((uint32_t)(row % gamma), (uint32_t)step, (uint32_t)(row / gamma),
-                                        STREAM_DRAFT, seed);
+                                        STREAM_DRAFT, *seed_p);
         pick = pick_chunk(sS, nch, uniform_f64(r.y));
     }
     __syncthreads();
@@ -220,7 +220,7 @@ __global__ __launch_bounds__(kThreads) void k_unmask_sample(const float* __restr
 // grid (batch).  Row statistics of P[0..gamma], the gamma acceptance tests, n = first rejection.
 __global__ __launch_bounds__(kThreads) void k_accept(const float* __restrict__ p_logits, const float* __restrict__ q,
                                                      const int32_t* __restrict__ draft, int ld, int vocab, int gamma,
-                                                     int nch, uint64_t seed, const double* __restrict__ part_m,
+                                                     int nch, const uint64_t* __restrict__ seed_p, const double* __restrict__ part_m,
                                                      const double* __restrict__ part_s, int32_t* __restrict__ n_acc,
                                                      double* __restrict__ row_m, double* __restrict__ row_z) {
     extern __shared__ double dyn[];          // [gamma+1] maxima, [gamma+1] normalisers
@@ -247,7 +247,7 @@ __global__ __launch_bounds__(kThreads) void k_accept(const float* __restrict__ p
             const size_t prow = (size_t)b * (gamma + 1) + k, qrow = (size_t)b * gamma + k;
             const float px = (float)(exp((double)p_logits[prow * ld + x] - rm[k]) / rz[k]);
             const float qx = q[qrow * ld + x];
-            const Philox4 r = philox4x32_10((uint32_t)k, 0u, (uint32_t)b, STREAM_VERIFY, seed);
+            const Philox4 r = philox4x32_10((uint32_t)k, 0u, (uint32_t)b, STREAM_VERIFY, *seed_p);
             ok = __fmul_rn(uniform_f32(r.x), qx) <= px;        // accept iff r q(x) <= p(x), fp32 product
         }
         if (!ok) first_reject = min(first_reject, k);
@@ -296,7 +296,7 @@ __global__ __launch_bounds__(kThreads) void k_final_partial(const float* __restr
 // grid (batch): pick the chunk, then the token.
 __global__ __launch_bounds__(kThreads) void k_final_sample(const float* __restrict__ p_logits,
                                                            const float* __restrict__ q, int ld, int vocab, int gamma,
-                                                           int nch, uint64_t seed, const int32_t* __restrict__ n_acc,
+                                                           int nch, const uint64_t* __restrict__ seed_p, const int32_t* __restrict__ n_acc,
                                                            const double* __restrict__ row_m,
                                                            const double* __restrict__ row_z,
                                                            const double* __restrict__ part_m,
@@ -314,7 +314,7 @@ __global__ __launch_bounds__(kThreads) void k_final_sample(const float* __restri
     for (int i = threadIdx.x; i < nch; i += kThreads) sS[i] = part_r[(size_t)b * nch + i];
     __syncthreads();
     if (threadIdx.x == 0) {
-        const Philox4 r = philox4x32_10((uint32_t)n, 0u, (uint32_t)b, STREAM_VERIFY, seed);
+        const Philox4 r = philox4x32_10((uint32_t)n, 0u, (uint32_t)b, STREAM_VERIFY, *seed_p);
         const double u = uniform_f64(r.y);
         int resid = n < gamma;
         if (resid) {
@@ -345,6 +345,19 @@ __global__ __launch_bounds__(kThreads) void k_final_sample(const float* __restri
     if (threadIdx.x == 0) token[b] = v;
 }
 
+// z <- value (the all-[MASK] start state of the block); a kernel rather than a memset so that it can
+// live inside a captured graph.
+__global__ void k_fill_i32(int32_t* __restrict__ p, int n, int v) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+hipError_t launch_fill_i32(int32_t* p, int n, int v, hipStream_t st) {
+    if (n <= 0) return hipSuccess;
+    k_fill_i32<<<(n + 255) / 256, 256, 0, st>>>(p, n, v);
+    return hipGetLastError();
+}
+
 // ---------------------------------------------------------------- host side
 int64_t sampling_scratch_bytes(int rows, int vocab) {
     if (rows <= 0 || vocab <= 0) return 0;
@@ -353,6 +366,7 @@ int64_t sampling_scratch_bytes(int rows, int vocab) {
     b += align_up(rows * nch * 8, 256) * 3;   // part_m, part_s, part_r
     b += align_up((int64_t)rows * 8, 256) * 2; // row_m, row_z
     b += align_up((int64_t)rows * 4, 256);     // active
+    b += 256;                                  // seed slot
     return b;
 }
 
@@ -366,11 +380,12 @@ SampleScratch sampling_scratch(void* base, int rows, int vocab) {
     s.part_r = reinterpret_cast<double*>(p); p += big;
     s.row_m = reinterpret_cast<double*>(p); p += small;
     s.row_z = reinterpret_cast<double*>(p); p += small;
-    s.active = reinterpret_cast<int32_t*>(p);
+    s.active = reinterpret_cast<int32_t*>(p); p += align_up((int64_t)rows * 4, 256);
+    s.seed = reinterpret_cast<uint64_t*>(p);
     return s;
 }
 
-hipError_t launch_unmask_sample(const float* logits, int batch, int gamma, int vocab, int step, uint64_t seed,
+hipError_t launch_unmask_sample(const float* logits, int batch, int gamma, int vocab, int step, const uint64_t* seed,
                                 int32_t* z, float* q, float* qtok, const SampleScratch& s, hipStream_t st) {
     const int rows = batch * gamma, nch = n_chunks(vocab), ld = vocab_pad(vocab);
     const dim3 grid(nch, rows);
@@ -381,7 +396,7 @@ hipError_t launch_unmask_sample(const float* logits, int batch, int gamma, int v
 }
 
 hipError_t launch_accept_resample(const float* p_logits, const float* q, const int32_t* draft, int batch,
-                                  int gamma, int vocab, uint64_t seed, int32_t* n_acc, int32_t* token,
+                                  int gamma, int vocab, const uint64_t* seed, int32_t* n_acc, int32_t* token,
                                   const SampleScratch& s, hipStream_t st) {
     const int rows = batch * (gamma + 1), nch = n_chunks(vocab), ld = vocab_pad(vocab);
     k_row_stats<<<dim3(nch, rows), kThreads, 0, st>>>(p_logits, ld, vocab, nullptr, gamma, 0, seed, s.part_m,

@@ -79,3 +79,12 @@ def test_gpt2_small_full_size():
     """The benchmark workload's shapes: 12 layers, d = 768, V = 50257, prefix 256, gamma 16."""
     w = synth.workload("gpt2s")
     check_forwards(w["target"], w["drafter"], [256], 16, 8, seed=6, steps=[8, 1])
+
+
+def test_bf16_larger_ragged_batch_uses_query_split_attention():
+    """Enough query tiles (tiles x heads >= 1024) that attention runs one tile per wave."""
+    w = synth.workload("gpt2s")
+    t = synth.shrink(w["target"], n_layer=1, vocab=1500, n_ctx=512)
+    d = synth.shrink(w["drafter"], n_layer=1, vocab=1500, n_ctx=512)
+    lens = [int(x) for x in synth.gen_prefix_lengths(12, 150, 420, 77)]
+    check_forwards(t, d, lens, 32, 4, seed=11, steps=[2])

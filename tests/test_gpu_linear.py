@@ -1,0 +1,60 @@
+"""GPU parity of the dense contraction y = epilogue(x W^T + bias) (QKV / MLP / LM-head layers)
+against the fp64 oracle, over shapes that cover every kernel variant, ragged tile edges and
+all four epilogues."""
+import numpy as np
+import pytest
+
+from oracle import transformer as otf
+from paper_2408_05636_amd import synth
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+SHAPES = [  # (m, n, k)
+    (17, 768, 768), (16, 50257, 768), (17, 2304, 768), (17, 768, 3072),      # target / LM-head rows of the bench workload
+    (272, 2304, 768), (272, 768, 768), (272, 3072, 768), (272, 768, 3072),   # drafter rows
+    (1, 64, 64), (33, 100, 128), (65, 33, 192), (130, 4801, 1600), (700, 1000, 256), (3000, 1100, 128),
+]
+
+
+def run_case(dtype, m, n, k, epi, seed):
+    from paper_2408_05636_amd import binding
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((m, k)).astype(np.float32)
+    w = (rng.standard_normal((n, k)) * 0.05).astype(np.float32)
+    b = rng.standard_normal(n).astype(np.float32) * 0.1
+    y0 = rng.standard_normal((m, n)).astype(np.float32)            # previous content (residual epilogue adds to it)
+    if dtype == "bf16":
+        x, w = synth.round_to_bf16(x), synth.round_to_bf16(w)
+    td = torch.bfloat16 if dtype == "bf16" else torch.float32
+    xd, wd = torch.from_numpy(x).to("cuda:0").to(td), torch.from_numpy(w).to("cuda:0").to(td)
+    bd = torch.from_numpy(b).to("cuda:0")
+    out_f32 = epi in (2, 3)
+    ld = n + 5 if n % 2 else n                                      # a leading dimension larger than n
+    yd = torch.zeros(m, ld, dtype=torch.float32 if out_f32 else td, device="cuda:0")
+    yd[:, :n] = torch.from_numpy(y0).to("cuda:0").to(yd.dtype)
+    binding.sd_linear(dtype, xd, wd, bd, yd, epi)
+    got = yd.float().cpu().numpy()
+    ref = otf.linear(x, w, b)
+    if epi == 1:
+        ref = otf.gelu_tanh(ref)
+    if epi == 2:
+        ref = ref + y0.astype(np.float64)
+    assert np.array_equal(got[:, n:], np.zeros((m, ld - n), dtype=np.float32))   # nothing written past column n
+    scale = np.sqrt((ref ** 2).mean())
+    err = np.abs(got[:, :n] - ref).max()
+    # fp32 accumulation of exact products; outputs rounded to bf16 (2^-9 relative) for epilogues 0, 1
+    tol = 2e-5 * scale * max(1.0, np.sqrt(k / 256)) if dtype == "f32" or out_f32 else 6e-3 * max(scale, np.abs(ref).max())
+    assert err <= tol, (dtype, m, n, k, epi, err, tol)
+
+
+@pytest.mark.parametrize("m,n,k", SHAPES)
+def test_linear_bf16_all_epilogues(m, n, k):
+    for epi in range(4):
+        run_case("bf16", m, n, k, epi, seed=m + n + k + epi)
+
+
+@pytest.mark.parametrize("m,n,k", [(9, 512, 128), (40, 384, 128), (40, 128, 512), (8, 512, 128), (70, 130, 72)])
+def test_linear_fp32_all_epilogues(m, n, k):
+    for epi in range(4):
+        run_case("f32", m, n, k, epi, seed=m + n + k + epi)

@@ -169,3 +169,26 @@ def test_argument_errors_are_reported():
     draft, n, tok = sd.sd_round([prefix], 8, 4, 1)                         # the handle still works
     assert draft.shape == (1, 8)
     sd.close()
+
+
+def test_graph_replay_equals_eager_launches():
+    """Captured launch sequences are replayed with new seeds and new prefixes of the same shape;
+    every replay must equal the eager result, with eager work and synchronisations in between."""
+    sd, t, d, Wt, Wd = make("gpt2s", seed=4, shrink_t=dict(n_layer=2, vocab=5003, n_ctx=128),
+                            shrink_d=dict(n_layer=2, vocab=5003, n_ctx=128), max_batch=2, gamma_max=16)
+    for trial in range(3):
+        prefixes = [synth.gen_prefix(t.vocab, L, 100 * trial + L) for L in (50, 21)]
+        for seed in (1, 2, 3):
+            sd.sd_set_graph_replay(True)
+            a = sd.sd_round(prefixes, 16, 8, seed)
+            d1, qt1, q1 = sd.sd_draft(prefixes, 16, 8, seed)
+            n1, t1 = sd.sd_verify(prefixes, d1, q1, seed)
+            sd.sd_set_graph_replay(False)
+            b = sd.sd_round(prefixes, 16, 8, seed)
+            d2, qt2, q2 = sd.sd_draft(prefixes, 16, 8, seed)
+            n2, t2 = sd.sd_verify(prefixes, d2, q2, seed)
+            for x, y in zip(a, b):
+                assert np.array_equal(x, y), (trial, seed)
+            assert np.array_equal(d1, d2) and np.array_equal(qt1, qt2) and np.array_equal(n1, n2) and np.array_equal(t1, t2)
+            assert np.array_equal(a[0], d1) and np.array_equal(a[1], n1) and np.array_equal(a[2], t1)
+    sd.close()

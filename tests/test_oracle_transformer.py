@@ -187,3 +187,10 @@ def test_elementwise_closed_forms():
     np.testing.assert_allclose(ln.mean(-1), 0, atol=1e-13)
     np.testing.assert_allclose((ln ** 2).mean(-1), 1, rtol=1e-12)
     np.testing.assert_allclose((otf.rms_norm(r, np.ones(33), 0.0) ** 2).mean(-1), 1, rtol=1e-12)
+
+
+def test_linear_matches_library_routine():
+    rng = np.random.default_rng(3)
+    x, W, b = rng.standard_normal((5, 7)), rng.standard_normal((4, 7)), rng.standard_normal(4)
+    np.testing.assert_allclose(otf.linear(x, W, b), F.linear(T64(x), T64(W), T64(b)).numpy(), rtol=1e-13)
+    assert otf.linear(np.eye(3), np.arange(6.0).reshape(2, 3)).tolist() == [[0, 3], [1, 4], [2, 5]]   # W is [out, in]
