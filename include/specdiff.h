@@ -162,6 +162,15 @@ int32_t sd_accept_resample(const float *p_logits, const float *q, const int32_t 
 int32_t sd_linear(int32_t dtype, const void *x, const void *w, const float *bias, void *y,
                   int32_t m, int32_t n, int32_t k, int32_t ldy, int32_t epilogue, void *hip_stream);
 
+/* y = epilogue(W norm(h) + bias): the normalisation in front of the QKV and MLP-up contractions folded
+ * into them (bf16 weights only).  norm_kind 1: LayerNorm(h; gain, beta, eps), 2: RMSNorm(h; gain, eps).
+ * h: fp32 [m, k] (the residual stream), w: bf16 [n, k], gain / beta: fp32 [k], bias: fp32 [n] or NULL,
+ * epilogue 0, 1 or 3 as in sd_linear.  fold_scratch: device, 2*n floats (receives W gain and
+ * W beta + bias, which a model computes once per layer).  All pointers device; asynchronous. */
+int32_t sd_norm_linear(int32_t norm_kind, const float *h, const void *w, const float *gain, const float *beta,
+                       const float *bias, void *y, int32_t m, int32_t n, int32_t k, int32_t ldy, int32_t epilogue,
+                       float eps, float *fold_scratch, void *hip_stream);
+
 /* Tuning hook for sd_linear and every contraction inside the forwards: force tile variant
  * `variant` of the matrix-core kernel (0..5, see the kernel source), -1 = choose by shape (default).
  * Process-wide; results do not depend on the variant beyond fp32 summation order. */

@@ -23,7 +23,7 @@ STATUS_NAMES = {0: "SD_OK", 1: "SD_ERR_ARG", 2: "SD_ERR_SHAPE", 3: "SD_ERR_TOKEN
 EXPORTS = ["sd_vocab_pad", "sd_weight_count", "sd_weight_desc", "sd_weight_bytes", "sd_workspace_bytes", "sd_create",
            "sd_destroy", "sd_last_error", "sd_prefill", "sd_draft", "sd_verify", "sd_round", "sd_drafter_logits",
            "sd_target_logits", "sd_sampling_scratch_bytes", "sd_unmask_sample", "sd_accept_resample", "sd_linear",
-           "sd_profile_begin", "sd_profile_end", "sd_profile_count", "sd_profile_entry", "sd_set_graph_replay", "sd_set_linear_variant"]
+           "sd_profile_begin", "sd_profile_end", "sd_profile_count", "sd_profile_entry", "sd_set_graph_replay", "sd_set_linear_variant", "sd_norm_linear"]
 
 
 class SdModelConfig(C.Structure):
@@ -78,6 +78,8 @@ def lib() -> C.CDLL:
         L.sd_linear.argtypes = [i32, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp]
         L.sd_set_graph_replay.restype = i32; L.sd_set_graph_replay.argtypes = [vp, i32]
         L.sd_set_linear_variant.restype = i32; L.sd_set_linear_variant.argtypes = [i32]
+        L.sd_norm_linear.restype = i32
+        L.sd_norm_linear.argtypes = [i32, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, C.c_float, vp, vp]
         L.sd_profile_begin.restype = i32; L.sd_profile_begin.argtypes = [vp]
         L.sd_profile_end.restype = i32; L.sd_profile_end.argtypes = [vp]
         L.sd_profile_count.restype = i32; L.sd_profile_count.argtypes = [vp]
@@ -316,3 +318,17 @@ def sd_linear(dtype: str, x, w, bias, y, epilogue: int):
     if rc:
         raise SdError(rc, "sd_linear")
     torch.cuda.synchronize(x.device)
+
+
+def sd_norm_linear(norm_kind: int, h, w, gain, beta, bias, y, epilogue: int, eps: float):
+    """y = epilogue(w norm(h) + bias) with the norm folded into the contraction; device tensors."""
+    import torch
+    m, k = h.shape
+    n = w.shape[0]
+    scratch = torch.empty(2 * n, dtype=torch.float32, device=h.device)
+    rc = lib().sd_norm_linear(norm_kind, h.data_ptr(), w.data_ptr(), gain.data_ptr(), beta.data_ptr() if beta is not None else None,
+                              bias.data_ptr() if bias is not None else None, y.data_ptr(), m, n, k, y.stride(0), epilogue, eps,
+                              scratch.data_ptr(), _stream_ptr(h))
+    if rc:
+        raise SdError(rc, "sd_norm_linear")
+    torch.cuda.synchronize(h.device)

@@ -85,6 +85,8 @@ struct Layer {
     const float *ln1_g = nullptr, *ln1_b = nullptr, *b_qkv = nullptr, *b_o = nullptr, *ln2_g = nullptr, *ln2_b = nullptr,
                 *b_fc = nullptr, *b_proj = nullptr;
     const void *w_qkv = nullptr, *w_o = nullptr, *w_fc = nullptr, *w_proj = nullptr;   // w_fc: [F,d] or gate|up [2F,d]
+    // LayerNorm folded into the next contraction: u = W g, v = W beta + bias (device, computed at creation)
+    float *fu_qkv = nullptr, *fv_qkv = nullptr, *fu_fc = nullptr, *fv_fc = nullptr;
 };
 
 struct Model {
@@ -93,6 +95,7 @@ struct Model {
     const void *wte = nullptr, *wpe = nullptr, *t_w1 = nullptr, *t_w2 = nullptr, *w_head = nullptr;
     const float *t_b1 = nullptr, *t_b2 = nullptr, *lnf_g = nullptr, *lnf_b = nullptr;
     std::vector<Layer> L;
+    bool fold = false;       // norms in front of QKV / MLP-up are folded into those contractions
 };
 
 bool bind_model(Model& m, const sd_model_config& c, const void* base) {
@@ -167,6 +170,7 @@ struct Buffers {
     char* maps[3];           // packed row maps: 0 drafter, 1 target query rows, 2 target prefill
     uint64_t* seed;          // Philox key of the current call
     void* sample_scratch;
+    float *fold_t, *fold_d;  // folded-norm vectors of the target / drafter layers
     void *kcache, *vcache;
 };
 
@@ -185,6 +189,13 @@ Limits limits_of(const sd_model_config& t, const sd_model_config& d, int max_bat
     l.prefix_cap = l.max_rows;
     l.map_bytes = align_up((l.prefix_cap + 6 * l.max_rows + (int64_t)max_batch * gamma_max) * 4 + 8 + l.max_rows * 8, 256);
     return l;
+}
+
+// floats needed for the folded LayerNorm vectors of a model (u and v for QKV and MLP-up of every layer)
+int64_t fold_floats(const sd_model_config& c) {
+    if (c.arch != SD_ARCH_GPT2 || c.dtype != SD_DTYPE_BF16) return 64;
+    const int64_t qkv = (int64_t)c.d_model + 2 * (int64_t)c.n_kv_head * (c.d_model / c.n_head);
+    return (int64_t)c.n_layer * 2 * (align_up(qkv, 64) + align_up(c.d_ff, 64));
 }
 
 int64_t carve(Arena& a, Buffers& b, const sd_model_config& t, const sd_model_config& d, int max_batch, int gamma_max) {
@@ -209,6 +220,8 @@ int64_t carve(Arena& a, Buffers& b, const sd_model_config& t, const sd_model_con
     for (int i = 0; i < 3; ++i) b.maps[i] = a.take<char>(l.map_bytes);
     b.seed = a.take<uint64_t>(32);
     b.sample_scratch = a.take<char>(sampling_scratch_bytes((int)l.rows_head, t.vocab));
+    b.fold_t = a.take<float>(fold_floats(t));
+    b.fold_d = a.take<float>(fold_floats(d));
     const int64_t cache = (int64_t)t.n_layer * max_batch * t.n_ctx * t.n_kv_head * (t.d_model / t.n_head);
     b.kcache = a.take<char>(cache, t.dtype == SD_DTYPE_BF16 ? 2 : 4);
     b.vcache = a.take<char>(cache, t.dtype == SD_DTYPE_BF16 ? 2 : 4);
@@ -525,6 +538,26 @@ int run_linear(sd_handle* h, int dt, const void* x, const void* w, const float* 
     return SD_OK;
 }
 
+// W norm(h) + bias with the norm folded into the contraction when the model allows it, else norm kernel + contraction.
+int run_norm_linear(sd_handle* h, const Model& m, const float* gain, const float* beta, const void* w, const float* bias,
+                    const float* fold_u, const float* fold_v, void* y, int rows, int n, int ldy, int epi) {
+    Buffers& B = h->buf;
+    const sd_model_config& c = m.c;
+    const int d = c.d_model;
+    if (m.fold && linear_normfold_supported(c.dtype, rows, n, d, ldy)) {
+        const double out_b = epi == EPI_F32 ? 4.0 : m.ew;
+        const double bytes = (double)rows * d * 4 + (double)n * d * m.ew + (double)rows * n * out_b;
+        const char* name = "linear_normfold";
+        const bool ln = c.arch == SD_ARCH_GPT2;
+        SD_LAUNCH(h, name, bytes, 2.0 * rows * n * d,
+                  launch_linear_normfold(B.h, w, gain, ln ? fold_u : nullptr, ln ? fold_v : bias, y, rows, n, d, ldy, epi,
+                                         ln ? 1 : 2, c.norm_eps, h->st, &name));
+        return SD_OK;
+    }
+    SD_LAUNCH(h, "k_norm", (double)rows * d * (4 + m.ew), 0, launch_norm(c.dtype, B.h, nullptr, gain, beta, B.xn, rows, d, c.norm_eps, h->st));
+    return run_linear(h, c.dtype, B.xn, w, bias, y, rows, n, d, ldy, epi);
+}
+
 int run_layers(sd_handle* h, const Model& m, const MapSet& rm, const float* temb) {
     Buffers& B = h->buf;
     const sd_model_config& c = m.c;
@@ -537,8 +570,7 @@ int run_layers(sd_handle* h, const Model& m, const MapSet& rm, const float* temb
     SD_LAUNCH(h, "k_embed", rd * (4 + ew), 0, launch_embed(dt, rm.src, rm.pos, rm.tokens, B.z, m.wte, m.wpe, temb, B.h, rows, d, h->st));
     for (int i = 0; i < c.n_layer; ++i) {
         const Layer& l = m.L[i];
-        SD_LAUNCH(h, "k_norm", rd * (4 + ew), 0, launch_norm(dt, B.h, nullptr, l.ln1_g, l.ln1_b, B.xn, rows, d, c.norm_eps, h->st));
-        if ((rc = run_linear(h, dt, B.xn, l.w_qkv, l.b_qkv, B.qkv, rows, qkv_w, d, qkv_w, EPI_STORE))) return rc;
+        if ((rc = run_norm_linear(h, m, l.ln1_g, l.ln1_b, l.w_qkv, l.b_qkv, l.fu_qkv, l.fv_qkv, B.qkv, rows, qkv_w, qkv_w, EPI_STORE))) return rc;
         if (c.arch == SD_ARCH_LLAMA)
             SD_LAUNCH(h, "k_rope", 2.0 * rows * (m.dq + m.dkv) * ew, 0, launch_rope(dt, B.qkv, rm.pos, rows, c.n_head, c.n_kv_head, m.dh, c.rope_theta, h->st));
         AttnArgs a;
@@ -561,12 +593,11 @@ int run_layers(sd_handle* h, const Model& m, const MapSet& rm, const float* temb
         const char* aname = "attention";
         SD_LAUNCH(h, aname, 2.0 * rd * ew + 2.0 * rm.kv_rows * m.dkv * ew, 4.0 * rm.kv_sum * d, launch_attention(dt, a, h->st, &aname));
         if ((rc = run_linear(h, dt, B.att, l.w_o, l.b_o, B.h, rows, d, d, d, EPI_RESID))) return rc;
-        SD_LAUNCH(h, "k_norm", rd * (4 + ew), 0, launch_norm(dt, B.h, nullptr, l.ln2_g, l.ln2_b, B.xn, rows, d, c.norm_eps, h->st));
         if (c.arch == SD_ARCH_GPT2) {
-            if ((rc = run_linear(h, dt, B.xn, l.w_fc, l.b_fc, B.mlp, rows, c.d_ff, d, c.d_ff, EPI_GELU))) return rc;
+            if ((rc = run_norm_linear(h, m, l.ln2_g, l.ln2_b, l.w_fc, l.b_fc, l.fu_fc, l.fv_fc, B.mlp, rows, c.d_ff, c.d_ff, EPI_GELU))) return rc;
             if ((rc = run_linear(h, dt, B.mlp, l.w_proj, l.b_proj, B.h, rows, d, c.d_ff, d, EPI_RESID))) return rc;
         } else {
-            if ((rc = run_linear(h, dt, B.xn, l.w_fc, nullptr, B.mlp, rows, 2 * c.d_ff, d, 2 * c.d_ff, EPI_STORE))) return rc;
+            if ((rc = run_norm_linear(h, m, l.ln2_g, nullptr, l.w_fc, nullptr, nullptr, nullptr, B.mlp, rows, 2 * c.d_ff, 2 * c.d_ff, EPI_STORE))) return rc;
             SD_LAUNCH(h, "k_swiglu", 3.0 * rows * c.d_ff * ew, 0, launch_swiglu(dt, B.mlp, B.act, rows, c.d_ff, h->st));
             if ((rc = run_linear(h, dt, B.act, l.w_proj, nullptr, B.h, rows, d, c.d_ff, d, EPI_RESID))) return rc;
         }
@@ -749,6 +780,31 @@ int32_t sd_create(const sd_model_config* target, const sd_model_config* drafter,
     const int64_t need = carve(a, h->buf, *target, *drafter, max_batch, gamma_max);
     if (need > workspace_bytes) { delete h; return SD_ERR_WORKSPACE; }
     if (!bind_model(h->target, *target, target_w) || !bind_model(h->drafter, *drafter, drafter_w)) { delete h; return SD_ERR_ARG; }
+    // Fold the LayerNorms in front of QKV and MLP-up into those contractions (bf16 models): u = W g, v = W beta + bias.
+    for (int which = 0; which < 2; ++which) {
+        Model& m = which ? h->drafter : h->target;
+        m.fold = m.c.dtype == SD_DTYPE_BF16;
+        if (!m.fold || m.c.arch != SD_ARCH_GPT2) continue;
+        float* p = which ? h->buf.fold_d : h->buf.fold_t;
+        const int qkv = m.dq + 2 * m.dkv, F = m.c.d_ff, d = m.c.d_model;
+        for (Layer& l : m.L) {
+            l.fu_qkv = p; p += align_up(qkv, 64);
+            l.fv_qkv = p; p += align_up(qkv, 64);
+            l.fu_fc = p; p += align_up(F, 64);
+            l.fv_fc = p; p += align_up(F, 64);
+            if (launch_fold_norm(l.w_qkv, l.ln1_g, l.ln1_b, l.b_qkv, l.fu_qkv, l.fv_qkv, qkv, d, static_cast<hipStream_t>(hip_stream)) != hipSuccess ||
+                launch_fold_norm(l.w_fc, l.ln2_g, l.ln2_b, l.b_fc, l.fu_fc, l.fv_fc, F, d, static_cast<hipStream_t>(hip_stream)) != hipSuccess) {
+                g_create_error = "launch of the norm-folding kernel failed";
+                delete h;
+                return SD_ERR_HIP;
+            }
+        }
+    }
+    if (hipStreamSynchronize(static_cast<hipStream_t>(hip_stream)) != hipSuccess) {
+        g_create_error = "norm folding failed";
+        delete h;
+        return SD_ERR_HIP;
+    }
     h->lim = limits_of(*target, *drafter, max_batch, gamma_max);
     h->max_batch = max_batch;
     h->gamma_max = gamma_max;
@@ -1006,6 +1062,20 @@ int32_t sd_accept_resample(const float* p_logits, const float* q, const int32_t*
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     if (hipMemcpyAsync(ss.seed, &seed, 8, hipMemcpyHostToDevice, st) != hipSuccess) return SD_ERR_HIP;   // pageable source: staged before return
     return launch_accept_resample(p_logits, q, draft, batch, gamma, vocab, ss.seed, n_accepted, token, ss, st) == hipSuccess ? SD_OK : SD_ERR_HIP;
+}
+
+int32_t sd_norm_linear(int32_t norm_kind, const float* h, const void* w, const float* gain, const float* beta,
+                       const float* bias, void* y, int32_t m, int32_t n, int32_t k, int32_t ldy, int32_t epilogue,
+                       float eps, float* fold_scratch, void* hip_stream) {
+    if (!h || !w || !gain || !y || !fold_scratch) return SD_ERR_ARG;
+    if (norm_kind != 1 && norm_kind != 2) return SD_ERR_ARG;
+    if (m <= 0 || n <= 0 || k <= 0 || ldy < n || epilogue < 0 || epilogue > 3 || epilogue == EPI_RESID) return SD_ERR_SHAPE;
+    if (!linear_normfold_supported(SD_DTYPE_BF16, m, n, k, ldy)) return SD_ERR_SHAPE;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    float* u = fold_scratch;
+    float* v = fold_scratch + n;
+    if (launch_fold_norm(w, gain, norm_kind == 1 ? beta : nullptr, bias, u, v, n, k, st) != hipSuccess) return SD_ERR_HIP;
+    return launch_linear_normfold(h, w, gain, u, v, y, m, n, k, ldy, epilogue, norm_kind, eps, st, nullptr) == hipSuccess ? SD_OK : SD_ERR_HIP;
 }
 
 int32_t sd_set_linear_variant(int32_t variant) {

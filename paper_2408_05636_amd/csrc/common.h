@@ -75,7 +75,14 @@ hipError_t launch_linear_generic(int dtype, const void* x, const void* w, const 
                                  int k, int ldy, int epilogue, hipStream_t st);
 
 bool linear_mfma_supported(int dtype, int m, int n, int k, int ldy);
-void linear_mfma_set_variant(int v);   // tuning hook: force a tile variant (-1 = choose by shape)
+void linear_mfma_set_variant(int v);
+// Contraction with the preceding LayerNorm (norm_kind 1) / RMSNorm (2) folded in: h is the fp32 residual stream.
+bool linear_normfold_supported(int dtype, int m, int n, int k, int ldy);
+hipError_t launch_linear_normfold(const float* h, const void* w, const float* gain, const float* fold_u,
+                                  const float* fold_v, void* y, int m, int n, int k, int ldy, int epilogue,
+                                  int norm_kind, float eps, hipStream_t st, const char** kernel_name);
+hipError_t launch_fold_norm(const void* w, const float* gain, const float* beta, const float* bias, float* u, float* v,
+                            int n, int k, hipStream_t st);   // tuning hook: force a tile variant (-1 = choose by shape)
 hipError_t launch_linear_mfma(const void* x, const void* w, const float* bias, void* y, int m, int n, int k, int ldy,
                               int epilogue, hipStream_t st, const char** kernel_name);
 

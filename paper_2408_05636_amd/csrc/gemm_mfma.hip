@@ -12,6 +12,8 @@
 //
 // A workgroup is WM x WN x KS waves (KS = waves that split the K range of one tile and reduce
 // through LDS in a fixed order: deterministic results, no atomics).
+#include <string>
+
 #include "common.h"
 
 namespace sd {
@@ -19,6 +21,7 @@ namespace sd {
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
 typedef __attribute__((__vector_size__(4 * sizeof(unsigned int)))) unsigned int u32x4;   // one 16-byte piece
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 constexpr int kBufFlags = 0x00020000;   // raw buffer, 32-bit data format (gfx9 family resource word 3)
 // Offset of accesses that must not happen.  Only the VGPR offset is range-checked (the scalar offset is
 // not), so everything that decides validity goes into the VGPR offset; buffers are < 2 GiB (checked on
@@ -31,10 +34,24 @@ __device__ inline float gelu_fast(float x) {
     return x / (1.f + __expf(-2.f * u));
 }
 
-template <int MT, int NT, int WM, int WN, int KS, int PD, int EPI>
-__global__ __launch_bounds__(256) void k_linear_mfma(const bf16_t* __restrict__ X, const bf16_t* __restrict__ W,
+// NF > 0: the normalisation in front of the contraction is folded into it.  X is then the fp32
+// residual stream h and the kernel computes  y = W norm(h) + bias  without a normalised copy of h:
+//   LayerNorm (NF = 1):  y_n = rstd_m (sum_k h_mk g_k W_nk - mu_m u_n) + v_n,  u = W g,  v = W beta + bias
+//   RMSNorm   (NF = 2):  y_n = rstd_m  sum_k h_mk g_k W_nk                         (u unused, v = bias)
+// The A operand is bf16(h_mk g_k), formed while the tile passes through the registers; sum h and
+// sum h^2 of every row ride along the K loop (each wave reads whole rows, or its K split of them), so
+// mu and rstd are known by the time the epilogue needs them.  u and v are precomputed per layer.
+struct NormFold {
+    const float* gain;   // g, [K]
+    const float* u;      // W g, [N] (LayerNorm only)
+    float eps;
+};
+
+template <int MT, int NT, int WM, int WN, int KS, int PD, int EPI, int NF>
+__global__ __launch_bounds__(256) void k_linear_mfma(const void* __restrict__ Xv, const bf16_t* __restrict__ W,
                                                      const float* __restrict__ bias, void* Y, int M,
-                                                     int N, int K, int ldy, int tiles_m, int tiles_n) {
+                                                     int N, int K, int ldy, int tiles_m, int tiles_n, NormFold nf) {
+    const bf16_t* X = static_cast<const bf16_t*>(Xv);
     static_assert(WM * WN * KS == 4, "four waves per workgroup");
     // The wave index is uniform across the wave; telling the compiler so keeps everything derived from it
     // (tile bases, K offsets) in scalar registers -- a scalar buffer offset it believes divergent costs a
@@ -58,7 +75,9 @@ __global__ __launch_bounds__(256) void k_linear_mfma(const bf16_t* __restrict__ 
     // All global traffic goes through buffer resources: the per-lane byte offset stays in one VGPR,
     // the K advance is a scalar offset (no address arithmetic in the loop), and out-of-range rows
     // need neither clamping nor branches -- loads beyond the matrix return 0, stores are dropped.
-    const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(X), 0, (uint32_t)M * (uint32_t)K * 2u, kBufFlags);
+    constexpr uint32_t kXBytes = NF > 0 ? 4u : 2u;
+    const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(X), 0, (uint32_t)M * (uint32_t)K * kXBytes, kBufFlags);
+    const __amdgpu_buffer_rsrc_t rg = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(nf.gain), 0, NF > 0 ? (uint32_t)K * 4u : 0u, kBufFlags);
     const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(W), 0, (uint32_t)N * (uint32_t)K * 2u, kBufFlags);
     // Load geometry: instruction i of a tile covers rows 8i .. 8i+7, lane -> (row 8i + lrow, 16-byte piece pc).
     const int lrow = lane >> 3, pc = lane & 7;
@@ -69,7 +88,7 @@ __global__ __launch_bounds__(256) void k_linear_mfma(const bf16_t* __restrict__ 
         for (int i = 0; i < 4; ++i) {
             const uint32_t row = t < MT ? (uint32_t)(m_base + 32 * t + 8 * i + lrow) : (uint32_t)(n_base + 32 * (t - MT) + 8 * i + lrow);
             const uint32_t lim = t < MT ? (uint32_t)M : (uint32_t)N;
-            goff[t][i] = row < lim ? (row * (uint32_t)K + 8u * pc) * 2u : kOutOfRange;
+            goff[t][i] = row < lim ? (row * (uint32_t)K + 8u * pc) * (t < MT ? kXBytes : 2u) : kOutOfRange;
         }
     const int wslot = lrow * 8 + (pc ^ lrow);            // swizzled slot of this lane's piece within an 8-row group
 
@@ -90,7 +109,8 @@ __global__ __launch_bounds__(256) void k_linear_mfma(const bf16_t* __restrict__ 
     // Output element (row m_base + 32 i + 8 (e/4) + 4 half + e%4, column n_base + 32 j + r): the lane part of
     // the byte offset; the (i, e) part is wave-uniform and goes into the scalar offset of each access.
     uint32_t yoff[NT];
-    float bv[NT];
+    float bv[NT], uv[NT];
+    const __amdgpu_buffer_rsrc_t ru = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(nf.u), 0, (NF == 1) ? (uint32_t)N * 4u : 0u, kBufFlags);
     floatx16 yres[kPrefetchResid ? MT : 1][kPrefetchResid ? NT : 1];
     if (wk == 0) {
 #pragma unroll
@@ -98,6 +118,7 @@ __global__ __launch_bounds__(256) void k_linear_mfma(const bf16_t* __restrict__ 
             const uint32_t n = (uint32_t)(n_base + 32 * j + r);
             yoff[j] = n < (uint32_t)N ? ((uint32_t)(m_base + 4 * half) * (uint32_t)ldy + n) * kOutBytes : kOutOfRange;
             bv[j] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rb, n * 4u, 0, 0));
+            uv[j] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(ru, n * 4u, 0, 0));
         }
         if constexpr (kPrefetchResid && EPI == EPI_RESID) {
 #pragma unroll
@@ -117,23 +138,56 @@ __global__ __launch_bounds__(256) void k_linear_mfma(const bf16_t* __restrict__ 
     // The steady-state loop has no conditional loads (the compiler's wait counts would otherwise
     // degrade to "wait for everything"); the last full group and the remainder are peeled.
     static_assert(PD % 2 == 0, "fragment double buffering assumes an even pipeline depth");
+    float s1[NF > 0 ? MT : 1][4] = {}, s2[NF > 0 ? MT : 1][4] = {};   // per-lane sum h, sum h^2 of rows 8i + lrow
     const int n_chunks = K / 64;
     const int n_mine = n_chunks > wk ? (n_chunks - wk + KS - 1) / KS : 0;
     if (n_mine > 0) {
         u32x4 g[PD][TILES][4];
+        u32x4 gx2[NF > 0 ? PD : 1][NF > 0 ? MT : 1][4];     // second half of the fp32 x pieces (NF)
+        u32x4 gg[NF > 0 ? PD : 1][2];                        // gain values of this lane's k range (NF)
         bf16x8 f[2][TILES][4];
 #define SD_GLOAD(P, LOCAL)                                                                               \
     {                                                                                                    \
         const uint32_t koff_ = (uint32_t)(wk + (LOCAL) * KS) * 128u;                                     \
         _Pragma("unroll") for (int t = 0; t < TILES; ++t) _Pragma("unroll") for (int i = 0; i < 4; ++i)  \
-            g[P][t][i] = __builtin_amdgcn_raw_buffer_load_b128(t < MT ? rx : rw, goff[t][i], koff_, 0);  \
+            g[P][t][i] = __builtin_amdgcn_raw_buffer_load_b128(t < MT ? rx : rw, goff[t][i],              \
+                                                               (NF > 0 && t < MT) ? 2u * koff_ : koff_, 0); \
+        if constexpr (NF > 0) {                                                                          \
+            _Pragma("unroll") for (int t = 0; t < MT; ++t) _Pragma("unroll") for (int i = 0; i < 4; ++i)  \
+                gx2[P][t][i] = __builtin_amdgcn_raw_buffer_load_b128(rx, goff[t][i] + 16u, 2u * koff_, 0); \
+            gg[P][0] = __builtin_amdgcn_raw_buffer_load_b128(rg, 32u * pc, 2u * koff_, 0);                \
+            gg[P][1] = __builtin_amdgcn_raw_buffer_load_b128(rg, 32u * pc + 16u, 2u * koff_, 0);          \
+        }                                                                                                \
     }
 // LDS operations of one wave execute in order: the fragment reads see the writes before them, and
 // the writes of the next chunk cannot overtake the reads of this one.
 #define SD_STAGE_TO_FRAG(P, FB)                                                                          \
     {                                                                                                    \
-        _Pragma("unroll") for (int t = 0; t < TILES; ++t) _Pragma("unroll") for (int i = 0; i < 4; ++i)  \
-            stage[t * 256 + i * 64 + wslot] = g[P][t][i];                                                \
+        _Pragma("unroll") for (int t = 0; t < TILES; ++t) _Pragma("unroll") for (int i = 0; i < 4; ++i) { \
+            if constexpr (NF > 0) {                                                                      \
+                if (t < MT) {                                                                            \
+                    constexpr int tx_ = 0;                                                               \
+                    float xs_[8], gs_[8];                                                                \
+                    const f32x4 xa_ = __builtin_bit_cast(f32x4, g[P][t][i]);                             \
+                    const f32x4 xb_ = __builtin_bit_cast(f32x4, gx2[P][t < MT ? t : tx_][i]);            \
+                    const f32x4 ga_ = __builtin_bit_cast(f32x4, gg[P][0]);                               \
+                    const f32x4 gb_ = __builtin_bit_cast(f32x4, gg[P][1]);                               \
+                    _Pragma("unroll") for (int u_ = 0; u_ < 4; ++u_) {                                   \
+                        xs_[u_] = xa_[u_];                                                               \
+                        xs_[4 + u_] = xb_[u_];                                                           \
+                        gs_[u_] = ga_[u_];                                                               \
+                        gs_[4 + u_] = gb_[u_];                                                           \
+                    }                                                                                    \
+                    bf16x8 pk_;                                                                          \
+                    _Pragma("unroll") for (int u_ = 0; u_ < 8; ++u_) {                                   \
+                        s1[t < MT ? t : tx_][i] += xs_[u_];                                              \
+                        s2[t < MT ? t : tx_][i] = fmaf(xs_[u_], xs_[u_], s2[t < MT ? t : tx_][i]);       \
+                        pk_[u_] = static_cast<bf16_t>(xs_[u_] * gs_[u_]);                                \
+                    }                                                                                    \
+                    stage[t * 256 + i * 64 + wslot] = __builtin_bit_cast(u32x4, pk_);                    \
+                } else stage[t * 256 + i * 64 + wslot] = g[P][t][i];                                     \
+            } else stage[t * 256 + i * 64 + wslot] = g[P][t][i];                                         \
+        }                                                                                                \
         _Pragma("unroll") for (int t = 0; t < TILES; ++t) _Pragma("unroll") for (int s4 = 0; s4 < 4; ++s4) \
             f[FB][t][s4] = __builtin_bit_cast(bf16x8, stage[t * 256 + r * 8 + ((2 * s4 + half) ^ (r & 7))]); \
     }
@@ -174,10 +228,40 @@ __global__ __launch_bounds__(256) void k_linear_mfma(const bf16_t* __restrict__ 
 #undef SD_MMA
     }
 
+    // Row statistics of the folded normalisation: combine the 8 lanes that share a row, then (K split) the waves.
+    float* const lds_f = reinterpret_cast<float*>(&stage_all[0][0]);
+    constexpr int kRedFloats = (KS - 1) * MT * NT * 16 * 64;
+    constexpr int kStatFloats = KS * MT * 32 * 2;
+    static_assert(sizeof(stage_all) >= (kRedFloats + kStatFloats + MT * 32 * 2) * sizeof(float), "epilogue scratch aliases the staging tiles");
+    if constexpr (NF > 0) {
+#pragma unroll
+        for (int t = 0; t < MT; ++t)
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int o = 1; o < 8; o <<= 1) {
+                    s1[t][i] += __shfl_xor(s1[t][i], o, 64);
+                    s2[t][i] += __shfl_xor(s2[t][i], o, 64);
+                }
+    }
+    // KS > 1: statistics of all waves at lds_f + kRedFloats; KS == 1: in the wave's own staging tile.
+    float* const stat = KS > 1 ? lds_f + kRedFloats : reinterpret_cast<float*>(stage);
+    float* const ab = stat + (KS > 1 ? kStatFloats : MT * 32 * 2);
+
     if constexpr (KS > 1) {           // fixed-order reduction over the K-splitting waves
-        static_assert(sizeof(stage_all) >= (KS - 1) * MT * NT * 16 * 64 * sizeof(float), "reduction buffer aliases the staging tiles");
-        float (*red)[MT * NT * 16][64] = reinterpret_cast<float (*)[MT * NT * 16][64]>(&stage_all[0][0]);
+        float (*red)[MT * NT * 16][64] = reinterpret_cast<float (*)[MT * NT * 16][64]>(lds_f);
         __syncthreads();               // every wave has finished with its staging tile
+        if constexpr (NF > 0) {
+            if (pc == 0) {
+#pragma unroll
+                for (int t = 0; t < MT; ++t)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        stat[((wk * MT + t) * 32 + 8 * i + lrow) * 2 + 0] = s1[t][i];
+                        stat[((wk * MT + t) * 32 + 8 * i + lrow) * 2 + 1] = s2[t][i];
+                    }
+            }
+        }
         if (wk > 0) {
 #pragma unroll
             for (int i = 0; i < MT; ++i)
@@ -196,6 +280,41 @@ __global__ __launch_bounds__(256) void k_linear_mfma(const bf16_t* __restrict__ 
                 for (int j = 0; j < NT; ++j)
 #pragma unroll
                     for (int e = 0; e < 16; ++e) acc[i][j][e] += red[k][(i * NT + j) * 16 + e][lane];
+    } else if constexpr (NF > 0) {
+        if (pc == 0) {
+#pragma unroll
+            for (int t = 0; t < MT; ++t)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    stat[(t * 32 + 8 * i + lrow) * 2 + 0] = s1[t][i];
+                    stat[(t * 32 + 8 * i + lrow) * 2 + 1] = s2[t][i];
+                }
+        }
+    }
+    float na[NF > 0 ? MT : 1][16], nb[NF > 0 ? MT : 1][16];   // per accumulator row: rstd and -rstd * mu
+    if constexpr (NF > 0) {
+        // (LDS operations of one wave execute in order: no barrier between these steps.)
+        if (lane < MT * 32) {
+            float S1 = 0.f, S2 = 0.f;
+#pragma unroll
+            for (int k = 0; k < KS; ++k) {
+                S1 += stat[(k * MT * 32 + lane) * 2 + 0];
+                S2 += stat[(k * MT * 32 + lane) * 2 + 1];
+            }
+            const float mu = NF == 1 ? S1 / (float)K : 0.f;
+            const float var = fmaxf(S2 / (float)K - mu * mu, 0.f);
+            const float rstd = rsqrtf(var + nf.eps);
+            ab[lane * 2 + 0] = rstd;
+            ab[lane * 2 + 1] = -rstd * mu;
+        }
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int row = 32 * i + 8 * (e >> 2) + 4 * half + (e & 3);
+                na[i][e] = ab[row * 2 + 0];
+                nb[i][e] = ab[row * 2 + 1];
+            }
     }
 
     // Epilogue.  Accumulator e of a 32 x 32 tile: row m = 8*(e/4) + 4*half + e%4, column n = lane & 31,
@@ -210,7 +329,9 @@ __global__ __launch_bounds__(256) void k_linear_mfma(const bf16_t* __restrict__ 
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 const uint32_t so = (uint32_t)(32 * i + 8 * (e >> 2) + (e & 3)) * (uint32_t)ldy * kOutBytes;
-                float v = acc[i][j][e] + bv[j];
+                float v = acc[i][j][e];
+                if constexpr (NF > 0) v = fmaf(na[i][e], v, nb[i][e] * uv[j]);
+                v += bv[j];
                 if constexpr (EPI == EPI_GELU) v = gelu_fast(v);
                 if constexpr (EPI == EPI_RESID) {
                     if constexpr (kPrefetchResid) v += yres[i][j][e];
@@ -223,18 +344,17 @@ __global__ __launch_bounds__(256) void k_linear_mfma(const bf16_t* __restrict__ 
             }
 }
 
-template <int MT, int NT, int WM, int WN, int KS, int PD>
+template <int MT, int NT, int WM, int WN, int KS, int PD, int NF>
 static hipError_t launch_variant(const void* x, const void* w, const float* bias, void* y, int m, int n, int k,
-                                 int ldy, int epi, hipStream_t st) {
+                                 int ldy, int epi, const NormFold& nf, hipStream_t st) {
     const int tiles_n = (n + 32 * NT * WN - 1) / (32 * NT * WN), tiles_m = (m + 32 * MT * WM - 1) / (32 * MT * WM);
     const int grid = 8 * ((tiles_n + 7) / 8) * tiles_m;       // every XCD gets the id range of the fullest one
-    const bf16_t* xb = (const bf16_t*)x;
     const bf16_t* wb = (const bf16_t*)w;
     switch (epi) {
-        case EPI_STORE: k_linear_mfma<MT, NT, WM, WN, KS, PD, EPI_STORE><<<grid, 256, 0, st>>>(xb, wb, bias, y, m, n, k, ldy, tiles_m, tiles_n); break;
-        case EPI_GELU: k_linear_mfma<MT, NT, WM, WN, KS, PD, EPI_GELU><<<grid, 256, 0, st>>>(xb, wb, bias, y, m, n, k, ldy, tiles_m, tiles_n); break;
-        case EPI_RESID: k_linear_mfma<MT, NT, WM, WN, KS, PD, EPI_RESID><<<grid, 256, 0, st>>>(xb, wb, bias, y, m, n, k, ldy, tiles_m, tiles_n); break;
-        default: k_linear_mfma<MT, NT, WM, WN, KS, PD, EPI_F32><<<grid, 256, 0, st>>>(xb, wb, bias, y, m, n, k, ldy, tiles_m, tiles_n); break;
+        case EPI_STORE: k_linear_mfma<MT, NT, WM, WN, KS, PD, EPI_STORE, NF><<<grid, 256, 0, st>>>(x, wb, bias, y, m, n, k, ldy, tiles_m, tiles_n, nf); break;
+        case EPI_GELU: k_linear_mfma<MT, NT, WM, WN, KS, PD, EPI_GELU, NF><<<grid, 256, 0, st>>>(x, wb, bias, y, m, n, k, ldy, tiles_m, tiles_n, nf); break;
+        case EPI_RESID: k_linear_mfma<MT, NT, WM, WN, KS, PD, EPI_RESID, NF><<<grid, 256, 0, st>>>(x, wb, bias, y, m, n, k, ldy, tiles_m, tiles_n, nf); break;
+        default: k_linear_mfma<MT, NT, WM, WN, KS, PD, EPI_F32, NF><<<grid, 256, 0, st>>>(x, wb, bias, y, m, n, k, ldy, tiles_m, tiles_n, nf); break;
     }
     return hipGetLastError();
 }
@@ -248,10 +368,18 @@ bool linear_mfma_supported(int dtype, int m, int n, int k, int ldy) {
 static int g_variant_override = -1;
 void linear_mfma_set_variant(int v) { g_variant_override = v; }
 
+static const char* const kEpiName[4] = {"0", "1", "2", "3"};
+static std::string g_names[2][8][4][3];   // [variant set][variant][epilogue][fold]: kernel names as rocprof prints them
+static const char* variant_name(const char* params, int v, int epi, int nfk) {
+    std::string& s = g_names[0][v][epi][nfk];
+    if (s.empty()) s = std::string("k_linear_mfma<") + params + "," + kEpiName[epi] + "," + kEpiName[nfk] + ">";
+    return s.c_str();
+}
+
 #define SD_VARIANT(ID, MT, NT, WM, WN, KS, PD)                                                      \
     case ID:                                                                                        \
-        if (kernel_name) *kernel_name = "k_linear_mfma<" #MT "," #NT "," #WM "," #WN "," #KS "," #PD ">"; \
-        return launch_variant<MT, NT, WM, WN, KS, PD>(x, w, bias, y, m, n, k, ldy, epi, st);
+        if (kernel_name) *kernel_name = variant_name(#MT "," #NT "," #WM "," #WN "," #KS "," #PD, ID, epi, 0); \
+        return launch_variant<MT, NT, WM, WN, KS, PD, 0>(x, w, bias, y, m, n, k, ldy, epi, NormFold{nullptr, nullptr, 0.f}, st);
 
 hipError_t launch_linear_mfma(const void* x, const void* w, const float* bias, void* y, int m, int n, int k, int ldy,
                               int epi, hipStream_t st, const char** kernel_name) {
@@ -270,6 +398,57 @@ hipError_t launch_linear_mfma(const void* x, const void* w, const float* bias, v
         SD_VARIANT(5, 1, 1, 2, 2, 1, 2)     // as 2 with a shallower global pipeline (more waves per SIMD)
         default: return hipErrorInvalidValue;
     }
+}
+
+// y = epilogue(W norm(h) + bias) with the normalisation folded in (see NormFold).  norm_kind 1 = LayerNorm
+// (u = W g and v = W beta + bias precomputed), 2 = RMSNorm (v = bias).  Same tile choice as above, restricted
+// to the variants with one 32-row x tile per wave.
+bool linear_normfold_supported(int dtype, int m, int n, int k, int ldy) {
+    return linear_mfma_supported(dtype, m, n, k, ldy) && (int64_t)m * k * 4 < ((int64_t)1 << 31);
+}
+
+hipError_t launch_linear_normfold(const float* h, const void* w, const float* gain, const float* fold_u,
+                                  const float* fold_v, void* y, int m, int n, int k, int ldy, int epi, int norm_kind,
+                                  float eps, hipStream_t st, const char** kernel_name) {
+    const long tiles64 = (long)((n + 63) / 64) * ((m + 63) / 64);
+    const bool small = m <= 32 || tiles64 < 160;
+    const NormFold nf{gain, fold_u, eps};
+    if (norm_kind == 1) {
+        if (small) {
+            if (kernel_name) *kernel_name = variant_name("1,1,1,1,4,2", 0, epi, 1);
+            return launch_variant<1, 1, 1, 1, 4, 2, 1>(h, w, fold_v, y, m, n, k, ldy, epi, nf, st);
+        }
+        if (kernel_name) *kernel_name = variant_name("1,1,2,2,1,2", 5, epi, 1);
+        return launch_variant<1, 1, 2, 2, 1, 2, 1>(h, w, fold_v, y, m, n, k, ldy, epi, nf, st);
+    }
+    if (small) {
+        if (kernel_name) *kernel_name = variant_name("1,1,1,1,4,2", 0, epi, 2);
+        return launch_variant<1, 1, 1, 1, 4, 2, 2>(h, w, fold_v, y, m, n, k, ldy, epi, nf, st);
+    }
+    if (kernel_name) *kernel_name = variant_name("1,1,2,2,1,2", 5, epi, 2);
+    return launch_variant<1, 1, 2, 2, 1, 2, 2>(h, w, fold_v, y, m, n, k, ldy, epi, nf, st);
+}
+
+// u[n] = sum_k g[k] W[n,k];  v[n] = sum_k beta[k] W[n,k] + bias[n]   (beta, bias may be NULL).  One wave per row.
+__global__ __launch_bounds__(256) void k_fold_norm(const bf16_t* __restrict__ W, const float* __restrict__ g,
+                                                   const float* __restrict__ beta, const float* __restrict__ bias,
+                                                   float* __restrict__ u, float* __restrict__ v, int N, int K) {
+    const int n = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (n >= N) return;
+    float su = 0.f, sv = 0.f;
+    for (int k = lane; k < K; k += 64) {
+        const float w = static_cast<float>(W[(size_t)n * K + k]);
+        su = fmaf(g[k], w, su);
+        if (beta) sv = fmaf(beta[k], w, sv);
+    }
+    for (int o = 32; o > 0; o >>= 1) { su += __shfl_xor(su, o, 64); sv += __shfl_xor(sv, o, 64); }
+    if (lane == 0) { u[n] = su; v[n] = sv + (bias ? bias[n] : 0.f); }
+}
+
+hipError_t launch_fold_norm(const void* w, const float* gain, const float* beta, const float* bias, float* u, float* v,
+                            int n, int k, hipStream_t st) {
+    k_fold_norm<<<(n + 3) / 4, 256, 0, st>>>((const bf16_t*)w, gain, beta, bias, u, v, n, k);
+    return hipGetLastError();
 }
 
 }  // namespace sd

@@ -58,3 +58,32 @@ def test_linear_bf16_all_epilogues(m, n, k):
 def test_linear_fp32_all_epilogues(m, n, k):
     for epi in range(4):
         run_case("f32", m, n, k, epi, seed=m + n + k + epi)
+
+
+@pytest.mark.parametrize("m,n,k", [(17, 2304, 768), (272, 2304, 768), (301, 3072, 768), (33, 100, 128), (65, 4801, 1600), (700, 1000, 256)])
+@pytest.mark.parametrize("norm_kind", [1, 2])
+def test_norm_folded_linear(m, n, k, norm_kind):
+    """LayerNorm / RMSNorm folded into the contraction vs. the oracle's norm followed by its linear."""
+    from paper_2408_05636_amd import binding
+    rng = np.random.default_rng(m + n + k + norm_kind)
+    # residual-stream-like rows: a common offset pattern plus row-specific parts, non-zero mean
+    h = (rng.standard_normal((1, k)) * 0.3 + rng.standard_normal((m, k)) * 0.2 + 0.05).astype(np.float32)
+    w = synth.round_to_bf16((rng.standard_normal((n, k)) * 0.05).astype(np.float32))
+    gain = (1 + rng.standard_normal(k) * 0.1).astype(np.float32)
+    beta = (rng.standard_normal(k) * 0.1).astype(np.float32)
+    bias = (rng.standard_normal(n) * 0.1).astype(np.float32)
+    eps = 1e-5
+    for epi in (0, 1, 3):
+        hd, wd = torch.from_numpy(h).to("cuda:0"), torch.from_numpy(w).to("cuda:0").bfloat16()
+        yd = torch.zeros(m, n, dtype=torch.float32 if epi == 3 else torch.bfloat16, device="cuda:0")
+        binding.sd_norm_linear(norm_kind, hd, wd, torch.from_numpy(gain).to("cuda:0"), torch.from_numpy(beta).to("cuda:0"),
+                               torch.from_numpy(bias).to("cuda:0"), yd, epi, eps)
+        x = otf.layer_norm(h.astype(np.float64), gain, beta, eps) if norm_kind == 1 else otf.rms_norm(h.astype(np.float64), gain, eps)
+        ref = otf.linear(x, w, bias)
+        if epi == 1:
+            ref = otf.gelu_tanh(ref)
+        got = yd.float().cpu().numpy()
+        scale = np.sqrt((ref ** 2).mean())
+        err = np.abs(got - ref).max()
+        # the A operand is rounded to bf16 (2^-9 relative per element): error ~ 2^-9 * scale / sqrt(3) * few sigma
+        assert err <= 0.012 * scale + (0.006 * np.abs(ref).max() if epi != 3 else 0), (m, n, k, norm_kind, epi, err, scale)
