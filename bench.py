@@ -64,6 +64,7 @@ def main():
     ap.add_argument("--T", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true", help="also launch one 64 MiB elementwise copy kernel, torch.neg (calibrates rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -96,6 +97,12 @@ def main():
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_per_step = dt / a.steps * 1e3
+    if a.copy_probe:
+        src = torch.ones(16 << 20, dtype=torch.float32, device="cuda:0")     # 64 MiB read, 64 MiB written
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        torch.neg(src, out=dst)                                              # one elementwise kernel ("neg")
+        torch.cuda.synchronize()
 
     roof = None
     phases = None

@@ -187,7 +187,8 @@ Limits limits_of(const sd_model_config& t, const sd_model_config& d, int max_bat
     l.ffmax = ffw(t) > ffw(d) ? ffw(t) : ffw(d);
     l.ew = (t.dtype == SD_DTYPE_F32 || d.dtype == SD_DTYPE_F32) ? 4 : 2;
     l.prefix_cap = l.max_rows;
-    l.map_bytes = align_up((l.prefix_cap + 6 * l.max_rows + (int64_t)max_batch * gamma_max) * 4 + 8 + l.max_rows * 8, 256);
+    l.map_bytes = align_up((l.prefix_cap + 4 * l.max_rows + (int64_t)max_batch * gamma_max) * 4 + 32 + l.max_rows * 8 +
+                           l.max_rows * (int64_t)sizeof(AttnTile), 256);
     return l;
 }
 
@@ -234,9 +235,9 @@ int64_t carve(Arena& a, Buffers& b, const sd_model_config& t, const sd_model_con
 // prefix tokens, per row: token source, position, sequence, visible key count, key offset;
 // per query tile: first row, row count; per block slot: its row.
 struct MapSet {
-    int32_t *tokens = nullptr, *src = nullptr, *pos = nullptr, *seq = nullptr, *kvl = nullptr, *t0 = nullptr,
-            *tn = nullptr, *blk = nullptr;
+    int32_t *tokens = nullptr, *src = nullptr, *pos = nullptr, *seq = nullptr, *kvl = nullptr, *blk = nullptr;
     int64_t* kv_off = nullptr;
+    AttnTile* tiles = nullptr;
     int rows = 0, n_tiles = 0, max_kv = 0;
     double kv_sum = 0, kv_rows = 0;     // sum of kv_len over rows; distinct key rows
     int64_t bytes = -1;
@@ -400,16 +401,20 @@ int upload_rows(sd_handle* h, int mode, int batch, const int32_t* tokens, const 
     int64_t o = 0;
     auto take = [&](int64_t n) { const int64_t at = o; o += n * 4; return at; };
     const int64_t o_tok = take(n_tokens), o_src = take(rows), o_pos = take(rows), o_seq = take(rows), o_kvl = take(rows),
-                  o_t0 = take(n_tiles), o_tn = take(n_tiles), o_blk = take(n_blk);
-    o = align_up(o, 8);
+                  o_blk = take(n_blk);
+    o = align_up(o, 16);
     const int64_t o_off = o;
     o += rows * 8;
+    o = align_up(o, 16);
+    const int64_t o_tiles = o;
+    o += n_tiles * (int64_t)sizeof(AttnTile);
     const int64_t bytes = o;
     char* hb = h->stage_maps[mode];
     int32_t *s_tok = (int32_t*)(hb + o_tok), *s_src = (int32_t*)(hb + o_src), *s_pos = (int32_t*)(hb + o_pos),
-            *s_seq = (int32_t*)(hb + o_seq), *s_kvl = (int32_t*)(hb + o_kvl), *s_t0 = (int32_t*)(hb + o_t0),
-            *s_tn = (int32_t*)(hb + o_tn), *s_blk = (int32_t*)(hb + o_blk);
+            *s_seq = (int32_t*)(hb + o_seq), *s_kvl = (int32_t*)(hb + o_kvl), *s_blk = (int32_t*)(hb + o_blk);
     int64_t* s_off = (int64_t*)(hb + o_off);
+    AttnTile* s_tiles = (AttnTile*)(hb + o_tiles);
+    memset(hb, 0, bytes);                                 // padding bytes take part in the "unchanged" comparison
     memcpy(s_tok, tokens, n_tokens * sizeof(int32_t));
     int64_t r = 0, tok_off = 0, nt = 0;
     int max_kv = 0;
@@ -454,9 +459,12 @@ int upload_rows(sd_handle* h, int mode, int batch, const int32_t* tokens, const 
             kv_rows += L - 1;
         }
         for (int64_t t0 = seq_row0; t0 < r; t0 += 32) {      // query tiles never span two sequences
-            s_t0[nt] = (int32_t)t0;
-            s_tn[nt] = (int32_t)(r - t0 < 32 ? r - t0 : 32);
-            ++nt;
+            AttnTile& tl = s_tiles[nt++];
+            tl.row0 = (int32_t)t0;
+            tl.nrows = (int32_t)(r - t0 < 32 ? r - t0 : 32);
+            tl.kv_max = 0;
+            for (int q = 0; q < tl.nrows; ++q) tl.kv_max = s_kvl[t0 + q] > tl.kv_max ? s_kvl[t0 + q] : tl.kv_max;
+            tl.kv_off = s_off[t0];
         }
         tok_off += L;
     }
@@ -469,8 +477,8 @@ int upload_rows(sd_handle* h, int mode, int batch, const int32_t* tokens, const 
     }
     char* db = h->buf.maps[mode];
     ms.tokens = (int32_t*)(db + o_tok); ms.src = (int32_t*)(db + o_src); ms.pos = (int32_t*)(db + o_pos);
-    ms.seq = (int32_t*)(db + o_seq); ms.kvl = (int32_t*)(db + o_kvl); ms.t0 = (int32_t*)(db + o_t0);
-    ms.tn = (int32_t*)(db + o_tn); ms.blk = (int32_t*)(db + o_blk); ms.kv_off = (int64_t*)(db + o_off);
+    ms.seq = (int32_t*)(db + o_seq); ms.kvl = (int32_t*)(db + o_kvl);
+    ms.blk = (int32_t*)(db + o_blk); ms.kv_off = (int64_t*)(db + o_off); ms.tiles = (AttnTile*)(db + o_tiles);
     ms.rows = (int)rows; ms.n_tiles = (int)n_tiles; ms.max_kv = max_kv; ms.kv_sum = kv_sum; ms.kv_rows = kv_rows;
     ms.bytes = bytes;
     return SD_OK;
@@ -578,7 +586,7 @@ int run_layers(sd_handle* h, const Model& m, const MapSet& rm, const float* temb
         a.kv_off = rm.kv_off; a.kv_len = rm.kvl;
         a.out = B.att; a.out_ld = d;
         a.rows = rows; a.n_head = c.n_head; a.n_kv_head = c.n_kv_head; a.d_head = m.dh; a.max_kv = rm.max_kv;
-        a.tile_row0 = rm.t0; a.tile_rows = rm.tn; a.n_tiles = rm.n_tiles;
+        a.tiles = rm.tiles; a.n_tiles = rm.n_tiles;
         if (cached) {
             const int64_t per_layer = (int64_t)h->max_batch * c.n_ctx * m.dkv * m.ew;
             char* kc = static_cast<char*>(B.kcache) + i * per_layer;

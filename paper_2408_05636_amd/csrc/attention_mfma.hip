@@ -25,29 +25,39 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
 
 constexpr int kVtLd = 40;    // LDS row stride of the transposed V tile (32 keys + 8 pad), in elements
 
+typedef __attribute__((__vector_size__(4 * sizeof(unsigned int)))) unsigned int u32x4;
+typedef __attribute__((__vector_size__(2 * sizeof(unsigned int)))) unsigned int u32x2;
+constexpr int kBufFlags = 0x00020000;          // raw buffer, 32-bit data format
+constexpr uint32_t kOutOfRange = 0x80000000u;  // VGPR offset of accesses that must not happen (buffers are < 2 GiB)
+
 template <int DH, bool KSPLIT>
 __global__ __launch_bounds__(256) void k_attention_mfma(AttnArgs a) {
     constexpr int NCH = DH / 64;     // 64-wide chunks of a q / k row
     constexpr int DT = DH / 32;      // 32-row tiles of O^T
+    constexpr int NV = DH / 16;      // 16-byte pieces of a V row handled per lane
     __shared__ __attribute__((aligned(16))) bf16_t vt_all[4][DH * kVtLd];
     __shared__ float mrg_m[KSPLIT ? 3 : 1][64], mrg_l[KSPLIT ? 3 : 1][64];
     __shared__ float mrg_o[KSPLIT ? 3 : 1][KSPLIT ? DT * 16 : 1][64];
 
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    // wave-uniform values are kept in scalar registers (tile description, buffer descriptors, block counters)
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int r = lane & 31, half = lane >> 5;
     const int tile = KSPLIT ? (int)blockIdx.x : (int)blockIdx.x * 4 + wave;
     const int head = blockIdx.y;
     if (!KSPLIT && tile >= a.n_tiles) return;           // whole wave; this variant has no barriers
 
-    const int row0 = a.tile_row0[tile], nrows = a.tile_rows[tile];
+    // One scalar load brings everything that is uniform over the tile; the per-row key counts, the query
+    // rows and the first key / value block are then requested together (two dependent round trips in all).
+    const AttnTile tl = a.tiles[tile];
+    const int row0 = tl.row0, nrows = tl.nrows, kv_max = tl.kv_max;
     const int qrow = row0 + min(r, nrows - 1);
-    const int kvl = a.kv_len[qrow];
-    int kv_max = kvl;
-#pragma unroll
-    for (int o = 16; o > 0; o >>= 1) kv_max = max(kv_max, __shfl_xor(kv_max, o, 64));
     const int g = head / (a.n_head / a.n_kv_head);
-    const bf16_t* Kp = static_cast<const bf16_t*>(a.k) + a.kv_off[row0] + (size_t)g * DH;
-    const bf16_t* Vp = static_cast<const bf16_t*>(a.v) + a.kv_off[row0] + (size_t)g * DH;
+    const uint32_t kv_bytes = ((uint32_t)(kv_max - 1) * (uint32_t)a.kv_ld + DH) * 2u;    // keys 0..kv_max-1 of this kv head
+    bf16_t* kbase = const_cast<bf16_t*>(static_cast<const bf16_t*>(a.k)) + tl.kv_off + (size_t)g * DH;
+    bf16_t* vbase = const_cast<bf16_t*>(static_cast<const bf16_t*>(a.v)) + tl.kv_off + (size_t)g * DH;
+    const __amdgpu_buffer_rsrc_t rk = __builtin_amdgcn_make_buffer_rsrc(kbase, 0, kv_bytes, kBufFlags);
+    const __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc(vbase, 0, kv_bytes, kBufFlags);
+    const int kvl = a.kv_len[qrow];
     const bf16_t* Qp = static_cast<const bf16_t*>(a.q) + (size_t)qrow * a.q_ld + (size_t)head * DH + 32 * half;
     bf16_t* vt = vt_all[wave];
 
@@ -55,13 +65,16 @@ __global__ __launch_bounds__(256) void k_attention_mfma(AttnArgs a) {
 #pragma unroll
     for (int c = 0; c < NCH; ++c)
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            const uint4 t = reinterpret_cast<const uint4*>(Qp + c * 64)[s];
-            qf[c][s] = *reinterpret_cast<const bf16x8*>(&t);
-        }
+        for (int s = 0; s < 4; ++s) qf[c][s] = __builtin_bit_cast(bf16x8, reinterpret_cast<const u32x4*>(Qp + c * 64)[s]);
 
     // MFMA row rho of the S^T tile carries key pi(rho) of the block: rho = 8g' + 4h' + i -> 16h' + 4g' + i
     const int pi_r = 16 * ((r >> 2) & 1) + 4 * (r >> 3) + (r & 3);
+    // Byte offsets inside the key / value buffers of this lane's row of block 0.  Rows beyond kv_max fall
+    // outside the buffer and read as 0 (they are masked below), so the last block needs no special case and
+    // the block after the last can be prefetched unconditionally.
+    const uint32_t k_lane = ((uint32_t)pi_r * (uint32_t)a.kv_ld + 32u * half) * 2u;
+    const uint32_t v_lane = ((uint32_t)r * (uint32_t)a.kv_ld + 8u * half) * 2u;
+    const uint32_t blk_bytes = 32u * (uint32_t)a.kv_ld * 2u;
 
     float m_run = -INFINITY, l_run = 0.f;
     floatx16 o[DT];
@@ -72,30 +85,35 @@ __global__ __launch_bounds__(256) void k_attention_mfma(AttnArgs a) {
     const float scale = rsqrtf((float)DH) * 1.4426950408889634f;     // scores in log2 units
 
     const int n_blocks = (kv_max + 31) / 32;
-    for (int kb = KSPLIT ? wave : 0; kb < n_blocks; kb += KSPLIT ? 4 : 1) {
+    constexpr int kStep = KSPLIT ? 4 : 1;
+    u32x4 kc[NCH][4], vc[NV], kn[NCH][4], vn[NV];
+#define SD_LOAD_BLOCK(KR, VR, KB)                                                                        \
+    {                                                                                                    \
+        const uint32_t ko_ = k_lane + (uint32_t)(KB) * blk_bytes, vo_ = v_lane + (uint32_t)(KB) * blk_bytes; \
+        _Pragma("unroll") for (int c = 0; c < NCH; ++c) _Pragma("unroll") for (int q4 = 0; q4 < 4; ++q4) \
+            KR[c][q4] = __builtin_amdgcn_raw_buffer_load_b128(rk, ko_ + (uint32_t)(c * 128 + q4 * 16), 0, 0); \
+        _Pragma("unroll") for (int i = 0; i < NV; ++i)                                                   \
+            VR[i] = __builtin_amdgcn_raw_buffer_load_b128(rv, vo_ + (uint32_t)(i * 32), 0, 0);            \
+    }
+    int kb = KSPLIT ? wave : 0;
+    SD_LOAD_BLOCK(kc, vc, kb)
+    for (; kb < n_blocks; kb += kStep) {
+        SD_LOAD_BLOCK(kn, vn, kb + kStep)                               // prefetch; beyond the end it reads nothing
         // ---- S^T = K Q^T
-        const int krow = min(kb * 32 + pi_r, kv_max - 1);             // clamped: masked below
-        const bf16_t* kr = Kp + (size_t)krow * a.kv_ld + 32 * half;
         floatx16 s;
 #pragma unroll
         for (int e = 0; e < 16; ++e) s[e] = 0.f;
 #pragma unroll
         for (int c = 0; c < NCH; ++c)
 #pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4) {
-                const uint4 t = reinterpret_cast<const uint4*>(kr + c * 64)[q4];
-                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(&t), qf[c][q4], s, 0, 0, 0);
-            }
-        // ---- stage V^T of this key block in the wave's LDS tile
-        const int vrow = min(kb * 32 + r, kv_max - 1);
-        const bf16_t* vr = Vp + (size_t)vrow * a.kv_ld;
+            for (int q4 = 0; q4 < 4; ++q4)
+                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kc[c][q4]), qf[c][q4], s, 0, 0, 0);
+        // ---- stage V^T of this key block in the wave's LDS tile (piece i of this lane: key r, d = 8 (half + 2i) ..)
 #pragma unroll
-        for (int i = 0; i < DH / 16; ++i) {
-            const int dg = half + 2 * i;
-            const uint4 t = *reinterpret_cast<const uint4*>(vr + 8 * dg);
-            const bf16_t* tv = reinterpret_cast<const bf16_t*>(&t);
+        for (int i = 0; i < NV; ++i) {
+            const bf16x8 tv = __builtin_bit_cast(bf16x8, vc[i]);
 #pragma unroll
-            for (int u = 0; u < 8; ++u) vt[(8 * dg + u) * kVtLd + r] = tv[u];
+            for (int u = 0; u < 8; ++u) vt[(8 * (half + 2 * i) + u) * kVtLd + r] = tv[u];
         }
         // ---- online softmax; accumulator e of this lane is key kb*32 + 16*half + e
         float mb = -INFINITY;
@@ -130,7 +148,14 @@ __global__ __launch_bounds__(256) void k_attention_mfma(AttnArgs a) {
                 const bf16x8 vf = *reinterpret_cast<const bf16x8*>(vt + (t * 32 + r) * kVtLd + 16 * half + 8 * s2);
                 o[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[s2], o[t], 0, 0, 0);
             }
+#pragma unroll
+        for (int c = 0; c < NCH; ++c)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) kc[c][q4] = kn[c][q4];
+#pragma unroll
+        for (int i = 0; i < NV; ++i) vc[i] = vn[i];
     }
+#undef SD_LOAD_BLOCK
 
     if constexpr (KSPLIT) {            // merge the four key ranges in a fixed order
         if (wave > 0) {
@@ -165,24 +190,26 @@ __global__ __launch_bounds__(256) void k_attention_mfma(AttnArgs a) {
     }
 
     const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
-    if (r >= nrows) return;
     const float inv = 1.f / l_tot;
-    bf16_t* op = static_cast<bf16_t*>(a.out) + (size_t)qrow * a.out_ld + (size_t)head * DH;
+    // Output row qrow, columns head*DH + d: accumulators 4*e4 .. 4*e4+3 are 4 consecutive d.  Lanes of rows
+    // beyond the tile carry the out-of-range offset and their stores are dropped.
+    const __amdgpu_buffer_rsrc_t ro = __builtin_amdgcn_make_buffer_rsrc(a.out, 0, (uint32_t)a.rows * (uint32_t)a.out_ld * 2u, kBufFlags);
+    const uint32_t o_lane = r < nrows ? ((uint32_t)qrow * (uint32_t)a.out_ld + (uint32_t)head * DH + 4u * half) * 2u : kOutOfRange;
 #pragma unroll
     for (int t = 0; t < DT; ++t)
 #pragma unroll
-        for (int e4 = 0; e4 < 4; ++e4) {       // accumulators 4*e4 .. 4*e4+3 are 4 consecutive d
-            const int d0 = t * 32 + 8 * e4 + 4 * half;
-            union { bf16_t h[4]; uint2 u; } pk;
+        for (int e4 = 0; e4 < 4; ++e4) {
+            union { bf16_t h[4]; u32x2 u; } pk;
 #pragma unroll
             for (int i = 0; i < 4; ++i) pk.h[i] = static_cast<bf16_t>(o[t][4 * e4 + i] * inv);
-            *reinterpret_cast<uint2*>(op + d0) = pk.u;
+            __builtin_amdgcn_raw_buffer_store_b64(pk.u, ro, o_lane + (uint32_t)(t * 32 + 8 * e4) * 2u, 0, 0);
         }
 }
 
 bool attention_mfma_supported(int dtype, const AttnArgs& a) {
-    return dtype == SD_DTYPE_BF16 && (a.d_head == 64 || a.d_head == 128) && a.tile_row0 != nullptr && a.n_tiles > 0 &&
-           a.q_ld % 8 == 0 && a.kv_ld % 8 == 0 && a.out_ld % 4 == 0;
+    return dtype == SD_DTYPE_BF16 && (a.d_head == 64 || a.d_head == 128) && a.tiles != nullptr && a.n_tiles > 0 &&
+           a.q_ld % 8 == 0 && a.kv_ld % 8 == 0 && a.out_ld % 4 == 0 && (int64_t)a.max_kv * a.kv_ld * 2 < ((int64_t)1 << 31) &&
+           (int64_t)a.rows * a.out_ld * 2 < ((int64_t)1 << 31);
 }
 
 hipError_t launch_attention_mfma(const AttnArgs& a, hipStream_t st, const char** kernel_name) {

@@ -53,6 +53,7 @@ hipError_t launch_kv_store(int dtype, const void* qkv, const int32_t* seq, const
 
 // out[r, h*dh:(h+1)*dh] = softmax(q_r k^T / sqrt(dh)) v over keys 0..kv_len[r]-1 of r's sequence.
 // Keys/values of sequence s start at kbase + kv_off[r] elements with row stride kv_ld.
+struct AttnTile;
 struct AttnArgs {
     const void* q; int q_ld;                 // query rows, head h at column h*dh
     const void* k; const void* v; int kv_ld; // key / value rows, kv head g at column g*dh
@@ -61,11 +62,15 @@ struct AttnArgs {
     void* out; int out_ld;
     int rows, n_head, n_kv_head, d_head;
     int max_kv;                              // upper bound of kv_len over the rows
-    // Query tiles for the matrix-core kernel: tile t = rows tile_row0[t] .. +tile_rows[t]-1 (<= 32 rows,
-    // all of one sequence).  NULL / 0 when not provided.
-    const int32_t* tile_row0 = nullptr;
-    const int32_t* tile_rows = nullptr;
+    // Query tiles for the matrix-core kernel (NULL / 0 when not provided).
+    const struct AttnTile* tiles = nullptr;
     int n_tiles = 0;
+};
+// Rows row0 .. row0 + nrows - 1 (<= 32, all of one sequence); kv_max = largest kv_len among them;
+// kv_off = element offset of the sequence's key row 0 (the kv_off of its rows).
+struct AttnTile {
+    int32_t row0, nrows, kv_max, pad;
+    int64_t kv_off, pad2;
 };
 bool attention_mfma_supported(int dtype, const AttnArgs& a);
 hipError_t launch_attention_mfma(const AttnArgs& a, hipStream_t st, const char** kernel_name);
