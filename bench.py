@@ -35,6 +35,22 @@ def prefixes_for(w, seed):
     return [synth.gen_prefix(V, int(L), seed + 1 + i) for i, L in enumerate(lens)]
 
 
+def log(msg):
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
+def gen_weights_logged(synth, cfg, seed, what):
+    """synth.gen_weights with a progress line every few seconds (large models take minutes)."""
+    out, last = {}, time.perf_counter()
+    specs = synth.weight_specs(cfg)
+    for i, (name, shape, role) in enumerate(specs):
+        out[name] = synth.gen_tensor(cfg, seed, i, shape, role)
+        if time.perf_counter() - last > 10.0:
+            last = time.perf_counter()
+            log(f"{what} weights: tensor {i + 1}/{len(specs)}")
+    return out
+
+
 def cpu_baseline(w, Wt, Wd, prefixes, seed):
     """The oracle as it stands, one round of sequence 0 of the same workload."""
     from threadpoolctl import threadpool_info
@@ -79,11 +95,15 @@ def main():
     if a.T:
         w["T"] = a.T
     t, d, gamma, T, B = w["target"], w["drafter"], w["gamma"], w["T"], w["batch"]
-    Wt, Wd = synth.gen_weights(t, 1), synth.gen_weights(d, 2)
+    Wt, Wd = gen_weights_logged(synth, t, 1, "target"), gen_weights_logged(synth, d, 2, "drafter")
+    log("weights generated; uploading")
     sd = binding.SpecDiff(t, d, Wt, Wd, max_batch=B, gamma_max=gamma)
+    if a.no_cpu_baseline:
+        Wt = Wd = None                            # the host copies only serve the oracle
     prefixes = prefixes_for(w, 3)
     flat, lens = binding._ragged(prefixes)
     sd.sd_prefill(prefixes)                       # prompt processing: outside the round
+    log("prefill done; timing")
 
     for i in range(a.warmup):
         sd.sd_round_flat(flat, lens, gamma, T, 100 + i)
@@ -104,6 +124,7 @@ def main():
         torch.neg(src, out=dst)                                              # one elementwise kernel ("neg")
         torch.cuda.synchronize()
 
+    log(f"timed pass done: {ms_per_step:.3f} ms per round")
     roof = None
     phases = None
     if not a.no_profile:

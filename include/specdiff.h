@@ -158,23 +158,36 @@ int32_t sd_accept_resample(const float *p_logits, const float *q, const int32_t 
 /* y = epilogue(x W^T + bias): the dense contraction used by every QKV / MLP / LM-head layer.
  * x: [m, k] (dtype), w: [n, k] (dtype), bias: fp32 [n] or NULL.
  * epilogue 0: y (dtype) = acc; 1: y (dtype) = gelu_tanh(acc); 2: y (fp32) += acc (residual);
- * 3: y (fp32) = acc.  ldy in elements of y. */
+ * 3: y (fp32) = acc.  ldy in elements of y.
+ * split_workspace: device, 256-byte aligned, or NULL.  With few rows (the target's gamma + 1 query
+ * rows) the K range of an output tile is divided over several workgroups, which needs memory for their
+ * partial sums: the first sd_linear_split_ticket_bytes() bytes are counters that must be zero before
+ * the first call (every call leaves them zero), the rest holds partial tiles; a larger workspace allows
+ * a finer split, NULL none.  Calls that share a workspace must not overlap.  Results are deterministic
+ * (partials are added in a fixed order). */
+int64_t sd_linear_split_ticket_bytes(void);
 int32_t sd_linear(int32_t dtype, const void *x, const void *w, const float *bias, void *y,
-                  int32_t m, int32_t n, int32_t k, int32_t ldy, int32_t epilogue, void *hip_stream);
+                  int32_t m, int32_t n, int32_t k, int32_t ldy, int32_t epilogue,
+                  void *split_workspace, int64_t split_workspace_bytes, void *hip_stream);
 
 /* y = epilogue(W norm(h) + bias): the normalisation in front of the QKV and MLP-up contractions folded
  * into them (bf16 weights only).  norm_kind 1: LayerNorm(h; gain, beta, eps), 2: RMSNorm(h; gain, eps).
  * h: fp32 [m, k] (the residual stream), w: bf16 [n, k], gain / beta: fp32 [k], bias: fp32 [n] or NULL,
  * epilogue 0, 1 or 3 as in sd_linear.  fold_scratch: device, 2*n floats (receives W gain and
- * W beta + bias, which a model computes once per layer).  All pointers device; asynchronous. */
+ * W beta + bias, which a model computes once per layer).  split_workspace as in sd_linear.
+ * All pointers device; asynchronous. */
 int32_t sd_norm_linear(int32_t norm_kind, const float *h, const void *w, const float *gain, const float *beta,
                        const float *bias, void *y, int32_t m, int32_t n, int32_t k, int32_t ldy, int32_t epilogue,
-                       float eps, float *fold_scratch, void *hip_stream);
+                       float eps, float *fold_scratch, void *split_workspace, int64_t split_workspace_bytes,
+                       void *hip_stream);
 
 /* Tuning hook for sd_linear and every contraction inside the forwards: force tile variant
- * `variant` of the matrix-core kernel (0..5, see the kernel source), -1 = choose by shape (default).
+ * `variant` of the matrix-core kernel (0..6, see the kernel source), -1 = choose by shape (default).
  * Process-wide; results do not depend on the variant beyond fp32 summation order. */
 int32_t sd_set_linear_variant(int32_t variant);
+/* Same for the number of workgroups that share the K range of one output tile (clamped to what the
+ * shape and the workspace allow); <= 0 = choose by shape (default). */
+int32_t sd_set_linear_split(int32_t split);
 
 /* The launch sequences of sd_draft / sd_verify / sd_round are captured into HIP graphs on first
  * use (one per combination of batch, gamma, T and sequence lengths) and replayed afterwards; the

@@ -23,7 +23,8 @@ STATUS_NAMES = {0: "SD_OK", 1: "SD_ERR_ARG", 2: "SD_ERR_SHAPE", 3: "SD_ERR_TOKEN
 EXPORTS = ["sd_vocab_pad", "sd_weight_count", "sd_weight_desc", "sd_weight_bytes", "sd_workspace_bytes", "sd_create",
            "sd_destroy", "sd_last_error", "sd_prefill", "sd_draft", "sd_verify", "sd_round", "sd_drafter_logits",
            "sd_target_logits", "sd_sampling_scratch_bytes", "sd_unmask_sample", "sd_accept_resample", "sd_linear",
-           "sd_profile_begin", "sd_profile_end", "sd_profile_count", "sd_profile_entry", "sd_set_graph_replay", "sd_set_linear_variant", "sd_norm_linear"]
+           "sd_profile_begin", "sd_profile_end", "sd_profile_count", "sd_profile_entry", "sd_set_graph_replay", "sd_set_linear_variant", "sd_norm_linear",
+           "sd_set_linear_split", "sd_linear_split_ticket_bytes"]
 
 
 class SdModelConfig(C.Structure):
@@ -75,11 +76,13 @@ def lib() -> C.CDLL:
         L.sd_accept_resample.restype = i32
         L.sd_accept_resample.argtypes = [vp, vp, vp, i32, i32, i32, u64, vp, vp, vp, i64, vp]
         L.sd_linear.restype = i32
-        L.sd_linear.argtypes = [i32, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp]
+        L.sd_linear.argtypes = [i32, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, i64, vp]
+        L.sd_set_linear_split.restype = i32; L.sd_set_linear_split.argtypes = [i32]
+        L.sd_linear_split_ticket_bytes.restype = i64; L.sd_linear_split_ticket_bytes.argtypes = []
         L.sd_set_graph_replay.restype = i32; L.sd_set_graph_replay.argtypes = [vp, i32]
         L.sd_set_linear_variant.restype = i32; L.sd_set_linear_variant.argtypes = [i32]
         L.sd_norm_linear.restype = i32
-        L.sd_norm_linear.argtypes = [i32, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, C.c_float, vp, vp]
+        L.sd_norm_linear.argtypes = [i32, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, C.c_float, vp, vp, i64, vp]
         L.sd_profile_begin.restype = i32; L.sd_profile_begin.argtypes = [vp]
         L.sd_profile_end.restype = i32; L.sd_profile_end.argtypes = [vp]
         L.sd_profile_count.restype = i32; L.sd_profile_count.argtypes = [vp]
@@ -308,27 +311,42 @@ def sd_accept_resample(p_logits, q, draft, batch: int, gamma: int, vocab: int, s
     return n, tok
 
 
-def sd_linear(dtype: str, x, w, bias, y, epilogue: int):
+_split_ws = {}
+
+
+def split_workspace(device, part_bytes: int = 16 << 20):
+    """Zero-filled device workspace for the contractions that split K over workgroups (one per device)."""
+    import torch
+    key = str(device)
+    if key not in _split_ws:
+        _split_ws[key] = torch.zeros(int(lib().sd_linear_split_ticket_bytes()) + part_bytes, dtype=torch.uint8, device=device)
+    return _split_ws[key]
+
+
+def sd_linear(dtype: str, x, w, bias, y, epilogue: int, split: bool = True):
     """y = epilogue(x w^T + bias) on device tensors; see specdiff.h."""
     import torch
     m, k = x.shape
     n = w.shape[0]
+    ws = split_workspace(x.device) if split else None
     rc = lib().sd_linear({"f32": 0, "bf16": 1}[dtype], x.data_ptr(), w.data_ptr(), bias.data_ptr() if bias is not None else None,
-                         y.data_ptr(), m, n, k, y.stride(0), epilogue, _stream_ptr(x))
+                         y.data_ptr(), m, n, k, y.stride(0), epilogue, ws.data_ptr() if split else None,
+                         ws.numel() if split else 0, _stream_ptr(x))
     if rc:
         raise SdError(rc, "sd_linear")
     torch.cuda.synchronize(x.device)
 
 
-def sd_norm_linear(norm_kind: int, h, w, gain, beta, bias, y, epilogue: int, eps: float):
+def sd_norm_linear(norm_kind: int, h, w, gain, beta, bias, y, epilogue: int, eps: float, split: bool = True):
     """y = epilogue(w norm(h) + bias) with the norm folded into the contraction; device tensors."""
     import torch
     m, k = h.shape
     n = w.shape[0]
     scratch = torch.empty(2 * n, dtype=torch.float32, device=h.device)
+    ws = split_workspace(h.device) if split else None
     rc = lib().sd_norm_linear(norm_kind, h.data_ptr(), w.data_ptr(), gain.data_ptr(), beta.data_ptr() if beta is not None else None,
                               bias.data_ptr() if bias is not None else None, y.data_ptr(), m, n, k, y.stride(0), epilogue, eps,
-                              scratch.data_ptr(), _stream_ptr(h))
+                              scratch.data_ptr(), ws.data_ptr() if split else None, ws.numel() if split else 0, _stream_ptr(h))
     if rc:
         raise SdError(rc, "sd_norm_linear")
     torch.cuda.synchronize(h.device)

@@ -171,6 +171,7 @@ struct Buffers {
     uint64_t* seed;          // Philox key of the current call
     void* sample_scratch;
     float *fold_t, *fold_d;  // folded-norm vectors of the target / drafter layers
+    SplitWorkspace split;    // tickets + partial sums of the contractions that split K over workgroups
     void *kcache, *vcache;
 };
 
@@ -193,6 +194,8 @@ Limits limits_of(const sd_model_config& t, const sd_model_config& d, int max_bat
 }
 
 // floats needed for the folded LayerNorm vectors of a model (u and v for QKV and MLP-up of every layer)
+constexpr int64_t kSplitBytes = kSplitTicketBytes + (16 << 20);
+
 int64_t fold_floats(const sd_model_config& c) {
     if (c.arch != SD_ARCH_GPT2 || c.dtype != SD_DTYPE_BF16) return 64;
     const int64_t qkv = (int64_t)c.d_model + 2 * (int64_t)c.n_kv_head * (c.d_model / c.n_head);
@@ -222,6 +225,8 @@ int64_t carve(Arena& a, Buffers& b, const sd_model_config& t, const sd_model_con
     b.seed = a.take<uint64_t>(32);
     b.sample_scratch = a.take<char>(sampling_scratch_bytes((int)l.rows_head, t.vocab));
     b.fold_t = a.take<float>(fold_floats(t));
+    b.split.bytes = kSplitBytes;
+    b.split.base = a.take<char>(kSplitBytes);
     b.fold_d = a.take<float>(fold_floats(d));
     const int64_t cache = (int64_t)t.n_layer * max_batch * t.n_ctx * t.n_kv_head * (t.d_model / t.n_head);
     b.kcache = a.take<char>(cache, t.dtype == SD_DTYPE_BF16 ? 2 : 4);
@@ -542,7 +547,7 @@ int run_linear(sd_handle* h, int dt, const void* x, const void* w, const float* 
     const double out_b = epi == EPI_RESID ? 8.0 : (epi == EPI_F32 ? 4.0 : ew);
     const double bytes = ((double)m * k + (double)n * k) * ew + (double)m * n * out_b;
     const char* name = "linear";
-    SD_LAUNCH(h, name, bytes, 2.0 * m * n * k, launch_linear(dt, x, w, bias, y, m, n, k, ldy, epi, h->st, &name));
+    SD_LAUNCH(h, name, bytes, 2.0 * m * n * k, launch_linear(dt, x, w, bias, y, m, n, k, ldy, epi, h->buf.split, h->st, &name));
     return SD_OK;
 }
 
@@ -559,7 +564,7 @@ int run_norm_linear(sd_handle* h, const Model& m, const float* gain, const float
         const bool ln = c.arch == SD_ARCH_GPT2;
         SD_LAUNCH(h, name, bytes, 2.0 * rows * n * d,
                   launch_linear_normfold(B.h, w, gain, ln ? fold_u : nullptr, ln ? fold_v : bias, y, rows, n, d, ldy, epi,
-                                         ln ? 1 : 2, c.norm_eps, h->st, &name));
+                                         ln ? 1 : 2, c.norm_eps, h->buf.split, h->st, &name));
         return SD_OK;
     }
     SD_LAUNCH(h, "k_norm", (double)rows * d * (4 + m.ew), 0, launch_norm(c.dtype, B.h, nullptr, gain, beta, B.xn, rows, d, c.norm_eps, h->st));
@@ -788,6 +793,11 @@ int32_t sd_create(const sd_model_config* target, const sd_model_config* drafter,
     const int64_t need = carve(a, h->buf, *target, *drafter, max_batch, gamma_max);
     if (need > workspace_bytes) { delete h; return SD_ERR_WORKSPACE; }
     if (!bind_model(h->target, *target, target_w) || !bind_model(h->drafter, *drafter, drafter_w)) { delete h; return SD_ERR_ARG; }
+    if (hipMemsetAsync(h->buf.split.base, 0, kSplitTicketBytes, static_cast<hipStream_t>(hip_stream)) != hipSuccess) {
+        g_create_error = "clearing the split-K tickets failed";
+        delete h;
+        return SD_ERR_HIP;
+    }
     // Fold the LayerNorms in front of QKV and MLP-up into those contractions (bf16 models): u = W g, v = W beta + bias.
     for (int which = 0; which < 2; ++which) {
         Model& m = which ? h->drafter : h->target;
@@ -1074,8 +1084,12 @@ int32_t sd_accept_resample(const float* p_logits, const float* q, const int32_t*
 
 int32_t sd_norm_linear(int32_t norm_kind, const float* h, const void* w, const float* gain, const float* beta,
                        const float* bias, void* y, int32_t m, int32_t n, int32_t k, int32_t ldy, int32_t epilogue,
-                       float eps, float* fold_scratch, void* hip_stream) {
+                       float eps, float* fold_scratch, void* split_workspace, int64_t split_workspace_bytes,
+                       void* hip_stream) {
     if (!h || !w || !gain || !y || !fold_scratch) return SD_ERR_ARG;
+    if (split_workspace && ((reinterpret_cast<uintptr_t>(split_workspace) & 255) || split_workspace_bytes <= kSplitTicketBytes))
+        return SD_ERR_WORKSPACE;
+    const SplitWorkspace ws{split_workspace, split_workspace ? split_workspace_bytes : 0};
     if (norm_kind != 1 && norm_kind != 2) return SD_ERR_ARG;
     if (m <= 0 || n <= 0 || k <= 0 || ldy < n || epilogue < 0 || epilogue > 3 || epilogue == EPI_RESID) return SD_ERR_SHAPE;
     if (!linear_normfold_supported(SD_DTYPE_BF16, m, n, k, ldy)) return SD_ERR_SHAPE;
@@ -1083,7 +1097,7 @@ int32_t sd_norm_linear(int32_t norm_kind, const float* h, const void* w, const f
     float* u = fold_scratch;
     float* v = fold_scratch + n;
     if (launch_fold_norm(w, gain, norm_kind == 1 ? beta : nullptr, bias, u, v, n, k, st) != hipSuccess) return SD_ERR_HIP;
-    return launch_linear_normfold(h, w, gain, u, v, y, m, n, k, ldy, epilogue, norm_kind, eps, st, nullptr) == hipSuccess ? SD_OK : SD_ERR_HIP;
+    return launch_linear_normfold(h, w, gain, u, v, y, m, n, k, ldy, epilogue, norm_kind, eps, ws, st, nullptr) == hipSuccess ? SD_OK : SD_ERR_HIP;
 }
 
 int32_t sd_set_linear_variant(int32_t variant) {
@@ -1091,12 +1105,23 @@ int32_t sd_set_linear_variant(int32_t variant) {
     return SD_OK;
 }
 
+int32_t sd_set_linear_split(int32_t split) {
+    linear_mfma_set_split(split);
+    return SD_OK;
+}
+
+int64_t sd_linear_split_ticket_bytes(void) { return kSplitTicketBytes; }
+
 int32_t sd_linear(int32_t dtype, const void* x, const void* w, const float* bias, void* y, int32_t m, int32_t n,
-                  int32_t k, int32_t ldy, int32_t epilogue, void* hip_stream) {
+                  int32_t k, int32_t ldy, int32_t epilogue, void* split_workspace, int64_t split_workspace_bytes,
+                  void* hip_stream) {
     if (!x || !w || !y) return SD_ERR_ARG;
+    if (split_workspace && ((reinterpret_cast<uintptr_t>(split_workspace) & 255) || split_workspace_bytes <= kSplitTicketBytes))
+        return SD_ERR_WORKSPACE;
+    const SplitWorkspace ws{split_workspace, split_workspace ? split_workspace_bytes : 0};
     if (dtype != SD_DTYPE_F32 && dtype != SD_DTYPE_BF16) return SD_ERR_ARG;
     if (m <= 0 || n <= 0 || k <= 0 || ldy < n || epilogue < 0 || epilogue > 3 || k % 8) return SD_ERR_SHAPE;
-    return launch_linear(dtype, x, w, bias, y, m, n, k, ldy, epilogue, static_cast<hipStream_t>(hip_stream), nullptr) == hipSuccess ? SD_OK : SD_ERR_HIP;
+    return launch_linear(dtype, x, w, bias, y, m, n, k, ldy, epilogue, ws, static_cast<hipStream_t>(hip_stream), nullptr) == hipSuccess ? SD_OK : SD_ERR_HIP;
 }
 
 }  // extern "C"

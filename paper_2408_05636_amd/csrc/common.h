@@ -26,8 +26,10 @@ enum Epilogue { EPI_STORE = 0, EPI_GELU = 1, EPI_RESID = 2, EPI_F32 = 3 };
 
 // y = epilogue(x W^T + bias); see sd_linear in specdiff.h.
 // *kernel_name (optional) receives the name of the kernel variant that was launched.
+struct SplitWorkspace;
 hipError_t launch_linear(int dtype, const void* x, const void* w, const float* bias, void* y, int m, int n,
-                         int k, int ldy, int epilogue, hipStream_t st, const char** kernel_name);
+                         int k, int ldy, int epilogue, const SplitWorkspace& ws, hipStream_t st,
+                         const char** kernel_name);
 
 // h[r, :] = wte[token(r)] + wpe[pos[r]] + temb, fp32 residual stream.  token(r) = src[r] >= 0 ?
 // prefix[src[r]] : block[-src[r] - 1].  wpe, temb may be NULL.
@@ -79,17 +81,26 @@ hipError_t launch_attention_generic(int dtype, const AttnArgs& a, int max_kv, hi
 hipError_t launch_linear_generic(int dtype, const void* x, const void* w, const float* bias, void* y, int m, int n,
                                  int k, int ldy, int epilogue, hipStream_t st);
 
+// Device workspace of the contractions that split K over workgroups: kSplitTicketBytes of counters
+// (zero between launches) followed by the partial-sum records.  base == nullptr: no such split.
+constexpr int64_t kSplitTicketBytes = 16384;
+struct SplitWorkspace {
+    void* base = nullptr;
+    int64_t bytes = 0;
+};
 bool linear_mfma_supported(int dtype, int m, int n, int k, int ldy);
-void linear_mfma_set_variant(int v);
+void linear_mfma_set_variant(int v);     // tuning hook: force a tile variant (-1 = choose by shape)
+void linear_mfma_set_split(int s);       // tuning hook: force the K split over workgroups (<= 0 = choose by shape)
 // Contraction with the preceding LayerNorm (norm_kind 1) / RMSNorm (2) folded in: h is the fp32 residual stream.
 bool linear_normfold_supported(int dtype, int m, int n, int k, int ldy);
 hipError_t launch_linear_normfold(const float* h, const void* w, const float* gain, const float* fold_u,
                                   const float* fold_v, void* y, int m, int n, int k, int ldy, int epilogue,
-                                  int norm_kind, float eps, hipStream_t st, const char** kernel_name);
+                                  int norm_kind, float eps, const SplitWorkspace& ws, hipStream_t st,
+                                  const char** kernel_name);
 hipError_t launch_fold_norm(const void* w, const float* gain, const float* beta, const float* bias, float* u, float* v,
-                            int n, int k, hipStream_t st);   // tuning hook: force a tile variant (-1 = choose by shape)
+                            int n, int k, hipStream_t st);
 hipError_t launch_linear_mfma(const void* x, const void* w, const float* bias, void* y, int m, int n, int k, int ldy,
-                              int epilogue, hipStream_t st, const char** kernel_name);
+                              int epilogue, const SplitWorkspace& ws, hipStream_t st, const char** kernel_name);
 
 // act[r, c] = silu(gu[r, c]) * gu[r, F + c]
 hipError_t launch_swiglu(int dtype, const void* gu, void* act, int rows, int F, hipStream_t st);

@@ -11,7 +11,14 @@
 // freely; bank conflicts are avoided by storing 16-byte piece c of row r at piece c ^ (r & 7).
 //
 // A workgroup is WM x WN x KS waves (KS = waves that split the K range of one tile and reduce
-// through LDS in a fixed order: deterministic results, no atomics).
+// through LDS in a fixed order: deterministic results).
+//
+// Few-row contractions (the target's gamma + 1 query rows) have too few output tiles to pull the
+// weights at HBM speed, so the K range can also be split over gridDim.y workgroups: each writes its
+// fp32 partial tile to a workspace and takes a ticket; whichever workgroup draws the last ticket adds
+// the partials in split order 0, 1, ... (its own included, read back from memory, so the result does
+// not depend on which one was last) and runs the epilogue.  Nobody waits for anybody.
+#include <algorithm>
 #include <string>
 
 #include "common.h"
@@ -47,10 +54,20 @@ struct NormFold {
     float eps;
 };
 
+// K split across workgroups: gsplit = gridDim.y ranges; part holds gsplit records per output tile,
+// ticket one counter per output tile (zero before the launch, zero again after it).
+struct SplitArgs {
+    float* part;
+    unsigned int* ticket;
+    int gsplit;
+    int x_stationary;   // workgroup -> tile mapping, see the kernel
+};
+
 template <int MT, int NT, int WM, int WN, int KS, int PD, int EPI, int NF>
 __global__ __launch_bounds__(256) void k_linear_mfma(const void* __restrict__ Xv, const bf16_t* __restrict__ W,
                                                      const float* __restrict__ bias, void* Y, int M,
-                                                     int N, int K, int ldy, int tiles_m, int tiles_n, NormFold nf) {
+                                                     int N, int K, int ldy, int tiles_m, int tiles_n, NormFold nf,
+                                                     SplitArgs sk) {
     const bf16_t* X = static_cast<const bf16_t*>(Xv);
     static_assert(WM * WN * KS == 4, "four waves per workgroup");
     // The wave index is uniform across the wave; telling the compiler so keeps everything derived from it
@@ -59,12 +76,22 @@ __global__ __launch_bounds__(256) void k_linear_mfma(const void* __restrict__ Xv
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int r = lane & 31, half = lane >> 5;
     const int wm = wave % WM, wn = (wave / WM) % WN, wk = wave / (WM * WN);
-    // Workgroups are handed to the 8 XCDs round-robin by linear id, and each XCD has its own L2.
-    // Column tile tn lives on XCD tn % 8 with all its row tiles, launched back to back: a panel of W is
-    // then fetched into exactly one L2 instead of being pulled through the fabric by several of them.
+    // Workgroups are handed to the 8 XCDs round-robin by linear id, and each XCD has its own L2.  The
+    // larger operand decides the mapping.  Weights larger (few rows): column tile tn lives on XCD tn % 8
+    // with all its row tiles, launched back to back, so a panel of W is fetched into exactly one L2
+    // instead of being pulled through the fabric by several of them.  x larger (many rows): row tile tm
+    // lives on XCD tm % 8 with all its column tiles back to back, so x is streamed from HBM once (per
+    // XCD a row tile at a time) while W, which then fits an L2, is re-read from there.
     const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
-    const int tn = xcd + 8 * (local / tiles_m), tm = local % tiles_m;
-    if (tn >= tiles_n) return;                          // padding workgroup of an XCD with fewer column tiles
+    int tn, tm;
+    if (sk.x_stationary) {
+        tm = xcd + 8 * (local / tiles_n);
+        tn = local % tiles_n;
+    } else {
+        tn = xcd + 8 * (local / tiles_m);
+        tm = local % tiles_m;
+    }
+    if (tn >= tiles_n || tm >= tiles_m) return;         // padding workgroup of an XCD with fewer tiles
     const int m_base = (tm * WM + wm) * 32 * MT;
     const int n_base = (tn * WN + wn) * 32 * NT;
 
@@ -134,13 +161,15 @@ __global__ __launch_bounds__(256) void k_linear_mfma(const void* __restrict__ Xv
 
     // K loop.  Two software pipelines: global -> registers runs PD chunks ahead (hides L2 / HBM
     // latency), registers -> LDS -> operand fragments runs one chunk ahead of the MFMAs (hides the LDS
-    // round trip).  This wave's chunks are wk, wk + KS, ...; local chunk i is global chunk wk + i*KS.
+    // round trip).  This wave's chunks are c0 + wk, c0 + wk + KS, ...
     // The steady-state loop has no conditional loads (the compiler's wait counts would otherwise
     // degrade to "wait for everything"); the last full group and the remainder are peeled.
     static_assert(PD % 2 == 0, "fragment double buffering assumes an even pipeline depth");
     float s1[NF > 0 ? MT : 1][4] = {}, s2[NF > 0 ? MT : 1][4] = {};   // per-lane sum h, sum h^2 of rows 8i + lrow
     const int n_chunks = K / 64;
-    const int n_mine = n_chunks > wk ? (n_chunks - wk + KS - 1) / KS : 0;
+    // chunks [c0, c1) belong to this workgroup (all of them unless K is split over gridDim.y)
+    const int c0 = (int)((long)blockIdx.y * n_chunks / sk.gsplit), c1 = (int)((long)(blockIdx.y + 1) * n_chunks / sk.gsplit);
+    const int n_mine = c1 - c0 > wk ? (c1 - c0 - wk + KS - 1) / KS : 0;
     if (n_mine > 0) {
         u32x4 g[PD][TILES][4];
         u32x4 gx2[NF > 0 ? PD : 1][NF > 0 ? MT : 1][4];     // second half of the fp32 x pieces (NF)
@@ -148,7 +177,7 @@ __global__ __launch_bounds__(256) void k_linear_mfma(const void* __restrict__ Xv
         bf16x8 f[2][TILES][4];
 #define SD_GLOAD(P, LOCAL)                                                                               \
     {                                                                                                    \
-        const uint32_t koff_ = (uint32_t)(wk + (LOCAL) * KS) * 128u;                                     \
+        const uint32_t koff_ = (uint32_t)(c0 + wk + (LOCAL) * KS) * 128u;                                \
         _Pragma("unroll") for (int t = 0; t < TILES; ++t) _Pragma("unroll") for (int i = 0; i < 4; ++i)  \
             g[P][t][i] = __builtin_amdgcn_raw_buffer_load_b128(t < MT ? rx : rw, goff[t][i],              \
                                                                (NF > 0 && t < MT) ? 2u * koff_ : koff_, 0); \
@@ -291,16 +320,73 @@ __global__ __launch_bounds__(256) void k_linear_mfma(const void* __restrict__ Xv
                 }
         }
     }
-    float na[NF > 0 ? MT : 1][16], nb[NF > 0 ? MT : 1][16];   // per accumulator row: rstd and -rstd * mu
+    // Row sums of this workgroup's K range (lane = row).
+    float S1 = 0.f, S2 = 0.f;
     if constexpr (NF > 0) {
         // (LDS operations of one wave execute in order: no barrier between these steps.)
         if (lane < MT * 32) {
-            float S1 = 0.f, S2 = 0.f;
 #pragma unroll
             for (int k = 0; k < KS; ++k) {
                 S1 += stat[(k * MT * 32 + lane) * 2 + 0];
                 S2 += stat[(k * MT * 32 + lane) * 2 + 1];
             }
+        }
+    }
+
+    // K split across workgroups (one output tile set per workgroup, one wave left at this point).
+    if constexpr (WM * WN == 1) {
+        if (sk.gsplit > 1) {
+            constexpr int kRec = MT * NT * 1024 + 128;      // accumulators [tile][e][lane], then S1[64], S2[64]
+            const int tile_id = tn * tiles_m + tm;
+            float* const rec0 = sk.part + (size_t)tile_id * sk.gsplit * kRec;
+            float* const mine = rec0 + (size_t)blockIdx.y * kRec;
+            // Partials travel as device-scope accesses (they go past the caches that are private to one
+            // XCD), so no cache-wide write-back or invalidation is needed: wait until the stores have
+            // completed, then draw the ticket.
+#pragma unroll
+            for (int i = 0; i < MT; ++i)
+#pragma unroll
+                for (int j = 0; j < NT; ++j)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e)
+                        __hip_atomic_store(&mine[((i * NT + j) * 16 + e) * 64 + lane], acc[i][j][e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if constexpr (NF > 0) {
+                __hip_atomic_store(&mine[MT * NT * 1024 + lane], S1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(&mine[MT * NT * 1024 + 64 + lane], S2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            unsigned int old = 0;
+            if (lane == 0) old = __hip_atomic_fetch_add(&sk.ticket[tile_id], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            old = __builtin_amdgcn_readfirstlane(old);
+            if (old != (unsigned int)sk.gsplit - 1u) return;
+            if (lane == 0) __hip_atomic_store(&sk.ticket[tile_id], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
+#pragma unroll
+            for (int i = 0; i < MT; ++i)
+#pragma unroll
+                for (int j = 0; j < NT; ++j)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+            S1 = S2 = 0.f;
+            for (int g = 0; g < sk.gsplit; ++g) {
+                float* rec = rec0 + (size_t)g * kRec;
+#pragma unroll
+                for (int i = 0; i < MT; ++i)
+#pragma unroll
+                    for (int j = 0; j < NT; ++j)
+#pragma unroll
+                        for (int e = 0; e < 16; ++e)
+                            acc[i][j][e] += __hip_atomic_load(&rec[((i * NT + j) * 16 + e) * 64 + lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if constexpr (NF > 0) {
+                    S1 += __hip_atomic_load(&rec[MT * NT * 1024 + lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    S2 += __hip_atomic_load(&rec[MT * NT * 1024 + 64 + lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+            }
+        }
+    }
+
+    float na[NF > 0 ? MT : 1][16], nb[NF > 0 ? MT : 1][16];   // per accumulator row: rstd and -rstd * mu
+    if constexpr (NF > 0) {
+        if (lane < MT * 32) {
             const float mu = NF == 1 ? S1 / (float)K : 0.f;
             const float var = fmaxf(S2 / (float)K - mu * mu, 0.f);
             const float rstd = rsqrtf(var + nf.eps);
@@ -344,17 +430,45 @@ __global__ __launch_bounds__(256) void k_linear_mfma(const void* __restrict__ Xv
             }
 }
 
+static int g_variant_override = -1, g_split_override = -1;
+void linear_mfma_set_variant(int v) { g_variant_override = v; }
+void linear_mfma_set_split(int s) { g_split_override = s; }
+
 template <int MT, int NT, int WM, int WN, int KS, int PD, int NF>
 static hipError_t launch_variant(const void* x, const void* w, const float* bias, void* y, int m, int n, int k,
-                                 int ldy, int epi, const NormFold& nf, hipStream_t st) {
+                                 int ldy, int epi, const NormFold& nf, const SplitWorkspace& ws, hipStream_t st) {
     const int tiles_n = (n + 32 * NT * WN - 1) / (32 * NT * WN), tiles_m = (m + 32 * MT * WM - 1) / (32 * MT * WM);
-    const int grid = 8 * ((tiles_n + 7) / 8) * tiles_m;       // every XCD gets the id range of the fullest one
+    // K split over workgroups: only for the one-tile-set-per-workgroup shapes, when the tiles alone cannot
+    // fill the chip, keeping at least two chunks per wave, within the workspace.
+    SplitArgs sk{nullptr, nullptr, 1, 0};
+    sk.x_stationary = (int64_t)m * (NF > 0 ? 4 : 2) > (int64_t)n * 2;
+    if constexpr (WM * WN == 1) {
+        const long tiles = (long)tiles_n * tiles_m;
+        const long part_floats = ws.base ? (ws.bytes - kSplitTicketBytes) / 4 : 0;
+        constexpr long kRec = MT * NT * 1024 + 128;
+        if (ws.base && tiles * 4 <= kSplitTicketBytes && part_floats > 0) {
+            // Worth it only for long K (the ticket and the final pass over the partials cost about a
+            // microsecond): aim at six chunks per wave, and stop splitting once the tiles fill the chip.
+            const long chunks = k / 64;
+            long want = g_split_override > 0 ? std::min((long)g_split_override, std::max(1L, chunks / (KS * 2)))
+                                             : std::min(chunks / (KS * 6), 256 / tiles);
+            want = std::min(want, part_floats / (tiles * kRec));
+            want = std::min(want, 64L);
+            if (want > 1) {
+                sk.gsplit = (int)want;
+                sk.ticket = static_cast<unsigned int*>(ws.base);
+                sk.part = reinterpret_cast<float*>(static_cast<char*>(ws.base) + kSplitTicketBytes);
+            }
+        }
+    }
+    // every XCD gets the id range of the fullest one
+    const dim3 grid(sk.x_stationary ? 8 * ((tiles_m + 7) / 8) * tiles_n : 8 * ((tiles_n + 7) / 8) * tiles_m, sk.gsplit);
     const bf16_t* wb = (const bf16_t*)w;
     switch (epi) {
-        case EPI_STORE: k_linear_mfma<MT, NT, WM, WN, KS, PD, EPI_STORE, NF><<<grid, 256, 0, st>>>(x, wb, bias, y, m, n, k, ldy, tiles_m, tiles_n, nf); break;
-        case EPI_GELU: k_linear_mfma<MT, NT, WM, WN, KS, PD, EPI_GELU, NF><<<grid, 256, 0, st>>>(x, wb, bias, y, m, n, k, ldy, tiles_m, tiles_n, nf); break;
-        case EPI_RESID: k_linear_mfma<MT, NT, WM, WN, KS, PD, EPI_RESID, NF><<<grid, 256, 0, st>>>(x, wb, bias, y, m, n, k, ldy, tiles_m, tiles_n, nf); break;
-        default: k_linear_mfma<MT, NT, WM, WN, KS, PD, EPI_F32, NF><<<grid, 256, 0, st>>>(x, wb, bias, y, m, n, k, ldy, tiles_m, tiles_n, nf); break;
+        case EPI_STORE: k_linear_mfma<MT, NT, WM, WN, KS, PD, EPI_STORE, NF><<<grid, 256, 0, st>>>(x, wb, bias, y, m, n, k, ldy, tiles_m, tiles_n, nf, sk); break;
+        case EPI_GELU: k_linear_mfma<MT, NT, WM, WN, KS, PD, EPI_GELU, NF><<<grid, 256, 0, st>>>(x, wb, bias, y, m, n, k, ldy, tiles_m, tiles_n, nf, sk); break;
+        case EPI_RESID: k_linear_mfma<MT, NT, WM, WN, KS, PD, EPI_RESID, NF><<<grid, 256, 0, st>>>(x, wb, bias, y, m, n, k, ldy, tiles_m, tiles_n, nf, sk); break;
+        default: k_linear_mfma<MT, NT, WM, WN, KS, PD, EPI_F32, NF><<<grid, 256, 0, st>>>(x, wb, bias, y, m, n, k, ldy, tiles_m, tiles_n, nf, sk); break;
     }
     return hipGetLastError();
 }
@@ -365,30 +479,33 @@ bool linear_mfma_supported(int dtype, int m, int n, int k, int ldy) {
            ((int64_t)m + 64) * ldy * 4 < lim;
 }
 
-static int g_variant_override = -1;
-void linear_mfma_set_variant(int v) { g_variant_override = v; }
-
 static const char* const kEpiName[4] = {"0", "1", "2", "3"};
-static std::string g_names[2][8][4][3];   // [variant set][variant][epilogue][fold]: kernel names as rocprof prints them
+static std::string g_names[8][4][3];   // [variant][epilogue][fold]: kernel names as rocprof prints them
 static const char* variant_name(const char* params, int v, int epi, int nfk) {
-    std::string& s = g_names[0][v][epi][nfk];
+    std::string& s = g_names[v][epi][nfk];
     if (s.empty()) s = std::string("k_linear_mfma<") + params + "," + kEpiName[epi] + "," + kEpiName[nfk] + ">";
     return s.c_str();
+}
+
+// Tile choice by shape.  Up to 64 rows the weights are the whole cost: one workgroup column per 32 weight
+// rows, all x rows in one wave (so W is fetched once), K split over the waves and over workgroups.
+static int choose_variant(int m, int n) {
+    const long tiles64 = (long)((n + 63) / 64) * ((m + 63) / 64);
+    if (m <= 32) return 0;
+    if (m <= 64) return 6;
+    if (tiles64 < 160) return 0;                // few tiles: smallest tile, K split over the four waves
+    if (tiles64 < 4096) return 5;
+    return 3;
 }
 
 #define SD_VARIANT(ID, MT, NT, WM, WN, KS, PD)                                                      \
     case ID:                                                                                        \
         if (kernel_name) *kernel_name = variant_name(#MT "," #NT "," #WM "," #WN "," #KS "," #PD, ID, epi, 0); \
-        return launch_variant<MT, NT, WM, WN, KS, PD, 0>(x, w, bias, y, m, n, k, ldy, epi, NormFold{nullptr, nullptr, 0.f}, st);
+        return launch_variant<MT, NT, WM, WN, KS, PD, 0>(x, w, bias, y, m, n, k, ldy, epi, NormFold{nullptr, nullptr, 0.f}, ws, st);
 
 hipError_t launch_linear_mfma(const void* x, const void* w, const float* bias, void* y, int m, int n, int k, int ldy,
-                              int epi, hipStream_t st, const char** kernel_name) {
-    const long tiles64 = (long)((n + 63) / 64) * ((m + 63) / 64);
-    int v;
-    if (g_variant_override >= 0) v = g_variant_override;
-    else if (m <= 32 || tiles64 < 160) v = 0;   // few tiles: smallest tile, K split over the four waves
-    else if (tiles64 < 4096) v = 5;
-    else v = 3;
+                              int epi, const SplitWorkspace& ws, hipStream_t st, const char** kernel_name) {
+    const int v = g_variant_override >= 0 ? g_variant_override : choose_variant(m, n);
     switch (v) {
         SD_VARIANT(0, 1, 1, 1, 1, 4, 2)     // 32 x 32 tile, four waves split K
         SD_VARIANT(1, 1, 1, 1, 1, 4, 4)     // the same with a deeper global pipeline (long K)
@@ -396,37 +513,35 @@ hipError_t launch_linear_mfma(const void* x, const void* w, const float* bias, v
         SD_VARIANT(3, 2, 2, 2, 2, 1, 2)     // 128 x 128 tile, one 64 x 64 quadrant per wave
         SD_VARIANT(4, 1, 1, 1, 2, 2, 2)     // 32 x 64 tile, two column halves x two K halves
         SD_VARIANT(5, 1, 1, 2, 2, 1, 2)     // as 2 with a shallower global pipeline (more waves per SIMD)
+        SD_VARIANT(6, 2, 1, 1, 1, 4, 2)     // 64 x 32 tile (up to 64 x rows against 32 weight rows), four waves split K
         default: return hipErrorInvalidValue;
     }
 }
 
 // y = epilogue(W norm(h) + bias) with the normalisation folded in (see NormFold).  norm_kind 1 = LayerNorm
 // (u = W g and v = W beta + bias precomputed), 2 = RMSNorm (v = bias).  Same tile choice as above, restricted
-// to the variants with one 32-row x tile per wave.
+// to the variants instantiated for it.
 bool linear_normfold_supported(int dtype, int m, int n, int k, int ldy) {
     return linear_mfma_supported(dtype, m, n, k, ldy) && (int64_t)m * k * 4 < ((int64_t)1 << 31);
 }
 
+#define SD_NF_VARIANT(ID, MT, NT, WM, WN, KS, PD)                                                              \
+    {                                                                                                          \
+        if (kernel_name) *kernel_name = variant_name(#MT "," #NT "," #WM "," #WN "," #KS "," #PD, ID, epi, norm_kind); \
+        return norm_kind == 1 ? launch_variant<MT, NT, WM, WN, KS, PD, 1>(h, w, fold_v, y, m, n, k, ldy, epi, nf, ws, st) \
+                              : launch_variant<MT, NT, WM, WN, KS, PD, 2>(h, w, fold_v, y, m, n, k, ldy, epi, nf, ws, st); \
+    }
+
 hipError_t launch_linear_normfold(const float* h, const void* w, const float* gain, const float* fold_u,
                                   const float* fold_v, void* y, int m, int n, int k, int ldy, int epi, int norm_kind,
-                                  float eps, hipStream_t st, const char** kernel_name) {
-    const long tiles64 = (long)((n + 63) / 64) * ((m + 63) / 64);
-    const bool small = m <= 32 || tiles64 < 160;
+                                  float eps, const SplitWorkspace& ws, hipStream_t st, const char** kernel_name) {
+    if (norm_kind != 1 && norm_kind != 2) return hipErrorInvalidValue;
     const NormFold nf{gain, fold_u, eps};
-    if (norm_kind == 1) {
-        if (small) {
-            if (kernel_name) *kernel_name = variant_name("1,1,1,1,4,2", 0, epi, 1);
-            return launch_variant<1, 1, 1, 1, 4, 2, 1>(h, w, fold_v, y, m, n, k, ldy, epi, nf, st);
-        }
-        if (kernel_name) *kernel_name = variant_name("1,1,2,2,1,2", 5, epi, 1);
-        return launch_variant<1, 1, 2, 2, 1, 2, 1>(h, w, fold_v, y, m, n, k, ldy, epi, nf, st);
-    }
-    if (small) {
-        if (kernel_name) *kernel_name = variant_name("1,1,1,1,4,2", 0, epi, 2);
-        return launch_variant<1, 1, 1, 1, 4, 2, 2>(h, w, fold_v, y, m, n, k, ldy, epi, nf, st);
-    }
-    if (kernel_name) *kernel_name = variant_name("1,1,2,2,1,2", 5, epi, 2);
-    return launch_variant<1, 1, 2, 2, 1, 2, 2>(h, w, fold_v, y, m, n, k, ldy, epi, nf, st);
+    int v = choose_variant(m, n);
+    if (v == 3) v = 5;
+    if (v == 0) SD_NF_VARIANT(0, 1, 1, 1, 1, 4, 2)
+    if (v == 6) SD_NF_VARIANT(6, 2, 1, 1, 1, 4, 2)
+    SD_NF_VARIANT(5, 1, 1, 2, 2, 1, 2)
 }
 
 // u[n] = sum_k g[k] W[n,k];  v[n] = sum_k beta[k] W[n,k] + bias[n]   (beta, bias may be NULL).  One wave per row.

@@ -14,6 +14,7 @@ SHAPES = [  # (m, n, k)
     (17, 768, 768), (16, 50257, 768), (17, 2304, 768), (17, 768, 3072),      # target / LM-head rows of the bench workload
     (272, 2304, 768), (272, 768, 768), (272, 3072, 768), (272, 768, 3072),   # drafter rows
     (1, 64, 64), (33, 100, 128), (65, 33, 192), (130, 4801, 1600), (700, 1000, 256), (3000, 1100, 128),
+    (17, 1600, 6400), (17, 1600, 1600), (33, 1024, 4096), (64, 200, 2048), (40, 100, 1024),   # K split over workgroups
 ]
 
 
@@ -60,7 +61,23 @@ def test_linear_fp32_all_epilogues(m, n, k):
         run_case("f32", m, n, k, epi, seed=m + n + k + epi)
 
 
-@pytest.mark.parametrize("m,n,k", [(17, 2304, 768), (272, 2304, 768), (301, 3072, 768), (33, 100, 128), (65, 4801, 1600), (700, 1000, 256)])
+@pytest.mark.parametrize("split", [2, 3, 7, 64])
+def test_linear_forced_split(split):
+    """Every split count gives the same contraction (up to fp32 summation order), twice in a row on
+    the same workspace, and agrees with the unsplit kernel."""
+    from paper_2408_05636_amd import binding
+    binding.lib().sd_set_linear_split(split)
+    try:
+        for m, n, k in [(17, 1600, 6400), (50, 300, 1024), (5, 96, 4096)]:
+            for epi in (2, 0):
+                run_case("bf16", m, n, k, epi, seed=split + m)
+                run_case("bf16", m, n, k, epi, seed=split + m + 1)
+    finally:
+        binding.lib().sd_set_linear_split(-1)
+
+
+@pytest.mark.parametrize("m,n,k", [(17, 2304, 768), (272, 2304, 768), (301, 3072, 768), (33, 100, 128), (65, 4801, 1600), (700, 1000, 256),
+                                   (17, 4800, 1600), (33, 512, 4096), (60, 96, 2048)])
 @pytest.mark.parametrize("norm_kind", [1, 2])
 def test_norm_folded_linear(m, n, k, norm_kind):
     """LayerNorm / RMSNorm folded into the contraction vs. the oracle's norm followed by its linear."""

@@ -80,5 +80,5 @@ def test_null_and_bad_arguments_are_reported_not_crashed():
     assert lib.sd_last_error(None) == b"null handle"
     assert lib.sd_sampling_scratch_bytes(0, 100) == 0
     assert lib.sd_unmask_sample(None, 1, 1, 10, 1, 0, None, None, None, None, 0, None) == 1
-    assert lib.sd_linear(0, None, None, None, None, 1, 1, 8, 1, 0, None) == 1
+    assert lib.sd_linear(0, None, None, None, None, 1, 1, 8, 1, 0, None, 0, None) == 1
     lib.sd_destroy(None)
