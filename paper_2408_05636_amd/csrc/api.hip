@@ -557,7 +557,8 @@ int run_norm_linear(sd_handle* h, const Model& m, const float* gain, const float
     Buffers& B = h->buf;
     const sd_model_config& c = m.c;
     const int d = c.d_model;
-    if (m.fold && linear_normfold_supported(c.dtype, rows, n, d, ldy)) {
+    // (many rows: a separate normalisation pass in front of the workgroup-shared tile kernel is faster than folding)
+    if (m.fold && linear_normfold_supported(c.dtype, rows, n, d, ldy) && !linear_tile_preferred(rows, n, d)) {
         const double out_b = epi == EPI_F32 ? 4.0 : m.ew;
         const double bytes = (double)rows * d * 4 + (double)n * d * m.ew + (double)rows * n * out_b;
         const char* name = "linear_normfold";

@@ -102,6 +102,11 @@ hipError_t launch_fold_norm(const void* w, const float* gain, const float* beta,
 hipError_t launch_linear_mfma(const void* x, const void* w, const float* bias, void* y, int m, int n, int k, int ldy,
                               int epilogue, const SplitWorkspace& ws, hipStream_t st, const char** kernel_name);
 
+// Many-row contraction with workgroup-shared 64 x 128 or 128 x 128 tiles (x bf16); rows = 0: height by shape.
+bool linear_tile_preferred(int m, int n, int k);
+hipError_t launch_linear_tile(const void* x, const void* w, const float* bias, void* y, int m, int n, int k, int ldy,
+                              int epilogue, int rows, hipStream_t st, const char** kernel_name);
+
 // act[r, c] = silu(gu[r, c]) * gu[r, F + c]
 hipError_t launch_swiglu(int dtype, const void* gu, void* act, int rows, int F, hipStream_t st);
 

@@ -66,37 +66,67 @@ __global__ __launch_bounds__(256) void k_timestep_matvec(const T* __restrict__ w
 }
 
 // ---------------------------------------------------------------- LayerNorm / RMSNorm
-// One workgroup per output row; the row is held in registers (d <= 256 * 32).
-constexpr int kNormMaxPerThread = 32;
-template <typename T>
+// One wave per output row (four rows per workgroup), the row held in registers as 16-byte pieces
+// (d % 4 == 0, d <= 64 * 4 * kNormPieces); reductions by lane shuffles only, no LDS and no barrier.
+constexpr int kNormPieces = 32;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float norm_f32x4;
+typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 norm_bf16x4;
+template <typename T, int P>
 __global__ __launch_bounds__(256) void k_norm(const float* __restrict__ h, const int32_t* __restrict__ idx,
                                               const float* __restrict__ gain, const float* __restrict__ bias,
-                                              T* __restrict__ out, int d, float eps) {
-    __shared__ float sh[4];
-    const int r = blockIdx.x;
+                                              T* __restrict__ out, int rows, int d, float eps) {
+    const int r = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (r >= rows) return;
     const float* x = h + (size_t)(idx ? idx[r] : r) * d;
-    float v[kNormMaxPerThread];
+    const int n4 = d >> 2;
+    norm_f32x4 v[P];
     float s = 0.f;
-    int cnt = 0;
-    for (int i = threadIdx.x; i < d; i += 256) { v[cnt] = x[i]; s += v[cnt]; ++cnt; }
-    auto bsum = [&](float a) {
+#pragma unroll
+    for (int p = 0; p < P; ++p) {
+        const int c = lane + 64 * p;
+        if (c < n4) {
+            v[p] = *reinterpret_cast<const norm_f32x4*>(x + 4 * c);
+            s += (v[p][0] + v[p][1]) + (v[p][2] + v[p][3]);
+        }
+    }
+    auto wsum = [](float a) {
+#pragma unroll
         for (int off = 32; off > 0; off >>= 1) a += __shfl_xor(a, off, 64);
-        __syncthreads();
-        if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = a;
-        __syncthreads();
-        return (sh[0] + sh[1]) + (sh[2] + sh[3]);
+        return a;
     };
     float mean = 0.f;
-    if (bias) mean = bsum(s) / (float)d;           // LayerNorm centres; RMSNorm does not
+    if (bias) mean = wsum(s) / (float)d;           // LayerNorm centres; RMSNorm does not
     float ss = 0.f;
-    for (int c = 0; c < cnt; ++c) { const float t = v[c] - mean; ss += t * t; }
-    const float rstd = rsqrtf(bsum(ss) / (float)d + eps);
-    cnt = 0;
-    for (int i = threadIdx.x; i < d; i += 256) {
-        float y = (v[cnt] - mean) * rstd * gain[i];
-        if (bias) y += bias[i];
-        out[(size_t)r * d + i] = from_f<T>(y);
-        ++cnt;
+#pragma unroll
+    for (int p = 0; p < P; ++p)
+        if (lane + 64 * p < n4) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) { const float t = v[p][u] - mean; ss = fmaf(t, t, ss); }
+        }
+    const float rstd = rsqrtf(wsum(ss) / (float)d + eps);
+#pragma unroll
+    for (int p = 0; p < P; ++p) {
+        const int c = lane + 64 * p;
+        if (c < n4) {
+            const norm_f32x4 g = *reinterpret_cast<const norm_f32x4*>(gain + 4 * c);
+            norm_f32x4 y;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) y[u] = (v[p][u] - mean) * rstd * g[u];
+            if (bias) {
+                const norm_f32x4 b = *reinterpret_cast<const norm_f32x4*>(bias + 4 * c);
+#pragma unroll
+                for (int u = 0; u < 4; ++u) y[u] += b[u];
+            }
+            T* o = out + (size_t)r * d + 4 * c;
+            if constexpr (sizeof(T) == 2) {
+                norm_bf16x4 pk;
+#pragma unroll
+                for (int u = 0; u < 4; ++u) pk[u] = static_cast<bf16_t>(y[u]);
+                *reinterpret_cast<norm_bf16x4*>(o) = pk;
+            } else {
+                *reinterpret_cast<norm_f32x4*>(o) = y;
+            }
+        }
     }
 }
 
@@ -173,8 +203,13 @@ hipError_t launch_timestep_embed(int dtype, const void* w1, const float* b1, con
 hipError_t launch_norm(int dtype, const float* h, const int32_t* idx, const float* gain, const float* bias,
                        void* out, int rows, int d, float eps, hipStream_t st) {
     if (rows <= 0) return hipSuccess;
-    if (d > 256 * kNormMaxPerThread) return hipErrorInvalidValue;
-    SD_DISPATCH(dtype, (k_norm<T><<<rows, 256, 0, st>>>(h, idx, gain, bias, (T*)out, d, eps)));
+    if (d % 4 || d > 64 * 4 * kNormPieces) return hipErrorInvalidValue;
+    const int pieces = (d / 4 + 63) / 64, grid = (rows + 3) / 4;
+    // register-resident row: instantiate a few row lengths so that short rows do not carry 32 pieces
+    if (pieces <= 4) { SD_DISPATCH(dtype, (k_norm<T, 4><<<grid, 256, 0, st>>>(h, idx, gain, bias, (T*)out, rows, d, eps))); }
+    else if (pieces <= 8) { SD_DISPATCH(dtype, (k_norm<T, 8><<<grid, 256, 0, st>>>(h, idx, gain, bias, (T*)out, rows, d, eps))); }
+    else if (pieces <= 16) { SD_DISPATCH(dtype, (k_norm<T, 16><<<grid, 256, 0, st>>>(h, idx, gain, bias, (T*)out, rows, d, eps))); }
+    else { SD_DISPATCH(dtype, (k_norm<T, kNormPieces><<<grid, 256, 0, st>>>(h, idx, gain, bias, (T*)out, rows, d, eps))); }
     return hipGetLastError();
 }
 

@@ -505,7 +505,8 @@ static int choose_variant(int m, int n) {
 
 hipError_t launch_linear_mfma(const void* x, const void* w, const float* bias, void* y, int m, int n, int k, int ldy,
                               int epi, const SplitWorkspace& ws, hipStream_t st, const char** kernel_name) {
-    const int v = g_variant_override >= 0 ? g_variant_override : choose_variant(m, n);
+    const int v = g_variant_override >= 0 ? g_variant_override : (linear_tile_preferred(m, n, k) ? 7 : choose_variant(m, n));
+    if (v == 7 || v == 8) return launch_linear_tile(x, w, bias, y, m, n, k, ldy, epi, g_variant_override == 8 ? 64 : (g_variant_override == 7 ? 128 : 0), st, kernel_name);
     switch (v) {
         SD_VARIANT(0, 1, 1, 1, 1, 4, 2)     // 32 x 32 tile, four waves split K
         SD_VARIANT(1, 1, 1, 1, 1, 4, 4)     // the same with a deeper global pipeline (long K)

@@ -1,0 +1,256 @@
+// bf16 contraction y = epilogue(x W^T + bias) for many rows (batched passes): a workgroup of four waves
+// owns a (64 WM) x 128 output tile and shares both operand tiles through LDS, so every byte fetched from
+// L2 / HBM feeds 64 rows of matrix-core work per wave instead of 32 (the few-row kernel keeps its tiles
+// private to a wave and pays for that with twice the loads per flop).  WM = 2: 128 x 128 tile, waves 2 x 2,
+// 64 x 64 outputs each; WM = 1: 64 x 128 tile, waves 1 x 4, 64 x 32 outputs each (a few hundred rows).
+//
+// K is walked in chunks of 64.  All 256 threads fetch the two operand tiles of a chunk with
+// 16-byte buffer loads (8 consecutive lanes per 128-byte line), hold them in registers for two chunks
+// and then store them into one of two LDS stages, XOR-swizzled (see swizzle_key) so that neither the
+// stores nor the operand reads conflict.  Wave (wm, wn) computes the
+// 64 x 64 quadrant: per 16-wide k step two A and two B fragments, four v_mfma_f32_32x32x16_bf16.  One
+// barrier per chunk; the global loads in the loop body are unconditional (past the end of K they
+// repeat the last chunk), so the compiler's wait counts stay exact.
+//
+// The normalisation in front of a contraction is not folded in here (the few-row kernel does that): with
+// this many rows a separate normalisation pass costs a fifth of the contraction, while converting the
+// fp32 residual stream on the way into LDS costs more than that in registers and vector-ALU time.
+#include <string>
+
+#include "common.h"
+
+namespace sd {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
+typedef __attribute__((__vector_size__(4 * sizeof(unsigned int)))) unsigned int u32x4;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+constexpr int kTileFlags = 0x00020000;            // raw buffer, 32-bit data format
+constexpr uint32_t kTileOutOfRange = 0x80000000u;  // voffset of accesses that must not happen (buffers < 2 GiB)
+
+__device__ inline float gelu_tile(float x) {
+    const float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
+    return x / (1.f + __expf(-2.f * u));
+}
+
+// 16-byte piece c of tile row r is stored at piece c ^ key(r).  A fragment read touches 16-byte pieces of
+// 32 consecutive rows at one logical piece index; rows are 128 bytes apart, so rows of equal parity share
+// their banks and the key must separate them: any 16 consecutive rows get 16 distinct (parity, key) pairs.
+__device__ inline int swizzle_key(int row) { return (row & 7) ^ ((row >> 3) & 1); }
+
+template <int EPI, int WM>
+__global__ __launch_bounds__(256) void k_linear_tile(const void* __restrict__ Xv, const bf16_t* __restrict__ W,
+                                                     const float* __restrict__ bias, void* Y, int M, int N, int K,
+                                                     int ldy, int tiles_m, int tiles_n, int x_stationary) {
+    constexpr int BM = 64 * WM;            // rows of the workgroup tile
+    constexpr int XI = BM / 32;            // x row groups per loader thread
+    constexpr int NT = WM == 2 ? 2 : 1;    // 32-column tiles per wave
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int r = lane & 31, half = lane >> 5;
+    const int wm = wave % WM, wn = wave / WM;
+    // XCD-aware tile order (workgroups go to the 8 XCDs round-robin): the larger operand is fetched by one XCD only.
+    const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
+    int tn, tm;
+    if (x_stationary) {
+        tm = xcd + 8 * (local / tiles_n);
+        tn = local % tiles_n;
+    } else {
+        tn = xcd + 8 * (local / tiles_m);
+        tm = local % tiles_m;
+    }
+    if (tn >= tiles_n || tm >= tiles_m) return;
+    const int m_base = tm * BM, n_base = tn * 128;
+
+    __shared__ u32x4 lds_x[2][BM * 8];                // [stage][rows x 8 pieces]
+    __shared__ u32x4 lds_w[2][1024];
+
+    const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(Xv), 0, (uint32_t)M * (uint32_t)K * 2u, kTileFlags);
+    const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(W), 0, (uint32_t)N * (uint32_t)K * 2u, kTileFlags);
+
+    // Loader geometry: thread t handles piece pc = t & 7 of rows 32 i + (t >> 3) of both tiles.
+    const int lrow = threadIdx.x >> 3, pc = threadIdx.x & 7;
+    uint32_t xoff[XI], woff[4];
+    int slot[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const uint32_t wr = (uint32_t)(n_base + 32 * i + lrow);
+        woff[i] = wr < (uint32_t)N ? (wr * (uint32_t)K + 8u * pc) * 2u : kTileOutOfRange;
+        const int row = 32 * i + lrow;
+        slot[i] = row * 8 + (pc ^ swizzle_key(row));
+        if (i < XI) {
+            const uint32_t xr = (uint32_t)(m_base + 32 * i + lrow);
+            xoff[i] = xr < (uint32_t)M ? (xr * (uint32_t)K + 8u * pc) * 2u : kTileOutOfRange;
+        }
+    }
+    // rows of the operand fragments this lane reads, and their swizzle keys
+    int ra[2], rbw[NT], ka[2], kb[NT];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        ra[i] = wm * 64 + 32 * i + r;
+        ka[i] = swizzle_key(ra[i]);
+    }
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {
+        rbw[j] = wn * 32 * NT + 32 * j + r;
+        kb[j] = swizzle_key(rbw[j]);
+    }
+    bf16x8 fa[2][2], fb[2][NT];
+
+    floatx16 acc[2][NT];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    // two register sets: the global loads run two chunks ahead of the LDS stores
+    u32x4 gx[2][XI], gw[2][4];
+    const int n_chunks = K / 64;
+
+#define SD_TILE_GLOAD(S, CHUNK)                                                                     \
+    {                                                                                               \
+        const uint32_t koff_ = (uint32_t)(CHUNK) * 128u;                                            \
+        _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                             \
+            if (i < XI) gx[S][i < XI ? i : 0] = __builtin_amdgcn_raw_buffer_load_b128(rx, xoff[i < XI ? i : 0], koff_, 0); \
+            gw[S][i] = __builtin_amdgcn_raw_buffer_load_b128(rw, woff[i], koff_, 0);                \
+        }                                                                                           \
+    }
+#define SD_TILE_SWRITE(S, STAGE)                                                                    \
+    {                                                                                               \
+        _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                             \
+            if (i < XI) lds_x[STAGE][slot[i]] = gx[S][i < XI ? i : 0];                              \
+            lds_w[STAGE][slot[i]] = gw[S][i];                                                       \
+        }                                                                                           \
+    }
+// Operand fragments are double-buffered by hand: the LDS reads of k step s4 + 1 are in flight while the
+// matrix cores work on step s4.
+#define SD_TILE_FRAGS(STAGE, FB, S4)                                                                \
+    {                                                                                               \
+        _Pragma("unroll") for (int i = 0; i < 2; ++i)                                               \
+            fa[FB][i] = __builtin_bit_cast(bf16x8, lds_x[STAGE][ra[i] * 8 + ((2 * (S4) + half) ^ ka[i])]); \
+        _Pragma("unroll") for (int j = 0; j < NT; ++j)                                              \
+            fb[FB][j] = __builtin_bit_cast(bf16x8, lds_w[STAGE][rbw[j] * 8 + ((2 * (S4) + half) ^ kb[j])]); \
+    }
+#define SD_TILE_COMPUTE(STAGE)                                                                      \
+    {                                                                                               \
+        SD_TILE_FRAGS(STAGE, 0, 0)                                                                  \
+        _Pragma("unroll") for (int s4 = 0; s4 < 4; ++s4) {                                          \
+            if (s4 < 3) SD_TILE_FRAGS(STAGE, (s4 + 1) & 1, s4 + 1)                                  \
+            __builtin_amdgcn_sched_barrier(0);     /* keep the reads of the next step ahead of these MFMAs */ \
+            _Pragma("unroll") for (int i = 0; i < 2; ++i) _Pragma("unroll") for (int j = 0; j < NT; ++j) \
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[s4 & 1][i], fb[s4 & 1][j], acc[i][j], 0, 0, 0); \
+            __builtin_amdgcn_sched_barrier(0);                                                      \
+        }                                                                                           \
+    }
+
+    // Step c: store chunk c + 1 (register set (c + 1) & 1) into LDS stage (c + 1) & 1 -- last read before the
+    // barrier that ended step c - 1 --, refill that register set with chunk c + 3, multiply chunk c.  The
+    // steady state is a branch-free pair of steps (with branches inside, the compiler's wait counts fall
+    // back to "everything outstanding" and the two-chunk prefetch distance is lost); the scheduling fences
+    // keep the global loads in front of the multiply phase instead of behind it.  Past the end of K the
+    // loads repeat the last chunk (unconditional, nobody reads them).
+#define SD_TILE_STEP(NEXT, CUR, C)                      \
+    {                                                   \
+        SD_TILE_SWRITE(NEXT, NEXT)                      \
+        SD_TILE_GLOAD(NEXT, min((C) + 3, last))         \
+        __builtin_amdgcn_sched_barrier(0);              \
+        SD_TILE_COMPUTE(CUR)                            \
+        __syncthreads();                                \
+    }
+    const int last = n_chunks - 1;
+    SD_TILE_GLOAD(0, 0)
+    SD_TILE_GLOAD(1, min(1, last))
+    SD_TILE_SWRITE(0, 0)
+    SD_TILE_GLOAD(0, min(2, last))
+    __syncthreads();
+    int c = 0;
+    for (; c + 2 <= last; c += 2) {
+        SD_TILE_STEP(1, 0, c)
+        SD_TILE_STEP(0, 1, c + 1)
+    }
+    if (c < last) {
+        SD_TILE_STEP(1, 0, c)
+        SD_TILE_COMPUTE(1)
+    } else {
+        SD_TILE_COMPUTE(0)
+    }
+#undef SD_TILE_STEP
+#undef SD_TILE_GLOAD
+#undef SD_TILE_SWRITE
+#undef SD_TILE_FRAGS
+#undef SD_TILE_COMPUTE
+
+    // Epilogue: accumulator e of a 32 x 32 tile is row 8 (e / 4) + 4 half + e % 4, column lane & 31.
+    constexpr uint32_t kOutBytes = (EPI == EPI_STORE || EPI == EPI_GELU) ? 2u : 4u;
+    const __amdgpu_buffer_rsrc_t ry = __builtin_amdgcn_make_buffer_rsrc(Y, 0, (uint32_t)M * (uint32_t)ldy * kOutBytes, kTileFlags);
+    const __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(bias), 0, bias ? (uint32_t)N * 4u : 0u, kTileFlags);
+    const int wm_base = m_base + wm * 64;
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {
+        const uint32_t n = (uint32_t)(n_base + wn * 32 * NT + 32 * j + r);
+        const uint32_t yoff = n < (uint32_t)N ? ((uint32_t)(wm_base + 4 * half) * (uint32_t)ldy + n) * kOutBytes : kTileOutOfRange;
+        const float bv = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rb, n * 4u, 0, 0));
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int lr = 32 * i + 8 * (e >> 2) + (e & 3);          // row within the wave's 64, minus 4 * half
+                const uint32_t so = (uint32_t)lr * (uint32_t)ldy * kOutBytes;
+                float v = acc[i][j][e] + bv;
+                if constexpr (EPI == EPI_GELU) v = gelu_tile(v);
+                if constexpr (EPI == EPI_RESID) v += __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(ry, yoff + so, 0, 0));
+                if constexpr (kOutBytes == 2)
+                    __builtin_amdgcn_raw_buffer_store_b16(__builtin_bit_cast(unsigned short, static_cast<bf16_t>(v)), ry, yoff + so, 0, 0);
+                else
+                    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned int, v), ry, yoff + so, 0, 0);
+            }
+    }
+}
+
+static std::string g_tile_names[4][3];
+static const char* tile_name(int epi, int wm) {
+    std::string& s = g_tile_names[epi][wm];
+    if (s.empty()) s = "k_linear_tile<" + std::to_string(epi) + "," + std::to_string(wm) + ">";
+    return s.c_str();
+}
+
+// Tile height for a shape (0: leave it to the few-row kernel).  Worth it from a few hundred rows on, when
+// the tiles can still occupy a good part of the chip and there is enough arithmetic per output element
+// (short, narrow contractions are bound by their fp32 output).
+int linear_tile_rows(int m, int n, int k) {
+    if (m < 192 || (n < 2048 && k < 2048)) return 0;
+    const long tn = (n + 127) / 128;
+    if (m >= 512 && (long)((m + 127) / 128) * tn >= 200) return 128;
+    if ((long)((m + 63) / 64) * tn >= 160) return 64;
+    return 0;
+}
+bool linear_tile_preferred(int m, int n, int k) { return linear_tile_rows(m, n, k) != 0; }
+
+template <int WM>
+static hipError_t launch_tile(const void* x, const bf16_t* wb, const float* bias, void* y, int m, int n, int k, int ldy,
+                              int epi, hipStream_t st) {
+    const int tiles_m = (m + 64 * WM - 1) / (64 * WM), tiles_n = (n + 127) / 128;
+    const int xs = (int64_t)m > (int64_t)n;
+    const int grid = xs ? 8 * ((tiles_m + 7) / 8) * tiles_n : 8 * ((tiles_n + 7) / 8) * tiles_m;
+    switch (epi) {
+        case EPI_STORE: k_linear_tile<EPI_STORE, WM><<<grid, 256, 0, st>>>(x, wb, bias, y, m, n, k, ldy, tiles_m, tiles_n, xs); break;
+        case EPI_GELU: k_linear_tile<EPI_GELU, WM><<<grid, 256, 0, st>>>(x, wb, bias, y, m, n, k, ldy, tiles_m, tiles_n, xs); break;
+        case EPI_RESID: k_linear_tile<EPI_RESID, WM><<<grid, 256, 0, st>>>(x, wb, bias, y, m, n, k, ldy, tiles_m, tiles_n, xs); break;
+        default: k_linear_tile<EPI_F32, WM><<<grid, 256, 0, st>>>(x, wb, bias, y, m, n, k, ldy, tiles_m, tiles_n, xs); break;
+    }
+    return hipGetLastError();
+}
+
+// x bf16 [m, k], w bf16 [n, k]; same shape limits as the few-row kernel (linear_mfma_supported).
+// rows: tile height, 64 or 128 (0: by shape, 128 if the shape has no preference).
+hipError_t launch_linear_tile(const void* x, const void* w, const float* bias, void* y, int m, int n, int k, int ldy,
+                              int epi, int rows, hipStream_t st, const char** kernel_name) {
+    if (epi < 0 || epi > 3) return hipErrorInvalidValue;
+    if (rows == 0) rows = linear_tile_rows(m, n, k) == 64 ? 64 : 128;
+    if (kernel_name) *kernel_name = tile_name(epi, rows / 64);
+    return rows == 64 ? launch_tile<1>(x, (const bf16_t*)w, bias, y, m, n, k, ldy, epi, st)
+                      : launch_tile<2>(x, (const bf16_t*)w, bias, y, m, n, k, ldy, epi, st);
+}
+
+}  // namespace sd

@@ -61,6 +61,19 @@ def test_linear_fp32_all_epilogues(m, n, k):
         run_case("f32", m, n, k, epi, seed=m + n + k + epi)
 
 
+@pytest.mark.parametrize("m,n,k", [(130, 4801, 1600), (700, 1000, 256), (1056, 2304, 768), (300, 130, 64), (1, 64, 64), (2100, 768, 3072)])
+@pytest.mark.parametrize("variant", [7, 8])
+def test_linear_shared_tile_kernel(m, n, k, variant):
+    """The workgroup-shared tile kernels (128 / 64 rows; normally chosen only for many rows), forced on ragged shapes."""
+    from paper_2408_05636_amd import binding
+    binding.lib().sd_set_linear_variant(variant)
+    try:
+        for epi in range(4):
+            run_case("bf16", m, n, k, epi, seed=7 + m + n + k + epi)
+    finally:
+        binding.lib().sd_set_linear_variant(-1)
+
+
 @pytest.mark.parametrize("split", [2, 3, 7, 64])
 def test_linear_forced_split(split):
     """Every split count gives the same contraction (up to fp32 summation order), twice in a row on
@@ -77,7 +90,7 @@ def test_linear_forced_split(split):
 
 
 @pytest.mark.parametrize("m,n,k", [(17, 2304, 768), (272, 2304, 768), (301, 3072, 768), (33, 100, 128), (65, 4801, 1600), (700, 1000, 256),
-                                   (17, 4800, 1600), (33, 512, 4096), (60, 96, 2048)])
+                                   (17, 4800, 1600), (33, 512, 4096), (60, 96, 2048), (2100, 2304, 768)])
 @pytest.mark.parametrize("norm_kind", [1, 2])
 def test_norm_folded_linear(m, n, k, norm_kind):
     """LayerNorm / RMSNorm folded into the contraction vs. the oracle's norm followed by its linear."""
