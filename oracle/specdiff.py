@@ -146,3 +146,97 @@ def oracle_verify(target_logits, prefix, draft, q, seed, batch=0):
 def expected_tokens(alpha, gamma):
     """Appendix A, Eq. (2): expected tokens per round for i.i.d. acceptance rate alpha."""
     return (1.0 - alpha ** (gamma + 1)) / (1.0 - alpha) if alpha < 1.0 else gamma + 1.0
+
+
+# ---------------------------------------------------------------------------------------
+# Temperature 0 (the setting of the paper's experiments, Section 4.1) and multi-round
+# generation.  At temperature 0 both laws are one-hot on their argmax, and Algorithm 1
+# degenerates: p(x)/q(x) is 1 when the drafted token is the target's argmax and 0 otherwise,
+# so a token is accepted iff it equals the target's argmax there, and the residual
+# norm(max(0, p - q)) after a rejection is p itself, i.e. the target's argmax.  No uniforms
+# are consumed by verification; the drafter still reveals slots by the same 1/j rule.
+# ---------------------------------------------------------------------------------------
+def argmax_f32(row):
+    """Index of the largest logit after rounding to fp32 (the precision the path stores
+    logits in), lowest index on ties.  Returns (index, gap to the runner-up)."""
+    x = np.asarray(row, dtype=np.float32)
+    v = int(np.argmax(x))
+    if x.size == 1:
+        return v, np.inf
+    rest = np.delete(x, v)
+    return v, float(x[v] - rest.max())
+
+
+def draft_greedy_with_uniforms(drafter_logits, prefix, gamma, T, ua, mask_id):
+    """Steps (1)-(3) at temperature 0: a slot revealed at step j takes the argmax of its row.
+    Returns (z, gaps, n_forwards)."""
+    prefix = np.asarray(prefix, dtype=np.int64)
+    z = np.full(gamma, mask_id, dtype=np.int64)
+    gaps = np.full(gamma, np.inf)
+    n_forwards = 0
+    for j in range(T, 0, -1):
+        masked = np.flatnonzero(z == mask_id)
+        if masked.size == 0:
+            continue
+        logits = np.asarray(drafter_logits(np.concatenate([prefix, z]), j / T), dtype=np.float64)
+        n_forwards += 1
+        for k in masked:
+            if j == 1 or ua[j, k] * j < 1.0:
+                z[k], gaps[k] = argmax_f32(logits[k])
+    return z, gaps, n_forwards
+
+
+def verify_greedy(logits, draft):
+    """Steps (4)-(7) at temperature 0.  logits: [gamma+1, V] target logits (row k follows
+    prefix o draft[:k]).  Returns (n, token, gaps[gamma+1])."""
+    gamma = len(draft)
+    top = [argmax_f32(logits[k]) for k in range(gamma + 1)]
+    n = gamma
+    for k in range(gamma):
+        if int(draft[k]) != top[k][0]:
+            n = k
+            break
+    return n, top[n][0], np.array([g for _, g in top])
+
+
+def oracle_draft_greedy(drafter_logits, prefix, gamma, T, seed, mask_id, batch=0):
+    ua, _ = draft_uniforms(seed, batch, gamma, T)
+    return draft_greedy_with_uniforms(drafter_logits, prefix, gamma, T, ua, mask_id)
+
+
+def oracle_verify_greedy(target_logits, prefix, draft):
+    prefix = np.asarray(prefix, dtype=np.int64)
+    draft = np.asarray(draft, dtype=np.int64)
+    rows = np.arange(prefix.size - 1, prefix.size + draft.size)
+    logits = np.asarray(target_logits(np.concatenate([prefix, draft]), rows), dtype=np.float64)
+    return verify_greedy(logits, draft)
+
+
+def generate(drafter_logits, target_logits, prefix, n_new, gamma, T, seed, mask_id, greedy):
+    """Rounds of Algorithm 1 until at least n_new tokens were emitted; round i uses seed + i and
+    appends its n accepted draft tokens and the extra token to the prefix.
+    Returns (tokens emitted [>= n_new], accepted count of every round)."""
+    seq = [int(t) for t in prefix]
+    start = len(seq)
+    accepted = []
+    rnd = 0
+    while len(seq) - start < n_new:
+        if greedy:
+            z, _, _ = oracle_draft_greedy(drafter_logits, seq, gamma, T, seed + rnd, mask_id)
+            n, tok, _ = oracle_verify_greedy(target_logits, seq, z)
+        else:
+            z, q, _, _ = oracle_draft(drafter_logits, seq, gamma, T, seed + rnd, mask_id)
+            n, tok, _, _ = oracle_verify(target_logits, seq, z, q, seed + rnd)
+        seq += [int(t) for t in z[:n]] + [int(tok)]
+        accepted.append(n)
+        rnd += 1
+    return np.array(seq[start:], dtype=np.int64), np.array(accepted, dtype=np.int64)
+
+
+def target_greedy_decode(target_logits, prefix, n_new):
+    """Plain autoregressive decoding of the target at temperature 0 (what SpecDiff must reproduce)."""
+    seq = [int(t) for t in prefix]
+    for _ in range(n_new):
+        logits = np.asarray(target_logits(np.array(seq), np.array([len(seq) - 1])), dtype=np.float64)
+        seq.append(argmax_f32(logits[0])[0])
+    return np.array(seq[len(prefix):], dtype=np.int64)

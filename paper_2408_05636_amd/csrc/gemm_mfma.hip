@@ -8,7 +8,7 @@
 // in registers PD chunks ahead, then passes them through a wave-private, XOR-swizzled LDS tile to
 // reach the MFMA operand layout (lane l supplies 8 consecutive k of row l & 31).  The LDS tile is
 // private to the wave, so the K loop has no workgroup barrier and waves of a workgroup drift
-// freely; bank conflicts are avoided by storing 16-byte piece c of row r at piece c ^ (r & 7).
+// freely; bank conflicts are avoided by an XOR swizzle of the 16-byte pieces of a row.
 //
 // A workgroup is WM x WN x KS waves (KS = waves that split the K range of one tile and reduce
 // through LDS in a fixed order: deterministic results).
@@ -117,7 +117,11 @@ __global__ __launch_bounds__(256) void k_linear_mfma(const void* __restrict__ Xv
             const uint32_t lim = t < MT ? (uint32_t)M : (uint32_t)N;
             goff[t][i] = row < lim ? (row * (uint32_t)K + 8u * pc) * (t < MT ? kXBytes : 2u) : kOutOfRange;
         }
-    const int wslot = lrow * 8 + (pc ^ lrow);            // swizzled slot of this lane's piece within an 8-row group
+    // Swizzled slot of this lane's piece within the 8-row group i (row 8 i + lrow): piece c of row r sits at
+    // piece c ^ key(r), key(r) = (r & 7) ^ ((r >> 3) & 1).  A fragment read covers 32 rows at one logical piece;
+    // rows are 128 bytes apart, so rows of equal parity share banks and the key must separate any 16 of them.
+    const int wslot2[2] = {lrow * 8 + (pc ^ lrow), lrow * 8 + (pc ^ lrow ^ 1)};
+    const int rkey = (r & 7) ^ ((r >> 3) & 1);
 
     floatx16 acc[MT][NT];
 #pragma unroll
@@ -213,12 +217,12 @@ __global__ __launch_bounds__(256) void k_linear_mfma(const void* __restrict__ Xv
                         s2[t < MT ? t : tx_][i] = fmaf(xs_[u_], xs_[u_], s2[t < MT ? t : tx_][i]);       \
                         pk_[u_] = static_cast<bf16_t>(xs_[u_] * gs_[u_]);                                \
                     }                                                                                    \
-                    stage[t * 256 + i * 64 + wslot] = __builtin_bit_cast(u32x4, pk_);                    \
-                } else stage[t * 256 + i * 64 + wslot] = g[P][t][i];                                     \
-            } else stage[t * 256 + i * 64 + wslot] = g[P][t][i];                                         \
+                    stage[t * 256 + i * 64 + wslot2[i & 1]] = __builtin_bit_cast(u32x4, pk_);                    \
+                } else stage[t * 256 + i * 64 + wslot2[i & 1]] = g[P][t][i];                                     \
+            } else stage[t * 256 + i * 64 + wslot2[i & 1]] = g[P][t][i];                                         \
         }                                                                                                \
         _Pragma("unroll") for (int t = 0; t < TILES; ++t) _Pragma("unroll") for (int s4 = 0; s4 < 4; ++s4) \
-            f[FB][t][s4] = __builtin_bit_cast(bf16x8, stage[t * 256 + r * 8 + ((2 * s4 + half) ^ (r & 7))]); \
+            f[FB][t][s4] = __builtin_bit_cast(bf16x8, stage[t * 256 + r * 8 + ((2 * s4 + half) ^ rkey)]); \
     }
 #define SD_MMA(FB)                                                                                       \
     {                                                                                                    \
