@@ -78,6 +78,7 @@ def main():
     ap.add_argument("--workload", default="gpt2s")
     ap.add_argument("--gamma", type=int, default=0)
     ap.add_argument("--T", type=int, default=0)
+    ap.add_argument("--greedy", action="store_true", help="temperature 0 (sd_set_greedy) instead of the stochastic rule")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true")
     ap.add_argument("--copy-probe", action="store_true", help="also launch one 64 MiB elementwise copy kernel, torch.neg (calibrates rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)")
@@ -100,6 +101,8 @@ def main():
     sd = binding.SpecDiff(t, d, Wt, Wd, max_batch=B, gamma_max=gamma)
     if a.no_cpu_baseline:
         Wt = Wd = None                            # the host copies only serve the oracle
+    if a.greedy:
+        sd.sd_set_greedy(True)
     prefixes = prefixes_for(w, 3)
     flat, lens = binding._ragged(prefixes)
     sd.sd_prefill(prefixes)                       # prompt processing: outside the round
@@ -155,7 +158,7 @@ def main():
             roof["traffic"] = json.load(open(tr)).get(a.workload, {}).get(e["name"])
 
     cpu = None
-    if not a.no_cpu_baseline:
+    if not a.no_cpu_baseline and not a.greedy:
         cpu = cpu_baseline(w, Wt, Wd, prefixes, 1000)
 
     out = {
@@ -164,7 +167,7 @@ def main():
         "vs_baseline": None, "dtype": t.dtype, "data": "synthetic",
         "config": {"workload": f"{a.workload}: one SpecDiff round, target {t.n_layer}L d={t.d_model} V={t.vocab}, "
                                f"drafter {d.n_layer}L d={d.d_model}, prefix {[int(x) for x in lens][:4]}, "
-                               f"gamma={gamma}, T={T}, batch={B}, random-init weights"},
+                               f"gamma={gamma}, T={T}, batch={B}, random-init weights" + (", temperature 0" if a.greedy else "")},
         "round_latency_us": ms_per_step * 1e3,
         "mean_accepted_per_round": accepted / (a.steps * B),
         "roofline": roof, "cpu_baseline": cpu, "kernels": phases,

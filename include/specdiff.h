@@ -122,6 +122,21 @@ int32_t sd_round(sd_handle *h, int32_t batch, const int32_t *prefix, const int32
                  int32_t gamma, int32_t T, uint64_t seed, int32_t *draft_out,
                  int32_t *n_accepted_out, int32_t *token_out);
 
+/* After sd_verify / sd_round: keep the n accepted tokens.  The target's KV cache then counts the rows of
+ * the last prefix token and of draft[0 .. n) as cached, so that the next call whose prefix is
+ * old prefix o draft[0 .. n) o token runs without a prefill (multi-round generation: the loop around
+ * Algorithm 1).  n_accepted: host [batch], each in [0, gamma].  Without this call the next round with a
+ * longer prefix prefills again (correct, only slower).  SD_ERR_STATE if no verification is pending. */
+int32_t sd_commit(sd_handle *h, int32_t batch, const int32_t *n_accepted);
+
+/* Temperature 0, the setting of the paper's experiments (Section 4.1): the one-hot limit of Algorithm 1.
+ * enable != 0: a slot revealed by the drafter takes the argmax of its row (reveal schedule unchanged;
+ * no q is produced, qtok = 1), a drafted token is accepted iff it is the argmax of the target's row,
+ * and the extra token is the argmax of row n; seeds only drive the reveal schedule.  Arg-maxima are taken
+ * on the fp32 logits, lowest id on ties.  Applies to sd_draft, sd_verify (its q_dev is ignored but must
+ * be non-NULL) and sd_round of this handle until switched off. */
+int32_t sd_set_greedy(sd_handle *h, int32_t enable);
+
 /* ---- single steps of the path, for parity checks and profiling --------------------------- */
 
 /* One drafter evaluation M_q(prefix o block, t = step/T) (Algorithm 1, loop body).
@@ -191,7 +206,8 @@ int32_t sd_set_linear_split(int32_t split);
 
 /* The launch sequences of sd_draft / sd_verify / sd_round are captured into HIP graphs on first
  * use (one per combination of batch, gamma, T and sequence lengths) and replayed afterwards; the
- * results are identical to eager launches.  enable = 0 turns replay off (it is also off while
+ * results are identical to eager launches.  (A sequence is launched eagerly the first time it is seen
+ * and captured the second time.)  enable = 0 turns replay off (it is also off while
  * profiling and when the handle runs on the NULL stream). */
 int32_t sd_set_graph_replay(sd_handle *h, int32_t enable);
 

@@ -24,7 +24,7 @@ EXPORTS = ["sd_vocab_pad", "sd_weight_count", "sd_weight_desc", "sd_weight_bytes
            "sd_destroy", "sd_last_error", "sd_prefill", "sd_draft", "sd_verify", "sd_round", "sd_drafter_logits",
            "sd_target_logits", "sd_sampling_scratch_bytes", "sd_unmask_sample", "sd_accept_resample", "sd_linear",
            "sd_profile_begin", "sd_profile_end", "sd_profile_count", "sd_profile_entry", "sd_set_graph_replay", "sd_set_linear_variant", "sd_norm_linear",
-           "sd_set_linear_split", "sd_linear_split_ticket_bytes"]
+           "sd_set_linear_split", "sd_linear_split_ticket_bytes", "sd_commit", "sd_set_greedy"]
 
 
 class SdModelConfig(C.Structure):
@@ -78,6 +78,8 @@ def lib() -> C.CDLL:
         L.sd_linear.restype = i32
         L.sd_linear.argtypes = [i32, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, i64, vp]
         L.sd_set_linear_split.restype = i32; L.sd_set_linear_split.argtypes = [i32]
+        L.sd_commit.restype = i32; L.sd_commit.argtypes = [vp, i32, C.POINTER(C.c_int32)]
+        L.sd_set_greedy.restype = i32; L.sd_set_greedy.argtypes = [vp, i32]
         L.sd_linear_split_ticket_bytes.restype = i64; L.sd_linear_split_ticket_bytes.argtypes = []
         L.sd_set_graph_replay.restype = i32; L.sd_set_graph_replay.argtypes = [vp, i32]
         L.sd_set_linear_variant.restype = i32; L.sd_set_linear_variant.argtypes = [i32]
@@ -255,6 +257,30 @@ class SpecDiff:
         tok = np.zeros(B, dtype=np.int32)
         self._check(lib().sd_round(self.h, B, _ip(flat), _ip(lens), gamma, T, seed, _ip(draft), _ip(n), _ip(tok)), "sd_round")
         return draft, n, tok
+
+    def sd_commit(self, n_accepted):
+        n = np.ascontiguousarray(n_accepted, dtype=np.int32)
+        self._check(lib().sd_commit(self.h, len(n), _ip(n)), "sd_commit")
+
+    def sd_set_greedy(self, enable: bool):
+        self._check(lib().sd_set_greedy(self.h, 1 if enable else 0), "sd_set_greedy")
+
+    def generate(self, prefixes, n_new: int, gamma: int, T: int, seed: int):
+        """Rounds of sd_round + sd_commit until every sequence has at least n_new new tokens; round i uses
+        seed + i.  -> (list of new-token arrays, list of per-round accepted counts [rounds, B])."""
+        seqs = [list(int(t) for t in p) for p in prefixes]
+        start = [len(s) for s in seqs]
+        accepted = []
+        rnd = 0
+        while min(len(s) - l for s, l in zip(seqs, start)) < n_new:
+            draft, n, tok = self.sd_round(seqs, gamma, T, seed + rnd)
+            self.sd_commit(n)
+            for b, s in enumerate(seqs):
+                s.extend(int(t) for t in draft[b, :n[b]])
+                s.append(int(tok[b]))
+            accepted.append(n.copy())
+            rnd += 1
+        return [np.array(s[l:], dtype=np.int64) for s, l in zip(seqs, start)], np.array(accepted)
 
     def sd_drafter_logits(self, sequences, gamma: int, step: int, T: int):
         """sequences: prefix o block per batch element (mask id = vocab).  -> device fp32 [B*gamma, ld]."""

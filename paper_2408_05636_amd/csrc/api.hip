@@ -5,6 +5,7 @@
 
 #include <string>
 #include <unordered_map>
+#include <unordered_set>
 #include <vector>
 
 #include "common.h"
@@ -284,10 +285,15 @@ struct sd_handle {
     std::vector<char> map_shadow[3];
     // captured launch sequences, keyed by everything that shapes them
     std::unordered_map<uint64_t, hipGraphExec_t> graphs;
+    std::unordered_set<uint64_t> seen;   // launch sequences run once so far (captured on their second use)
     bool use_graphs = true;
+    bool greedy = false;                 // temperature 0 instead of the stochastic rule
     // KV-cache state per sequence: number of cached positions and a hash of their tokens
     std::vector<int32_t> cached_len;
-    std::vector<uint64_t> cached_hash;
+    std::vector<uint64_t> cached_hash, cached_fnv;
+    // what the last verification scored, for sd_commit: per sequence the prefix length and its last token, and the draft
+    int pend_batch = 0, pend_gamma = 0;
+    std::vector<int32_t> pend_len, pend_tail, pend_draft;
     std::string err;
 };
 
@@ -364,11 +370,12 @@ int fail(sd_handle* h, int code, const std::string& msg) {
     return code;
 }
 
-uint64_t hash_tokens(const int32_t* t, int n) {
-    uint64_t x = 1469598103934665603ull;
+constexpr uint64_t kFnvBasis = 1469598103934665603ull;
+uint64_t fnv_extend(uint64_t x, const int32_t* t, int n) {
     for (int i = 0; i < n; ++i) { x ^= (uint32_t)t[i]; x *= 1099511628211ull; }
-    return x ^ (uint64_t)n;
+    return x;
 }
+uint64_t hash_tokens(const int32_t* t, int n) { return fnv_extend(kFnvBasis, t, n) ^ (uint64_t)n; }
 
 // Validate a ragged batch; returns total token count through *total.
 int check_batch(sd_handle* h, int batch, const int32_t* tokens, const int32_t* len, int vocab_limit, int64_t* total) {
@@ -489,7 +496,9 @@ int upload_rows(sd_handle* h, int mode, int batch, const int32_t* tokens, const 
     return SD_OK;
 }
 
-// Replay a launch sequence through a captured graph (capturing it on first use).  `key` must
+// Replay a launch sequence through a captured graph.  A sequence is launched eagerly the first time
+// its key is seen and captured the second time (a generation loop changes its lengths every round and
+// would otherwise pay for a capture it never replays).  `key` must
 // identify everything that shapes the sequence: the call, batch, gamma, T, every sequence length
 // and every pointer argument.  Falls back to eager launches when profiling is on, when the handle
 // runs on the legacy default stream, or when capture is not possible.
@@ -498,6 +507,10 @@ int replay(sd_handle* h, uint64_t key, F&& enqueue) {
     if (!h->use_graphs || h->prof.on || h->st == nullptr) return enqueue();
     auto it = h->graphs.find(key);
     if (it == h->graphs.end()) {
+        if (h->seen.insert(key).second) {
+            if (h->seen.size() > 65536) h->seen.clear();
+            return enqueue();
+        }
         if (h->graphs.size() >= 256) {
             for (auto& g : h->graphs) (void)hipGraphExecDestroy(g.second);
             h->graphs.clear();
@@ -644,10 +657,23 @@ int do_prefill(sd_handle* h, int batch, const int32_t* prefix, const int32_t* le
     int64_t off = 0;
     for (int b = 0; b < batch; ++b) {
         h->cached_len[b] = len[b] - 1;
-        h->cached_hash[b] = hash_tokens(prefix + off, len[b] - 1);
+        h->cached_fnv[b] = fnv_extend(kFnvBasis, prefix + off, len[b] - 1);
+        h->cached_hash[b] = h->cached_fnv[b] ^ (uint64_t)(len[b] - 1);
         off += len[b];
     }
+    h->pend_batch = 0;
     return SD_OK;
+}
+
+// Remember what a verification scored (the cache now also holds the K, V rows of prefix[L-1] and the draft).
+void note_pending(sd_handle* h, int batch, const int32_t* prefix, const int32_t* len, int gamma, const int32_t* draft) {
+    h->pend_batch = batch;
+    h->pend_gamma = gamma;
+    h->pend_len.assign(len, len + batch);
+    h->pend_tail.resize(batch);
+    int64_t off = 0;
+    for (int b = 0; b < batch; ++b) { off += len[b]; h->pend_tail[b] = prefix[off - 1]; }
+    h->pend_draft.assign(draft, draft + (int64_t)batch * gamma);
 }
 
 bool cache_matches(sd_handle* h, int batch, const int32_t* prefix, const int32_t* len) {
@@ -684,8 +710,13 @@ int enqueue_draft(sd_handle* h, int batch, int gamma, int T) {
         if (rc) return rc;
         rc = run_head(h, m, rm.blk, batch * gamma, B.logits_d);
         if (rc) return rc;
-        SD_LAUNCH(h, "unmask_sample(k_row_stats+k_unmask_sample)", 3.0 * batch * gamma / T * m.ld * 4, 0,
-                  launch_unmask_sample(B.logits_d, batch, gamma, m.c.vocab, j, B.seed, B.z, B.q, B.qtok, ss, h->st));
+        if (h->greedy) {
+            SD_LAUNCH(h, "unmask_greedy(k_chunk_argmax+k_greedy_reveal)", 1.0 * batch * gamma / T * m.ld * 4, 0,
+                      launch_unmask_greedy(B.logits_d, batch, gamma, m.c.vocab, j, B.seed, B.z, B.qtok, ss, h->st));
+        } else {
+            SD_LAUNCH(h, "unmask_sample(k_row_stats+k_unmask_sample)", 3.0 * batch * gamma / T * m.ld * 4, 0,
+                      launch_unmask_sample(B.logits_d, batch, gamma, m.c.vocab, j, B.seed, B.z, B.q, B.qtok, ss, h->st));
+        }
     }
     return SD_OK;
 }
@@ -709,6 +740,11 @@ int enqueue_target(sd_handle* h) {
 
 int enqueue_accept(sd_handle* h, int batch, int gamma, const float* q_dev) {
     const SampleScratch ss = sampling_scratch(h->buf.sample_scratch, (int)h->lim.rows_head, h->target.c.vocab);
+    if (h->greedy) {
+        SD_LAUNCH(h, "accept_greedy(k_chunk_argmax+k_greedy_accept)", (double)batch * (gamma + 1) * h->target.ld * 4, 0,
+                  launch_accept_greedy(h->buf.logits_t, h->buf.z, batch, gamma, h->target.c.vocab, h->buf.n_acc, h->buf.tok, ss, h->st));
+        return SD_OK;
+    }
     SD_LAUNCH(h, "accept_resample(k_row_stats+k_accept+k_final_partial+k_final_sample)",
               ((double)batch * (gamma + 1) + 4.0 * batch) * h->target.ld * 4, 0,
               launch_accept_resample(h->buf.logits_t, q_dev, h->buf.z, batch, gamma, h->target.c.vocab, h->buf.seed,
@@ -830,6 +866,7 @@ int32_t sd_create(const sd_model_config* target, const sd_model_config* drafter,
     h->st = static_cast<hipStream_t>(hip_stream);
     h->cached_len.assign(max_batch, -1);
     h->cached_hash.assign(max_batch, 0);
+    h->cached_fnv.assign(max_batch, 0);
     const int64_t n_out = (int64_t)max_batch * (gamma_max + 2) + 16;
     struct { void** p; int64_t bytes; } pinned[] = {
         {reinterpret_cast<void**>(&h->stage_maps[0]), h->lim.map_bytes},
@@ -889,7 +926,7 @@ int32_t sd_draft(sd_handle* h, int32_t batch, const int32_t* prefix, const int32
     if (rc) return rc;
     rc = prepare_draft(h, batch, prefix, prefix_len, n, gamma, seed);
     if (rc) return rc;
-    rc = replay(h, shape_key(1, batch, gamma, T, prefix_len, nullptr), [&] { return enqueue_draft(h, batch, gamma, T); });
+    rc = replay(h, shape_key(1 + (h->greedy ? 16 : 0), batch, gamma, T, prefix_len, nullptr), [&] { return enqueue_draft(h, batch, gamma, T); });
     if (rc) return rc;
     const int64_t cnt = (int64_t)batch * gamma;
     SD_HIP(h, hipMemcpyAsync(h->stage_out, h->buf.z, cnt * 4, hipMemcpyDeviceToHost, h->st));
@@ -919,14 +956,17 @@ int32_t sd_verify(sd_handle* h, int32_t batch, const int32_t* prefix, const int3
     SD_HIP(h, hipMemcpyAsync(h->buf.seed, h->stage_seed, 8, hipMemcpyHostToDevice, h->st));
     rc = prepare_target(h, batch, prefix, prefix_len, n, gamma);
     if (rc) return rc;
-    rc = replay(h, shape_key(2, batch, gamma, 0, prefix_len, q_dev), [&] {
+    rc = replay(h, shape_key(2 + (h->greedy ? 16 : 0), batch, gamma, 0, prefix_len, q_dev), [&] {
         const int r2 = enqueue_target(h);
         return r2 ? r2 : enqueue_accept(h, batch, gamma, q_dev);
     });
     if (rc) return rc;
     rc = read_back(h, n_accepted_out, h->buf.n_acc, batch);
     if (rc) return rc;
-    return read_back(h, token_out, h->buf.tok, batch);
+    rc = read_back(h, token_out, h->buf.tok, batch);
+    if (rc) return rc;
+    note_pending(h, batch, prefix, prefix_len, gamma, draft);
+    return SD_OK;
 }
 
 int32_t sd_round(sd_handle* h, int32_t batch, const int32_t* prefix, const int32_t* prefix_len, int32_t gamma,
@@ -942,7 +982,7 @@ int32_t sd_round(sd_handle* h, int32_t batch, const int32_t* prefix, const int32
     if (rc) return rc;
     rc = prepare_target(h, batch, prefix, prefix_len, n, gamma);
     if (rc) return rc;
-    rc = replay(h, shape_key(3, batch, gamma, T, prefix_len, nullptr), [&] {
+    rc = replay(h, shape_key(3 + (h->greedy ? 16 : 0), batch, gamma, T, prefix_len, nullptr), [&] {
         int r2 = enqueue_draft(h, batch, gamma, T);
         if (!r2) r2 = enqueue_target(h);
         return r2 ? r2 : enqueue_accept(h, batch, gamma, h->buf.q);
@@ -957,6 +997,31 @@ int32_t sd_round(sd_handle* h, int32_t batch, const int32_t* prefix, const int32
     memcpy(draft_out, so, cnt * 4);
     memcpy(n_accepted_out, so + cnt, batch * 4);
     memcpy(token_out, so + cnt + batch, batch * 4);
+    note_pending(h, batch, prefix, prefix_len, gamma, draft_out);
+    return SD_OK;
+}
+
+int32_t sd_commit(sd_handle* h, int32_t batch, const int32_t* n_accepted) {
+    if (!h) return SD_ERR_ARG;
+    if (!n_accepted) return fail(h, SD_ERR_ARG, "n_accepted is null");
+    if (h->pend_batch == 0 || batch != h->pend_batch) return fail(h, SD_ERR_STATE, "no verification of this batch to commit");
+    for (int b = 0; b < batch; ++b)
+        if (n_accepted[b] < 0 || n_accepted[b] > h->pend_gamma) return fail(h, SD_ERR_ARG, "n_accepted outside [0, gamma]");
+    for (int b = 0; b < batch; ++b) {
+        if (h->cached_len[b] != h->pend_len[b] - 1) return fail(h, SD_ERR_STATE, "KV cache no longer matches the verified prefix");
+        uint64_t x = fnv_extend(h->cached_fnv[b], &h->pend_tail[b], 1);
+        x = fnv_extend(x, h->pend_draft.data() + (int64_t)b * h->pend_gamma, n_accepted[b]);
+        h->cached_fnv[b] = x;
+        h->cached_len[b] = h->pend_len[b] + n_accepted[b];
+        h->cached_hash[b] = x ^ (uint64_t)h->cached_len[b];
+    }
+    h->pend_batch = 0;
+    return SD_OK;
+}
+
+int32_t sd_set_greedy(sd_handle* h, int32_t enable) {
+    if (!h) return SD_ERR_ARG;
+    h->greedy = enable != 0;
     return SD_OK;
 }
 

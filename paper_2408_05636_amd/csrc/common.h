@@ -131,4 +131,10 @@ hipError_t launch_accept_resample(const float* p_logits, const float* q, const i
                                   int gamma, int vocab, const uint64_t* seed, int32_t* n_acc, int32_t* token,
                                   const SampleScratch& s, hipStream_t st);
 
+// Temperature 0: argmax at reveal (qtok = 1, no q row); accept iff the drafted token is the target's argmax.
+hipError_t launch_unmask_greedy(const float* logits, int batch, int gamma, int vocab, int step, const uint64_t* seed,
+                                int32_t* z, float* qtok, const SampleScratch& s, hipStream_t st);
+hipError_t launch_accept_greedy(const float* p_logits, const int32_t* draft, int batch, int gamma, int vocab,
+                                int32_t* n_acc, int32_t* token, const SampleScratch& s, hipStream_t st);
+
 }  // namespace sd

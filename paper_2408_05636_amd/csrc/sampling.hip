@@ -345,6 +345,86 @@ __global__ __launch_bounds__(kThreads) void k_final_sample(const float* __restri
     if (threadIdx.x == 0) token[b] = v;
 }
 
+// ---------------------------------------------------------------- temperature 0
+// The one-hot limit of the rule: a revealed slot takes the argmax of its row, a drafted token is accepted
+// iff it is the argmax of the target's row, and the extra token is the argmax of row n.  Arg-maxima are
+// taken on the stored fp32 logits, lowest column on ties.
+struct MaxAt { float v; int i; };
+__device__ inline MaxAt better(MaxAt a, MaxAt b) { return (b.v > a.v || (b.v == a.v && b.i < a.i)) ? b : a; }
+__device__ inline MaxAt wave_best(MaxAt a) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        MaxAt b;
+        b.v = __shfl_xor(a.v, o, 64);
+        b.i = __shfl_xor(a.i, o, 64);
+        a = better(a, b);
+    }
+    return a;
+}
+
+// grid (n_chunks, rows): per chunk the largest logit and its column.  z != NULL: drafter mode, rows that are
+// not revealed at this step are skipped (and flagged in active[]).
+__global__ __launch_bounds__(kThreads) void k_chunk_argmax(const float* __restrict__ logits, int ld, int vocab,
+                                                           const int32_t* __restrict__ z, int gamma, int step,
+                                                           const uint64_t* __restrict__ seed_p, float* __restrict__ part_v,
+                                                           int32_t* __restrict__ part_i, int32_t* __restrict__ active) {
+    __shared__ float shv[4];
+    __shared__ int shi[4];
+    const int row = blockIdx.y, c = blockIdx.x, nch = gridDim.x;
+    if (z != nullptr) {
+        const bool act = (z[row] == vocab) && reveal_now(row % gamma, step, row / gamma, *seed_p);
+        if (c == 0 && threadIdx.x == 0) active[row] = act ? 1 : 0;
+        if (!act) return;
+    }
+    const int col0 = c * kChunk + threadIdx.x * 4;
+    float l[4];
+    load4(logits + (size_t)row * ld, col0, vocab, l);            // columns >= vocab read as -inf
+    MaxAt m{l[0], col0};
+#pragma unroll
+    for (int i = 1; i < 4; ++i) m = better(m, MaxAt{l[i], col0 + i});
+    m = wave_best(m);
+    if ((threadIdx.x & 63) == 0) { shv[threadIdx.x >> 6] = m.v; shi[threadIdx.x >> 6] = m.i; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        MaxAt b{shv[0], shi[0]};
+        for (int w = 1; w < 4; ++w) b = better(b, MaxAt{shv[w], shi[w]});
+        part_v[(size_t)row * nch + c] = b.v;
+        part_i[(size_t)row * nch + c] = b.i;
+    }
+}
+
+// One wave: best chunk of a row.
+__device__ inline MaxAt row_best(const float* pv, const int32_t* pi, int nch, int lane) {
+    MaxAt m{-INFINITY, INT_MAX};
+    for (int i = lane; i < nch; i += 64) m = better(m, MaxAt{pv[i], pi[i]});
+    return wave_best(m);
+}
+
+// grid (rows), one wave: revealed slots take the argmax of their row.
+__global__ __launch_bounds__(64) void k_greedy_reveal(const float* __restrict__ part_v, const int32_t* __restrict__ part_i,
+                                                      int nch, const int32_t* __restrict__ active,
+                                                      int32_t* __restrict__ z, float* __restrict__ qtok) {
+    const int row = blockIdx.x;
+    if (!active[row]) return;
+    const MaxAt m = row_best(part_v + (size_t)row * nch, part_i + (size_t)row * nch, nch, threadIdx.x);
+    if (threadIdx.x == 0) { z[row] = m.i; qtok[row] = 1.f; }
+}
+
+// grid (batch), one wave: n = first drafted token that is not the argmax of its target row, token = argmax of row n.
+__global__ __launch_bounds__(64) void k_greedy_accept(const float* __restrict__ part_v, const int32_t* __restrict__ part_i,
+                                                      int nch, const int32_t* __restrict__ draft, int gamma,
+                                                      int32_t* __restrict__ n_acc, int32_t* __restrict__ token) {
+    const int b = blockIdx.x;
+    int n = gamma, tok = 0;
+    for (int k = 0; k <= gamma; ++k) {
+        const size_t o = ((size_t)b * (gamma + 1) + k) * nch;
+        const MaxAt m = row_best(part_v + o, part_i + o, nch, threadIdx.x);
+        tok = m.i;
+        if (k < gamma && draft[b * gamma + k] != m.i) { n = k; break; }
+    }
+    if (threadIdx.x == 0) { n_acc[b] = n; token[b] = tok; }
+}
+
 // z <- value (the all-[MASK] start state of the block); a kernel rather than a memset so that it can
 // live inside a captured graph.
 __global__ void k_fill_i32(int32_t* __restrict__ p, int n, int v) {
@@ -392,6 +472,26 @@ hipError_t launch_unmask_sample(const float* logits, int batch, int gamma, int v
     k_row_stats<<<grid, kThreads, 0, st>>>(logits, ld, vocab, z, gamma, step, seed, s.part_m, s.part_s, s.active);
     k_unmask_sample<<<grid, kThreads, 0, st>>>(logits, ld, vocab, gamma, step, seed, s.part_m, s.part_s, s.active, z,
                                                q, qtok);
+    return hipGetLastError();
+}
+
+hipError_t launch_unmask_greedy(const float* logits, int batch, int gamma, int vocab, int step, const uint64_t* seed,
+                                int32_t* z, float* qtok, const SampleScratch& s, hipStream_t st) {
+    const int rows = batch * gamma, nch = n_chunks(vocab), ld = vocab_pad(vocab);
+    float* pv = reinterpret_cast<float*>(s.part_m);          // the fp64 partial arrays are free in this mode
+    int32_t* pi = reinterpret_cast<int32_t*>(s.part_s);
+    k_chunk_argmax<<<dim3(nch, rows), kThreads, 0, st>>>(logits, ld, vocab, z, gamma, step, seed, pv, pi, s.active);
+    k_greedy_reveal<<<rows, 64, 0, st>>>(pv, pi, nch, s.active, z, qtok);
+    return hipGetLastError();
+}
+
+hipError_t launch_accept_greedy(const float* p_logits, const int32_t* draft, int batch, int gamma, int vocab,
+                                int32_t* n_acc, int32_t* token, const SampleScratch& s, hipStream_t st) {
+    const int rows = batch * (gamma + 1), nch = n_chunks(vocab), ld = vocab_pad(vocab);
+    float* pv = reinterpret_cast<float*>(s.part_m);
+    int32_t* pi = reinterpret_cast<int32_t*>(s.part_s);
+    k_chunk_argmax<<<dim3(nch, rows), kThreads, 0, st>>>(p_logits, ld, vocab, nullptr, gamma, 0, nullptr, pv, pi, s.active);
+    k_greedy_accept<<<batch, 64, 0, st>>>(pv, pi, nch, draft, gamma, n_acc, token);
     return hipGetLastError();
 }
 
