@@ -189,8 +189,10 @@ Limits limits_of(const sd_model_config& t, const sd_model_config& d, int max_bat
     l.ffmax = ffw(t) > ffw(d) ? ffw(t) : ffw(d);
     l.ew = (t.dtype == SD_DTYPE_F32 || d.dtype == SD_DTYPE_F32) ? 4 : 2;
     l.prefix_cap = l.max_rows;
+    const int64_t max_heads = t.n_head > d.n_head ? t.n_head : d.n_head;
+    const int64_t order_cap = 8 * (l.max_rows / 32 + max_batch + 1) * max_heads;      // attention launch order, see upload_rows
     l.map_bytes = align_up((l.prefix_cap + 4 * l.max_rows + (int64_t)max_batch * gamma_max) * 4 + 32 + l.max_rows * 8 +
-                           l.max_rows * (int64_t)sizeof(AttnTile), 256);
+                           l.max_rows * (int64_t)sizeof(AttnTile) + 16 + order_cap * 4, 256);
     return l;
 }
 
@@ -244,6 +246,8 @@ struct MapSet {
     int32_t *tokens = nullptr, *src = nullptr, *pos = nullptr, *seq = nullptr, *kvl = nullptr, *blk = nullptr;
     int64_t* kv_off = nullptr;
     AttnTile* tiles = nullptr;
+    int32_t* order = nullptr;            // attention workgroup -> tile | head << 20 (or -1), see upload_rows
+    int n_order = 0;
     int rows = 0, n_tiles = 0, max_kv = 0;
     double kv_sum = 0, kv_rows = 0;     // sum of kv_len over rows; distinct key rows
     int64_t bytes = -1;
@@ -420,14 +424,47 @@ int upload_rows(sd_handle* h, int mode, int batch, const int32_t* tokens, const 
     o = align_up(o, 16);
     const int64_t o_tiles = o;
     o += n_tiles * (int64_t)sizeof(AttnTile);
-    const int64_t bytes = o;
+    o = align_up(o, 16);
+    const int64_t o_order = o;            // filled below, its size depends on the grouping
     char* hb = h->stage_maps[mode];
+    // Attention launch order.  Workgroups go to the 8 XCDs round-robin by linear id and every XCD has its own
+    // L2: all query tiles and query heads that read the same keys and values (one sequence, one KV head) are
+    // placed on one XCD, back to back, so that K and V are fetched into one L2 once instead of into all of
+    // them by turns.  When all keys and values fit any L2 anyway the plain order spreads the load better.
+    const int n_kv_groups = m.c.n_kv_head, q_per_kv = m.c.n_head / m.c.n_kv_head;
+    std::vector<std::vector<int32_t>> per_xcd(8);
+    {
+        double kv_bytes = 0;
+        for (int b = 0; b < batch; ++b) kv_bytes += 2.0 * m.ew * m.dkv * (mode == 0 ? len[b] + gamma : (mode == 1 ? len[b] + gamma : len[b] - 1));
+        const bool grouped = kv_bytes > 2.0e6;
+        int64_t t0 = 0, lin = 0;
+        for (int b = 0; b < batch; ++b) {
+            const int64_t rb = mode == 0 ? len[b] + gamma : (mode == 1 ? gamma + 1 : len[b] - 1);
+            const int64_t ntb = (rb + 31) / 32;
+            for (int g = 0; g < n_kv_groups; ++g)
+                for (int qh = 0; qh < q_per_kv; ++qh)
+                    for (int64_t t = 0; t < ntb; ++t, ++lin)
+                        per_xcd[grouped ? (b * n_kv_groups + g) % 8 : lin % 8].push_back((int32_t)(t0 + t) | ((g * q_per_kv + qh) << 20));
+            t0 += ntb;
+        }
+    }
+    size_t per_max = 0;
+    for (auto& v : per_xcd) per_max = v.size() > per_max ? v.size() : per_max;
+    const int64_t n_order = 8 * (int64_t)per_max;
+    o += n_order * 4;
+    const int64_t bytes = o;
+    if (bytes > h->lim.map_bytes || n_tiles >= (1 << 20)) return fail(h, SD_ERR_SHAPE, "row maps exceed the workspace");
     int32_t *s_tok = (int32_t*)(hb + o_tok), *s_src = (int32_t*)(hb + o_src), *s_pos = (int32_t*)(hb + o_pos),
             *s_seq = (int32_t*)(hb + o_seq), *s_kvl = (int32_t*)(hb + o_kvl), *s_blk = (int32_t*)(hb + o_blk);
     int64_t* s_off = (int64_t*)(hb + o_off);
     AttnTile* s_tiles = (AttnTile*)(hb + o_tiles);
     memset(hb, 0, bytes);                                 // padding bytes take part in the "unchanged" comparison
     memcpy(s_tok, tokens, n_tokens * sizeof(int32_t));
+    {
+        int32_t* s_order = (int32_t*)(hb + o_order);
+        for (int64_t j = 0; j < (int64_t)per_max; ++j)
+            for (int x = 0; x < 8; ++x) s_order[j * 8 + x] = j < (int64_t)per_xcd[x].size() ? per_xcd[x][j] : -1;
+    }
     int64_t r = 0, tok_off = 0, nt = 0;
     int max_kv = 0;
     double kv_sum = 0, kv_rows = 0;
@@ -491,6 +528,7 @@ int upload_rows(sd_handle* h, int mode, int batch, const int32_t* tokens, const 
     ms.tokens = (int32_t*)(db + o_tok); ms.src = (int32_t*)(db + o_src); ms.pos = (int32_t*)(db + o_pos);
     ms.seq = (int32_t*)(db + o_seq); ms.kvl = (int32_t*)(db + o_kvl);
     ms.blk = (int32_t*)(db + o_blk); ms.kv_off = (int64_t*)(db + o_off); ms.tiles = (AttnTile*)(db + o_tiles);
+    ms.order = (int32_t*)(db + o_order); ms.n_order = (int)n_order;
     ms.rows = (int)rows; ms.n_tiles = (int)n_tiles; ms.max_kv = max_kv; ms.kv_sum = kv_sum; ms.kv_rows = kv_rows;
     ms.bytes = bytes;
     return SD_OK;
@@ -606,6 +644,7 @@ int run_layers(sd_handle* h, const Model& m, const MapSet& rm, const float* temb
         a.out = B.att; a.out_ld = d;
         a.rows = rows; a.n_head = c.n_head; a.n_kv_head = c.n_kv_head; a.d_head = m.dh; a.max_kv = rm.max_kv;
         a.tiles = rm.tiles; a.n_tiles = rm.n_tiles;
+        a.order = rm.order; a.n_order = rm.n_order;
         if (cached) {
             const int64_t per_layer = (int64_t)h->max_batch * c.n_ctx * m.dkv * m.ew;
             char* kc = static_cast<char*>(B.kcache) + i * per_layer;

@@ -9,11 +9,14 @@
 //                      -> lane = query, its 16 accumulators = 16 keys: row max / sum are in-lane,
 //                         plus one exchange between the two lane halves;
 //   O^T += V^T P^T     B = P^T comes straight from the S^T accumulators (cast to bf16);
-//                      A = V^T needs keys contiguous per d: the 32 x d_head V block is transposed
-//                      through a wave-private LDS tile (no workgroup barrier in the loop).
-// The K rows are fed to the first MFMA in a permuted order chosen so that accumulator e of lane
-// half h is key 16h + e of the block: then the P^T operand of MFMA step s is registers 8s..8s+7 and
-// the matching V^T operand is 16 contiguous bytes of the LDS tile.
+//                      A = V^T needs keys contiguous per d.  The matrix cores transpose the block:
+//                      V (rows = keys, as loaded) times a 0/1 selection matrix lands in the
+//                      accumulators with lane = d and registers = keys, exactly (a bf16 value times one
+//                      plus zeros), which after a cast back to bf16 is the V^T operand.  No LDS, no
+//                      barrier and no cross-lane traffic in the loop.
+// The K and V rows are fed to those MFMAs in a permuted order chosen so that accumulator e of lane
+// half h is key 16h + e of the block: then the P^T operand of MFMA step s is registers 8s..8s+7 of
+// the scores and the matching V^T operand is registers 8s..8s+7 of the transposed block.
 // A workgroup is 4 waves: either 4 query tiles (large batches) or 4 interleaved key ranges of one
 // tile merged through LDS (few query rows: the target's gamma+1 rows, batch-1 drafter).
 #include "common.h"
@@ -23,7 +26,6 @@ namespace sd {
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
 
-constexpr int kVtLd = 40;    // LDS row stride of the transposed V tile (32 keys + 8 pad), in elements
 
 typedef __attribute__((__vector_size__(4 * sizeof(unsigned int)))) unsigned int u32x4;
 typedef __attribute__((__vector_size__(2 * sizeof(unsigned int)))) unsigned int u32x2;
@@ -31,19 +33,28 @@ constexpr int kBufFlags = 0x00020000;          // raw buffer, 32-bit data format
 constexpr uint32_t kOutOfRange = 0x80000000u;  // VGPR offset of accesses that must not happen (buffers are < 2 GiB)
 
 template <int DH, bool KSPLIT>
-__global__ __launch_bounds__(256) void k_attention_mfma(AttnArgs a) {
+__global__ __launch_bounds__(256, (DH == 64 ? 2 : 1)) void k_attention_mfma(AttnArgs a) {
     constexpr int NCH = DH / 64;     // 64-wide chunks of a q / k row
     constexpr int DT = DH / 32;      // 32-row tiles of O^T
     constexpr int NV = DH / 16;      // 16-byte pieces of a V row handled per lane
-    __shared__ __attribute__((aligned(16))) bf16_t vt_all[4][DH * kVtLd];
-    __shared__ float mrg_m[KSPLIT ? 3 : 1][64], mrg_l[KSPLIT ? 3 : 1][64];
-    __shared__ float mrg_o[KSPLIT ? 3 : 1][KSPLIT ? DT * 16 : 1][64];
+    // Per wave: a K tile and a V tile of 32 keys (NCH x 4 KB each), private to the wave.  After the loop the
+    // key-splitting variant reuses the memory to merge its four partial results.
+    constexpr int kStageVecs = 4 * 2 * NCH * 256;                              // u32x4 units
+    constexpr int kMergeFloats = KSPLIT ? 3 * (2 + DT * 16) * 64 : 0;
+    constexpr int kSmemVecs = kStageVecs > (kMergeFloats + 3) / 4 ? kStageVecs : (kMergeFloats + 3) / 4;
+    __shared__ u32x4 smem[kSmemVecs];
 
     // wave-uniform values are kept in scalar registers (tile description, buffer descriptors, block counters)
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int r = lane & 31, half = lane >> 5;
-    const int tile = KSPLIT ? (int)blockIdx.x : (int)blockIdx.x * 4 + wave;
-    const int head = blockIdx.y;
+    int tile = KSPLIT ? (int)blockIdx.x : (int)blockIdx.x * 4 + wave;
+    int head = blockIdx.y;
+    if (KSPLIT && a.order != nullptr) {                 // XCD-aware launch order supplied by the host
+        const int ent = a.order[blockIdx.x];
+        if (ent < 0) return;                            // padding entry (whole workgroup)
+        tile = ent & 0xFFFFF;
+        head = ent >> 20;
+    }
     if (!KSPLIT && tile >= a.n_tiles) return;           // whole wave; this variant has no barriers
 
     // One scalar load brings everything that is uniform over the tile; the per-row key counts, the query
@@ -58,8 +69,11 @@ __global__ __launch_bounds__(256) void k_attention_mfma(AttnArgs a) {
     const __amdgpu_buffer_rsrc_t rk = __builtin_amdgcn_make_buffer_rsrc(kbase, 0, kv_bytes, kBufFlags);
     const __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc(vbase, 0, kv_bytes, kBufFlags);
     const int kvl = a.kv_len[qrow];
+    int kv_min = kvl;                                    // smallest key count among the tile's rows (wave-uniform)
+#pragma unroll
+    for (int o_ = 32; o_ > 0; o_ >>= 1) kv_min = min(kv_min, __shfl_xor(kv_min, o_, 64));
+    kv_min = __builtin_amdgcn_readfirstlane(kv_min);
     const bf16_t* Qp = static_cast<const bf16_t*>(a.q) + (size_t)qrow * a.q_ld + (size_t)head * DH + 32 * half;
-    bf16_t* vt = vt_all[wave];
 
     bf16x8 qf[NCH][4];
 #pragma unroll
@@ -72,8 +86,29 @@ __global__ __launch_bounds__(256) void k_attention_mfma(AttnArgs a) {
     // Byte offsets inside the key / value buffers of this lane's row of block 0.  Rows beyond kv_max fall
     // outside the buffer and read as 0 (they are masked below), so the last block needs no special case and
     // the block after the last can be prefetched unconditionally.
-    const uint32_t k_lane = ((uint32_t)pi_r * (uint32_t)a.kv_ld + 32u * half) * 2u;
-    const uint32_t v_lane = ((uint32_t)r * (uint32_t)a.kv_ld + 8u * half) * 2u;
+    // Global loads are coalesced (8 consecutive lanes cover one 128-byte piece of a key row; one row per lane
+    // would leave the loads bound by the address unit, 32 cache lines per instruction) and pass through the
+    // wave-private LDS tile, XOR-swizzled by 16-byte pieces, into the operand layout -- lane = key pi(r).
+    const int lrow = lane >> 3, pc = lane & 7;
+    const uint32_t kv_lane = ((uint32_t)lrow * (uint32_t)a.kv_ld + 8u * pc) * 2u;
+    const uint32_t row8_bytes = 8u * (uint32_t)a.kv_ld * 2u;
+    u32x4* const stage_k = smem + wave * (2 * NCH * 256);
+    u32x4* const stage_v = stage_k + NCH * 256;
+    // piece p of tile row x sits at piece p ^ key(x); the 16 rows a fragment read touches per cycle group are
+    // {0..7, 16..23} or {8..15, 24..31} (pi of 16 consecutive lanes): bit 4 of the row separates the two halves.
+    int wslot[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int row = 8 * i + lrow;
+        wslot[i] = row * 8 + (pc ^ ((row & 7) ^ ((row >> 4) & 1)));
+    }
+    const int rkey = (pi_r & 7) ^ ((pi_r >> 4) & 1);
+    // Selection matrix of the transposing MFMA, k chunk c2 (16 values of d): B[k][col] = 1 iff 16 c2 + k == col.
+    bf16x8 sel[2];
+#pragma unroll
+    for (int c2 = 0; c2 < 2; ++c2)
+#pragma unroll
+        for (int u = 0; u < 8; ++u) sel[c2][u] = static_cast<bf16_t>((16 * c2 + 8 * half + u == r) ? 1.f : 0.f);
     const uint32_t blk_bytes = 32u * (uint32_t)a.kv_ld * 2u;
 
     float m_run = -INFINITY, l_run = 0.f;
@@ -86,78 +121,91 @@ __global__ __launch_bounds__(256) void k_attention_mfma(AttnArgs a) {
 
     const int n_blocks = (kv_max + 31) / 32;
     constexpr int kStep = KSPLIT ? 4 : 1;
-    u32x4 kc[NCH][4], vc[NV], kn[NCH][4], vn[NV];
+    u32x4 kc[NCH][4], vc[NCH][4], kn[NCH][4], vn[NCH][4];
 #define SD_LOAD_BLOCK(KR, VR, KB)                                                                        \
     {                                                                                                    \
-        const uint32_t ko_ = k_lane + (uint32_t)(KB) * blk_bytes, vo_ = v_lane + (uint32_t)(KB) * blk_bytes; \
-        _Pragma("unroll") for (int c = 0; c < NCH; ++c) _Pragma("unroll") for (int q4 = 0; q4 < 4; ++q4) \
-            KR[c][q4] = __builtin_amdgcn_raw_buffer_load_b128(rk, ko_ + (uint32_t)(c * 128 + q4 * 16), 0, 0); \
-        _Pragma("unroll") for (int i = 0; i < NV; ++i)                                                   \
-            VR[i] = __builtin_amdgcn_raw_buffer_load_b128(rv, vo_ + (uint32_t)(i * 32), 0, 0);            \
+        const uint32_t o_ = kv_lane + (uint32_t)(KB) * blk_bytes;                                        \
+        _Pragma("unroll") for (int c = 0; c < NCH; ++c) _Pragma("unroll") for (int i = 0; i < 4; ++i) {  \
+            KR[c][i] = __builtin_amdgcn_raw_buffer_load_b128(rk, o_ + (uint32_t)i * row8_bytes + (uint32_t)(c * 128), 0, 0); \
+            VR[c][i] = __builtin_amdgcn_raw_buffer_load_b128(rv, o_ + (uint32_t)i * row8_bytes + (uint32_t)(c * 128), 0, 0); \
+        }                                                                                                \
     }
+// One key block: scores, online softmax, transpose of the V block, accumulation.  KC / VC: registers of
+// this block; the caller has already requested the next block into the other register set.
+#define SD_ATTN_BLOCK(KC, VC, KB)                                                                        \
+    {                                                                                                    \
+        /* LDS operations of one wave execute in order: no barrier around the private tiles */           \
+        _Pragma("unroll") for (int c = 0; c < NCH; ++c) _Pragma("unroll") for (int i = 0; i < 4; ++i) {  \
+            stage_k[c * 256 + wslot[i]] = KC[c][i];                                                      \
+            stage_v[c * 256 + wslot[i]] = VC[c][i];                                                      \
+        }                                                                                                \
+        floatx16 s;                                                                                      \
+        _Pragma("unroll") for (int e = 0; e < 16; ++e) s[e] = 0.f;                                       \
+        _Pragma("unroll") for (int c = 0; c < NCH; ++c) _Pragma("unroll") for (int q4 = 0; q4 < 4; ++q4) \
+            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                                                 \
+                __builtin_bit_cast(bf16x8, stage_k[c * 256 + pi_r * 8 + ((4 * half + q4) ^ rkey)]), qf[c][q4], s, 0, 0, 0); \
+        /* V^T of the block: tile t (d = 32 t ..) = sum over its two 16-wide d chunks of V_chunk x selection */ \
+        floatx16 vt_[DT];                                                                                \
+        _Pragma("unroll") for (int t = 0; t < DT; ++t) {                                                 \
+            _Pragma("unroll") for (int e = 0; e < 16; ++e) vt_[t][e] = 0.f;                              \
+            _Pragma("unroll") for (int c2 = 0; c2 < 2; ++c2) {                                           \
+                const int pv_ = 2 * (2 * t + c2) + half;              /* 16-byte piece of the V row: d = 8 pv_ .. */ \
+                vt_[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                                        \
+                    __builtin_bit_cast(bf16x8, stage_v[(pv_ >> 3) * 256 + pi_r * 8 + ((pv_ & 7) ^ rkey)]), sel[c2], vt_[t], 0, 0, 0); \
+            }                                                                                            \
+        }                                                                                                \
+        /* online softmax on the raw scores (the scale is positive and is applied inside the exponent);     \
+           accumulator e of this lane is key KB*32 + 16*half + e.  Only blocks that reach past the smallest \
+           key count of the tile need masking. */                                                         \
+        if ((KB) * 32 + 32 > kv_min) {                                                                   \
+            _Pragma("unroll") for (int e = 0; e < 16; ++e)                                               \
+                s[e] = ((KB) * 32 + 16 * half + e < kvl) ? s[e] : -INFINITY;                             \
+        }                                                                                                \
+        float mb_ = fmaxf(s[0], s[1]);                                                                   \
+        _Pragma("unroll") for (int e = 2; e < 16; ++e) mb_ = fmaxf(mb_, s[e]);                           \
+        mb_ = fmaxf(mb_, __shfl_xor(mb_, 32, 64));                                                       \
+        const float m_new_ = fmaxf(m_run, mb_);                                                          \
+        const float m_fin_ = fmaxf(m_new_, -1e30f);              /* finite even if no key was visible yet */ \
+        const float msc_ = m_fin_ * scale;                                                               \
+        const float alpha_ = __builtin_amdgcn_exp2f((m_run - m_fin_) * scale);   /* 0 on the first visible block */ \
+        float psum_ = 0.f;                                                                               \
+        bf16x8 pf_[2];                                                                                   \
+        _Pragma("unroll") for (int e = 0; e < 16; ++e) {                                                 \
+            const float p_ = __builtin_amdgcn_exp2f(fmaf(s[e], scale, -msc_));                           \
+            psum_ += p_;                                                                                 \
+            pf_[e >> 3][e & 7] = static_cast<bf16_t>(p_);                                                \
+        }                                                                                                \
+        l_run = l_run * alpha_ + psum_;                                                                  \
+        m_run = m_new_;                                                                                  \
+        if (__builtin_amdgcn_ballot_w64(alpha_ != 1.f) != 0) {    /* some row's maximum moved */          \
+            _Pragma("unroll") for (int t = 0; t < DT; ++t) _Pragma("unroll") for (int e = 0; e < 16; ++e) o[t][e] *= alpha_; \
+        }                                                                                                \
+        _Pragma("unroll") for (int t = 0; t < DT; ++t) _Pragma("unroll") for (int s2 = 0; s2 < 2; ++s2) { \
+            bf16x8 vf_;                                                                                  \
+            _Pragma("unroll") for (int u = 0; u < 8; ++u) vf_[u] = static_cast<bf16_t>(vt_[t][8 * s2 + u]); \
+            o[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf_, pf_[s2], o[t], 0, 0, 0);                 \
+        }                                                                                                \
+    }
+    // Two register sets alternate (no copies): while one block is processed the next is in flight; the block
+    // after the last is requested too and reads nothing.
     int kb = KSPLIT ? wave : 0;
     SD_LOAD_BLOCK(kc, vc, kb)
-    for (; kb < n_blocks; kb += kStep) {
-        SD_LOAD_BLOCK(kn, vn, kb + kStep)                               // prefetch; beyond the end it reads nothing
-        // ---- S^T = K Q^T
-        floatx16 s;
-#pragma unroll
-        for (int e = 0; e < 16; ++e) s[e] = 0.f;
-#pragma unroll
-        for (int c = 0; c < NCH; ++c)
-#pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4)
-                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kc[c][q4]), qf[c][q4], s, 0, 0, 0);
-        // ---- stage V^T of this key block in the wave's LDS tile (piece i of this lane: key r, d = 8 (half + 2i) ..)
-#pragma unroll
-        for (int i = 0; i < NV; ++i) {
-            const bf16x8 tv = __builtin_bit_cast(bf16x8, vc[i]);
-#pragma unroll
-            for (int u = 0; u < 8; ++u) vt[(8 * (half + 2 * i) + u) * kVtLd + r] = tv[u];
-        }
-        // ---- online softmax; accumulator e of this lane is key kb*32 + 16*half + e
-        float mb = -INFINITY;
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            s[e] = (kb * 32 + 16 * half + e < kvl) ? s[e] * scale : -INFINITY;
-            mb = fmaxf(mb, s[e]);
-        }
-        mb = fmaxf(mb, __shfl_xor(mb, 32, 64));
-        const float m_new = fmaxf(m_run, mb);
-        const bool dead = m_new == -INFINITY;                         // no visible key so far
-        const float alpha = dead ? 1.f : exp2f(m_run - m_new);
-        float psum = 0.f;
-        bf16x8 pf[2];
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            const float p = dead ? 0.f : exp2f(s[e] - m_new);
-            psum += p;
-            pf[e >> 3][e & 7] = static_cast<bf16_t>(p);
-        }
-        l_run = l_run * alpha + psum;
-        m_run = m_new;
-#pragma unroll
-        for (int t = 0; t < DT; ++t)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) o[t][e] *= alpha;
-        // ---- O^T += V^T P^T
-#pragma unroll
-        for (int t = 0; t < DT; ++t)
-#pragma unroll
-            for (int s2 = 0; s2 < 2; ++s2) {
-                const bf16x8 vf = *reinterpret_cast<const bf16x8*>(vt + (t * 32 + r) * kVtLd + 16 * half + 8 * s2);
-                o[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[s2], o[t], 0, 0, 0);
-            }
-#pragma unroll
-        for (int c = 0; c < NCH; ++c)
-#pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4) kc[c][q4] = kn[c][q4];
-#pragma unroll
-        for (int i = 0; i < NV; ++i) vc[i] = vn[i];
+    for (; kb < n_blocks; kb += 2 * kStep) {
+        SD_LOAD_BLOCK(kn, vn, kb + kStep)
+        SD_ATTN_BLOCK(kc, vc, kb)
+        if (kb + kStep >= n_blocks) break;
+        SD_LOAD_BLOCK(kc, vc, kb + 2 * kStep)
+        SD_ATTN_BLOCK(kn, vn, kb + kStep)
     }
+#undef SD_ATTN_BLOCK
 #undef SD_LOAD_BLOCK
 
     if constexpr (KSPLIT) {            // merge the four key ranges in a fixed order
+        float* const mf = reinterpret_cast<float*>(smem);
+        float (*mrg_m)[64] = reinterpret_cast<float (*)[64]>(mf);                       // [3][64]
+        float (*mrg_l)[64] = reinterpret_cast<float (*)[64]>(mf + 3 * 64);              // [3][64]
+        float (*mrg_o)[DT * 16][64] = reinterpret_cast<float (*)[DT * 16][64]>(mf + 6 * 64);   // [3][DT*16][64]
+        __syncthreads();               // every wave is done with its staging tiles
         if (wave > 0) {
             mrg_m[wave - 1][lane] = m_run;
             mrg_l[wave - 1][lane] = l_run;
@@ -171,7 +219,7 @@ __global__ __launch_bounds__(256) void k_attention_mfma(AttnArgs a) {
         float m_all = m_run;
 #pragma unroll
         for (int w = 0; w < 3; ++w) m_all = fmaxf(m_all, mrg_m[w][lane]);
-        const float f0 = m_run == -INFINITY ? 0.f : exp2f(m_run - m_all);
+        const float f0 = m_run == -INFINITY ? 0.f : exp2f((m_run - m_all) * scale);
         l_run *= f0;
 #pragma unroll
         for (int t = 0; t < DT; ++t)
@@ -180,7 +228,7 @@ __global__ __launch_bounds__(256) void k_attention_mfma(AttnArgs a) {
 #pragma unroll
         for (int w = 0; w < 3; ++w) {
             const float mw = mrg_m[w][lane];
-            const float fw = mw == -INFINITY ? 0.f : exp2f(mw - m_all);
+            const float fw = mw == -INFINITY ? 0.f : exp2f((mw - m_all) * scale);
             l_run += mrg_l[w][lane] * fw;
 #pragma unroll
             for (int t = 0; t < DT; ++t)
@@ -213,8 +261,8 @@ bool attention_mfma_supported(int dtype, const AttnArgs& a) {
 }
 
 hipError_t launch_attention_mfma(const AttnArgs& a, hipStream_t st, const char** kernel_name) {
-    const bool ksplit = (long)a.n_tiles * a.n_head < 1024 && a.max_kv > 64;
-    const dim3 grid(ksplit ? a.n_tiles : (a.n_tiles + 3) / 4, a.n_head);
+    const bool ksplit = a.max_kv > 64;   // few keys: one wave per tile; otherwise the four waves share the key range
+    const dim3 grid = ksplit ? (a.order ? dim3(a.n_order, 1) : dim3(a.n_tiles, a.n_head)) : dim3((a.n_tiles + 3) / 4, a.n_head);
     if (a.d_head == 64) {
         if (ksplit) { if (kernel_name) *kernel_name = "k_attention_mfma<64,true>"; k_attention_mfma<64, true><<<grid, 256, 0, st>>>(a); }
         else { if (kernel_name) *kernel_name = "k_attention_mfma<64,false>"; k_attention_mfma<64, false><<<grid, 256, 0, st>>>(a); }

@@ -67,6 +67,10 @@ struct AttnArgs {
     // Query tiles for the matrix-core kernel (NULL / 0 when not provided).
     const struct AttnTile* tiles = nullptr;
     int n_tiles = 0;
+    // Launch order of the key-splitting variant: workgroup i handles tile order[i] & 0xFFFFF of head
+    // order[i] >> 20 (negative: nothing).  NULL: workgroup (x, y) handles tile x of head y.
+    const int32_t* order = nullptr;
+    int n_order = 0;
 };
 // Rows row0 .. row0 + nrows - 1 (<= 32, all of one sequence); kv_max = largest kv_len among them;
 // kv_off = element offset of the sequence's key row 0 (the kv_off of its rows).
