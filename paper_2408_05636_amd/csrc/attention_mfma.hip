@@ -261,7 +261,7 @@ bool attention_mfma_supported(int dtype, const AttnArgs& a) {
 }
 
 hipError_t launch_attention_mfma(const AttnArgs& a, hipStream_t st, const char** kernel_name) {
-    const bool ksplit = a.max_kv > 64;   // few keys: one wave per tile; otherwise the four waves share the key range
+    const bool ksplit = (long)a.n_tiles * a.n_head < 1024 && a.max_kv > 64;   // few tiles: the four waves share the key range of one tile
     const dim3 grid = ksplit ? (a.order ? dim3(a.n_order, 1) : dim3(a.n_tiles, a.n_head)) : dim3((a.n_tiles + 3) / 4, a.n_head);
     if (a.d_head == 64) {
         if (ksplit) { if (kernel_name) *kernel_name = "k_attention_mfma<64,true>"; k_attention_mfma<64, true><<<grid, 256, 0, st>>>(a); }
