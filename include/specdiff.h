@@ -185,12 +185,16 @@ int32_t sd_linear(int32_t dtype, const void *x, const void *w, const float *bias
                   int32_t m, int32_t n, int32_t k, int32_t ldy, int32_t epilogue,
                   void *split_workspace, int64_t split_workspace_bytes, void *hip_stream);
 
-/* y = epilogue(W norm(h) + bias): the normalisation in front of the QKV and MLP-up contractions folded
- * into them (bf16 weights only).  norm_kind 1: LayerNorm(h; gain, beta, eps), 2: RMSNorm(h; gain, eps).
+/* y = epilogue(W norm(h) + bias): the normalisation in front of a contraction folded into it, as the
+ * forwards of bf16 models do it.  norm_kind 1: LayerNorm(h; gain, beta, eps), 2: RMSNorm(h; gain, eps).
+ * The A operand is bf16(h * gain) and the row sums of h are prepared by a row kernel (inside a forward: by
+ * the kernel that wrote h), the contraction applies mean and variance in its epilogue:
+ *   y_n = rstd_m (acc_mn - mu_m u_n) + v_n,  u = W gain,  v = W beta + bias   (RMSNorm: mu = 0, v = bias).
  * h: fp32 [m, k] (the residual stream), w: bf16 [n, k], gain / beta: fp32 [k], bias: fp32 [n] or NULL,
- * epilogue 0, 1 or 3 as in sd_linear.  fold_scratch: device, 2*n floats (receives W gain and
- * W beta + bias, which a model computes once per layer).  split_workspace as in sd_linear.
- * All pointers device; asynchronous. */
+ * epilogue 0, 1 or 3 as in sd_linear.  fold_scratch: device, 256-byte aligned,
+ * sd_norm_linear_scratch_floats(m, n, k) floats (receives u, v, the row sums and the bf16 operand).
+ * split_workspace as in sd_linear.  All pointers device; asynchronous. */
+int64_t sd_norm_linear_scratch_floats(int32_t m, int32_t n, int32_t k);
 int32_t sd_norm_linear(int32_t norm_kind, const float *h, const void *w, const float *gain, const float *beta,
                        const float *bias, void *y, int32_t m, int32_t n, int32_t k, int32_t ldy, int32_t epilogue,
                        float eps, float *fold_scratch, void *split_workspace, int64_t split_workspace_bytes,

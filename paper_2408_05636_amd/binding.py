@@ -24,7 +24,7 @@ EXPORTS = ["sd_vocab_pad", "sd_weight_count", "sd_weight_desc", "sd_weight_bytes
            "sd_destroy", "sd_last_error", "sd_prefill", "sd_draft", "sd_verify", "sd_round", "sd_drafter_logits",
            "sd_target_logits", "sd_sampling_scratch_bytes", "sd_unmask_sample", "sd_accept_resample", "sd_linear",
            "sd_profile_begin", "sd_profile_end", "sd_profile_count", "sd_profile_entry", "sd_set_graph_replay", "sd_set_linear_variant", "sd_norm_linear",
-           "sd_set_linear_split", "sd_linear_split_ticket_bytes", "sd_commit", "sd_set_greedy"]
+           "sd_set_linear_split", "sd_linear_split_ticket_bytes", "sd_commit", "sd_set_greedy", "sd_norm_linear_scratch_floats"]
 
 
 class SdModelConfig(C.Structure):
@@ -78,6 +78,7 @@ def lib() -> C.CDLL:
         L.sd_linear.restype = i32
         L.sd_linear.argtypes = [i32, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, i64, vp]
         L.sd_set_linear_split.restype = i32; L.sd_set_linear_split.argtypes = [i32]
+        L.sd_norm_linear_scratch_floats.restype = i64; L.sd_norm_linear_scratch_floats.argtypes = [i32, i32, i32]
         L.sd_commit.restype = i32; L.sd_commit.argtypes = [vp, i32, C.POINTER(C.c_int32)]
         L.sd_set_greedy.restype = i32; L.sd_set_greedy.argtypes = [vp, i32]
         L.sd_linear_split_ticket_bytes.restype = i64; L.sd_linear_split_ticket_bytes.argtypes = []
@@ -368,7 +369,7 @@ def sd_norm_linear(norm_kind: int, h, w, gain, beta, bias, y, epilogue: int, eps
     import torch
     m, k = h.shape
     n = w.shape[0]
-    scratch = torch.empty(2 * n, dtype=torch.float32, device=h.device)
+    scratch = torch.empty(int(lib().sd_norm_linear_scratch_floats(m, n, k)), dtype=torch.float32, device=h.device)
     ws = split_workspace(h.device) if split else None
     rc = lib().sd_norm_linear(norm_kind, h.data_ptr(), w.data_ptr(), gain.data_ptr(), beta.data_ptr() if beta is not None else None,
                               bias.data_ptr() if bias is not None else None, y.data_ptr(), m, n, k, y.stride(0), epilogue, eps,

@@ -172,6 +172,7 @@ struct Buffers {
     uint64_t* seed;          // Philox key of the current call
     void* sample_scratch;
     float *fold_t, *fold_d;  // folded-norm vectors of the target / drafter layers
+    float* stats;            // partial row sums (sum h, sum h^2) of the residual stream, [rows][parts][2]
     SplitWorkspace split;    // tickets + partial sums of the contractions that split K over workgroups
     void *kcache, *vcache;
 };
@@ -228,6 +229,7 @@ int64_t carve(Arena& a, Buffers& b, const sd_model_config& t, const sd_model_con
     b.seed = a.take<uint64_t>(32);
     b.sample_scratch = a.take<char>(sampling_scratch_bytes((int)l.rows_head, t.vocab));
     b.fold_t = a.take<float>(fold_floats(t));
+    b.stats = a.take<float>(l.max_rows * ((l.dmax + 31) / 32) * 2);
     b.split.bytes = kSplitBytes;
     b.split.base = a.take<char>(kSplitBytes);
     b.fold_d = a.take<float>(fold_floats(d));
@@ -593,36 +595,21 @@ uint64_t shape_key(int call, int batch, int gamma, int T, const int32_t* len, co
 // The byte / flop figures passed to SD_LAUNCH are the algorithmic ones (operands read once,
 // results written once).
 int run_linear(sd_handle* h, int dt, const void* x, const void* w, const float* bias, void* y, int m, int n, int k,
-               int ldy, int epi) {
+               int ldy, int epi, const NormIn& ni = NormIn(), const NormOut& no = NormOut()) {
     const double ew = dt == SD_DTYPE_BF16 ? 2 : 4;
     const double out_b = epi == EPI_RESID ? 8.0 : (epi == EPI_F32 ? 4.0 : ew);
-    const double bytes = ((double)m * k + (double)n * k) * ew + (double)m * n * out_b;
+    const double bytes = ((double)m * k + (double)n * k) * ew + (double)m * n * (out_b + (no.gain ? 2.0 : 0.0));
     const char* name = "linear";
-    SD_LAUNCH(h, name, bytes, 2.0 * m * n * k, launch_linear(dt, x, w, bias, y, m, n, k, ldy, epi, h->buf.split, h->st, &name));
+    SD_LAUNCH(h, name, bytes, 2.0 * m * n * k, launch_linear(dt, x, w, bias, y, m, n, k, ldy, epi, ni, no, h->buf.split, h->st, &name));
     return SD_OK;
 }
 
-// W norm(h) + bias with the norm folded into the contraction when the model allows it, else norm kernel + contraction.
-int run_norm_linear(sd_handle* h, const Model& m, const float* gain, const float* beta, const void* w, const float* bias,
-                    const float* fold_u, const float* fold_v, void* y, int rows, int n, int ldy, int epi) {
-    Buffers& B = h->buf;
-    const sd_model_config& c = m.c;
-    const int d = c.d_model;
-    // (many rows: a separate normalisation pass in front of the workgroup-shared tile kernel is faster than folding)
-    if (m.fold && linear_normfold_supported(c.dtype, rows, n, d, ldy) && !linear_tile_preferred(rows, n, d)) {
-        const double out_b = epi == EPI_F32 ? 4.0 : m.ew;
-        const double bytes = (double)rows * d * 4 + (double)n * d * m.ew + (double)rows * n * out_b;
-        const char* name = "linear_normfold";
-        const bool ln = c.arch == SD_ARCH_GPT2;
-        SD_LAUNCH(h, name, bytes, 2.0 * rows * n * d,
-                  launch_linear_normfold(B.h, w, gain, ln ? fold_u : nullptr, ln ? fold_v : bias, y, rows, n, d, ldy, epi,
-                                         ln ? 1 : 2, c.norm_eps, h->buf.split, h->st, &name));
-        return SD_OK;
-    }
-    SD_LAUNCH(h, "k_norm", (double)rows * d * (4 + m.ew), 0, launch_norm(c.dtype, B.h, nullptr, gain, beta, B.xn, rows, d, c.norm_eps, h->st));
-    return run_linear(h, c.dtype, B.xn, w, bias, y, rows, n, d, ldy, epi);
-}
-
+// Transformer layers over the rows described by the uploaded maps; residual stream in buf.h.
+//
+// bf16 models: every normalisation in front of a contraction is folded into it (NormIn / NormOut).  Whoever
+// writes the residual stream -- the embedding kernel, the attention-output and MLP-down contractions --
+// also writes xn = bf16(h * gain of the next normalisation) and the partial row sums, so a layer is five
+// launches (QKV, attention, attention-output, MLP-up, MLP-down) with no normalisation kernel.
 int run_layers(sd_handle* h, const Model& m, const MapSet& rm, const float* temb) {
     Buffers& B = h->buf;
     const sd_model_config& c = m.c;
@@ -630,12 +617,35 @@ int run_layers(sd_handle* h, const Model& m, const MapSet& rm, const float* temb
     if (rows == 0) return SD_OK;
     const bool cached = !c.bidirectional;
     const int qkv_w = m.dq + 2 * m.dkv;
+    const int up_w = c.arch == SD_ARCH_GPT2 ? c.d_ff : 2 * c.d_ff;
     const double ew = m.ew, rd = (double)rows * d;
+    const bool ln = c.arch == SD_ARCH_GPT2;
+    // all four contractions of a layer must be on the matrix-core path for the folded chain
+    const bool fold = m.fold && linear_mfma_supported(dt, rows, qkv_w, d, qkv_w) && linear_mfma_supported(dt, rows, d, d, d) &&
+                      linear_mfma_supported(dt, rows, up_w, d, up_w) && linear_mfma_supported(dt, rows, d, c.d_ff, d);
+    const int parts_d = (d + 31) / 32;
+    int parts = 1;                      // partial row sums per row currently in buf.stats
+    auto fold_in = [&](const float* u) {
+        NormIn ni;
+        ni.kind = ln ? 1 : 2; ni.stats = B.stats; ni.parts = parts; ni.u = ln ? u : nullptr; ni.eps = c.norm_eps;
+        return ni;
+    };
+    auto fold_out = [&](const float* gain) {
+        NormOut no;
+        no.gain = gain; no.xg = B.xn; no.stats = B.stats;
+        return no;
+    };
     int rc;
-    SD_LAUNCH(h, "k_embed", rd * (4 + ew), 0, launch_embed(dt, rm.src, rm.pos, rm.tokens, B.z, m.wte, m.wpe, temb, B.h, rows, d, h->st));
+    SD_LAUNCH(h, "k_embed", rd * (4 + ew + (fold ? 2 : 0)), 0,
+              launch_embed(dt, rm.src, rm.pos, rm.tokens, B.z, m.wte, m.wpe, temb, B.h, rows, d, fold ? m.L[0].ln1_g : nullptr, B.xn, B.stats, h->st));
     for (int i = 0; i < c.n_layer; ++i) {
         const Layer& l = m.L[i];
-        if ((rc = run_norm_linear(h, m, l.ln1_g, l.ln1_b, l.w_qkv, l.b_qkv, l.fu_qkv, l.fv_qkv, B.qkv, rows, qkv_w, qkv_w, EPI_STORE))) return rc;
+        if (fold) {
+            if ((rc = run_linear(h, dt, B.xn, l.w_qkv, ln ? l.fv_qkv : l.b_qkv, B.qkv, rows, qkv_w, d, qkv_w, EPI_STORE, fold_in(l.fu_qkv)))) return rc;
+        } else {
+            SD_LAUNCH(h, "k_norm", rd * (4 + ew), 0, launch_norm(dt, B.h, nullptr, l.ln1_g, l.ln1_b, B.xn, rows, d, c.norm_eps, h->st));
+            if ((rc = run_linear(h, dt, B.xn, l.w_qkv, l.b_qkv, B.qkv, rows, qkv_w, d, qkv_w, EPI_STORE))) return rc;
+        }
         if (c.arch == SD_ARCH_LLAMA)
             SD_LAUNCH(h, "k_rope", 2.0 * rows * (m.dq + m.dkv) * ew, 0, launch_rope(dt, B.qkv, rm.pos, rows, c.n_head, c.n_kv_head, m.dh, c.rope_theta, h->st));
         AttnArgs a;
@@ -658,15 +668,25 @@ int run_layers(sd_handle* h, const Model& m, const MapSet& rm, const float* temb
         }
         const char* aname = "attention";
         SD_LAUNCH(h, aname, 2.0 * rd * ew + 2.0 * rm.kv_rows * m.dkv * ew, 4.0 * rm.kv_sum * d, launch_attention(dt, a, h->st, &aname));
-        if ((rc = run_linear(h, dt, B.att, l.w_o, l.b_o, B.h, rows, d, d, d, EPI_RESID))) return rc;
-        if (c.arch == SD_ARCH_GPT2) {
-            if ((rc = run_norm_linear(h, m, l.ln2_g, l.ln2_b, l.w_fc, l.b_fc, l.fu_fc, l.fv_fc, B.mlp, rows, c.d_ff, c.d_ff, EPI_GELU))) return rc;
-            if ((rc = run_linear(h, dt, B.mlp, l.w_proj, l.b_proj, B.h, rows, d, c.d_ff, d, EPI_RESID))) return rc;
+        // attention output: h += ..., and xn / row sums for the normalisation in front of the MLP
+        if ((rc = run_linear(h, dt, B.att, l.w_o, l.b_o, B.h, rows, d, d, d, EPI_RESID, NormIn(), fold ? fold_out(l.ln2_g) : NormOut()))) return rc;
+        if (fold) parts = parts_d;
+        if (!fold) SD_LAUNCH(h, "k_norm", rd * (4 + ew), 0, launch_norm(dt, B.h, nullptr, l.ln2_g, ln ? l.ln2_b : nullptr, B.xn, rows, d, c.norm_eps, h->st));
+        const NormIn up_in = fold ? fold_in(l.fu_fc) : NormIn();
+        const float* up_bias = ln ? (fold ? l.fv_fc : l.b_fc) : nullptr;
+        const void* down_x;
+        if (ln) {
+            if ((rc = run_linear(h, dt, B.xn, l.w_fc, up_bias, B.mlp, rows, up_w, d, up_w, EPI_GELU, up_in))) return rc;
+            down_x = B.mlp;
         } else {
-            if ((rc = run_norm_linear(h, m, l.ln2_g, nullptr, l.w_fc, nullptr, nullptr, nullptr, B.mlp, rows, 2 * c.d_ff, 2 * c.d_ff, EPI_STORE))) return rc;
+            if ((rc = run_linear(h, dt, B.xn, l.w_fc, up_bias, B.mlp, rows, up_w, d, up_w, EPI_STORE, up_in))) return rc;
             SD_LAUNCH(h, "k_swiglu", 3.0 * rows * c.d_ff * ew, 0, launch_swiglu(dt, B.mlp, B.act, rows, c.d_ff, h->st));
-            if ((rc = run_linear(h, dt, B.act, l.w_proj, nullptr, B.h, rows, d, c.d_ff, d, EPI_RESID))) return rc;
+            down_x = B.act;
         }
+        // MLP down: h += ..., and xn / row sums for the first normalisation of the next layer
+        const bool more = fold && i + 1 < c.n_layer;
+        if ((rc = run_linear(h, dt, down_x, l.w_proj, ln ? l.b_proj : nullptr, B.h, rows, d, c.d_ff, d, EPI_RESID, NormIn(),
+                             more ? fold_out(m.L[i + 1].ln1_g) : NormOut()))) return rc;
     }
     return SD_OK;
 }
@@ -1187,6 +1207,10 @@ int32_t sd_accept_resample(const float* p_logits, const float* q, const int32_t*
     return launch_accept_resample(p_logits, q, draft, batch, gamma, vocab, ss.seed, n_accepted, token, ss, st) == hipSuccess ? SD_OK : SD_ERR_HIP;
 }
 
+int64_t sd_norm_linear_scratch_floats(int32_t m, int32_t n, int32_t k) {
+    return 2 * (int64_t)align_up(n, 64) + 2 * (int64_t)align_up(m, 64) + ((int64_t)m * k + 1) / 2 + 64;
+}
+
 int32_t sd_norm_linear(int32_t norm_kind, const float* h, const void* w, const float* gain, const float* beta,
                        const float* bias, void* y, int32_t m, int32_t n, int32_t k, int32_t ldy, int32_t epilogue,
                        float eps, float* fold_scratch, void* split_workspace, int64_t split_workspace_bytes,
@@ -1194,15 +1218,22 @@ int32_t sd_norm_linear(int32_t norm_kind, const float* h, const void* w, const f
     if (!h || !w || !gain || !y || !fold_scratch) return SD_ERR_ARG;
     if (split_workspace && ((reinterpret_cast<uintptr_t>(split_workspace) & 255) || split_workspace_bytes <= kSplitTicketBytes))
         return SD_ERR_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(fold_scratch) & 255) return SD_ERR_WORKSPACE;
     const SplitWorkspace ws{split_workspace, split_workspace ? split_workspace_bytes : 0};
     if (norm_kind != 1 && norm_kind != 2) return SD_ERR_ARG;
     if (m <= 0 || n <= 0 || k <= 0 || ldy < n || epilogue < 0 || epilogue > 3 || epilogue == EPI_RESID) return SD_ERR_SHAPE;
-    if (!linear_normfold_supported(SD_DTYPE_BF16, m, n, k, ldy)) return SD_ERR_SHAPE;
+    if (!linear_mfma_supported(SD_DTYPE_BF16, m, n, k, ldy)) return SD_ERR_SHAPE;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    // scratch: u [n], v [n], row sums [m][2], x = bf16(h gain) [m][k]
     float* u = fold_scratch;
-    float* v = fold_scratch + n;
+    float* v = u + align_up(n, 64);
+    float* stats = v + align_up(n, 64);
+    void* xg = stats + 2 * align_up(m, 64);
     if (launch_fold_norm(w, gain, norm_kind == 1 ? beta : nullptr, bias, u, v, n, k, st) != hipSuccess) return SD_ERR_HIP;
-    return launch_linear_normfold(h, w, gain, u, v, y, m, n, k, ldy, epilogue, norm_kind, eps, ws, st, nullptr) == hipSuccess ? SD_OK : SD_ERR_HIP;
+    if (launch_norm_prep(h, gain, xg, stats, m, k, st) != hipSuccess) return SD_ERR_HIP;
+    NormIn ni;
+    ni.kind = norm_kind; ni.stats = stats; ni.parts = 1; ni.u = norm_kind == 1 ? u : nullptr; ni.eps = eps;
+    return launch_linear(SD_DTYPE_BF16, xg, w, v, y, m, n, k, ldy, epilogue, ni, NormOut(), ws, st, nullptr) == hipSuccess ? SD_OK : SD_ERR_HIP;
 }
 
 int32_t sd_set_linear_variant(int32_t variant) {
@@ -1226,7 +1257,7 @@ int32_t sd_linear(int32_t dtype, const void* x, const void* w, const float* bias
     const SplitWorkspace ws{split_workspace, split_workspace ? split_workspace_bytes : 0};
     if (dtype != SD_DTYPE_F32 && dtype != SD_DTYPE_BF16) return SD_ERR_ARG;
     if (m <= 0 || n <= 0 || k <= 0 || ldy < n || epilogue < 0 || epilogue > 3 || k % 8) return SD_ERR_SHAPE;
-    return launch_linear(dtype, x, w, bias, y, m, n, k, ldy, epilogue, ws, static_cast<hipStream_t>(hip_stream), nullptr) == hipSuccess ? SD_OK : SD_ERR_HIP;
+    return launch_linear(dtype, x, w, bias, y, m, n, k, ldy, epilogue, NormIn(), NormOut(), ws, static_cast<hipStream_t>(hip_stream), nullptr) == hipSuccess ? SD_OK : SD_ERR_HIP;
 }
 
 }  // extern "C"

@@ -20,7 +20,25 @@ __host__ __device__ inline int64_t align_up(int64_t x, int64_t a) { return (x + 
 __host__ __device__ inline int vocab_pad(int v) { return (v + 255) / 256 * 256; }
 __host__ __device__ inline int n_chunks(int vocab) { return (vocab + kChunk - 1) / kChunk; }
 
-enum Epilogue { EPI_STORE = 0, EPI_GELU = 1, EPI_RESID = 2, EPI_F32 = 3 };
+enum Epilogue { EPI_STORE = 0, EPI_GELU = 1, EPI_RESID = 2, EPI_F32 = 3, EPI_RESID_NORM = 4 /* kernels only: EPI_RESID with NormOut */ };
+
+// A normalisation folded around a contraction  y = W norm(h) + bias  (bf16 models).  Whoever produces the
+// residual stream h also writes x = bf16(h * gain) and partial row sums (sum h, sum h^2); the contraction
+// multiplies x and applies mean and variance in its epilogue:
+//   LayerNorm (kind 1): y_n = rstd_m (sum_k x_mk W_nk - mu_m u_n) + v_n, u = W gain, v = W beta + bias;
+//   RMSNorm   (kind 2): y_n = rstd_m  sum_k x_mk W_nk + bias_n.
+struct NormIn {              // consumer: how to finish the contraction
+    int kind = 0;            // 0: plain contraction
+    const float* stats = nullptr;   // [m][parts][2] partial (sum h, sum h^2) of every row, added in order
+    int parts = 0;
+    const float* u = nullptr;       // W gain [n] (kind 1); the bias argument then carries v
+    float eps = 0.f;
+};
+struct NormOut {             // producer (residual epilogue): what to prepare for the normalisation after it
+    const float* gain = nullptr;    // [n] gain of that normalisation; NULL: nothing to prepare
+    void* xg = nullptr;             // bf16 [m][n] = bf16(y * gain)
+    float* stats = nullptr;         // [m][ceil(n / 32)][2]
+};
 
 // ---- launchers (all asynchronous on `st`; return hipGetLastError()) ------------------------
 
@@ -28,14 +46,15 @@ enum Epilogue { EPI_STORE = 0, EPI_GELU = 1, EPI_RESID = 2, EPI_F32 = 3 };
 // *kernel_name (optional) receives the name of the kernel variant that was launched.
 struct SplitWorkspace;
 hipError_t launch_linear(int dtype, const void* x, const void* w, const float* bias, void* y, int m, int n,
-                         int k, int ldy, int epilogue, const SplitWorkspace& ws, hipStream_t st,
-                         const char** kernel_name);
+                         int k, int ldy, int epilogue, const NormIn& ni, const NormOut& no, const SplitWorkspace& ws,
+                         hipStream_t st, const char** kernel_name);
 
 // h[r, :] = wte[token(r)] + wpe[pos[r]] + temb, fp32 residual stream.  token(r) = src[r] >= 0 ?
-// prefix[src[r]] : block[-src[r] - 1].  wpe, temb may be NULL.
+// prefix[src[r]] : block[-src[r] - 1].  wpe, temb may be NULL.  gain != NULL: also xg = bf16(h * gain) and
+// stats[r] = (sum h, sum h^2) for a normalisation folded into the first contraction (see NormIn).
 hipError_t launch_embed(int dtype, const int32_t* src, const int32_t* pos, const int32_t* prefix,
                         const int32_t* block, const void* wte, const void* wpe, const float* temb,
-                        float* h, int rows, int d, hipStream_t st);
+                        float* h, int rows, int d, const float* gain, void* xg, float* stats, hipStream_t st);
 
 // temb[j-1, :] = W2 silu(W1 s(j/T) + b1) + b2 for j = 1..T  (sinusoidal s of 1000 t).
 hipError_t launch_timestep_embed(int dtype, const void* w1, const float* b1, const void* w2, const float* b2,
@@ -95,21 +114,20 @@ struct SplitWorkspace {
 bool linear_mfma_supported(int dtype, int m, int n, int k, int ldy);
 void linear_mfma_set_variant(int v);     // tuning hook: force a tile variant (-1 = choose by shape)
 void linear_mfma_set_split(int s);       // tuning hook: force the K split over workgroups (<= 0 = choose by shape)
-// Contraction with the preceding LayerNorm (norm_kind 1) / RMSNorm (2) folded in: h is the fp32 residual stream.
-bool linear_normfold_supported(int dtype, int m, int n, int k, int ldy);
-hipError_t launch_linear_normfold(const float* h, const void* w, const float* gain, const float* fold_u,
-                                  const float* fold_v, void* y, int m, int n, int k, int ldy, int epilogue,
-                                  int norm_kind, float eps, const SplitWorkspace& ws, hipStream_t st,
-                                  const char** kernel_name);
 hipError_t launch_fold_norm(const void* w, const float* gain, const float* beta, const float* bias, float* u, float* v,
                             int n, int k, hipStream_t st);
 hipError_t launch_linear_mfma(const void* x, const void* w, const float* bias, void* y, int m, int n, int k, int ldy,
-                              int epilogue, const SplitWorkspace& ws, hipStream_t st, const char** kernel_name);
+                              int epilogue, const NormIn& ni, const NormOut& no, const SplitWorkspace& ws,
+                              hipStream_t st, const char** kernel_name);
+// x = bf16(h * gain) and one pair (sum h, sum h^2) per row (parts = 1): prepares a folded normalisation for
+// rows that no contraction epilogue produced (after the embedding).  d % 4 == 0.
+hipError_t launch_norm_prep(const float* h, const float* gain, void* xg, float* stats, int rows, int d, hipStream_t st);
 
 // Many-row contraction with workgroup-shared 64 x 128 or 128 x 128 tiles (x bf16); rows = 0: height by shape.
 bool linear_tile_preferred(int m, int n, int k);
 hipError_t launch_linear_tile(const void* x, const void* w, const float* bias, void* y, int m, int n, int k, int ldy,
-                              int epilogue, int rows, hipStream_t st, const char** kernel_name);
+                              int epilogue, const NormIn& ni, const NormOut& no, int rows, hipStream_t st,
+                              const char** kernel_name);
 
 // act[r, c] = silu(gu[r, c]) * gu[r, F + c]
 hipError_t launch_swiglu(int dtype, const void* gu, void* act, int rows, int F, hipStream_t st);

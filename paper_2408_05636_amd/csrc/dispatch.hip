@@ -4,8 +4,10 @@
 namespace sd {
 
 hipError_t launch_linear(int dtype, const void* x, const void* w, const float* bias, void* y, int m, int n, int k,
-                         int ldy, int epilogue, const SplitWorkspace& ws, hipStream_t st, const char** kernel_name) {
-    if (linear_mfma_supported(dtype, m, n, k, ldy)) return launch_linear_mfma(x, w, bias, y, m, n, k, ldy, epilogue, ws, st, kernel_name);
+                         int ldy, int epilogue, const NormIn& ni, const NormOut& no, const SplitWorkspace& ws,
+                         hipStream_t st, const char** kernel_name) {
+    if (linear_mfma_supported(dtype, m, n, k, ldy)) return launch_linear_mfma(x, w, bias, y, m, n, k, ldy, epilogue, ni, no, ws, st, kernel_name);
+    if (ni.kind || no.gain) return hipErrorInvalidValue;     // folded normalisations exist on the matrix-core path only
     if (kernel_name) *kernel_name = "k_linear_generic";
     return launch_linear_generic(dtype, x, w, bias, y, m, n, k, ldy, epilogue, st);
 }

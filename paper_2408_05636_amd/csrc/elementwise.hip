@@ -10,23 +10,79 @@ template <typename T> __device__ inline float to_f(T v) { return static_cast<flo
 template <typename T> __device__ inline T from_f(float v) { return static_cast<T>(v); }
 
 // ---------------------------------------------------------------- embedding
-// One workgroup per row; d floats.  The drafter adds the timestep embedding to every row.
+// One wave per row (four rows per workgroup), 4 elements per lane and step (d % 4 == 0).  The drafter adds
+// the timestep embedding to every row.  gain != NULL: the first layer's normalisation is folded into its
+// QKV contraction, which wants x = bf16(h * gain) and the row sums (sum h, sum h^2) of every row.
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float emb_f32x4;
+typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 emb_bf16x4;
+template <typename T>
+__device__ inline emb_f32x4 load4_as_f32(const T* p) {
+    if constexpr (sizeof(T) == 2) {
+        const emb_bf16x4 v = *reinterpret_cast<const emb_bf16x4*>(p);
+        return emb_f32x4{(float)v[0], (float)v[1], (float)v[2], (float)v[3]};
+    } else {
+        return *reinterpret_cast<const emb_f32x4*>(p);
+    }
+}
 template <typename T>
 __global__ __launch_bounds__(256) void k_embed(const int32_t* __restrict__ src, const int32_t* __restrict__ pos,
                                                const int32_t* __restrict__ prefix, const int32_t* __restrict__ block,
                                                const T* __restrict__ wte, const T* __restrict__ wpe,
-                                               const float* __restrict__ temb, float* __restrict__ h, int d) {
-    const int r = blockIdx.x;
+                                               const float* __restrict__ temb, float* __restrict__ h, int rows, int d,
+                                               const float* __restrict__ gain, bf16_t* __restrict__ xg,
+                                               float* __restrict__ stats) {
+    const int r = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (r >= rows) return;
     const int s = src[r];
     const int tok = s >= 0 ? prefix[s] : block[-s - 1];
     const T* e = wte + (size_t)tok * d;
     const T* p = wpe ? wpe + (size_t)pos[r] * d : nullptr;
-    for (int i = threadIdx.x; i < d; i += blockDim.x) {
-        float v = to_f(e[i]);
-        if (p) v += to_f(p[i]);
-        if (temb) v += temb[i];
-        h[(size_t)r * d + i] = v;
+    float s1 = 0.f, s2 = 0.f;
+    for (int c = lane * 4; c < d; c += 256) {
+        emb_f32x4 v = load4_as_f32(e + c);
+        if (p) v += load4_as_f32(p + c);
+        if (temb) v += *reinterpret_cast<const emb_f32x4*>(temb + c);
+        *reinterpret_cast<emb_f32x4*>(h + (size_t)r * d + c) = v;
+        if (gain) {
+            const emb_f32x4 g = *reinterpret_cast<const emb_f32x4*>(gain + c);
+            emb_bf16x4 o;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                s1 += v[u];
+                s2 = fmaf(v[u], v[u], s2);
+                o[u] = static_cast<bf16_t>(v[u] * g[u]);
+            }
+            *reinterpret_cast<emb_bf16x4*>(xg + (size_t)r * d + c) = o;
+        }
     }
+    if (gain) {
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) { s1 += __shfl_xor(s1, off, 64); s2 += __shfl_xor(s2, off, 64); }
+        if (lane == 0) { stats[2 * (size_t)r] = s1; stats[2 * (size_t)r + 1] = s2; }
+    }
+}
+
+// x = bf16(h * gain) and (sum h, sum h^2) per row for rows that already sit in the residual stream.
+__global__ __launch_bounds__(256) void k_norm_prep(const float* __restrict__ h, const float* __restrict__ gain,
+                                                   bf16_t* __restrict__ xg, float* __restrict__ stats, int rows, int d) {
+    const int r = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (r >= rows) return;
+    float s1 = 0.f, s2 = 0.f;
+    for (int c = lane * 4; c < d; c += 256) {
+        const emb_f32x4 v = *reinterpret_cast<const emb_f32x4*>(h + (size_t)r * d + c);
+        const emb_f32x4 g = *reinterpret_cast<const emb_f32x4*>(gain + c);
+        emb_bf16x4 o;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            s1 += v[u];
+            s2 = fmaf(v[u], v[u], s2);
+            o[u] = static_cast<bf16_t>(v[u] * g[u]);
+        }
+        *reinterpret_cast<emb_bf16x4*>(xg + (size_t)r * d + c) = o;
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) { s1 += __shfl_xor(s1, off, 64); s2 += __shfl_xor(s2, off, 64); }
+    if (lane == 0) { stats[2 * (size_t)r] = s1; stats[2 * (size_t)r + 1] = s2; }
 }
 
 // ---------------------------------------------------------------- timestep embedding (drafter)
@@ -186,9 +242,18 @@ __global__ __launch_bounds__(256) void k_swiglu(const T* __restrict__ gu, T* __r
 
 hipError_t launch_embed(int dtype, const int32_t* src, const int32_t* pos, const int32_t* prefix,
                         const int32_t* block, const void* wte, const void* wpe, const float* temb, float* h,
-                        int rows, int d, hipStream_t st) {
+                        int rows, int d, const float* gain, void* xg, float* stats, hipStream_t st) {
     if (rows <= 0) return hipSuccess;
-    SD_DISPATCH(dtype, (k_embed<T><<<rows, 256, 0, st>>>(src, pos, prefix, block, (const T*)wte, (const T*)wpe, temb, h, d)));
+    if (d % 4) return hipErrorInvalidValue;
+    SD_DISPATCH(dtype, (k_embed<T><<<(rows + 3) / 4, 256, 0, st>>>(src, pos, prefix, block, (const T*)wte, (const T*)wpe, temb, h,
+                                                                 rows, d, gain, (bf16_t*)xg, stats)));
+    return hipGetLastError();
+}
+
+hipError_t launch_norm_prep(const float* h, const float* gain, void* xg, float* stats, int rows, int d, hipStream_t st) {
+    if (rows <= 0) return hipSuccess;
+    if (d % 4) return hipErrorInvalidValue;
+    k_norm_prep<<<(rows + 3) / 4, 256, 0, st>>>(h, gain, (bf16_t*)xg, stats, rows, d);
     return hipGetLastError();
 }
 

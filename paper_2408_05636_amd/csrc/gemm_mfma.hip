@@ -41,17 +41,27 @@ __device__ inline float gelu_fast(float x) {
     return x / (1.f + __expf(-2.f * u));
 }
 
-// NF > 0: the normalisation in front of the contraction is folded into it.  X is then the fp32
-// residual stream h and the kernel computes  y = W norm(h) + bias  without a normalised copy of h:
+// Normalisation folded around the contraction (no normalised copy of the residual stream h, no separate
+// normalisation kernel).  For y = W norm(h) + bias:
 //   LayerNorm (NF = 1):  y_n = rstd_m (sum_k h_mk g_k W_nk - mu_m u_n) + v_n,  u = W g,  v = W beta + bias
-//   RMSNorm   (NF = 2):  y_n = rstd_m  sum_k h_mk g_k W_nk                         (u unused, v = bias)
-// The A operand is bf16(h_mk g_k), formed while the tile passes through the registers; sum h and
-// sum h^2 of every row ride along the K loop (each wave reads whole rows, or its K split of them), so
-// mu and rstd are known by the time the epilogue needs them.  u and v are precomputed per layer.
-struct NormFold {
-    const float* gain;   // g, [K]
+//   RMSNorm   (NF = 2):  y_n = rstd_m  sum_k h_mk g_k W_nk + bias_n
+// The A operand x = bf16(h g) and the row sums of h are prepared by whoever produced h: the residual
+// epilogue EPI_RESID_NORM of the previous contraction (below) or the row kernel that follows the
+// embedding.  The row sums arrive as `parts` partial pairs (sum h, sum h^2) per row, added here in a
+// fixed order; u and v are precomputed per layer.
+struct FoldIn {
+    const float* stats;  // [M][parts][2]
     const float* u;      // W g, [N] (LayerNorm only)
+    int parts;
     float eps;
+};
+// EPI_RESID_NORM: y (fp32, the residual stream) += acc + bias as EPI_RESID, and for the normalisation that
+// follows: xg[m][n] = bf16(y[m][n] gain[n]) and, per row and per 32-column tile, (sum y, sum y^2) over the
+// tile's columns -> stats[m][n / 32][2].
+struct FoldOut {
+    const float* gain;   // [N]
+    bf16_t* xg;          // [M][N]
+    float* stats;        // [M][ceil(N / 32)][2]
 };
 
 // K split across workgroups: gsplit = gridDim.y ranges; part holds gsplit records per output tile,
@@ -66,8 +76,8 @@ struct SplitArgs {
 template <int MT, int NT, int WM, int WN, int KS, int PD, int EPI, int NF>
 __global__ __launch_bounds__(256) void k_linear_mfma(const void* __restrict__ Xv, const bf16_t* __restrict__ W,
                                                      const float* __restrict__ bias, void* Y, int M,
-                                                     int N, int K, int ldy, int tiles_m, int tiles_n, NormFold nf,
-                                                     SplitArgs sk) {
+                                                     int N, int K, int ldy, int tiles_m, int tiles_n, FoldIn nf,
+                                                     FoldOut fo, SplitArgs sk) {
     const bf16_t* X = static_cast<const bf16_t*>(Xv);
     static_assert(WM * WN * KS == 4, "four waves per workgroup");
     // The wave index is uniform across the wave; telling the compiler so keeps everything derived from it
@@ -102,9 +112,8 @@ __global__ __launch_bounds__(256) void k_linear_mfma(const void* __restrict__ Xv
     // All global traffic goes through buffer resources: the per-lane byte offset stays in one VGPR,
     // the K advance is a scalar offset (no address arithmetic in the loop), and out-of-range rows
     // need neither clamping nor branches -- loads beyond the matrix return 0, stores are dropped.
-    constexpr uint32_t kXBytes = NF > 0 ? 4u : 2u;
+    constexpr uint32_t kXBytes = 2u;
     const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(X), 0, (uint32_t)M * (uint32_t)K * kXBytes, kBufFlags);
-    const __amdgpu_buffer_rsrc_t rg = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(nf.gain), 0, NF > 0 ? (uint32_t)K * 4u : 0u, kBufFlags);
     const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(W), 0, (uint32_t)N * (uint32_t)K * 2u, kBufFlags);
     // Load geometry: instruction i of a tile covers rows 8i .. 8i+7, lane -> (row 8i + lrow, 16-byte piece pc).
     const int lrow = lane >> 3, pc = lane & 7;
@@ -133,6 +142,7 @@ __global__ __launch_bounds__(256) void k_linear_mfma(const void* __restrict__ Xv
 
     // What the epilogue will need from memory (bias, and the residual stream for the accumulate
     // epilogue) is requested now, so that these round trips overlap the K loop instead of following it.
+    constexpr bool kResid = EPI == EPI_RESID || EPI == EPI_RESID_NORM;
     constexpr bool kPrefetchResid = MT * NT <= 2;
     constexpr uint32_t kOutBytes = (EPI == EPI_STORE || EPI == EPI_GELU) ? 2u : 4u;
     const __amdgpu_buffer_rsrc_t ry = __builtin_amdgcn_make_buffer_rsrc(Y, 0, (uint32_t)M * (uint32_t)ldy * kOutBytes, kBufFlags);
@@ -140,8 +150,9 @@ __global__ __launch_bounds__(256) void k_linear_mfma(const void* __restrict__ Xv
     // Output element (row m_base + 32 i + 8 (e/4) + 4 half + e%4, column n_base + 32 j + r): the lane part of
     // the byte offset; the (i, e) part is wave-uniform and goes into the scalar offset of each access.
     uint32_t yoff[NT];
-    float bv[NT], uv[NT];
+    float bv[NT], uv[NT], gv[NT];
     const __amdgpu_buffer_rsrc_t ru = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(nf.u), 0, (NF == 1) ? (uint32_t)N * 4u : 0u, kBufFlags);
+    const __amdgpu_buffer_rsrc_t rgn = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(fo.gain), 0, (EPI == EPI_RESID_NORM) ? (uint32_t)N * 4u : 0u, kBufFlags);
     floatx16 yres[kPrefetchResid ? MT : 1][kPrefetchResid ? NT : 1];
     if (wk == 0) {
 #pragma unroll
@@ -150,8 +161,9 @@ __global__ __launch_bounds__(256) void k_linear_mfma(const void* __restrict__ Xv
             yoff[j] = n < (uint32_t)N ? ((uint32_t)(m_base + 4 * half) * (uint32_t)ldy + n) * kOutBytes : kOutOfRange;
             bv[j] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rb, n * 4u, 0, 0));
             uv[j] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(ru, n * 4u, 0, 0));
+            gv[j] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rgn, n * 4u, 0, 0));
         }
-        if constexpr (kPrefetchResid && EPI == EPI_RESID) {
+        if constexpr (kPrefetchResid && kResid) {
 #pragma unroll
             for (int j = 0; j < NT; ++j)
 #pragma unroll
@@ -163,64 +175,62 @@ __global__ __launch_bounds__(256) void k_linear_mfma(const void* __restrict__ Xv
         }
     }
 
+    // Row sums of the folded normalisation.  The producer left `parts` partial pairs (sum h, sum h^2) per row;
+    // they are added in a fixed order: the KS waves and the two lane halves each take every (2 KS)-th pair
+    // (four loads in flight at a time), the halves are combined by one lane exchange and the waves through
+    // LDS below.  Requested here so that the round trips overlap the start of the K loop.
+    float w1[NF > 0 ? MT : 1] = {}, w2[NF > 0 ? MT : 1] = {};     // this wave's share, rows 32 t + r (both halves hold it)
+    if constexpr (NF > 0) {
+        typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2;
+        constexpr int kStride = 2 * KS;
+#pragma unroll
+        for (int t = 0; t < MT; ++t) {
+            const int row = m_base + 32 * t + r;
+            float b1[4] = {0.f, 0.f, 0.f, 0.f}, b2[4] = {0.f, 0.f, 0.f, 0.f};
+            if (row < M) {
+                const f32x2* sp = reinterpret_cast<const f32x2*>(nf.stats) + (size_t)row * nf.parts;
+                int p = 2 * wk + half;
+                for (; p + 3 * kStride < nf.parts; p += 4 * kStride) {
+                    f32x2 v[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) v[u] = sp[p + u * kStride];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) { b1[u] += v[u][0]; b2[u] += v[u][1]; }
+                }
+                for (; p < nf.parts; p += kStride) { const f32x2 v = sp[p]; b1[0] += v[0]; b2[0] += v[1]; }
+            }
+            w1[t] = (b1[0] + b1[1]) + (b1[2] + b1[3]);
+            w2[t] = (b2[0] + b2[1]) + (b2[2] + b2[3]);
+            w1[t] += __shfl_xor(w1[t], 32, 64);
+            w2[t] += __shfl_xor(w2[t], 32, 64);
+        }
+    }
+
     // K loop.  Two software pipelines: global -> registers runs PD chunks ahead (hides L2 / HBM
     // latency), registers -> LDS -> operand fragments runs one chunk ahead of the MFMAs (hides the LDS
     // round trip).  This wave's chunks are c0 + wk, c0 + wk + KS, ...
     // The steady-state loop has no conditional loads (the compiler's wait counts would otherwise
     // degrade to "wait for everything"); the last full group and the remainder are peeled.
     static_assert(PD % 2 == 0, "fragment double buffering assumes an even pipeline depth");
-    float s1[NF > 0 ? MT : 1][4] = {}, s2[NF > 0 ? MT : 1][4] = {};   // per-lane sum h, sum h^2 of rows 8i + lrow
     const int n_chunks = K / 64;
     // chunks [c0, c1) belong to this workgroup (all of them unless K is split over gridDim.y)
     const int c0 = (int)((long)blockIdx.y * n_chunks / sk.gsplit), c1 = (int)((long)(blockIdx.y + 1) * n_chunks / sk.gsplit);
     const int n_mine = c1 - c0 > wk ? (c1 - c0 - wk + KS - 1) / KS : 0;
     if (n_mine > 0) {
         u32x4 g[PD][TILES][4];
-        u32x4 gx2[NF > 0 ? PD : 1][NF > 0 ? MT : 1][4];     // second half of the fp32 x pieces (NF)
-        u32x4 gg[NF > 0 ? PD : 1][2];                        // gain values of this lane's k range (NF)
         bf16x8 f[2][TILES][4];
 #define SD_GLOAD(P, LOCAL)                                                                               \
     {                                                                                                    \
         const uint32_t koff_ = (uint32_t)(c0 + wk + (LOCAL) * KS) * 128u;                                \
         _Pragma("unroll") for (int t = 0; t < TILES; ++t) _Pragma("unroll") for (int i = 0; i < 4; ++i)  \
-            g[P][t][i] = __builtin_amdgcn_raw_buffer_load_b128(t < MT ? rx : rw, goff[t][i],              \
-                                                               (NF > 0 && t < MT) ? 2u * koff_ : koff_, 0); \
-        if constexpr (NF > 0) {                                                                          \
-            _Pragma("unroll") for (int t = 0; t < MT; ++t) _Pragma("unroll") for (int i = 0; i < 4; ++i)  \
-                gx2[P][t][i] = __builtin_amdgcn_raw_buffer_load_b128(rx, goff[t][i] + 16u, 2u * koff_, 0); \
-            gg[P][0] = __builtin_amdgcn_raw_buffer_load_b128(rg, 32u * pc, 2u * koff_, 0);                \
-            gg[P][1] = __builtin_amdgcn_raw_buffer_load_b128(rg, 32u * pc + 16u, 2u * koff_, 0);          \
-        }                                                                                                \
+            g[P][t][i] = __builtin_amdgcn_raw_buffer_load_b128(t < MT ? rx : rw, goff[t][i], koff_, 0);   \
     }
 // LDS operations of one wave execute in order: the fragment reads see the writes before them, and
 // the writes of the next chunk cannot overtake the reads of this one.
 #define SD_STAGE_TO_FRAG(P, FB)                                                                          \
     {                                                                                                    \
-        _Pragma("unroll") for (int t = 0; t < TILES; ++t) _Pragma("unroll") for (int i = 0; i < 4; ++i) { \
-            if constexpr (NF > 0) {                                                                      \
-                if (t < MT) {                                                                            \
-                    constexpr int tx_ = 0;                                                               \
-                    float xs_[8], gs_[8];                                                                \
-                    const f32x4 xa_ = __builtin_bit_cast(f32x4, g[P][t][i]);                             \
-                    const f32x4 xb_ = __builtin_bit_cast(f32x4, gx2[P][t < MT ? t : tx_][i]);            \
-                    const f32x4 ga_ = __builtin_bit_cast(f32x4, gg[P][0]);                               \
-                    const f32x4 gb_ = __builtin_bit_cast(f32x4, gg[P][1]);                               \
-                    _Pragma("unroll") for (int u_ = 0; u_ < 4; ++u_) {                                   \
-                        xs_[u_] = xa_[u_];                                                               \
-                        xs_[4 + u_] = xb_[u_];                                                           \
-                        gs_[u_] = ga_[u_];                                                               \
-                        gs_[4 + u_] = gb_[u_];                                                           \
-                    }                                                                                    \
-                    bf16x8 pk_;                                                                          \
-                    _Pragma("unroll") for (int u_ = 0; u_ < 8; ++u_) {                                   \
-                        s1[t < MT ? t : tx_][i] += xs_[u_];                                              \
-                        s2[t < MT ? t : tx_][i] = fmaf(xs_[u_], xs_[u_], s2[t < MT ? t : tx_][i]);       \
-                        pk_[u_] = static_cast<bf16_t>(xs_[u_] * gs_[u_]);                                \
-                    }                                                                                    \
-                    stage[t * 256 + i * 64 + wslot2[i & 1]] = __builtin_bit_cast(u32x4, pk_);                    \
-                } else stage[t * 256 + i * 64 + wslot2[i & 1]] = g[P][t][i];                                     \
-            } else stage[t * 256 + i * 64 + wslot2[i & 1]] = g[P][t][i];                                         \
-        }                                                                                                \
+        _Pragma("unroll") for (int t = 0; t < TILES; ++t) _Pragma("unroll") for (int i = 0; i < 4; ++i)  \
+            stage[t * 256 + i * 64 + wslot2[i & 1]] = g[P][t][i];                                        \
         _Pragma("unroll") for (int t = 0; t < TILES; ++t) _Pragma("unroll") for (int s4 = 0; s4 < 4; ++s4) \
             f[FB][t][s4] = __builtin_bit_cast(bf16x8, stage[t * 256 + r * 8 + ((2 * s4 + half) ^ rkey)]); \
     }
@@ -261,38 +271,27 @@ __global__ __launch_bounds__(256) void k_linear_mfma(const void* __restrict__ Xv
 #undef SD_MMA
     }
 
-    // Row statistics of the folded normalisation: combine the 8 lanes that share a row, then (K split) the waves.
     float* const lds_f = reinterpret_cast<float*>(&stage_all[0][0]);
     constexpr int kRedFloats = (KS - 1) * MT * NT * 16 * 64;
-    constexpr int kStatFloats = KS * MT * 32 * 2;
-    static_assert(sizeof(stage_all) >= (kRedFloats + kStatFloats + MT * 32 * 2) * sizeof(float), "epilogue scratch aliases the staging tiles");
-    if constexpr (NF > 0) {
-#pragma unroll
-        for (int t = 0; t < MT; ++t)
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int o = 1; o < 8; o <<= 1) {
-                    s1[t][i] += __shfl_xor(s1[t][i], o, 64);
-                    s2[t][i] += __shfl_xor(s2[t][i], o, 64);
-                }
-    }
-    // KS > 1: statistics of all waves at lds_f + kRedFloats; KS == 1: in the wave's own staging tile.
-    float* const stat = KS > 1 ? lds_f + kRedFloats : reinterpret_cast<float*>(stage);
-    float* const ab = stat + (KS > 1 ? kStatFloats : MT * 32 * 2);
+    constexpr int kStatFloats = KS > 1 ? KS * MT * 32 * 2 : 0; // the waves' shares of the row sums
+    constexpr int kRowSumFloats = 32 * 33;                     // one 32 x 32 tile, padded rows (EPI_RESID_NORM)
+    static_assert(sizeof(stage_all) >= (kRedFloats + kStatFloats + MT * 32 * 2 + kRowSumFloats) * sizeof(float), "epilogue scratch aliases the staging tiles");
+    // KS > 1: scratch behind the reduction area (one wave is left); KS == 1: in the wave's own staging tile.
+    float* const stat = lds_f + kRedFloats;
+    float* const ab = KS > 1 ? stat + kStatFloats : reinterpret_cast<float*>(stage);
+    float* const rowsum = ab + MT * 32 * 2;
+    float S1 = 0.f, S2 = 0.f;          // row sums of row m_base + lane (lanes < 32 MT)
 
     if constexpr (KS > 1) {           // fixed-order reduction over the K-splitting waves
         float (*red)[MT * NT * 16][64] = reinterpret_cast<float (*)[MT * NT * 16][64]>(lds_f);
         __syncthreads();               // every wave has finished with its staging tile
         if constexpr (NF > 0) {
-            if (pc == 0) {
+            if (half == 0) {
 #pragma unroll
-                for (int t = 0; t < MT; ++t)
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        stat[((wk * MT + t) * 32 + 8 * i + lrow) * 2 + 0] = s1[t][i];
-                        stat[((wk * MT + t) * 32 + 8 * i + lrow) * 2 + 1] = s2[t][i];
-                    }
+                for (int t = 0; t < MT; ++t) {
+                    stat[((wk * MT + t) * 32 + r) * 2 + 0] = w1[t];
+                    stat[((wk * MT + t) * 32 + r) * 2 + 1] = w2[t];
+                }
             }
         }
         if (wk > 0) {
@@ -313,34 +312,24 @@ __global__ __launch_bounds__(256) void k_linear_mfma(const void* __restrict__ Xv
                 for (int j = 0; j < NT; ++j)
 #pragma unroll
                     for (int e = 0; e < 16; ++e) acc[i][j][e] += red[k][(i * NT + j) * 16 + e][lane];
-    } else if constexpr (NF > 0) {
-        if (pc == 0) {
+        if constexpr (NF > 0) {
+            if (lane < MT * 32) {
 #pragma unroll
-            for (int t = 0; t < MT; ++t)
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    stat[(t * 32 + 8 * i + lrow) * 2 + 0] = s1[t][i];
-                    stat[(t * 32 + 8 * i + lrow) * 2 + 1] = s2[t][i];
+                for (int k = 0; k < KS; ++k) {
+                    S1 += stat[(k * MT * 32 + lane) * 2 + 0];
+                    S2 += stat[(k * MT * 32 + lane) * 2 + 1];
                 }
-        }
-    }
-    // Row sums of this workgroup's K range (lane = row).
-    float S1 = 0.f, S2 = 0.f;
-    if constexpr (NF > 0) {
-        // (LDS operations of one wave execute in order: no barrier between these steps.)
-        if (lane < MT * 32) {
-#pragma unroll
-            for (int k = 0; k < KS; ++k) {
-                S1 += stat[(k * MT * 32 + lane) * 2 + 0];
-                S2 += stat[(k * MT * 32 + lane) * 2 + 1];
             }
         }
+    } else if constexpr (NF > 0) {
+        S1 = w1[MT == 2 && lane >= 32 ? 1 : 0];
+        S2 = w2[MT == 2 && lane >= 32 ? 1 : 0];
     }
 
     // K split across workgroups (one output tile set per workgroup, one wave left at this point).
     if constexpr (WM * WN == 1) {
         if (sk.gsplit > 1) {
-            constexpr int kRec = MT * NT * 1024 + 128;      // accumulators [tile][e][lane], then S1[64], S2[64]
+            constexpr int kRec = MT * NT * 1024;            // accumulators [tile][e][lane]
             const int tile_id = tn * tiles_m + tm;
             float* const rec0 = sk.part + (size_t)tile_id * sk.gsplit * kRec;
             float* const mine = rec0 + (size_t)blockIdx.y * kRec;
@@ -354,10 +343,6 @@ __global__ __launch_bounds__(256) void k_linear_mfma(const void* __restrict__ Xv
 #pragma unroll
                     for (int e = 0; e < 16; ++e)
                         __hip_atomic_store(&mine[((i * NT + j) * 16 + e) * 64 + lane], acc[i][j][e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if constexpr (NF > 0) {
-                __hip_atomic_store(&mine[MT * NT * 1024 + lane], S1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                __hip_atomic_store(&mine[MT * NT * 1024 + 64 + lane], S2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             unsigned int old = 0;
             if (lane == 0) old = __hip_atomic_fetch_add(&sk.ticket[tile_id], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -370,7 +355,6 @@ __global__ __launch_bounds__(256) void k_linear_mfma(const void* __restrict__ Xv
                 for (int j = 0; j < NT; ++j)
 #pragma unroll
                     for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-            S1 = S2 = 0.f;
             for (int g = 0; g < sk.gsplit; ++g) {
                 float* rec = rec0 + (size_t)g * kRec;
 #pragma unroll
@@ -380,10 +364,6 @@ __global__ __launch_bounds__(256) void k_linear_mfma(const void* __restrict__ Xv
 #pragma unroll
                         for (int e = 0; e < 16; ++e)
                             acc[i][j][e] += __hip_atomic_load(&rec[((i * NT + j) * 16 + e) * 64 + lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                if constexpr (NF > 0) {
-                    S1 += __hip_atomic_load(&rec[MT * NT * 1024 + lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    S2 += __hip_atomic_load(&rec[MT * NT * 1024 + 64 + lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                }
             }
         }
     }
@@ -412,18 +392,23 @@ __global__ __launch_bounds__(256) void k_linear_mfma(const void* __restrict__ Xv
     // behind the end of the buffer, columns >= N carry the out-of-range offset, and the hardware drops both.
     // (The epilogue kind is a template parameter: with a run-time switch the compiler puts a full
     // memory wait in front of every store and the 16 stores of a tile serialise.)
+    const __amdgpu_buffer_rsrc_t rxg = __builtin_amdgcn_make_buffer_rsrc(fo.xg, 0, (EPI == EPI_RESID_NORM) ? (uint32_t)M * (uint32_t)N * 2u : 0u, kBufFlags);
+    const int parts_out = (N + 31) / 32;
 #pragma unroll
-    for (int j = 0; j < NT; ++j)
+    for (int j = 0; j < NT; ++j) {
+        const uint32_t n = (uint32_t)(n_base + 32 * j + r);
+        const uint32_t xgoff = n < (uint32_t)N ? ((uint32_t)(m_base + 4 * half) * (uint32_t)N + n) * 2u : kOutOfRange;
 #pragma unroll
-        for (int i = 0; i < MT; ++i)
+        for (int i = 0; i < MT; ++i) {
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
-                const uint32_t so = (uint32_t)(32 * i + 8 * (e >> 2) + (e & 3)) * (uint32_t)ldy * kOutBytes;
+                const int lr = 32 * i + 8 * (e >> 2) + (e & 3);           // row within the wave's tiles, minus 4 * half
+                const uint32_t so = (uint32_t)lr * (uint32_t)ldy * kOutBytes;
                 float v = acc[i][j][e];
                 if constexpr (NF > 0) v = fmaf(na[i][e], v, nb[i][e] * uv[j]);
                 v += bv[j];
                 if constexpr (EPI == EPI_GELU) v = gelu_fast(v);
-                if constexpr (EPI == EPI_RESID) {
+                if constexpr (kResid) {
                     if constexpr (kPrefetchResid) v += yres[i][j][e];
                     else v += __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(ry, yoff[j] + so, 0, 0));
                 }
@@ -431,25 +416,50 @@ __global__ __launch_bounds__(256) void k_linear_mfma(const void* __restrict__ Xv
                     __builtin_amdgcn_raw_buffer_store_b16(__builtin_bit_cast(unsigned short, static_cast<bf16_t>(v)), ry, yoff[j] + so, 0, 0);
                 else
                     __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned int, v), ry, yoff[j] + so, 0, 0);
+                if constexpr (EPI == EPI_RESID_NORM) {
+                    __builtin_amdgcn_raw_buffer_store_b16(__builtin_bit_cast(unsigned short, static_cast<bf16_t>(v * gv[j])), rxg,
+                                                          xgoff + (uint32_t)lr * (uint32_t)N * 2u, 0, 0);
+                    rowsum[(8 * (e >> 2) + 4 * half + (e & 3)) * 33 + r] = v;       // columns >= N hold 0
+                }
             }
+            if constexpr (EPI == EPI_RESID_NORM) {
+                // Row sums of this 32 x 32 tile, columns in ascending order.  (LDS operations of one wave execute
+                // in order: the reads see the stores above, the next tile's stores come after these reads.)
+                const int row = m_base + 32 * i + lane;
+                if (lane < 32 && row < M && n_base + 32 * j < N) {
+                    float t1 = 0.f, t2 = 0.f;
+#pragma unroll
+                    for (int c = 0; c < 32; ++c) {
+                        const float x = rowsum[lane * 33 + c];
+                        t1 += x;
+                        t2 = fmaf(x, x, t2);
+                    }
+                    float* so_ = fo.stats + ((size_t)row * parts_out + (n_base / 32 + j)) * 2;
+                    so_[0] = t1;
+                    so_[1] = t2;
+                }
+            }
+        }
+    }
 }
 
 static int g_variant_override = -1, g_split_override = -1;
 void linear_mfma_set_variant(int v) { g_variant_override = v; }
 void linear_mfma_set_split(int s) { g_split_override = s; }
 
-template <int MT, int NT, int WM, int WN, int KS, int PD, int NF>
+template <int MT, int NT, int WM, int WN, int KS, int PD>
 static hipError_t launch_variant(const void* x, const void* w, const float* bias, void* y, int m, int n, int k,
-                                 int ldy, int epi, const NormFold& nf, const SplitWorkspace& ws, hipStream_t st) {
+                                 int ldy, int epi, const NormIn& ni, const NormOut& no, const SplitWorkspace& ws,
+                                 hipStream_t st) {
     const int tiles_n = (n + 32 * NT * WN - 1) / (32 * NT * WN), tiles_m = (m + 32 * MT * WM - 1) / (32 * MT * WM);
     // K split over workgroups: only for the one-tile-set-per-workgroup shapes, when the tiles alone cannot
     // fill the chip, keeping at least two chunks per wave, within the workspace.
     SplitArgs sk{nullptr, nullptr, 1, 0};
-    sk.x_stationary = (int64_t)m * (NF > 0 ? 4 : 2) > (int64_t)n * 2;
+    sk.x_stationary = m > n;
     if constexpr (WM * WN == 1) {
         const long tiles = (long)tiles_n * tiles_m;
         const long part_floats = ws.base ? (ws.bytes - kSplitTicketBytes) / 4 : 0;
-        constexpr long kRec = MT * NT * 1024 + 128;
+        constexpr long kRec = MT * NT * 1024;
         if (ws.base && tiles * 4 <= kSplitTicketBytes && part_floats > 0) {
             // Worth it only for long K (the ticket and the final pass over the partials cost about a
             // microsecond): aim at six chunks per wave, and stop splitting once the tiles fill the chip.
@@ -468,12 +478,32 @@ static hipError_t launch_variant(const void* x, const void* w, const float* bias
     // every XCD gets the id range of the fullest one
     const dim3 grid(sk.x_stationary ? 8 * ((tiles_m + 7) / 8) * tiles_n : 8 * ((tiles_n + 7) / 8) * tiles_m, sk.gsplit);
     const bf16_t* wb = (const bf16_t*)w;
-    switch (epi) {
-        case EPI_STORE: k_linear_mfma<MT, NT, WM, WN, KS, PD, EPI_STORE, NF><<<grid, 256, 0, st>>>(x, wb, bias, y, m, n, k, ldy, tiles_m, tiles_n, nf, sk); break;
-        case EPI_GELU: k_linear_mfma<MT, NT, WM, WN, KS, PD, EPI_GELU, NF><<<grid, 256, 0, st>>>(x, wb, bias, y, m, n, k, ldy, tiles_m, tiles_n, nf, sk); break;
-        case EPI_RESID: k_linear_mfma<MT, NT, WM, WN, KS, PD, EPI_RESID, NF><<<grid, 256, 0, st>>>(x, wb, bias, y, m, n, k, ldy, tiles_m, tiles_n, nf, sk); break;
-        default: k_linear_mfma<MT, NT, WM, WN, KS, PD, EPI_F32, NF><<<grid, 256, 0, st>>>(x, wb, bias, y, m, n, k, ldy, tiles_m, tiles_n, nf, sk); break;
+    const FoldIn fi{ni.stats, ni.u, ni.parts, ni.eps};
+    const FoldOut fo{no.gain, static_cast<bf16_t*>(no.xg), no.stats};
+#define SD_GO(EPI, NF) k_linear_mfma<MT, NT, WM, WN, KS, PD, EPI, NF><<<grid, 256, 0, st>>>(x, wb, bias, y, m, n, k, ldy, tiles_m, tiles_n, fi, fo, sk)
+    if (ni.kind == 0) {
+        switch (epi) {
+            case EPI_STORE: SD_GO(EPI_STORE, 0); break;
+            case EPI_GELU: SD_GO(EPI_GELU, 0); break;
+            case EPI_RESID: if (no.gain) SD_GO(EPI_RESID_NORM, 0); else SD_GO(EPI_RESID, 0); break;
+            default: SD_GO(EPI_F32, 0); break;
+        }
+    } else if (ni.kind == 1) {
+        switch (epi) {
+            case EPI_STORE: SD_GO(EPI_STORE, 1); break;
+            case EPI_GELU: SD_GO(EPI_GELU, 1); break;
+            case EPI_F32: SD_GO(EPI_F32, 1); break;
+            default: return hipErrorInvalidValue;
+        }
+    } else {
+        switch (epi) {
+            case EPI_STORE: SD_GO(EPI_STORE, 2); break;
+            case EPI_GELU: SD_GO(EPI_GELU, 2); break;
+            case EPI_F32: SD_GO(EPI_F32, 2); break;
+            default: return hipErrorInvalidValue;
+        }
     }
+#undef SD_GO
     return hipGetLastError();
 }
 
@@ -483,11 +513,10 @@ bool linear_mfma_supported(int dtype, int m, int n, int k, int ldy) {
            ((int64_t)m + 64) * ldy * 4 < lim;
 }
 
-static const char* const kEpiName[4] = {"0", "1", "2", "3"};
-static std::string g_names[8][4][3];   // [variant][epilogue][fold]: kernel names as rocprof prints them
+static std::string g_names[8][5][3];   // [variant][epilogue][fold]: kernel names as rocprof prints them
 static const char* variant_name(const char* params, int v, int epi, int nfk) {
     std::string& s = g_names[v][epi][nfk];
-    if (s.empty()) s = std::string("k_linear_mfma<") + params + "," + kEpiName[epi] + "," + kEpiName[nfk] + ">";
+    if (s.empty()) s = std::string("k_linear_mfma<") + params + "," + std::to_string(epi) + "," + std::to_string(nfk) + ">";
     return s.c_str();
 }
 
@@ -504,13 +533,21 @@ static int choose_variant(int m, int n) {
 
 #define SD_VARIANT(ID, MT, NT, WM, WN, KS, PD)                                                      \
     case ID:                                                                                        \
-        if (kernel_name) *kernel_name = variant_name(#MT "," #NT "," #WM "," #WN "," #KS "," #PD, ID, epi, 0); \
-        return launch_variant<MT, NT, WM, WN, KS, PD, 0>(x, w, bias, y, m, n, k, ldy, epi, NormFold{nullptr, nullptr, 0.f}, ws, st);
+        if (kernel_name) *kernel_name = variant_name(#MT "," #NT "," #WM "," #WN "," #KS "," #PD, ID, kepi, ni.kind); \
+        return launch_variant<MT, NT, WM, WN, KS, PD>(x, w, bias, y, m, n, k, ldy, epi, ni, no, ws, st);
 
+// ni.kind != 0: x = bf16(h gain) and the row sums of h come from the producer of h (see FoldIn), bias = W beta + bias.
+// no.gain != NULL (residual epilogue only): also emit x and row sums for the normalisation that follows (FoldOut).
 hipError_t launch_linear_mfma(const void* x, const void* w, const float* bias, void* y, int m, int n, int k, int ldy,
-                              int epi, const SplitWorkspace& ws, hipStream_t st, const char** kernel_name) {
-    const int v = g_variant_override >= 0 ? g_variant_override : (linear_tile_preferred(m, n, k) ? 7 : choose_variant(m, n));
-    if (v == 7 || v == 8) return launch_linear_tile(x, w, bias, y, m, n, k, ldy, epi, g_variant_override == 8 ? 64 : (g_variant_override == 7 ? 128 : 0), st, kernel_name);
+                              int epi, const NormIn& ni, const NormOut& no, const SplitWorkspace& ws, hipStream_t st,
+                              const char** kernel_name) {
+    if (no.gain && epi != EPI_RESID) return hipErrorInvalidValue;
+    if (ni.kind < 0 || ni.kind > 2 || (ni.kind && (epi == EPI_RESID || !ni.stats || ni.parts <= 0))) return hipErrorInvalidValue;
+    const int kepi = no.gain ? (int)EPI_RESID_NORM : epi;
+    if (g_variant_override == 7 || g_variant_override == 8 || (g_variant_override < 0 && linear_tile_preferred(m, n, k)))
+        return launch_linear_tile(x, w, bias, y, m, n, k, ldy, epi, ni, no, g_variant_override == 8 ? 64 : (g_variant_override == 7 ? 128 : 0), st, kernel_name);
+    int v = g_variant_override >= 0 ? g_variant_override : choose_variant(m, n);
+    if (ni.kind && v == 3) v = 5;               // the 128 x 128 wave-private tile is not instantiated with a fold
     switch (v) {
         SD_VARIANT(0, 1, 1, 1, 1, 4, 2)     // 32 x 32 tile, four waves split K
         SD_VARIANT(1, 1, 1, 1, 1, 4, 4)     // the same with a deeper global pipeline (long K)
@@ -521,32 +558,6 @@ hipError_t launch_linear_mfma(const void* x, const void* w, const float* bias, v
         SD_VARIANT(6, 2, 1, 1, 1, 4, 2)     // 64 x 32 tile (up to 64 x rows against 32 weight rows), four waves split K
         default: return hipErrorInvalidValue;
     }
-}
-
-// y = epilogue(W norm(h) + bias) with the normalisation folded in (see NormFold).  norm_kind 1 = LayerNorm
-// (u = W g and v = W beta + bias precomputed), 2 = RMSNorm (v = bias).  Same tile choice as above, restricted
-// to the variants instantiated for it.
-bool linear_normfold_supported(int dtype, int m, int n, int k, int ldy) {
-    return linear_mfma_supported(dtype, m, n, k, ldy) && (int64_t)m * k * 4 < ((int64_t)1 << 31);
-}
-
-#define SD_NF_VARIANT(ID, MT, NT, WM, WN, KS, PD)                                                              \
-    {                                                                                                          \
-        if (kernel_name) *kernel_name = variant_name(#MT "," #NT "," #WM "," #WN "," #KS "," #PD, ID, epi, norm_kind); \
-        return norm_kind == 1 ? launch_variant<MT, NT, WM, WN, KS, PD, 1>(h, w, fold_v, y, m, n, k, ldy, epi, nf, ws, st) \
-                              : launch_variant<MT, NT, WM, WN, KS, PD, 2>(h, w, fold_v, y, m, n, k, ldy, epi, nf, ws, st); \
-    }
-
-hipError_t launch_linear_normfold(const float* h, const void* w, const float* gain, const float* fold_u,
-                                  const float* fold_v, void* y, int m, int n, int k, int ldy, int epi, int norm_kind,
-                                  float eps, const SplitWorkspace& ws, hipStream_t st, const char** kernel_name) {
-    if (norm_kind != 1 && norm_kind != 2) return hipErrorInvalidValue;
-    const NormFold nf{gain, fold_u, eps};
-    int v = choose_variant(m, n);
-    if (v == 3) v = 5;
-    if (v == 0) SD_NF_VARIANT(0, 1, 1, 1, 1, 4, 2)
-    if (v == 6) SD_NF_VARIANT(6, 2, 1, 1, 1, 4, 2)
-    SD_NF_VARIANT(5, 1, 1, 2, 2, 1, 2)
 }
 
 // u[n] = sum_k g[k] W[n,k];  v[n] = sum_k beta[k] W[n,k] + bias[n]   (beta, bias may be NULL).  One wave per row.

@@ -12,9 +12,9 @@
 // barrier per chunk; the global loads in the loop body are unconditional (past the end of K they
 // repeat the last chunk), so the compiler's wait counts stay exact.
 //
-// The normalisation in front of a contraction is not folded in here (the few-row kernel does that): with
-// this many rows a separate normalisation pass costs a fifth of the contraction, while converting the
-// fp32 residual stream on the way into LDS costs more than that in registers and vector-ALU time.
+// A normalisation folded around the contraction works as in the few-row kernel: x = bf16(h gain) and the
+// partial row sums come from the producer of h (NF), and the residual epilogue can prepare both for the
+// normalisation that follows (EPI_RESID_NORM).
 #include <string>
 
 #include "common.h"
@@ -38,10 +38,23 @@ __device__ inline float gelu_tile(float x) {
 // their banks and the key must separate them: any 16 consecutive rows get 16 distinct (parity, key) pairs.
 __device__ inline int swizzle_key(int row) { return (row & 7) ^ ((row >> 3) & 1); }
 
-template <int EPI, int WM>
+struct TileFoldIn {
+    const float* stats;  // [M][parts][2] partial (sum h, sum h^2)
+    const float* u;      // W gain [N] (LayerNorm)
+    int parts;
+    float eps;
+};
+struct TileFoldOut {
+    const float* gain;   // [N]
+    bf16_t* xg;          // [M][N]
+    float* stats;        // [M][ceil(N / 32)][2]
+};
+
+template <int EPI, int WM, int NF>
 __global__ __launch_bounds__(256) void k_linear_tile(const void* __restrict__ Xv, const bf16_t* __restrict__ W,
                                                      const float* __restrict__ bias, void* Y, int M, int N, int K,
-                                                     int ldy, int tiles_m, int tiles_n, int x_stationary) {
+                                                     int ldy, int tiles_m, int tiles_n, int x_stationary,
+                                                     TileFoldIn nf, TileFoldOut fo) {
     constexpr int BM = 64 * WM;            // rows of the workgroup tile
     constexpr int XI = BM / 32;            // x row groups per loader thread
     constexpr int NT = WM == 2 ? 2 : 1;    // 32-column tiles per wave
@@ -103,6 +116,36 @@ __global__ __launch_bounds__(256) void k_linear_tile(const void* __restrict__ Xv
         for (int j = 0; j < NT; ++j)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    // Row sums of a folded normalisation: thread t adds the partial pairs p = (t & 3), (t & 3) + 4, ... of row
+    // t >> 2 (BM = 64) -- or of rows t >> 2 and 64 + (t >> 2) (BM = 128) --, four loads in flight; the four
+    // threads of a row are combined by two lane exchanges.  Requested before the K loop so that the round
+    // trips overlap its start; consumed in the epilogue.
+    float fs1[NF > 0 ? WM : 1] = {}, fs2[NF > 0 ? WM : 1] = {};
+    if constexpr (NF > 0) {
+        typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2;
+#pragma unroll
+        for (int t = 0; t < WM; ++t) {
+            const int row = m_base + 64 * t + (threadIdx.x >> 2);
+            float b1[4] = {0.f, 0.f, 0.f, 0.f}, b2[4] = {0.f, 0.f, 0.f, 0.f};
+            if (row < M) {
+                const f32x2* sp = reinterpret_cast<const f32x2*>(nf.stats) + (size_t)row * nf.parts;
+                int p = threadIdx.x & 3;
+                for (; p + 12 < nf.parts; p += 16) {
+                    f32x2 v[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) v[u] = sp[p + 4 * u];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) { b1[u] += v[u][0]; b2[u] += v[u][1]; }
+                }
+                for (; p < nf.parts; p += 4) { const f32x2 v = sp[p]; b1[0] += v[0]; b2[0] += v[1]; }
+            }
+            fs1[t] = (b1[0] + b1[1]) + (b1[2] + b1[3]);
+            fs2[t] = (b2[0] + b2[1]) + (b2[2] + b2[3]);
+            fs1[t] += __shfl_xor(fs1[t], 1, 64); fs2[t] += __shfl_xor(fs2[t], 1, 64);
+            fs1[t] += __shfl_xor(fs1[t], 2, 64); fs2[t] += __shfl_xor(fs2[t], 2, 64);
+        }
+    }
 
     // two register sets: the global loads run two chunks ahead of the LDS stores
     u32x4 gx[2][XI], gw[2][4];
@@ -181,37 +224,92 @@ __global__ __launch_bounds__(256) void k_linear_tile(const void* __restrict__ Xv
 #undef SD_TILE_FRAGS
 #undef SD_TILE_COMPUTE
 
-    // Epilogue: accumulator e of a 32 x 32 tile is row 8 (e / 4) + 4 half + e % 4, column lane & 31.
+    // Epilogue scratch in LDS (the staging tiles are free once every wave has left the loop): rstd and
+    // -rstd mu of the BM rows, then one padded 32 x 32 tile per wave for the row sums of EPI_RESID_NORM.
+    float* const ab = reinterpret_cast<float*>(&lds_w[0][0]);             // [BM][2]
+    float* const rowsum = ab + BM * 2 + wave * (32 * 33);
+    if constexpr (NF > 0 || EPI == EPI_RESID_NORM) __syncthreads();
+    if constexpr (NF > 0) {
+        if ((threadIdx.x & 3) == 0) {
+#pragma unroll
+            for (int t = 0; t < WM; ++t) {
+                const float mu = NF == 1 ? fs1[t] / (float)K : 0.f;
+                const float var = fmaxf(fs2[t] / (float)K - mu * mu, 0.f);
+                const float rstd = rsqrtf(var + nf.eps);
+                ab[(64 * t + (threadIdx.x >> 2)) * 2 + 0] = rstd;
+                ab[(64 * t + (threadIdx.x >> 2)) * 2 + 1] = -rstd * mu;
+            }
+        }
+        __syncthreads();
+    }
+
+    // Accumulator e of a 32 x 32 tile is row 8 (e / 4) + 4 half + e % 4, column lane & 31.
+    constexpr bool kResid = EPI == EPI_RESID || EPI == EPI_RESID_NORM;
     constexpr uint32_t kOutBytes = (EPI == EPI_STORE || EPI == EPI_GELU) ? 2u : 4u;
     const __amdgpu_buffer_rsrc_t ry = __builtin_amdgcn_make_buffer_rsrc(Y, 0, (uint32_t)M * (uint32_t)ldy * kOutBytes, kTileFlags);
     const __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(bias), 0, bias ? (uint32_t)N * 4u : 0u, kTileFlags);
+    const __amdgpu_buffer_rsrc_t ru = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(nf.u), 0, (NF == 1) ? (uint32_t)N * 4u : 0u, kTileFlags);
+    const __amdgpu_buffer_rsrc_t rgn = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(fo.gain), 0, (EPI == EPI_RESID_NORM) ? (uint32_t)N * 4u : 0u, kTileFlags);
+    const __amdgpu_buffer_rsrc_t rxg = __builtin_amdgcn_make_buffer_rsrc(fo.xg, 0, (EPI == EPI_RESID_NORM) ? (uint32_t)M * (uint32_t)N * 2u : 0u, kTileFlags);
     const int wm_base = m_base + wm * 64;
+    const int parts_out = (N + 31) / 32;
 #pragma unroll
     for (int j = 0; j < NT; ++j) {
-        const uint32_t n = (uint32_t)(n_base + wn * 32 * NT + 32 * j + r);
+        const int col0 = n_base + wn * 32 * NT + 32 * j;
+        const uint32_t n = (uint32_t)(col0 + r);
         const uint32_t yoff = n < (uint32_t)N ? ((uint32_t)(wm_base + 4 * half) * (uint32_t)ldy + n) * kOutBytes : kTileOutOfRange;
+        const uint32_t xgoff = n < (uint32_t)N ? ((uint32_t)(wm_base + 4 * half) * (uint32_t)N + n) * 2u : kTileOutOfRange;
         const float bv = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rb, n * 4u, 0, 0));
+        const float uv = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(ru, n * 4u, 0, 0));
+        const float gvn = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rgn, n * 4u, 0, 0));
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < 2; ++i) {
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 const int lr = 32 * i + 8 * (e >> 2) + (e & 3);          // row within the wave's 64, minus 4 * half
                 const uint32_t so = (uint32_t)lr * (uint32_t)ldy * kOutBytes;
-                float v = acc[i][j][e] + bv;
+                float v = acc[i][j][e];
+                if constexpr (NF > 0) {
+                    const int row = wm * 64 + lr + 4 * half;
+                    v = fmaf(ab[row * 2 + 0], v, ab[row * 2 + 1] * uv);
+                }
+                v += bv;
                 if constexpr (EPI == EPI_GELU) v = gelu_tile(v);
-                if constexpr (EPI == EPI_RESID) v += __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(ry, yoff + so, 0, 0));
+                if constexpr (kResid) v += __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(ry, yoff + so, 0, 0));
                 if constexpr (kOutBytes == 2)
                     __builtin_amdgcn_raw_buffer_store_b16(__builtin_bit_cast(unsigned short, static_cast<bf16_t>(v)), ry, yoff + so, 0, 0);
                 else
                     __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned int, v), ry, yoff + so, 0, 0);
+                if constexpr (EPI == EPI_RESID_NORM) {
+                    __builtin_amdgcn_raw_buffer_store_b16(__builtin_bit_cast(unsigned short, static_cast<bf16_t>(v * gvn)), rxg,
+                                                          xgoff + (uint32_t)lr * (uint32_t)N * 2u, 0, 0);
+                    rowsum[(8 * (e >> 2) + 4 * half + (e & 3)) * 33 + r] = v;       // columns >= N hold 0
+                }
             }
+            if constexpr (EPI == EPI_RESID_NORM) {
+                // Row sums of this 32 x 32 tile, columns ascending (LDS operations of one wave execute in order).
+                const int row = wm_base + 32 * i + lane;
+                if (lane < 32 && row < M && col0 < N) {
+                    float t1 = 0.f, t2 = 0.f;
+#pragma unroll
+                    for (int c = 0; c < 32; ++c) {
+                        const float x = rowsum[lane * 33 + c];
+                        t1 += x;
+                        t2 = fmaf(x, x, t2);
+                    }
+                    float* so_ = fo.stats + ((size_t)row * parts_out + col0 / 32) * 2;
+                    so_[0] = t1;
+                    so_[1] = t2;
+                }
+            }
+        }
     }
 }
 
-static std::string g_tile_names[4][3];
-static const char* tile_name(int epi, int wm) {
-    std::string& s = g_tile_names[epi][wm];
-    if (s.empty()) s = "k_linear_tile<" + std::to_string(epi) + "," + std::to_string(wm) + ">";
+static std::string g_tile_names[5][3][3];
+static const char* tile_name(int epi, int wm, int nfk) {
+    std::string& s = g_tile_names[epi][wm][nfk];
+    if (s.empty()) s = "k_linear_tile<" + std::to_string(epi) + "," + std::to_string(wm) + "," + std::to_string(nfk) + ">";
     return s.c_str();
 }
 
@@ -229,28 +327,49 @@ bool linear_tile_preferred(int m, int n, int k) { return linear_tile_rows(m, n, 
 
 template <int WM>
 static hipError_t launch_tile(const void* x, const bf16_t* wb, const float* bias, void* y, int m, int n, int k, int ldy,
-                              int epi, hipStream_t st) {
+                              int epi, const NormIn& ni, const NormOut& no, hipStream_t st) {
     const int tiles_m = (m + 64 * WM - 1) / (64 * WM), tiles_n = (n + 127) / 128;
     const int xs = (int64_t)m > (int64_t)n;
     const int grid = xs ? 8 * ((tiles_m + 7) / 8) * tiles_n : 8 * ((tiles_n + 7) / 8) * tiles_m;
-    switch (epi) {
-        case EPI_STORE: k_linear_tile<EPI_STORE, WM><<<grid, 256, 0, st>>>(x, wb, bias, y, m, n, k, ldy, tiles_m, tiles_n, xs); break;
-        case EPI_GELU: k_linear_tile<EPI_GELU, WM><<<grid, 256, 0, st>>>(x, wb, bias, y, m, n, k, ldy, tiles_m, tiles_n, xs); break;
-        case EPI_RESID: k_linear_tile<EPI_RESID, WM><<<grid, 256, 0, st>>>(x, wb, bias, y, m, n, k, ldy, tiles_m, tiles_n, xs); break;
-        default: k_linear_tile<EPI_F32, WM><<<grid, 256, 0, st>>>(x, wb, bias, y, m, n, k, ldy, tiles_m, tiles_n, xs); break;
+    const TileFoldIn fi{ni.stats, ni.u, ni.parts, ni.eps};
+    const TileFoldOut fo{no.gain, static_cast<bf16_t*>(no.xg), no.stats};
+#define SD_GO(EPI, NF) k_linear_tile<EPI, WM, NF><<<grid, 256, 0, st>>>(x, wb, bias, y, m, n, k, ldy, tiles_m, tiles_n, xs, fi, fo)
+    if (ni.kind == 0) {
+        switch (epi) {
+            case EPI_STORE: SD_GO(EPI_STORE, 0); break;
+            case EPI_GELU: SD_GO(EPI_GELU, 0); break;
+            case EPI_RESID: if (no.gain) SD_GO(EPI_RESID_NORM, 0); else SD_GO(EPI_RESID, 0); break;
+            default: SD_GO(EPI_F32, 0); break;
+        }
+    } else if (ni.kind == 1) {
+        switch (epi) {
+            case EPI_STORE: SD_GO(EPI_STORE, 1); break;
+            case EPI_GELU: SD_GO(EPI_GELU, 1); break;
+            case EPI_F32: SD_GO(EPI_F32, 1); break;
+            default: return hipErrorInvalidValue;
+        }
+    } else {
+        switch (epi) {
+            case EPI_STORE: SD_GO(EPI_STORE, 2); break;
+            case EPI_GELU: SD_GO(EPI_GELU, 2); break;
+            case EPI_F32: SD_GO(EPI_F32, 2); break;
+            default: return hipErrorInvalidValue;
+        }
     }
+#undef SD_GO
     return hipGetLastError();
 }
 
-// x bf16 [m, k], w bf16 [n, k]; same shape limits as the few-row kernel (linear_mfma_supported).
+// x bf16 [m, k], w bf16 [n, k]; same shape limits as the few-row kernel (linear_mfma_supported); ni / no as there.
 // rows: tile height, 64 or 128 (0: by shape, 128 if the shape has no preference).
 hipError_t launch_linear_tile(const void* x, const void* w, const float* bias, void* y, int m, int n, int k, int ldy,
-                              int epi, int rows, hipStream_t st, const char** kernel_name) {
+                              int epi, const NormIn& ni, const NormOut& no, int rows, hipStream_t st,
+                              const char** kernel_name) {
     if (epi < 0 || epi > 3) return hipErrorInvalidValue;
     if (rows == 0) rows = linear_tile_rows(m, n, k) == 64 ? 64 : 128;
-    if (kernel_name) *kernel_name = tile_name(epi, rows / 64);
-    return rows == 64 ? launch_tile<1>(x, (const bf16_t*)w, bias, y, m, n, k, ldy, epi, st)
-                      : launch_tile<2>(x, (const bf16_t*)w, bias, y, m, n, k, ldy, epi, st);
+    if (kernel_name) *kernel_name = tile_name(no.gain ? (int)EPI_RESID_NORM : epi, rows / 64, ni.kind);
+    return rows == 64 ? launch_tile<1>(x, (const bf16_t*)w, bias, y, m, n, k, ldy, epi, ni, no, st)
+                      : launch_tile<2>(x, (const bf16_t*)w, bias, y, m, n, k, ldy, epi, ni, no, st);
 }
 
 }  // namespace sd
