@@ -200,6 +200,14 @@ int32_t sd_norm_linear(int32_t norm_kind, const float *h, const void *w, const f
                        float eps, float *fold_scratch, void *split_workspace, int64_t split_workspace_bytes,
                        void *hip_stream);
 
+/* The producer side of a folded normalisation (bf16 weights): y (fp32 [m, n], the residual stream) += x W^T + bias
+ * as sd_linear's epilogue 2, and for the normalisation that follows: xg (bf16 [m, n]) = bf16(y * gain) and
+ * stats (fp32 [m, ceil(n/32), 2]) = per row and 32-column tile the sums of y and of y^2 over the tile's columns.
+ * gain: fp32 [n].  split_workspace as in sd_linear.  All pointers device; asynchronous. */
+int32_t sd_linear_resid_norm(const void *x, const void *w, const float *bias, float *y, const float *gain,
+                             void *xg, float *stats, int32_t m, int32_t n, int32_t k,
+                             void *split_workspace, int64_t split_workspace_bytes, void *hip_stream);
+
 /* Tuning hook for sd_linear and every contraction inside the forwards: force tile variant
  * `variant` of the matrix-core kernel (0..6 few-row / mid-size tiles, 7, 8 = workgroup-shared 128 x 128, 64 x 128 tiles; see the kernel sources), -1 = choose by shape (default).
  * Process-wide; results do not depend on the variant beyond fp32 summation order. */

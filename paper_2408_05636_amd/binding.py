@@ -24,7 +24,7 @@ EXPORTS = ["sd_vocab_pad", "sd_weight_count", "sd_weight_desc", "sd_weight_bytes
            "sd_destroy", "sd_last_error", "sd_prefill", "sd_draft", "sd_verify", "sd_round", "sd_drafter_logits",
            "sd_target_logits", "sd_sampling_scratch_bytes", "sd_unmask_sample", "sd_accept_resample", "sd_linear",
            "sd_profile_begin", "sd_profile_end", "sd_profile_count", "sd_profile_entry", "sd_set_graph_replay", "sd_set_linear_variant", "sd_norm_linear",
-           "sd_set_linear_split", "sd_linear_split_ticket_bytes", "sd_commit", "sd_set_greedy", "sd_norm_linear_scratch_floats"]
+           "sd_set_linear_split", "sd_linear_split_ticket_bytes", "sd_commit", "sd_set_greedy", "sd_norm_linear_scratch_floats", "sd_linear_resid_norm"]
 
 
 class SdModelConfig(C.Structure):
@@ -79,6 +79,8 @@ def lib() -> C.CDLL:
         L.sd_linear.argtypes = [i32, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, i64, vp]
         L.sd_set_linear_split.restype = i32; L.sd_set_linear_split.argtypes = [i32]
         L.sd_norm_linear_scratch_floats.restype = i64; L.sd_norm_linear_scratch_floats.argtypes = [i32, i32, i32]
+        L.sd_linear_resid_norm.restype = i32
+        L.sd_linear_resid_norm.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, vp, i64, vp]
         L.sd_commit.restype = i32; L.sd_commit.argtypes = [vp, i32, C.POINTER(C.c_int32)]
         L.sd_set_greedy.restype = i32; L.sd_set_greedy.argtypes = [vp, i32]
         L.sd_linear_split_ticket_bytes.restype = i64; L.sd_linear_split_ticket_bytes.argtypes = []
@@ -377,3 +379,20 @@ def sd_norm_linear(norm_kind: int, h, w, gain, beta, bias, y, epilogue: int, eps
     if rc:
         raise SdError(rc, "sd_norm_linear")
     torch.cuda.synchronize(h.device)
+
+
+def sd_linear_resid_norm(x, w, bias, y, gain, split: bool = True):
+    """y += x w^T + bias (fp32, in place); returns (xg bf16 [m, n], stats fp32 [m, ceil(n/32), 2]); see specdiff.h."""
+    import torch
+    m, k = x.shape
+    n = w.shape[0]
+    xg = torch.zeros(m, n, dtype=torch.bfloat16, device=x.device)
+    stats = torch.zeros(m, (n + 31) // 32, 2, dtype=torch.float32, device=x.device)
+    ws = split_workspace(x.device) if split else None
+    rc = lib().sd_linear_resid_norm(x.data_ptr(), w.data_ptr(), bias.data_ptr() if bias is not None else None, y.data_ptr(),
+                                    gain.data_ptr(), xg.data_ptr(), stats.data_ptr(), m, n, k,
+                                    ws.data_ptr() if split else None, ws.numel() if split else 0, _stream_ptr(x))
+    if rc:
+        raise SdError(rc, "sd_linear_resid_norm")
+    torch.cuda.synchronize(x.device)
+    return xg, stats

@@ -1236,6 +1236,19 @@ int32_t sd_norm_linear(int32_t norm_kind, const float* h, const void* w, const f
     return launch_linear(SD_DTYPE_BF16, xg, w, v, y, m, n, k, ldy, epilogue, ni, NormOut(), ws, st, nullptr) == hipSuccess ? SD_OK : SD_ERR_HIP;
 }
 
+int32_t sd_linear_resid_norm(const void* x, const void* w, const float* bias, float* y, const float* gain, void* xg,
+                             float* stats, int32_t m, int32_t n, int32_t k, void* split_workspace,
+                             int64_t split_workspace_bytes, void* hip_stream) {
+    if (!x || !w || !y || !gain || !xg || !stats) return SD_ERR_ARG;
+    if (split_workspace && ((reinterpret_cast<uintptr_t>(split_workspace) & 255) || split_workspace_bytes <= kSplitTicketBytes))
+        return SD_ERR_WORKSPACE;
+    const SplitWorkspace ws{split_workspace, split_workspace ? split_workspace_bytes : 0};
+    if (m <= 0 || n <= 0 || k <= 0 || !linear_mfma_supported(SD_DTYPE_BF16, m, n, k, n)) return SD_ERR_SHAPE;
+    NormOut no;
+    no.gain = gain; no.xg = xg; no.stats = stats;
+    return launch_linear(SD_DTYPE_BF16, x, w, bias, y, m, n, k, n, EPI_RESID, NormIn(), no, ws, static_cast<hipStream_t>(hip_stream), nullptr) == hipSuccess ? SD_OK : SD_ERR_HIP;
+}
+
 int32_t sd_set_linear_variant(int32_t variant) {
     linear_mfma_set_variant(variant);
     return SD_OK;

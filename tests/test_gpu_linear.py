@@ -117,3 +117,40 @@ def test_norm_folded_linear(m, n, k, norm_kind):
         err = np.abs(got - ref).max()
         # the A operand is rounded to bf16 (2^-9 relative per element): error ~ 2^-9 * scale / sqrt(3) * few sigma
         assert err <= 0.012 * scale + (0.006 * np.abs(ref).max() if epi != 3 else 0), (m, n, k, norm_kind, epi, err, scale)
+
+
+@pytest.mark.parametrize("variant", [-1, 5, 7, 8])
+@pytest.mark.parametrize("m,n,k", [(17, 768, 768), (272, 768, 3072), (40, 100, 1024), (17, 1600, 6400), (300, 1601, 128), (1056, 768, 3072)])
+def test_residual_epilogue_prepares_the_next_normalisation(m, n, k, variant):
+    """Producer side of a folded normalisation: h += x W^T + b, xg = bf16(h * gain), per-tile row sums of h and h^2
+    (every kernel family: few-row with K split, wave-private 64 x 64, workgroup-shared tiles)."""
+    from paper_2408_05636_amd import binding
+    rng = np.random.default_rng(m + n + k)
+    x = synth.round_to_bf16(rng.standard_normal((m, k)).astype(np.float32))
+    w = synth.round_to_bf16((rng.standard_normal((n, k)) * 0.05).astype(np.float32))
+    b = (rng.standard_normal(n) * 0.1).astype(np.float32)
+    h0 = (rng.standard_normal((m, n)) + 0.3).astype(np.float32)
+    gain = (1 + rng.standard_normal(n) * 0.1).astype(np.float32)
+    binding.lib().sd_set_linear_variant(variant)
+    try:
+        yd = torch.from_numpy(h0.copy()).to("cuda:0")
+        xg, stats = binding.sd_linear_resid_norm(torch.from_numpy(x).to("cuda:0").bfloat16(), torch.from_numpy(w).to("cuda:0").bfloat16(),
+                                                 torch.from_numpy(b).to("cuda:0"), yd, torch.from_numpy(gain).to("cuda:0"))
+    finally:
+        binding.lib().sd_set_linear_variant(-1)
+    ref = otf.linear(x, w, b) + h0.astype(np.float64)
+    got = yd.cpu().numpy().astype(np.float64)
+    scale = np.sqrt((ref ** 2).mean())
+    assert np.abs(got - ref).max() <= 2e-5 * scale * max(1.0, np.sqrt(k / 256))
+    # xg is the bf16 rounding of the fp32 product the kernel formed from its own y
+    want_xg = synth.round_to_bf16((got.astype(np.float32) * gain[None, :]).astype(np.float32))
+    got_xg = xg.float().cpu().numpy()
+    assert np.abs(got_xg - want_xg).max() <= 2.0 ** -7 * np.abs(want_xg).max()      # at most one bf16 ulp apart
+    assert (got_xg == want_xg).mean() > 0.999
+    parts = (n + 31) // 32
+    pad = np.zeros((m, parts * 32))
+    pad[:, :n] = got
+    tiles = pad.reshape(m, parts, 32)
+    st = stats.cpu().numpy().astype(np.float64)
+    assert np.abs(st[:, :, 0] - tiles.sum(axis=2)).max() <= 1e-5 * 32 * np.abs(got).max()
+    assert np.abs(st[:, :, 1] - (tiles ** 2).sum(axis=2)).max() <= 1e-5 * 32 * (got ** 2).max()
