@@ -87,36 +87,44 @@ __global__ __launch_bounds__(256) void k_norm_prep(const float* __restrict__ h, 
 
 // ---------------------------------------------------------------- timestep embedding (drafter)
 // temb(j/T) = W2 silu(W1 s + b1) + b2 with s_i = sin(1000 t f_i), s_{i+d/2} = cos(1000 t f_i),
-// f_i = 10000^(-2i/d), the sinusoid evaluated in fp64.  Two launches of the same mat-vec kernel,
-// grid (d / 16, T): a workgroup produces 16 outputs of one timestep, one wave per 4 outputs.
-template <typename T, bool FIRST>
+// f_i = 10000^(-2i/d), for all T steps of a round at once.  Three small launches: the sinusoid table
+// (fp64 arguments, one thread per (step, frequency)), then twice the same mat-vec kernel in which one
+// wave owns one output row of the weight matrix, keeps it in registers and applies it to all T inputs.
+__global__ __launch_bounds__(256) void k_timestep_sinusoid(float* __restrict__ s, int n_steps, int d) {
+    const int half = d / 2;
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= n_steps * half) return;
+    const int j = idx / half + 1, i = idx % half;
+    const double t = (double)j / (double)n_steps;
+    const double f = exp(-log(10000.0) * 2.0 * (double)i / (double)d);
+    s[(size_t)(j - 1) * d + i] = (float)sin(1000.0 * t * f);
+    s[(size_t)(j - 1) * d + i + half] = (float)cos(1000.0 * t * f);
+}
+
+constexpr int kMatvecMax = 32;     // register-resident weight row: d <= 64 * 4 * kMatvecMax
+template <typename T, bool SILU>
 __global__ __launch_bounds__(256) void k_timestep_matvec(const T* __restrict__ w, const float* __restrict__ b,
                                                          const float* __restrict__ in, float* __restrict__ out,
                                                          int n_steps, int d) {
-    extern __shared__ float s[];       // [d] input vector of this timestep
-    const int j = blockIdx.y + 1;
-    if (FIRST) {
-        const double t = (double)j / (double)n_steps;
-        const int half = d / 2;
-        for (int i = threadIdx.x; i < half; i += blockDim.x) {
-            const double f = exp(-log(10000.0) * 2.0 * (double)i / (double)d);
-            s[i] = (float)sin(1000.0 * t * f);
-            s[i + half] = (float)cos(1000.0 * t * f);
-        }
-    } else {
-        for (int i = threadIdx.x; i < d; i += blockDim.x) s[i] = in[(size_t)(j - 1) * d + i];
-    }
-    __syncthreads();
-    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-    for (int q = 0; q < 4; ++q) {
-        const int o = blockIdx.x * 16 + wv * 4 + q;
-        if (o >= d) break;
+    const int o = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (o >= d) return;
+    emb_f32x4 wr[kMatvecMax];
+    int cnt = 0;
+    for (int c = lane * 4; c < d; c += 256) wr[cnt++] = load4_as_f32(w + (size_t)o * d + c);
+    const float bias = b[o];
+    for (int j = 0; j < n_steps; ++j) {
         float acc = 0.f;
-        for (int i = lane; i < d; i += 64) acc += to_f(w[(size_t)o * d + i]) * s[i];
-        for (int off = 32; off > 0; off >>= 1) acc += __shfl_down(acc, off, 64);
+        int q = 0;
+        for (int c = lane * 4; c < d; c += 256, ++q) {
+            const emb_f32x4 x = *reinterpret_cast<const emb_f32x4*>(in + (size_t)j * d + c);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) acc = fmaf(wr[q][u], x[u], acc);
+        }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 64);
         if (lane == 0) {
-            const float x = acc + b[o];
-            out[(size_t)(j - 1) * d + o] = FIRST ? x / (1.f + expf(-x)) : x;
+            const float x = acc + bias;
+            out[(size_t)j * d + o] = SILU ? x / (1.f + expf(-x)) : x;
         }
     }
 }
@@ -259,9 +267,11 @@ hipError_t launch_norm_prep(const float* h, const float* gain, void* xg, float* 
 
 hipError_t launch_timestep_embed(int dtype, const void* w1, const float* b1, const void* w2, const float* b2,
                                  float* hidden, float* temb, int T_steps, int d, hipStream_t st) {
-    const dim3 grid((d + 15) / 16, T_steps);
-    SD_DISPATCH(dtype, (k_timestep_matvec<T, true><<<grid, 256, d * sizeof(float), st>>>((const T*)w1, b1, nullptr, hidden, T_steps, d)));
-    SD_DISPATCH(dtype, (k_timestep_matvec<T, false><<<grid, 256, d * sizeof(float), st>>>((const T*)w2, b2, hidden, temb, T_steps, d)));
+    if (d % 4 || d > 64 * 4 * kMatvecMax) return hipErrorInvalidValue;
+    const int n_sin = T_steps * (d / 2);
+    k_timestep_sinusoid<<<(n_sin + 255) / 256, 256, 0, st>>>(temb, T_steps, d);               // temb doubles as the sinusoid table
+    SD_DISPATCH(dtype, (k_timestep_matvec<T, true><<<(d + 3) / 4, 256, 0, st>>>((const T*)w1, b1, temb, hidden, T_steps, d)));
+    SD_DISPATCH(dtype, (k_timestep_matvec<T, false><<<(d + 3) / 4, 256, 0, st>>>((const T*)w2, b2, hidden, temb, T_steps, d)));
     return hipGetLastError();
 }
 
