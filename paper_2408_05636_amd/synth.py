@@ -73,6 +73,10 @@ def workload(name: str):
         t = ModelConfig("llama", "bf16", 32, 4096, 32, 8, 14336, 128256, 2048, False)
         d = gpt2_shape("bf16", 12, 768, 12, 3072, 128256, 2048, True)
         return dict(target=t, drafter=d, prefix_len=1024, gamma=32, T=8, batch=1)
+    if name == "llama8b_b8":    # the same pair, eight sequences
+        w = workload("llama8b")
+        w.update(batch=8)
+        return w
     raise KeyError(name)
 
 
