@@ -36,7 +36,6 @@ template <int DH, bool KSPLIT>
 __global__ __launch_bounds__(256, (DH == 64 ? 2 : 1)) void k_attention_mfma(AttnArgs a) {
     constexpr int NCH = DH / 64;     // 64-wide chunks of a q / k row
     constexpr int DT = DH / 32;      // 32-row tiles of O^T
-    constexpr int NV = DH / 16;      // 16-byte pieces of a V row handled per lane
     // Per wave: a K tile and a V tile of 32 keys (NCH x 4 KB each), private to the wave.  After the loop the
     // key-splitting variant reuses the memory to merge its four partial results.
     constexpr int kStageVecs = 4 * 2 * NCH * 256;                              // u32x4 units

@@ -550,11 +550,8 @@ hipError_t launch_linear_mfma(const void* x, const void* w, const float* bias, v
     if (ni.kind && v == 3) v = 5;               // the 128 x 128 wave-private tile is not instantiated with a fold
     switch (v) {
         SD_VARIANT(0, 1, 1, 1, 1, 4, 2)     // 32 x 32 tile, four waves split K
-        SD_VARIANT(1, 1, 1, 1, 1, 4, 4)     // the same with a deeper global pipeline (long K)
-        SD_VARIANT(2, 1, 1, 2, 2, 1, 4)     // 64 x 64 tile, one 32 x 32 quadrant per wave
         SD_VARIANT(3, 2, 2, 2, 2, 1, 2)     // 128 x 128 tile, one 64 x 64 quadrant per wave
-        SD_VARIANT(4, 1, 1, 1, 2, 2, 2)     // 32 x 64 tile, two column halves x two K halves
-        SD_VARIANT(5, 1, 1, 2, 2, 1, 2)     // as 2 with a shallower global pipeline (more waves per SIMD)
+        SD_VARIANT(5, 1, 1, 2, 2, 1, 2)     // 64 x 64 tile, one 32 x 32 quadrant per wave
         SD_VARIANT(6, 2, 1, 1, 1, 4, 2)     // 64 x 32 tile (up to 64 x rows against 32 weight rows), four waves split K
         default: return hipErrorInvalidValue;
     }
