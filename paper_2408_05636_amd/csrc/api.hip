@@ -193,7 +193,7 @@ Limits limits_of(const sd_model_config& t, const sd_model_config& d, int max_bat
     const int64_t max_heads = t.n_head > d.n_head ? t.n_head : d.n_head;
     const int64_t order_cap = 8 * (l.max_rows / 32 + max_batch + 1) * max_heads;      // attention launch order, see upload_rows
     l.map_bytes = align_up((l.prefix_cap + 4 * l.max_rows + (int64_t)max_batch * gamma_max) * 4 + 32 + l.max_rows * 8 +
-                           l.max_rows * (int64_t)sizeof(AttnTile) + 16 + order_cap * 4, 256);
+                           l.max_rows * (int64_t)sizeof(AttnTile) + 32 + 2 * order_cap * 4, 256);
     return l;
 }
 
@@ -250,6 +250,8 @@ struct MapSet {
     AttnTile* tiles = nullptr;
     int32_t* order = nullptr;            // attention workgroup -> tile | head << 20 (or -1), see upload_rows
     int n_order = 0;
+    int32_t* groups = nullptr;           // attention workgroup -> up to four tiles of one sequence and head (AttnArgs::groups)
+    int n_groups = 0, group_tiles = 0;
     int rows = 0, n_tiles = 0, max_kv = 0;
     double kv_sum = 0, kv_rows = 0;     // sum of kv_len over rows; distinct key rows
     int64_t bytes = -1;
@@ -434,7 +436,8 @@ int upload_rows(sd_handle* h, int mode, int batch, const int32_t* tokens, const 
     // placed on one XCD, back to back, so that K and V are fetched into one L2 once instead of into all of
     // them by turns.  When all keys and values fit any L2 anyway the plain order spreads the load better.
     const int n_kv_groups = m.c.n_kv_head, q_per_kv = m.c.n_head / m.c.n_kv_head;
-    std::vector<std::vector<int32_t>> per_xcd(8);
+    std::vector<std::vector<int32_t>> per_xcd(8), grp_xcd(8);
+    int group_tiles = 0;
     {
         double kv_bytes = 0;
         for (int b = 0; b < batch; ++b) kv_bytes += 2.0 * m.ew * m.dkv * (mode == 0 ? len[b] + gamma : (mode == 1 ? len[b] + gamma : len[b] - 1));
@@ -447,6 +450,14 @@ int upload_rows(sd_handle* h, int mode, int batch, const int32_t* tokens, const 
                 for (int qh = 0; qh < q_per_kv; ++qh)
                     for (int64_t t = 0; t < ntb; ++t, ++lin)
                         per_xcd[grouped ? (b * n_kv_groups + g) % 8 : lin % 8].push_back((int32_t)(t0 + t) | ((g * q_per_kv + qh) << 20));
+            // the same work as groups of up to four consecutive tiles (they share the sequence's keys)
+            for (int g = 0; g < n_kv_groups; ++g)
+                for (int qh = 0; qh < q_per_kv; ++qh)
+                    for (int64_t t = 0; t < ntb; t += 4) {
+                        const int n = (int)(ntb - t < 4 ? ntb - t : 4);
+                        group_tiles = n > group_tiles ? n : group_tiles;
+                        grp_xcd[(b * n_kv_groups + g) % 8].push_back((int32_t)(t0 + t) | ((n - 1) << 18) | ((g * q_per_kv + qh) << 20));
+                    }
             t0 += ntb;
         }
     }
@@ -454,8 +465,12 @@ int upload_rows(sd_handle* h, int mode, int batch, const int32_t* tokens, const 
     for (auto& v : per_xcd) per_max = v.size() > per_max ? v.size() : per_max;
     const int64_t n_order = 8 * (int64_t)per_max;
     o += n_order * 4;
+    size_t grp_max = 0;
+    for (auto& v : grp_xcd) grp_max = v.size() > grp_max ? v.size() : grp_max;
+    const int64_t o_groups = o, n_groups = 8 * (int64_t)grp_max;
+    o += n_groups * 4;
     const int64_t bytes = o;
-    if (bytes > h->lim.map_bytes || n_tiles >= (1 << 20)) return fail(h, SD_ERR_SHAPE, "row maps exceed the workspace");
+    if (bytes > h->lim.map_bytes || n_tiles >= (1 << 18)) return fail(h, SD_ERR_SHAPE, "row maps exceed the workspace");
     int32_t *s_tok = (int32_t*)(hb + o_tok), *s_src = (int32_t*)(hb + o_src), *s_pos = (int32_t*)(hb + o_pos),
             *s_seq = (int32_t*)(hb + o_seq), *s_kvl = (int32_t*)(hb + o_kvl), *s_blk = (int32_t*)(hb + o_blk);
     int64_t* s_off = (int64_t*)(hb + o_off);
@@ -466,6 +481,9 @@ int upload_rows(sd_handle* h, int mode, int batch, const int32_t* tokens, const 
         int32_t* s_order = (int32_t*)(hb + o_order);
         for (int64_t j = 0; j < (int64_t)per_max; ++j)
             for (int x = 0; x < 8; ++x) s_order[j * 8 + x] = j < (int64_t)per_xcd[x].size() ? per_xcd[x][j] : -1;
+        int32_t* s_groups = (int32_t*)(hb + o_groups);
+        for (int64_t j = 0; j < (int64_t)grp_max; ++j)
+            for (int x = 0; x < 8; ++x) s_groups[j * 8 + x] = j < (int64_t)grp_xcd[x].size() ? grp_xcd[x][j] : -1;
     }
     int64_t r = 0, tok_off = 0, nt = 0;
     int max_kv = 0;
@@ -531,6 +549,7 @@ int upload_rows(sd_handle* h, int mode, int batch, const int32_t* tokens, const 
     ms.seq = (int32_t*)(db + o_seq); ms.kvl = (int32_t*)(db + o_kvl);
     ms.blk = (int32_t*)(db + o_blk); ms.kv_off = (int64_t*)(db + o_off); ms.tiles = (AttnTile*)(db + o_tiles);
     ms.order = (int32_t*)(db + o_order); ms.n_order = (int)n_order;
+    ms.groups = (int32_t*)(db + o_groups); ms.n_groups = (int)n_groups; ms.group_tiles = group_tiles;
     ms.rows = (int)rows; ms.n_tiles = (int)n_tiles; ms.max_kv = max_kv; ms.kv_sum = kv_sum; ms.kv_rows = kv_rows;
     ms.bytes = bytes;
     return SD_OK;
@@ -655,6 +674,7 @@ int run_layers(sd_handle* h, const Model& m, const MapSet& rm, const float* temb
         a.rows = rows; a.n_head = c.n_head; a.n_kv_head = c.n_kv_head; a.d_head = m.dh; a.max_kv = rm.max_kv;
         a.tiles = rm.tiles; a.n_tiles = rm.n_tiles;
         a.order = rm.order; a.n_order = rm.n_order;
+        a.groups = rm.groups; a.n_groups = rm.n_groups; a.group_tiles = rm.group_tiles;
         if (cached) {
             const int64_t per_layer = (int64_t)h->max_batch * c.n_ctx * m.dkv * m.ew;
             char* kc = static_cast<char*>(B.kcache) + i * per_layer;

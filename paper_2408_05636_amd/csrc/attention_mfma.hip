@@ -253,6 +253,173 @@ __global__ __launch_bounds__(256, (DH == 64 ? 2 : 1)) void k_attention_mfma(Attn
         }
 }
 
+// ---------------------------------------------------------------------------------------------------
+// Query tiles that share their keys: a workgroup takes up to four consecutive query tiles of one sequence
+// and one head (one tile per wave) and walks the key blocks once for all of them.  A key / value block is
+// fetched by the whole workgroup (one 16-byte piece of K and of V per thread and 64-wide chunk), parked in
+// one of two LDS stages shared by the waves, and each wave runs the same block step as above on its own
+// queries.  This divides the L2 -> CU traffic of K and V by the number of tiles per group -- at a few
+// hundred keys and more the one-tile-per-workgroup variants are bound by exactly that traffic -- at the
+// price of one barrier per key block.  Global loads run two blocks ahead through two register sets.
+template <int DH>
+__global__ __launch_bounds__(256, (DH == 64 ? 2 : 1)) void k_attention_group(AttnArgs a) {
+    constexpr int NCH = DH / 64, DT = DH / 32;
+    constexpr int kStageStride = 2 * NCH * 256;                // one stage: K tile, V tile (u32x4 units)
+    __shared__ u32x4 smem[2 * kStageStride];
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int r = lane & 31, half = lane >> 5;
+    const int ent = a.groups[blockIdx.x];
+    if (ent < 0) return;                                       // padding entry (whole workgroup)
+    const int tile0 = ent & 0x3FFFF, nt = ((ent >> 18) & 3) + 1, head = ent >> 20;
+    const bool has_tile = wave < nt;                           // the other waves only help loading
+    const AttnTile tl = a.tiles[tile0 + min(wave, nt - 1)];
+    int kv_all = 0;                                            // keys any tile of the group can see
+    for (int t = 0; t < nt; ++t) kv_all = max(kv_all, a.tiles[tile0 + t].kv_max);
+    const int row0 = tl.row0, nrows = tl.nrows, kv_max = tl.kv_max;
+    const int qrow = row0 + min(r, nrows - 1);
+    const int g = head / (a.n_head / a.n_kv_head);
+    const uint32_t kv_bytes = ((uint32_t)(kv_all - 1) * (uint32_t)a.kv_ld + DH) * 2u;
+    bf16_t* kbase = const_cast<bf16_t*>(static_cast<const bf16_t*>(a.k)) + tl.kv_off + (size_t)g * DH;
+    bf16_t* vbase = const_cast<bf16_t*>(static_cast<const bf16_t*>(a.v)) + tl.kv_off + (size_t)g * DH;
+    const __amdgpu_buffer_rsrc_t rk = __builtin_amdgcn_make_buffer_rsrc(kbase, 0, kv_bytes, kBufFlags);
+    const __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc(vbase, 0, kv_bytes, kBufFlags);
+    const int kvl = a.kv_len[qrow];
+    int kv_min = kvl;
+#pragma unroll
+    for (int o_ = 32; o_ > 0; o_ >>= 1) kv_min = min(kv_min, __shfl_xor(kv_min, o_, 64));
+    kv_min = __builtin_amdgcn_readfirstlane(kv_min);
+    const bf16_t* Qp = static_cast<const bf16_t*>(a.q) + (size_t)qrow * a.q_ld + (size_t)head * DH + 32 * half;
+    bf16x8 qf[NCH][4];
+#pragma unroll
+    for (int c = 0; c < NCH; ++c)
+#pragma unroll
+        for (int s = 0; s < 4; ++s) qf[c][s] = __builtin_bit_cast(bf16x8, reinterpret_cast<const u32x4*>(Qp + c * 64)[s]);
+
+    const int pi_r = 16 * ((r >> 2) & 1) + 4 * (r >> 3) + (r & 3);      // see k_attention_mfma
+    const int rkey = (pi_r & 7) ^ ((pi_r >> 4) & 1);
+    bf16x8 sel[2];
+#pragma unroll
+    for (int c2 = 0; c2 < 2; ++c2)
+#pragma unroll
+        for (int u = 0; u < 8; ++u) sel[c2][u] = static_cast<bf16_t>((16 * c2 + 8 * half + u == r) ? 1.f : 0.f);
+    // cooperative loader: thread t brings piece t & 7 of key row t >> 3 of the block (per 64-wide chunk)
+    const int lrow = threadIdx.x >> 3, pc = threadIdx.x & 7;
+    const uint32_t kv_lane = ((uint32_t)lrow * (uint32_t)a.kv_ld + 8u * pc) * 2u;
+    const uint32_t blk_bytes = 32u * (uint32_t)a.kv_ld * 2u;
+    const int wslot = lrow * 8 + (pc ^ ((lrow & 7) ^ ((lrow >> 4) & 1)));
+
+    float m_run = -INFINITY, l_run = 0.f;
+    floatx16 o[DT];
+#pragma unroll
+    for (int t = 0; t < DT; ++t)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) o[t][e] = 0.f;
+    const float scale = rsqrtf((float)DH) * 1.4426950408889634f;
+    const int n_blocks = (kv_all + 31) / 32;
+    const int my_blocks = has_tile ? (kv_max + 31) / 32 : 0;
+
+    u32x4 gk[2][NCH], gv[2][NCH];
+#define SD_G_LOAD(S, KB)                                                                                 \
+    {                                                                                                    \
+        const uint32_t o_ = kv_lane + (uint32_t)(KB) * blk_bytes;                                        \
+        _Pragma("unroll") for (int c = 0; c < NCH; ++c) {                                                \
+            gk[S][c] = __builtin_amdgcn_raw_buffer_load_b128(rk, o_ + (uint32_t)(c * 128), 0, 0);         \
+            gv[S][c] = __builtin_amdgcn_raw_buffer_load_b128(rv, o_ + (uint32_t)(c * 128), 0, 0);         \
+        }                                                                                                \
+    }
+#define SD_G_STAGE(S, STG)                                                                               \
+    {                                                                                                    \
+        _Pragma("unroll") for (int c = 0; c < NCH; ++c) {                                                \
+            smem[(STG) * kStageStride + c * 256 + wslot] = gk[S][c];                                     \
+            smem[(STG) * kStageStride + NCH * 256 + c * 256 + wslot] = gv[S][c];                         \
+        }                                                                                                \
+    }
+#define SD_G_BLOCK(STG, KB)                                                                              \
+    if ((KB) < my_blocks) {                                                                              \
+        const u32x4* sk_ = smem + (STG) * kStageStride;                                                  \
+        const u32x4* sv_ = sk_ + NCH * 256;                                                              \
+        floatx16 s;                                                                                      \
+        _Pragma("unroll") for (int e = 0; e < 16; ++e) s[e] = 0.f;                                       \
+        _Pragma("unroll") for (int c = 0; c < NCH; ++c) _Pragma("unroll") for (int q4 = 0; q4 < 4; ++q4) \
+            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                                                 \
+                __builtin_bit_cast(bf16x8, sk_[c * 256 + pi_r * 8 + ((4 * half + q4) ^ rkey)]), qf[c][q4], s, 0, 0, 0); \
+        floatx16 vt_[DT];                                                                                \
+        _Pragma("unroll") for (int t = 0; t < DT; ++t) {                                                 \
+            _Pragma("unroll") for (int e = 0; e < 16; ++e) vt_[t][e] = 0.f;                              \
+            _Pragma("unroll") for (int c2 = 0; c2 < 2; ++c2) {                                           \
+                const int pv_ = 2 * (2 * t + c2) + half;                                                 \
+                vt_[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                                        \
+                    __builtin_bit_cast(bf16x8, sv_[(pv_ >> 3) * 256 + pi_r * 8 + ((pv_ & 7) ^ rkey)]), sel[c2], vt_[t], 0, 0, 0); \
+            }                                                                                            \
+        }                                                                                                \
+        if ((KB) * 32 + 32 > kv_min) {                                                                   \
+            _Pragma("unroll") for (int e = 0; e < 16; ++e)                                               \
+                s[e] = ((KB) * 32 + 16 * half + e < kvl) ? s[e] : -INFINITY;                             \
+        }                                                                                                \
+        float mb_ = fmaxf(s[0], s[1]);                                                                   \
+        _Pragma("unroll") for (int e = 2; e < 16; ++e) mb_ = fmaxf(mb_, s[e]);                           \
+        mb_ = fmaxf(mb_, __shfl_xor(mb_, 32, 64));                                                       \
+        const float m_new_ = fmaxf(m_run, mb_);                                                          \
+        const float m_fin_ = fmaxf(m_new_, -1e30f);                                                      \
+        const float msc_ = m_fin_ * scale;                                                               \
+        const float alpha_ = __builtin_amdgcn_exp2f((m_run - m_fin_) * scale);                           \
+        float psum_ = 0.f;                                                                               \
+        bf16x8 pf_[2];                                                                                   \
+        _Pragma("unroll") for (int e = 0; e < 16; ++e) {                                                 \
+            const float p_ = __builtin_amdgcn_exp2f(fmaf(s[e], scale, -msc_));                           \
+            psum_ += p_;                                                                                 \
+            pf_[e >> 3][e & 7] = static_cast<bf16_t>(p_);                                                \
+        }                                                                                                \
+        l_run = l_run * alpha_ + psum_;                                                                  \
+        m_run = m_new_;                                                                                  \
+        if (__builtin_amdgcn_ballot_w64(alpha_ != 1.f) != 0) {                                           \
+            _Pragma("unroll") for (int t = 0; t < DT; ++t) _Pragma("unroll") for (int e = 0; e < 16; ++e) o[t][e] *= alpha_; \
+        }                                                                                                \
+        _Pragma("unroll") for (int t = 0; t < DT; ++t) _Pragma("unroll") for (int s2 = 0; s2 < 2; ++s2) { \
+            bf16x8 vf_;                                                                                  \
+            _Pragma("unroll") for (int u = 0; u < 8; ++u) vf_[u] = static_cast<bf16_t>(vt_[t][8 * s2 + u]); \
+            o[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf_, pf_[s2], o[t], 0, 0, 0);                 \
+        }                                                                                                \
+    }
+    // Step kb: park block kb + 1 (register set (kb + 1) & 1) in LDS stage (kb + 1) & 1 -- last read before the
+    // barrier that ended step kb - 1 --, refill that set with block kb + 3, work on block kb.  Blocks past the
+    // end are requested too and read nothing.
+    SD_G_LOAD(0, 0)
+    SD_G_LOAD(1, 1)
+    SD_G_STAGE(0, 0)
+    SD_G_LOAD(0, 2)
+    __syncthreads();
+    for (int kb = 0; kb < n_blocks; kb += 2) {
+        SD_G_STAGE(1, 1)
+        SD_G_LOAD(1, kb + 3)
+        SD_G_BLOCK(0, kb)
+        __syncthreads();
+        if (kb + 1 >= n_blocks) break;
+        SD_G_STAGE(0, 0)
+        SD_G_LOAD(0, kb + 4)
+        SD_G_BLOCK(1, kb + 1)
+        __syncthreads();
+    }
+#undef SD_G_LOAD
+#undef SD_G_STAGE
+#undef SD_G_BLOCK
+    if (!has_tile) return;
+
+    const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+    const float inv = 1.f / l_tot;
+    const __amdgpu_buffer_rsrc_t ro = __builtin_amdgcn_make_buffer_rsrc(a.out, 0, (uint32_t)a.rows * (uint32_t)a.out_ld * 2u, kBufFlags);
+    const uint32_t o_lane = r < nrows ? ((uint32_t)qrow * (uint32_t)a.out_ld + (uint32_t)head * DH + 4u * half) * 2u : kOutOfRange;
+#pragma unroll
+    for (int t = 0; t < DT; ++t)
+#pragma unroll
+        for (int e4 = 0; e4 < 4; ++e4) {
+            union { bf16_t h[4]; u32x2 u; } pk;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) pk.h[i] = static_cast<bf16_t>(o[t][4 * e4 + i] * inv);
+            __builtin_amdgcn_raw_buffer_store_b64(pk.u, ro, o_lane + (uint32_t)(t * 32 + 8 * e4) * 2u, 0, 0);
+        }
+}
+
 bool attention_mfma_supported(int dtype, const AttnArgs& a) {
     return dtype == SD_DTYPE_BF16 && (a.d_head == 64 || a.d_head == 128) && a.tiles != nullptr && a.n_tiles > 0 &&
            a.q_ld % 8 == 0 && a.kv_ld % 8 == 0 && a.out_ld % 4 == 0 && (int64_t)a.max_kv * a.kv_ld * 2 < ((int64_t)1 << 31) &&
@@ -260,6 +427,12 @@ bool attention_mfma_supported(int dtype, const AttnArgs& a) {
 }
 
 hipError_t launch_attention_mfma(const AttnArgs& a, hipStream_t st, const char** kernel_name) {
+    // several query tiles per sequence: share the key / value blocks among up to four of them
+    if (a.groups != nullptr && a.n_groups > 0 && a.group_tiles >= 2 && (long)a.n_tiles * a.n_head >= 1024 && a.max_kv > 64) {
+        if (a.d_head == 64) { if (kernel_name) *kernel_name = "k_attention_group<64>"; k_attention_group<64><<<a.n_groups, 256, 0, st>>>(a); }
+        else { if (kernel_name) *kernel_name = "k_attention_group<128>"; k_attention_group<128><<<a.n_groups, 256, 0, st>>>(a); }
+        return hipGetLastError();
+    }
     const bool ksplit = (long)a.n_tiles * a.n_head < 1024 && a.max_kv > 64;   // few tiles: the four waves share the key range of one tile
     const dim3 grid = ksplit ? (a.order ? dim3(a.n_order, 1) : dim3(a.n_tiles, a.n_head)) : dim3((a.n_tiles + 3) / 4, a.n_head);
     if (a.d_head == 64) {

@@ -90,6 +90,11 @@ struct AttnArgs {
     // order[i] >> 20 (negative: nothing).  NULL: workgroup (x, y) handles tile x of head y.
     const int32_t* order = nullptr;
     int n_order = 0;
+    // Launch order of the key-sharing variant: workgroup i handles tiles t0 .. t0 + n - 1 (consecutive tiles
+    // of one sequence, n <= 4) of one head, groups[i] = t0 | (n - 1) << 18 | head << 20 (negative: nothing).
+    // group_tiles: the largest n (the variant is used from 2 on).
+    const int32_t* groups = nullptr;
+    int n_groups = 0, group_tiles = 0;
 };
 // Rows row0 .. row0 + nrows - 1 (<= 32, all of one sequence); kv_max = largest kv_len among them;
 // kv_off = element offset of the sequence's key row 0 (the kv_off of its rows).
