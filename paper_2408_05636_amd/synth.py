@@ -124,10 +124,14 @@ def weight_specs(cfg: ModelConfig) -> List[Tuple[str, Tuple[int, ...], str]]:
 
 
 def round_to_bf16(x: np.ndarray) -> np.ndarray:
-    """fp32 array -> nearest bf16 value (ties to even), returned as fp32."""
-    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
-    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
-    return u.astype(np.uint32).view(np.float32).reshape(x.shape)
+    """fp32 array -> nearest bf16 value (ties to even), returned as fp32.  (Finite inputs well below
+    the largest fp32: the rounding increment is added in 32-bit arithmetic.)"""
+    u = np.array(x, dtype=np.float32, order="C", copy=True).view(np.uint32)
+    bias = (u >> np.uint32(16)) & np.uint32(1)
+    bias += np.uint32(0x7FFF)
+    u += bias
+    u &= np.uint32(0xFFFF0000)
+    return u.view(np.float32).reshape(np.shape(x))
 
 
 def gen_tensor(cfg: ModelConfig, seed: int, index: int, shape, role: str) -> np.ndarray:
