@@ -209,7 +209,8 @@ int32_t sd_linear_resid_norm(const void *x, const void *w, const float *bias, fl
                              void *split_workspace, int64_t split_workspace_bytes, void *hip_stream);
 
 /* Tuning hook for sd_linear and every contraction inside the forwards: force tile variant
- * `variant` of the matrix-core kernel (0, 3, 5, 6: few-row / mid-size tiles; 7, 8: workgroup-shared 128 x 128, 64 x 128 tiles; see the kernel
+ * `variant` of the matrix-core kernel (0, 3, 5, 6: few-row / mid-size tiles; 7, 8: workgroup-shared 128 x 128, 64 x 128 tiles;
+ * 9: the weight-streaming kernel for up to 64 rows wherever the shape fits it, the choice by shape elsewhere; see the kernel
  * sources; other values are rejected at the next contraction), -1 = choose by shape (default).
  * Process-wide; results do not depend on the variant beyond fp32 summation order. */
 int32_t sd_set_linear_variant(int32_t variant);

@@ -343,7 +343,7 @@ def sd_accept_resample(p_logits, q, draft, batch: int, gamma: int, vocab: int, s
 _split_ws = {}
 
 
-def split_workspace(device, part_bytes: int = 16 << 20):
+def split_workspace(device, part_bytes: int = 64 << 20):
     """Zero-filled device workspace for the contractions that split K over workgroups (one per device)."""
     import torch
     key = str(device)

@@ -198,7 +198,7 @@ Limits limits_of(const sd_model_config& t, const sd_model_config& d, int max_bat
 }
 
 // floats needed for the folded LayerNorm vectors of a model (u and v for QKV and MLP-up of every layer)
-constexpr int64_t kSplitBytes = kSplitTicketBytes + (16 << 20);
+constexpr int64_t kSplitBytes = kSplitTicketBytes + (64 << 20);
 
 int64_t fold_floats(const sd_model_config& c) {
     if (c.arch != SD_ARCH_GPT2 || c.dtype != SD_DTYPE_BF16) return 64;

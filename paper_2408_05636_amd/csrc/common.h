@@ -128,6 +128,13 @@ hipError_t launch_linear_mfma(const void* x, const void* w, const float* bias, v
 // rows that no contraction epilogue produced (after the embedding).  d % 4 == 0.
 hipError_t launch_norm_prep(const float* h, const float* gain, void* xg, float* stats, int rows, int d, hipStream_t st);
 
+// Up to 64 rows against a long weight stream: x parked in LDS, weights streamed (gemm_stream.hip).  Returns
+// hipErrorNotSupported when the shape does not fit (the caller then uses another kernel).
+bool linear_stream_preferred(int m, int n, int k);
+hipError_t launch_linear_stream(const void* x, const void* w, const float* bias, void* y, int m, int n, int k, int ldy,
+                                int epilogue, const NormIn& ni, const NormOut& no, const SplitWorkspace& ws,
+                                int force_split, hipStream_t st, const char** kernel_name);
+
 // Many-row contraction with workgroup-shared 64 x 128 or 128 x 128 tiles (x bf16); rows = 0: height by shape.
 bool linear_tile_preferred(int m, int n, int k);
 hipError_t launch_linear_tile(const void* x, const void* w, const float* bias, void* y, int m, int n, int k, int ldy,

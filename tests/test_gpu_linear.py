@@ -74,6 +74,24 @@ def test_linear_shared_tile_kernel(m, n, k, variant):
         binding.lib().sd_set_linear_variant(-1)
 
 
+@pytest.mark.parametrize("split", [-1, 3, 64])
+@pytest.mark.parametrize("m,n,k", [(17, 768, 768), (16, 50257, 768), (33, 2304, 1024), (64, 200, 2048), (40, 100, 4096), (1, 64, 64),
+                                   (33, 4100, 4096), (17, 1600, 6400), (31, 130, 2304)])
+def test_linear_streaming_kernel(m, n, k, split):
+    """The weight-streaming kernel for up to 64 rows (x parked in LDS; normally chosen for long weight streams only),
+    forced on small and ragged shapes, with the K range in one piece and split over workgroups, twice in a row."""
+    from paper_2408_05636_amd import binding
+    binding.lib().sd_set_linear_variant(9)
+    binding.lib().sd_set_linear_split(split)
+    try:
+        for epi in range(4):
+            run_case("bf16", m, n, k, epi, seed=11 + m + n + k + epi)
+        run_case("bf16", m, n, k, 2, seed=12 + m + n + k)
+    finally:
+        binding.lib().sd_set_linear_variant(-1)
+        binding.lib().sd_set_linear_split(-1)
+
+
 @pytest.mark.parametrize("split", [2, 3, 7, 64])
 def test_linear_forced_split(split):
     """Every split count gives the same contraction (up to fp32 summation order), twice in a row on
@@ -92,8 +110,21 @@ def test_linear_forced_split(split):
 @pytest.mark.parametrize("m,n,k", [(17, 2304, 768), (272, 2304, 768), (301, 3072, 768), (33, 100, 128), (65, 4801, 1600), (700, 1000, 256),
                                    (17, 4800, 1600), (33, 512, 4096), (60, 96, 2048), (2100, 2304, 768)])
 @pytest.mark.parametrize("norm_kind", [1, 2])
-def test_norm_folded_linear(m, n, k, norm_kind):
-    """LayerNorm / RMSNorm folded into the contraction vs. the oracle's norm followed by its linear."""
+@pytest.mark.parametrize("variant", [-1, 9])
+def test_norm_folded_linear(m, n, k, norm_kind, variant):
+    """LayerNorm / RMSNorm folded into the contraction vs. the oracle's norm followed by its linear
+    (variant 9: the weight-streaming kernel, up to 64 rows)."""
+    from paper_2408_05636_amd import binding
+    if variant == 9 and m > 64:
+        pytest.skip("the streaming kernel takes up to 64 rows")
+    binding.lib().sd_set_linear_variant(variant)
+    try:
+        norm_folded_case(m, n, k, norm_kind)
+    finally:
+        binding.lib().sd_set_linear_variant(-1)
+
+
+def norm_folded_case(m, n, k, norm_kind):
     from paper_2408_05636_amd import binding
     rng = np.random.default_rng(m + n + k + norm_kind)
     # residual-stream-like rows: a common offset pattern plus row-specific parts, non-zero mean
@@ -119,12 +150,14 @@ def test_norm_folded_linear(m, n, k, norm_kind):
         assert err <= 0.012 * scale + (0.006 * np.abs(ref).max() if epi != 3 else 0), (m, n, k, norm_kind, epi, err, scale)
 
 
-@pytest.mark.parametrize("variant", [-1, 5, 7, 8])
+@pytest.mark.parametrize("variant", [-1, 5, 7, 8, 9])
 @pytest.mark.parametrize("m,n,k", [(17, 768, 768), (272, 768, 3072), (40, 100, 1024), (17, 1600, 6400), (300, 1601, 128), (1056, 768, 3072)])
 def test_residual_epilogue_prepares_the_next_normalisation(m, n, k, variant):
     """Producer side of a folded normalisation: h += x W^T + b, xg = bf16(h * gain), per-tile row sums of h and h^2
-    (every kernel family: few-row with K split, wave-private 64 x 64, workgroup-shared tiles)."""
+    (every kernel family: few-row with K split, wave-private 64 x 64, workgroup-shared tiles, weight streaming)."""
     from paper_2408_05636_amd import binding
+    if variant == 9 and m > 64:
+        pytest.skip("the streaming kernel takes up to 64 rows")
     rng = np.random.default_rng(m + n + k)
     x = synth.round_to_bf16(rng.standard_normal((m, k)).astype(np.float32))
     w = synth.round_to_bf16((rng.standard_normal((n, k)) * 0.05).astype(np.float32))
