@@ -32,6 +32,10 @@ typedef __attribute__((__vector_size__(2 * sizeof(unsigned int)))) unsigned int 
 constexpr int kBufFlags = 0x00020000;          // raw buffer, 32-bit data format
 constexpr uint32_t kOutOfRange = 0x80000000u;  // VGPR offset of accesses that must not happen (buffers are < 2 GiB)
 
+// Workgroup barrier that orders LDS traffic only (__syncthreads() also waits for every global load in flight,
+// i.e. for the key / value blocks requested ahead).
+__device__ inline void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 template <int DH, bool KSPLIT>
 __global__ __launch_bounds__(256, (DH == 64 ? 2 : 1)) void k_attention_mfma(AttnArgs a) {
     constexpr int NCH = DH / 64;     // 64-wide chunks of a q / k row
@@ -393,12 +397,12 @@ __global__ __launch_bounds__(256, (DH == 64 ? 2 : 1)) void k_attention_group(Att
         SD_G_STAGE(1, 1)
         SD_G_LOAD(1, kb + 3)
         SD_G_BLOCK(0, kb)
-        __syncthreads();
+        lds_barrier();
         if (kb + 1 >= n_blocks) break;
         SD_G_STAGE(0, 0)
         SD_G_LOAD(0, kb + 4)
         SD_G_BLOCK(1, kb + 1)
-        __syncthreads();
+        lds_barrier();
     }
 #undef SD_G_LOAD
 #undef SD_G_STAGE

@@ -73,7 +73,7 @@ struct SplitArgs {
     int x_stationary;   // workgroup -> tile mapping, see the kernel
 };
 
-template <int MT, int NT, int WM, int WN, int KS, int PD, int EPI, int NF>
+template <int MT, int NT, int WM, int WN, int KS, int PD, int EPI, int NF, int WNT>
 __global__ __launch_bounds__(256) void k_linear_mfma(const void* __restrict__ Xv, const bf16_t* __restrict__ W,
                                                      const float* __restrict__ bias, void* Y, int M,
                                                      int N, int K, int ldy, int tiles_m, int tiles_n, FoldIn nf,
@@ -220,9 +220,10 @@ __global__ __launch_bounds__(256) void k_linear_mfma(const void* __restrict__ Xv
     // 128-byte pieces of the same stretch.
     const int lo = c0 + (int)((long)(c1 - c0) * wk / KS), hi = c0 + (int)((long)(c1 - c0) * (wk + 1) / KS);
     const int n_mine = hi - lo;
-    // Weights that only one workgroup reads (a single row tile) are fetched with the non-temporal hint:
-    // +10 % streaming rate, and they do not push x out of L2.
-    constexpr int kAuxW = (WM * WN == 1) ? 2 : 0;
+    // WNT: weights that only one workgroup reads (a single row tile) are fetched with the non-temporal hint
+    // (+5-10 % streaming rate, and they do not push x out of L2); with several row tiles the later ones
+    // find the panel in L2 and the hint would throw that away.
+    constexpr int kAuxW = WNT ? 2 : 0;
     if (n_mine > 0) {
         u32x4 g[PD][TILES][4];
         bf16x8 f[2][TILES][4];
@@ -488,7 +489,16 @@ static hipError_t launch_variant(const void* x, const void* w, const float* bias
     const bf16_t* wb = (const bf16_t*)w;
     const FoldIn fi{ni.stats, ni.u, ni.parts, ni.eps};
     const FoldOut fo{no.gain, static_cast<bf16_t*>(no.xg), no.stats};
-#define SD_GO(EPI, NF) k_linear_mfma<MT, NT, WM, WN, KS, PD, EPI, NF><<<grid, 256, 0, st>>>(x, wb, bias, y, m, n, k, ldy, tiles_m, tiles_n, fi, fo, sk)
+    const bool stream_w = WM * WN == 1 && tiles_m == 1;
+#define SD_GO(EPI, NF)                                                                                                  \
+    do {                                                                                                                \
+        if constexpr (WM * WN == 1) {                                                                                   \
+            if (stream_w) k_linear_mfma<MT, NT, WM, WN, KS, PD, EPI, NF, 1><<<grid, 256, 0, st>>>(x, wb, bias, y, m, n, k, ldy, tiles_m, tiles_n, fi, fo, sk); \
+            else k_linear_mfma<MT, NT, WM, WN, KS, PD, EPI, NF, 0><<<grid, 256, 0, st>>>(x, wb, bias, y, m, n, k, ldy, tiles_m, tiles_n, fi, fo, sk); \
+        } else {                                                                                                        \
+            k_linear_mfma<MT, NT, WM, WN, KS, PD, EPI, NF, 0><<<grid, 256, 0, st>>>(x, wb, bias, y, m, n, k, ldy, tiles_m, tiles_n, fi, fo, sk); \
+        }                                                                                                               \
+    } while (0)
     if (ni.kind == 0) {
         switch (epi) {
             case EPI_STORE: SD_GO(EPI_STORE, 0); break;
@@ -521,10 +531,10 @@ bool linear_mfma_supported(int dtype, int m, int n, int k, int ldy) {
            ((int64_t)m + 64) * ldy * 4 < lim;
 }
 
-static std::string g_names[8][5][3];   // [variant][epilogue][fold]: kernel names as rocprof prints them
-static const char* variant_name(const char* params, int v, int epi, int nfk) {
-    std::string& s = g_names[v][epi][nfk];
-    if (s.empty()) s = std::string("k_linear_mfma<") + params + "," + std::to_string(epi) + "," + std::to_string(nfk) + ">";
+static std::string g_names[8][5][3][2];   // [variant][epilogue][fold][streamed weights]: kernel names as rocprof prints them
+static const char* variant_name(const char* params, int v, int epi, int nfk, int wnt) {
+    std::string& s = g_names[v][epi][nfk][wnt];
+    if (s.empty()) s = std::string("k_linear_mfma<") + params + "," + std::to_string(epi) + "," + std::to_string(nfk) + "," + std::to_string(wnt) + ">";
     return s.c_str();
 }
 
@@ -541,7 +551,7 @@ static int choose_variant(int m, int n) {
 
 #define SD_VARIANT(ID, MT, NT, WM, WN, KS, PD)                                                      \
     case ID:                                                                                        \
-        if (kernel_name) *kernel_name = variant_name(#MT "," #NT "," #WM "," #WN "," #KS "," #PD, ID, kepi, ni.kind); \
+        if (kernel_name) *kernel_name = variant_name(#MT "," #NT "," #WM "," #WN "," #KS "," #PD, ID, kepi, ni.kind, WM * WN == 1 && m <= 32 * MT); \
         return launch_variant<MT, NT, WM, WN, KS, PD>(x, w, bias, y, m, n, k, ldy, epi, ni, no, ws, st);
 
 // ni.kind != 0: x = bf16(h gain) and the row sums of h come from the producer of h (see FoldIn), bias = W beta + bias.

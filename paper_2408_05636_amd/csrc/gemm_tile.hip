@@ -28,6 +28,11 @@ typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 constexpr int kTileFlags = 0x00020000;            // raw buffer, 32-bit data format
 constexpr uint32_t kTileOutOfRange = 0x80000000u;  // voffset of accesses that must not happen (buffers < 2 GiB)
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every global load in flight,
+// which would cut the two-chunk prefetch down to what one multiply phase can hide; the stage hand-over needs the
+// LDS writes and reads alone.
+__device__ inline void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 __device__ inline float gelu_tile(float x) {
     const float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
     return x / (1.f + __expf(-2.f * u));
@@ -199,7 +204,7 @@ __global__ __launch_bounds__(256) void k_linear_tile(const void* __restrict__ Xv
         SD_TILE_GLOAD(NEXT, min((C) + 3, last))         \
         __builtin_amdgcn_sched_barrier(0);              \
         SD_TILE_COMPUTE(CUR)                            \
-        __syncthreads();                                \
+        lds_barrier();                                  \
     }
     const int last = n_chunks - 1;
     SD_TILE_GLOAD(0, 0)
