@@ -540,11 +540,13 @@ static const char* variant_name(const char* params, int v, int epi, int nfk, int
 
 // Tile choice by shape.  Up to 64 rows the weights are the whole cost: one workgroup column per 32 weight
 // rows, all x rows in one wave (so W is fetched once), K split over the waves and over workgroups.
-static int choose_variant(int m, int n) {
+static int choose_variant(int m, int n, int k) {
     const long tiles64 = (long)((n + 63) / 64) * ((m + 63) / 64);
+    const long tiles32 = (long)((n + 31) / 32) * ((m + 31) / 32);
     if (m <= 32) return 0;
     if (m <= 64) return 6;
     if (tiles64 < 160) return 0;                // few tiles: smallest tile, K split over the four waves
+    if (k >= 2048 && tiles32 <= 1024) return 0; // long K, a few tiles per CU: the K split still wins (1056 x 768 x 3072: 22 vs 29 us)
     if (tiles64 < 4096) return 5;
     return 3;
 }
@@ -568,7 +570,7 @@ hipError_t launch_linear_mfma(const void* x, const void* w, const float* bias, v
     }
     if (g_variant_override == 7 || g_variant_override == 8 || (g_variant_override < 0 && linear_tile_preferred(m, n, k)))
         return launch_linear_tile(x, w, bias, y, m, n, k, ldy, epi, ni, no, g_variant_override == 8 ? 64 : (g_variant_override == 7 ? 128 : 0), st, kernel_name);
-    int v = (g_variant_override >= 0 && g_variant_override != 9) ? g_variant_override : choose_variant(m, n);
+    int v = (g_variant_override >= 0 && g_variant_override != 9) ? g_variant_override : choose_variant(m, n, k);
     if (ni.kind && v == 3) v = 5;               // the 128 x 128 wave-private tile is not instantiated with a fold
     switch (v) {
         SD_VARIANT(0, 1, 1, 1, 1, 4, 2)     // 32 x 32 tile, four waves split K
