@@ -296,6 +296,7 @@ struct sd_handle {
     std::unordered_set<uint64_t> seen;   // launch sequences run once so far (captured on their second use)
     bool use_graphs = true;
     bool greedy = false;                 // temperature 0 instead of the stochastic rule
+    int temb_T = 0;                      // number of steps the timestep-embedding table in the workspace was built for
     // KV-cache state per sequence: number of cached positions and a hash of their tokens
     std::vector<int32_t> cached_len;
     std::vector<uint64_t> cached_hash, cached_fnv;
@@ -774,15 +775,25 @@ int prepare_draft(sd_handle* h, int batch, const int32_t* prefix, const int32_t*
     return SD_OK;
 }
 
+// temb[j-1] for j = 1..T depends on the drafter's weights and on T only: built once per T (eagerly, outside any
+// captured sequence) and kept in the workspace until a call asks for another T.
+int ensure_timestep_table(sd_handle* h, int T) {
+    if (h->temb_T == T) return SD_OK;
+    const Model& m = h->drafter;
+    SD_LAUNCH(h, "k_timestep_matvec(x2)", 2.0 * m.c.d_model * m.c.d_model * m.ew, 4.0 * T * m.c.d_model * m.c.d_model,
+              launch_timestep_embed(m.c.dtype, m.t_w1, m.t_b1, m.t_w2, m.t_b2, h->buf.temb_hidden, h->buf.temb, T, m.c.d_model, h->st));
+    h->temb_T = T;
+    return SD_OK;
+}
+
 // The T reverse-diffusion steps (launches only: capturable).  Leaves z (draft), q, qtok in the workspace.
+// The timestep table is in place (ensure_timestep_table).
 int enqueue_draft(sd_handle* h, int batch, int gamma, int T) {
     Buffers& B = h->buf;
     const Model& m = h->drafter;
     const MapSet& rm = h->maps[0];
     int rc;
     SD_LAUNCH(h, "k_fill_i32", 4.0 * batch * gamma, 0, launch_fill_i32(B.z, batch * gamma, m.c.vocab, h->st));   // z <- [MASK]^gamma
-    SD_LAUNCH(h, "k_timestep_matvec(x2)", 2.0 * m.c.d_model * m.c.d_model * m.ew, 4.0 * T * m.c.d_model * m.c.d_model,
-              launch_timestep_embed(m.c.dtype, m.t_w1, m.t_b1, m.t_w2, m.t_b2, B.temb_hidden, B.temb, T, m.c.d_model, h->st));
     const SampleScratch ss = sampling_scratch(B.sample_scratch, (int)h->lim.rows_head, m.c.vocab);
     for (int j = T; j >= 1; --j) {
         rc = run_layers(h, m, rm, B.temb + (int64_t)(j - 1) * m.c.d_model);
@@ -1005,6 +1016,8 @@ int32_t sd_draft(sd_handle* h, int32_t batch, const int32_t* prefix, const int32
     if (rc) return rc;
     rc = prepare_draft(h, batch, prefix, prefix_len, n, gamma, seed);
     if (rc) return rc;
+    rc = ensure_timestep_table(h, T);
+    if (rc) return rc;
     rc = replay(h, shape_key(1 + (h->greedy ? 16 : 0), batch, gamma, T, prefix_len, nullptr), [&] { return enqueue_draft(h, batch, gamma, T); });
     if (rc) return rc;
     const int64_t cnt = (int64_t)batch * gamma;
@@ -1060,6 +1073,8 @@ int32_t sd_round(sd_handle* h, int32_t batch, const int32_t* prefix, const int32
     rc = prepare_draft(h, batch, prefix, prefix_len, n, gamma, seed);
     if (rc) return rc;
     rc = prepare_target(h, batch, prefix, prefix_len, n, gamma);
+    if (rc) return rc;
+    rc = ensure_timestep_table(h, T);
     if (rc) return rc;
     rc = replay(h, shape_key(3 + (h->greedy ? 16 : 0), batch, gamma, T, prefix_len, nullptr), [&] {
         int r2 = enqueue_draft(h, batch, gamma, T);
@@ -1132,7 +1147,8 @@ int32_t sd_drafter_logits(sd_handle* h, int32_t batch, const int32_t* tokens, co
     memcpy(h->stage_z, blk.data(), blk.size() * 4);
     SD_HIP(h, hipMemcpyAsync(h->buf.z, h->stage_z, blk.size() * 4, hipMemcpyHostToDevice, h->st));
     const Model& m = h->drafter;
-    SD_HIP(h, launch_timestep_embed(m.c.dtype, m.t_w1, m.t_b1, m.t_w2, m.t_b2, h->buf.temb_hidden, h->buf.temb, T, m.c.d_model, h->st));
+    rc = ensure_timestep_table(h, T);
+    if (rc) return rc;
     rc = run_layers(h, m, h->maps[0], h->buf.temb + (int64_t)(step - 1) * m.c.d_model);
     if (rc) return rc;
     rc = run_head(h, m, h->maps[0].blk, batch * gamma, h->buf.logits_d);
