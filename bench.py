@@ -130,6 +130,7 @@ def main():
     log(f"timed pass done: {ms_per_step:.3f} ms per round")
     roof = None
     phases = None
+    kernels = None
     if not a.no_profile:
         sd.sd_profile_begin()
         for i in range(a.steps):
@@ -137,8 +138,24 @@ def main():
         prof = sd.sd_profile_end()
         prof.sort(key=lambda e: -e["ms"])
         total = sum(e["ms"] for e in prof)
-        phases = [{"kernel": e["name"], "launches_per_step": e["launches"] / a.steps,
-                   "us_per_launch": round(1e3 * e["ms"] / e["launches"], 3), "share": round(e["ms"] / total, 4)} for e in prof]
+        for e in prof:                                    # entry names are "<part of the round>:<kernel>"
+            e["phase"], _, e["name"] = e["name"].rpartition(":")
+        kernels = [{"phase": e["phase"], "kernel": e["name"], "launches_per_step": e["launches"] / a.steps,
+                    "us_per_launch": round(1e3 * e["ms"] / e["launches"], 3), "share": round(e["ms"] / total, 4)} for e in prof]
+        # Per part of the round: event time, algorithmic bytes and flops, and the time the same work takes at the
+        # HBM and matrix-core peaks (the larger of the two is that part's roofline).
+        phases = {}
+        for ph in ("draft", "verify", "accept"):
+            es = [e for e in prof if e["phase"] == ph]
+            if not es:
+                continue
+            us = 1e3 * sum(e["ms"] for e in es) / a.steps
+            by = sum(e["bytes"] for e in es) / a.steps
+            fl = sum(e["flops"] for e in es) / a.steps
+            t_hbm, t_mfma = by / (PEAK_HBM_GBS * 1e9) * 1e6, fl / (PEAK_MFMA_TFLOPS[t.dtype] * 1e12) * 1e6
+            phases[ph] = {"us": round(us, 1), "launches": sum(e["launches"] for e in es) / a.steps, "algorithmic_MB": round(by / 1e6, 1),
+                          "GFLOP": round(fl / 1e9, 2), "us_at_hbm_peak": round(t_hbm, 1), "us_at_mfma_peak": round(t_mfma, 1),
+                          "bound": "hbm" if t_hbm >= t_mfma else "mfma", "frac_of_roofline": round(max(t_hbm, t_mfma) / us, 4)}
         e = prof[0]
         us = 1e3 * e["ms"] / e["launches"]
         gbs = e["bytes"] / e["launches"] / (us * 1e-6) / 1e9
@@ -170,7 +187,7 @@ def main():
                                f"gamma={gamma}, T={T}, batch={B}, random-init weights" + (", temperature 0" if a.greedy else "")},
         "round_latency_us": ms_per_step * 1e3,
         "mean_accepted_per_round": accepted / (a.steps * B),
-        "roofline": roof, "cpu_baseline": cpu, "kernels": phases,
+        "roofline": roof, "cpu_baseline": cpu, "phases": phases, "kernels": kernels,
     }
     print(json.dumps(out))
 

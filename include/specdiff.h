@@ -227,7 +227,8 @@ int32_t sd_set_graph_replay(sd_handle *h, int32_t enable);
 
 /* ---- per-kernel timing ----------------------------------------------------------------------
  * Between sd_profile_begin and sd_profile_end every kernel launch of the handle is bracketed by
- * HIP events on its stream; entries accumulate, per kernel name, the launch count, the summed
+ * HIP events on its stream; entries accumulate, per part of the round and kernel name ("draft:", "verify:"
+ * or "accept:" followed by the name; the bare name for launches outside a round), the launch count, the summed
  * elapsed milliseconds and the summed algorithmic bytes and flops of those launches (operands
  * read once, results written once).  The events cost a few microseconds per launch: time a
  * round without profiling.  name: caller buffer of name_cap bytes. */

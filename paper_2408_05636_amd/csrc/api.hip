@@ -271,6 +271,7 @@ struct Profiler {
     size_t used = 0;
     std::vector<int> pending;            // entry index per used pair
     std::vector<ProfEntry> entries;
+    const char* phase = "";              // prefix of the entry names: which part of the round is being enqueued
 };
 
 // ------------------------------------------------------------------------------------------
@@ -334,10 +335,11 @@ void prof_stop(sd_handle* h, const char* name, double bytes, double flops) {
     Profiler& p = h->prof;
     if (!p.on) return;
     (void)hipEventRecord(p.events[p.used + 1], h->st);
+    const std::string key = std::string(p.phase) + name;
     int idx = -1;
     for (size_t i = 0; i < p.entries.size(); ++i)
-        if (p.entries[i].name == name) { idx = (int)i; break; }
-    if (idx < 0) { p.entries.push_back(ProfEntry()); idx = (int)p.entries.size() - 1; p.entries[idx].name = name; }
+        if (p.entries[i].name == key) { idx = (int)i; break; }
+    if (idx < 0) { p.entries.push_back(ProfEntry()); idx = (int)p.entries.size() - 1; p.entries[idx].name = key; }
     p.entries[idx].launches += 1;
     p.entries[idx].bytes += bytes;
     p.entries[idx].flops += flops;
@@ -732,6 +734,7 @@ int check_round_shapes(sd_handle* h, int batch, const int32_t* len, int gamma) {
 int do_prefill(sd_handle* h, int batch, const int32_t* prefix, const int32_t* len, int64_t n_tokens) {
     int rc = upload_rows(h, 2, batch, prefix, len, n_tokens, 0);
     if (rc) return rc;
+    h->prof.phase = "prefill:";
     rc = run_layers(h, h->target, h->maps[2], nullptr);
     if (rc) return rc;
     int64_t off = 0;
@@ -780,6 +783,7 @@ int prepare_draft(sd_handle* h, int batch, const int32_t* prefix, const int32_t*
 int ensure_timestep_table(sd_handle* h, int T) {
     if (h->temb_T == T) return SD_OK;
     const Model& m = h->drafter;
+    h->prof.phase = "draft:";
     SD_LAUNCH(h, "k_timestep_matvec(x2)", 2.0 * m.c.d_model * m.c.d_model * m.ew, 4.0 * T * m.c.d_model * m.c.d_model,
               launch_timestep_embed(m.c.dtype, m.t_w1, m.t_b1, m.t_w2, m.t_b2, h->buf.temb_hidden, h->buf.temb, T, m.c.d_model, h->st));
     h->temb_T = T;
@@ -793,6 +797,7 @@ int enqueue_draft(sd_handle* h, int batch, int gamma, int T) {
     const Model& m = h->drafter;
     const MapSet& rm = h->maps[0];
     int rc;
+    h->prof.phase = "draft:";
     SD_LAUNCH(h, "k_fill_i32", 4.0 * batch * gamma, 0, launch_fill_i32(B.z, batch * gamma, m.c.vocab, h->st));   // z <- [MASK]^gamma
     const SampleScratch ss = sampling_scratch(B.sample_scratch, (int)h->lim.rows_head, m.c.vocab);
     for (int j = T; j >= 1; --j) {
@@ -823,12 +828,14 @@ int prepare_target(sd_handle* h, int batch, const int32_t* prefix, const int32_t
 // Target forward over the gamma+1 query rows (draft tokens taken from buf.z) -> buf.logits_t (capturable).
 int enqueue_target(sd_handle* h) {
     const MapSet& rm = h->maps[1];
+    h->prof.phase = "verify:";
     const int rc = run_layers(h, h->target, rm, nullptr);
     if (rc) return rc;
     return run_head(h, h->target, nullptr, rm.rows, h->buf.logits_t);
 }
 
 int enqueue_accept(sd_handle* h, int batch, int gamma, const float* q_dev) {
+    h->prof.phase = "accept:";
     const SampleScratch ss = sampling_scratch(h->buf.sample_scratch, (int)h->lim.rows_head, h->target.c.vocab);
     if (h->greedy) {
         SD_LAUNCH(h, "accept_greedy(k_chunk_argmax+k_greedy_accept)", (double)batch * (gamma + 1) * h->target.ld * 4, 0,
