@@ -9,14 +9,16 @@
 //                      -> lane = query, its 16 accumulators = 16 keys: row max / sum are in-lane,
 //                         plus one exchange between the two lane halves;
 //   O^T += V^T P^T     B = P^T comes straight from the S^T accumulators (cast to bf16);
-//                      A = V^T needs keys contiguous per d.  The matrix cores transpose the block:
-//                      V (rows = keys, as loaded) times a 0/1 selection matrix lands in the
-//                      accumulators with lane = d and registers = keys, exactly (a bf16 value times one
-//                      plus zeros), which after a cast back to bf16 is the V^T operand.  No LDS, no
-//                      barrier and no cross-lane traffic in the loop.
-// The K and V rows are fed to those MFMAs in a permuted order chosen so that accumulator e of lane
-// half h is key 16h + e of the block: then the P^T operand of MFMA step s is registers 8s..8s+7 of
-// the scores and the matching V^T operand is registers 8s..8s+7 of the transposed block.
+//                      A = V^T needs keys contiguous per d, while the block sits in LDS as loaded (rows = keys).
+//                      The transposing LDS read of gfx950 (ds_read_b64_tr_b16) delivers exactly that: within
+//                      each group of 16 lanes, lane 4a + c receives element c of the 8-byte pieces addressed by
+//                      lanes a, a + 4, a + 8, a + 12.  Lanes a + 4j point at key j of a run of four keys and at
+//                      the four d values 4a .. 4a + 3, so lane 4a + c ends up with four consecutive keys of
+//                      d = 4a + c; two such reads make the 8-key operand.  No extra MFMA, no conversion and no
+//                      cross-lane traffic in the loop.
+// The K rows are fed to the score MFMAs in a permuted order chosen so that accumulator e of lane half h is
+// key 16h + e of the block: then the P^T operand of MFMA step s is registers 8s..8s+7 of the scores, and the
+// matching V^T operand is keys 16h + 8s .. 16h + 8s + 7.
 // A workgroup is 4 waves: either 4 query tiles (large batches) or 4 interleaved key ranges of one
 // tile merged through LDS (few query rows: the target's gamma+1 rows, batch-1 drafter).
 #include "common.h"
@@ -35,6 +37,30 @@ constexpr uint32_t kOutOfRange = 0x80000000u;  // VGPR offset of accesses that m
 // Workgroup barrier that orders LDS traffic only (__syncthreads() also waits for every global load in flight,
 // i.e. for the key / value blocks requested ahead).
 __device__ inline void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4;
+// Offsets (in 2-byte units from the start of a V tile in LDS: [64-wide d chunk][32 keys][8 pieces of 16 bytes],
+// piece p of key row x at p ^ swz(x)) of the two transposing reads that give this lane the V^T operand of d tile t,
+// MFMA step s2: keys 16 half + 8 s2 + 0..3 and + 4..7 of d = 32 t + (lane & 31).
+__device__ inline void vt_offsets(int lane, int t, int s2, int* off) {
+    const int s = lane & 15, grp = lane >> 4;
+    const int d = 32 * t + 16 * (grp & 1) + 4 * (s & 3);
+#pragma unroll
+    for (int u4 = 0; u4 < 2; ++u4) {
+        const int row = 16 * (grp >> 1) + 8 * s2 + (s >> 2) + 4 * u4;
+        const int piece = ((d & 63) >> 3) ^ ((row & 7) ^ ((row >> 4) & 1));
+        off[u4] = ((d >> 6) * 256 + row * 8 + piece) * 8 + ((d & 7) >> 2) * 4;
+    }
+}
+__device__ inline bf16x8 vt_operand(const u32x4* v_tile, const int* off) {
+    typedef s16x4 __attribute__((address_space(3))) * lds_ptr;
+    const short* base = reinterpret_cast<const short*>(v_tile);
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(base + off[0]));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(base + off[1]));
+    typedef __attribute__((__vector_size__(8 * sizeof(short)))) short s16x8;
+    const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, both);
+}
 
 template <int DH, bool KSPLIT>
 __global__ __launch_bounds__(256, (DH == 64 ? 2 : 1)) void k_attention_mfma(AttnArgs a) {
@@ -106,12 +132,11 @@ __global__ __launch_bounds__(256, (DH == 64 ? 2 : 1)) void k_attention_mfma(Attn
         wslot[i] = row * 8 + (pc ^ ((row & 7) ^ ((row >> 4) & 1)));
     }
     const int rkey = (pi_r & 7) ^ ((pi_r >> 4) & 1);
-    // Selection matrix of the transposing MFMA, k chunk c2 (16 values of d): B[k][col] = 1 iff 16 c2 + k == col.
-    bf16x8 sel[2];
+    int voff[DT][2][2];                  // transposing reads of the V^T operands, see vt_offsets
 #pragma unroll
-    for (int c2 = 0; c2 < 2; ++c2)
+    for (int t = 0; t < DT; ++t)
 #pragma unroll
-        for (int u = 0; u < 8; ++u) sel[c2][u] = static_cast<bf16_t>((16 * c2 + 8 * half + u == r) ? 1.f : 0.f);
+        for (int s2 = 0; s2 < 2; ++s2) vt_offsets(lane, t, s2, voff[t][s2]);
     const uint32_t blk_bytes = 32u * (uint32_t)a.kv_ld * 2u;
 
     float m_run = -INFINITY, l_run = 0.f;
@@ -147,16 +172,10 @@ __global__ __launch_bounds__(256, (DH == 64 ? 2 : 1)) void k_attention_mfma(Attn
         _Pragma("unroll") for (int c = 0; c < NCH; ++c) _Pragma("unroll") for (int q4 = 0; q4 < 4; ++q4) \
             s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                                                 \
                 __builtin_bit_cast(bf16x8, stage_k[c * 256 + pi_r * 8 + ((4 * half + q4) ^ rkey)]), qf[c][q4], s, 0, 0, 0); \
-        /* V^T of the block: tile t (d = 32 t ..) = sum over its two 16-wide d chunks of V_chunk x selection */ \
-        floatx16 vt_[DT];                                                                                \
-        _Pragma("unroll") for (int t = 0; t < DT; ++t) {                                                 \
-            _Pragma("unroll") for (int e = 0; e < 16; ++e) vt_[t][e] = 0.f;                              \
-            _Pragma("unroll") for (int c2 = 0; c2 < 2; ++c2) {                                           \
-                const int pv_ = 2 * (2 * t + c2) + half;              /* 16-byte piece of the V row: d = 8 pv_ .. */ \
-                vt_[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                                        \
-                    __builtin_bit_cast(bf16x8, stage_v[(pv_ >> 3) * 256 + pi_r * 8 + ((pv_ & 7) ^ rkey)]), sel[c2], vt_[t], 0, 0, 0); \
-            }                                                                                            \
-        }                                                                                                \
+        /* V^T operands of the block, requested now so that they arrive during the softmax */            \
+        bf16x8 vfa_[DT][2];                                                                              \
+        _Pragma("unroll") for (int t = 0; t < DT; ++t) _Pragma("unroll") for (int s2 = 0; s2 < 2; ++s2)  \
+            vfa_[t][s2] = vt_operand(stage_v, voff[t][s2]);                                              \
         /* online softmax on the raw scores (the scale is positive and is applied inside the exponent);     \
            accumulator e of this lane is key KB*32 + 16*half + e.  Only blocks that reach past the smallest \
            key count of the tile need masking. */                                                         \
@@ -184,9 +203,7 @@ __global__ __launch_bounds__(256, (DH == 64 ? 2 : 1)) void k_attention_mfma(Attn
             _Pragma("unroll") for (int t = 0; t < DT; ++t) _Pragma("unroll") for (int e = 0; e < 16; ++e) o[t][e] *= alpha_; \
         }                                                                                                \
         _Pragma("unroll") for (int t = 0; t < DT; ++t) _Pragma("unroll") for (int s2 = 0; s2 < 2; ++s2) { \
-            bf16x8 vf_;                                                                                  \
-            _Pragma("unroll") for (int u = 0; u < 8; ++u) vf_[u] = static_cast<bf16_t>(vt_[t][8 * s2 + u]); \
-            o[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf_, pf_[s2], o[t], 0, 0, 0);                 \
+            o[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfa_[t][s2], pf_[s2], o[t], 0, 0, 0);         \
         }                                                                                                \
     }
     // Two register sets alternate (no copies): while one block is processed the next is in flight; the block
@@ -301,11 +318,11 @@ __global__ __launch_bounds__(256, (DH == 64 ? 2 : 1)) void k_attention_group(Att
 
     const int pi_r = 16 * ((r >> 2) & 1) + 4 * (r >> 3) + (r & 3);      // see k_attention_mfma
     const int rkey = (pi_r & 7) ^ ((pi_r >> 4) & 1);
-    bf16x8 sel[2];
+    int voff[DT][2][2];                  // transposing reads of the V^T operands, see vt_offsets
 #pragma unroll
-    for (int c2 = 0; c2 < 2; ++c2)
+    for (int t = 0; t < DT; ++t)
 #pragma unroll
-        for (int u = 0; u < 8; ++u) sel[c2][u] = static_cast<bf16_t>((16 * c2 + 8 * half + u == r) ? 1.f : 0.f);
+        for (int s2 = 0; s2 < 2; ++s2) vt_offsets(lane, t, s2, voff[t][s2]);
     // cooperative loader: thread t brings piece t & 7 of key row t >> 3 of the block (per 64-wide chunk)
     const int lrow = threadIdx.x >> 3, pc = threadIdx.x & 7;
     const uint32_t kv_lane = ((uint32_t)lrow * (uint32_t)a.kv_ld + 8u * pc) * 2u;
@@ -347,15 +364,9 @@ __global__ __launch_bounds__(256, (DH == 64 ? 2 : 1)) void k_attention_group(Att
         _Pragma("unroll") for (int c = 0; c < NCH; ++c) _Pragma("unroll") for (int q4 = 0; q4 < 4; ++q4) \
             s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                                                 \
                 __builtin_bit_cast(bf16x8, sk_[c * 256 + pi_r * 8 + ((4 * half + q4) ^ rkey)]), qf[c][q4], s, 0, 0, 0); \
-        floatx16 vt_[DT];                                                                                \
-        _Pragma("unroll") for (int t = 0; t < DT; ++t) {                                                 \
-            _Pragma("unroll") for (int e = 0; e < 16; ++e) vt_[t][e] = 0.f;                              \
-            _Pragma("unroll") for (int c2 = 0; c2 < 2; ++c2) {                                           \
-                const int pv_ = 2 * (2 * t + c2) + half;                                                 \
-                vt_[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                                        \
-                    __builtin_bit_cast(bf16x8, sv_[(pv_ >> 3) * 256 + pi_r * 8 + ((pv_ & 7) ^ rkey)]), sel[c2], vt_[t], 0, 0, 0); \
-            }                                                                                            \
-        }                                                                                                \
+        bf16x8 vfa_[DT][2];                                                                              \
+        _Pragma("unroll") for (int t = 0; t < DT; ++t) _Pragma("unroll") for (int s2 = 0; s2 < 2; ++s2)  \
+            vfa_[t][s2] = vt_operand(sv_, voff[t][s2]);                                                  \
         if ((KB) * 32 + 32 > kv_min) {                                                                   \
             _Pragma("unroll") for (int e = 0; e < 16; ++e)                                               \
                 s[e] = ((KB) * 32 + 16 * half + e < kvl) ? s[e] : -INFINITY;                             \
@@ -380,9 +391,7 @@ __global__ __launch_bounds__(256, (DH == 64 ? 2 : 1)) void k_attention_group(Att
             _Pragma("unroll") for (int t = 0; t < DT; ++t) _Pragma("unroll") for (int e = 0; e < 16; ++e) o[t][e] *= alpha_; \
         }                                                                                                \
         _Pragma("unroll") for (int t = 0; t < DT; ++t) _Pragma("unroll") for (int s2 = 0; s2 < 2; ++s2) { \
-            bf16x8 vf_;                                                                                  \
-            _Pragma("unroll") for (int u = 0; u < 8; ++u) vf_[u] = static_cast<bf16_t>(vt_[t][8 * s2 + u]); \
-            o[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf_, pf_[s2], o[t], 0, 0, 0);                 \
+            o[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfa_[t][s2], pf_[s2], o[t], 0, 0, 0);         \
         }                                                                                                \
     }
     // Step kb: park block kb + 1 (register set (kb + 1) & 1) in LDS stage (kb + 1) & 1 -- last read before the
