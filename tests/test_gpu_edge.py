@@ -44,3 +44,29 @@ def test_largest_step_count():
     assert ((draft >= 0) & (draft < t.vocab)).all() and 0 <= n[0] <= 3
     check_rounds(sd, prefix, 3, 64, seeds=[8])
     sd.close()
+
+
+def test_step_count_changes_back_and_forth():
+    """The timestep-embedding table is kept between calls and rebuilt when T changes: T = 4, 8, 4 on one handle
+    (and one eager, one captured and one replayed launch sequence per T) each reproduce Algorithm 1."""
+    sd, t, d, Wt, Wd = make("tiny", seed=24, max_batch=1, gamma_max=8)
+    prefix = [synth.gen_prefix(t.vocab, 20, 11)]
+    for T in (4, 8, 4, 8):
+        check_rounds(sd, prefix, 6, T, seeds=[30 + T, 31 + T])
+    sd.close()
+
+
+def test_profile_entries_name_the_part_of_the_round():
+    sd, t, d, Wt, Wd = make("tiny", seed=25, max_batch=1, gamma_max=8)
+    prefix = [synth.gen_prefix(t.vocab, 16, 12)]
+    sd.sd_round(prefix, 4, 3, 1)
+    sd.sd_profile_begin()
+    sd.sd_round(prefix, 4, 3, 2)
+    prof = sd.sd_profile_end()
+    parts = {e["name"].split(":")[0] for e in prof}
+    assert parts == {"draft", "verify", "accept"}, parts
+    launches = {p: sum(e["launches"] for e in prof if e["name"].startswith(p + ":")) for p in parts}
+    # the draft part is T forwards (every layer kernel T times), the verify part one forward
+    assert launches["draft"] > 2 * launches["verify"] and launches["accept"] >= 1
+    assert all(e["ms"] > 0 for e in prof)
+    sd.close()
