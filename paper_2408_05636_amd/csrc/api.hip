@@ -95,6 +95,7 @@ struct Model {
     int dh, dq, dkv, ld, ew;
     const void *wte = nullptr, *wpe = nullptr, *t_w1 = nullptr, *t_w2 = nullptr, *w_head = nullptr;
     const float *t_b1 = nullptr, *t_b2 = nullptr, *lnf_g = nullptr, *lnf_b = nullptr;
+    float *fu_head = nullptr, *fv_head = nullptr;   // final LayerNorm folded into the LM head: u = W g, v = W beta
     std::vector<Layer> L;
     bool fold = false;       // norms in front of QKV / MLP-up are folded into those contractions
 };
@@ -197,13 +198,13 @@ Limits limits_of(const sd_model_config& t, const sd_model_config& d, int max_bat
     return l;
 }
 
-// floats needed for the folded LayerNorm vectors of a model (u and v for QKV and MLP-up of every layer)
+// floats needed for the folded LayerNorm vectors of a model (u and v for QKV and MLP-up of every layer and for the LM head)
 constexpr int64_t kSplitBytes = kSplitTicketBytes + (64 << 20);
 
 int64_t fold_floats(const sd_model_config& c) {
     if (c.arch != SD_ARCH_GPT2 || c.dtype != SD_DTYPE_BF16) return 64;
     const int64_t qkv = (int64_t)c.d_model + 2 * (int64_t)c.n_kv_head * (c.d_model / c.n_head);
-    return (int64_t)c.n_layer * 2 * (align_up(qkv, 64) + align_up(c.d_ff, 64));
+    return (int64_t)c.n_layer * 2 * (align_up(qkv, 64) + align_up(c.d_ff, 64)) + 2 * align_up(c.vocab, 64);
 }
 
 int64_t carve(Arena& a, Buffers& b, const sd_model_config& t, const sd_model_config& d, int max_batch, int gamma_max) {
@@ -253,6 +254,7 @@ struct MapSet {
     int32_t* groups = nullptr;           // attention workgroup -> up to four tiles of one sequence and head (AttnArgs::groups)
     int n_groups = 0, group_tiles = 0;
     int rows = 0, n_tiles = 0, max_kv = 0;
+    int head_row0 = -1;                  // first of the rows the LM head reads when they are one contiguous run, else -1
     double kv_sum = 0, kv_rows = 0;     // sum of kv_len over rows; distinct key rows
     int64_t bytes = -1;
 };
@@ -298,6 +300,7 @@ struct sd_handle {
     bool use_graphs = true;
     bool greedy = false;                 // temperature 0 instead of the stochastic rule
     int temb_T = 0;                      // number of steps the timestep-embedding table in the workspace was built for
+    bool head_folded = false;            // the last run_layers left x and row sums for the final normalisation (run_head folds it)
     // KV-cache state per sequence: number of cached positions and a hash of their tokens
     std::vector<int32_t> cached_len;
     std::vector<uint64_t> cached_hash, cached_fnv;
@@ -554,6 +557,7 @@ int upload_rows(sd_handle* h, int mode, int batch, const int32_t* tokens, const 
     ms.order = (int32_t*)(db + o_order); ms.n_order = (int)n_order;
     ms.groups = (int32_t*)(db + o_groups); ms.n_groups = (int)n_groups; ms.group_tiles = group_tiles;
     ms.rows = (int)rows; ms.n_tiles = (int)n_tiles; ms.max_kv = max_kv; ms.kv_sum = kv_sum; ms.kv_rows = kv_rows;
+    ms.head_row0 = mode == 1 ? 0 : (mode == 0 && batch == 1 ? len[0] : -1);   // target: all rows; drafter: the block of a single sequence
     ms.bytes = bytes;
     return SD_OK;
 }
@@ -632,7 +636,9 @@ int run_linear(sd_handle* h, int dt, const void* x, const void* w, const float* 
 // writes the residual stream -- the embedding kernel, the attention-output and MLP-down contractions --
 // also writes xn = bf16(h * gain of the next normalisation) and the partial row sums, so a layer is five
 // launches (QKV, attention, attention-output, MLP-up, MLP-down) with no normalisation kernel.
-int run_layers(sd_handle* h, const Model& m, const MapSet& rm, const float* temb) {
+// head_rows > 0: an LM head over head_rows rows follows; when those rows are one contiguous run the last residual
+// epilogue also prepares the final normalisation for it (x = bf16(h gain_f), row sums), and run_head folds it.
+int run_layers(sd_handle* h, const Model& m, const MapSet& rm, const float* temb, int head_rows = 0) {
     Buffers& B = h->buf;
     const sd_model_config& c = m.c;
     const int rows = rm.rows, d = c.d_model, dt = c.dtype;
@@ -646,6 +652,8 @@ int run_layers(sd_handle* h, const Model& m, const MapSet& rm, const float* temb
     const bool fold = m.fold && linear_mfma_supported(dt, rows, qkv_w, d, qkv_w) && linear_mfma_supported(dt, rows, d, d, d) &&
                       linear_mfma_supported(dt, rows, up_w, d, up_w) && linear_mfma_supported(dt, rows, d, c.d_ff, d);
     const int parts_d = (d + 31) / 32;
+    const bool head_fold = fold && head_rows > 0 && rm.head_row0 >= 0 && linear_mfma_supported(dt, head_rows, c.vocab, d, m.ld);
+    h->head_folded = head_fold;
     int parts = 1;                      // partial row sums per row currently in buf.stats
     auto fold_in = [&](const float* u) {
         NormIn ni;
@@ -709,15 +717,25 @@ int run_layers(sd_handle* h, const Model& m, const MapSet& rm, const float* temb
         // MLP down: h += ..., and xn / row sums for the first normalisation of the next layer
         const bool more = fold && i + 1 < c.n_layer;
         if ((rc = run_linear(h, dt, down_x, l.w_proj, ln ? l.b_proj : nullptr, B.h, rows, d, c.d_ff, d, EPI_RESID, NormIn(),
-                             more ? fold_out(m.L[i + 1].ln1_g) : NormOut()))) return rc;
+                             more ? fold_out(m.L[i + 1].ln1_g) : (head_fold ? fold_out(m.lnf_g) : NormOut())))) return rc;
     }
     return SD_OK;
 }
 
-// Final norm on selected rows + LM head -> fp32 logits [n_rows, ld].
-int run_head(sd_handle* h, const Model& m, const int32_t* idx, int n_rows, float* logits) {
+// Final norm on selected rows + LM head -> fp32 logits [n_rows, ld].  idx: the rows (NULL: rows 0 .. n_rows - 1);
+// row0: their first row when they are one contiguous run (MapSet::head_row0).
+int run_head(sd_handle* h, const Model& m, const int32_t* idx, int row0, int n_rows, float* logits) {
     Buffers& B = h->buf;
     const sd_model_config& c = m.c;
+    if (h->head_folded && row0 >= 0) {
+        // the last residual epilogue left x = bf16(h gain_f) and the row sums of every row: no normalisation kernel
+        const bool ln = c.arch == SD_ARCH_GPT2;
+        const int parts = (c.d_model + 31) / 32;
+        NormIn ni;
+        ni.kind = ln ? 1 : 2; ni.stats = B.stats + (int64_t)row0 * parts * 2; ni.parts = parts; ni.u = ln ? m.fu_head : nullptr; ni.eps = c.norm_eps;
+        const char* x = static_cast<const char*>(B.xn) + (int64_t)row0 * c.d_model * 2;
+        return run_linear(h, c.dtype, x, m.w_head, ln ? m.fv_head : nullptr, logits, n_rows, c.vocab, c.d_model, m.ld, EPI_F32, ni);
+    }
     SD_LAUNCH(h, "k_norm", (double)n_rows * c.d_model * (4 + m.ew), 0, launch_norm(c.dtype, B.h, idx, m.lnf_g, m.lnf_b, B.xf, n_rows, c.d_model, c.norm_eps, h->st));
     return run_linear(h, c.dtype, B.xf, m.w_head, nullptr, logits, n_rows, c.vocab, c.d_model, m.ld, EPI_F32);
 }
@@ -801,9 +819,9 @@ int enqueue_draft(sd_handle* h, int batch, int gamma, int T) {
     SD_LAUNCH(h, "k_fill_i32", 4.0 * batch * gamma, 0, launch_fill_i32(B.z, batch * gamma, m.c.vocab, h->st));   // z <- [MASK]^gamma
     const SampleScratch ss = sampling_scratch(B.sample_scratch, (int)h->lim.rows_head, m.c.vocab);
     for (int j = T; j >= 1; --j) {
-        rc = run_layers(h, m, rm, B.temb + (int64_t)(j - 1) * m.c.d_model);
+        rc = run_layers(h, m, rm, B.temb + (int64_t)(j - 1) * m.c.d_model, batch * gamma);
         if (rc) return rc;
-        rc = run_head(h, m, rm.blk, batch * gamma, B.logits_d);
+        rc = run_head(h, m, rm.blk, rm.head_row0, batch * gamma, B.logits_d);
         if (rc) return rc;
         if (h->greedy) {
             SD_LAUNCH(h, "unmask_greedy(k_chunk_argmax+k_greedy_reveal)", 1.0 * batch * gamma / T * m.ld * 4, 0,
@@ -829,9 +847,9 @@ int prepare_target(sd_handle* h, int batch, const int32_t* prefix, const int32_t
 int enqueue_target(sd_handle* h) {
     const MapSet& rm = h->maps[1];
     h->prof.phase = "verify:";
-    const int rc = run_layers(h, h->target, rm, nullptr);
+    const int rc = run_layers(h, h->target, rm, nullptr, rm.rows);
     if (rc) return rc;
-    return run_head(h, h->target, nullptr, rm.rows, h->buf.logits_t);
+    return run_head(h, h->target, nullptr, rm.head_row0, rm.rows, h->buf.logits_t);
 }
 
 int enqueue_accept(sd_handle* h, int batch, int gamma, const float* q_dev) {
@@ -950,6 +968,13 @@ int32_t sd_create(const sd_model_config* target, const sd_model_config* drafter,
                 delete h;
                 return SD_ERR_HIP;
             }
+        }
+        m.fu_head = p; p += align_up(m.c.vocab, 64);
+        m.fv_head = p; p += align_up(m.c.vocab, 64);
+        if (launch_fold_norm(m.w_head, m.lnf_g, m.lnf_b, nullptr, m.fu_head, m.fv_head, m.c.vocab, d, static_cast<hipStream_t>(hip_stream)) != hipSuccess) {
+            g_create_error = "launch of the norm-folding kernel failed";
+            delete h;
+            return SD_ERR_HIP;
         }
     }
     if (hipStreamSynchronize(static_cast<hipStream_t>(hip_stream)) != hipSuccess) {
@@ -1156,9 +1181,9 @@ int32_t sd_drafter_logits(sd_handle* h, int32_t batch, const int32_t* tokens, co
     const Model& m = h->drafter;
     rc = ensure_timestep_table(h, T);
     if (rc) return rc;
-    rc = run_layers(h, m, h->maps[0], h->buf.temb + (int64_t)(step - 1) * m.c.d_model);
+    rc = run_layers(h, m, h->maps[0], h->buf.temb + (int64_t)(step - 1) * m.c.d_model, batch * gamma);
     if (rc) return rc;
-    rc = run_head(h, m, h->maps[0].blk, batch * gamma, h->buf.logits_d);
+    rc = run_head(h, m, h->maps[0].blk, h->maps[0].head_row0, batch * gamma, h->buf.logits_d);
     if (rc) return rc;
     { const int rc_ = sync_stream(h); if (rc_) return rc_; }
     *logits_dev_out = h->buf.logits_d;

@@ -74,7 +74,7 @@ struct SplitArgs {
 };
 
 template <int MT, int NT, int WM, int WN, int KS, int PD, int EPI, int NF, int WNT>
-__global__ __launch_bounds__(256) void k_linear_mfma(const void* __restrict__ Xv, const bf16_t* __restrict__ W,
+__global__ __launch_bounds__(256, (MT * NT == 1 ? 3 : 1)) void k_linear_mfma(const void* __restrict__ Xv, const bf16_t* __restrict__ W,
                                                      const float* __restrict__ bias, void* Y, int M,
                                                      int N, int K, int ldy, int tiles_m, int tiles_n, FoldIn nf,
                                                      FoldOut fo, SplitArgs sk) {
@@ -140,6 +140,40 @@ __global__ __launch_bounds__(256) void k_linear_mfma(const void* __restrict__ Xv
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
+    // K loop.  Two software pipelines: global -> registers runs PD chunks ahead (hides L2 / HBM
+    // latency), registers -> LDS -> operand fragments runs one chunk ahead of the MFMAs (hides the LDS
+    // round trip).
+    // The steady-state loop has no conditional loads (the compiler's wait counts would otherwise
+    // degrade to "wait for everything"); the last full group and the remainder are peeled.
+    static_assert(PD % 2 == 0, "fragment double buffering assumes an even pipeline depth");
+    const int n_chunks = K / 64;
+    // chunks [c0, c1) belong to this workgroup (all of them unless K is split over gridDim.y)
+    const int c0 = (int)((long)blockIdx.y * n_chunks / sk.gsplit), c1 = (int)((long)(blockIdx.y + 1) * n_chunks / sk.gsplit);
+    // The KS waves take contiguous shares [lo, hi) of them: measured on this part, four waves that each stream
+    // their own stretch of a row pull 25-40 % more bytes per second from HBM than four waves that interleave
+    // 128-byte pieces of the same stretch.
+    const int lo = c0 + (int)((long)(c1 - c0) * wk / KS), hi = c0 + (int)((long)(c1 - c0) * (wk + 1) / KS);
+    const int n_mine = hi - lo;
+    // WNT: weights that only one workgroup reads (a single row tile) are fetched with the non-temporal hint
+    // (+5-10 % streaming rate, and they do not push x out of L2); with several row tiles the later ones
+    // find the panel in L2 and the hint would throw that away.
+    constexpr int kAuxW = WNT ? 2 : 0;
+    // The first PD chunks of both operands are requested before anything else that needs a round trip (epilogue
+    // operands, the row sums of a folded normalisation): those waits would otherwise sit in front of the loop.
+    u32x4 g[PD][TILES][4];
+#define SD_GLOAD(P, LOCAL)                                                                               \
+    {                                                                                                    \
+        const uint32_t koff_ = (uint32_t)(lo + (LOCAL)) * 128u;                                          \
+        _Pragma("unroll") for (int t = 0; t < TILES; ++t) _Pragma("unroll") for (int i = 0; i < 4; ++i)  \
+            g[P][t][i] = t < MT ? __builtin_amdgcn_raw_buffer_load_b128(rx, goff[t][i], koff_, 0)        \
+                                : __builtin_amdgcn_raw_buffer_load_b128(rw, goff[t][i], koff_, kAuxW);   \
+    }
+    if (n_mine > 0) {
+#pragma unroll
+        for (int p = 0; p < PD; ++p) SD_GLOAD(p, min(p, n_mine - 1))
+    }
+    __builtin_amdgcn_sched_barrier(0);
+
     // What the epilogue will need from memory (bias, and the residual stream for the accumulate
     // epilogue) is requested now, so that these round trips overlap the K loop instead of following it.
     constexpr bool kResid = EPI == EPI_RESID || EPI == EPI_RESID_NORM;
@@ -177,8 +211,8 @@ __global__ __launch_bounds__(256) void k_linear_mfma(const void* __restrict__ Xv
 
     // Row sums of the folded normalisation.  The producer left `parts` partial pairs (sum h, sum h^2) per row;
     // they are added in a fixed order: the KS waves and the two lane halves each take every (2 KS)-th pair
-    // (four loads in flight at a time), the halves are combined by one lane exchange and the waves through
-    // LDS below.  Requested here so that the round trips overlap the start of the K loop.
+    // (eight loads in flight at a time), the halves are combined by one lane exchange and the waves through
+    // LDS below.  The first operand chunks are already on their way, so these round trips overlap theirs.
     float w1[NF > 0 ? MT : 1] = {}, w2[NF > 0 ? MT : 1] = {};     // this wave's share, rows 32 t + r (both halves hold it)
     if constexpr (NF > 0) {
         typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2;
@@ -188,16 +222,19 @@ __global__ __launch_bounds__(256) void k_linear_mfma(const void* __restrict__ Xv
             const int row = m_base + 32 * t + r;
             float b1[4] = {0.f, 0.f, 0.f, 0.f}, b2[4] = {0.f, 0.f, 0.f, 0.f};
             if (row < M) {
+                // eight pairs per round trip; loads past the end re-read the last pair and are not added
                 const f32x2* sp = reinterpret_cast<const f32x2*>(nf.stats) + (size_t)row * nf.parts;
-                int p = 2 * wk + half;
-                for (; p + 3 * kStride < nf.parts; p += 4 * kStride) {
-                    f32x2 v[4];
+                for (int p = 2 * wk + half; p < nf.parts; p += 8 * kStride) {
+                    f32x2 v[8];
 #pragma unroll
-                    for (int u = 0; u < 4; ++u) v[u] = sp[p + u * kStride];
+                    for (int u = 0; u < 8; ++u) v[u] = sp[min(p + u * kStride, nf.parts - 1)];
 #pragma unroll
-                    for (int u = 0; u < 4; ++u) { b1[u] += v[u][0]; b2[u] += v[u][1]; }
+                    for (int u = 0; u < 8; ++u) {
+                        const bool have = p + u * kStride < nf.parts;
+                        b1[u & 3] += have ? v[u][0] : 0.f;
+                        b2[u & 3] += have ? v[u][1] : 0.f;
+                    }
                 }
-                for (; p < nf.parts; p += kStride) { const f32x2 v = sp[p]; b1[0] += v[0]; b2[0] += v[1]; }
             }
             w1[t] = (b1[0] + b1[1]) + (b1[2] + b1[3]);
             w2[t] = (b2[0] + b2[1]) + (b2[2] + b2[3]);
@@ -206,34 +243,8 @@ __global__ __launch_bounds__(256) void k_linear_mfma(const void* __restrict__ Xv
         }
     }
 
-    // K loop.  Two software pipelines: global -> registers runs PD chunks ahead (hides L2 / HBM
-    // latency), registers -> LDS -> operand fragments runs one chunk ahead of the MFMAs (hides the LDS
-    // round trip).
-    // The steady-state loop has no conditional loads (the compiler's wait counts would otherwise
-    // degrade to "wait for everything"); the last full group and the remainder are peeled.
-    static_assert(PD % 2 == 0, "fragment double buffering assumes an even pipeline depth");
-    const int n_chunks = K / 64;
-    // chunks [c0, c1) belong to this workgroup (all of them unless K is split over gridDim.y)
-    const int c0 = (int)((long)blockIdx.y * n_chunks / sk.gsplit), c1 = (int)((long)(blockIdx.y + 1) * n_chunks / sk.gsplit);
-    // The KS waves take contiguous shares [lo, hi) of them: measured on this part, four waves that each stream
-    // their own stretch of a row pull 25-40 % more bytes per second from HBM than four waves that interleave
-    // 128-byte pieces of the same stretch.
-    const int lo = c0 + (int)((long)(c1 - c0) * wk / KS), hi = c0 + (int)((long)(c1 - c0) * (wk + 1) / KS);
-    const int n_mine = hi - lo;
-    // WNT: weights that only one workgroup reads (a single row tile) are fetched with the non-temporal hint
-    // (+5-10 % streaming rate, and they do not push x out of L2); with several row tiles the later ones
-    // find the panel in L2 and the hint would throw that away.
-    constexpr int kAuxW = WNT ? 2 : 0;
     if (n_mine > 0) {
-        u32x4 g[PD][TILES][4];
         bf16x8 f[2][TILES][4];
-#define SD_GLOAD(P, LOCAL)                                                                               \
-    {                                                                                                    \
-        const uint32_t koff_ = (uint32_t)(lo + (LOCAL)) * 128u;                                          \
-        _Pragma("unroll") for (int t = 0; t < TILES; ++t) _Pragma("unroll") for (int i = 0; i < 4; ++i)  \
-            g[P][t][i] = t < MT ? __builtin_amdgcn_raw_buffer_load_b128(rx, goff[t][i], koff_, 0)        \
-                                : __builtin_amdgcn_raw_buffer_load_b128(rw, goff[t][i], koff_, kAuxW);   \
-    }
 // LDS operations of one wave execute in order: the fragment reads see the writes before them, and
 // the writes of the next chunk cannot overtake the reads of this one.
 #define SD_STAGE_TO_FRAG(P, FB)                                                                          \
@@ -250,8 +261,6 @@ __global__ __launch_bounds__(256) void k_linear_mfma(const void* __restrict__ Xv
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[FB][i][s4], f[FB][MT + j][s4], acc[i][j], 0, 0, 0); \
     }
         const int full = n_mine / PD, rem = n_mine % PD;
-#pragma unroll
-        for (int p = 0; p < PD; ++p) SD_GLOAD(p, min(p, n_mine - 1))
         SD_STAGE_TO_FRAG(0, 0)
         for (int it = 0; it + 1 < full; ++it) {
 #pragma unroll

@@ -198,15 +198,18 @@ __global__ __launch_bounds__(256) void k_linear_stream(const bf16_t* __restrict_
         float b1[4] = {0.f, 0.f, 0.f, 0.f}, b2[4] = {0.f, 0.f, 0.f, 0.f};
         if (row < M) {
             const f32x2* sp = reinterpret_cast<const f32x2*>(nf.stats) + (size_t)row * nf.parts;
-            int p = threadIdx.x & 3;
-            for (; p + 12 < nf.parts; p += 16) {
-                f32x2 v[4];
+            // eight pairs per round trip; loads past the end re-read the last pair and are not added
+            for (int p = threadIdx.x & 3; p < nf.parts; p += 32) {
+                f32x2 v[8];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) v[u] = sp[p + 4 * u];
+                for (int u = 0; u < 8; ++u) v[u] = sp[min(p + 4 * u, nf.parts - 1)];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) { b1[u] += v[u][0]; b2[u] += v[u][1]; }
+                for (int u = 0; u < 8; ++u) {
+                    const bool have = p + 4 * u < nf.parts;
+                    b1[u & 3] += have ? v[u][0] : 0.f;
+                    b2[u & 3] += have ? v[u][1] : 0.f;
+                }
             }
-            for (; p < nf.parts; p += 4) { const f32x2 v = sp[p]; b1[0] += v[0]; b2[0] += v[1]; }
         }
         float s1 = (b1[0] + b1[1]) + (b1[2] + b1[3]), s2 = (b2[0] + b2[1]) + (b2[2] + b2[3]);
         s1 += __shfl_xor(s1, 1, 64); s2 += __shfl_xor(s2, 1, 64);

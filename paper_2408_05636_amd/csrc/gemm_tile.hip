@@ -122,36 +122,6 @@ __global__ __launch_bounds__(256) void k_linear_tile(const void* __restrict__ Xv
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    // Row sums of a folded normalisation: thread t adds the partial pairs p = (t & 3), (t & 3) + 4, ... of row
-    // t >> 2 (BM = 64) -- or of rows t >> 2 and 64 + (t >> 2) (BM = 128) --, four loads in flight; the four
-    // threads of a row are combined by two lane exchanges.  Requested before the K loop so that the round
-    // trips overlap its start; consumed in the epilogue.
-    float fs1[NF > 0 ? WM : 1] = {}, fs2[NF > 0 ? WM : 1] = {};
-    if constexpr (NF > 0) {
-        typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2;
-#pragma unroll
-        for (int t = 0; t < WM; ++t) {
-            const int row = m_base + 64 * t + (threadIdx.x >> 2);
-            float b1[4] = {0.f, 0.f, 0.f, 0.f}, b2[4] = {0.f, 0.f, 0.f, 0.f};
-            if (row < M) {
-                const f32x2* sp = reinterpret_cast<const f32x2*>(nf.stats) + (size_t)row * nf.parts;
-                int p = threadIdx.x & 3;
-                for (; p + 12 < nf.parts; p += 16) {
-                    f32x2 v[4];
-#pragma unroll
-                    for (int u = 0; u < 4; ++u) v[u] = sp[p + 4 * u];
-#pragma unroll
-                    for (int u = 0; u < 4; ++u) { b1[u] += v[u][0]; b2[u] += v[u][1]; }
-                }
-                for (; p < nf.parts; p += 4) { const f32x2 v = sp[p]; b1[0] += v[0]; b2[0] += v[1]; }
-            }
-            fs1[t] = (b1[0] + b1[1]) + (b1[2] + b1[3]);
-            fs2[t] = (b2[0] + b2[1]) + (b2[2] + b2[3]);
-            fs1[t] += __shfl_xor(fs1[t], 1, 64); fs2[t] += __shfl_xor(fs2[t], 1, 64);
-            fs1[t] += __shfl_xor(fs1[t], 2, 64); fs2[t] += __shfl_xor(fs2[t], 2, 64);
-        }
-    }
-
     // two register sets: the global loads run two chunks ahead of the LDS stores
     u32x4 gx[2][XI], gw[2][4];
     const int n_chunks = K / 64;
@@ -209,6 +179,40 @@ __global__ __launch_bounds__(256) void k_linear_tile(const void* __restrict__ Xv
     const int last = n_chunks - 1;
     SD_TILE_GLOAD(0, 0)
     SD_TILE_GLOAD(1, min(1, last))
+    __builtin_amdgcn_sched_barrier(0);
+    // Row sums of a folded normalisation: thread t adds the partial pairs p = (t & 3), (t & 3) + 4, ... of row
+    // t >> 2 (BM = 64) -- or of rows t >> 2 and 64 + (t >> 2) (BM = 128) --, eight loads in flight; the four
+    // threads of a row are combined by two lane exchanges.  Requested behind the first two operand chunks, so that
+    // its round trips overlap theirs; consumed in the epilogue.
+    float fs1[NF > 0 ? WM : 1] = {}, fs2[NF > 0 ? WM : 1] = {};
+    if constexpr (NF > 0) {
+        typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2;
+#pragma unroll
+        for (int t = 0; t < WM; ++t) {
+            const int row = m_base + 64 * t + (threadIdx.x >> 2);
+            float b1[4] = {0.f, 0.f, 0.f, 0.f}, b2[4] = {0.f, 0.f, 0.f, 0.f};
+            if (row < M) {
+                const f32x2* sp = reinterpret_cast<const f32x2*>(nf.stats) + (size_t)row * nf.parts;
+                // eight pairs per round trip; loads past the end re-read the last pair and are not added
+                for (int p = threadIdx.x & 3; p < nf.parts; p += 32) {
+                    f32x2 v[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) v[u] = sp[min(p + 4 * u, nf.parts - 1)];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        const bool have = p + 4 * u < nf.parts;
+                        b1[u & 3] += have ? v[u][0] : 0.f;
+                        b2[u & 3] += have ? v[u][1] : 0.f;
+                    }
+                }
+            }
+            fs1[t] = (b1[0] + b1[1]) + (b1[2] + b1[3]);
+            fs2[t] = (b2[0] + b2[1]) + (b2[2] + b2[3]);
+            fs1[t] += __shfl_xor(fs1[t], 1, 64); fs2[t] += __shfl_xor(fs2[t], 1, 64);
+            fs1[t] += __shfl_xor(fs1[t], 2, 64); fs2[t] += __shfl_xor(fs2[t], 2, 64);
+        }
+    }
+
     SD_TILE_SWRITE(0, 0)
     SD_TILE_GLOAD(0, min(2, last))
     __syncthreads();
