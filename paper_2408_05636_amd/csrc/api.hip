@@ -676,7 +676,8 @@ int run_layers(sd_handle* h, const Model& m, const MapSet& rm, const float* temb
             SD_LAUNCH(h, "k_norm", rd * (4 + ew), 0, launch_norm(dt, B.h, nullptr, l.ln1_g, l.ln1_b, B.xn, rows, d, c.norm_eps, h->st));
             if ((rc = run_linear(h, dt, B.xn, l.w_qkv, l.b_qkv, B.qkv, rows, qkv_w, d, qkv_w, EPI_STORE))) return rc;
         }
-        if (c.arch == SD_ARCH_LLAMA)
+        const bool rope_into_cache = c.arch == SD_ARCH_LLAMA && cached;     // one kernel for both
+        if (c.arch == SD_ARCH_LLAMA && !rope_into_cache)
             SD_LAUNCH(h, "k_rope", 2.0 * rows * (m.dq + m.dkv) * ew, 0, launch_rope(dt, B.qkv, rm.pos, rows, c.n_head, c.n_kv_head, m.dh, c.rope_theta, h->st));
         AttnArgs a;
         a.q = B.qkv; a.q_ld = qkv_w;
@@ -690,7 +691,11 @@ int run_layers(sd_handle* h, const Model& m, const MapSet& rm, const float* temb
             const int64_t per_layer = (int64_t)h->max_batch * c.n_ctx * m.dkv * m.ew;
             char* kc = static_cast<char*>(B.kcache) + i * per_layer;
             char* vc = static_cast<char*>(B.vcache) + i * per_layer;
-            SD_LAUNCH(h, "k_kv_store", 4.0 * rows * m.dkv * ew, 0, launch_kv_store(dt, B.qkv, rm.seq, rm.pos, kc, vc, rows, c.n_head, c.n_kv_head, m.dh, c.n_ctx, h->st));
+            if (rope_into_cache)
+                SD_LAUNCH(h, "k_rope_kv_store", (2.0 * (m.dq + m.dkv) + 4.0 * m.dkv) * rows * ew, 0,
+                          launch_rope_kv_store(dt, B.qkv, rm.seq, rm.pos, kc, vc, rows, c.n_head, c.n_kv_head, m.dh, c.rope_theta, c.n_ctx, h->st));
+            else
+                SD_LAUNCH(h, "k_kv_store", 4.0 * rows * m.dkv * ew, 0, launch_kv_store(dt, B.qkv, rm.seq, rm.pos, kc, vc, rows, c.n_head, c.n_kv_head, m.dh, c.n_ctx, h->st));
             a.k = kc; a.v = vc; a.kv_ld = m.dkv;
         } else {
             a.k = static_cast<char*>(B.qkv) + (int64_t)m.dq * m.ew;

@@ -68,6 +68,10 @@ hipError_t launch_norm(int dtype, const float* h, const int32_t* idx, const floa
 hipError_t launch_rope(int dtype, void* qkv, const int32_t* pos, int rows, int n_head, int n_kv_head, int d_head,
                        float theta, hipStream_t st);
 
+// Both of the above in one pass (rotary embedding, then the cache append of the rotated k and of v).
+hipError_t launch_rope_kv_store(int dtype, void* qkv, const int32_t* seq, const int32_t* pos, void* kcache, void* vcache,
+                                int rows, int n_head, int n_kv_head, int d_head, float theta, int n_ctx, hipStream_t st);
+
 // Copy the k and v parts of qkv rows into the cache at (seq[r], pos[r]).
 hipError_t launch_kv_store(int dtype, const void* qkv, const int32_t* seq, const int32_t* pos, void* kcache,
                            void* vcache, int rows, int n_head, int n_kv_head, int d_head, int n_ctx, hipStream_t st);

@@ -217,6 +217,45 @@ __global__ __launch_bounds__(256) void k_rope(T* __restrict__ qkv, const int32_t
     x[i + half] = from_f<T>(b * c + a * s);
 }
 
+// Rotary embedding and KV-cache append in one pass over the qkv rows (the causal Llama-shaped target): q is rotated
+// in place, k is rotated on its way into the cache (and in place), v is copied.  Thread -> one (i, i + d_head/2)
+// pair of one head of one row; the arithmetic is that of k_rope.
+template <typename T>
+__global__ __launch_bounds__(256) void k_rope_kv_store(T* __restrict__ qkv, const int32_t* __restrict__ seq,
+                                                       const int32_t* __restrict__ pos, T* __restrict__ kc, T* __restrict__ vc,
+                                                       int rows, int n_head, int n_kv_head, int d_head, float theta, int n_ctx) {
+    const int half = d_head / 2;
+    const int heads = n_head + 2 * n_kv_head;      // q heads, k heads, v heads of a qkv row
+    const long total = (long)rows * heads * half;
+    const long t = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= total) return;
+    const int i = (int)(t % half);
+    const int hd = (int)((t / half) % heads);
+    const int r = (int)(t / ((long)half * heads));
+    const int dkv = n_kv_head * d_head;
+    T* x = qkv + (size_t)r * ((size_t)heads * d_head) + (size_t)hd * d_head;
+    const int p = pos[r];
+    const size_t o = ((size_t)seq[r] * n_ctx + p) * dkv;
+    if (hd >= n_head + n_kv_head) {                // v: copy
+        T* dst = vc + o + (size_t)(hd - n_head - n_kv_head) * d_head;
+        dst[i] = x[i];
+        dst[i + half] = x[i + half];
+        return;
+    }
+    const double inv = exp(-log((double)theta) * 2.0 * (double)i / (double)d_head);
+    const double ang = (double)p * inv;
+    const float c = (float)cos(ang), s = (float)sin(ang);
+    const float a = to_f(x[i]), b = to_f(x[i + half]);
+    const T lo = from_f<T>(a * c - b * s), hi = from_f<T>(b * c + a * s);
+    x[i] = lo;
+    x[i + half] = hi;
+    if (hd >= n_head) {                            // k: also into the cache
+        T* dst = kc + o + (size_t)(hd - n_head) * d_head;
+        dst[i] = lo;
+        dst[i + half] = hi;
+    }
+}
+
 // ---------------------------------------------------------------- KV-cache append
 // cache layout [max_batch, n_ctx, n_kv_head * d_head]; one workgroup per row.
 template <typename T>
@@ -294,6 +333,15 @@ hipError_t launch_rope(int dtype, void* qkv, const int32_t* pos, int rows, int n
     if (total <= 0) return hipSuccess;
     const int grid = (int)((total + 255) / 256);
     SD_DISPATCH(dtype, (k_rope<T><<<grid, 256, 0, st>>>((T*)qkv, pos, rows, n_head, n_kv_head, d_head, theta)));
+    return hipGetLastError();
+}
+
+hipError_t launch_rope_kv_store(int dtype, void* qkv, const int32_t* seq, const int32_t* pos, void* kcache, void* vcache,
+                                int rows, int n_head, int n_kv_head, int d_head, float theta, int n_ctx, hipStream_t st) {
+    const long total = (long)rows * (n_head + 2 * n_kv_head) * (d_head / 2);
+    if (total <= 0) return hipSuccess;
+    const int grid = (int)((total + 255) / 256);
+    SD_DISPATCH(dtype, (k_rope_kv_store<T><<<grid, 256, 0, st>>>((T*)qkv, seq, pos, (T*)kcache, (T*)vcache, rows, n_head, n_kv_head, d_head, theta, n_ctx)));
     return hipGetLastError();
 }
 
