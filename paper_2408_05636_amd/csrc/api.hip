@@ -255,6 +255,8 @@ struct MapSet {
     int n_groups = 0, group_tiles = 0;
     int rows = 0, n_tiles = 0, max_kv = 0;
     int head_row0 = -1;                  // first of the rows the LM head reads when they are one contiguous run, else -1
+    int regular = 0;                     // one sequence whose rows all see all keys (AttnArgs::regular)
+    bool grouped = false;                // the attention launch order groups sequences per XCD (else it is the plain order)
     double kv_sum = 0, kv_rows = 0;     // sum of kv_len over rows; distinct key rows
     int64_t bytes = -1;
 };
@@ -444,10 +446,12 @@ int upload_rows(sd_handle* h, int mode, int batch, const int32_t* tokens, const 
     const int n_kv_groups = m.c.n_kv_head, q_per_kv = m.c.n_head / m.c.n_kv_head;
     std::vector<std::vector<int32_t>> per_xcd(8), grp_xcd(8);
     int group_tiles = 0;
+    bool grouped_order = false;
     {
         double kv_bytes = 0;
         for (int b = 0; b < batch; ++b) kv_bytes += 2.0 * m.ew * m.dkv * (mode == 0 ? len[b] + gamma : (mode == 1 ? len[b] + gamma : len[b] - 1));
         const bool grouped = kv_bytes > 2.0e6;
+        grouped_order = grouped;
         int64_t t0 = 0, lin = 0;
         for (int b = 0; b < batch; ++b) {
             const int64_t rb = mode == 0 ? len[b] + gamma : (mode == 1 ? gamma + 1 : len[b] - 1);
@@ -558,6 +562,8 @@ int upload_rows(sd_handle* h, int mode, int batch, const int32_t* tokens, const 
     ms.groups = (int32_t*)(db + o_groups); ms.n_groups = (int)n_groups; ms.group_tiles = group_tiles;
     ms.rows = (int)rows; ms.n_tiles = (int)n_tiles; ms.max_kv = max_kv; ms.kv_sum = kv_sum; ms.kv_rows = kv_rows;
     ms.head_row0 = mode == 1 ? 0 : (mode == 0 && batch == 1 ? len[0] : -1);   // target: all rows; drafter: the block of a single sequence
+    ms.regular = mode == 0 && batch == 1;
+    ms.grouped = grouped_order;
     ms.bytes = bytes;
     return SD_OK;
 }
@@ -685,7 +691,8 @@ int run_layers(sd_handle* h, const Model& m, const MapSet& rm, const float* temb
         a.out = B.att; a.out_ld = d;
         a.rows = rows; a.n_head = c.n_head; a.n_kv_head = c.n_kv_head; a.d_head = m.dh; a.max_kv = rm.max_kv;
         a.tiles = rm.tiles; a.n_tiles = rm.n_tiles;
-        a.order = rm.order; a.n_order = rm.n_order;
+        a.regular = !cached && rm.regular;
+        if (rm.grouped) { a.order = rm.order; a.n_order = rm.n_order; }      // the plain order needs no table (and no load of it)
         a.groups = rm.groups; a.n_groups = rm.n_groups; a.group_tiles = rm.group_tiles;
         if (cached) {
             const int64_t per_layer = (int64_t)h->max_batch * c.n_ctx * m.dkv * m.ew;

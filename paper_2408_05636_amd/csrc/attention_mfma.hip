@@ -87,8 +87,14 @@ __global__ __launch_bounds__(256, (DH == 64 ? 2 : 1)) void k_attention_mfma(Attn
     if (!KSPLIT && tile >= a.n_tiles) return;           // whole wave; this variant has no barriers
 
     // One scalar load brings everything that is uniform over the tile; the per-row key counts, the query
-    // rows and the first key / value block are then requested together (two dependent round trips in all).
-    const AttnTile tl = a.tiles[tile];
+    // rows and the first key / value block are then requested together (two dependent round trips in all;
+    // one for a regular single sequence, whose tile needs no description).
+    AttnTile tl;
+    if (a.regular) {
+        tl.row0 = 32 * tile; tl.nrows = min(32, a.rows - 32 * tile); tl.kv_max = a.max_kv; tl.kv_off = 0;
+    } else {
+        tl = a.tiles[tile];
+    }
     const int row0 = tl.row0, nrows = tl.nrows, kv_max = tl.kv_max;
     const int qrow = row0 + min(r, nrows - 1);
     const int g = head / (a.n_head / a.n_kv_head);
@@ -97,11 +103,13 @@ __global__ __launch_bounds__(256, (DH == 64 ? 2 : 1)) void k_attention_mfma(Attn
     bf16_t* vbase = const_cast<bf16_t*>(static_cast<const bf16_t*>(a.v)) + tl.kv_off + (size_t)g * DH;
     const __amdgpu_buffer_rsrc_t rk = __builtin_amdgcn_make_buffer_rsrc(kbase, 0, kv_bytes, kBufFlags);
     const __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc(vbase, 0, kv_bytes, kBufFlags);
-    const int kvl = a.kv_len[qrow];
+    const int kvl = a.regular ? a.max_kv : a.kv_len[qrow];
     int kv_min = kvl;                                    // smallest key count among the tile's rows (wave-uniform)
+    if (!a.regular) {
 #pragma unroll
-    for (int o_ = 32; o_ > 0; o_ >>= 1) kv_min = min(kv_min, __shfl_xor(kv_min, o_, 64));
-    kv_min = __builtin_amdgcn_readfirstlane(kv_min);
+        for (int o_ = 32; o_ > 0; o_ >>= 1) kv_min = min(kv_min, __shfl_xor(kv_min, o_, 64));
+        kv_min = __builtin_amdgcn_readfirstlane(kv_min);
+    }
     const bf16_t* Qp = static_cast<const bf16_t*>(a.q) + (size_t)qrow * a.q_ld + (size_t)head * DH + 32 * half;
 
     bf16x8 qf[NCH][4];
