@@ -137,7 +137,7 @@ hipError_t launch_norm_prep(const float* h, const float* gain, void* xg, float* 
 
 // Up to 64 rows against a long weight stream: x parked in LDS, weights streamed (gemm_stream.hip).  Returns
 // hipErrorNotSupported when the shape does not fit (the caller then uses another kernel).
-bool linear_stream_preferred(int m, int n, int k);
+bool linear_stream_preferred(int m, int n, int k, bool folded);
 hipError_t launch_linear_stream(const void* x, const void* w, const float* bias, void* y, int m, int n, int k, int ldy,
                                 int epilogue, const NormIn& ni, const NormOut& no, const SplitWorkspace& ws,
                                 int force_split, hipStream_t st, const char** kernel_name);

@@ -573,7 +573,7 @@ hipError_t launch_linear_mfma(const void* x, const void* w, const float* bias, v
     if (no.gain && epi != EPI_RESID) return hipErrorInvalidValue;
     if (ni.kind < 0 || ni.kind > 2 || (ni.kind && (epi == EPI_RESID || !ni.stats || ni.parts <= 0))) return hipErrorInvalidValue;
     const int kepi = no.gain ? (int)EPI_RESID_NORM : epi;
-    if (g_variant_override == 9 || (g_variant_override < 0 && linear_stream_preferred(m, n, k))) {
+    if (g_variant_override == 9 || (g_variant_override < 0 && linear_stream_preferred(m, n, k, ni.kind != 0))) {
         const hipError_t e = launch_linear_stream(x, w, bias, y, m, n, k, ldy, epi, ni, no, ws, g_split_override, st, kernel_name);
         if (e != hipErrorNotSupported) return e;          // does not fit (K range vs. LDS, workspace): the kernels below
     }
