@@ -38,7 +38,7 @@ constexpr uint32_t kOutOfRange = 0x80000000u;
 __device__ inline float gelu_fast(float x) {
     // tanh form: 0.5 x (1 + tanh(u)) = x / (1 + exp(-2u))
     const float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
-    return x / (1.f + __expf(-2.f * u));
+    return x * __builtin_amdgcn_rcpf(1.f + __expf(-2.f * u));    // 1 ulp reciprocal: the result is rounded to bf16 anyway
 }
 
 // Normalisation folded around the contraction (no normalised copy of the residual stream h, no separate

@@ -35,7 +35,7 @@ __device__ inline void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_b
 
 __device__ inline float gelu_tile(float x) {
     const float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
-    return x / (1.f + __expf(-2.f * u));
+    return x * __builtin_amdgcn_rcpf(1.f + __expf(-2.f * u));    // 1 ulp reciprocal: the result is rounded to bf16 anyway
 }
 
 // 16-byte piece c of tile row r is stored at piece c ^ key(r).  A fragment read touches 16-byte pieces of
