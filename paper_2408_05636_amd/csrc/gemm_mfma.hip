@@ -373,15 +373,26 @@ __global__ __launch_bounds__(256, (MT * NT == 1 ? 3 : 1)) void k_linear_mfma(con
                 for (int j = 0; j < NT; ++j)
 #pragma unroll
                     for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-            for (int g = 0; g < sk.gsplit; ++g) {
-                float* rec = rec0 + (size_t)g * kRec;
+            // in split order, four splits per round trip to device-scope memory
+            for (int g0 = 0; g0 < sk.gsplit; g0 += 4) {
+                float v[4][MT * NT * 16];
 #pragma unroll
-                for (int i = 0; i < MT; ++i)
+                for (int b = 0; b < 4; ++b) {
+                    const float* rec = rec0 + (size_t)min(g0 + b, sk.gsplit - 1) * kRec;
 #pragma unroll
-                    for (int j = 0; j < NT; ++j)
+                    for (int q = 0; q < MT * NT * 16; ++q)
+                        v[b][q] = __hip_atomic_load(&rec[q * 64 + lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
 #pragma unroll
-                        for (int e = 0; e < 16; ++e)
-                            acc[i][j][e] += __hip_atomic_load(&rec[((i * NT + j) * 16 + e) * 64 + lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                for (int b = 0; b < 4; ++b) {
+                    const bool have = g0 + b < sk.gsplit;          // uniform
+#pragma unroll
+                    for (int i = 0; i < MT; ++i)
+#pragma unroll
+                        for (int j = 0; j < NT; ++j)
+#pragma unroll
+                            for (int e = 0; e < 16; ++e) acc[i][j][e] += have ? v[b][(i * NT + j) * 16 + e] : 0.f;
+                }
             }
         }
     }
