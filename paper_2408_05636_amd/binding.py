@@ -185,10 +185,11 @@ class SpecDiff:
         if rc:
             raise SdError(rc, "sd_create", lib().sd_last_error(None).decode())
         self.h = h
+        self._destroy = lib().sd_destroy          # module globals may be gone when __del__ runs at interpreter exit
 
     def close(self):
         if getattr(self, "h", None):
-            lib().sd_destroy(self.h)
+            self._destroy(self.h)
             self.h = None
 
     def __del__(self):
