@@ -148,6 +148,14 @@ hipError_t launch_linear_tile(const void* x, const void* w, const float* bias, v
                               int epilogue, const NormIn& ni, const NormOut& no, int rows, hipStream_t st,
                               const char** kernel_name);
 
+// Many-row contraction whose operand tiles go from global memory straight into a ring of LDS stages
+// (gemm_pipe.hip).  shape: 0 = 64 x 64, 1 = 64 x 128, 2 = 128 x 128, 3 = 256 x 128 workgroup tiles.
+// hipErrorNotSupported: K shorter than the ring (the caller then uses another kernel).
+int linear_pipe_shape(int m, int n, int k);     // shape this kernel wants for a contraction, -1: none
+hipError_t launch_linear_pipe(const void* x, const void* w, const float* bias, void* y, int m, int n, int k, int ldy,
+                              int epilogue, const NormIn& ni, const NormOut& no, int shape, hipStream_t st,
+                              const char** kernel_name);
+
 // act[r, c] = silu(gu[r, c]) * gu[r, F + c]
 hipError_t launch_swiglu(int dtype, const void* gu, void* act, int rows, int F, hipStream_t st);
 

@@ -588,9 +588,15 @@ hipError_t launch_linear_mfma(const void* x, const void* w, const float* bias, v
         const hipError_t e = launch_linear_stream(x, w, bias, y, m, n, k, ldy, epi, ni, no, ws, g_split_override, st, kernel_name);
         if (e != hipErrorNotSupported) return e;          // does not fit (K range vs. LDS, workspace): the kernels below
     }
+    const int pipe = g_variant_override >= 10 && g_variant_override <= 13 ? g_variant_override - 10
+                     : (g_variant_override < 0 ? linear_pipe_shape(m, n, k) : -1);
+    if (pipe >= 0) {
+        const hipError_t e = launch_linear_pipe(x, w, bias, y, m, n, k, ldy, epi, ni, no, pipe, st, kernel_name);
+        if (e != hipErrorNotSupported) return e;          // K shorter than the ring: the kernels below
+    }
     if (g_variant_override == 7 || g_variant_override == 8 || (g_variant_override < 0 && linear_tile_preferred(m, n, k)))
         return launch_linear_tile(x, w, bias, y, m, n, k, ldy, epi, ni, no, g_variant_override == 8 ? 64 : (g_variant_override == 7 ? 128 : 0), st, kernel_name);
-    int v = (g_variant_override >= 0 && g_variant_override != 9) ? g_variant_override : choose_variant(m, n, k);
+    int v = (g_variant_override >= 0 && g_variant_override < 9) ? g_variant_override : choose_variant(m, n, k);
     if (ni.kind && v == 3) v = 5;               // the 128 x 128 wave-private tile is not instantiated with a fold
     switch (v) {
         SD_VARIANT(0, 1, 1, 1, 1, 4, 2)     // 32 x 32 tile, four waves split K
