@@ -177,6 +177,19 @@ __global__ __launch_bounds__(256) void k_linear_tile(const void* __restrict__ Xv
         lds_barrier();                                  \
     }
     const int last = n_chunks - 1;
+    // Per-column operands of the epilogue, requested ahead of the operand tiles: their round trip is over long
+    // before the loop ends.
+    const __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(bias), 0, bias ? (uint32_t)N * 4u : 0u, kTileFlags);
+    const __amdgpu_buffer_rsrc_t ru = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(nf.u), 0, (NF == 1) ? (uint32_t)N * 4u : 0u, kTileFlags);
+    const __amdgpu_buffer_rsrc_t rgn = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(fo.gain), 0, (EPI == EPI_RESID_NORM) ? (uint32_t)N * 4u : 0u, kTileFlags);
+    float bvs[NT], uvs[NT], gvns[NT];
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {
+        const uint32_t n = (uint32_t)(n_base + wn * 32 * NT + 32 * j + r);
+        bvs[j] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rb, n * 4u, 0, 0));
+        uvs[j] = NF == 1 ? __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(ru, n * 4u, 0, 0)) : 0.f;
+        gvns[j] = EPI == EPI_RESID_NORM ? __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rgn, n * 4u, 0, 0)) : 0.f;
+    }
     SD_TILE_GLOAD(0, 0)
     SD_TILE_GLOAD(1, min(1, last))
     __builtin_amdgcn_sched_barrier(0);
@@ -256,9 +269,6 @@ __global__ __launch_bounds__(256) void k_linear_tile(const void* __restrict__ Xv
     constexpr bool kResid = EPI == EPI_RESID || EPI == EPI_RESID_NORM;
     constexpr uint32_t kOutBytes = (EPI == EPI_STORE || EPI == EPI_GELU) ? 2u : 4u;
     const __amdgpu_buffer_rsrc_t ry = __builtin_amdgcn_make_buffer_rsrc(Y, 0, (uint32_t)M * (uint32_t)ldy * kOutBytes, kTileFlags);
-    const __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(bias), 0, bias ? (uint32_t)N * 4u : 0u, kTileFlags);
-    const __amdgpu_buffer_rsrc_t ru = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(nf.u), 0, (NF == 1) ? (uint32_t)N * 4u : 0u, kTileFlags);
-    const __amdgpu_buffer_rsrc_t rgn = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(fo.gain), 0, (EPI == EPI_RESID_NORM) ? (uint32_t)N * 4u : 0u, kTileFlags);
     const __amdgpu_buffer_rsrc_t rxg = __builtin_amdgcn_make_buffer_rsrc(fo.xg, 0, (EPI == EPI_RESID_NORM) ? (uint32_t)M * (uint32_t)N * 2u : 0u, kTileFlags);
     const int wm_base = m_base + wm * 64;
     const int parts_out = (N + 31) / 32;
@@ -268,9 +278,7 @@ __global__ __launch_bounds__(256) void k_linear_tile(const void* __restrict__ Xv
         const uint32_t n = (uint32_t)(col0 + r);
         const uint32_t yoff = n < (uint32_t)N ? ((uint32_t)(wm_base + 4 * half) * (uint32_t)ldy + n) * kOutBytes : kTileOutOfRange;
         const uint32_t xgoff = n < (uint32_t)N ? ((uint32_t)(wm_base + 4 * half) * (uint32_t)N + n) * 2u : kTileOutOfRange;
-        const float bv = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rb, n * 4u, 0, 0));
-        const float uv = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(ru, n * 4u, 0, 0));
-        const float gvn = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rgn, n * 4u, 0, 0));
+        const float bv = bvs[j], uv = uvs[j], gvn = gvns[j];
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
 #pragma unroll
