@@ -334,10 +334,10 @@ __global__ __launch_bounds__(256) void k_linear_pipe(const void* __restrict__ Xv
 }
 
 // Tile shapes: id -> (waves WMV x WNV, wave part TM x TN of 32 x 32 tiles, stages)
-//   0:  64 x  64, 6 stages (96 KB)     1:  64 x 128, 4 stages (96 KB)
+//   0:  64 x  64, 4 stages (64 KB)     1:  64 x 128, 4 stages (96 KB)
 //   2: 128 x 128, 4 stages (128 KB)    3: 256 x 128, 3 stages (144 KB)
 struct PipeShape { int bm, bn, ns; };
-static const PipeShape kPipeShapes[4] = {{64, 64, 6}, {64, 128, 4}, {128, 128, 4}, {256, 128, 3}};
+static const PipeShape kPipeShapes[4] = {{64, 64, 4}, {64, 128, 4}, {128, 128, 4}, {256, 128, 3}};
 
 static std::string g_pipe_names[4][5][3];
 static const char* pipe_name(int shape, int epi, int nfk) {
@@ -424,7 +424,7 @@ hipError_t launch_linear_pipe(const void* x, const void* w, const float* bias, v
     if (kernel_name) *kernel_name = pipe_name(shape, no.gain ? (int)EPI_RESID_NORM : epi, ni.kind);
     const bf16_t* wb = static_cast<const bf16_t*>(w);
     switch (shape) {
-        case 0: return launch_pipe<2, 2, 1, 1, 6>(x, wb, bias, y, m, n, k, ldy, epi, ni, no, st);
+        case 0: return launch_pipe<2, 2, 1, 1, 4>(x, wb, bias, y, m, n, k, ldy, epi, ni, no, st);
         case 1: return launch_pipe<1, 4, 2, 1, 4>(x, wb, bias, y, m, n, k, ldy, epi, ni, no, st);
         case 2: return launch_pipe<2, 2, 2, 2, 4>(x, wb, bias, y, m, n, k, ldy, epi, ni, no, st);
         default: return launch_pipe<2, 2, 4, 2, 3>(x, wb, bias, y, m, n, k, ldy, epi, ni, no, st);
