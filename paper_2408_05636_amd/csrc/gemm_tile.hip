@@ -70,8 +70,15 @@ __global__ __launch_bounds__(256) void k_linear_tile(const void* __restrict__ Xv
     const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
     int tn, tm;
     if (x_stationary) {
-        tm = xcd + 8 * (local / tiles_n);
-        tn = local % tiles_n;
+        // x_stationary = number of column groups cg (1, 2 or 4): the XCDs form a cg x (8 / cg) grid, XCD (c, r) takes
+        // the column tiles of group c and the row tiles r, r + 8 / cg, ...  With cg > 1 an XCD keeps 1 / cg of W in its
+        // L2 while a (8 / cg)-th of x streams through once.
+        const int cgn = x_stationary, rgn = 8 / cgn;
+        const int cg = xcd % cgn, rg = xcd / cgn;
+        const int per = (tiles_n + cgn - 1) / cgn;
+        tn = cg * per + local % per;
+        tm = rg + rgn * (local / per);
+        if (tn >= (cg + 1) * per) return;
     } else {
         tn = xcd + 8 * (local / tiles_m);
         tm = local % tiles_m;
@@ -351,12 +358,15 @@ int linear_tile_rows(int m, int n, int k) {
 }
 bool linear_tile_preferred(int m, int n, int k) { return linear_tile_rows(m, n, k) != 0; }
 
+// Column groups of the XCD grid when x is the larger operand (see the kernel): with two, an XCD keeps half of W in
+// its L2 and a quarter of x streams through once (7424-row drafter passes: 1 % faster than one group; four: slower).
+constexpr int kTileColumnGroups = 2;
 template <int WM>
 static hipError_t launch_tile(const void* x, const bf16_t* wb, const float* bias, void* y, int m, int n, int k, int ldy,
                               int epi, const NormIn& ni, const NormOut& no, hipStream_t st) {
     const int tiles_m = (m + 64 * WM - 1) / (64 * WM), tiles_n = (n + 127) / 128;
-    const int xs = (int64_t)m > (int64_t)n;
-    const int grid = xs ? 8 * ((tiles_m + 7) / 8) * tiles_n : 8 * ((tiles_n + 7) / 8) * tiles_m;
+    const int xs = (int64_t)m > (int64_t)n ? kTileColumnGroups : 0;
+    const int grid = xs ? 8 * ((tiles_m + 8 / xs - 1) / (8 / xs)) * ((tiles_n + xs - 1) / xs) : 8 * ((tiles_n + 7) / 8) * tiles_m;
     const TileFoldIn fi{ni.stats, ni.u, ni.parts, ni.eps};
     const TileFoldOut fo{no.gain, static_cast<bf16_t*>(no.xg), no.stats};
 #define SD_GO(EPI, NF) k_linear_tile<EPI, WM, NF><<<grid, 256, 0, st>>>(x, wb, bias, y, m, n, k, ldy, tiles_m, tiles_n, xs, fi, fo)

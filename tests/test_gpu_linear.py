@@ -61,7 +61,8 @@ def test_linear_fp32_all_epilogues(m, n, k):
         run_case("f32", m, n, k, epi, seed=m + n + k + epi)
 
 
-@pytest.mark.parametrize("m,n,k", [(130, 4801, 1600), (700, 1000, 256), (1056, 2304, 768), (300, 130, 64), (1, 64, 64), (2100, 768, 3072)])
+@pytest.mark.parametrize("m,n,k", [(130, 4801, 1600), (700, 1000, 256), (1056, 2304, 768), (300, 130, 64), (1, 64, 64), (2100, 768, 3072),
+                                   (70, 200, 128), (70, 200, 192), (257, 129, 320), (64, 128, 384)])     # K around the ring lengths (2 to 6 chunks)
 @pytest.mark.parametrize("variant", [7, 8, 10, 11, 12, 13])
 def test_linear_shared_tile_kernel(m, n, k, variant):
     """The workgroup-shared tile kernels (7, 8: 128 / 64 rows, prefetch through registers; 10-13: 64 x 64 to 256 x 128
