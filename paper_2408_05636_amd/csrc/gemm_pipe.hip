@@ -336,16 +336,16 @@ __global__ __launch_bounds__(256) void k_linear_pipe(const void* __restrict__ Xv
 // Tile shapes: id -> (waves WMV x WNV, wave part TM x TN of 32 x 32 tiles, stages)
 //   0:  64 x  64, 4 stages (64 KB)     1:  64 x 128, 4 stages (96 KB)
 //   2: 128 x 128, 4 stages (128 KB)    3: 256 x 128, 3 stages (144 KB)
-struct PipeShape { int bm, bn, ns; };
-static const PipeShape kPipeShapes[4] = {{64, 64, 4}, {64, 128, 4}, {128, 128, 4}, {256, 128, 3}};
+struct PipeShape { int wmv, wnv, tm, tn, ns, bm, bn; };
+static const PipeShape kPipeShapes[4] = {{2, 2, 1, 1, 4, 64, 64}, {1, 4, 2, 1, 4, 64, 128}, {2, 2, 2, 2, 4, 128, 128}, {2, 2, 4, 2, 3, 256, 128}};
 
 static std::string g_pipe_names[4][5][3];
-static const char* pipe_name(int shape, int epi, int nfk) {
+static const char* pipe_name(int shape, int epi, int nfk) {      // the template arguments, as a profiler prints them
     std::string& s = g_pipe_names[shape][epi][nfk];
     if (s.empty()) {
         const PipeShape& p = kPipeShapes[shape];
-        s = "k_linear_pipe<" + std::to_string(p.bm) + "x" + std::to_string(p.bn) + "," + std::to_string(p.ns) + "," +
-            std::to_string(epi) + "," + std::to_string(nfk) + ">";
+        s = "k_linear_pipe<" + std::to_string(epi) + "," + std::to_string(p.wmv) + "," + std::to_string(p.wnv) + "," +
+            std::to_string(p.tm) + "," + std::to_string(p.tn) + "," + std::to_string(p.ns) + "," + std::to_string(nfk) + ">";
     }
     return s.c_str();
 }
