@@ -149,8 +149,9 @@ hipError_t launch_linear_tile(const void* x, const void* w, const float* bias, v
                               const char** kernel_name);
 
 // Many-row contraction whose operand tiles go from global memory straight into a ring of LDS stages
-// (gemm_pipe.hip).  shape: 0 = 64 x 64, 1 = 64 x 128, 2 = 128 x 128, 3 = 256 x 128 workgroup tiles.
-// hipErrorNotSupported: K shorter than the ring (the caller then uses another kernel).
+// (gemm_pipe.hip).  shape: 0 = 64 x 64, 1 = 64 x 128, 2 = 128 x 128, 3 = 256 x 128 workgroup tiles, one 64-wide
+// chunk of K per stage; 4 = 64 x 64, 5 = 64 x 128 with two chunks per stage (K a multiple of 128).
+// hipErrorNotSupported: K shorter than the ring or not a multiple of the stage width (the caller then uses another kernel).
 int linear_pipe_shape(int m, int n, int k);     // shape this kernel wants for a contraction, -1: none
 hipError_t launch_linear_pipe(const void* x, const void* w, const float* bias, void* y, int m, int n, int k, int ldy,
                               int epilogue, const NormIn& ni, const NormOut& no, int shape, hipStream_t st,

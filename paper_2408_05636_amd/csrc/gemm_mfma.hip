@@ -588,7 +588,7 @@ hipError_t launch_linear_mfma(const void* x, const void* w, const float* bias, v
         const hipError_t e = launch_linear_stream(x, w, bias, y, m, n, k, ldy, epi, ni, no, ws, g_split_override, st, kernel_name);
         if (e != hipErrorNotSupported) return e;          // does not fit (K range vs. LDS, workspace): the kernels below
     }
-    const int pipe = g_variant_override >= 10 && g_variant_override <= 13 ? g_variant_override - 10
+    const int pipe = g_variant_override >= 10 && g_variant_override <= 15 ? g_variant_override - 10
                      : (g_variant_override < 0 ? linear_pipe_shape(m, n, k) : -1);
     if (pipe >= 0) {
         const hipError_t e = launch_linear_pipe(x, w, bias, y, m, n, k, ldy, epi, ni, no, pipe, st, kernel_name);

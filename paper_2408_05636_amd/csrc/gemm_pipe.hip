@@ -73,7 +73,7 @@ struct PipeFoldOut {
     float* stats;        // [M][ceil(N / 32)][2]
 };
 
-template <int EPI, int WMV, int WNV, int TM, int TN, int NS, int NF>
+template <int EPI, int WMV, int WNV, int TM, int TN, int NS, int KC, int NF>
 __global__ __launch_bounds__(256) void k_linear_pipe(const void* __restrict__ Xv, const bf16_t* __restrict__ W,
                                                      const float* __restrict__ bias, void* Y, int M, int N, int K,
                                                      int ldy, int tiles_m, int tiles_n, int x_stationary,
@@ -81,9 +81,10 @@ __global__ __launch_bounds__(256) void k_linear_pipe(const void* __restrict__ Xv
     static_assert(WMV * WNV == 4, "four waves");
     constexpr int BM = 32 * TM * WMV, BN = 32 * TN * WNV;
     static_assert(BM % 64 == 0, "the row-sum gather works on 64 rows at a time");
-    constexpr int LX = BM / 32, LW = BN / 32, L = LX + LW;      // loads per wave and stage
+    constexpr int LX = BM / 32, LW = BN / 32, L = (LX + LW) * KC;   // loads per wave and stage
     static_assert((NS - 2) * L <= 63, "too many loads in flight for the wait counter");
-    constexpr int kStageVecs = (BM + BN) * 8;                   // u32x4 units
+    constexpr int kChunkVecs = (BM + BN) * 8;                   // one chunk of both tiles, u32x4 units
+    constexpr int kStageVecs = kChunkVecs * KC;                 // a stage holds KC consecutive chunks
     constexpr uint32_t kStageBytes = kStageVecs * 16u;
     extern __shared__ u32x4 smem[];
 
@@ -122,9 +123,10 @@ __global__ __launch_bounds__(256) void k_linear_pipe(const void* __restrict__ Xv
         woff[i] = row < (uint32_t)N ? (row * (uint32_t)K + 8u * piece) * 2u : kPipeOutOfRange;
     }
     const uint32_t lds0 = (uint32_t)reinterpret_cast<uintptr_t>(smem) + (uint32_t)wave * 1024u;
-#define SD_PIPE_REQUEST(STAGE, CHUNK)                                                               \
-    {                                                                                               \
-        const uint32_t sb_ = lds0 + (uint32_t)(STAGE) * kStageBytes, so_ = (uint32_t)(CHUNK) * 128u; \
+#define SD_PIPE_REQUEST(STAGE, GROUP)                                                               \
+    _Pragma("unroll") for (int kc = 0; kc < KC; ++kc) {                                             \
+        const uint32_t sb_ = lds0 + (uint32_t)(STAGE) * kStageBytes + (uint32_t)(kc * kChunkVecs * 16); \
+        const uint32_t so_ = (uint32_t)((GROUP) * KC + kc) * 128u;                                  \
         _Pragma("unroll") for (int i = 0; i < LX; ++i) dma16(dx, xoff[i], so_, sb_ + (uint32_t)i * 4096u); \
         _Pragma("unroll") for (int i = 0; i < LW; ++i) dma16(dw, woff[i], so_, sb_ + (uint32_t)(BM * 128 + i * 4096)); \
     }
@@ -163,11 +165,11 @@ __global__ __launch_bounds__(256) void k_linear_pipe(const void* __restrict__ Xv
     {                                                                                               \
         const u32x4* sp_ = smem + (STAGE) * kStageVecs;                                             \
         SD_PIPE_FRAGS(sp_, 0, 0)                                                                    \
-        _Pragma("unroll") for (int s4 = 0; s4 < 4; ++s4) {                                          \
-            if (s4 < 3) SD_PIPE_FRAGS(sp_, (s4 + 1) & 1, s4 + 1)                                    \
+        _Pragma("unroll") for (int q = 0; q < 4 * KC; ++q) {        /* k steps of 16 over the KC chunks of the stage */ \
+            if (q + 1 < 4 * KC) SD_PIPE_FRAGS(sp_ + ((q + 1) >> 2) * kChunkVecs, (q + 1) & 1, (q + 1) & 3) \
             __builtin_amdgcn_sched_barrier(0);     /* keep the reads of the next step ahead of these MFMAs */ \
             _Pragma("unroll") for (int i = 0; i < TM; ++i) _Pragma("unroll") for (int j = 0; j < TN; ++j) \
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[s4 & 1][i], fb[s4 & 1][j], acc[i][j], 0, 0, 0); \
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[q & 1][i], fb[q & 1][j], acc[i][j], 0, 0, 0); \
             __builtin_amdgcn_sched_barrier(0);                                                      \
         }                                                                                           \
     }
@@ -216,7 +218,7 @@ __global__ __launch_bounds__(256) void k_linear_pipe(const void* __restrict__ Xv
         gvns[j] = EPI == EPI_RESID_NORM ? __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rgn, n * 4u, 0, 0)) : 0.f;
     }
 
-    const int n_chunks = K / 64;                 // >= NS - 1 (checked by the launcher)
+    const int n_chunks = K / (64 * KC);          // groups of KC chunks: >= NS - 1, K a multiple of 64 KC (checked by the launcher)
 #pragma unroll
     for (int s = 0; s < NS - 1; ++s) SD_PIPE_REQUEST(s, s)
 
@@ -333,51 +335,56 @@ __global__ __launch_bounds__(256) void k_linear_pipe(const void* __restrict__ Xv
     }
 }
 
-// Tile shapes: id -> (waves WMV x WNV, wave part TM x TN of 32 x 32 tiles, stages)
-//   0:  64 x  64, 4 stages (64 KB)     1:  64 x 128, 4 stages (96 KB)
-//   2: 128 x 128, 4 stages (128 KB)    3: 256 x 128, 3 stages (144 KB)
-struct PipeShape { int wmv, wnv, tm, tn, ns, bm, bn; };
-static const PipeShape kPipeShapes[4] = {{2, 2, 1, 1, 4, 64, 64}, {1, 4, 2, 1, 4, 64, 128}, {2, 2, 2, 2, 4, 128, 128}, {2, 2, 4, 2, 3, 256, 128}};
+// Tile shapes: id -> (waves WMV x WNV, wave part TM x TN of 32 x 32 tiles, stages, chunks per stage)
+//   0:  64 x  64, 4 stages of 1 chunk (64 KB)     1:  64 x 128, 4 x 1 (96 KB)
+//   2: 128 x 128, 4 x 1 (128 KB)                  3: 256 x 128, 3 x 1 (144 KB)
+//   4:  64 x  64, 3 stages of 2 chunks (96 KB)    5:  64 x 128, 3 x 2 (144 KB)   -- K a multiple of 128
+// Two chunks per stage halve what a step costs besides its MFMAs (the wait and barrier, the burst of load
+// requests, the first operand read that nothing hides): with 4 MFMAs per wave and chunk (64 x 64) that is most of it.
+constexpr int kPipeShapeCount = 6;
+struct PipeShape { int wmv, wnv, tm, tn, ns, kc, bm, bn; };
+static const PipeShape kPipeShapes[kPipeShapeCount] = {{2, 2, 1, 1, 4, 1, 64, 64}, {1, 4, 2, 1, 4, 1, 64, 128}, {2, 2, 2, 2, 4, 1, 128, 128},
+                                                       {2, 2, 4, 2, 3, 1, 256, 128}, {2, 2, 1, 1, 3, 2, 64, 64}, {1, 4, 2, 1, 3, 2, 64, 128}};
 
-static std::string g_pipe_names[4][5][3];
+static std::string g_pipe_names[kPipeShapeCount][5][3];
 static const char* pipe_name(int shape, int epi, int nfk) {      // the template arguments, as a profiler prints them
     std::string& s = g_pipe_names[shape][epi][nfk];
     if (s.empty()) {
         const PipeShape& p = kPipeShapes[shape];
         s = "k_linear_pipe<" + std::to_string(epi) + "," + std::to_string(p.wmv) + "," + std::to_string(p.wnv) + "," +
-            std::to_string(p.tm) + "," + std::to_string(p.tn) + "," + std::to_string(p.ns) + "," + std::to_string(nfk) + ">";
+            std::to_string(p.tm) + "," + std::to_string(p.tn) + "," + std::to_string(p.ns) + "," + std::to_string(p.kc) + "," + std::to_string(nfk) + ">";
     }
     return s.c_str();
 }
 
-template <int EPI, int WMV, int WNV, int TM, int TN, int NS, int NF>
+template <int EPI, int WMV, int WNV, int TM, int TN, int NS, int KC, int NF>
 static hipError_t launch_pipe_kernel(int grid, hipStream_t st, const void* x, const bf16_t* wb, const float* bias, void* y,
                                      int m, int n, int k, int ldy, int tiles_m, int tiles_n, int xs, const PipeFoldIn& fi,
                                      const PipeFoldOut& fo) {
-    constexpr int kLds = NS * (32 * TM * WMV + 32 * TN * WNV) * 128;
+    constexpr int kLds = NS * KC * (32 * TM * WMV + 32 * TN * WNV) * 128;
     static_assert(kLds >= (32 * TM * WMV * 2 + 4 * 32 * 33) * 4, "epilogue scratch fits in the stages");
     static bool raised = false;                   // more than the default 64 KB of LDS: allowed once per kernel
     if (!raised) {
-        const hipError_t e = hipFuncSetAttribute((const void*)k_linear_pipe<EPI, WMV, WNV, TM, TN, NS, NF>,
+        const hipError_t e = hipFuncSetAttribute((const void*)k_linear_pipe<EPI, WMV, WNV, TM, TN, NS, KC, NF>,
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
         if (e != hipSuccess) return e;
         raised = true;
     }
-    k_linear_pipe<EPI, WMV, WNV, TM, TN, NS, NF><<<grid, 256, kLds, st>>>(x, wb, bias, y, m, n, k, ldy, tiles_m, tiles_n, xs, fi, fo);
+    k_linear_pipe<EPI, WMV, WNV, TM, TN, NS, KC, NF><<<grid, 256, kLds, st>>>(x, wb, bias, y, m, n, k, ldy, tiles_m, tiles_n, xs, fi, fo);
     return hipGetLastError();
 }
 
-template <int WMV, int WNV, int TM, int TN, int NS>
+template <int WMV, int WNV, int TM, int TN, int NS, int KC>
 static hipError_t launch_pipe(const void* x, const bf16_t* wb, const float* bias, void* y, int m, int n, int k, int ldy,
                               int epi, const NormIn& ni, const NormOut& no, hipStream_t st) {
     constexpr int BM = 32 * TM * WMV, BN = 32 * TN * WNV;
-    if (k / 64 < NS - 1) return hipErrorNotSupported;
+    if (k % (64 * KC) != 0 || k / (64 * KC) < NS - 1) return hipErrorNotSupported;
     const int tiles_m = (m + BM - 1) / BM, tiles_n = (n + BN - 1) / BN;
     const int xs = (int64_t)m > (int64_t)n;
     const int grid = xs ? 8 * ((tiles_m + 7) / 8) * tiles_n : 8 * ((tiles_n + 7) / 8) * tiles_m;
     const PipeFoldIn fi{ni.stats, ni.u, ni.parts, ni.eps};
     const PipeFoldOut fo{no.gain, static_cast<bf16_t*>(no.xg), no.stats};
-#define SD_GO(EPI, NF) return launch_pipe_kernel<EPI, WMV, WNV, TM, TN, NS, NF>(grid, st, x, wb, bias, y, m, n, k, ldy, tiles_m, tiles_n, xs, fi, fo)
+#define SD_GO(EPI, NF) return launch_pipe_kernel<EPI, WMV, WNV, TM, TN, NS, KC, NF>(grid, st, x, wb, bias, y, m, n, k, ldy, tiles_m, tiles_n, xs, fi, fo)
     if (ni.kind == 0) {
         switch (epi) {
             case EPI_STORE: SD_GO(EPI_STORE, 0);
@@ -410,7 +417,8 @@ int linear_pipe_shape(int m, int n, int k) {
     if (m < 192 || m > 2048 || n < 2048 || k / 64 < 5) return -1;
     for (int s = 2; s >= 0; --s) {
         const PipeShape& p = kPipeShapes[s];
-        if ((long)((m + p.bm - 1) / p.bm) * ((n + p.bn - 1) / p.bn) >= 150) return s;
+        if ((long)((m + p.bm - 1) / p.bm) * ((n + p.bn - 1) / p.bn) >= 150)
+            return s < 2 && k % 128 == 0 ? s + 4 : s;       // the 64-row tiles: two chunks per stage when K allows
     }
     return -1;
 }
@@ -420,14 +428,16 @@ int linear_pipe_shape(int m, int n, int k) {
 hipError_t launch_linear_pipe(const void* x, const void* w, const float* bias, void* y, int m, int n, int k, int ldy,
                               int epi, const NormIn& ni, const NormOut& no, int shape, hipStream_t st,
                               const char** kernel_name) {
-    if (epi < 0 || epi > 3 || shape < 0 || shape > 3) return hipErrorInvalidValue;
+    if (epi < 0 || epi > 3 || shape < 0 || shape >= kPipeShapeCount) return hipErrorInvalidValue;
     if (kernel_name) *kernel_name = pipe_name(shape, no.gain ? (int)EPI_RESID_NORM : epi, ni.kind);
     const bf16_t* wb = static_cast<const bf16_t*>(w);
     switch (shape) {
-        case 0: return launch_pipe<2, 2, 1, 1, 4>(x, wb, bias, y, m, n, k, ldy, epi, ni, no, st);
-        case 1: return launch_pipe<1, 4, 2, 1, 4>(x, wb, bias, y, m, n, k, ldy, epi, ni, no, st);
-        case 2: return launch_pipe<2, 2, 2, 2, 4>(x, wb, bias, y, m, n, k, ldy, epi, ni, no, st);
-        default: return launch_pipe<2, 2, 4, 2, 3>(x, wb, bias, y, m, n, k, ldy, epi, ni, no, st);
+        case 0: return launch_pipe<2, 2, 1, 1, 4, 1>(x, wb, bias, y, m, n, k, ldy, epi, ni, no, st);
+        case 1: return launch_pipe<1, 4, 2, 1, 4, 1>(x, wb, bias, y, m, n, k, ldy, epi, ni, no, st);
+        case 2: return launch_pipe<2, 2, 2, 2, 4, 1>(x, wb, bias, y, m, n, k, ldy, epi, ni, no, st);
+        case 3: return launch_pipe<2, 2, 4, 2, 3, 1>(x, wb, bias, y, m, n, k, ldy, epi, ni, no, st);
+        case 4: return launch_pipe<2, 2, 1, 1, 3, 2>(x, wb, bias, y, m, n, k, ldy, epi, ni, no, st);
+        default: return launch_pipe<1, 4, 2, 1, 3, 2>(x, wb, bias, y, m, n, k, ldy, epi, ni, no, st);
     }
 }
 

@@ -63,11 +63,11 @@ def test_linear_fp32_all_epilogues(m, n, k):
 
 @pytest.mark.parametrize("m,n,k", [(130, 4801, 1600), (700, 1000, 256), (1056, 2304, 768), (300, 130, 64), (1, 64, 64), (2100, 768, 3072),
                                    (70, 200, 128), (70, 200, 192), (257, 129, 320), (64, 128, 384)])     # K around the ring lengths (2 to 6 chunks)
-@pytest.mark.parametrize("variant", [7, 8, 10, 11, 12, 13])
+@pytest.mark.parametrize("variant", [7, 8, 10, 11, 12, 13, 14, 15])
 def test_linear_shared_tile_kernel(m, n, k, variant):
     """The workgroup-shared tile kernels (7, 8: 128 / 64 rows, prefetch through registers; 10-13: 64 x 64 to 256 x 128
-    tiles fed straight into a ring of LDS stages; a K shorter than the ring falls back to the default choice), forced
-    on ragged shapes."""
+    tiles fed straight into a ring of LDS stages, 14, 15: the 64-row ones with two chunks of K per stage; a K shorter
+    than the ring or not a multiple of the stage width falls back to the default choice), forced on ragged shapes."""
     from paper_2408_05636_amd import binding
     binding.lib().sd_set_linear_variant(variant)
     try:
@@ -113,7 +113,7 @@ def test_linear_forced_split(split):
 @pytest.mark.parametrize("m,n,k", [(17, 2304, 768), (272, 2304, 768), (301, 3072, 768), (33, 100, 128), (65, 4801, 1600), (700, 1000, 256),
                                    (17, 4800, 1600), (33, 512, 4096), (60, 96, 2048), (2100, 2304, 768)])
 @pytest.mark.parametrize("norm_kind", [1, 2])
-@pytest.mark.parametrize("variant", [-1, 9, 10, 11, 12, 13])
+@pytest.mark.parametrize("variant", [-1, 9, 10, 11, 12, 13, 14, 15])
 def test_norm_folded_linear(m, n, k, norm_kind, variant):
     """LayerNorm / RMSNorm folded into the contraction vs. the oracle's norm followed by its linear
     (variant 9: the weight-streaming kernel, up to 64 rows)."""
@@ -153,7 +153,7 @@ def norm_folded_case(m, n, k, norm_kind):
         assert err <= 0.012 * scale + (0.006 * np.abs(ref).max() if epi != 3 else 0), (m, n, k, norm_kind, epi, err, scale)
 
 
-@pytest.mark.parametrize("variant", [-1, 5, 7, 8, 9, 10, 11, 12, 13])
+@pytest.mark.parametrize("variant", [-1, 5, 7, 8, 9, 10, 11, 12, 13, 14, 15])
 @pytest.mark.parametrize("m,n,k", [(17, 768, 768), (272, 768, 3072), (40, 100, 1024), (17, 1600, 6400), (300, 1601, 128), (1056, 768, 3072)])
 def test_residual_epilogue_prepares_the_next_normalisation(m, n, k, variant):
     """Producer side of a folded normalisation: h += x W^T + b, xg = bf16(h * gain), per-tile row sums of h and h^2
