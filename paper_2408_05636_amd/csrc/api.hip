@@ -256,6 +256,7 @@ struct MapSet {
     int rows = 0, n_tiles = 0, max_kv = 0;
     int head_row0 = -1;                  // first of the rows the LM head reads when they are one contiguous run, else -1
     int regular = 0;                     // one sequence whose rows all see all keys (AttnArgs::regular)
+    int64_t kv_row0 = -1;                // target query rows of a single sequence: the KV-cache row of row 0 (row r goes to kv_row0 + r), else -1
     bool grouped = false;                // the attention launch order groups sequences per XCD (else it is the plain order)
     double kv_sum = 0, kv_rows = 0;     // sum of kv_len over rows; distinct key rows
     int64_t bytes = -1;
@@ -563,6 +564,7 @@ int upload_rows(sd_handle* h, int mode, int batch, const int32_t* tokens, const 
     ms.rows = (int)rows; ms.n_tiles = (int)n_tiles; ms.max_kv = max_kv; ms.kv_sum = kv_sum; ms.kv_rows = kv_rows;
     ms.head_row0 = mode == 1 ? 0 : (mode == 0 && batch == 1 ? len[0] : -1);   // target: all rows; drafter: the block of a single sequence
     ms.regular = mode == 0 && batch == 1;
+    ms.kv_row0 = mode == 1 && batch == 1 ? len[0] - 1 : -1;
     ms.grouped = grouped_order;
     ms.bytes = bytes;
     return SD_OK;
@@ -676,8 +678,20 @@ int run_layers(sd_handle* h, const Model& m, const MapSet& rm, const float* temb
               launch_embed(dt, rm.src, rm.pos, rm.tokens, B.z, m.wte, m.wpe, temb, B.h, rows, d, fold ? m.L[0].ln1_g : nullptr, B.xn, B.stats, h->st));
     for (int i = 0; i < c.n_layer; ++i) {
         const Layer& l = m.L[i];
+        // The query rows of a single sequence sit at consecutive cache rows: the QKV contraction then writes its K and V
+        // columns straight into the cache (few-row kernel, plain store epilogue) and no copy kernel runs.
+        const int64_t per_layer = cached ? (int64_t)h->max_batch * c.n_ctx * m.dkv * m.ew : 0;
+        char* const kc = cached ? static_cast<char*>(B.kcache) + i * per_layer : nullptr;
+        char* const vc = cached ? static_cast<char*>(B.vcache) + i * per_layer : nullptr;
+        const bool kv_direct = fold && cached && c.arch == SD_ARCH_GPT2 && rm.kv_row0 >= 0 && rows <= 64 && m.dq % 32 == 0 && m.dkv % 32 == 0;
         if (fold) {
-            if ((rc = run_linear(h, dt, B.xn, l.w_qkv, ln ? l.fv_qkv : l.b_qkv, B.qkv, rows, qkv_w, d, qkv_w, EPI_STORE, fold_in(l.fu_qkv)))) return rc;
+            NormOut qkv_out;
+            if (kv_direct) {
+                qkv_out.y1 = kc + rm.kv_row0 * m.dkv * (int64_t)m.ew;
+                qkv_out.y2 = vc + rm.kv_row0 * m.dkv * (int64_t)m.ew;
+                qkv_out.c1 = m.dq; qkv_out.c2 = m.dq + m.dkv; qkv_out.ld12 = m.dkv;
+            }
+            if ((rc = run_linear(h, dt, B.xn, l.w_qkv, ln ? l.fv_qkv : l.b_qkv, B.qkv, rows, qkv_w, d, qkv_w, EPI_STORE, fold_in(l.fu_qkv), qkv_out))) return rc;
         } else {
             SD_LAUNCH(h, "k_norm", rd * (4 + ew), 0, launch_norm(dt, B.h, nullptr, l.ln1_g, l.ln1_b, B.xn, rows, d, c.norm_eps, h->st));
             if ((rc = run_linear(h, dt, B.xn, l.w_qkv, l.b_qkv, B.qkv, rows, qkv_w, d, qkv_w, EPI_STORE))) return rc;
@@ -695,10 +709,9 @@ int run_layers(sd_handle* h, const Model& m, const MapSet& rm, const float* temb
         if (rm.grouped) { a.order = rm.order; a.n_order = rm.n_order; }      // the plain order needs no table (and no load of it)
         a.groups = rm.groups; a.n_groups = rm.n_groups; a.group_tiles = rm.group_tiles;
         if (cached) {
-            const int64_t per_layer = (int64_t)h->max_batch * c.n_ctx * m.dkv * m.ew;
-            char* kc = static_cast<char*>(B.kcache) + i * per_layer;
-            char* vc = static_cast<char*>(B.vcache) + i * per_layer;
-            if (rope_into_cache)
+            if (kv_direct) {
+                // already in the cache
+            } else if (rope_into_cache)
                 SD_LAUNCH(h, "k_rope_kv_store", (2.0 * (m.dq + m.dkv) + 4.0 * m.dkv) * rows * ew, 0,
                           launch_rope_kv_store(dt, B.qkv, rm.seq, rm.pos, kc, vc, rows, c.n_head, c.n_kv_head, m.dh, c.rope_theta, c.n_ctx, h->st));
             else

@@ -38,6 +38,12 @@ struct NormOut {             // producer (residual epilogue): what to prepare fo
     const float* gain = nullptr;    // [n] gain of that normalisation; NULL: nothing to prepare
     void* xg = nullptr;             // bf16 [m][n] = bf16(y * gain)
     float* stats = nullptr;         // [m][ceil(n / 32)][2]
+    // Output columns from c1 on go elsewhere (plain bf16 store epilogue of the few-row matrix-core kernel only; c1, c2
+    // multiples of 32): columns [c1, c2) to y1[row * ld12 + col - c1], columns >= c2 to y2[row * ld12 + col - c2] -- the
+    // K and V parts of a QKV contraction written straight into the KV cache.  y1 == NULL: everything goes to y.
+    void* y1 = nullptr;
+    void* y2 = nullptr;
+    int c1 = 0, c2 = 0, ld12 = 0;
 };
 
 // ---- launchers (all asynchronous on `st`; return hipGetLastError()) ------------------------

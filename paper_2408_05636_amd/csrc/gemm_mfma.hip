@@ -71,6 +71,9 @@ struct SplitArgs {
     unsigned int* ticket;
     int gsplit;
     int x_stationary;   // workgroup -> tile mapping, see the kernel
+    void* y1;           // NormOut::y1, y2, c1, c2, ld12: where the output columns from c1 on go (NULL: to Y)
+    void* y2;
+    int c1, c2, ld12;
 };
 
 template <int MT, int NT, int WM, int WN, int KS, int PD, int EPI, int NF, int WNT>
@@ -179,7 +182,19 @@ __global__ __launch_bounds__(256, (MT * NT == 1 ? 3 : 1)) void k_linear_mfma(con
     constexpr bool kResid = EPI == EPI_RESID || EPI == EPI_RESID_NORM;
     constexpr bool kPrefetchResid = MT * NT <= 2;
     constexpr uint32_t kOutBytes = (EPI == EPI_STORE || EPI == EPI_GELU) ? 2u : 4u;
-    const __amdgpu_buffer_rsrc_t ry = __builtin_amdgcn_make_buffer_rsrc(Y, 0, (uint32_t)M * (uint32_t)ldy * kOutBytes, kBufFlags);
+    // Where this wave's columns go: normally Y; with a column split (plain store, one column tile per wave; the split
+    // points are multiples of 32, so a tile lies on one side) the tiles from c1 / c2 on go to y1 / y2.
+    void* Yo = Y;
+    int ldo = ldy, ncol0 = 0;
+    if constexpr (EPI == EPI_STORE && NT == 1) {
+        if (sk.y1 != nullptr && n_base >= sk.c1) {
+            const bool second = n_base >= sk.c2;
+            Yo = second ? sk.y2 : sk.y1;
+            ldo = sk.ld12;
+            ncol0 = second ? sk.c2 : sk.c1;
+        }
+    }
+    const __amdgpu_buffer_rsrc_t ry = __builtin_amdgcn_make_buffer_rsrc(Yo, 0, (uint32_t)M * (uint32_t)ldo * kOutBytes, kBufFlags);
     const __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(bias), 0, bias ? (uint32_t)N * 4u : 0u, kBufFlags);
     // Output element (row m_base + 32 i + 8 (e/4) + 4 half + e%4, column n_base + 32 j + r): the lane part of
     // the byte offset; the (i, e) part is wave-uniform and goes into the scalar offset of each access.
@@ -192,7 +207,7 @@ __global__ __launch_bounds__(256, (MT * NT == 1 ? 3 : 1)) void k_linear_mfma(con
 #pragma unroll
         for (int j = 0; j < NT; ++j) {
             const uint32_t n = (uint32_t)(n_base + 32 * j + r);
-            yoff[j] = n < (uint32_t)N ? ((uint32_t)(m_base + 4 * half) * (uint32_t)ldy + n) * kOutBytes : kOutOfRange;
+            yoff[j] = n < (uint32_t)N ? ((uint32_t)(m_base + 4 * half) * (uint32_t)ldo + (n - (uint32_t)ncol0)) * kOutBytes : kOutOfRange;
             bv[j] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rb, n * 4u, 0, 0));
             uv[j] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(ru, n * 4u, 0, 0));
             gv[j] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rgn, n * 4u, 0, 0));
@@ -205,7 +220,7 @@ __global__ __launch_bounds__(256, (MT * NT == 1 ? 3 : 1)) void k_linear_mfma(con
 #pragma unroll
                     for (int e = 0; e < 16; ++e)
                         yres[i][j][e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
-                            ry, yoff[j] + (uint32_t)(32 * i + 8 * (e >> 2) + (e & 3)) * (uint32_t)ldy * 4u, 0, 0));
+                            ry, yoff[j] + (uint32_t)(32 * i + 8 * (e >> 2) + (e & 3)) * (uint32_t)ldo * 4u, 0, 0));
         }
     }
 
@@ -432,7 +447,7 @@ __global__ __launch_bounds__(256, (MT * NT == 1 ? 3 : 1)) void k_linear_mfma(con
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 const int lr = 32 * i + 8 * (e >> 2) + (e & 3);           // row within the wave's tiles, minus 4 * half
-                const uint32_t so = (uint32_t)lr * (uint32_t)ldy * kOutBytes;
+                const uint32_t so = (uint32_t)lr * (uint32_t)ldo * kOutBytes;
                 float v = acc[i][j][e];
                 if constexpr (NF > 0) v = fmaf(na[i][e], v, nb[i][e] * uv[j]);
                 v += bv[j];
@@ -483,7 +498,8 @@ static hipError_t launch_variant(const void* x, const void* w, const float* bias
     const int tiles_n = (n + 32 * NT * WN - 1) / (32 * NT * WN), tiles_m = (m + 32 * MT * WM - 1) / (32 * MT * WM);
     // K split over workgroups: only for the one-tile-set-per-workgroup shapes, when the tiles alone cannot
     // fill the chip, keeping at least two chunks per wave, within the workspace.
-    SplitArgs sk{nullptr, nullptr, 1, 0};
+    SplitArgs sk{nullptr, nullptr, 1, 0, no.y1, no.y2, no.c1, no.c2, no.ld12};
+    if (no.y1 && (NT != 1 || epi != EPI_STORE)) return hipErrorInvalidValue;
     sk.x_stationary = m > n;
     if constexpr (WM * WN == 1) {
         const long tiles = (long)tiles_n * tiles_m;
@@ -584,6 +600,14 @@ hipError_t launch_linear_mfma(const void* x, const void* w, const float* bias, v
     if (no.gain && epi != EPI_RESID) return hipErrorInvalidValue;
     if (ni.kind < 0 || ni.kind > 2 || (ni.kind && (epi == EPI_RESID || !ni.stats || ni.parts <= 0))) return hipErrorInvalidValue;
     const int kepi = no.gain ? (int)EPI_RESID_NORM : epi;
+    if (no.y1) {       // a column split exists in the few-row kernel only
+        if (epi != EPI_STORE || m > 64 || !no.y2 || no.c1 % 32 || no.c2 % 32 || no.c1 > no.c2 || no.c2 > n || no.ld12 <= 0) return hipErrorInvalidValue;
+        switch (choose_variant(m, n, k)) {
+            SD_VARIANT(0, 1, 1, 1, 1, 4, 2)
+            SD_VARIANT(6, 2, 1, 1, 1, 4, 2)
+            default: return hipErrorInvalidValue;
+        }
+    }
     if (g_variant_override == 9 || (g_variant_override < 0 && linear_stream_preferred(m, n, k, ni.kind != 0))) {
         const hipError_t e = launch_linear_stream(x, w, bias, y, m, n, k, ldy, epi, ni, no, ws, g_split_override, st, kernel_name);
         if (e != hipErrorNotSupported) return e;          // does not fit (K range vs. LDS, workspace): the kernels below
