@@ -210,8 +210,10 @@ int32_t sd_linear_resid_norm(const void *x, const void *w, const float *bias, fl
 
 /* Tuning hook for sd_linear and every contraction inside the forwards: force tile variant
  * `variant` of the matrix-core kernel (0, 3, 5, 6: few-row / mid-size tiles; 7, 8: workgroup-shared 128 x 128, 64 x 128 tiles;
- * 9: the weight-streaming kernel for up to 64 rows wherever the shape fits it, the choice by shape elsewhere; see the kernel
- * sources; other values are rejected at the next contraction), -1 = choose by shape (default).
+ * 9: the weight-streaming kernel for up to 64 rows wherever the shape fits it, the choice by shape elsewhere;
+ * 10-13: 64 x 64, 64 x 128, 128 x 128, 256 x 128 tiles fed straight from global memory into a ring of LDS stages, 14, 15: the
+ * first two with two 64-wide chunks of K per stage -- the choice by shape when K is shorter than the ring or no multiple of
+ * the stage width; see the kernel sources; other values are rejected at the next contraction), -1 = choose by shape (default).
  * Process-wide; results do not depend on the variant beyond fp32 summation order. */
 int32_t sd_set_linear_variant(int32_t variant);
 /* Same for the number of workgroups that share the K range of one output tile (clamped to what the
