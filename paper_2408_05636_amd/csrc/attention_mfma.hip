@@ -21,23 +21,11 @@
 // matching V^T operand is keys 16h + 8s .. 16h + 8s + 7.
 // A workgroup is 4 waves: either 4 query tiles (large batches) or 4 interleaved key ranges of one
 // tile merged through LDS (few query rows: the target's gamma+1 rows, batch-1 drafter).
-#include "common.h"
+#include "mfma_common.hip.h"
 
 namespace sd {
 
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
-typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
-
-
-typedef __attribute__((__vector_size__(4 * sizeof(unsigned int)))) unsigned int u32x4;
 typedef __attribute__((__vector_size__(2 * sizeof(unsigned int)))) unsigned int u32x2;
-constexpr int kBufFlags = 0x00020000;          // raw buffer, 32-bit data format
-constexpr uint32_t kOutOfRange = 0x80000000u;  // VGPR offset of accesses that must not happen (buffers are < 2 GiB)
-
-// Workgroup barrier that orders LDS traffic only (__syncthreads() also waits for every global load in flight,
-// i.e. for the key / value blocks requested ahead).
-__device__ inline void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
-
 typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4;
 // Offsets (in 2-byte units from the start of a V tile in LDS: [64-wide d chunk][32 keys][8 pieces of 16 bytes],
 // piece p of key row x at p ^ swz(x)) of the two transposing reads that give this lane the V^T operand of d tile t,

@@ -21,25 +21,9 @@
 #include <algorithm>
 #include <string>
 
-#include "common.h"
+#include "mfma_common.hip.h"
 
 namespace sd {
-
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
-typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
-typedef __attribute__((__vector_size__(4 * sizeof(unsigned int)))) unsigned int u32x4;   // one 16-byte piece
-typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
-constexpr int kBufFlags = 0x00020000;   // raw buffer, 32-bit data format (gfx9 family resource word 3)
-// Offset of accesses that must not happen.  Only the VGPR offset is range-checked (the scalar offset is
-// not), so everything that decides validity goes into the VGPR offset; buffers are < 2 GiB (checked on
-// the host), and 2 GiB plus any in-matrix offset cannot wrap around 2^32.
-constexpr uint32_t kOutOfRange = 0x80000000u;
-
-__device__ inline float gelu_fast(float x) {
-    // tanh form: 0.5 x (1 + tanh(u)) = x / (1 + exp(-2u))
-    const float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
-    return x * __builtin_amdgcn_rcpf(1.f + __expf(-2.f * u));    // 1 ulp reciprocal: the result is rounded to bf16 anyway
-}
 
 // Normalisation folded around the contraction (no normalised copy of the residual stream h, no separate
 // normalisation kernel).  For y = W norm(h) + bias:

@@ -20,23 +20,9 @@
 // The last NS - 1 steps request nothing and wait for one stage less each.
 #include <string>
 
-#include "common.h"
+#include "mfma_common.hip.h"
 
 namespace sd {
-
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
-typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
-typedef __attribute__((__vector_size__(4 * sizeof(unsigned int)))) unsigned int u32x4;
-constexpr int kPipeFlags = 0x00020000;            // raw buffer, 32-bit data format
-constexpr uint32_t kPipeOutOfRange = 0x80000000u;  // voffset of accesses that must not happen (buffers < 2 GiB)
-
-__device__ inline float gelu_pipe(float x) {
-    const float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
-    return x * __builtin_amdgcn_rcpf(1.f + __expf(-2.f * u));    // 1 ulp reciprocal: the result is rounded to bf16 anyway
-}
-
-// see gemm_tile.hip: any 16 consecutive rows get 16 distinct (row parity, key) pairs
-__device__ inline int pipe_key(int row) { return (row & 7) ^ ((row >> 3) & 1); }
 
 // 64 x 16 bytes from a raw buffer (descriptor in scalar registers) to LDS bytes lds_addr + 16 lane.  The LDS base
 // travels in M0; an LDS-bound load needs one wait state after M0 is written (the compiler would insert it for
@@ -57,7 +43,7 @@ __device__ inline u32x4 raw_descriptor(const void* p, uint32_t bytes) {
     d[0] = __builtin_amdgcn_readfirstlane((uint32_t)a);
     d[1] = __builtin_amdgcn_readfirstlane((uint32_t)(a >> 32) & 0xffffu);
     d[2] = __builtin_amdgcn_readfirstlane(bytes);
-    d[3] = (uint32_t)kPipeFlags;
+    d[3] = (uint32_t)kBufFlags;
     return d;
 }
 
@@ -115,12 +101,12 @@ __global__ __launch_bounds__(256) void k_linear_pipe(const void* __restrict__ Xv
 #pragma unroll
     for (int i = 0; i < LX; ++i) {
         const uint32_t row = (uint32_t)(m_base + 32 * i + 8 * wave + lrow);
-        xoff[i] = row < (uint32_t)M ? (row * (uint32_t)K + 8u * piece) * 2u : kPipeOutOfRange;
+        xoff[i] = row < (uint32_t)M ? (row * (uint32_t)K + 8u * piece) * 2u : kOutOfRange;
     }
 #pragma unroll
     for (int i = 0; i < LW; ++i) {
         const uint32_t row = (uint32_t)(n_base + 32 * i + 8 * wave + lrow);
-        woff[i] = row < (uint32_t)N ? (row * (uint32_t)K + 8u * piece) * 2u : kPipeOutOfRange;
+        woff[i] = row < (uint32_t)N ? (row * (uint32_t)K + 8u * piece) * 2u : kOutOfRange;
     }
     const uint32_t lds0 = (uint32_t)reinterpret_cast<uintptr_t>(smem) + (uint32_t)wave * 1024u;
 #define SD_PIPE_REQUEST(STAGE, GROUP)                                                               \
@@ -137,13 +123,13 @@ __global__ __launch_bounds__(256) void k_linear_pipe(const void* __restrict__ Xv
     for (int i = 0; i < TM; ++i) {
         const int row = wm * 32 * TM + 32 * i + r;
 #pragma unroll
-        for (int s4 = 0; s4 < 4; ++s4) offa[i][s4] = row * 8 + ((2 * s4 + half) ^ pipe_key(row));
+        for (int s4 = 0; s4 < 4; ++s4) offa[i][s4] = row * 8 + ((2 * s4 + half) ^ swizzle_key(row));
     }
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
         const int row = wn * 32 * TN + 32 * j + r;
 #pragma unroll
-        for (int s4 = 0; s4 < 4; ++s4) offb[j][s4] = BM * 8 + row * 8 + ((2 * s4 + half) ^ pipe_key(row));
+        for (int s4 = 0; s4 < 4; ++s4) offb[j][s4] = BM * 8 + row * 8 + ((2 * s4 + half) ^ swizzle_key(row));
     }
     bf16x8 fa[2][TM], fb[2][TN];
     floatx16 acc[TM][TN];
@@ -206,9 +192,9 @@ __global__ __launch_bounds__(256) void k_linear_pipe(const void* __restrict__ Xv
 
     // Per-column operands of the epilogue, requested ahead of everything else: their round trip is over long
     // before the loop ends (and, being older than every tile load, they never delay the waits of the loop).
-    const __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(bias), 0, bias ? (uint32_t)N * 4u : 0u, kPipeFlags);
-    const __amdgpu_buffer_rsrc_t ru = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(nf.u), 0, (NF == 1) ? (uint32_t)N * 4u : 0u, kPipeFlags);
-    const __amdgpu_buffer_rsrc_t rgn = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(fo.gain), 0, (EPI == EPI_RESID_NORM) ? (uint32_t)N * 4u : 0u, kPipeFlags);
+    const __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(bias), 0, bias ? (uint32_t)N * 4u : 0u, kBufFlags);
+    const __amdgpu_buffer_rsrc_t ru = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(nf.u), 0, (NF == 1) ? (uint32_t)N * 4u : 0u, kBufFlags);
+    const __amdgpu_buffer_rsrc_t rgn = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(fo.gain), 0, (EPI == EPI_RESID_NORM) ? (uint32_t)N * 4u : 0u, kBufFlags);
     float bvs[TN], uvs[TN], gvns[TN];
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
@@ -280,16 +266,16 @@ __global__ __launch_bounds__(256) void k_linear_pipe(const void* __restrict__ Xv
     // Accumulator e of a 32 x 32 tile is row 8 (e / 4) + 4 half + e % 4, column lane & 31.
     constexpr bool kResid = EPI == EPI_RESID || EPI == EPI_RESID_NORM;
     constexpr uint32_t kOutBytes = (EPI == EPI_STORE || EPI == EPI_GELU) ? 2u : 4u;
-    const __amdgpu_buffer_rsrc_t ry = __builtin_amdgcn_make_buffer_rsrc(Y, 0, (uint32_t)M * (uint32_t)ldy * kOutBytes, kPipeFlags);
-    const __amdgpu_buffer_rsrc_t rxg = __builtin_amdgcn_make_buffer_rsrc(fo.xg, 0, (EPI == EPI_RESID_NORM) ? (uint32_t)M * (uint32_t)N * 2u : 0u, kPipeFlags);
+    const __amdgpu_buffer_rsrc_t ry = __builtin_amdgcn_make_buffer_rsrc(Y, 0, (uint32_t)M * (uint32_t)ldy * kOutBytes, kBufFlags);
+    const __amdgpu_buffer_rsrc_t rxg = __builtin_amdgcn_make_buffer_rsrc(fo.xg, 0, (EPI == EPI_RESID_NORM) ? (uint32_t)M * (uint32_t)N * 2u : 0u, kBufFlags);
     const int wm_base = m_base + wm * 32 * TM;
     const int parts_out = (N + 31) / 32;
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
         const int col0 = n_base + wn * 32 * TN + 32 * j;
         const uint32_t n = (uint32_t)(col0 + r);
-        const uint32_t yoff = n < (uint32_t)N ? ((uint32_t)(wm_base + 4 * half) * (uint32_t)ldy + n) * kOutBytes : kPipeOutOfRange;
-        const uint32_t xgoff = n < (uint32_t)N ? ((uint32_t)(wm_base + 4 * half) * (uint32_t)N + n) * 2u : kPipeOutOfRange;
+        const uint32_t yoff = n < (uint32_t)N ? ((uint32_t)(wm_base + 4 * half) * (uint32_t)ldy + n) * kOutBytes : kOutOfRange;
+        const uint32_t xgoff = n < (uint32_t)N ? ((uint32_t)(wm_base + 4 * half) * (uint32_t)N + n) * 2u : kOutOfRange;
         const float bv = bvs[j], uv = uvs[j], gvn = gvns[j];
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
@@ -303,7 +289,7 @@ __global__ __launch_bounds__(256) void k_linear_pipe(const void* __restrict__ Xv
                     v = fmaf(ab[row * 2 + 0], v, ab[row * 2 + 1] * uv);
                 }
                 v += bv;
-                if constexpr (EPI == EPI_GELU) v = gelu_pipe(v);
+                if constexpr (EPI == EPI_GELU) v = gelu_fast(v);
                 if constexpr (kResid) v += __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(ry, yoff + so, 0, 0));
                 if constexpr (kOutBytes == 2)
                     __builtin_amdgcn_raw_buffer_store_b16(__builtin_bit_cast(unsigned short, static_cast<bf16_t>(v)), ry, yoff + so, 0, 0);

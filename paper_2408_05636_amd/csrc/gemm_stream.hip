@@ -25,28 +25,14 @@
 #include <algorithm>
 #include <string>
 
-#include "common.h"
+#include "mfma_common.hip.h"
 
 namespace sd {
 
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
-typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
-typedef __attribute__((__vector_size__(4 * sizeof(unsigned int)))) unsigned int u32x4;
-constexpr int kStreamFlags = 0x00020000;            // raw buffer, 32-bit data format
-constexpr uint32_t kStreamOutOfRange = 0x80000000u;  // voffset of accesses that must not happen (buffers < 2 GiB)
 constexpr int kStagePieces = 272;                    // per wave: 4 KB weight tile; reused as a 32 x 33 fp32 tile
 constexpr int kAbPieces = 32;                        // 64 rows x (rstd, -rstd mu)
 constexpr int kStreamPD = 4;                         // chunks in flight per wave (16 KB)
 constexpr int kStep = 4;                             // chunks per slab step
-
-// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every global load in flight,
-// which would drain the weight prefetch at each step; the slab hand-over needs the LDS writes alone.
-__device__ inline void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
-
-__device__ inline float gelu_stream(float x) {
-    const float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
-    return x * __builtin_amdgcn_rcpf(1.f + __expf(-2.f * u));    // 1 ulp reciprocal: the result is rounded to bf16 anyway
-}
 
 struct StreamFoldIn {
     const float* stats;  // [M][parts][2] partial (sum h, sum h^2)
@@ -88,8 +74,8 @@ __global__ __launch_bounds__(256) void k_linear_stream(const bf16_t* __restrict_
     const int c0 = blockIdx.y * sk.split_chunks, nck = min(sk.split_chunks, n_chunks - c0);   // >= 1 (host)
     const int steps = (nck + S - 1) / S;
 
-    const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(X), 0, (uint32_t)M * (uint32_t)K * 2u, kStreamFlags);
-    const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(W), 0, (uint32_t)N * (uint32_t)K * 2u, kStreamFlags);
+    const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(X), 0, (uint32_t)M * (uint32_t)K * 2u, kBufFlags);
+    const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(W), 0, (uint32_t)N * (uint32_t)K * 2u, kBufFlags);
     // Weight loads: instruction i covers rows 8 i .. 8 i + 7 of the tile, lane -> (row 8 i + lrow, 16-byte piece pc).
     // (A wave whose tile lies beyond N loads nothing, multiplies zeros and stores nothing, but keeps the barriers.)
     const int lrow = lane >> 3, pc = lane & 7;
@@ -97,7 +83,7 @@ __global__ __launch_bounds__(256) void k_linear_stream(const bf16_t* __restrict_
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const uint32_t row = (uint32_t)(n_base + 8 * i + lrow);
-        goff[i] = row < (uint32_t)N ? (row * (uint32_t)K + 8u * pc) * 2u : kStreamOutOfRange;
+        goff[i] = row < (uint32_t)N ? (row * (uint32_t)K + 8u * pc) * 2u : kOutOfRange;
     }
     // Piece c of tile row q sits at piece c ^ key(q), key(q) = (q & 7) ^ ((q >> 3) & 1): a fragment read covers 32
     // rows at one logical piece, rows are 128 bytes apart, and the key separates any 16 consecutive rows.
@@ -127,7 +113,7 @@ __global__ __launch_bounds__(256) void k_linear_stream(const bf16_t* __restrict_
         const int lc_ = pos_ < nck ? ch_ : nck;                                                     \
         const uint32_t koff_ = (uint32_t)(c0 + ch_) * 128u;                                         \
         _Pragma("unroll") for (int i = 0; i < 4; ++i)                                               \
-            g[P][i] = __builtin_amdgcn_raw_buffer_load_b128(rw, lc_ < nck ? goff[i] : kStreamOutOfRange, koff_, 2 /* non-temporal */); \
+            g[P][i] = __builtin_amdgcn_raw_buffer_load_b128(rw, lc_ < nck ? goff[i] : kOutOfRange, koff_, 2 /* non-temporal */); \
     }
     // The weights do not depend on the slab: their first PD chunks are requested before it is filled.
 #pragma unroll
@@ -136,13 +122,13 @@ __global__ __launch_bounds__(256) void k_linear_stream(const bf16_t* __restrict_
     // What the epilogue needs from memory (bias, the residual stream) is requested now as well.
     constexpr bool kResid = EPI == EPI_RESID || EPI == EPI_RESID_NORM;
     constexpr uint32_t kOutBytes = (EPI == EPI_STORE || EPI == EPI_GELU) ? 2u : 4u;
-    const __amdgpu_buffer_rsrc_t ry = __builtin_amdgcn_make_buffer_rsrc(Y, 0, (uint32_t)M * (uint32_t)ldy * kOutBytes, kStreamFlags);
-    const __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(bias), 0, bias ? (uint32_t)N * 4u : 0u, kStreamFlags);
-    const __amdgpu_buffer_rsrc_t ru = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(nf.u), 0, (NF == 1) ? (uint32_t)N * 4u : 0u, kStreamFlags);
-    const __amdgpu_buffer_rsrc_t rgn = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(fo.gain), 0, (EPI == EPI_RESID_NORM) ? (uint32_t)N * 4u : 0u, kStreamFlags);
+    const __amdgpu_buffer_rsrc_t ry = __builtin_amdgcn_make_buffer_rsrc(Y, 0, (uint32_t)M * (uint32_t)ldy * kOutBytes, kBufFlags);
+    const __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(bias), 0, bias ? (uint32_t)N * 4u : 0u, kBufFlags);
+    const __amdgpu_buffer_rsrc_t ru = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(nf.u), 0, (NF == 1) ? (uint32_t)N * 4u : 0u, kBufFlags);
+    const __amdgpu_buffer_rsrc_t rgn = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(fo.gain), 0, (EPI == EPI_RESID_NORM) ? (uint32_t)N * 4u : 0u, kBufFlags);
     // Output element (row 32 t + 8 (e/4) + 4 half + e%4, column n_base + r).
     const uint32_t ncol = (uint32_t)(n_base + r);
-    const uint32_t yoff = ncol < (uint32_t)N ? ((uint32_t)(4 * half) * (uint32_t)ldy + ncol) * kOutBytes : kStreamOutOfRange;
+    const uint32_t yoff = ncol < (uint32_t)N ? ((uint32_t)(4 * half) * (uint32_t)ldy + ncol) * kOutBytes : kOutOfRange;
     const float bv = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rb, ncol * 4u, 0, 0));
     const float uv = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(ru, ncol * 4u, 0, 0));
     const float gv = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rgn, ncol * 4u, 0, 0));
@@ -166,7 +152,7 @@ __global__ __launch_bounds__(256) void k_linear_stream(const bf16_t* __restrict_
 #pragma unroll
     for (int t = 0; t < MT; ++t) {
         const int row = 32 * t + srow;
-        xoff[t] = row < M ? ((uint32_t)row * (uint32_t)K + 8u * spc) * 2u : kStreamOutOfRange;     // rows >= M read as 0
+        xoff[t] = row < M ? ((uint32_t)row * (uint32_t)K + 8u * spc) * 2u : kOutOfRange;     // rows >= M read as 0
         sslot[t] = row < rows_s ? row * 8 + (spc ^ (row & 7) ^ ((row >> 3) & 1)) : rows_s * 8 + spc;
     }
     u32x4 xv[S][MT];
@@ -336,8 +322,8 @@ __global__ __launch_bounds__(256) void k_linear_stream(const bf16_t* __restrict_
 
     // Epilogue (one 32-column tile per wave).  Rows >= M fall behind the end of the buffers, columns >= N carry the
     // out-of-range offset; the hardware drops both.
-    const __amdgpu_buffer_rsrc_t rxg = __builtin_amdgcn_make_buffer_rsrc(fo.xg, 0, (EPI == EPI_RESID_NORM) ? (uint32_t)M * (uint32_t)N * 2u : 0u, kStreamFlags);
-    const uint32_t xgoff = ncol < (uint32_t)N ? ((uint32_t)(4 * half) * (uint32_t)N + ncol) * 2u : kStreamOutOfRange;
+    const __amdgpu_buffer_rsrc_t rxg = __builtin_amdgcn_make_buffer_rsrc(fo.xg, 0, (EPI == EPI_RESID_NORM) ? (uint32_t)M * (uint32_t)N * 2u : 0u, kBufFlags);
+    const uint32_t xgoff = ncol < (uint32_t)N ? ((uint32_t)(4 * half) * (uint32_t)N + ncol) * 2u : kOutOfRange;
     float* const rowsum = reinterpret_cast<float*>(stage);
     const int parts_out = (N + 31) / 32;
 #pragma unroll
@@ -349,7 +335,7 @@ __global__ __launch_bounds__(256) void k_linear_stream(const bf16_t* __restrict_
             float v = acc[t][e];
             if constexpr (NF > 0) v = fmaf(ab[(lr + 4 * half) * 2 + 0], v, ab[(lr + 4 * half) * 2 + 1] * uv);
             v += bv;
-            if constexpr (EPI == EPI_GELU) v = gelu_stream(v);
+            if constexpr (EPI == EPI_GELU) v = gelu_fast(v);
             if constexpr (kResid) v += yres[t][e];
             if constexpr (kOutBytes == 2)
                 __builtin_amdgcn_raw_buffer_store_b16(__builtin_bit_cast(unsigned short, static_cast<bf16_t>(v)), ry, yoff + so, 0, 0);

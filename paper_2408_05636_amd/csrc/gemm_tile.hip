@@ -17,31 +17,9 @@
 // normalisation that follows (EPI_RESID_NORM).
 #include <string>
 
-#include "common.h"
+#include "mfma_common.hip.h"
 
 namespace sd {
-
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
-typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
-typedef __attribute__((__vector_size__(4 * sizeof(unsigned int)))) unsigned int u32x4;
-typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
-constexpr int kTileFlags = 0x00020000;            // raw buffer, 32-bit data format
-constexpr uint32_t kTileOutOfRange = 0x80000000u;  // voffset of accesses that must not happen (buffers < 2 GiB)
-
-// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every global load in flight,
-// which would cut the two-chunk prefetch down to what one multiply phase can hide; the stage hand-over needs the
-// LDS writes and reads alone.
-__device__ inline void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
-
-__device__ inline float gelu_tile(float x) {
-    const float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
-    return x * __builtin_amdgcn_rcpf(1.f + __expf(-2.f * u));    // 1 ulp reciprocal: the result is rounded to bf16 anyway
-}
-
-// 16-byte piece c of tile row r is stored at piece c ^ key(r).  A fragment read touches 16-byte pieces of
-// 32 consecutive rows at one logical piece index; rows are 128 bytes apart, so rows of equal parity share
-// their banks and the key must separate them: any 16 consecutive rows get 16 distinct (parity, key) pairs.
-__device__ inline int swizzle_key(int row) { return (row & 7) ^ ((row >> 3) & 1); }
 
 struct TileFoldIn {
     const float* stats;  // [M][parts][2] partial (sum h, sum h^2)
@@ -89,8 +67,8 @@ __global__ __launch_bounds__(256) void k_linear_tile(const void* __restrict__ Xv
     __shared__ u32x4 lds_x[2][BM * 8];                // [stage][rows x 8 pieces]
     __shared__ u32x4 lds_w[2][1024];
 
-    const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(Xv), 0, (uint32_t)M * (uint32_t)K * 2u, kTileFlags);
-    const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(W), 0, (uint32_t)N * (uint32_t)K * 2u, kTileFlags);
+    const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(Xv), 0, (uint32_t)M * (uint32_t)K * 2u, kBufFlags);
+    const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(W), 0, (uint32_t)N * (uint32_t)K * 2u, kBufFlags);
 
     // Loader geometry: thread t handles piece pc = t & 7 of rows 32 i + (t >> 3) of both tiles.
     const int lrow = threadIdx.x >> 3, pc = threadIdx.x & 7;
@@ -99,12 +77,12 @@ __global__ __launch_bounds__(256) void k_linear_tile(const void* __restrict__ Xv
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const uint32_t wr = (uint32_t)(n_base + 32 * i + lrow);
-        woff[i] = wr < (uint32_t)N ? (wr * (uint32_t)K + 8u * pc) * 2u : kTileOutOfRange;
+        woff[i] = wr < (uint32_t)N ? (wr * (uint32_t)K + 8u * pc) * 2u : kOutOfRange;
         const int row = 32 * i + lrow;
         slot[i] = row * 8 + (pc ^ swizzle_key(row));
         if (i < XI) {
             const uint32_t xr = (uint32_t)(m_base + 32 * i + lrow);
-            xoff[i] = xr < (uint32_t)M ? (xr * (uint32_t)K + 8u * pc) * 2u : kTileOutOfRange;
+            xoff[i] = xr < (uint32_t)M ? (xr * (uint32_t)K + 8u * pc) * 2u : kOutOfRange;
         }
     }
     // rows of the operand fragments this lane reads, and their swizzle keys
@@ -186,9 +164,9 @@ __global__ __launch_bounds__(256) void k_linear_tile(const void* __restrict__ Xv
     const int last = n_chunks - 1;
     // Per-column operands of the epilogue, requested ahead of the operand tiles: their round trip is over long
     // before the loop ends.
-    const __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(bias), 0, bias ? (uint32_t)N * 4u : 0u, kTileFlags);
-    const __amdgpu_buffer_rsrc_t ru = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(nf.u), 0, (NF == 1) ? (uint32_t)N * 4u : 0u, kTileFlags);
-    const __amdgpu_buffer_rsrc_t rgn = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(fo.gain), 0, (EPI == EPI_RESID_NORM) ? (uint32_t)N * 4u : 0u, kTileFlags);
+    const __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(bias), 0, bias ? (uint32_t)N * 4u : 0u, kBufFlags);
+    const __amdgpu_buffer_rsrc_t ru = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(nf.u), 0, (NF == 1) ? (uint32_t)N * 4u : 0u, kBufFlags);
+    const __amdgpu_buffer_rsrc_t rgn = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(fo.gain), 0, (EPI == EPI_RESID_NORM) ? (uint32_t)N * 4u : 0u, kBufFlags);
     float bvs[NT], uvs[NT], gvns[NT];
 #pragma unroll
     for (int j = 0; j < NT; ++j) {
@@ -275,16 +253,16 @@ __global__ __launch_bounds__(256) void k_linear_tile(const void* __restrict__ Xv
     // Accumulator e of a 32 x 32 tile is row 8 (e / 4) + 4 half + e % 4, column lane & 31.
     constexpr bool kResid = EPI == EPI_RESID || EPI == EPI_RESID_NORM;
     constexpr uint32_t kOutBytes = (EPI == EPI_STORE || EPI == EPI_GELU) ? 2u : 4u;
-    const __amdgpu_buffer_rsrc_t ry = __builtin_amdgcn_make_buffer_rsrc(Y, 0, (uint32_t)M * (uint32_t)ldy * kOutBytes, kTileFlags);
-    const __amdgpu_buffer_rsrc_t rxg = __builtin_amdgcn_make_buffer_rsrc(fo.xg, 0, (EPI == EPI_RESID_NORM) ? (uint32_t)M * (uint32_t)N * 2u : 0u, kTileFlags);
+    const __amdgpu_buffer_rsrc_t ry = __builtin_amdgcn_make_buffer_rsrc(Y, 0, (uint32_t)M * (uint32_t)ldy * kOutBytes, kBufFlags);
+    const __amdgpu_buffer_rsrc_t rxg = __builtin_amdgcn_make_buffer_rsrc(fo.xg, 0, (EPI == EPI_RESID_NORM) ? (uint32_t)M * (uint32_t)N * 2u : 0u, kBufFlags);
     const int wm_base = m_base + wm * 64;
     const int parts_out = (N + 31) / 32;
 #pragma unroll
     for (int j = 0; j < NT; ++j) {
         const int col0 = n_base + wn * 32 * NT + 32 * j;
         const uint32_t n = (uint32_t)(col0 + r);
-        const uint32_t yoff = n < (uint32_t)N ? ((uint32_t)(wm_base + 4 * half) * (uint32_t)ldy + n) * kOutBytes : kTileOutOfRange;
-        const uint32_t xgoff = n < (uint32_t)N ? ((uint32_t)(wm_base + 4 * half) * (uint32_t)N + n) * 2u : kTileOutOfRange;
+        const uint32_t yoff = n < (uint32_t)N ? ((uint32_t)(wm_base + 4 * half) * (uint32_t)ldy + n) * kOutBytes : kOutOfRange;
+        const uint32_t xgoff = n < (uint32_t)N ? ((uint32_t)(wm_base + 4 * half) * (uint32_t)N + n) * 2u : kOutOfRange;
         const float bv = bvs[j], uv = uvs[j], gvn = gvns[j];
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
@@ -298,7 +276,7 @@ __global__ __launch_bounds__(256) void k_linear_tile(const void* __restrict__ Xv
                     v = fmaf(ab[row * 2 + 0], v, ab[row * 2 + 1] * uv);
                 }
                 v += bv;
-                if constexpr (EPI == EPI_GELU) v = gelu_tile(v);
+                if constexpr (EPI == EPI_GELU) v = gelu_fast(v);
                 if constexpr (kResid) v += __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(ry, yoff + so, 0, 0));
                 if constexpr (kOutBytes == 2)
                     __builtin_amdgcn_raw_buffer_store_b16(__builtin_bit_cast(unsigned short, static_cast<bf16_t>(v)), ry, yoff + so, 0, 0);
