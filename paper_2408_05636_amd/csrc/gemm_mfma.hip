@@ -25,29 +25,6 @@
 
 namespace sd {
 
-// Normalisation folded around the contraction (no normalised copy of the residual stream h, no separate
-// normalisation kernel).  For y = W norm(h) + bias:
-//   LayerNorm (NF = 1):  y_n = rstd_m (sum_k h_mk g_k W_nk - mu_m u_n) + v_n,  u = W g,  v = W beta + bias
-//   RMSNorm   (NF = 2):  y_n = rstd_m  sum_k h_mk g_k W_nk + bias_n
-// The A operand x = bf16(h g) and the row sums of h are prepared by whoever produced h: the residual
-// epilogue EPI_RESID_NORM of the previous contraction (below) or the row kernel that follows the
-// embedding.  The row sums arrive as `parts` partial pairs (sum h, sum h^2) per row, added here in a
-// fixed order; u and v are precomputed per layer.
-struct FoldIn {
-    const float* stats;  // [M][parts][2]
-    const float* u;      // W g, [N] (LayerNorm only)
-    int parts;
-    float eps;
-};
-// EPI_RESID_NORM: y (fp32, the residual stream) += acc + bias as EPI_RESID, and for the normalisation that
-// follows: xg[m][n] = bf16(y[m][n] gain[n]) and, per row and per 32-column tile, (sum y, sum y^2) over the
-// tile's columns -> stats[m][n / 32][2].
-struct FoldOut {
-    const float* gain;   // [N]
-    bf16_t* xg;          // [M][N]
-    float* stats;        // [M][ceil(N / 32)][2]
-};
-
 // K split across workgroups: gsplit = gridDim.y ranges; part holds gsplit records per output tile,
 // ticket one counter per output tile (zero before the launch, zero again after it).
 struct SplitArgs {

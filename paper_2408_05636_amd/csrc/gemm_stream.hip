@@ -21,7 +21,7 @@
 // draws the last ticket of the tile adds the partials in split order (its own included, read back) and runs
 // the epilogue: deterministic, and nobody waits for anybody.
 //
-// Normalisations folded around the contraction work as in gemm_mfma.hip (FoldIn / FoldOut there).
+// Normalisations folded around the contraction work as in gemm_mfma.hip (FoldIn / FoldOut in mfma_common.hip.h).
 #include <algorithm>
 #include <string>
 
@@ -34,17 +34,6 @@ constexpr int kAbPieces = 32;                        // 64 rows x (rstd, -rstd m
 constexpr int kStreamPD = 4;                         // chunks in flight per wave (16 KB)
 constexpr int kStep = 4;                             // chunks per slab step
 
-struct StreamFoldIn {
-    const float* stats;  // [M][parts][2] partial (sum h, sum h^2)
-    const float* u;      // W gain [N] (LayerNorm)
-    int parts;
-    float eps;
-};
-struct StreamFoldOut {
-    const float* gain;   // [N]
-    bf16_t* xg;          // [M][N]
-    float* stats;        // [M][ceil(N / 32)][2]
-};
 struct StreamSplit {
     float* part;            // [column tile][split][MT * 16][64] fp32
     unsigned int* ticket;   // one counter per column tile, zero between launches
@@ -54,7 +43,7 @@ struct StreamSplit {
 template <int MT, int EPI, int NF>
 __global__ __launch_bounds__(256) void k_linear_stream(const bf16_t* __restrict__ X, const bf16_t* __restrict__ W,
                                                        const float* __restrict__ bias, void* Y, int M, int N, int K,
-                                                       int ldy, StreamFoldIn nf, StreamFoldOut fo, StreamSplit sk) {
+                                                       int ldy, FoldIn nf, FoldOut fo, StreamSplit sk) {
     constexpr int PD = kStreamPD, S = kStep;
     static_assert(S == PD && PD % 2 == 0, "one group of PD chunks per step; fragment double buffering needs an even PD");
     extern __shared__ u32x4 lds[];
@@ -417,7 +406,7 @@ static const char* stream_name(int mt, int epi, int nfk) {
 
 template <int MT, int EPI, int NF>
 static hipError_t go(const dim3& grid, int bytes, hipStream_t st, const bf16_t* x, const bf16_t* w, const float* bias, void* y,
-                     int m, int n, int k, int ldy, const StreamFoldIn& fi, const StreamFoldOut& fo, const StreamSplit& sk) {
+                     int m, int n, int k, int ldy, const FoldIn& fi, const FoldOut& fo, const StreamSplit& sk) {
     static bool raised = false;          // dynamic LDS beyond 64 KB has to be allowed once per kernel
     if (!raised) {
         const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_linear_stream<MT, EPI, NF>),
@@ -433,8 +422,8 @@ template <int MT>
 static hipError_t launch_mt(const dim3& grid, int bytes, hipStream_t st, const bf16_t* x, const bf16_t* w, const float* bias,
                             void* y, int m, int n, int k, int ldy, int epi, const NormIn& ni, const NormOut& no,
                             const StreamSplit& sk) {
-    const StreamFoldIn fi{ni.stats, ni.u, ni.parts, ni.eps};
-    const StreamFoldOut fo{no.gain, static_cast<bf16_t*>(no.xg), no.stats};
+    const FoldIn fi{ni.stats, ni.u, ni.parts, ni.eps};
+    const FoldOut fo{no.gain, static_cast<bf16_t*>(no.xg), no.stats};
 #define SD_GO(EPI, NF) return go<MT, EPI, NF>(grid, bytes, st, x, w, bias, y, m, n, k, ldy, fi, fo, sk)
     if (ni.kind == 0) {
         switch (epi) {

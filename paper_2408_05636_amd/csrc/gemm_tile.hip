@@ -21,23 +21,11 @@
 
 namespace sd {
 
-struct TileFoldIn {
-    const float* stats;  // [M][parts][2] partial (sum h, sum h^2)
-    const float* u;      // W gain [N] (LayerNorm)
-    int parts;
-    float eps;
-};
-struct TileFoldOut {
-    const float* gain;   // [N]
-    bf16_t* xg;          // [M][N]
-    float* stats;        // [M][ceil(N / 32)][2]
-};
-
 template <int EPI, int WM, int NF>
 __global__ __launch_bounds__(256) void k_linear_tile(const void* __restrict__ Xv, const bf16_t* __restrict__ W,
                                                      const float* __restrict__ bias, void* Y, int M, int N, int K,
                                                      int ldy, int tiles_m, int tiles_n, int x_stationary,
-                                                     TileFoldIn nf, TileFoldOut fo) {
+                                                     FoldIn nf, FoldOut fo) {
     constexpr int BM = 64 * WM;            // rows of the workgroup tile
     constexpr int XI = BM / 32;            // x row groups per loader thread
     constexpr int NT = WM == 2 ? 2 : 1;    // 32-column tiles per wave
@@ -231,81 +219,10 @@ __global__ __launch_bounds__(256) void k_linear_tile(const void* __restrict__ Xv
 #undef SD_TILE_FRAGS
 #undef SD_TILE_COMPUTE
 
-    // Epilogue scratch in LDS (the staging tiles are free once every wave has left the loop): rstd and
-    // -rstd mu of the BM rows, then one padded 32 x 32 tile per wave for the row sums of EPI_RESID_NORM.
-    float* const ab = reinterpret_cast<float*>(&lds_w[0][0]);             // [BM][2]
-    float* const rowsum = ab + BM * 2 + wave * (32 * 33);
-    if constexpr (NF > 0 || EPI == EPI_RESID_NORM) __syncthreads();
-    if constexpr (NF > 0) {
-        if ((threadIdx.x & 3) == 0) {
-#pragma unroll
-            for (int t = 0; t < WM; ++t) {
-                const float mu = NF == 1 ? fs1[t] / (float)K : 0.f;
-                const float var = fmaxf(fs2[t] / (float)K - mu * mu, 0.f);
-                const float rstd = rsqrtf(var + nf.eps);
-                ab[(64 * t + (threadIdx.x >> 2)) * 2 + 0] = rstd;
-                ab[(64 * t + (threadIdx.x >> 2)) * 2 + 1] = -rstd * mu;
-            }
-        }
-        __syncthreads();
-    }
-
-    // Accumulator e of a 32 x 32 tile is row 8 (e / 4) + 4 half + e % 4, column lane & 31.
-    constexpr bool kResid = EPI == EPI_RESID || EPI == EPI_RESID_NORM;
-    constexpr uint32_t kOutBytes = (EPI == EPI_STORE || EPI == EPI_GELU) ? 2u : 4u;
-    const __amdgpu_buffer_rsrc_t ry = __builtin_amdgcn_make_buffer_rsrc(Y, 0, (uint32_t)M * (uint32_t)ldy * kOutBytes, kBufFlags);
-    const __amdgpu_buffer_rsrc_t rxg = __builtin_amdgcn_make_buffer_rsrc(fo.xg, 0, (EPI == EPI_RESID_NORM) ? (uint32_t)M * (uint32_t)N * 2u : 0u, kBufFlags);
-    const int wm_base = m_base + wm * 64;
-    const int parts_out = (N + 31) / 32;
-#pragma unroll
-    for (int j = 0; j < NT; ++j) {
-        const int col0 = n_base + wn * 32 * NT + 32 * j;
-        const uint32_t n = (uint32_t)(col0 + r);
-        const uint32_t yoff = n < (uint32_t)N ? ((uint32_t)(wm_base + 4 * half) * (uint32_t)ldy + n) * kOutBytes : kOutOfRange;
-        const uint32_t xgoff = n < (uint32_t)N ? ((uint32_t)(wm_base + 4 * half) * (uint32_t)N + n) * 2u : kOutOfRange;
-        const float bv = bvs[j], uv = uvs[j], gvn = gvns[j];
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int lr = 32 * i + 8 * (e >> 2) + (e & 3);          // row within the wave's 64, minus 4 * half
-                const uint32_t so = (uint32_t)lr * (uint32_t)ldy * kOutBytes;
-                float v = acc[i][j][e];
-                if constexpr (NF > 0) {
-                    const int row = wm * 64 + lr + 4 * half;
-                    v = fmaf(ab[row * 2 + 0], v, ab[row * 2 + 1] * uv);
-                }
-                v += bv;
-                if constexpr (EPI == EPI_GELU) v = gelu_fast(v);
-                if constexpr (kResid) v += __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(ry, yoff + so, 0, 0));
-                if constexpr (kOutBytes == 2)
-                    __builtin_amdgcn_raw_buffer_store_b16(__builtin_bit_cast(unsigned short, static_cast<bf16_t>(v)), ry, yoff + so, 0, 0);
-                else
-                    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned int, v), ry, yoff + so, 0, 0);
-                if constexpr (EPI == EPI_RESID_NORM) {
-                    __builtin_amdgcn_raw_buffer_store_b16(__builtin_bit_cast(unsigned short, static_cast<bf16_t>(v * gvn)), rxg,
-                                                          xgoff + (uint32_t)lr * (uint32_t)N * 2u, 0, 0);
-                    rowsum[(8 * (e >> 2) + 4 * half + (e & 3)) * 33 + r] = v;       // columns >= N hold 0
-                }
-            }
-            if constexpr (EPI == EPI_RESID_NORM) {
-                // Row sums of this 32 x 32 tile, columns ascending (LDS operations of one wave execute in order).
-                const int row = wm_base + 32 * i + lane;
-                if (lane < 32 && row < M && col0 < N) {
-                    float t1 = 0.f, t2 = 0.f;
-#pragma unroll
-                    for (int c = 0; c < 32; ++c) {
-                        const float x = rowsum[lane * 33 + c];
-                        t1 += x;
-                        t2 = fmaf(x, x, t2);
-                    }
-                    float* so_ = fo.stats + ((size_t)row * parts_out + col0 / 32) * 2;
-                    so_[0] = t1;
-                    so_[1] = t2;
-                }
-            }
-        }
-    }
+    // Epilogue (shared with the kernel that feeds its tiles straight into LDS); its LDS scratch is the W staging area,
+    // free once every wave has left the loop.
+    shared_tile_epilogue<EPI, NF, 2, NT, BM>(acc, reinterpret_cast<float*>(&lds_w[0][0]), fs1, fs2, bvs, uvs, gvns, wave, wm, wn,
+                                             m_base, n_base, Y, M, N, K, ldy, nf, fo);
 }
 
 static std::string g_tile_names[5][3][3];
@@ -345,8 +262,8 @@ static hipError_t launch_tile(const void* x, const bf16_t* wb, const float* bias
     const int tiles_m = (m + 64 * WM - 1) / (64 * WM), tiles_n = (n + 127) / 128;
     const int xs = (int64_t)m > (int64_t)n ? kTileColumnGroups : 0;
     const int grid = xs ? 8 * ((tiles_m + 8 / xs - 1) / (8 / xs)) * ((tiles_n + xs - 1) / xs) : 8 * ((tiles_n + 7) / 8) * tiles_m;
-    const TileFoldIn fi{ni.stats, ni.u, ni.parts, ni.eps};
-    const TileFoldOut fo{no.gain, static_cast<bf16_t*>(no.xg), no.stats};
+    const FoldIn fi{ni.stats, ni.u, ni.parts, ni.eps};
+    const FoldOut fo{no.gain, static_cast<bf16_t*>(no.xg), no.stats};
 #define SD_GO(EPI, NF) k_linear_tile<EPI, WM, NF><<<grid, 256, 0, st>>>(x, wb, bias, y, m, n, k, ldy, tiles_m, tiles_n, xs, fi, fo)
     if (ni.kind == 0) {
         switch (epi) {

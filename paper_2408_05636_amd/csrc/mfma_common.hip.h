@@ -1,5 +1,6 @@
 // Device-side pieces shared by the matrix-core kernels (contractions and attention): the vector types of the
-// MFMA operands, the raw-buffer constants, the LDS-only barrier, the tanh-form GELU and the LDS swizzle key.
+// MFMA operands, the raw-buffer constants, the LDS-only barrier, the tanh-form GELU, the LDS swizzle key, the
+// description of a folded normalisation and the epilogue of the kernels with workgroup-shared tiles.
 #pragma once
 
 #include "common.h"
@@ -31,5 +32,114 @@ __device__ inline float gelu_fast(float x) {
 // 32 consecutive rows at one logical piece index; rows are 128 bytes apart, so rows of equal parity share
 // their banks and the key must separate them: any 16 consecutive rows get 16 distinct (parity, key) pairs.
 __device__ inline int swizzle_key(int row) { return (row & 7) ^ ((row >> 3) & 1); }
+
+// Normalisation folded around the contraction (no normalised copy of the residual stream h, no separate
+// normalisation kernel).  For y = W norm(h) + bias:
+//   LayerNorm (NF = 1):  y_n = rstd_m (sum_k h_mk g_k W_nk - mu_m u_n) + v_n,  u = W g,  v = W beta + bias
+//   RMSNorm   (NF = 2):  y_n = rstd_m  sum_k h_mk g_k W_nk + bias_n
+// The A operand x = bf16(h g) and the row sums of h are prepared by whoever produced h: the residual
+// epilogue EPI_RESID_NORM of the previous contraction (below) or the row kernel that follows the
+// embedding.  The row sums arrive as `parts` partial pairs (sum h, sum h^2) per row, added here in a
+// fixed order; u and v are precomputed per layer.
+struct FoldIn {
+    const float* stats;  // [M][parts][2]
+    const float* u;      // W g, [N] (LayerNorm only)
+    int parts;
+    float eps;
+};
+// EPI_RESID_NORM: y (fp32, the residual stream) += acc + bias as EPI_RESID, and for the normalisation that
+// follows: xg[m][n] = bf16(y[m][n] gain[n]) and, per row and per 32-column tile, (sum y, sum y^2) over the
+// tile's columns -> stats[m][n / 32][2].
+struct FoldOut {
+    const float* gain;   // [N]
+    bf16_t* xg;          // [M][N]
+    float* stats;        // [M][ceil(N / 32)][2]
+};
+
+// Epilogue of the kernels whose four waves share a workgroup tile (gemm_tile.hip, gemm_pipe.hip).  Wave (wm, wn) holds
+// TM x TN accumulator tiles of 32 x 32 (accumulator e of a tile: row 8 (e / 4) + 4 half + e % 4, column lane & 31) of a
+// tile with BM rows at (m_base, n_base).  scratch: LDS that is free once every wave has left the K loop -- rstd and
+// -rstd mu of the BM rows, then one padded 32 x 32 tile per wave for the row sums of EPI_RESID_NORM.  fs1, fs2 (NF > 0):
+// the sums of h and h^2 of row m_base + 64 t + (thread >> 2), complete in every thread.  bvs, uvs, gvns: bias, W gain and
+// the next normalisation's gain at this lane's columns.  No barrier after the first two.
+template <int EPI, int NF, int TM, int TN, int BM>
+__device__ inline void shared_tile_epilogue(const floatx16 (&acc)[TM][TN], float* scratch, const float* fs1, const float* fs2,
+                                            const float (&bvs)[TN], const float (&uvs)[TN], const float (&gvns)[TN], int wave,
+                                            int wm, int wn, int m_base, int n_base, void* Y, int M, int N, int K, int ldy,
+                                            const FoldIn& nf, const FoldOut& fo) {
+    const int lane = threadIdx.x & 63, r = lane & 31, half = lane >> 5;
+    float* const ab = scratch;                                            // [BM][2]
+    float* const rowsum = ab + BM * 2 + wave * (32 * 33);
+    if constexpr (NF > 0 || EPI == EPI_RESID_NORM) __syncthreads();
+    if constexpr (NF > 0) {
+        if ((threadIdx.x & 3) == 0) {
+#pragma unroll
+            for (int t = 0; t < BM / 64; ++t) {
+                const float mu = NF == 1 ? fs1[t] / (float)K : 0.f;
+                const float var = fmaxf(fs2[t] / (float)K - mu * mu, 0.f);
+                const float rstd = rsqrtf(var + nf.eps);
+                ab[(64 * t + (threadIdx.x >> 2)) * 2 + 0] = rstd;
+                ab[(64 * t + (threadIdx.x >> 2)) * 2 + 1] = -rstd * mu;
+            }
+        }
+        __syncthreads();
+    }
+
+    constexpr bool kResid = EPI == EPI_RESID || EPI == EPI_RESID_NORM;
+    constexpr uint32_t kOutBytes = (EPI == EPI_STORE || EPI == EPI_GELU) ? 2u : 4u;
+    const __amdgpu_buffer_rsrc_t ry = __builtin_amdgcn_make_buffer_rsrc(Y, 0, (uint32_t)M * (uint32_t)ldy * kOutBytes, kBufFlags);
+    const __amdgpu_buffer_rsrc_t rxg = __builtin_amdgcn_make_buffer_rsrc(fo.xg, 0, (EPI == EPI_RESID_NORM) ? (uint32_t)M * (uint32_t)N * 2u : 0u, kBufFlags);
+    const int wm_base = m_base + wm * 32 * TM;
+    const int parts_out = (N + 31) / 32;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int col0 = n_base + wn * 32 * TN + 32 * j;
+        const uint32_t n = (uint32_t)(col0 + r);
+        const uint32_t yoff = n < (uint32_t)N ? ((uint32_t)(wm_base + 4 * half) * (uint32_t)ldy + n) * kOutBytes : kOutOfRange;
+        const uint32_t xgoff = n < (uint32_t)N ? ((uint32_t)(wm_base + 4 * half) * (uint32_t)N + n) * 2u : kOutOfRange;
+        const float bv = bvs[j], uv = uvs[j], gvn = gvns[j];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int lr = 32 * i + 8 * (e >> 2) + (e & 3);          // row within the wave's part, minus 4 * half
+                const uint32_t so = (uint32_t)lr * (uint32_t)ldy * kOutBytes;
+                float v = acc[i][j][e];
+                if constexpr (NF > 0) {
+                    const int row = wm * 32 * TM + lr + 4 * half;
+                    v = fmaf(ab[row * 2 + 0], v, ab[row * 2 + 1] * uv);
+                }
+                v += bv;
+                if constexpr (EPI == EPI_GELU) v = gelu_fast(v);
+                if constexpr (kResid) v += __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(ry, yoff + so, 0, 0));
+                if constexpr (kOutBytes == 2)
+                    __builtin_amdgcn_raw_buffer_store_b16(__builtin_bit_cast(unsigned short, static_cast<bf16_t>(v)), ry, yoff + so, 0, 0);
+                else
+                    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned int, v), ry, yoff + so, 0, 0);
+                if constexpr (EPI == EPI_RESID_NORM) {
+                    __builtin_amdgcn_raw_buffer_store_b16(__builtin_bit_cast(unsigned short, static_cast<bf16_t>(v * gvn)), rxg,
+                                                          xgoff + (uint32_t)lr * (uint32_t)N * 2u, 0, 0);
+                    rowsum[(8 * (e >> 2) + 4 * half + (e & 3)) * 33 + r] = v;       // columns >= N hold 0
+                }
+            }
+            if constexpr (EPI == EPI_RESID_NORM) {
+                // Row sums of this 32 x 32 tile, columns ascending (LDS operations of one wave execute in order).
+                const int row = wm_base + 32 * i + lane;
+                if (lane < 32 && row < M && col0 < N) {
+                    float t1 = 0.f, t2 = 0.f;
+#pragma unroll
+                    for (int cc = 0; cc < 32; ++cc) {
+                        const float x = rowsum[lane * 33 + cc];
+                        t1 += x;
+                        t2 = fmaf(x, x, t2);
+                    }
+                    float* so_ = fo.stats + ((size_t)row * parts_out + col0 / 32) * 2;
+                    so_[0] = t1;
+                    so_[1] = t2;
+                }
+            }
+        }
+    }
+}
 
 }  // namespace sd
