@@ -1,22 +1,24 @@
 // bf16 contraction y = epilogue(x W^T + bias) for a few hundred rows and more, with the operand tiles
 // sent from global memory straight into LDS (buffer_load ... lds of gfx950: 16 bytes per lane, no register
-// staging, no LDS store instruction) through a ring of NS stages, so that NS - 1 chunks of K are in flight
-// while the matrix cores work on one.  The shared-tile kernel (gemm_tile.hip) holds its prefetch in registers
-// and can keep two chunks ahead; at a few hundred kilobytes per workgroup and a round trip of a microsecond or
-// so that depth, not the matrix cores, sets its pace.
+// staging, no LDS store instruction) through a ring of NS stages.  The shared-tile kernel (gemm_tile.hip) passes
+// its tiles through two register sets (64 VGPRs, a store instruction per 16 bytes, two chunks of prefetch at
+// most); here the tiles cost no registers and no instruction slots beyond the request, and a stage can hold
+// several chunks, so a few-hundred-row contraction spends fewer of its cycles outside the MFMAs.  (Depth itself
+// is not what pays: with two or three chunks in flight the pace is set by the LDS traffic of the tile, and 4, 6
+// or 8 stages run alike.)
 //
 // A workgroup of four waves (WMV x WNV) owns a BM x BN tile, wave (wm, wn) a (32 TM) x (32 TN) part of it.
-// K is walked in chunks of 64.  A stage holds the x tile (BM rows of 128 bytes) and the W tile (BN rows); piece
-// c (16 bytes) of row r sits at piece c ^ key(r), the same XOR swizzle as in the shared-tile kernel.  One load
-// instruction fills 8 consecutive rows: lane l lands at piece l & 7 of row l >> 3 of those eight (the hardware
-// places lane l at base + 16 l), so the swizzle is applied by choosing which piece of global memory lane l
-// asks for.  Rows beyond M or N carry an out-of-range offset and arrive as zeros.
+// K is walked in chunks of 64, KC chunks per stage.  A chunk of a stage holds the x tile (BM rows of 128 bytes)
+// and the W tile (BN rows); piece c (16 bytes) of row r sits at piece c ^ key(r), the same XOR swizzle as in the
+// shared-tile kernel.  One load instruction fills 8 consecutive rows: lane l lands at piece l & 7 of row l >> 3 of
+// those eight (the hardware places lane l at base + 16 l), so the swizzle is applied by choosing which piece of
+// global memory lane l asks for.  Rows beyond M or N carry an out-of-range offset and arrive as zeros.
 //
 // The loads are written in assembly: the compiler then neither knows about them nor waits for them, and the loop
 // waits by hand -- "all but the newest (NS - 2) stages have landed" before the barrier that hands the oldest
 // stage to the matrix cores.  Operand reads and MFMAs stay ordinary code with compiler-managed waits.
-//   step c:  wait for chunk c; barrier (everybody has chunk c, everybody is done with chunk c - 1);
-//            request chunk c + NS - 1 into the stage chunk c - 1 used; multiply chunk c.
+//   step c:  wait for stage c; barrier (everybody has stage c, everybody is done with stage c - 1);
+//            request stage c + NS - 1 into the memory stage c - 1 used; multiply stage c.
 // The last NS - 1 steps request nothing and wait for one stage less each.
 #include <string>
 
