@@ -43,9 +43,12 @@ def invcdf(w, u):
     return v, float(margin)
 
 
-def draft_with_uniforms(drafter_logits, prefix, gamma, T, ua, ub, mask_id, skip_when_done=True):
+def draft_with_uniforms(drafter_logits, prefix, gamma, T, ua, ub, mask_id, skip_when_done=True, skip_idle_steps=False):
     """Steps (1)-(3).  drafter_logits(tokens, t) -> [gamma, V] logits of the block rows for the
     sequence prefix o block.  ua, ub: [T+1, gamma] uniforms indexed [j, k] (row 0 unused).
+    skip_idle_steps: also leave out the forward of a step at which no masked slot is revealed -- which
+    slots a step reveals is decided by the uniforms alone, and the output of a step's forward is read
+    by nothing but the slots revealed at that step, so z and q cannot depend on it.
     Returns (z int64[gamma], q fp32[gamma, V], margins fp64[gamma], n_forwards)."""
     prefix = np.asarray(prefix, dtype=np.int64)
     z = np.full(gamma, mask_id, dtype=np.int64)
@@ -56,6 +59,8 @@ def draft_with_uniforms(drafter_logits, prefix, gamma, T, ua, ub, mask_id, skip_
         masked = np.flatnonzero(z == mask_id)
         if masked.size == 0 and skip_when_done:
             continue                                   # nothing left to reveal: the step is a no-op
+        if skip_idle_steps and not any(j == 1 or ua[j, k] * j < 1.0 for k in masked):
+            continue                                   # nobody looks at this step's logits
         logits = np.asarray(drafter_logits(np.concatenate([prefix, z]), j / T), dtype=np.float64)
         n_forwards += 1
         if q is None:

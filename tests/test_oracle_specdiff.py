@@ -325,6 +325,26 @@ def test_revealed_block_is_a_fixed_point_and_skipping_is_harmless():
         assert all(q1[k, z1[k]] > 0 for k in range(gamma))     # a token is drawn from its own row
 
 
+def test_steps_that_reveal_nothing_can_be_left_out():
+    """Which slots a step reveals is decided by the uniforms alone and a step's logits are read by nothing but
+    the slots revealed at it: leaving out the forwards of steps that reveal nothing changes neither z nor q, for
+    a drafter whose logits depend on the time and on the state of the block.  The forwards that remain are those
+    of the distinct reveal steps (each slot's reveal step is uniform on 1..T: Algorithm 1's 1/j rule)."""
+    MASK, gamma, T = 3, 2, 6
+    saved = 0
+    for seed in range(60):
+        ua, ub = sd.draft_uniforms(seed, 0, gamma, T)
+        d1, d2 = ToyDrafter(), ToyDrafter()
+        z1, q1, m1, n1 = sd.draft_with_uniforms(d1, [2, 2, 1], gamma, T, ua, ub, MASK)
+        z2, q2, m2, n2 = sd.draft_with_uniforms(d2, [2, 2, 1], gamma, T, ua, ub, MASK, skip_idle_steps=True)
+        assert (z1 == z2).all() and np.array_equal(q1, q2) and np.array_equal(m1, m2)
+        # reveal step of slot k: the first j, counting down from T, with ua[j, k] * j < 1 (j = 1 always)
+        steps = {next(j for j in range(T, 0, -1) if j == 1 or ua[j, k] * j < 1.0) for k in range(gamma)}
+        assert n2 == d2.calls == len(steps) <= n1
+        saved += n1 - n2
+    assert saved > 0                                           # the option does leave forwards out
+
+
 def test_draft_uses_the_documented_counters():
     gamma, T = 3, 2
     ua, ub = sd.draft_uniforms(77, 4, gamma, T)
