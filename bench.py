@@ -81,6 +81,7 @@ def main():
     ap.add_argument("--greedy", action="store_true", help="temperature 0 (sd_set_greedy) instead of the stochastic rule")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true")
+    ap.add_argument("--no-step-skipping", action="store_true", help="leave out the extra timed pass with sd_set_step_skipping")
     ap.add_argument("--copy-probe", action="store_true", help="also launch one 64 MiB elementwise copy kernel, torch.neg (calibrates rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)")
     a = ap.parse_args()
     if a.gpus != 1:
@@ -128,6 +129,29 @@ def main():
         torch.cuda.synchronize()
 
     log(f"timed pass done: {ms_per_step:.3f} ms per round")
+    # The same rounds once more with the drafter left out at the steps that reveal no slot (sd_set_step_skipping: same
+    # drafts and verdicts, fewer forwards).  Reported beside the headline value, which runs all T steps.
+    skipping = None
+    if not a.no_step_skipping:
+        sd.sd_set_step_skipping(True)
+        for i in range(a.warmup):
+            sd.sd_round_flat(flat, lens, gamma, T, 100 + i)
+        for i in range(a.steps):                              # every step's launch sequence seen, captured and replayed
+            sd.sd_round_flat(flat, lens, gamma, T, 1000 + i)
+        torch.cuda.synchronize()
+        tok2 = steps_run = 0
+        t1 = time.perf_counter()
+        for i in range(a.steps):
+            _, n, _ = sd.sd_round_flat(flat, lens, gamma, T, 1000 + i)
+            tok2 += int(n.sum()) + B
+            steps_run += sd.sd_steps_run()
+        torch.cuda.synchronize()
+        dt2 = time.perf_counter() - t1
+        sd.sd_set_step_skipping(False)
+        assert tok2 == tokens, "step skipping changed the outcome of a round"
+        skipping = {"value": tok2 / dt2, "unit": "tokens/s", "ms_per_step": dt2 / a.steps * 1e3,
+                    "mean_drafter_forwards_per_round": steps_run / a.steps, "of": T}
+        log(f"with step skipping: {skipping['ms_per_step']:.3f} ms per round, {skipping['mean_drafter_forwards_per_round']:.2f} of {T} forwards")
     roof = None
     phases = None
     kernels = None
@@ -187,7 +211,7 @@ def main():
                                f"gamma={gamma}, T={T}, batch={B}, random-init weights" + (", temperature 0" if a.greedy else "")},
         "round_latency_us": ms_per_step * 1e3,
         "mean_accepted_per_round": accepted / (a.steps * B),
-        "roofline": roof, "cpu_baseline": cpu, "phases": phases, "kernels": kernels,
+        "roofline": roof, "cpu_baseline": cpu, "step_skipping": skipping, "phases": phases, "kernels": kernels,
     }
     print(json.dumps(out))
 

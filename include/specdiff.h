@@ -137,6 +137,16 @@ int32_t sd_commit(sd_handle *h, int32_t batch, const int32_t *n_accepted);
  * be non-NULL) and sd_round of this handle until switched off. */
 int32_t sd_set_greedy(sd_handle *h, int32_t enable);
 
+/* Leaving out drafting steps that reveal nothing (in the spirit of the cached sampling strategy that the appendix's
+ * table of parametric setups names for the drafter, applied to the reveal rule of Algorithm 1's sampling loop).  Which masked slots step j reveals is decided by the
+ * seed alone (probability 1/j per slot), and the logits of step j are read by the slots revealed at step j and by
+ * nothing else; enable != 0: sd_draft and sd_round replay the reveal schedule on the host and run the drafter only
+ * at the steps that reveal at least one slot -- same draft, same q, same verification, fewer forwards (each
+ * step is uniformly distributed per slot, so a step is idle with probability (1 - 1/T)^(batch gamma)).  Off by
+ * default.  sd_steps_run: drafter forwards of the last sd_draft / sd_round of this handle (T when off). */
+int32_t sd_set_step_skipping(sd_handle *h, int32_t enable);
+int32_t sd_steps_run(const sd_handle *h);
+
 /* ---- single steps of the path, for parity checks and profiling --------------------------- */
 
 /* One drafter evaluation M_q(prefix o block, t = step/T) (Algorithm 1, loop body).

@@ -24,7 +24,7 @@ EXPORTS = ["sd_vocab_pad", "sd_weight_count", "sd_weight_desc", "sd_weight_bytes
            "sd_destroy", "sd_last_error", "sd_prefill", "sd_draft", "sd_verify", "sd_round", "sd_drafter_logits",
            "sd_target_logits", "sd_sampling_scratch_bytes", "sd_unmask_sample", "sd_accept_resample", "sd_linear",
            "sd_profile_begin", "sd_profile_end", "sd_profile_count", "sd_profile_entry", "sd_set_graph_replay", "sd_set_linear_variant", "sd_norm_linear",
-           "sd_set_linear_split", "sd_linear_split_ticket_bytes", "sd_commit", "sd_set_greedy", "sd_norm_linear_scratch_floats", "sd_linear_resid_norm"]
+           "sd_set_linear_split", "sd_linear_split_ticket_bytes", "sd_commit", "sd_set_greedy", "sd_set_step_skipping", "sd_steps_run", "sd_norm_linear_scratch_floats", "sd_linear_resid_norm"]
 
 
 class SdModelConfig(C.Structure):
@@ -83,6 +83,8 @@ def lib() -> C.CDLL:
         L.sd_linear_resid_norm.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, vp, i64, vp]
         L.sd_commit.restype = i32; L.sd_commit.argtypes = [vp, i32, C.POINTER(C.c_int32)]
         L.sd_set_greedy.restype = i32; L.sd_set_greedy.argtypes = [vp, i32]
+        L.sd_set_step_skipping.restype = i32; L.sd_set_step_skipping.argtypes = [vp, i32]
+        L.sd_steps_run.restype = i32; L.sd_steps_run.argtypes = [vp]
         L.sd_linear_split_ticket_bytes.restype = i64; L.sd_linear_split_ticket_bytes.argtypes = []
         L.sd_set_graph_replay.restype = i32; L.sd_set_graph_replay.argtypes = [vp, i32]
         L.sd_set_linear_variant.restype = i32; L.sd_set_linear_variant.argtypes = [i32]
@@ -265,6 +267,12 @@ class SpecDiff:
     def sd_commit(self, n_accepted):
         n = np.ascontiguousarray(n_accepted, dtype=np.int32)
         self._check(lib().sd_commit(self.h, len(n), _ip(n)), "sd_commit")
+
+    def sd_set_step_skipping(self, enable: bool):
+        self._check(lib().sd_set_step_skipping(self.h, 1 if enable else 0), "sd_set_step_skipping")
+
+    def sd_steps_run(self) -> int:
+        return int(lib().sd_steps_run(self.h))
 
     def sd_set_greedy(self, enable: bool):
         self._check(lib().sd_set_greedy(self.h, 1 if enable else 0), "sd_set_greedy")

@@ -9,6 +9,7 @@
 #include <vector>
 
 #include "common.h"
+#include "philox.hip.h"
 
 using namespace sd;
 
@@ -302,6 +303,8 @@ struct sd_handle {
     std::unordered_set<uint64_t> seen;   // launch sequences run once so far (captured on their second use)
     bool use_graphs = true;
     bool greedy = false;                 // temperature 0 instead of the stochastic rule
+    bool skip_idle_steps = false;        // leave out the drafter forwards of steps that reveal no slot (sd_set_step_skipping)
+    int steps_run = 0;                   // drafter forwards of the last sd_draft / sd_round
     int temb_T = 0;                      // number of steps the timestep-embedding table in the workspace was built for
     bool head_folded = false;            // the last run_layers left x and row sums for the final normalisation (run_head folds it)
     // KV-cache state per sequence: number of cached positions and a hash of their tokens
@@ -835,28 +838,70 @@ int ensure_timestep_table(sd_handle* h, int T) {
 
 // The T reverse-diffusion steps (launches only: capturable).  Leaves z (draft), q, qtok in the workspace.
 // The timestep table is in place (ensure_timestep_table).
-int enqueue_draft(sd_handle* h, int batch, int gamma, int T) {
+// z <- [MASK]^gamma
+int enqueue_fill(sd_handle* h, int batch, int gamma) {
+    h->prof.phase = "draft:";
+    SD_LAUNCH(h, "k_fill_i32", 4.0 * batch * gamma, 0, launch_fill_i32(h->buf.z, batch * gamma, h->drafter.c.vocab, h->st));
+    return SD_OK;
+}
+
+// Drafting step j of T: forward at t = j / T, LM head on the block rows, reveal + sample.
+int enqueue_draft_step(sd_handle* h, int batch, int gamma, int T, int j) {
     Buffers& B = h->buf;
     const Model& m = h->drafter;
     const MapSet& rm = h->maps[0];
-    int rc;
     h->prof.phase = "draft:";
-    SD_LAUNCH(h, "k_fill_i32", 4.0 * batch * gamma, 0, launch_fill_i32(B.z, batch * gamma, m.c.vocab, h->st));   // z <- [MASK]^gamma
     const SampleScratch ss = sampling_scratch(B.sample_scratch, (int)h->lim.rows_head, m.c.vocab);
-    for (int j = T; j >= 1; --j) {
-        rc = run_layers(h, m, rm, B.temb + (int64_t)(j - 1) * m.c.d_model, batch * gamma);
-        if (rc) return rc;
-        rc = run_head(h, m, rm.blk, rm.head_row0, batch * gamma, B.logits_d);
-        if (rc) return rc;
-        if (h->greedy) {
-            SD_LAUNCH(h, "unmask_greedy(k_chunk_argmax+k_greedy_reveal)", 1.0 * batch * gamma / T * m.ld * 4, 0,
-                      launch_unmask_greedy(B.logits_d, batch, gamma, m.c.vocab, j, B.seed, B.z, B.qtok, ss, h->st));
-        } else {
-            SD_LAUNCH(h, "unmask_sample(k_row_stats+k_unmask_sample)", 3.0 * batch * gamma / T * m.ld * 4, 0,
-                      launch_unmask_sample(B.logits_d, batch, gamma, m.c.vocab, j, B.seed, B.z, B.q, B.qtok, ss, h->st));
-        }
+    int rc = run_layers(h, m, rm, B.temb + (int64_t)(j - 1) * m.c.d_model, batch * gamma);
+    if (rc) return rc;
+    rc = run_head(h, m, rm.blk, rm.head_row0, batch * gamma, B.logits_d);
+    if (rc) return rc;
+    if (h->greedy) {
+        SD_LAUNCH(h, "unmask_greedy(k_chunk_argmax+k_greedy_reveal)", 1.0 * batch * gamma / T * m.ld * 4, 0,
+                  launch_unmask_greedy(B.logits_d, batch, gamma, m.c.vocab, j, B.seed, B.z, B.qtok, ss, h->st));
+    } else {
+        SD_LAUNCH(h, "unmask_sample(k_row_stats+k_unmask_sample)", 3.0 * batch * gamma / T * m.ld * 4, 0,
+                  launch_unmask_sample(B.logits_d, batch, gamma, m.c.vocab, j, B.seed, B.z, B.q, B.qtok, ss, h->st));
     }
     return SD_OK;
+}
+
+int enqueue_draft(sd_handle* h, int batch, int gamma, int T) {
+    int rc = enqueue_fill(h, batch, gamma);
+    for (int j = T; j >= 1 && !rc; --j) rc = enqueue_draft_step(h, batch, gamma, T, j);
+    return rc;
+}
+
+// Which of the T drafting steps reveal at least one slot: needed[j] for j = 1 .. T; returns their number.  Whether a
+// masked slot is revealed at step j is decided by its Philox draw alone (reveal_now), so the whole schedule is
+// known before anything runs: slot (b, k) is revealed at the first j, counting down from T, whose draw says so.
+// The logits of a step are read by the slots revealed at it and by nothing else.
+int steps_that_reveal(int batch, int gamma, int T, uint64_t seed, std::vector<char>& needed) {
+    needed.assign(T + 1, 0);
+    for (int b = 0; b < batch; ++b)
+        for (int k = 0; k < gamma; ++k)
+            for (int j = T; j >= 1; --j)
+                if (reveal_now(k, j, b, STREAM_DRAFT, seed)) { needed[j] = 1; break; }
+    int n = 0;
+    for (int j = 1; j <= T; ++j) n += needed[j];
+    return n;
+}
+
+// The drafting part of a call, as graphs: one for all T steps, or -- leaving out the steps that reveal nothing -- one
+// per step (every step has its own time embedding and counter, hence its own graph).  call: distinguishes the
+// entry points in the graph keys.
+int replay_draft(sd_handle* h, int call, int batch, int gamma, int T, const int32_t* prefix_len, uint64_t seed) {
+    const int g = h->greedy ? 16 : 0;
+    if (!h->skip_idle_steps) {
+        h->steps_run = T;
+        return replay(h, shape_key(call + g, batch, gamma, T, prefix_len, nullptr), [&] { return enqueue_draft(h, batch, gamma, T); });
+    }
+    std::vector<char> needed;
+    h->steps_run = steps_that_reveal(batch, gamma, T, seed, needed);
+    int rc = replay(h, shape_key(6 + g, batch, gamma, 0, prefix_len, nullptr), [&] { return enqueue_fill(h, batch, gamma); });
+    for (int j = T; j >= 1 && !rc; --j)
+        if (needed[j]) rc = replay(h, shape_key(7 + g, batch, gamma, T * 4096 + j, prefix_len, nullptr), [&] { return enqueue_draft_step(h, batch, gamma, T, j); });
+    return rc;
 }
 
 // Prefill on demand and upload the maps of the gamma+1 query rows.
@@ -1075,7 +1120,7 @@ int32_t sd_draft(sd_handle* h, int32_t batch, const int32_t* prefix, const int32
     if (rc) return rc;
     rc = ensure_timestep_table(h, T);
     if (rc) return rc;
-    rc = replay(h, shape_key(1 + (h->greedy ? 16 : 0), batch, gamma, T, prefix_len, nullptr), [&] { return enqueue_draft(h, batch, gamma, T); });
+    rc = replay_draft(h, 1, batch, gamma, T, prefix_len, seed);
     if (rc) return rc;
     const int64_t cnt = (int64_t)batch * gamma;
     SD_HIP(h, hipMemcpyAsync(h->stage_out, h->buf.z, cnt * 4, hipMemcpyDeviceToHost, h->st));
@@ -1133,11 +1178,21 @@ int32_t sd_round(sd_handle* h, int32_t batch, const int32_t* prefix, const int32
     if (rc) return rc;
     rc = ensure_timestep_table(h, T);
     if (rc) return rc;
-    rc = replay(h, shape_key(3 + (h->greedy ? 16 : 0), batch, gamma, T, prefix_len, nullptr), [&] {
-        int r2 = enqueue_draft(h, batch, gamma, T);
-        if (!r2) r2 = enqueue_target(h);
-        return r2 ? r2 : enqueue_accept(h, batch, gamma, h->buf.q);
-    });
+    if (!h->skip_idle_steps) {
+        h->steps_run = T;
+        rc = replay(h, shape_key(3 + (h->greedy ? 16 : 0), batch, gamma, T, prefix_len, nullptr), [&] {
+            int r2 = enqueue_draft(h, batch, gamma, T);
+            if (!r2) r2 = enqueue_target(h);
+            return r2 ? r2 : enqueue_accept(h, batch, gamma, h->buf.q);
+        });
+    } else {
+        rc = replay_draft(h, 3, batch, gamma, T, prefix_len, seed);
+        if (!rc)
+            rc = replay(h, shape_key(8 + (h->greedy ? 16 : 0), batch, gamma, 0, prefix_len, nullptr), [&] {
+                const int r2 = enqueue_target(h);
+                return r2 ? r2 : enqueue_accept(h, batch, gamma, h->buf.q);
+            });
+    }
     if (rc) return rc;
     const int64_t cnt = (int64_t)batch * gamma;
     int32_t* so = h->stage_out;
@@ -1169,6 +1224,14 @@ int32_t sd_commit(sd_handle* h, int32_t batch, const int32_t* n_accepted) {
     h->pend_batch = 0;
     return SD_OK;
 }
+
+int32_t sd_set_step_skipping(sd_handle* h, int32_t enable) {
+    if (!h) return SD_ERR_ARG;
+    h->skip_idle_steps = enable != 0;
+    return SD_OK;
+}
+
+int32_t sd_steps_run(const sd_handle* h) { return h ? h->steps_run : -1; }
 
 int32_t sd_set_greedy(sd_handle* h, int32_t enable) {
     if (!h) return SD_ERR_ARG;

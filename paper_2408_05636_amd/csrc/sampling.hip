@@ -85,14 +85,6 @@ __device__ inline void load4(const float* row, int col, int vocab, float (&l)[4]
     }
 }
 
-// Is slot (b, k) revealed at reverse step `step`?  Probability 1/step: u < 1/step with
-// u = m 2^-24, decided exactly in integers as m * step < 2^24.
-__device__ inline bool reveal_now(int k, int step, int b, uint64_t seed) {
-    if (step == 1) return true;
-    const Philox4 r = philox4x32_10((uint32_t)k, (uint32_t)step, (uint32_t)b, STREAM_DRAFT, seed);
-    return (uint64_t)uniform_bits(r.x) * (uint64_t)step < (1ull << 24);
-}
-
 // ---------------------------------------------------------------- chunk statistics
 // grid (n_chunks, rows).  z != NULL: drafter mode, rows that are not revealed at this step are skipped.
 __global__ __launch_bounds__(kThreads) void k_row_stats(const float* __restrict__ logits, int ld, int vocab,
@@ -102,7 +94,7 @@ __global__ __launch_bounds__(kThreads) void k_row_stats(const float* __restrict_
     __shared__ double sh[4];
     const int row = blockIdx.y, c = blockIdx.x, nch = gridDim.x;
     if (z != nullptr) {
-        const bool act = (z[row] == vocab) && reveal_now(row % gamma, step, row / gamma, *seed_p);
+        const bool act = (z[row] == vocab) && reveal_now(row % gamma, step, row / gamma, STREAM_DRAFT, *seed_p);
         if (c == 0 && threadIdx.x == 0) active[row] = act ? 1 : 0;
         if (!act) return;
     }
@@ -372,7 +364,7 @@ __global__ __launch_bounds__(kThreads) void k_chunk_argmax(const float* __restri
     __shared__ int shi[4];
     const int row = blockIdx.y, c = blockIdx.x, nch = gridDim.x;
     if (z != nullptr) {
-        const bool act = (z[row] == vocab) && reveal_now(row % gamma, step, row / gamma, *seed_p);
+        const bool act = (z[row] == vocab) && reveal_now(row % gamma, step, row / gamma, STREAM_DRAFT, *seed_p);
         if (c == 0 && threadIdx.x == 0) active[row] = act ? 1 : 0;
         if (!act) return;
     }

@@ -70,3 +70,42 @@ def test_profile_entries_name_the_part_of_the_round():
     assert launches["draft"] > 2 * launches["verify"] and launches["accept"] >= 1
     assert all(e["ms"] > 0 for e in prof)
     sd.close()
+
+
+def test_step_skipping_changes_nothing_but_the_number_of_forwards():
+    """sd_set_step_skipping: the drafter runs only at the steps that reveal a slot.  Draft, q, q(x), accepted counts
+    and extra tokens are bit-identical with the option on and off (stochastic and temperature-0 rule, single
+    sequence and batch, each launch sequence eager, captured and replayed), the number of forwards is the number of
+    distinct reveal steps of the oracle's reveal rule, and with the option on the rounds still reproduce Algorithm 1."""
+    from oracle import specdiff as osd
+    sd, t, d, Wt, Wd = make("tiny", seed=26, max_batch=3, gamma_max=8)
+    V = t.vocab
+    saved = 0
+    for prefixes, gamma, T in (([synth.gen_prefix(V, 24, 13)], 4, 8), ([synth.gen_prefix(V, 9, 14), synth.gen_prefix(V, 30, 15), synth.gen_prefix(V, 17, 16)], 3, 6)):
+        for greedy in (False, True):
+            sd.sd_set_greedy(greedy)
+            for seed in range(500, 512):
+                sd.sd_set_step_skipping(False)
+                d0, qt0, q0 = sd.sd_draft(prefixes, gamma, T, seed)
+                q0 = q0.cpu().numpy().copy()
+                assert sd.sd_steps_run() == T
+                r0 = sd.sd_round(prefixes, gamma, T, seed)
+                sd.sd_set_step_skipping(True)
+                d1, qt1, q1 = sd.sd_draft(prefixes, gamma, T, seed)
+                q1 = q1.cpu().numpy().copy()
+                steps = set()
+                for b in range(len(prefixes)):
+                    ua, _ = osd.draft_uniforms(seed, b, gamma, T)
+                    steps |= {next(j for j in range(T, 0, -1) if j == 1 or ua[j, k] * j < 1.0) for k in range(gamma)}
+                assert sd.sd_steps_run() == len(steps)
+                saved += T - len(steps)
+                r1 = sd.sd_round(prefixes, gamma, T, seed)
+                assert sd.sd_steps_run() == len(steps)
+                assert np.array_equal(d0, d1) and np.array_equal(qt0, qt1)
+                if not greedy:
+                    assert np.array_equal(q0[:, :V], q1[:, :V])
+                assert all(np.array_equal(a, b) for a, b in zip(r0, r1))
+    assert saved > 0
+    sd.sd_set_greedy(False)
+    check_rounds(sd, [synth.gen_prefix(V, 24, 13)], 4, 8, seeds=[601, 602, 603])     # with the option still on
+    sd.close()
