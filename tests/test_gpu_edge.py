@@ -109,3 +109,14 @@ def test_step_skipping_changes_nothing_but_the_number_of_forwards():
     sd.sd_set_greedy(False)
     check_rounds(sd, [synth.gen_prefix(V, 24, 13)], 4, 8, seeds=[601, 602, 603])     # with the option still on
     sd.close()
+    # bf16 pair at GPT-2 width (matrix-core kernels, folded normalisations, direct KV-cache writes)
+    sd, t, d, Wt, Wd = make("gpt2s", seed=27, shrink_t=dict(n_layer=2, vocab=3001, n_ctx=256), shrink_d=dict(n_layer=2, vocab=3001, n_ctx=256),
+                            max_batch=1, gamma_max=8)
+    prefix = [synth.gen_prefix(t.vocab, 200, 17)]
+    for seed in range(700, 706):
+        sd.sd_set_step_skipping(False)
+        r0 = sd.sd_round(prefix, 8, 8, seed)
+        sd.sd_set_step_skipping(True)
+        r1 = sd.sd_round(prefix, 8, 8, seed)
+        assert all(np.array_equal(a, b) for a, b in zip(r0, r1)) and 1 <= sd.sd_steps_run() <= 8
+    sd.close()
