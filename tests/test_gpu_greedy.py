@@ -126,3 +126,22 @@ def test_stochastic_generation_equals_round_by_round_calls():
             seqs[b] += list(draft[b, :n[b]]) + [tok[b]]
     for b in range(2):
         assert np.array_equal(np.array(seqs[b][len(prefixes[b]):]), new[b])
+
+
+def test_generation_with_step_skipping_is_the_same_generation():
+    """A multi-round generation (prefix growing by every round's accepted tokens, sd_commit in between, one launch
+    sequence per step and length) with the drafter left out at idle steps emits the same tokens and accepts the same
+    counts as without, at temperature 0 (where it is also the target's own greedy string) and with the stochastic rule."""
+    sd, t, d, Wt, Wd = build("tiny", 11, {}, {}, sharpen=40.0, max_batch=1)
+    prefix = [synth.gen_prefix(t.vocab, 24, 1)]
+    tl = lambda tokens, rows: otf.logits_at(Wt, t, tokens, rows)
+    for greedy in (True, False):
+        sd.sd_set_greedy(greedy)
+        sd.sd_set_step_skipping(False)
+        new0, acc0 = sd.generate(prefix, 20, 4, 6, seed=300)
+        sd.sd_set_step_skipping(True)
+        new1, acc1 = sd.generate(prefix, 20, 4, 6, seed=300)
+        assert np.array_equal(new0[0], new1[0]) and np.array_equal(acc0, acc1)
+        if greedy:
+            assert np.array_equal(new1[0], osd.target_greedy_decode(tl, prefix[0], len(new1[0])))
+    sd.close()
