@@ -113,11 +113,13 @@ def main():
         sd.sd_round_flat(flat, lens, gamma, T, 100 + i)
     torch.cuda.synchronize()
     tokens = accepted = 0
+    n_hist = []
     t0 = time.perf_counter()
     for i in range(a.steps):
         _, n, _ = sd.sd_round_flat(flat, lens, gamma, T, 1000 + i)
         tokens += int(n.sum()) + B
         accepted += int(n.sum())
+        n_hist.extend(n.tolist())
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_per_step = dt / a.steps * 1e3
@@ -202,6 +204,17 @@ def main():
     if not a.no_cpu_baseline and not a.greedy:
         cpu = cpu_baseline(w, Wt, Wd, prefixes, 1000)
 
+    # Acceptance: random-init models agree far less often than the paper's trained pairs.  alpha_hat = accepted /
+    # tested positions (a round tests positions up to and including its first rejection).  As context only: the rate
+    # the same round latency would give at an acceptance rate the paper reports for a trained pair (vanilla SpecDiff,
+    # GPT-2 XL with an MDLM drafter on OpenWebText: alpha = 0.78), by the expected-tokens formula of Appendix A, Eq. (2).
+    tested = sum(min(int(x) + 1, gamma) for x in n_hist)
+    alpha_paper = 0.78
+    per_round = (1.0 - alpha_paper ** (gamma + 1)) / (1.0 - alpha_paper)
+    acceptance = {"alpha_hat": accepted / max(tested, 1), "mean_tokens_per_round": tokens / (a.steps * B),
+                  "context_only": {"alpha": alpha_paper, "expected_tokens_per_round": per_round,
+                                   "tokens_per_s_at_this_latency": B * per_round / (ms_per_step * 1e-3)}}
+
     out = {
         "metric": "verified tokens/s", "value": tokens / dt, "unit": "tokens/s", "n_gpus": 1, "steps": a.steps,
         "warmup": a.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
@@ -211,6 +224,7 @@ def main():
                                f"gamma={gamma}, T={T}, batch={B}, random-init weights" + (", temperature 0" if a.greedy else "")},
         "round_latency_us": ms_per_step * 1e3,
         "mean_accepted_per_round": accepted / (a.steps * B),
+        "acceptance": acceptance,
         "roofline": roof, "cpu_baseline": cpu, "step_skipping": skipping, "phases": phases, "kernels": kernels,
     }
     print(json.dumps(out))
