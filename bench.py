@@ -51,6 +51,53 @@ def gen_weights_logged(synth, cfg, seed, what):
     return out
 
 
+def accept_micro(torch, binding, vocab, gamma, batch):
+    """The fused accept / residual-sampling kernels alone, on synthetic rows whose agreement is controlled:
+    q = (1 - lam) p + lam noise, x_k ~ q_k.  lam = 0.15: most positions accepted (long scans of the stats pass
+    only); lam = 1: early rejections.  Returns per lam: mean accepted count, microseconds per call (HIP events
+    around 20 calls on one stream) and the algorithmic bytes behind them ((gamma + 1) V fp32 for the row
+    statistics and the tests, 4 V fp32 for the two passes over row n of p and q)."""
+    ld = binding.sd_vocab_pad(vocab)
+    rows = batch * (gamma + 1)
+    g = torch.Generator(device="cuda:0").manual_seed(7)
+    p_logits = torch.zeros(rows, ld, device="cuda:0")
+    p_logits[:, :vocab] = torch.randn(rows, vocab, device="cuda:0", generator=g) * 1.5
+    P = torch.softmax(p_logits[:, :vocab].double(), dim=1).view(batch, gamma + 1, vocab)
+    out = {}
+    for lam in (0.15, 1.0):
+        noise = torch.softmax(torch.randn(batch, gamma, vocab, device="cuda:0", generator=g).double() * 1.5, dim=2)
+        q = ((1 - lam) * P[:, :gamma] + lam * noise).float()
+        draft = torch.multinomial(q.view(-1, vocab), 1, generator=g).view(batch, gamma).int()
+        qp = torch.zeros(batch * gamma, ld, device="cuda:0")
+        qp[:, :vocab] = q.view(-1, vocab)
+        nb = binding.sd_sampling_scratch_bytes(rows, vocab)
+        scratch = torch.empty(nb, dtype=torch.uint8, device="cuda:0")
+        n = torch.zeros(batch, dtype=torch.int32, device="cuda:0")
+        tok = torch.zeros(batch, dtype=torch.int32, device="cuda:0")
+        st = torch.cuda.current_stream().cuda_stream
+        call = lambda seed: binding.lib().sd_accept_resample(p_logits.data_ptr(), qp.data_ptr(), draft.data_ptr(), batch, gamma, vocab,
+                                                             seed, n.data_ptr(), tok.data_ptr(), scratch.data_ptr(), nb, st)
+        acc = 0
+        for seed in range(3):
+            assert call(seed) == 0
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for seed in range(20):
+            assert call(100 + seed) == 0
+        e1.record()
+        torch.cuda.synchronize()
+        for seed in range(20):                                    # accepted counts (outside the timed calls)
+            call(100 + seed)
+            torch.cuda.synchronize()
+            acc += int(n.sum())
+        us = e0.elapsed_time(e1) * 1e3 / 20
+        nbytes = batch * ((gamma + 1) * vocab * 4 + 4 * vocab * 4)
+        out[f"lam={lam}"] = {"mean_accepted": acc / (20 * batch), "us_per_call": round(us, 2), "algorithmic_MB": round(nbytes / 1e6, 2),
+                             "GB_per_s": round(nbytes / us / 1e3, 1)}
+    return out
+
+
 def cpu_baseline(w, Wt, Wd, prefixes, seed):
     """The oracle as it stands, one round of sequence 0 of the same workload."""
     from threadpoolctl import threadpool_info
@@ -81,6 +128,7 @@ def main():
     ap.add_argument("--greedy", action="store_true", help="temperature 0 (sd_set_greedy) instead of the stochastic rule")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true")
+    ap.add_argument("--no-accept-micro", action="store_true", help="leave out the micro-benchmark of the accept / residual-sampling kernels")
     ap.add_argument("--no-step-skipping", action="store_true", help="leave out the extra timed pass with sd_set_step_skipping")
     ap.add_argument("--copy-probe", action="store_true", help="also launch one 64 MiB elementwise copy kernel, torch.neg (calibrates rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)")
     a = ap.parse_args()
@@ -215,6 +263,11 @@ def main():
                   "context_only": {"alpha": alpha_paper, "expected_tokens_per_round": per_round,
                                    "tokens_per_s_at_this_latency": B * per_round / (ms_per_step * 1e-3)}}
 
+    micro = None
+    if not a.no_accept_micro:
+        micro = accept_micro(torch, binding, t.vocab, gamma, B)
+        log(f"accept kernels alone: {micro}")
+
     out = {
         "metric": "verified tokens/s", "value": tokens / dt, "unit": "tokens/s", "n_gpus": 1, "steps": a.steps,
         "warmup": a.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
@@ -225,7 +278,7 @@ def main():
         "round_latency_us": ms_per_step * 1e3,
         "mean_accepted_per_round": accepted / (a.steps * B),
         "acceptance": acceptance,
-        "roofline": roof, "cpu_baseline": cpu, "step_skipping": skipping, "phases": phases, "kernels": kernels,
+        "roofline": roof, "cpu_baseline": cpu, "step_skipping": skipping, "accept_micro": micro, "phases": phases, "kernels": kernels,
     }
     print(json.dumps(out))
 
