@@ -2,8 +2,10 @@
 
   python -m paper_2408_05636_amd.profsum kernels <dir-with-*_kernel_stats.csv> "<command that produced it>"
   python -m paper_2408_05636_amd.profsum traffic <fetch-dir> <write-dir> <kernel-name-substring> <copy-bytes>
+  python -m paper_2408_05636_amd.profsum counters <dir-with-*_counter_collection.csv> "<command that produced it>"
 
-`traffic` reads the per-dispatch FETCH_SIZE / WRITE_SIZE counters (KiB) of two --pmc runs, scales
+`counters` prints, per kernel, the mean over its dispatches of every counter of one --pmc run (ten largest kernels
+by dispatch count x first counter).  `traffic` reads the per-dispatch FETCH_SIZE / WRITE_SIZE counters (KiB) of two --pmc runs, scales
 them by what the same counters report for the known-size copy kernel that `bench.py --copy-probe`
 launches (torch.neg over <copy-bytes> bytes: that many read and as many written) and prints the HBM bytes per launch of the
 chosen kernel.
@@ -62,9 +64,30 @@ def traffic(fetch_dir, write_dir, substr, copy_bytes):
     print(f"HBM bytes per launch: read {kf * 1024 * sf:.0f} + written {kw * 1024 * sw:.0f} = {total:.0f}")
 
 
+def counters(d, command):
+    rows = counter_rows(d)
+    names = sorted({r["Counter_Name"] for r in rows})
+    per = {}
+    for r in rows:
+        k = short(r["Kernel_Name"])
+        per.setdefault(k, {}).setdefault(r["Counter_Name"], []).append(float(r["Counter_Value"]))
+    print(f"# rocprofv3 --pmc counters, mean per dispatch\n# command: {command}\n")
+    print(f"{'kernel':56s} {'dispatches':>10s} " + " ".join(f"{n:>16s}" for n in names))
+    order = sorted(per, key=lambda k: -sum(per[k].get(names[0], [0.0])))
+    for k in order[:12]:
+        n_disp = max(len(v) for v in per[k].values())
+        cells = []
+        for n in names:
+            v = per[k].get(n, [])
+            cells.append(f"{sum(v) / len(v):16.4g}" if v else f"{'-':>16s}")
+        print(f"{k[:56]:56s} {n_disp:10d} " + " ".join(cells))
+
+
 if __name__ == "__main__":
     if len(sys.argv) >= 4 and sys.argv[1] == "kernels":
         kernels(sys.argv[2], sys.argv[3])
+    elif len(sys.argv) >= 4 and sys.argv[1] == "counters":
+        counters(sys.argv[2], sys.argv[3])
     elif len(sys.argv) == 6 and sys.argv[1] == "traffic":
         traffic(*sys.argv[2:6])
     else:
