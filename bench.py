@@ -180,7 +180,7 @@ def main():
 
     log(f"timed pass done: {ms_per_step:.3f} ms per round")
     # The same rounds once more with the drafter left out at the steps that reveal no slot (sd_set_step_skipping: same
-    # drafts and verdicts, fewer forwards).  Reported beside the headline value, which runs all T steps.
+    # drafts and acceptance outcomes, fewer forwards).  Reported beside the headline value, which runs all T steps.
     skipping = None
     if not a.no_step_skipping:
         sd.sd_set_step_skipping(True)
