@@ -108,8 +108,17 @@ def test_tiny_fp32_rounds_against_pure_oracle():
             continue
         n, tok, vm, fb = osd.oracle_verify(oracle_target_fn(Wt, t), prefix, z, q, seed)
         assert not fb
-        if n != n_g[0] or tok != tok_g[0]:
-            assert vm < tau or n != n_g[0], (seed, n, n_g[0], tok, tok_g[0], vm)
+        if n != n_g[0]:
+            # only an acceptance test sitting on its threshold (within reach of the logit tolerance) may differ
+            rows = np.arange(len(prefix) - 1, len(prefix) + gamma)
+            P = softmax_rows(oracle_target_fn(Wt, t)(np.concatenate([prefix, z]), rows))
+            r, _ = osd.verify_uniforms(seed, 0, gamma)
+            am = osd.accept_margins(P, q, z, r)
+            assert am[min(n, int(n_g[0]))] < 1e-3, (seed, n, n_g[0], am)
+            weak += 1
+            continue
+        if tok != tok_g[0]:
+            assert vm < tau, (seed, n, tok, tok_g[0], vm)
             weak += 1
             continue
         exact += 1

@@ -102,3 +102,40 @@ def test_stochastic_generation_bookkeeping_and_seed_schedule():
         assert n == n_ref
         seq += list(z[:n]) + [tok]
     assert np.array_equal(np.array(seq[len(prefix):]), toks)
+
+
+@pytest.mark.parametrize("T", [1, 2, 3, 5])
+def test_greedy_draft_reveals_the_slots_of_the_stochastic_draft(T):
+    """Temperature 0 changes how a revealed slot picks its token, not when it is revealed: with the same
+    uniforms, the greedy draft and the stochastic draft reveal every slot at the same step (1/j rule,
+    everything at j = 1), evaluate the drafter at the same steps, and the greedy token is the argmax of the
+    row the stochastic draft stored as q_k."""
+    rng = np.random.default_rng(100 + T)
+    V, gamma, mask = 9, 6, 9
+    table = rng.standard_normal((T + 1, gamma, V))            # time-dependent, state-independent rows ...
+    calls = {"g": [], "s": []}
+
+    def drafter(tag):
+        def f(tokens, t):
+            j = int(round(t * T))
+            block = np.asarray(tokens[-gamma:])
+            calls[tag].append((j, tuple(int(x) for x in np.flatnonzero(block == mask))))
+            return table[j] + 0.25 * (block != mask).sum()     # ... shifted by the number of revealed slots
+        return f
+
+    for trial in range(20):
+        ua = rng.random((T + 1, gamma))
+        ub = rng.random((T + 1, gamma))
+        calls["g"].clear(); calls["s"].clear()
+        zg, gaps, nfg = osd.draft_greedy_with_uniforms(drafter("g"), np.arange(4), gamma, T, ua, mask)
+        zs, q, _, nfs = osd.draft_with_uniforms(drafter("s"), np.arange(4), gamma, T, ua, ub, mask)
+        # same forwards, at the same steps, seeing the same set of still-masked slots
+        assert calls["g"] == calls["s"] and nfg == nfs
+        # reveal step of every slot by the rule itself: first j (counting down) with ua * j < 1, else 1
+        for k in range(gamma):
+            jk = next((j for j in range(T, 1, -1) if ua[j, k] * j < 1.0), 1)
+            row = table[jk][k]
+            assert zg[k] == int(np.argmax(row.astype(np.float32)))
+            # the stochastic draft stored the softmax of the very same row
+            np.testing.assert_allclose(q[k], np.exp(row - row.max()) / np.exp(row - row.max()).sum(), rtol=1e-6)
+        assert (zg != mask).all() and (zs != mask).all()

@@ -369,3 +369,59 @@ def test_oracle_verify_reads_the_right_rows_of_the_target():
     n, tok, _, _ = sd.oracle_verify(target_logits, prefix, draft, q, seed=3)
     r, u = sd.verify_uniforms(3, 0, 2)
     assert (n, tok) == sd.verify_with_uniforms(toy_target(draft), q, draft, r, u)[:2]
+
+
+# ------------------------------------------------------------------ accept_margins
+def test_accept_margins_hand_computed_cases():
+    """The margin of acceptance test k is |r_k q_k(x_k) - p_k(x_k)| / p_k(x_k) (Section 3: the test compares
+    r with p(x)/q(x)).  Hand-computed cases: an exact tie gives 0, a known ratio gives its distance from 1,
+    p(x) = 0 gives infinity, and the margin is small exactly where flipping r across p/q flips accept_flags."""
+    P = np.array([[0.5, 0.5, 0.0], [0.2, 0.3, 0.5], [0.0, 1.0, 0.0], [0.25, 0.25, 0.5]])
+    q = np.array([[0.25, 0.75, 0.0], [0.4, 0.4, 0.2], [0.5, 0.5, 0.0], [0.5, 0.25, 0.25]])
+    draft = np.array([0, 0, 0, 0])
+    r = np.array([0.5, 0.5, 0.3, 0.75])
+    m = sd.accept_margins(P, q, draft, r)
+    # k = 0: r q = 0.125 vs p = 0.5 -> |0.125 - 0.5| / 0.5 = 0.75
+    # k = 1: r q = 0.2 vs p = 0.2 -> exact tie (0.5 * 0.4 is exact in binary up to the rounding of 0.4 and 0.2)
+    # k = 2: p(x) = 0 -> inf (always rejected, never close)
+    # k = 3: r q = 0.375 vs p = 0.25 -> 0.5
+    assert m[0] == pytest.approx(0.75, abs=1e-15)
+    assert m[1] < 1e-15
+    assert np.isinf(m[2])
+    assert m[3] == pytest.approx(0.5, abs=1e-15)
+    # only x_k's entries matter: other columns may change freely
+    P2, q2 = P.copy(), q.copy()
+    P2[:, 1:] += 0.125
+    q2[:, 1:] *= 0.5
+    np.testing.assert_array_equal(sd.accept_margins(P2, q2, draft, r), m)
+    # the draft index is honoured (not always column 0)
+    m1 = sd.accept_margins(P, q, np.array([1, 2, 1, 2]), r)
+    assert m1[0] == pytest.approx(abs(0.5 * 0.75 - 0.5) / 0.5) and m1[1] == pytest.approx(abs(0.5 * 0.2 - 0.5) / 0.5)
+    assert m1[2] == pytest.approx(abs(0.3 * 0.5 - 1.0)) and m1[3] == pytest.approx(abs(0.75 * 0.25 - 0.5) / 0.5)
+
+
+def test_accept_margin_is_small_exactly_where_the_flag_can_flip():
+    """Sweep r across the threshold p/q: accept_flags changes sign where the margin passes through 0, and a
+    relative perturbation of p(x) smaller than the margin never changes the flag."""
+    rng = np.random.default_rng(5)
+    for _ in range(200):
+        V = 6
+        p = rng.dirichlet(np.ones(V))
+        q = rng.dirichlet(np.ones(V))
+        x = int(rng.integers(V))
+        r = float(rng.random())
+        P, Q, d, rr = p[None], q[None], np.array([x]), np.array([r])
+        m = sd.accept_margins(P, Q, d, rr)[0]
+        flag = sd.accept_flags(P, Q, d, rr)[0]
+        assert flag == (r * q[x] <= p[x]) or m < 1e-6          # the flag is the fp32 form of the same comparison
+        for eps in (0.5 * m, -0.5 * m):                        # p(x) moved by less than the margin: same decision
+            if m < 1e-5:
+                continue
+            P2 = P.copy()
+            P2[0, x] *= 1.0 + eps
+            assert sd.accept_flags(P2, Q, d, rr)[0] == flag
+        if np.isfinite(m):                                     # moved past the margin: the decision flips
+            P3 = P.copy()
+            P3[0, x] *= (1.0 + 2.0 * m + 1e-3) if not flag else max(0.0, 1.0 - 2.0 * m - 1e-3)
+            if P3[0, x] > 0:
+                assert sd.accept_flags(P3, Q, d, rr)[0] != flag
