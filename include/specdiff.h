@@ -100,7 +100,8 @@ int32_t sd_prefill(sd_handle *h, int32_t batch, const int32_t *prefix, const int
  * drawn by inverse CDF from that step's softmax row, which becomes q_k.
  *   draft_out: host [batch, gamma]; qtok_out: host [batch, gamma] = q_k(x_k), may be NULL;
  *   q_dev_out: receives a device pointer to q, fp32 [batch, gamma, ld], library-owned,
- *   valid until the next sd_draft / sd_round on this handle. */
+ *   valid until the next sd_draft / sd_round on this handle (NULL at temperature 0, which
+ *   produces no q). */
 int32_t sd_draft(sd_handle *h, int32_t batch, const int32_t *prefix, const int32_t *prefix_len,
                  int32_t gamma, int32_t T, uint64_t seed, int32_t *draft_out, float *qtok_out,
                  const float **q_dev_out);
@@ -133,8 +134,8 @@ int32_t sd_commit(sd_handle *h, int32_t batch, const int32_t *n_accepted);
  * enable != 0: a slot revealed by the drafter takes the argmax of its row (reveal schedule unchanged;
  * no q is produced, qtok = 1), a drafted token is accepted iff it is the argmax of the target's row,
  * and the extra token is the argmax of row n; seeds only drive the reveal schedule.  Arg-maxima are taken
- * on the fp32 logits, lowest id on ties.  Applies to sd_draft, sd_verify (its q_dev is ignored but must
- * be non-NULL) and sd_round of this handle until switched off. */
+ * on the fp32 logits, lowest id on ties.  Applies to sd_draft, sd_verify (its q_dev is ignored and may be
+ * NULL) and sd_round of this handle until switched off. */
 int32_t sd_set_greedy(sd_handle *h, int32_t enable);
 
 /* Leaving out drafting steps that reveal nothing (in the spirit of the cached sampling strategy that the appendix's
@@ -224,7 +225,8 @@ int32_t sd_linear_resid_norm(const void *x, const void *w, const float *bias, fl
  * 10-13: 64 x 64, 64 x 128, 128 x 128, 256 x 128 tiles fed straight from global memory into a ring of LDS stages, 14, 15: the
  * first two with two 64-wide chunks of K per stage -- the choice by shape when K is shorter than the ring or no multiple of
  * the stage width; see the kernel sources; other values are rejected at the next contraction), -1 = choose by shape (default).
- * Process-wide; results do not depend on the variant beyond fp32 summation order. */
+ * Process-wide (captured launch sequences are keyed by it, so a change takes effect at the next call); results do not
+ * depend on the variant beyond fp32 summation order. */
 int32_t sd_set_linear_variant(int32_t variant);
 /* Same for the number of workgroups that share the K range of one output tile (clamped to what the
  * shape and the workspace allow); <= 0 = choose by shape (default). */
@@ -236,6 +238,14 @@ int32_t sd_set_linear_split(int32_t split);
  * and captured the second time.)  enable = 0 turns replay off (it is also off while
  * profiling and when the handle runs on the NULL stream). */
 int32_t sd_set_graph_replay(sd_handle *h, int32_t enable);
+/* What became of the launch sequences of this handle since creation: replays = sequences sent as a graph replay;
+ * failures = captures or instantiations that failed (the first failure switches replay off for the handle: results
+ * stay correct, every sequence is launched eagerly from then on); eager_after_failure = sequences launched eagerly
+ * because of that; captured = graphs currently held.  Any pointer may be NULL.  sd_graph_error: library-owned text
+ * naming the call that failed ("" if none).  A caller that times rounds checks failures == 0. */
+int32_t sd_graph_stats(const sd_handle *h, int64_t *replays, int64_t *eager_after_failure, int32_t *failures,
+                       int32_t *captured);
+const char *sd_graph_error(const sd_handle *h);
 
 /* ---- per-kernel timing ----------------------------------------------------------------------
  * Between sd_profile_begin and sd_profile_end every kernel launch of the handle is bracketed by

@@ -24,7 +24,8 @@ EXPORTS = ["sd_vocab_pad", "sd_weight_count", "sd_weight_desc", "sd_weight_bytes
            "sd_destroy", "sd_last_error", "sd_prefill", "sd_draft", "sd_verify", "sd_round", "sd_drafter_logits",
            "sd_target_logits", "sd_sampling_scratch_bytes", "sd_unmask_sample", "sd_accept_resample", "sd_linear",
            "sd_profile_begin", "sd_profile_end", "sd_profile_count", "sd_profile_entry", "sd_set_graph_replay", "sd_set_linear_variant", "sd_norm_linear",
-           "sd_set_linear_split", "sd_linear_split_ticket_bytes", "sd_commit", "sd_set_greedy", "sd_set_step_skipping", "sd_steps_run", "sd_norm_linear_scratch_floats", "sd_linear_resid_norm"]
+           "sd_set_linear_split", "sd_linear_split_ticket_bytes", "sd_commit", "sd_set_greedy", "sd_set_step_skipping", "sd_steps_run", "sd_norm_linear_scratch_floats", "sd_linear_resid_norm",
+           "sd_graph_stats", "sd_graph_error"]
 
 
 class SdModelConfig(C.Structure):
@@ -88,6 +89,9 @@ def lib() -> C.CDLL:
         L.sd_linear_split_ticket_bytes.restype = i64; L.sd_linear_split_ticket_bytes.argtypes = []
         L.sd_set_graph_replay.restype = i32; L.sd_set_graph_replay.argtypes = [vp, i32]
         L.sd_set_linear_variant.restype = i32; L.sd_set_linear_variant.argtypes = [i32]
+        L.sd_graph_stats.restype = i32
+        L.sd_graph_stats.argtypes = [vp, C.POINTER(i64), C.POINTER(i64), C.POINTER(i32), C.POINTER(i32)]
+        L.sd_graph_error.restype = C.c_char_p; L.sd_graph_error.argtypes = [vp]
         L.sd_norm_linear.restype = i32
         L.sd_norm_linear.argtypes = [i32, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, C.c_float, vp, vp, i64, vp]
         L.sd_profile_begin.restype = i32; L.sd_profile_begin.argtypes = [vp]
@@ -210,6 +214,13 @@ class SpecDiff:
     def sd_set_graph_replay(self, enable: bool):
         self._check(lib().sd_set_graph_replay(self.h, int(enable)), "sd_set_graph_replay")
 
+    def sd_graph_stats(self):
+        """-> dict(replays, eager_after_failure, failures, captured, error)."""
+        r, e, f, c = C.c_int64(), C.c_int64(), C.c_int32(), C.c_int32()
+        self._check(lib().sd_graph_stats(self.h, C.byref(r), C.byref(e), C.byref(f), C.byref(c)), "sd_graph_stats")
+        return dict(replays=r.value, eager_after_failure=e.value, failures=f.value, captured=c.value,
+                    error=lib().sd_graph_error(self.h).decode())
+
     def sd_profile_begin(self):
         self._check(lib().sd_profile_begin(self.h), "sd_profile_begin")
 
@@ -238,7 +249,7 @@ class SpecDiff:
         qp = C.c_void_p()
         self._check(lib().sd_draft(self.h, B, _ip(flat), _ip(lens), gamma, T, seed, _ip(draft),
                                    qtok.ctypes.data_as(C.POINTER(C.c_float)), C.byref(qp)), "sd_draft")
-        return draft, qtok, self._view(qp.value, B * gamma)
+        return draft, qtok, (self._view(qp.value, B * gamma) if qp.value else None)      # no q at temperature 0
 
     def sd_verify(self, prefixes, draft: np.ndarray, q_dev, seed: int):
         """-> (n_accepted int32 [B], token int32 [B])."""
@@ -247,8 +258,8 @@ class SpecDiff:
         draft = np.ascontiguousarray(draft, dtype=np.int32).reshape(B, -1)
         n = np.zeros(B, dtype=np.int32)
         tok = np.zeros(B, dtype=np.int32)
-        self._check(lib().sd_verify(self.h, B, _ip(flat), _ip(lens), draft.shape[1], _ip(draft), q_dev.data_ptr(), seed,
-                                    _ip(n), _ip(tok)), "sd_verify")
+        self._check(lib().sd_verify(self.h, B, _ip(flat), _ip(lens), draft.shape[1], _ip(draft),
+                                    q_dev.data_ptr() if q_dev is not None else None, seed, _ip(n), _ip(tok)), "sd_verify")
         return n, tok
 
     def sd_round(self, prefixes, gamma: int, T: int, seed: int):

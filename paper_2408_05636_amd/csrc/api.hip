@@ -302,6 +302,10 @@ struct sd_handle {
     std::unordered_map<uint64_t, hipGraphExec_t> graphs;
     std::unordered_set<uint64_t> seen;   // launch sequences run once so far (captured on their second use)
     bool use_graphs = true;
+    int64_t graph_replays = 0;           // launch sequences sent as a graph replay since creation
+    int64_t graph_eager = 0;             // launch sequences that ran as eager launches although replay was wanted (first sight of a key excluded)
+    int graph_failures = 0;              // captures or instantiations that failed (replay is switched off after the first)
+    std::string graph_error;             // what failed
     bool greedy = false;                 // temperature 0 instead of the stochastic rule
     bool skip_idle_steps = false;        // leave out the drafter forwards of steps that reveal no slot (sd_set_step_skipping)
     int steps_run = 0;                   // drafter forwards of the last sd_draft / sd_round
@@ -581,7 +585,18 @@ int upload_rows(sd_handle* h, int mode, int batch, const int32_t* tokens, const 
 // runs on the legacy default stream, or when capture is not possible.
 template <typename F>
 int replay(sd_handle* h, uint64_t key, F&& enqueue) {
-    if (!h->use_graphs || h->prof.on || h->st == nullptr) return enqueue();
+    if (!h->use_graphs || h->prof.on || h->st == nullptr) {
+        if (h->graph_failures > 0) ++h->graph_eager;
+        return enqueue();
+    }
+    // A failed capture switches replay off for the handle (results stay correct, launches run eagerly); the
+    // failure is kept in graph_error / sd_graph_stats so that a caller who times rounds can see it.
+    auto give_up = [&](const char* what, hipError_t e) {
+        h->use_graphs = false;
+        ++h->graph_failures;
+        h->graph_error = std::string(what) + ": " + hipGetErrorString(e);
+        (void)hipGetLastError();
+    };
     auto it = h->graphs.find(key);
     if (it == h->graphs.end()) {
         if (h->seen.insert(key).second) {
@@ -592,9 +607,10 @@ int replay(sd_handle* h, uint64_t key, F&& enqueue) {
             for (auto& g : h->graphs) (void)hipGraphExecDestroy(g.second);
             h->graphs.clear();
         }
-        if (hipStreamBeginCapture(h->st, hipStreamCaptureModeThreadLocal) != hipSuccess) {
-            (void)hipGetLastError();
-            h->use_graphs = false;
+        const hipError_t e0 = hipStreamBeginCapture(h->st, hipStreamCaptureModeThreadLocal);
+        if (e0 != hipSuccess) {
+            give_up("hipStreamBeginCapture", e0);
+            ++h->graph_eager;
             return enqueue();
         }
         const int rc = enqueue();
@@ -602,21 +618,23 @@ int replay(sd_handle* h, uint64_t key, F&& enqueue) {
         const hipError_t e1 = hipStreamEndCapture(h->st, &graph);
         if (rc != SD_OK || e1 != hipSuccess || graph == nullptr) {
             if (graph) (void)hipGraphDestroy(graph);
-            (void)hipGetLastError();
-            h->use_graphs = false;
-            return rc != SD_OK ? rc : enqueue();
+            give_up(rc != SD_OK ? "launch sequence failed under capture" : "hipStreamEndCapture", e1);
+            if (rc != SD_OK) return rc;
+            ++h->graph_eager;
+            return enqueue();
         }
         hipGraphExec_t exec = nullptr;
         const hipError_t e2 = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
         (void)hipGraphDestroy(graph);
         if (e2 != hipSuccess || exec == nullptr) {
-            (void)hipGetLastError();
-            h->use_graphs = false;
+            give_up("hipGraphInstantiate", e2);
+            ++h->graph_eager;
             return enqueue();
         }
         it = h->graphs.emplace(key, exec).first;
     }
     SD_HIP(h, hipGraphLaunch(it->second, h->st));
+    ++h->graph_replays;
     return SD_OK;
 }
 
@@ -624,6 +642,7 @@ uint64_t shape_key(int call, int batch, int gamma, int T, const int32_t* len, co
     uint64_t x = 1469598103934665603ull;
     auto mix = [&](uint64_t v) { x ^= v; x *= 1099511628211ull; };
     mix((uint64_t)call); mix((uint64_t)batch); mix((uint64_t)gamma); mix((uint64_t)T); mix((uint64_t)(uintptr_t)ptr);
+    mix((uint64_t)(uint32_t)linear_mfma_get_variant()); mix((uint64_t)(uint32_t)linear_mfma_get_split());   // process-wide tuning hooks shape the launches too
     for (int b = 0; b < batch; ++b) mix((uint64_t)(uint32_t)len[b]);
     return x;
 }
@@ -1128,7 +1147,7 @@ int32_t sd_draft(sd_handle* h, int32_t batch, const int32_t* prefix, const int32
     { const int rc_ = sync_stream(h); if (rc_) return rc_; }
     memcpy(draft_out, h->stage_out, cnt * 4);
     if (qtok_out) memcpy(qtok_out, h->stage_f, cnt * 4);
-    if (q_dev_out) *q_dev_out = h->buf.q;
+    if (q_dev_out) *q_dev_out = h->greedy ? nullptr : h->buf.q;      // temperature 0 produces no q
     return SD_OK;
 }
 
@@ -1138,7 +1157,7 @@ int32_t sd_verify(sd_handle* h, int32_t batch, const int32_t* prefix, const int3
     int64_t n;
     int rc = check_batch(h, batch, prefix, prefix_len, h ? h->target.c.vocab : 0, &n);
     if (rc) return rc;
-    if (!draft || !q_dev || !n_accepted_out || !token_out) return fail(h, SD_ERR_ARG, "null argument");
+    if (!draft || (!q_dev && !h->greedy) || !n_accepted_out || !token_out) return fail(h, SD_ERR_ARG, "null argument");
     rc = check_round_shapes(h, batch, prefix_len, gamma);
     if (rc) return rc;
     const int64_t cnt = (int64_t)batch * gamma;
@@ -1305,6 +1324,18 @@ int32_t sd_set_graph_replay(sd_handle* h, int32_t enable) {
     h->use_graphs = enable != 0;
     return SD_OK;
 }
+
+int32_t sd_graph_stats(const sd_handle* h, int64_t* replays, int64_t* eager_after_failure, int32_t* failures,
+                       int32_t* captured) {
+    if (!h) return SD_ERR_ARG;
+    if (replays) *replays = h->graph_replays;
+    if (eager_after_failure) *eager_after_failure = h->graph_eager;
+    if (failures) *failures = h->graph_failures;
+    if (captured) *captured = (int32_t)h->graphs.size();
+    return SD_OK;
+}
+
+const char* sd_graph_error(const sd_handle* h) { return h ? h->graph_error.c_str() : ""; }
 
 int32_t sd_profile_begin(sd_handle* h) {
     if (!h) return SD_ERR_ARG;

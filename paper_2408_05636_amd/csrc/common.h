@@ -132,6 +132,8 @@ struct SplitWorkspace {
 bool linear_mfma_supported(int dtype, int m, int n, int k, int ldy);
 void linear_mfma_set_variant(int v);     // tuning hook: force a tile variant (-1 = choose by shape)
 void linear_mfma_set_split(int s);       // tuning hook: force the K split over workgroups (<= 0 = choose by shape)
+int linear_mfma_get_variant();
+int linear_mfma_get_split();
 hipError_t launch_fold_norm(const void* w, const float* gain, const float* beta, const float* bias, float* u, float* v,
                             int n, int k, hipStream_t st);
 hipError_t launch_linear_mfma(const void* x, const void* w, const float* bias, void* y, int m, int n, int k, int ldy,

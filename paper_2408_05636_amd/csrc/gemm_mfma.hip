@@ -337,12 +337,16 @@ __global__ __launch_bounds__(256, (MT * NT == 1 ? 3 : 1)) void k_linear_mfma(con
 #pragma unroll
                     for (int e = 0; e < 16; ++e)
                         __hip_atomic_store(&mine[((i * NT + j) * 16 + e) * 64 + lane], acc[i][j][e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                // Release: every lane's partial stores are complete and visible device-wide before the ticket is drawn
+            // (the fence states it for the memory model, the explicit wait keeps the stores of all 64 lanes behind it).
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
             unsigned int old = 0;
             if (lane == 0) old = __hip_atomic_fetch_add(&sk.ticket[tile_id], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             old = __builtin_amdgcn_readfirstlane(old);
             if (old != (unsigned int)sk.gsplit - 1u) return;
             if (lane == 0) __hip_atomic_store(&sk.ticket[tile_id], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");     // the last arrival reads what the others released
 #pragma unroll
             for (int i = 0; i < MT; ++i)
 #pragma unroll
@@ -451,6 +455,8 @@ __global__ __launch_bounds__(256, (MT * NT == 1 ? 3 : 1)) void k_linear_mfma(con
 static int g_variant_override = -1, g_split_override = -1;
 void linear_mfma_set_variant(int v) { g_variant_override = v; }
 void linear_mfma_set_split(int s) { g_split_override = s; }
+int linear_mfma_get_variant() { return g_variant_override; }
+int linear_mfma_get_split() { return g_split_override; }
 
 template <int MT, int NT, int WM, int WN, int KS, int PD>
 static hipError_t launch_variant(const void* x, const void* w, const float* bias, void* y, int m, int n, int k,
