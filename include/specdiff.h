@@ -248,12 +248,14 @@ int32_t sd_graph_stats(const sd_handle *h, int64_t *replays, int64_t *eager_afte
 const char *sd_graph_error(const sd_handle *h);
 
 /* ---- per-kernel timing ----------------------------------------------------------------------
- * Between sd_profile_begin and sd_profile_end every kernel launch of the handle is bracketed by
- * HIP events on its stream; entries accumulate, per part of the round and kernel name ("draft:", "verify:"
- * or "accept:" followed by the name; the bare name for launches outside a round), the launch count, the summed
- * elapsed milliseconds and the summed algorithmic bytes and flops of those launches (operands
- * read once, results written once).  The events cost a few microseconds per launch: time a
- * round without profiling.  name: caller buffer of name_cap bytes. */
+ * Between sd_profile_begin and sd_profile_end every kernel of the handle is launched with a pair of HIP events on
+ * its stream that receive the kernel's own start and end of execution (hipExtLaunchKernelGGL), and launch
+ * sequences run eagerly instead of as graph replays; entries accumulate, per part of the round and kernel name
+ * ("draft:", "verify:" or "accept:" followed by the name; the bare name for launches outside a round), the launch
+ * count, the summed kernel milliseconds (gaps between kernels are not in them) and the summed algorithmic bytes
+ * and flops of those launches (operands read once, results written once).  The eager launches are slower than
+ * a replay: time a round without profiling.  One handle of the process profiles at a time.
+ * name: caller buffer of name_cap bytes. */
 int32_t sd_profile_begin(sd_handle *h);
 int32_t sd_profile_end(sd_handle *h);
 int32_t sd_profile_count(const sd_handle *h);

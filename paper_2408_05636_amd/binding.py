@@ -138,10 +138,12 @@ def sd_workspace_bytes(target: ModelConfig, drafter: ModelConfig, max_batch: int
     return lib().sd_workspace_bytes(C.byref(ct), C.byref(cd), max_batch, gamma_max)
 
 
-def pack_weights(cfg: ModelConfig, weights: Dict[str, np.ndarray]) -> np.ndarray:
+def pack_weights(cfg: ModelConfig, weights: Dict[str, np.ndarray], threads: int = 8) -> np.ndarray:
     """Host image (uint8) of the flat weight buffer in the library's layout."""
     buf = np.zeros(sd_weight_bytes(cfg), dtype=np.uint8)
-    for name, rows, cols, eb, off in sd_weight_layout(cfg):
+
+    def put(entry):
+        name, rows, cols, eb, off = entry
         w = np.ascontiguousarray(weights[name], dtype=np.float32).reshape(rows, cols)
         if eb == 4:
             raw = w.view(np.uint8).reshape(-1)
@@ -150,6 +152,15 @@ def pack_weights(cfg: ModelConfig, weights: Dict[str, np.ndarray]) -> np.ndarray
             assert not (bits & 0xFFFF).any(), f"{name}: value not representable in bf16"
             raw = (bits >> 16).astype(np.uint16).view(np.uint8).reshape(-1)
         buf[off:off + raw.size] = raw
+
+    layout = sd_weight_layout(cfg)
+    if threads <= 1 or len(layout) < 8:
+        for e in layout:
+            put(e)
+    else:
+        from concurrent.futures import ThreadPoolExecutor
+        with ThreadPoolExecutor(max_workers=threads) as ex:
+            list(ex.map(put, layout))
     return buf
 
 
@@ -167,15 +178,22 @@ class SpecDiff:
     """Owns the device buffers (through torch) and a library handle."""
 
     def __init__(self, target: ModelConfig, drafter: ModelConfig, target_w: Dict[str, np.ndarray],
-                 drafter_w: Dict[str, np.ndarray], max_batch: int = 1, gamma_max: int = 64, device: str = "cuda:0"):
+                 drafter_w: Dict[str, np.ndarray], max_batch: int = 1, gamma_max: int = 64, device: str = "cuda:0",
+                 device_weights=None):
+        """target_w / drafter_w: host tensors by name (packed and uploaded here), or -- device_weights = (target buffer,
+        drafter buffer), uint8 device tensors already in the library's layout (pack_weights) -- None."""
         import torch
         self.torch = torch
         self.target, self.drafter = target, drafter
         self.max_batch, self.gamma_max = max_batch, gamma_max
         self.device = torch.device(device)
         self.ld = sd_vocab_pad(target.vocab)
-        self.tw = torch.from_numpy(pack_weights(target, target_w)).to(self.device)
-        self.dw = torch.from_numpy(pack_weights(drafter, drafter_w)).to(self.device)
+        if device_weights is not None:
+            self.tw, self.dw = device_weights
+            assert self.tw.numel() == sd_weight_bytes(target) and self.dw.numel() == sd_weight_bytes(drafter)
+        else:
+            self.tw = torch.from_numpy(pack_weights(target, target_w)).to(self.device)
+            self.dw = torch.from_numpy(pack_weights(drafter, drafter_w)).to(self.device)
         nbytes = sd_workspace_bytes(target, drafter, max_batch, gamma_max)
         if nbytes <= 0:
             raise SdError(1, "sd_workspace_bytes", "configuration rejected")

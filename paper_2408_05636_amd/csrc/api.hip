@@ -13,6 +13,11 @@
 
 using namespace sd;
 
+namespace sd {
+launch_hook_t g_launch_hook = nullptr;
+void* g_launch_hook_ctx = nullptr;
+}  // namespace sd
+
 namespace {
 
 constexpr int kMaxSteps = 256;   // upper limit of T
@@ -275,6 +280,7 @@ struct Profiler {
     bool on = false;
     std::vector<hipEvent_t> events;      // pairs (start, stop)
     size_t used = 0;
+    size_t scope_first = 0;              // first event of the SD_LAUNCH scope that is open
     std::vector<int> pending;            // entry index per used pair
     std::vector<ProfEntry> entries;
     const char* phase = "";              // prefix of the entry names: which part of the round is being enqueued
@@ -331,23 +337,34 @@ namespace {
         }                                                                                         \
     } while (0)
 
-void prof_start(sd_handle* h) {
+// One SD_LAUNCH scope = one entry of the profile (a launcher may start several kernels: their times add up).
+void prof_hook(void* ctx, hipEvent_t* start, hipEvent_t* stop) {
+    sd_handle* h = static_cast<sd_handle*>(ctx);
     Profiler& p = h->prof;
-    if (!p.on) return;
     if (p.used + 2 > p.events.size()) {
         for (int i = 0; i < 2; ++i) {
-            hipEvent_t e;
-            if (hipEventCreate(&e) != hipSuccess) { p.on = false; return; }
+            hipEvent_t e = nullptr;
+            if (hipEventCreate(&e) != hipSuccess) { *start = *stop = nullptr; return; }
             p.events.push_back(e);
         }
     }
-    (void)hipEventRecord(p.events[p.used], h->st);
+    *start = p.events[p.used];
+    *stop = p.events[p.used + 1];
+    p.used += 2;
+}
+
+void prof_start(sd_handle* h) {
+    Profiler& p = h->prof;
+    if (!p.on) return;
+    p.scope_first = p.used;
+    sd::g_launch_hook_ctx = h;
+    sd::g_launch_hook = prof_hook;
 }
 
 void prof_stop(sd_handle* h, const char* name, double bytes, double flops) {
     Profiler& p = h->prof;
     if (!p.on) return;
-    (void)hipEventRecord(p.events[p.used + 1], h->st);
+    sd::g_launch_hook = nullptr;
     const std::string key = std::string(p.phase) + name;
     int idx = -1;
     for (size_t i = 0; i < p.entries.size(); ++i)
@@ -356,11 +373,10 @@ void prof_stop(sd_handle* h, const char* name, double bytes, double flops) {
     p.entries[idx].launches += 1;
     p.entries[idx].bytes += bytes;
     p.entries[idx].flops += flops;
-    p.pending.push_back(idx);
-    p.used += 2;
+    for (size_t e = p.scope_first; e < p.used; e += 2) p.pending.push_back(idx);
 }
 
-// After a stream synchronisation: fold the elapsed times of the recorded pairs into the entries.
+// After a stream synchronisation: fold the kernel times of the recorded pairs into the entries.
 void prof_flush(sd_handle* h) {
     Profiler& p = h->prof;
     for (size_t i = 0; i < p.pending.size(); ++i) {
@@ -371,7 +387,7 @@ void prof_flush(sd_handle* h) {
     p.used = 0;
 }
 
-// Launch with optional event bracketing.  NAME may be assigned by the launcher (kernel variant).
+// Launch with optional per-kernel timing.  NAME may be assigned by the launcher (kernel variant).
 #define SD_LAUNCH(h, NAME, BYTES, FLOPS, expr)                                                    \
     do {                                                                                          \
         prof_start(h);                                                                            \

@@ -438,18 +438,18 @@ bool attention_mfma_supported(int dtype, const AttnArgs& a) {
 hipError_t launch_attention_mfma(const AttnArgs& a, hipStream_t st, const char** kernel_name) {
     // several query tiles per sequence: share the key / value blocks among up to four of them
     if (a.groups != nullptr && a.n_groups > 0 && a.group_tiles >= 2 && (long)a.n_tiles * a.n_head >= 1024 && a.max_kv > 64) {
-        if (a.d_head == 64) { if (kernel_name) *kernel_name = "k_attention_group<64>"; k_attention_group<64><<<a.n_groups, 256, 0, st>>>(a); }
-        else { if (kernel_name) *kernel_name = "k_attention_group<128>"; k_attention_group<128><<<a.n_groups, 256, 0, st>>>(a); }
+        if (a.d_head == 64) { if (kernel_name) *kernel_name = "k_attention_group<64>"; launch_kernel(k_attention_group<64>, dim3(a.n_groups), dim3(256), 0, st, a); }
+        else { if (kernel_name) *kernel_name = "k_attention_group<128>"; launch_kernel(k_attention_group<128>, dim3(a.n_groups), dim3(256), 0, st, a); }
         return hipGetLastError();
     }
     const bool ksplit = (long)a.n_tiles * a.n_head < 1024 && a.max_kv > 64;   // few tiles: the four waves share the key range of one tile
     const dim3 grid = ksplit ? (a.order ? dim3(a.n_order, 1) : dim3(a.n_tiles, a.n_head)) : dim3((a.n_tiles + 3) / 4, a.n_head);
     if (a.d_head == 64) {
-        if (ksplit) { if (kernel_name) *kernel_name = "k_attention_mfma<64,true>"; k_attention_mfma<64, true><<<grid, 256, 0, st>>>(a); }
-        else { if (kernel_name) *kernel_name = "k_attention_mfma<64,false>"; k_attention_mfma<64, false><<<grid, 256, 0, st>>>(a); }
+        if (ksplit) { if (kernel_name) *kernel_name = "k_attention_mfma<64,true>"; launch_kernel(k_attention_mfma<64, true>, dim3(grid), dim3(256), 0, st, a); }
+        else { if (kernel_name) *kernel_name = "k_attention_mfma<64,false>"; launch_kernel(k_attention_mfma<64, false>, dim3(grid), dim3(256), 0, st, a); }
     } else {
-        if (ksplit) { if (kernel_name) *kernel_name = "k_attention_mfma<128,true>"; k_attention_mfma<128, true><<<grid, 256, 0, st>>>(a); }
-        else { if (kernel_name) *kernel_name = "k_attention_mfma<128,false>"; k_attention_mfma<128, false><<<grid, 256, 0, st>>>(a); }
+        if (ksplit) { if (kernel_name) *kernel_name = "k_attention_mfma<128,true>"; launch_kernel(k_attention_mfma<128, true>, dim3(grid), dim3(256), 0, st, a); }
+        else { if (kernel_name) *kernel_name = "k_attention_mfma<128,false>"; launch_kernel(k_attention_mfma<128, false>, dim3(grid), dim3(256), 0, st, a); }
     }
     return hipGetLastError();
 }

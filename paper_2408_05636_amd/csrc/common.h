@@ -3,6 +3,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include "../../include/specdiff.h"
@@ -45,6 +46,27 @@ struct NormOut {             // producer (residual epilogue): what to prepare fo
     void* y2 = nullptr;
     int c1 = 0, c2 = 0, ld12 = 0;
 };
+
+// Every kernel of the library is launched through launch_kernel().  Ordinarily that is a plain launch.  While a
+// handle's per-kernel timing is on (sd_profile_begin), g_launch_hook hands out a pair of HIP events per launch and the
+// launch goes through hipExtLaunchKernelGGL, which stamps them with the kernel's own start and end of execution (what
+// a profiler's kernel trace shows): events recorded around a launch would also count the gap in front of it.
+// The hook is process-wide: one handle profiles at a time.
+typedef void (*launch_hook_t)(void* ctx, hipEvent_t* start, hipEvent_t* stop);
+extern launch_hook_t g_launch_hook;
+extern void* g_launch_hook_ctx;
+
+template <typename... KArgs, typename... Args>
+inline void launch_kernel(void (*kernel)(KArgs...), const dim3& grid, const dim3& block, size_t lds_bytes, hipStream_t st,
+                          Args&&... args) {
+    if (g_launch_hook != nullptr) {
+        hipEvent_t e0 = nullptr, e1 = nullptr;
+        g_launch_hook(g_launch_hook_ctx, &e0, &e1);
+        hipExtLaunchKernelGGL(kernel, grid, block, (uint32_t)lds_bytes, st, e0, e1, 0u, static_cast<KArgs>(args)...);
+    } else {
+        kernel<<<grid, block, lds_bytes, st>>>(static_cast<KArgs>(args)...);
+    }
+}
 
 // ---- launchers (all asynchronous on `st`; return hipGetLastError()) ------------------------
 

@@ -292,7 +292,7 @@ hipError_t launch_embed(int dtype, const int32_t* src, const int32_t* pos, const
                         int rows, int d, const float* gain, void* xg, float* stats, hipStream_t st) {
     if (rows <= 0) return hipSuccess;
     if (d % 4) return hipErrorInvalidValue;
-    SD_DISPATCH(dtype, (k_embed<T><<<(rows + 3) / 4, 256, 0, st>>>(src, pos, prefix, block, (const T*)wte, (const T*)wpe, temb, h,
+    SD_DISPATCH(dtype, (launch_kernel(k_embed<T>, dim3((rows + 3) / 4), dim3(256), 0, st, src, pos, prefix, block, (const T*)wte, (const T*)wpe, temb, h,
                                                                  rows, d, gain, (bf16_t*)xg, stats)));
     return hipGetLastError();
 }
@@ -300,7 +300,7 @@ hipError_t launch_embed(int dtype, const int32_t* src, const int32_t* pos, const
 hipError_t launch_norm_prep(const float* h, const float* gain, void* xg, float* stats, int rows, int d, hipStream_t st) {
     if (rows <= 0) return hipSuccess;
     if (d % 4) return hipErrorInvalidValue;
-    k_norm_prep<<<(rows + 3) / 4, 256, 0, st>>>(h, gain, (bf16_t*)xg, stats, rows, d);
+    launch_kernel(k_norm_prep, dim3((rows + 3) / 4), dim3(256), 0, st, h, gain, (bf16_t*)xg, stats, rows, d);
     return hipGetLastError();
 }
 
@@ -308,9 +308,9 @@ hipError_t launch_timestep_embed(int dtype, const void* w1, const float* b1, con
                                  float* hidden, float* temb, int T_steps, int d, hipStream_t st) {
     if (d % 4 || d > 64 * 4 * kMatvecMax) return hipErrorInvalidValue;
     const int n_sin = T_steps * (d / 2);
-    k_timestep_sinusoid<<<(n_sin + 255) / 256, 256, 0, st>>>(temb, T_steps, d);               // temb doubles as the sinusoid table
-    SD_DISPATCH(dtype, (k_timestep_matvec<T, true><<<(d + 3) / 4, 256, 0, st>>>((const T*)w1, b1, temb, hidden, T_steps, d)));
-    SD_DISPATCH(dtype, (k_timestep_matvec<T, false><<<(d + 3) / 4, 256, 0, st>>>((const T*)w2, b2, hidden, temb, T_steps, d)));
+    launch_kernel(k_timestep_sinusoid, dim3((n_sin + 255) / 256), dim3(256), 0, st, temb, T_steps, d);               // temb doubles as the sinusoid table
+    SD_DISPATCH(dtype, (launch_kernel(k_timestep_matvec<T, true>, dim3((d + 3) / 4), dim3(256), 0, st, (const T*)w1, b1, temb, hidden, T_steps, d)));
+    SD_DISPATCH(dtype, (launch_kernel(k_timestep_matvec<T, false>, dim3((d + 3) / 4), dim3(256), 0, st, (const T*)w2, b2, hidden, temb, T_steps, d)));
     return hipGetLastError();
 }
 
@@ -320,10 +320,10 @@ hipError_t launch_norm(int dtype, const float* h, const int32_t* idx, const floa
     if (d % 4 || d > 64 * 4 * kNormPieces) return hipErrorInvalidValue;
     const int pieces = (d / 4 + 63) / 64, grid = (rows + 3) / 4;
     // register-resident row: instantiate a few row lengths so that short rows do not carry 32 pieces
-    if (pieces <= 4) { SD_DISPATCH(dtype, (k_norm<T, 4><<<grid, 256, 0, st>>>(h, idx, gain, bias, (T*)out, rows, d, eps))); }
-    else if (pieces <= 8) { SD_DISPATCH(dtype, (k_norm<T, 8><<<grid, 256, 0, st>>>(h, idx, gain, bias, (T*)out, rows, d, eps))); }
-    else if (pieces <= 16) { SD_DISPATCH(dtype, (k_norm<T, 16><<<grid, 256, 0, st>>>(h, idx, gain, bias, (T*)out, rows, d, eps))); }
-    else { SD_DISPATCH(dtype, (k_norm<T, kNormPieces><<<grid, 256, 0, st>>>(h, idx, gain, bias, (T*)out, rows, d, eps))); }
+    if (pieces <= 4) { SD_DISPATCH(dtype, (launch_kernel(k_norm<T, 4>, dim3(grid), dim3(256), 0, st, h, idx, gain, bias, (T*)out, rows, d, eps))); }
+    else if (pieces <= 8) { SD_DISPATCH(dtype, (launch_kernel(k_norm<T, 8>, dim3(grid), dim3(256), 0, st, h, idx, gain, bias, (T*)out, rows, d, eps))); }
+    else if (pieces <= 16) { SD_DISPATCH(dtype, (launch_kernel(k_norm<T, 16>, dim3(grid), dim3(256), 0, st, h, idx, gain, bias, (T*)out, rows, d, eps))); }
+    else { SD_DISPATCH(dtype, (launch_kernel(k_norm<T, kNormPieces>, dim3(grid), dim3(256), 0, st, h, idx, gain, bias, (T*)out, rows, d, eps))); }
     return hipGetLastError();
 }
 
@@ -332,7 +332,7 @@ hipError_t launch_rope(int dtype, void* qkv, const int32_t* pos, int rows, int n
     const long total = (long)rows * (n_head + n_kv_head) * (d_head / 2);
     if (total <= 0) return hipSuccess;
     const int grid = (int)((total + 255) / 256);
-    SD_DISPATCH(dtype, (k_rope<T><<<grid, 256, 0, st>>>((T*)qkv, pos, rows, n_head, n_kv_head, d_head, theta)));
+    SD_DISPATCH(dtype, (launch_kernel(k_rope<T>, dim3(grid), dim3(256), 0, st, (T*)qkv, pos, rows, n_head, n_kv_head, d_head, theta)));
     return hipGetLastError();
 }
 
@@ -341,14 +341,14 @@ hipError_t launch_rope_kv_store(int dtype, void* qkv, const int32_t* seq, const 
     const long total = (long)rows * (n_head + 2 * n_kv_head) * (d_head / 2);
     if (total <= 0) return hipSuccess;
     const int grid = (int)((total + 255) / 256);
-    SD_DISPATCH(dtype, (k_rope_kv_store<T><<<grid, 256, 0, st>>>((T*)qkv, seq, pos, (T*)kcache, (T*)vcache, rows, n_head, n_kv_head, d_head, theta, n_ctx)));
+    SD_DISPATCH(dtype, (launch_kernel(k_rope_kv_store<T>, dim3(grid), dim3(256), 0, st, (T*)qkv, seq, pos, (T*)kcache, (T*)vcache, rows, n_head, n_kv_head, d_head, theta, n_ctx)));
     return hipGetLastError();
 }
 
 hipError_t launch_kv_store(int dtype, const void* qkv, const int32_t* seq, const int32_t* pos, void* kcache,
                            void* vcache, int rows, int n_head, int n_kv_head, int d_head, int n_ctx, hipStream_t st) {
     if (rows <= 0) return hipSuccess;
-    SD_DISPATCH(dtype, (k_kv_store<T><<<rows, 256, 0, st>>>((const T*)qkv, seq, pos, (T*)kcache, (T*)vcache, n_head * d_head, n_kv_head * d_head, n_ctx)));
+    SD_DISPATCH(dtype, (launch_kernel(k_kv_store<T>, dim3(rows), dim3(256), 0, st, (const T*)qkv, seq, pos, (T*)kcache, (T*)vcache, n_head * d_head, n_kv_head * d_head, n_ctx)));
     return hipGetLastError();
 }
 
@@ -356,7 +356,7 @@ hipError_t launch_swiglu(int dtype, const void* gu, void* act, int rows, int F, 
     const long total = (long)rows * F;
     if (total <= 0) return hipSuccess;
     const int grid = (int)((total + 255) / 256);
-    SD_DISPATCH(dtype, (k_swiglu<T><<<grid, 256, 0, st>>>((const T*)gu, (T*)act, total, F)));
+    SD_DISPATCH(dtype, (launch_kernel(k_swiglu<T>, dim3(grid), dim3(256), 0, st, (const T*)gu, (T*)act, total, F)));
     return hipGetLastError();
 }
 

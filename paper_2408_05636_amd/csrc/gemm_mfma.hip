@@ -496,10 +496,10 @@ static hipError_t launch_variant(const void* x, const void* w, const float* bias
 #define SD_GO(EPI, NF)                                                                                                  \
     do {                                                                                                                \
         if constexpr (WM * WN == 1) {                                                                                   \
-            if (stream_w) k_linear_mfma<MT, NT, WM, WN, KS, PD, EPI, NF, 1><<<grid, 256, 0, st>>>(x, wb, bias, y, m, n, k, ldy, tiles_m, tiles_n, fi, fo, sk); \
-            else k_linear_mfma<MT, NT, WM, WN, KS, PD, EPI, NF, 0><<<grid, 256, 0, st>>>(x, wb, bias, y, m, n, k, ldy, tiles_m, tiles_n, fi, fo, sk); \
+            if (stream_w) launch_kernel(k_linear_mfma<MT, NT, WM, WN, KS, PD, EPI, NF, 1>, dim3(grid), dim3(256), 0, st, x, wb, bias, y, m, n, k, ldy, tiles_m, tiles_n, fi, fo, sk); \
+            else launch_kernel(k_linear_mfma<MT, NT, WM, WN, KS, PD, EPI, NF, 0>, dim3(grid), dim3(256), 0, st, x, wb, bias, y, m, n, k, ldy, tiles_m, tiles_n, fi, fo, sk); \
         } else {                                                                                                        \
-            k_linear_mfma<MT, NT, WM, WN, KS, PD, EPI, NF, 0><<<grid, 256, 0, st>>>(x, wb, bias, y, m, n, k, ldy, tiles_m, tiles_n, fi, fo, sk); \
+            launch_kernel(k_linear_mfma<MT, NT, WM, WN, KS, PD, EPI, NF, 0>, dim3(grid), dim3(256), 0, st, x, wb, bias, y, m, n, k, ldy, tiles_m, tiles_n, fi, fo, sk); \
         }                                                                                                               \
     } while (0)
     if (ni.kind == 0) {
@@ -616,7 +616,7 @@ __global__ __launch_bounds__(256) void k_fold_norm(const bf16_t* __restrict__ W,
 
 hipError_t launch_fold_norm(const void* w, const float* gain, const float* beta, const float* bias, float* u, float* v,
                             int n, int k, hipStream_t st) {
-    k_fold_norm<<<(n + 3) / 4, 256, 0, st>>>((const bf16_t*)w, gain, beta, bias, u, v, n, k);
+    launch_kernel(k_fold_norm, dim3((n + 3) / 4), dim3(256), 0, st, (const bf16_t*)w, gain, beta, bias, u, v, n, k);
     return hipGetLastError();
 }
 

@@ -277,7 +277,7 @@ static hipError_t launch_pipe_kernel(int grid, hipStream_t st, const void* x, co
         if (e != hipSuccess) return e;
         raised = true;
     }
-    k_linear_pipe<EPI, WMV, WNV, TM, TN, NS, KC, NF><<<grid, 256, kLds, st>>>(x, wb, bias, y, m, n, k, ldy, tiles_m, tiles_n, xs, fi, fo);
+    launch_kernel(k_linear_pipe<EPI, WMV, WNV, TM, TN, NS, KC, NF>, dim3(grid), dim3(256), kLds, st, x, wb, bias, y, m, n, k, ldy, tiles_m, tiles_n, xs, fi, fo);
     return hipGetLastError();
 }
 

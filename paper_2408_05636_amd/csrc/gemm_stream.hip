@@ -418,7 +418,7 @@ static hipError_t go(const dim3& grid, int bytes, hipStream_t st, const bf16_t* 
         if (e != hipSuccess) return e;
         raised = true;
     }
-    k_linear_stream<MT, EPI, NF><<<grid, 256, bytes, st>>>(x, w, bias, y, m, n, k, ldy, fi, fo, sk);
+    launch_kernel(k_linear_stream<MT, EPI, NF>, dim3(grid), dim3(256), bytes, st, x, w, bias, y, m, n, k, ldy, fi, fo, sk);
     return hipGetLastError();
 }
 

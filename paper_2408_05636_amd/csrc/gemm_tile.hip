@@ -264,7 +264,7 @@ static hipError_t launch_tile(const void* x, const bf16_t* wb, const float* bias
     const int grid = xs ? 8 * ((tiles_m + 8 / xs - 1) / (8 / xs)) * ((tiles_n + xs - 1) / xs) : 8 * ((tiles_n + 7) / 8) * tiles_m;
     const FoldIn fi{ni.stats, ni.u, ni.parts, ni.eps};
     const FoldOut fo{no.gain, static_cast<bf16_t*>(no.xg), no.stats};
-#define SD_GO(EPI, NF) k_linear_tile<EPI, WM, NF><<<grid, 256, 0, st>>>(x, wb, bias, y, m, n, k, ldy, tiles_m, tiles_n, xs, fi, fo)
+#define SD_GO(EPI, NF) launch_kernel(k_linear_tile<EPI, WM, NF>, dim3(grid), dim3(256), 0, st, x, wb, bias, y, m, n, k, ldy, tiles_m, tiles_n, xs, fi, fo)
     if (ni.kind == 0) {
         switch (epi) {
             case EPI_STORE: SD_GO(EPI_STORE, 0); break;

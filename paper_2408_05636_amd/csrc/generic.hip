@@ -69,9 +69,9 @@ hipError_t launch_linear_generic(int dtype, const void* x, const void* w, const 
     if (m <= 0 || n <= 0) return hipSuccess;
     const dim3 grid((n + GT - 1) / GT, (m + GT - 1) / GT);
     if (dtype == SD_DTYPE_F32)
-        k_linear_generic<float><<<grid, 256, 0, st>>>((const float*)x, (const float*)w, bias, y, m, n, k, ldy, epilogue);
+        launch_kernel(k_linear_generic<float>, dim3(grid), dim3(256), 0, st, (const float*)x, (const float*)w, bias, y, m, n, k, ldy, epilogue);
     else
-        k_linear_generic<bf16_t><<<grid, 256, 0, st>>>((const bf16_t*)x, (const bf16_t*)w, bias, y, m, n, k, ldy, epilogue);
+        launch_kernel(k_linear_generic<bf16_t>, dim3(grid), dim3(256), 0, st, (const bf16_t*)x, (const bf16_t*)w, bias, y, m, n, k, ldy, epilogue);
     return hipGetLastError();
 }
 
@@ -140,8 +140,8 @@ hipError_t launch_attention_generic(int dtype, const AttnArgs& a, int max_kv, hi
     const int grid = (int)((pairs + 3) / 4);
     const size_t shm = (size_t)4 * (max_kv + a.d_head) * sizeof(float);
     if (shm > 64 * 1024) return hipErrorInvalidValue;
-    if (dtype == SD_DTYPE_F32) k_attention_generic<float><<<grid, 256, shm, st>>>(a, max_kv);
-    else k_attention_generic<bf16_t><<<grid, 256, shm, st>>>(a, max_kv);
+    if (dtype == SD_DTYPE_F32) launch_kernel(k_attention_generic<float>, dim3(grid), dim3(256), shm, st, a, max_kv);
+    else launch_kernel(k_attention_generic<bf16_t>, dim3(grid), dim3(256), shm, st, a, max_kv);
     return hipGetLastError();
 }
 

@@ -426,7 +426,7 @@ __global__ void k_fill_i32(int32_t* __restrict__ p, int n, int v) {
 
 hipError_t launch_fill_i32(int32_t* p, int n, int v, hipStream_t st) {
     if (n <= 0) return hipSuccess;
-    k_fill_i32<<<(n + 255) / 256, 256, 0, st>>>(p, n, v);
+    launch_kernel(k_fill_i32, dim3((n + 255) / 256), dim3(256), 0, st, p, n, v);
     return hipGetLastError();
 }
 
@@ -461,8 +461,8 @@ hipError_t launch_unmask_sample(const float* logits, int batch, int gamma, int v
                                 int32_t* z, float* q, float* qtok, const SampleScratch& s, hipStream_t st) {
     const int rows = batch * gamma, nch = n_chunks(vocab), ld = vocab_pad(vocab);
     const dim3 grid(nch, rows);
-    k_row_stats<<<grid, kThreads, 0, st>>>(logits, ld, vocab, z, gamma, step, seed, s.part_m, s.part_s, s.active);
-    k_unmask_sample<<<grid, kThreads, 0, st>>>(logits, ld, vocab, gamma, step, seed, s.part_m, s.part_s, s.active, z,
+    launch_kernel(k_row_stats, dim3(grid), dim3(kThreads), 0, st, logits, ld, vocab, z, gamma, step, seed, s.part_m, s.part_s, s.active);
+    launch_kernel(k_unmask_sample, dim3(grid), dim3(kThreads), 0, st, logits, ld, vocab, gamma, step, seed, s.part_m, s.part_s, s.active, z,
                                                q, qtok);
     return hipGetLastError();
 }
@@ -472,8 +472,8 @@ hipError_t launch_unmask_greedy(const float* logits, int batch, int gamma, int v
     const int rows = batch * gamma, nch = n_chunks(vocab), ld = vocab_pad(vocab);
     float* pv = reinterpret_cast<float*>(s.part_m);          // the fp64 partial arrays are free in this mode
     int32_t* pi = reinterpret_cast<int32_t*>(s.part_s);
-    k_chunk_argmax<<<dim3(nch, rows), kThreads, 0, st>>>(logits, ld, vocab, z, gamma, step, seed, pv, pi, s.active);
-    k_greedy_reveal<<<rows, 64, 0, st>>>(pv, pi, nch, s.active, z, qtok);
+    launch_kernel(k_chunk_argmax, dim3(dim3(nch, rows)), dim3(kThreads), 0, st, logits, ld, vocab, z, gamma, step, seed, pv, pi, s.active);
+    launch_kernel(k_greedy_reveal, dim3(rows), dim3(64), 0, st, pv, pi, nch, s.active, z, qtok);
     return hipGetLastError();
 }
 
@@ -482,8 +482,8 @@ hipError_t launch_accept_greedy(const float* p_logits, const int32_t* draft, int
     const int rows = batch * (gamma + 1), nch = n_chunks(vocab), ld = vocab_pad(vocab);
     float* pv = reinterpret_cast<float*>(s.part_m);
     int32_t* pi = reinterpret_cast<int32_t*>(s.part_s);
-    k_chunk_argmax<<<dim3(nch, rows), kThreads, 0, st>>>(p_logits, ld, vocab, nullptr, gamma, 0, nullptr, pv, pi, s.active);
-    k_greedy_accept<<<batch, 64, 0, st>>>(pv, pi, nch, draft, gamma, n_acc, token);
+    launch_kernel(k_chunk_argmax, dim3(dim3(nch, rows)), dim3(kThreads), 0, st, p_logits, ld, vocab, nullptr, gamma, 0, nullptr, pv, pi, s.active);
+    launch_kernel(k_greedy_accept, dim3(batch), dim3(64), 0, st, pv, pi, nch, draft, gamma, n_acc, token);
     return hipGetLastError();
 }
 
@@ -491,14 +491,14 @@ hipError_t launch_accept_resample(const float* p_logits, const float* q, const i
                                   int gamma, int vocab, const uint64_t* seed, int32_t* n_acc, int32_t* token,
                                   const SampleScratch& s, hipStream_t st) {
     const int rows = batch * (gamma + 1), nch = n_chunks(vocab), ld = vocab_pad(vocab);
-    k_row_stats<<<dim3(nch, rows), kThreads, 0, st>>>(p_logits, ld, vocab, nullptr, gamma, 0, seed, s.part_m,
+    launch_kernel(k_row_stats, dim3(dim3(nch, rows)), dim3(kThreads), 0, st, p_logits, ld, vocab, nullptr, gamma, 0, seed, s.part_m,
                                                       s.part_s, s.active);
-    k_accept<<<batch, kThreads, 2 * (gamma + 1) * sizeof(double), st>>>(p_logits, q, draft, ld, vocab, gamma, nch,
+    launch_kernel(k_accept, dim3(batch), dim3(kThreads), 2 * (gamma + 1) * sizeof(double), st, p_logits, q, draft, ld, vocab, gamma, nch,
                                                                        seed, s.part_m, s.part_s, n_acc, s.row_m,
                                                                        s.row_z);
-    k_final_partial<<<dim3(nch, batch), kThreads, 0, st>>>(p_logits, q, ld, vocab, gamma, n_acc, s.row_m, s.row_z,
+    launch_kernel(k_final_partial, dim3(dim3(nch, batch)), dim3(kThreads), 0, st, p_logits, q, ld, vocab, gamma, n_acc, s.row_m, s.row_z,
                                                            s.part_r);
-    k_final_sample<<<batch, kThreads, 0, st>>>(p_logits, q, ld, vocab, gamma, nch, seed, n_acc, s.row_m, s.row_z,
+    launch_kernel(k_final_sample, dim3(batch), dim3(kThreads), 0, st, p_logits, q, ld, vocab, gamma, nch, seed, n_acc, s.row_m, s.row_z,
                                                s.part_m, s.part_s, s.part_r, token);
     return hipGetLastError();
 }

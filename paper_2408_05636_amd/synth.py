@@ -147,9 +147,16 @@ def gen_tensor(cfg: ModelConfig, seed: int, index: int, shape, role: str) -> np.
     return w
 
 
-def gen_weights(cfg: ModelConfig, seed: int) -> Dict[str, np.ndarray]:
-    return {name: gen_tensor(cfg, seed, i, shape, role)
-            for i, (name, shape, role) in enumerate(weight_specs(cfg))}
+def gen_weights(cfg: ModelConfig, seed: int, threads: int = 1) -> Dict[str, np.ndarray]:
+    """All parameter tensors of a model.  Every tensor has a generator of its own (seed, tensor index), so the
+    values do not depend on `threads` (numpy's generators release the interpreter lock while they fill)."""
+    specs = list(enumerate(weight_specs(cfg)))
+    if threads <= 1:
+        return {name: gen_tensor(cfg, seed, i, shape, role) for i, (name, shape, role) in specs}
+    from concurrent.futures import ThreadPoolExecutor
+    with ThreadPoolExecutor(max_workers=threads) as ex:
+        vals = list(ex.map(lambda it: gen_tensor(cfg, seed, it[0], it[1][1], it[1][2]), specs))
+    return {name: v for (_, (name, _, _)), v in zip(specs, vals)}
 
 
 def gen_prefix(vocab: int, length: int, seed: int) -> np.ndarray:

@@ -9,16 +9,17 @@ from oracle import transformer as otf
 # |gpu - ref| <= 1e-4 * (|ref| + rms(ref row)), since an elementwise relative bound is void at
 # zero crossings -- and bf16 path 2e-2 absolute.  The absolute figure belongs to the logit scale of
 # the GPT-2-small-shaped workloads (rms 0.55 with the N(0, 0.02) initialisation).  The error of a
-# pipeline that stores its activations in bf16 is proportional to the logit scale and depends on the
-# architecture: measured rms error 0.42 % of the logit rms for the GPT-2 shapes (d = 768 and 1600) and
-# 0.98 % for the Llama shape at d = 4096 -- the same 0.98 % that a numpy forward with bf16 rounding at
-# the same storage points shows against the fp64 oracle --, with maxima at 5-6 sigma over 10^6-10^7
-# logits.  Wider models, whose random-init logits are larger (rms 0.80 at d = 1600, 1.28 at d = 4096),
-# are therefore held to 6 % of the logit rms where that exceeds 2e-2.
-BF16_ABS_TOL, BF16_REL_RMS = 2e-2, 0.06
+# pipeline that stores its activations in bf16 is relative (2^-9 per stored value), grows with the
+# logit scale and with depth, and is predicted -- independently of the kernels -- by the storage
+# model of tests/bf16_model.py on the very inputs of a test.  With `model` given (that model's
+# logits) the bound is  max |gpu - ref| <= max(2e-2, 6.5 sigma)  and  rms(gpu - ref) <= 1.3 sigma + 1e-4,
+# sigma = rms(model - ref): 6.5 sigma because the largest of 10^6 - 10^7 near-Gaussian errors sits
+# at 5 - 5.5 sigma; the rms condition is the tight one (an error source beyond the storage format,
+# e.g. a wrong folded-norm term, shows there first).  Without `model` the stated 2e-2 holds as is.
+BF16_ABS_TOL, SIGMA_MAX, SIGMA_RMS = 2e-2, 6.5, 1.3
 
 
-def assert_logits_close(got, ref, dtype, what=""):
+def assert_logits_close(got, ref, dtype, what="", model=None, stats=None):
     got = np.asarray(got, dtype=np.float64)
     ref = np.asarray(ref, dtype=np.float64)
     assert got.shape == ref.shape, (got.shape, ref.shape)
@@ -27,9 +28,20 @@ def assert_logits_close(got, ref, dtype, what=""):
         bound = 1e-4 * (np.abs(ref) + np.sqrt((ref ** 2).mean(axis=-1, keepdims=True)))
         worst = (err / bound).max()
         assert worst <= 1.0, f"{what}: fp32 logits off by {worst:.3f}x the 1e-4 relative bound (max abs err {err.max():.3e})"
-    else:
-        tol = max(BF16_ABS_TOL, BF16_REL_RMS * float(np.sqrt((ref ** 2).mean())))
-        assert err.max() <= tol, f"{what}: bf16 logits max abs err {err.max():.4f} > {tol:.4f}"
+        return err.max()
+    rms_err = float(np.sqrt((err ** 2).mean()))
+    sigma = None
+    tol = BF16_ABS_TOL
+    if model is not None:
+        model = np.asarray(model, dtype=np.float64)
+        sigma = float(np.sqrt(((model - ref) ** 2).mean()))
+        tol = max(BF16_ABS_TOL, SIGMA_MAX * sigma)
+    if stats is not None:
+        stats.update(what=what, logit_rms=float(np.sqrt((ref ** 2).mean())), max_err=float(err.max()), rms_err=rms_err,
+                     sigma_model=sigma, tol=tol, n=int(ref.size))
+    assert err.max() <= tol, f"{what}: bf16 logits max abs err {err.max():.4f} > {tol:.4f} (storage model sigma {sigma})"
+    if sigma is not None:
+        assert rms_err <= SIGMA_RMS * sigma + 1e-4, f"{what}: rms error {rms_err:.5f} beyond {SIGMA_RMS} x the storage model's {sigma:.5f}"
     return err.max()
 
 

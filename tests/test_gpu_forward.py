@@ -5,6 +5,7 @@ import pytest
 
 from oracle import transformer as otf
 from paper_2408_05636_amd import synth
+from tests import bf16_model as bm
 from tests.helpers import assert_logits_close
 
 pytestmark = pytest.mark.gpu
@@ -31,16 +32,20 @@ def check_forwards(target, drafter, prefix_lens, gamma, T, seed, steps=None, boo
             seqs.append(np.concatenate([p, blk]).astype(np.int32))
         got = sd.sd_drafter_logits(seqs, gamma, j, T).cpu().numpy()
         for b, s in enumerate(seqs):
-            ref = otf.logits_at(Wd, drafter, s, np.arange(len(s) - gamma, len(s)), j / T)
-            assert_logits_close(got[b * gamma:(b + 1) * gamma, :V], ref, drafter.dtype, f"drafter step {j} seq {b}")
+            rows = np.arange(len(s) - gamma, len(s))
+            ref = otf.logits_at(Wd, drafter, s, rows, j / T)
+            model = bm.logits_at(Wd, drafter, s, rows, j / T) if drafter.dtype == "bf16" else None
+            assert_logits_close(got[b * gamma:(b + 1) * gamma, :V], ref, drafter.dtype, f"drafter step {j} seq {b}", model)
     # target: gamma + 1 query rows against the prefilled cache
     draft = rng.integers(0, V, (len(prefixes), gamma)).astype(np.int32)
     sd.sd_prefill(prefixes)
     got = sd.sd_target_logits(prefixes, draft).cpu().numpy()
     for b, p in enumerate(prefixes):
         L = len(p)
-        ref = otf.logits_at(Wt, target, np.concatenate([p, draft[b]]), np.arange(L - 1, L + gamma))
-        assert_logits_close(got[b * (gamma + 1):(b + 1) * (gamma + 1), :V], ref, target.dtype, f"target seq {b}")
+        toks, rows = np.concatenate([p, draft[b]]), np.arange(L - 1, L + gamma)
+        ref = otf.logits_at(Wt, target, toks, rows)
+        model = bm.logits_at(Wt, target, toks, rows) if target.dtype == "bf16" else None
+        assert_logits_close(got[b * (gamma + 1):(b + 1) * (gamma + 1), :V], ref, target.dtype, f"target seq {b}", model)
     # a cold cache (different prefix, no explicit prefill) must give the same rows as an explicit one
     other = [synth.gen_prefix(V, L, seed + 99 + i) for i, L in enumerate(prefix_lens)]
     cold = sd.sd_target_logits(other, draft).cpu().numpy().copy()
