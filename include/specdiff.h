@@ -181,6 +181,21 @@ int32_t sd_accept_resample(const float *p_logits, const float *q, const int32_t 
                            int32_t *n_accepted, int32_t *token,
                            void *scratch, int64_t scratch_bytes, void *hip_stream);
 
+/* sd_accept_resample for callers that cannot allocate device memory or pass a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same results, no scratch
+ * argument: the partial row statistics live in a fixed buffer of sd_static_scratch_bytes() bytes (4 MiB) that the
+ * library holds in device memory on every GPU it runs on, for the life of the process.  The call allocates nothing
+ * (no hipMalloc / hipFree, no staging copy: the seed travels as a kernel argument) and is asynchronous on
+ * hip_stream.  Shapes whose statistics do not fit, i.e. sd_sampling_scratch_bytes(batch * (gamma + 1), vocab) >
+ * sd_static_scratch_bytes(), are rejected with SD_ERR_WORKSPACE (text in sd_last_error(NULL)); nothing is launched
+ * then.  All calls on one GPU share that GPU's buffer: calls that overlap in time on one GPU (two streams, two
+ * threads) race and give undefined results; calls on one stream, or otherwise ordered, are fine.  Nothing in the
+ * buffer needs to be zero and nothing is kept between calls. */
+int64_t sd_static_scratch_bytes(void);
+int32_t sd_accept_resample_static(const float *p_logits, const float *q, const int32_t *draft,
+                                  int32_t batch, int32_t gamma, int32_t vocab, uint64_t seed,
+                                  int32_t *n_accepted, int32_t *token, void *hip_stream);
+
 /* y = epilogue(x W^T + bias): the dense contraction used by every QKV / MLP / LM-head layer.
  * x: [m, k] (dtype), w: [n, k] (dtype), bias: fp32 [n] or NULL.
  * epilogue 0: y (dtype) = acc; 1: y (dtype) = gelu_tanh(acc); 2: y (fp32) += acc (residual);

@@ -25,7 +25,7 @@ EXPORTS = ["sd_vocab_pad", "sd_weight_count", "sd_weight_desc", "sd_weight_bytes
            "sd_target_logits", "sd_sampling_scratch_bytes", "sd_unmask_sample", "sd_accept_resample", "sd_linear",
            "sd_profile_begin", "sd_profile_end", "sd_profile_count", "sd_profile_entry", "sd_set_graph_replay", "sd_set_linear_variant", "sd_norm_linear",
            "sd_set_linear_split", "sd_linear_split_ticket_bytes", "sd_commit", "sd_set_greedy", "sd_set_step_skipping", "sd_steps_run", "sd_norm_linear_scratch_floats", "sd_linear_resid_norm",
-           "sd_graph_stats", "sd_graph_error"]
+           "sd_graph_stats", "sd_graph_error", "sd_static_scratch_bytes", "sd_accept_resample_static"]
 
 
 class SdModelConfig(C.Structure):
@@ -76,6 +76,9 @@ def lib() -> C.CDLL:
         L.sd_unmask_sample.argtypes = [vp, i32, i32, i32, i32, u64, vp, vp, vp, vp, i64, vp]
         L.sd_accept_resample.restype = i32
         L.sd_accept_resample.argtypes = [vp, vp, vp, i32, i32, i32, u64, vp, vp, vp, i64, vp]
+        L.sd_static_scratch_bytes.restype = i64; L.sd_static_scratch_bytes.argtypes = []
+        L.sd_accept_resample_static.restype = i32
+        L.sd_accept_resample_static.argtypes = [vp, vp, vp, i32, i32, i32, u64, vp, vp, vp]
         L.sd_linear.restype = i32
         L.sd_linear.argtypes = [i32, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, i64, vp]
         L.sd_set_linear_split.restype = i32; L.sd_set_linear_split.argtypes = [i32]
@@ -376,6 +379,16 @@ def sd_accept_resample(p_logits, q, draft, batch: int, gamma: int, vocab: int, s
         raise SdError(rc, "sd_accept_resample")
     torch.cuda.synchronize(p_logits.device)
     return n, tok
+
+
+def sd_accept_resample_static(p_logits, q, draft, batch: int, gamma: int, vocab: int, seed: int, n, tok):
+    """The same on the library's fixed scratch buffer; n, tok: caller's int32 device tensors [B].  Allocates nothing."""
+    import torch
+    rc = lib().sd_accept_resample_static(p_logits.data_ptr(), q.data_ptr(), draft.data_ptr(), batch, gamma, vocab, seed,
+                                         n.data_ptr(), tok.data_ptr(), _stream_ptr(p_logits))
+    if rc:
+        raise SdError(rc, "sd_accept_resample_static", lib().sd_last_error(None).decode())
+    torch.cuda.synchronize(p_logits.device)
 
 
 _split_ws = {}

@@ -3,6 +3,7 @@
 // Algorithm 1 runs on the device.
 #include <string.h>
 
+#include <mutex>
 #include <string>
 #include <unordered_map>
 #include <unordered_set>
@@ -986,6 +987,43 @@ int read_back(sd_handle* h, int32_t* dst, const int32_t* dev, int64_t n) {
 // ------------------------------------------------------------------------------------------
 static std::string g_create_error = "null handle";   // reported by sd_last_error(NULL)
 
+// ------------------------------------------------------------------------------------------
+// Scratch of the allocation-free entry point (sd_accept_resample_static): a fixed array in device memory instead of
+// a caller workspace.  Every GPU holds its own copy at its own address; host code never uses the array's name as an
+// address, only what hipGetSymbolAddress returned for the current device.
+// ------------------------------------------------------------------------------------------
+constexpr int64_t kStaticScratchBytes = 4 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device (looked up once per device).
+int static_scratch(void** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        g_create_error = "sd_accept_resample_static: no current HIP device";
+        return SD_ERR_HIP;
+    }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr) {
+            g_create_error = std::string("hipGetSymbolAddress(scratch): ") + hipGetErrorString(e);
+            return SD_ERR_HIP;
+        }
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return SD_OK;
+}
+
+__global__ void k_store_u64(uint64_t* p, uint64_t v) { *p = v; }
+}  // namespace
+
 extern "C" {
 
 int32_t sd_vocab_pad(int32_t vocab) { return vocab_pad(vocab); }
@@ -1087,6 +1125,7 @@ int32_t sd_create(const sd_model_config* target, const sd_model_config* drafter,
         delete h;
         return SD_ERR_HIP;
     }
+    { void* fixed = nullptr; (void)static_scratch(&fixed); }     // set-up of the allocation-free entry point on this device (it retries by itself if this failed)
     h->lim = limits_of(*target, *drafter, max_batch, gamma_max);
     h->max_batch = max_batch;
     h->gamma_max = gamma_max;
@@ -1407,6 +1446,31 @@ int32_t sd_accept_resample(const float* p_logits, const float* q, const int32_t*
     const SampleScratch ss = sampling_scratch(scratch, batch * (gamma + 1), vocab);
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     if (hipMemcpyAsync(ss.seed, &seed, 8, hipMemcpyHostToDevice, st) != hipSuccess) return SD_ERR_HIP;   // pageable source: staged before return
+    return launch_accept_resample(p_logits, q, draft, batch, gamma, vocab, ss.seed, n_accepted, token, ss, st) == hipSuccess ? SD_OK : SD_ERR_HIP;
+}
+
+int64_t sd_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+int32_t sd_accept_resample_static(const float* p_logits, const float* q, const int32_t* draft, int32_t batch, int32_t gamma,
+                                  int32_t vocab, uint64_t seed, int32_t* n_accepted, int32_t* token, void* hip_stream) {
+    if (!p_logits || !q || !draft || !n_accepted || !token) return SD_ERR_ARG;
+    if (batch <= 0 || gamma <= 0 || vocab <= 0 || vocab > kChunk * 512 || gamma > 4095) return SD_ERR_SHAPE;
+    const int64_t rows = (int64_t)batch * (gamma + 1);
+    if (rows > (1 << 20) || sampling_scratch_bytes((int)rows, vocab) > kStaticScratchBytes) {
+        g_create_error = "sd_accept_resample_static: batch * (gamma + 1) rows of this vocabulary need " +
+                         std::to_string(rows > (1 << 20) ? -1 : sampling_scratch_bytes((int)rows, vocab)) + " bytes of scratch, the fixed buffer holds " +
+                         std::to_string(kStaticScratchBytes) + "; use sd_accept_resample with a workspace";
+        return SD_ERR_WORKSPACE;
+    }
+    void* base = nullptr;
+    const int rc = static_scratch(&base);
+    if (rc) return rc;
+    const SampleScratch ss = sampling_scratch(base, (int)rows, vocab);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    // Nothing in the scratch has to start at zero: every partial, row statistic and the seed slot is written by this
+    // call before it is read.  The seed travels as a kernel argument (no staging copy).
+    launch_kernel(k_store_u64, dim3(1), dim3(1), 0, st, ss.seed, seed);
+    if (hipGetLastError() != hipSuccess) return SD_ERR_HIP;
     return launch_accept_resample(p_logits, q, draft, batch, gamma, vocab, ss.seed, n_accepted, token, ss, st) == hipSuccess ? SD_OK : SD_ERR_HIP;
 }
 
