@@ -3,6 +3,7 @@
 // Algorithm 1 runs on the device.
 #include <string.h>
 
+#include <algorithm>
 #include <mutex>
 #include <string>
 #include <unordered_map>
@@ -175,6 +176,7 @@ struct Arena {
 struct Buffers {
     float* h; void* xn; void* qkv; void* att; void* mlp; void* act; void* xf;
     float *logits_d, *logits_t, *q, *qtok, *temb, *temb_hidden;
+    float* rope_cs;          // (cos, sin) of the rotation angles of the target's query rows, [rows][d_head / 2][2]
     int32_t *z, *n_acc, *tok;
     char* maps[3];           // packed row maps: 0 drafter, 1 target query rows, 2 target prefill
     uint64_t* seed;          // Philox key of the current call
@@ -228,6 +230,7 @@ int64_t carve(Arena& a, Buffers& b, const sd_model_config& t, const sd_model_con
     b.logits_t = a.take<float>(l.rows_head * ld);
     b.q = a.take<float>((int64_t)max_batch * gamma_max * ld);
     b.qtok = a.take<float>((int64_t)max_batch * gamma_max);
+    b.rope_cs = a.take<float>(l.rows_head * (int64_t)(t.d_model / t.n_head));
     b.temb = a.take<float>((int64_t)kMaxSteps * d.d_model);
     b.temb_hidden = a.take<float>((int64_t)kMaxSteps * d.d_model);
     b.z = a.take<int32_t>((int64_t)max_batch * gamma_max);
@@ -715,20 +718,25 @@ int run_layers(sd_handle* h, const Model& m, const MapSet& rm, const float* temb
     int rc;
     SD_LAUNCH(h, "k_embed", rd * (4 + ew + (fold ? 2 : 0)), 0,
               launch_embed(dt, rm.src, rm.pos, rm.tokens, B.z, m.wte, m.wpe, temb, B.h, rows, d, fold ? m.L[0].ln1_g : nullptr, B.xn, B.stats, h->st));
+    // The query rows of a single sequence sit at consecutive cache rows: the QKV contraction then writes its K and V
+    // columns straight into the cache (few-row kernel, plain store epilogue) and no copy kernel runs.  With rotary
+    // positions the same epilogue rotates q and k; the angles depend on the positions only: one table per forward.
+    const bool kv_direct = fold && cached && rm.kv_row0 >= 0 && rows <= 64 && m.dq % 32 == 0 && m.dkv % 32 == 0 &&
+                           (c.arch == SD_ARCH_GPT2 || ((m.dh == 64 || m.dh == 128) && qkv_w % 32 == 0));
+    if (kv_direct && c.arch == SD_ARCH_LLAMA)
+        SD_LAUNCH(h, "k_rope_table", 8.0 * rows * (m.dh / 2), 0, launch_rope_table(rm.pos, rows, m.dh, c.rope_theta, B.rope_cs, h->st));
     for (int i = 0; i < c.n_layer; ++i) {
         const Layer& l = m.L[i];
-        // The query rows of a single sequence sit at consecutive cache rows: the QKV contraction then writes its K and V
-        // columns straight into the cache (few-row kernel, plain store epilogue) and no copy kernel runs.
         const int64_t per_layer = cached ? (int64_t)h->max_batch * c.n_ctx * m.dkv * m.ew : 0;
         char* const kc = cached ? static_cast<char*>(B.kcache) + i * per_layer : nullptr;
         char* const vc = cached ? static_cast<char*>(B.vcache) + i * per_layer : nullptr;
-        const bool kv_direct = fold && cached && c.arch == SD_ARCH_GPT2 && rm.kv_row0 >= 0 && rows <= 64 && m.dq % 32 == 0 && m.dkv % 32 == 0;
         if (fold) {
             NormOut qkv_out;
             if (kv_direct) {
                 qkv_out.y1 = kc + rm.kv_row0 * m.dkv * (int64_t)m.ew;
                 qkv_out.y2 = vc + rm.kv_row0 * m.dkv * (int64_t)m.ew;
                 qkv_out.c1 = m.dq; qkv_out.c2 = m.dq + m.dkv; qkv_out.ld12 = m.dkv;
+                if (c.arch == SD_ARCH_LLAMA) { qkv_out.rope_cs = B.rope_cs; qkv_out.rope_cols = m.dq + m.dkv; qkv_out.rope_dh = m.dh; }
             }
             if ((rc = run_linear(h, dt, B.xn, l.w_qkv, ln ? l.fv_qkv : l.b_qkv, B.qkv, rows, qkv_w, d, qkv_w, EPI_STORE, fold_in(l.fu_qkv), qkv_out))) return rc;
         } else {
@@ -774,8 +782,19 @@ int run_layers(sd_handle* h, const Model& m, const MapSet& rm, const float* temb
             if ((rc = run_linear(h, dt, B.xn, l.w_fc, up_bias, B.mlp, rows, up_w, d, up_w, EPI_GELU, up_in))) return rc;
             down_x = B.mlp;
         } else {
-            if ((rc = run_linear(h, dt, B.xn, l.w_fc, up_bias, B.mlp, rows, up_w, d, up_w, EPI_STORE, up_in))) return rc;
-            SD_LAUNCH(h, "k_swiglu", 3.0 * rows * c.d_ff * ew, 0, launch_swiglu(dt, B.mlp, B.act, rows, c.d_ff, h->st));
+            // Few rows against the long gate | up stream: the gating runs in the contraction's epilogue (gate and up tiles
+            // of the same columns in one workgroup), gate / up never reach memory.  Otherwise contraction, then gating kernel.
+            const bool gated = fold && rows <= 64 && up_w % 128 == 0;
+            if (gated) {
+                const double bytes = ((double)rows * d + (double)up_w * d) * ew + (double)rows * c.d_ff * ew;
+                const char* name = "linear";
+                SD_LAUNCH(h, name, bytes, 2.0 * rows * up_w * d,
+                          launch_linear_stream(B.xn, l.w_fc, nullptr, B.act, rows, up_w, d, c.d_ff, EPI_SWIGLU, up_in, NormOut(), h->buf.split, 0, h->st, &name));
+            }
+            if (!gated) {
+                if ((rc = run_linear(h, dt, B.xn, l.w_fc, up_bias, B.mlp, rows, up_w, d, up_w, EPI_STORE, up_in))) return rc;
+                SD_LAUNCH(h, "k_swiglu", 3.0 * rows * c.d_ff * ew, 0, launch_swiglu(dt, B.mlp, B.act, rows, c.d_ff, h->st));
+            }
             down_x = B.act;
         }
         // MLP down: h += ..., and xn / row sums for the first normalisation of the next layer

@@ -21,7 +21,13 @@ __host__ __device__ inline int64_t align_up(int64_t x, int64_t a) { return (x + 
 __host__ __device__ inline int vocab_pad(int v) { return (v + 255) / 256 * 256; }
 __host__ __device__ inline int n_chunks(int vocab) { return (vocab + kChunk - 1) / kChunk; }
 
-enum Epilogue { EPI_STORE = 0, EPI_GELU = 1, EPI_RESID = 2, EPI_F32 = 3, EPI_RESID_NORM = 4 /* kernels only: EPI_RESID with NormOut */ };
+enum Epilogue {
+    EPI_STORE = 0, EPI_GELU = 1, EPI_RESID = 2, EPI_F32 = 3,
+    EPI_RESID_NORM = 4,  // kernels only: EPI_RESID with NormOut
+    EPI_STORE_ROPE = 6,  // kernels only: EPI_STORE with NormOut::rope_cs (rotary embedding in the epilogue)
+    EPI_SWIGLU = 5       // W = [gate rows | up rows] ([n, k], n even): y[m, n / 2] (dtype) = silu(gate part) * (up part); the few-row
+                         // streaming kernel only (launch_linear_stream), callers fall back to EPI_STORE + launch_swiglu
+};
 
 // A normalisation folded around a contraction  y = W norm(h) + bias  (bf16 models).  Whoever produces the
 // residual stream h also writes x = bf16(h * gain) and partial row sums (sum h, sum h^2); the contraction
@@ -45,6 +51,11 @@ struct NormOut {             // producer (residual epilogue): what to prepare fo
     void* y1 = nullptr;
     void* y2 = nullptr;
     int c1 = 0, c2 = 0, ld12 = 0;
+    // Rotary embedding of the output columns [0, rope_cols) (the q and k parts of a QKV contraction; same kernel and
+    // epilogue as the column split): heads of rope_dh columns (64 or 128), the pair (i, i + rope_dh / 2) of row m is
+    // rotated by the angle whose (cos, sin) is rope_cs[m * rope_dh / 2 + i] (launch_rope_table).  NULL: no rotation.
+    const float* rope_cs = nullptr;
+    int rope_cols = 0, rope_dh = 0;
 };
 
 // Every kernel of the library is launched through launch_kernel().  Ordinarily that is a plain launch.  While a
@@ -95,6 +106,11 @@ hipError_t launch_norm(int dtype, const float* h, const int32_t* idx, const floa
 // In-place rotary embedding of the q and k parts of qkv rows (llama), positions pos[r].
 hipError_t launch_rope(int dtype, void* qkv, const int32_t* pos, int rows, int n_head, int n_kv_head, int d_head,
                        float theta, hipStream_t st);
+
+// cs[r * d_head / 2 + i] = (cos, sin) of pos[r] * theta^(-2 i / d_head): the rotation angles of `rows` rows, for the
+// contraction epilogue that rotates q and k itself (NormOut::rope_cs).  The angles depend on the positions only, so one
+// table serves every layer of a forward.
+hipError_t launch_rope_table(const int32_t* pos, int rows, int d_head, float theta, float* cs, hipStream_t st);
 
 // Both of the above in one pass (rotary embedding, then the cache append of the rotated k and of v).
 hipError_t launch_rope_kv_store(int dtype, void* qkv, const int32_t* seq, const int32_t* pos, void* kcache, void* vcache,

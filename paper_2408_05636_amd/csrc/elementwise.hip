@@ -217,6 +217,19 @@ __global__ __launch_bounds__(256) void k_rope(T* __restrict__ qkv, const int32_t
     x[i + half] = from_f<T>(b * c + a * s);
 }
 
+// (cos, sin) of pos[r] * theta^(-2 i / d_head), the arithmetic of k_rope; one thread per (row, pair).
+__global__ __launch_bounds__(256) void k_rope_table(const int32_t* __restrict__ pos, int rows, int d_head, float theta,
+                                                    float* __restrict__ cs) {
+    const int half = d_head / 2;
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= rows * half) return;
+    const int i = t % half, r = t / half;
+    const double inv = exp(-log((double)theta) * 2.0 * (double)i / (double)d_head);
+    const double ang = (double)pos[r] * inv;
+    cs[2 * t + 0] = (float)cos(ang);
+    cs[2 * t + 1] = (float)sin(ang);
+}
+
 // Rotary embedding and KV-cache append in one pass over the qkv rows (the causal Llama-shaped target): q is rotated
 // in place, k is rotated on its way into the cache (and in place), v is copied.  Thread -> one (i, i + d_head/2)
 // pair of one head of one row; the arithmetic is that of k_rope.
@@ -333,6 +346,13 @@ hipError_t launch_rope(int dtype, void* qkv, const int32_t* pos, int rows, int n
     if (total <= 0) return hipSuccess;
     const int grid = (int)((total + 255) / 256);
     SD_DISPATCH(dtype, (launch_kernel(k_rope<T>, dim3(grid), dim3(256), 0, st, (T*)qkv, pos, rows, n_head, n_kv_head, d_head, theta)));
+    return hipGetLastError();
+}
+
+hipError_t launch_rope_table(const int32_t* pos, int rows, int d_head, float theta, float* cs, hipStream_t st) {
+    const int total = rows * (d_head / 2);
+    if (total <= 0) return hipSuccess;
+    launch_kernel(k_rope_table, dim3((total + 255) / 256), dim3(256), 0, st, pos, rows, d_head, theta, cs);
     return hipGetLastError();
 }
 

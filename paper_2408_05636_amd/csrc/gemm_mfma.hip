@@ -35,6 +35,8 @@ struct SplitArgs {
     void* y1;           // NormOut::y1, y2, c1, c2, ld12: where the output columns from c1 on go (NULL: to Y)
     void* y2;
     int c1, c2, ld12;
+    const float* rope_cs;   // NormOut::rope_cs, rope_cols, rope_dh (EPI_STORE_ROPE)
+    int rope_cols, rope_dh;
 };
 
 template <int MT, int NT, int WM, int WN, int KS, int PD, int EPI, int NF, int WNT>
@@ -68,6 +70,20 @@ __global__ __launch_bounds__(256, (MT * NT == 1 ? 3 : 1)) void k_linear_mfma(con
     if (tn >= tiles_n || tm >= tiles_m) return;         // padding workgroup of an XCD with fewer tiles
     const int m_base = (tm * WM + wm) * 32 * MT;
     const int n_base = (tn * WN + wn) * 32 * NT;
+    // EPI_STORE_ROPE (one column tile per wave): a tile inside the rotated columns does not take 32 consecutive W rows but
+    // 16 pairs (i, i + dh / 2) of one head -- tile-local column q is W row / output column cm0 + (q & 15) + (q >> 4) * cm_half --
+    // so that both elements of a pair sit in one wave, 16 lanes apart, and the epilogue can rotate them.
+    int cm0 = n_base, cm_half = 16;
+    bool rotated = false;
+    if constexpr (EPI == EPI_STORE_ROPE) {
+        rotated = n_base < sk.rope_cols;
+        if (rotated) {
+            const int tph = sk.rope_dh / 32, tl = n_base / 32;
+            cm0 = (tl / tph) * sk.rope_dh + 16 * (tl % tph);
+            cm_half = sk.rope_dh / 2;
+        }
+    }
+#define SD_COLMAP(Q) (cm0 + ((Q) & 15) + ((Q) >> 4) * cm_half)
 
     constexpr int TILES = MT + NT;                       // 32-row operand tiles of this wave: x tiles, then W tiles
     __shared__ u32x4 stage_all[4][TILES * 256];          // 4 KB per tile and wave
@@ -86,7 +102,8 @@ __global__ __launch_bounds__(256, (MT * NT == 1 ? 3 : 1)) void k_linear_mfma(con
     for (int t = 0; t < TILES; ++t)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const uint32_t row = t < MT ? (uint32_t)(m_base + 32 * t + 8 * i + lrow) : (uint32_t)(n_base + 32 * (t - MT) + 8 * i + lrow);
+            const uint32_t row = t < MT ? (uint32_t)(m_base + 32 * t + 8 * i + lrow)
+                                        : (EPI == EPI_STORE_ROPE ? (uint32_t)SD_COLMAP(8 * i + lrow) : (uint32_t)(n_base + 32 * (t - MT) + 8 * i + lrow));
             const uint32_t lim = t < MT ? (uint32_t)M : (uint32_t)N;
             goff[t][i] = row < lim ? (row * (uint32_t)K + 8u * pc) * (t < MT ? kXBytes : 2u) : kOutOfRange;
         }
@@ -142,12 +159,12 @@ __global__ __launch_bounds__(256, (MT * NT == 1 ? 3 : 1)) void k_linear_mfma(con
     // epilogue) is requested now, so that these round trips overlap the K loop instead of following it.
     constexpr bool kResid = EPI == EPI_RESID || EPI == EPI_RESID_NORM;
     constexpr bool kPrefetchResid = MT * NT <= 2;
-    constexpr uint32_t kOutBytes = (EPI == EPI_STORE || EPI == EPI_GELU) ? 2u : 4u;
+    constexpr uint32_t kOutBytes = (EPI == EPI_STORE || EPI == EPI_GELU || EPI == EPI_STORE_ROPE) ? 2u : 4u;
     // Where this wave's columns go: normally Y; with a column split (plain store, one column tile per wave; the split
     // points are multiples of 32, so a tile lies on one side) the tiles from c1 / c2 on go to y1 / y2.
     void* Yo = Y;
     int ldo = ldy, ncol0 = 0;
-    if constexpr (EPI == EPI_STORE && NT == 1) {
+    if constexpr ((EPI == EPI_STORE || EPI == EPI_STORE_ROPE) && NT == 1) {
         if (sk.y1 != nullptr && n_base >= sk.c1) {
             const bool second = n_base >= sk.c2;
             Yo = second ? sk.y2 : sk.y1;
@@ -167,7 +184,7 @@ __global__ __launch_bounds__(256, (MT * NT == 1 ? 3 : 1)) void k_linear_mfma(con
     if (wk == 0) {
 #pragma unroll
         for (int j = 0; j < NT; ++j) {
-            const uint32_t n = (uint32_t)(n_base + 32 * j + r);
+            const uint32_t n = EPI == EPI_STORE_ROPE ? (uint32_t)SD_COLMAP(r) : (uint32_t)(n_base + 32 * j + r);
             yoff[j] = n < (uint32_t)N ? ((uint32_t)(m_base + 4 * half) * (uint32_t)ldo + (n - (uint32_t)ncol0)) * kOutBytes : kOutOfRange;
             bv[j] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rb, n * 4u, 0, 0));
             uv[j] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(ru, n * 4u, 0, 0));
@@ -402,10 +419,33 @@ __global__ __launch_bounds__(256, (MT * NT == 1 ? 3 : 1)) void k_linear_mfma(con
     // (The epilogue kind is a template parameter: with a run-time switch the compiler puts a full
     // memory wait in front of every store and the 16 stores of a tile serialise.)
     const __amdgpu_buffer_rsrc_t rxg = __builtin_amdgcn_make_buffer_rsrc(fo.xg, 0, (EPI == EPI_RESID_NORM) ? (uint32_t)M * (uint32_t)N * 2u : 0u, kBufFlags);
+    const __amdgpu_buffer_rsrc_t rcs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(sk.rope_cs), 0, (EPI == EPI_STORE_ROPE) ? (uint32_t)M * (uint32_t)(sk.rope_dh / 2) * 8u : 0u, kBufFlags);
     const int parts_out = (N + 31) / 32;
+    // Rotation angles of this lane's accumulator rows: all requested at once, without conditions (a load under a
+    // condition is waited for on the spot); tiles outside the rotated columns read nothing and rotate by zero.
+    float rope_c[EPI == EPI_STORE_ROPE ? MT : 1][16], rope_s[EPI == EPI_STORE_ROPE ? MT : 1][16];
+    if constexpr (EPI == EPI_STORE_ROPE) {
+        const uint32_t t0 = rotated ? ((uint32_t)(m_base + 4 * half) * (uint32_t)(sk.rope_dh / 2) + (uint32_t)(cm0 % sk.rope_dh + (r & 15))) * 8u : kOutOfRange;
+        unsigned int cc[MT][16], ss[MT][16];
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const uint32_t o_ = t0 + (uint32_t)(32 * i + 8 * (e >> 2) + (e & 3)) * (uint32_t)(sk.rope_dh / 2) * 8u;
+                cc[i][e] = __builtin_amdgcn_raw_buffer_load_b32(rcs, o_, 0, 0);
+                ss[i][e] = __builtin_amdgcn_raw_buffer_load_b32(rcs, o_ + 4u, 0, 0);
+            }
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                rope_c[i][e] = rotated ? __builtin_bit_cast(float, cc[i][e]) : 1.f;
+                rope_s[i][e] = rotated ? __builtin_bit_cast(float, ss[i][e]) : 0.f;
+            }
+    }
 #pragma unroll
     for (int j = 0; j < NT; ++j) {
-        const uint32_t n = (uint32_t)(n_base + 32 * j + r);
+        const uint32_t n = EPI == EPI_STORE_ROPE ? (uint32_t)SD_COLMAP(r) : (uint32_t)(n_base + 32 * j + r);
         const uint32_t xgoff = n < (uint32_t)N ? ((uint32_t)(m_base + 4 * half) * (uint32_t)N + n) * 2u : kOutOfRange;
 #pragma unroll
         for (int i = 0; i < MT; ++i) {
@@ -417,6 +457,12 @@ __global__ __launch_bounds__(256, (MT * NT == 1 ? 3 : 1)) void k_linear_mfma(con
                 if constexpr (NF > 0) v = fmaf(na[i][e], v, nb[i][e] * uv[j]);
                 v += bv[j];
                 if constexpr (EPI == EPI_GELU) v = gelu_fast(v);
+                if constexpr (EPI == EPI_STORE_ROPE) {
+                    // lanes r < 16 hold x_i, lanes r >= 16 hold x_{i + dh/2} of the same row: (a c - b s, b c + a s);
+                    // tiles outside the rotated columns got (1, 0) above
+                    const float other = __shfl_xor(v, 16, 64);
+                    v = r < 16 ? v * rope_c[i][e] - other * rope_s[i][e] : v * rope_c[i][e] + other * rope_s[i][e];
+                }
                 if constexpr (kResid) {
                     if constexpr (kPrefetchResid) v += yres[i][j][e];
                     else v += __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(ry, yoff[j] + so, 0, 0));
@@ -465,7 +511,7 @@ static hipError_t launch_variant(const void* x, const void* w, const float* bias
     const int tiles_n = (n + 32 * NT * WN - 1) / (32 * NT * WN), tiles_m = (m + 32 * MT * WM - 1) / (32 * MT * WM);
     // K split over workgroups: only for the one-tile-set-per-workgroup shapes, when the tiles alone cannot
     // fill the chip, keeping at least two chunks per wave, within the workspace.
-    SplitArgs sk{nullptr, nullptr, 1, 0, no.y1, no.y2, no.c1, no.c2, no.ld12};
+    SplitArgs sk{nullptr, nullptr, 1, 0, no.y1, no.y2, no.c1, no.c2, no.ld12, no.rope_cs, no.rope_cols, no.rope_dh};
     if (no.y1 && (NT != 1 || epi != EPI_STORE)) return hipErrorInvalidValue;
     sk.x_stationary = m > n;
     if constexpr (WM * WN == 1) {
@@ -502,6 +548,15 @@ static hipError_t launch_variant(const void* x, const void* w, const float* bias
             launch_kernel(k_linear_mfma<MT, NT, WM, WN, KS, PD, EPI, NF, 0>, dim3(grid), dim3(256), 0, st, x, wb, bias, y, m, n, k, ldy, tiles_m, tiles_n, fi, fo, sk); \
         }                                                                                                               \
     } while (0)
+    if (no.rope_cs) {      // rotary epilogue: few-row tiles with one column tile per wave, plain or RMS-folded input
+        if constexpr (NT == 1 && WM * WN == 1) {
+            if (epi != EPI_STORE || ni.kind == 1) return hipErrorInvalidValue;
+            if (ni.kind == 0) SD_GO(EPI_STORE_ROPE, 0); else SD_GO(EPI_STORE_ROPE, 2);
+            return hipGetLastError();
+        } else {
+            return hipErrorInvalidValue;
+        }
+    }
     if (ni.kind == 0) {
         switch (epi) {
             case EPI_STORE: SD_GO(EPI_STORE, 0); break;
@@ -534,7 +589,7 @@ bool linear_mfma_supported(int dtype, int m, int n, int k, int ldy) {
            ((int64_t)m + 64) * ldy * 4 < lim;
 }
 
-static std::string g_names[8][5][3][2];   // [variant][epilogue][fold][streamed weights]: kernel names as rocprof prints them
+static std::string g_names[8][7][3][2];   // [variant][epilogue][fold][streamed weights]: kernel names as rocprof prints them
 static const char* variant_name(const char* params, int v, int epi, int nfk, int wnt) {
     std::string& s = g_names[v][epi][nfk][wnt];
     if (s.empty()) s = std::string("k_linear_mfma<") + params + "," + std::to_string(epi) + "," + std::to_string(nfk) + "," + std::to_string(wnt) + ">";
@@ -566,7 +621,10 @@ hipError_t launch_linear_mfma(const void* x, const void* w, const float* bias, v
                               const char** kernel_name) {
     if (no.gain && epi != EPI_RESID) return hipErrorInvalidValue;
     if (ni.kind < 0 || ni.kind > 2 || (ni.kind && (epi == EPI_RESID || !ni.stats || ni.parts <= 0))) return hipErrorInvalidValue;
-    const int kepi = no.gain ? (int)EPI_RESID_NORM : epi;
+    const int kepi = no.gain ? (int)EPI_RESID_NORM : (no.rope_cs ? (int)EPI_STORE_ROPE : epi);
+    if (no.rope_cs && (!no.y1 || (no.rope_dh != 64 && no.rope_dh != 128) || no.rope_cols % no.rope_dh || no.rope_cols > n || n % 32 ||
+                       no.c1 % no.rope_dh || no.c2 % no.rope_dh))
+        return hipErrorInvalidValue;                      // the rotary epilogue comes with the column split (q | k | v)
     if (no.y1) {       // a column split exists in the few-row kernel only
         if (epi != EPI_STORE || m > 64 || !no.y2 || no.c1 % 32 || no.c2 % 32 || no.c1 > no.c2 || no.c2 > n || no.ld12 <= 0) return hipErrorInvalidValue;
         switch (choose_variant(m, n, k)) {

@@ -22,6 +22,11 @@
 // the epilogue: deterministic, and nobody waits for anybody.
 //
 // Normalisations folded around the contraction work as in gemm_mfma.hip (FoldIn / FoldOut in mfma_common.hip.h).
+//
+// EPI_SWIGLU (the gated MLP of the Llama-shaped target): W holds the gate rows followed by the up rows; a workgroup
+// takes 64 gate columns and the 64 up columns that belong to them -- waves 0, 1 the gate tiles, waves 2, 3 the up
+// tiles --, the up waves hand their results over through LDS and the gate waves store silu(gate) * up.  The gate / up
+// activations never reach memory and no separate gating kernel runs.  No K split in this form.
 #include <algorithm>
 #include <string>
 
@@ -58,7 +63,11 @@ __global__ __launch_bounds__(256) void k_linear_stream(const bf16_t* __restrict_
     const int blk = (rows_s + (MT == 2 ? 1 : 0)) * 8;             // pieces per chunk block
     const int buf_pieces = S * blk;
 
-    const int tile = blockIdx.x * 4 + wave, n_base = tile * 32;
+    // EPI_SWIGLU: wave -> (column pair 0 / 1, gate / up); W row n_base + r, output column o_base + r of N / 2.
+    const int sw_pair = wave & 1, sw_up = wave >> 1;
+    const int tile = EPI == EPI_SWIGLU ? (int)blockIdx.x * 2 + sw_pair : (int)blockIdx.x * 4 + wave;
+    const int o_base = tile * 32;
+    const int n_base = EPI == EPI_SWIGLU ? o_base + sw_up * (N / 2) : o_base;
     const int n_chunks = K / 64;
     const int c0 = blockIdx.y * sk.split_chunks, nck = min(sk.split_chunks, n_chunks - c0);   // >= 1 (host)
     const int steps = (nck + S - 1) / S;
@@ -110,14 +119,15 @@ __global__ __launch_bounds__(256) void k_linear_stream(const bf16_t* __restrict_
 
     // What the epilogue needs from memory (bias, the residual stream) is requested now as well.
     constexpr bool kResid = EPI == EPI_RESID || EPI == EPI_RESID_NORM;
-    constexpr uint32_t kOutBytes = (EPI == EPI_STORE || EPI == EPI_GELU) ? 2u : 4u;
+    constexpr uint32_t kOutBytes = (EPI == EPI_STORE || EPI == EPI_GELU || EPI == EPI_SWIGLU) ? 2u : 4u;
     const __amdgpu_buffer_rsrc_t ry = __builtin_amdgcn_make_buffer_rsrc(Y, 0, (uint32_t)M * (uint32_t)ldy * kOutBytes, kBufFlags);
     const __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(bias), 0, bias ? (uint32_t)N * 4u : 0u, kBufFlags);
     const __amdgpu_buffer_rsrc_t ru = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(nf.u), 0, (NF == 1) ? (uint32_t)N * 4u : 0u, kBufFlags);
     const __amdgpu_buffer_rsrc_t rgn = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(fo.gain), 0, (EPI == EPI_RESID_NORM) ? (uint32_t)N * 4u : 0u, kBufFlags);
     // Output element (row 32 t + 8 (e/4) + 4 half + e%4, column n_base + r).
     const uint32_t ncol = (uint32_t)(n_base + r);
-    const uint32_t yoff = ncol < (uint32_t)N ? ((uint32_t)(4 * half) * (uint32_t)ldy + ncol) * kOutBytes : kOutOfRange;
+    const uint32_t ocol = (uint32_t)(o_base + r);            // == ncol except for EPI_SWIGLU
+    const uint32_t yoff = ncol < (uint32_t)N ? ((uint32_t)(4 * half) * (uint32_t)ldy + ocol) * kOutBytes : kOutOfRange;
     const float bv = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rb, ncol * 4u, 0, 0));
     const float uv = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(ru, ncol * 4u, 0, 0));
     const float gv = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rgn, ncol * 4u, 0, 0));
@@ -257,7 +267,9 @@ __global__ __launch_bounds__(256) void k_linear_stream(const bf16_t* __restrict_
 #undef SD_FRAG_X
 #undef SD_MMA
     }
-    if (n_base >= N) return;             // wave-uniform; no barrier follows
+    if constexpr (EPI != EPI_SWIGLU) {
+        if (n_base >= N) return;         // wave-uniform; no barrier follows
+    }
 
     // K split across workgroups.  Partials travel as device-scope accesses (past the caches that are private
     // to one XCD): wait until the stores have completed, then draw the ticket.
@@ -311,6 +323,42 @@ __global__ __launch_bounds__(256) void k_linear_stream(const bf16_t* __restrict_
                     for (int e = 0; e < 16; ++e) acc[t][e] += have ? v[j][t][e] : 0.f;
             }
         }
+    }
+
+    if constexpr (EPI == EPI_SWIGLU) {
+        // The up waves park their tiles (normalisation and bias applied) in LDS, the gate waves of the same column pair
+        // pick them up.  The slabs are free once every wave has left the K loop.
+        float* const xch = reinterpret_cast<float*>(slab) + sw_pair * (MT * 16 * 64);
+        __syncthreads();
+        floatx16 val[MT];
+#pragma unroll
+        for (int t = 0; t < MT; ++t)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int lr = 32 * t + 8 * (e >> 2) + (e & 3);
+                float v = acc[t][e];
+                if constexpr (NF > 0) v = fmaf(ab[(lr + 4 * half) * 2 + 0], v, ab[(lr + 4 * half) * 2 + 1] * uv);
+                val[t][e] = v + bv;
+            }
+        if (sw_up) {
+#pragma unroll
+            for (int t = 0; t < MT; ++t)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) xch[(t * 16 + e) * 64 + lane] = val[t][e];
+        }
+        __syncthreads();
+        if (sw_up) return;
+#pragma unroll
+        for (int t = 0; t < MT; ++t)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int lr = 32 * t + 8 * (e >> 2) + (e & 3);
+                const float g = val[t][e], u = xch[(t * 16 + e) * 64 + lane];
+                const float v = g * __builtin_amdgcn_rcpf(1.f + __expf(-g)) * u;       // silu(g) * u; rounded to bf16 below
+                __builtin_amdgcn_raw_buffer_store_b16(__builtin_bit_cast(unsigned short, static_cast<bf16_t>(v)), ry,
+                                                      yoff + (uint32_t)lr * (uint32_t)ldy * 2u, 0, 0);
+            }
+        return;
     }
 
     // Epilogue (one 32-column tile per wave).  Rows >= M fall behind the end of the buffers, columns >= N carry the
@@ -401,7 +449,7 @@ bool linear_stream_preferred(int m, int n, int k, bool folded) {
     return (folded && m <= 32) || (groups >= 160 && groups <= 256) || groups >= 700;
 }
 
-static std::string g_stream_names[3][5][3];
+static std::string g_stream_names[3][6][3];
 static const char* stream_name(int mt, int epi, int nfk) {
     std::string& s = g_stream_names[mt][epi][nfk];
     if (s.empty()) s = "k_linear_stream<" + std::to_string(mt) + "," + std::to_string(epi) + "," + std::to_string(nfk) + ">";
@@ -434,6 +482,7 @@ static hipError_t launch_mt(const dim3& grid, int bytes, hipStream_t st, const b
             case EPI_STORE: SD_GO(EPI_STORE, 0);
             case EPI_GELU: SD_GO(EPI_GELU, 0);
             case EPI_RESID: if (no.gain) SD_GO(EPI_RESID_NORM, 0); else SD_GO(EPI_RESID, 0);
+            case EPI_SWIGLU: SD_GO(EPI_SWIGLU, 0);
             default: SD_GO(EPI_F32, 0);
         }
     } else if (ni.kind == 1) {
@@ -448,6 +497,7 @@ static hipError_t launch_mt(const dim3& grid, int bytes, hipStream_t st, const b
             case EPI_STORE: SD_GO(EPI_STORE, 2);
             case EPI_GELU: SD_GO(EPI_GELU, 2);
             case EPI_F32: SD_GO(EPI_F32, 2);
+            case EPI_SWIGLU: SD_GO(EPI_SWIGLU, 2);
             default: return hipErrorInvalidValue;
         }
     }
@@ -459,15 +509,17 @@ static hipError_t launch_mt(const dim3& grid, int bytes, hipStream_t st, const b
 hipError_t launch_linear_stream(const void* x, const void* w, const float* bias, void* y, int m, int n, int k, int ldy,
                                 int epi, const NormIn& ni, const NormOut& no, const SplitWorkspace& ws, int force_split,
                                 hipStream_t st, const char** kernel_name) {
-    if (epi < 0 || epi > 3) return hipErrorInvalidValue;
+    if (epi < 0 || (epi > 3 && epi != EPI_SWIGLU)) return hipErrorInvalidValue;
     StreamPlan p;
-    if (!plan_stream(m, n, k, ws, force_split, &p)) return hipErrorNotSupported;
+    if (!plan_stream(m, n, k, ws, epi == EPI_SWIGLU ? 1 : force_split, &p)) return hipErrorNotSupported;
+    // gate / up pairs of 64 columns per workgroup, no K split, LayerNorm folds not instantiated
+    if (epi == EPI_SWIGLU && (n % 128 != 0 || p.gsplit != 1 || ni.kind == 1 || no.gain)) return hipErrorNotSupported;
     StreamSplit sk{nullptr, nullptr, p.split_chunks};
     if (p.gsplit > 1) {
         sk.ticket = static_cast<unsigned int*>(ws.base);
         sk.part = reinterpret_cast<float*>(static_cast<char*>(ws.base) + kSplitTicketBytes);
     }
-    const dim3 grid((unsigned)(((n + 31) / 32 + 3) / 4), (unsigned)p.gsplit);
+    const dim3 grid(epi == EPI_SWIGLU ? (unsigned)(n / 128) : (unsigned)(((n + 31) / 32 + 3) / 4), (unsigned)p.gsplit);
     const int bytes = lds_bytes(p.mt, m);
     if (kernel_name) *kernel_name = stream_name(p.mt, no.gain ? (int)EPI_RESID_NORM : epi, ni.kind);
     return p.mt == 1 ? launch_mt<1>(grid, bytes, st, (const bf16_t*)x, (const bf16_t*)w, bias, y, m, n, k, ldy, epi, ni, no, sk)

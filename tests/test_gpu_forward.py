@@ -80,6 +80,30 @@ def test_llama_shape_fp32_and_bf16():
         check_forwards(t, d, [40, 17], 8, 2, seed=seed)
 
 
+def test_llama_shape_bf16_heads_of_64_and_gated_mlp_widths():
+    """Rotary heads of 64 columns (the contraction's epilogue rotates pairs 32 apart) and MLP widths that are and are
+    not a multiple of 64 (the gating runs in the gate | up contraction's epilogue, or in a kernel of its own)."""
+    w = synth.workload("llama8b")
+    for d_ff, seed in ((1024, 14), (1056, 15)):
+        t = synth.shrink(w["target"], n_layer=2, d_model=256, n_head=4, n_kv_head=2, d_ff=d_ff, vocab=1500, n_ctx=128)
+        d = synth.shrink(w["drafter"], n_layer=1, d_model=256, n_head=4, n_kv_head=4, d_ff=512, vocab=1500, n_ctx=128)
+        check_forwards(t, d, [70], 16, 2, seed=seed)            # 17 query rows: one row tile
+        check_forwards(t, d, [33], 40, 2, seed=seed + 2)        # 41 query rows: two row tiles
+
+
+def test_few_query_rows_against_a_long_cache():
+    """Prefixes of ~900 tokens with one or two query tiles (heads of 64 and of 128 columns, grouped-query attention):
+    the four waves of a workgroup share the long key range of a (tile, head)."""
+    w = synth.workload("gpt2s")
+    t = synth.shrink(w["target"], n_layer=2, d_model=256, n_head=4, n_kv_head=4, d_ff=512, vocab=1200, n_ctx=1024)
+    d = synth.shrink(w["drafter"], n_layer=1, d_model=256, n_head=4, n_kv_head=4, d_ff=512, vocab=1200, n_ctx=1024)
+    check_forwards(t, d, [900], 16, 2, seed=21, steps=[1])
+    wl = synth.workload("llama8b")
+    t = synth.shrink(wl["target"], n_layer=2, d_model=512, n_head=4, n_kv_head=2, d_ff=1024, vocab=1200, n_ctx=1024)
+    d = synth.shrink(wl["drafter"], n_layer=1, d_model=256, n_head=4, n_kv_head=4, d_ff=512, vocab=1200, n_ctx=1024)
+    check_forwards(t, d, [930], 40, 2, seed=22, steps=[1])
+
+
 def test_gpt2_small_full_size():
     """The benchmark workload's shapes: 12 layers, d = 768, V = 50257, prefix 256, gamma 16."""
     w = synth.workload("gpt2s")
