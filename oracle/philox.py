@@ -10,12 +10,14 @@ GPU and this oracle consume identical numbers.
   counter = (position k, step j, batch b, stream)
   stream  : DRAFT = 1 -> word 0: unmask decision u_a, word 1: token sample u_b
             VERIFY = 2 -> word 0: acceptance r,      word 1: final-token sample u
+            SPS = 3    -> word 1: token sample of the autoregressive drafter's step k (position k, step 0)
   uniform = (word >> 8) * 2**-24, in [0, 1), exactly representable in fp32
 """
 import numpy as np
 
 STREAM_DRAFT = 1
 STREAM_VERIFY = 2
+STREAM_SPS = 3
 
 _M0 = np.uint64(0xD2511F53)
 _M1 = np.uint64(0xCD9E8D57)

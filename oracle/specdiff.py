@@ -245,3 +245,68 @@ def target_greedy_decode(target_logits, prefix, n_new):
         logits = np.asarray(target_logits(np.array(seq), np.array([len(seq) - 1])), dtype=np.float64)
         seq.append(argmax_f32(logits[0])[0])
     return np.array(seq[len(prefix):], dtype=np.int64)
+
+
+# ---------------------------------------------------------------------------------------
+# Standard speculative decoding (SpS), the paper's baseline (Section 3, "Speculative decoding"; Table 1, row
+# SpS: depth D_p + gamma D_q): the drafter is a small *autoregressive* model that produces the gamma draft
+# tokens one after the other, x_k ~ q_k = M_q(prefix o x_0 .. x_{k-1}); verification is the same
+# (verify_with_uniforms).  And the paper's "sequence initialisation" (Section 4): the first tokens of a
+# generation are produced with SpS, the rest with the diffusion drafter.
+# ---------------------------------------------------------------------------------------
+def sps_draft_with_uniforms(drafter_logits, prefix, gamma, u, greedy=False):
+    """gamma sequential evaluations of a causal drafter.  drafter_logits(tokens, rows) -> logits [len(rows), V]
+    of the causal model at those positions; u: [gamma] uniforms (step k uses u[k]; unused when greedy).
+    Returns (z int64[gamma], q fp32[gamma, V], margins fp64[gamma], n_forwards)."""
+    seq = [int(t) for t in prefix]
+    z = np.zeros(gamma, dtype=np.int64)
+    q = None
+    margins = np.zeros(gamma)
+    for k in range(gamma):
+        logits = np.asarray(drafter_logits(np.array(seq), np.array([len(seq) - 1])), dtype=np.float64)[0]
+        if q is None:
+            q = np.zeros((gamma, logits.size), dtype=np.float64)
+        if greedy:
+            z[k], margins[k] = argmax_f32(logits)
+            q[k, z[k]] = 1.0
+        else:
+            pi = softmax_rows(logits)
+            z[k], margins[k] = invcdf(pi, u[k])
+            q[k] = pi
+        seq.append(int(z[k]))
+    return z, q.astype(np.float32), margins, gamma
+
+
+def sps_uniforms(seed, batch, gamma):
+    return philox.uniforms(seed, philox.STREAM_SPS, batch, 0, np.arange(gamma))[1]
+
+
+def oracle_sps_draft(drafter_logits, prefix, gamma, seed, batch=0):
+    return sps_draft_with_uniforms(drafter_logits, prefix, gamma, sps_uniforms(seed, batch, gamma))
+
+
+def generate_hybrid(sps_logits, drafter_logits, target_logits, prefix, n_new, gamma_sps, gamma, T, seed, mask_id, n_init, greedy):
+    """Sequence initialisation: rounds of SpS (draft length gamma_sps) until at least n_init tokens were emitted, then
+    rounds of SpecDiff (gamma, T) until n_new in all; round i uses seed + i whichever drafter runs it.
+    Returns (tokens emitted, accepted count per round, number of SpS rounds)."""
+    seq = [int(t) for t in prefix]
+    start = len(seq)
+    accepted = []
+    rnd = sps_rounds = 0
+    while len(seq) - start < n_new:
+        use_sps = len(seq) - start < n_init
+        if use_sps:
+            z, q, _, _ = sps_draft_with_uniforms(sps_logits, seq, gamma_sps, sps_uniforms(seed + rnd, 0, gamma_sps), greedy)
+            sps_rounds += 1
+        elif greedy:
+            z, _, _ = oracle_draft_greedy(drafter_logits, seq, gamma, T, seed + rnd, mask_id)
+        else:
+            z, q, _, _ = oracle_draft(drafter_logits, seq, gamma, T, seed + rnd, mask_id)
+        if greedy:
+            n, tok, _ = oracle_verify_greedy(target_logits, seq, z)
+        else:
+            n, tok, _, _ = oracle_verify(target_logits, seq, z, q, seed + rnd)
+        seq += [int(t) for t in z[:n]] + [int(tok)]
+        accepted.append(n)
+        rnd += 1
+    return np.array(seq[start:], dtype=np.int64), np.array(accepted, dtype=np.int64), sps_rounds
