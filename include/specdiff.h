@@ -148,6 +148,39 @@ int32_t sd_set_greedy(sd_handle *h, int32_t enable);
 int32_t sd_set_step_skipping(sd_handle *h, int32_t enable);
 int32_t sd_steps_run(const sd_handle *h);
 
+/* ---- standard speculative decoding (SpS): the paper's baseline and its sequence initialisation ---------------
+ * Section 3, "Speculative decoding", and Table 1, row SpS (depth D_p + gamma D_q): the drafter is a small
+ * autoregressive model that produces the gamma draft tokens one after the other, x_k ~ q_k = M_q(prefix o x_0 ..
+ * x_{k-1}) by inverse CDF with the Philox draw (position k, step 0, sequence b, stream 3) word 1; verification is
+ * sd_verify's.  Section 4, "Sequence initialization": the first tokens of a generation are produced this way, the
+ * rest with the diffusion drafter -- the caller alternates sd_sps_round and sd_round on one handle (both share the
+ * target, its KV cache and sd_commit).
+ *
+ * sd_sps_attach adds the autoregressive drafter to a handle: a causal model (bidirectional = 0) with the target's
+ * vocabulary and storage type whose widths do not exceed the handle's activation buffers (d_model, QKV and MLP widths
+ * at most those of the wider of target and diffusion drafter, no more heads, n_ctx * max_batch rows at most; a
+ * Llama-shaped one only beside a Llama-shaped target).  sps_w: device weights in the layout of sd_weight_desc, borrowed;
+ * workspace: device, 256-byte aligned, sd_sps_workspace_bytes() bytes (its KV cache, folded-norm vectors, row maps),
+ * borrowed for the handle's lifetime.  The drafter keeps a KV cache of its own and brings it up to the prefix by itself
+ * (only the rows it does not hold yet); sd_commit advances it together with the target's. */
+int64_t sd_sps_workspace_bytes(const sd_handle *h, const sd_model_config *sps);
+int32_t sd_sps_attach(sd_handle *h, const sd_model_config *sps, const void *sps_w, void *workspace,
+                      int64_t workspace_bytes);
+/* gamma sequential drafter evaluations.  Outputs as sd_draft: draft_out host [batch, gamma], qtok_out host or NULL,
+ * q_dev_out device fp32 [batch, gamma, ld] (NULL at temperature 0, where x_k is the argmax of its row). */
+int32_t sd_sps_draft(sd_handle *h, int32_t batch, const int32_t *prefix, const int32_t *prefix_len,
+                     int32_t gamma, uint64_t seed, int32_t *draft_out, float *qtok_out,
+                     const float **q_dev_out);
+/* sd_sps_draft followed by the target pass and the acceptance / residual sampling of sd_verify, one
+ * synchronisation at the end.  Same results as the two calls. */
+int32_t sd_sps_round(sd_handle *h, int32_t batch, const int32_t *prefix, const int32_t *prefix_len,
+                     int32_t gamma, uint64_t seed, int32_t *draft_out, int32_t *n_accepted_out,
+                     int32_t *token_out);
+/* Parity hook: next-token logits of the autoregressive drafter after each sequence (tokens: host, back to back,
+ * seq_len[b] tokens each).  logits_dev_out: device fp32 [batch, ld], library-owned. */
+int32_t sd_sps_logits(sd_handle *h, int32_t batch, const int32_t *tokens, const int32_t *seq_len,
+                      const float **logits_dev_out);
+
 /* ---- single steps of the path, for parity checks and profiling --------------------------- */
 
 /* One drafter evaluation M_q(prefix o block, t = step/T) (Algorithm 1, loop body).

@@ -25,7 +25,7 @@ EXPORTS = ["sd_vocab_pad", "sd_weight_count", "sd_weight_desc", "sd_weight_bytes
            "sd_target_logits", "sd_sampling_scratch_bytes", "sd_unmask_sample", "sd_accept_resample", "sd_linear",
            "sd_profile_begin", "sd_profile_end", "sd_profile_count", "sd_profile_entry", "sd_set_graph_replay", "sd_set_linear_variant", "sd_norm_linear",
            "sd_set_linear_split", "sd_linear_split_ticket_bytes", "sd_commit", "sd_set_greedy", "sd_set_step_skipping", "sd_steps_run", "sd_norm_linear_scratch_floats", "sd_linear_resid_norm",
-           "sd_graph_stats", "sd_graph_error", "sd_static_scratch_bytes", "sd_accept_resample_static"]
+           "sd_graph_stats", "sd_graph_error", "sd_sps_workspace_bytes", "sd_sps_attach", "sd_sps_draft", "sd_sps_round", "sd_sps_logits", "sd_static_scratch_bytes", "sd_accept_resample_static"]
 
 
 class SdModelConfig(C.Structure):
@@ -92,6 +92,11 @@ def lib() -> C.CDLL:
         L.sd_linear_split_ticket_bytes.restype = i64; L.sd_linear_split_ticket_bytes.argtypes = []
         L.sd_set_graph_replay.restype = i32; L.sd_set_graph_replay.argtypes = [vp, i32]
         L.sd_set_linear_variant.restype = i32; L.sd_set_linear_variant.argtypes = [i32]
+        L.sd_sps_workspace_bytes.restype = i64; L.sd_sps_workspace_bytes.argtypes = [vp, cfgp]
+        L.sd_sps_attach.restype = i32; L.sd_sps_attach.argtypes = [vp, cfgp, vp, vp, i64]
+        L.sd_sps_draft.restype = i32; L.sd_sps_draft.argtypes = [vp, i32, ip, ip, i32, u64, ip, fp, C.POINTER(vp)]
+        L.sd_sps_round.restype = i32; L.sd_sps_round.argtypes = [vp, i32, ip, ip, i32, u64, ip, ip, ip]
+        L.sd_sps_logits.restype = i32; L.sd_sps_logits.argtypes = [vp, i32, ip, ip, C.POINTER(vp)]
         L.sd_graph_stats.restype = i32
         L.sd_graph_stats.argtypes = [vp, C.POINTER(i64), C.POINTER(i64), C.POINTER(i32), C.POINTER(i32)]
         L.sd_graph_error.restype = C.c_char_p; L.sd_graph_error.argtypes = [vp]
@@ -295,6 +300,71 @@ class SpecDiff:
         tok = np.zeros(B, dtype=np.int32)
         self._check(lib().sd_round(self.h, B, _ip(flat), _ip(lens), gamma, T, seed, _ip(draft), _ip(n), _ip(tok)), "sd_round")
         return draft, n, tok
+
+    # ---- standard speculative decoding: an autoregressive drafter beside the diffusion drafter
+    def sd_sps_attach(self, cfg: ModelConfig, weights: Dict[str, np.ndarray] = None, device_weights=None):
+        torch = self.torch
+        self.sps = cfg
+        self._cs = c_config(cfg)
+        self.sw = device_weights if device_weights is not None else torch.from_numpy(pack_weights(cfg, weights)).to(self.device)
+        nbytes = lib().sd_sps_workspace_bytes(self.h, C.byref(self._cs))
+        if nbytes <= 0:
+            raise SdError(1, "sd_sps_workspace_bytes", "configuration rejected")
+        self.sps_workspace = torch.zeros(nbytes, dtype=torch.uint8, device=self.device)
+        torch.cuda.synchronize(self.device)
+        self._check(lib().sd_sps_attach(self.h, C.byref(self._cs), self.sw.data_ptr(), self.sps_workspace.data_ptr(), nbytes), "sd_sps_attach")
+
+    def sd_sps_draft(self, prefixes, gamma: int, seed: int):
+        """-> (draft int32 [B, gamma], qtok fp32 [B, gamma], q device tensor fp32 [B*gamma, ld] or None)."""
+        flat, lens = _ragged(prefixes)
+        B = len(lens)
+        draft = np.zeros((B, gamma), dtype=np.int32)
+        qtok = np.zeros((B, gamma), dtype=np.float32)
+        qp = C.c_void_p()
+        self._check(lib().sd_sps_draft(self.h, B, _ip(flat), _ip(lens), gamma, seed, _ip(draft),
+                                       qtok.ctypes.data_as(C.POINTER(C.c_float)), C.byref(qp)), "sd_sps_draft")
+        return draft, qtok, (self._view(qp.value, B * gamma) if qp.value else None)
+
+    def sd_sps_round(self, prefixes, gamma: int, seed: int):
+        flat, lens = _ragged(prefixes)
+        return self.sd_sps_round_flat(flat, lens, gamma, seed)
+
+    def sd_sps_round_flat(self, flat: np.ndarray, lens: np.ndarray, gamma: int, seed: int):
+        B = len(lens)
+        draft = np.zeros((B, gamma), dtype=np.int32)
+        n = np.zeros(B, dtype=np.int32)
+        tok = np.zeros(B, dtype=np.int32)
+        self._check(lib().sd_sps_round(self.h, B, _ip(flat), _ip(lens), gamma, seed, _ip(draft), _ip(n), _ip(tok)), "sd_sps_round")
+        return draft, n, tok
+
+    def sd_sps_logits(self, sequences):
+        """Next-token logits of the autoregressive drafter after each sequence -> device fp32 [B, ld]."""
+        flat, lens = _ragged(sequences)
+        p = C.c_void_p()
+        self._check(lib().sd_sps_logits(self.h, len(lens), _ip(flat), _ip(lens), C.byref(p)), "sd_sps_logits")
+        return self._view(p.value, len(lens))
+
+    def generate_hybrid(self, prefixes, n_new: int, gamma_sps: int, gamma: int, T: int, seed: int, n_init: int):
+        """Sequence initialisation: rounds of sd_sps_round until every sequence has n_init new tokens, then rounds of
+        sd_round, until n_new; round i uses seed + i; sd_commit after every round.
+        -> (new tokens per sequence, accepted counts [rounds, B], number of SpS rounds)."""
+        seqs = [list(int(t) for t in p) for p in prefixes]
+        start = [len(s) for s in seqs]
+        accepted = []
+        rnd = sps_rounds = 0
+        while min(len(s) - l for s, l in zip(seqs, start)) < n_new:
+            if min(len(s) - l for s, l in zip(seqs, start)) < n_init:
+                draft, n, tok = self.sd_sps_round(seqs, gamma_sps, seed + rnd)
+                sps_rounds += 1
+            else:
+                draft, n, tok = self.sd_round(seqs, gamma, T, seed + rnd)
+            self.sd_commit(n)
+            for b, s in enumerate(seqs):
+                s.extend(int(t) for t in draft[b, :n[b]])
+                s.append(int(tok[b]))
+            accepted.append(n.copy())
+            rnd += 1
+        return [np.array(s[l:], dtype=np.int64) for s, l in zip(seqs, start)], accepted, sps_rounds
 
     def sd_commit(self, n_accepted):
         n = np.ascontiguousarray(n_accepted, dtype=np.int32)

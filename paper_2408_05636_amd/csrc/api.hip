@@ -106,6 +106,7 @@ struct Model {
     float *fu_head = nullptr, *fv_head = nullptr;   // final LayerNorm folded into the LM head: u = W g, v = W beta
     std::vector<Layer> L;
     bool fold = false;       // norms in front of QKV / MLP-up are folded into those contractions
+    void *kcache = nullptr, *vcache = nullptr;   // causal models: [layer][sequence][n_ctx][n_kv_head * d_head] each
 };
 
 bool bind_model(Model& m, const sd_model_config& c, const void* base) {
@@ -318,6 +319,7 @@ struct sd_handle {
     std::string graph_error;             // what failed
     bool greedy = false;                 // temperature 0 instead of the stochastic rule
     bool skip_idle_steps = false;        // leave out the drafter forwards of steps that reveal no slot (sd_set_step_skipping)
+    bool last_draft_sps = false;         // the last drafting call was sd_sps_draft
     int steps_run = 0;                   // drafter forwards of the last sd_draft / sd_round
     int temb_T = 0;                      // number of steps the timestep-embedding table in the workspace was built for
     bool head_folded = false;            // the last run_layers left x and row sums for the final normalisation (run_head folds it)
@@ -327,6 +329,16 @@ struct sd_handle {
     // what the last verification scored, for sd_commit: per sequence the prefix length and its last token, and the draft
     int pend_batch = 0, pend_gamma = 0;
     std::vector<int32_t> pend_len, pend_tail, pend_draft;
+    // Standard speculative decoding (sd_sps_attach): a small causal drafter with a KV cache of its own
+    bool has_sps = false;
+    Model sps;
+    std::vector<int32_t> sps_cached_len;      // per sequence: positions of the drafter's cache that hold tokens of ...
+    std::vector<uint64_t> sps_cached_fnv;     // ... a token string with this running hash
+    int64_t sps_map_cap = 0;                  // bytes of one step's row maps
+    std::vector<char*> sps_dev, sps_stage;    // row maps: slot 0 = catch-up rows, slot 1 + k = step k (device / pinned host)
+    std::vector<MapSet> sps_ms;
+    std::vector<std::vector<char>> sps_shadow;
+    bool pend_sps = false;                    // the pending verification's draft came from the autoregressive drafter
     std::string err;
 };
 
@@ -439,15 +451,27 @@ int check_batch(sd_handle* h, int batch, const int32_t* tokens, const int32_t* l
 }
 
 // Build and upload the packed row maps of one forward.  mode 0: drafter over prefix o block;
-// 1: target query rows (last prefix token + gamma draft tokens); 2: target prefill rows [0, L-1).
+// 1: target query rows (last prefix token + gamma draft tokens); 2: target prefill rows [0, L-1);
+// 3: step k of the autoregressive drafter (one row per sequence: position L - 1 + k, whose token is the last prefix
+// token for k = 0 and draft token k - 1 otherwise); 4: rows [start[b], L - 1) of the autoregressive drafter (the part
+// of the prefix its cache does not hold yet).
 // The upload is skipped when the device buffer already holds exactly these maps (same prefix,
 // same shapes as the previous call of this mode).
 int upload_rows(sd_handle* h, int mode, int batch, const int32_t* tokens, const int32_t* len, int64_t n_tokens,
-                int gamma) {
-    const Model& m = mode == 0 ? h->drafter : h->target;
+                int gamma, int k = 0, const int32_t* start = nullptr) {
+    const Model& m = mode == 0 ? h->drafter : (mode >= 3 ? h->sps : h->target);
+    auto rows_of = [&](int b) -> int64_t {
+        switch (mode) {
+            case 0: return len[b] + gamma;
+            case 1: return gamma + 1;
+            case 2: return len[b] - 1;
+            case 3: return 1;
+            default: return len[b] - 1 - start[b];
+        }
+    };
     int64_t rows = 0, n_tiles = 0;
     for (int b = 0; b < batch; ++b) {
-        const int64_t rb = mode == 0 ? len[b] + gamma : (mode == 1 ? gamma + 1 : len[b] - 1);
+        const int64_t rb = rows_of(b);
         rows += rb;
         n_tiles += (rb + 31) / 32;
     }
@@ -466,7 +490,9 @@ int upload_rows(sd_handle* h, int mode, int batch, const int32_t* tokens, const 
     o += n_tiles * (int64_t)sizeof(AttnTile);
     o = align_up(o, 16);
     const int64_t o_order = o;            // filled below, its size depends on the grouping
-    char* hb = h->stage_maps[mode];
+    const int sps_slot = mode == 3 ? 1 + k : 0;
+    char* hb = mode >= 3 ? h->sps_stage[sps_slot] : h->stage_maps[mode];
+    const int64_t map_cap = mode == 3 ? h->sps_map_cap : h->lim.map_bytes;
     // Attention launch order.  Workgroups go to the 8 XCDs round-robin by linear id and every XCD has its own
     // L2: all query tiles and query heads that read the same keys and values (one sequence, one KV head) are
     // placed on one XCD, back to back, so that K and V are fetched into one L2 once instead of into all of
@@ -477,12 +503,12 @@ int upload_rows(sd_handle* h, int mode, int batch, const int32_t* tokens, const 
     bool grouped_order = false;
     {
         double kv_bytes = 0;
-        for (int b = 0; b < batch; ++b) kv_bytes += 2.0 * m.ew * m.dkv * (mode == 0 ? len[b] + gamma : (mode == 1 ? len[b] + gamma : len[b] - 1));
+        for (int b = 0; b < batch; ++b) kv_bytes += 2.0 * m.ew * m.dkv * (mode == 2 || mode == 4 ? len[b] - 1 : len[b] + gamma);
         const bool grouped = kv_bytes > 2.0e6;
         grouped_order = grouped;
         int64_t t0 = 0, lin = 0;
         for (int b = 0; b < batch; ++b) {
-            const int64_t rb = mode == 0 ? len[b] + gamma : (mode == 1 ? gamma + 1 : len[b] - 1);
+            const int64_t rb = rows_of(b);
             const int64_t ntb = (rb + 31) / 32;
             for (int g = 0; g < n_kv_groups; ++g)
                 for (int qh = 0; qh < q_per_kv; ++qh)
@@ -508,7 +534,7 @@ int upload_rows(sd_handle* h, int mode, int batch, const int32_t* tokens, const 
     const int64_t o_groups = o, n_groups = 8 * (int64_t)grp_max;
     o += n_groups * 4;
     const int64_t bytes = o;
-    if (bytes > h->lim.map_bytes || n_tiles >= (1 << 18)) return fail(h, SD_ERR_SHAPE, "row maps exceed the workspace");
+    if (bytes > map_cap || n_tiles >= (1 << 18)) return fail(h, SD_ERR_SHAPE, "row maps exceed the workspace");
     int32_t *s_tok = (int32_t*)(hb + o_tok), *s_src = (int32_t*)(hb + o_src), *s_pos = (int32_t*)(hb + o_pos),
             *s_seq = (int32_t*)(hb + o_seq), *s_kvl = (int32_t*)(hb + o_kvl), *s_blk = (int32_t*)(hb + o_blk);
     int64_t* s_off = (int64_t*)(hb + o_off);
@@ -553,8 +579,18 @@ int upload_rows(sd_handle* h, int mode, int batch, const int32_t* tokens, const 
             }
             if (L + gamma > max_kv) max_kv = L + gamma;
             kv_rows += L + gamma;
+        } else if (mode == 3) {
+            s_src[r] = k == 0 ? (int32_t)(tok_off + L - 1) : -(b * gamma + k - 1) - 1;
+            s_pos[r] = L - 1 + k;
+            s_seq[r] = b;
+            s_kvl[r] = L + k;
+            s_off[r] = (int64_t)b * m.c.n_ctx * m.dkv;
+            kv_sum += L + k;
+            ++r;
+            if (L + k > max_kv) max_kv = L + k;
+            kv_rows += L + k;
         } else {
-            for (int p = 0; p < L - 1; ++p, ++r) {
+            for (int p = mode == 4 ? start[b] : 0; p < L - 1; ++p, ++r) {
                 s_src[r] = (int32_t)(tok_off + p);
                 s_pos[r] = p;
                 s_seq[r] = b;
@@ -575,23 +611,23 @@ int upload_rows(sd_handle* h, int mode, int batch, const int32_t* tokens, const 
         }
         tok_off += L;
     }
-    MapSet& ms = h->maps[mode];
-    std::vector<char>& shadow = h->map_shadow[mode];
+    MapSet& ms = mode >= 3 ? h->sps_ms[sps_slot] : h->maps[mode];
+    std::vector<char>& shadow = mode >= 3 ? h->sps_shadow[sps_slot] : h->map_shadow[mode];
+    char* db = mode >= 3 ? h->sps_dev[sps_slot] : h->buf.maps[mode];
     const bool same = ms.bytes == bytes && (int64_t)shadow.size() == bytes && memcmp(shadow.data(), hb, bytes) == 0;
     if (!same) {
-        if (bytes > 0) SD_HIP(h, hipMemcpyAsync(h->buf.maps[mode], hb, bytes, hipMemcpyHostToDevice, h->st));
+        if (bytes > 0) SD_HIP(h, hipMemcpyAsync(db, hb, bytes, hipMemcpyHostToDevice, h->st));
         shadow.assign(hb, hb + bytes);
     }
-    char* db = h->buf.maps[mode];
     ms.tokens = (int32_t*)(db + o_tok); ms.src = (int32_t*)(db + o_src); ms.pos = (int32_t*)(db + o_pos);
     ms.seq = (int32_t*)(db + o_seq); ms.kvl = (int32_t*)(db + o_kvl);
     ms.blk = (int32_t*)(db + o_blk); ms.kv_off = (int64_t*)(db + o_off); ms.tiles = (AttnTile*)(db + o_tiles);
     ms.order = (int32_t*)(db + o_order); ms.n_order = (int)n_order;
     ms.groups = (int32_t*)(db + o_groups); ms.n_groups = (int)n_groups; ms.group_tiles = group_tiles;
     ms.rows = (int)rows; ms.n_tiles = (int)n_tiles; ms.max_kv = max_kv; ms.kv_sum = kv_sum; ms.kv_rows = kv_rows;
-    ms.head_row0 = mode == 1 ? 0 : (mode == 0 && batch == 1 ? len[0] : -1);   // target: all rows; drafter: the block of a single sequence
+    ms.head_row0 = (mode == 1 || mode == 3) ? 0 : (mode == 0 && batch == 1 ? len[0] : -1);   // target, autoregressive step: all rows; drafter: the block of a single sequence
     ms.regular = mode == 0 && batch == 1;
-    ms.kv_row0 = mode == 1 && batch == 1 ? len[0] - 1 : -1;
+    ms.kv_row0 = (mode == 1 || mode == 3) && batch == 1 ? len[0] - 1 + k : -1;
     ms.grouped = grouped_order;
     ms.bytes = bytes;
     return SD_OK;
@@ -728,8 +764,8 @@ int run_layers(sd_handle* h, const Model& m, const MapSet& rm, const float* temb
     for (int i = 0; i < c.n_layer; ++i) {
         const Layer& l = m.L[i];
         const int64_t per_layer = cached ? (int64_t)h->max_batch * c.n_ctx * m.dkv * m.ew : 0;
-        char* const kc = cached ? static_cast<char*>(B.kcache) + i * per_layer : nullptr;
-        char* const vc = cached ? static_cast<char*>(B.vcache) + i * per_layer : nullptr;
+        char* const kc = cached ? static_cast<char*>(m.kcache) + i * per_layer : nullptr;
+        char* const vc = cached ? static_cast<char*>(m.vcache) + i * per_layer : nullptr;
         if (fold) {
             NormOut qkv_out;
             if (kv_direct) {
@@ -850,8 +886,9 @@ int do_prefill(sd_handle* h, int batch, const int32_t* prefix, const int32_t* le
 }
 
 // Remember what a verification scored (the cache now also holds the K, V rows of prefix[L-1] and the draft).
-void note_pending(sd_handle* h, int batch, const int32_t* prefix, const int32_t* len, int gamma, const int32_t* draft) {
+void note_pending(sd_handle* h, int batch, const int32_t* prefix, const int32_t* len, int gamma, const int32_t* draft, bool from_sps = false) {
     h->pend_batch = batch;
+    h->pend_sps = from_sps;
     h->pend_gamma = gamma;
     h->pend_len.assign(len, len + batch);
     h->pend_tail.resize(batch);
@@ -999,6 +1036,121 @@ int read_back(sd_handle* h, int32_t* dst, const int32_t* dev, int64_t n) {
     return SD_OK;
 }
 
+
+// LayerNorms in front of QKV / MLP-up / LM head folded into those contractions: u = W g, v = W beta + bias into p
+// (fold_floats(config) floats).  RMSNorm models need no vectors.
+bool fold_model(Model& m, float* p, hipStream_t st) {
+    m.fold = m.c.dtype == SD_DTYPE_BF16;
+    if (!m.fold || m.c.arch != SD_ARCH_GPT2) return true;
+    const int qkv = m.dq + 2 * m.dkv, F = m.c.d_ff, d = m.c.d_model;
+    for (Layer& l : m.L) {
+        l.fu_qkv = p; p += align_up(qkv, 64);
+        l.fv_qkv = p; p += align_up(qkv, 64);
+        l.fu_fc = p; p += align_up(F, 64);
+        l.fv_fc = p; p += align_up(F, 64);
+        if (launch_fold_norm(l.w_qkv, l.ln1_g, l.ln1_b, l.b_qkv, l.fu_qkv, l.fv_qkv, qkv, d, st) != hipSuccess ||
+            launch_fold_norm(l.w_fc, l.ln2_g, l.ln2_b, l.b_fc, l.fu_fc, l.fv_fc, F, d, st) != hipSuccess)
+            return false;
+    }
+    m.fu_head = p; p += align_up(m.c.vocab, 64);
+    m.fv_head = p; p += align_up(m.c.vocab, 64);
+    return launch_fold_norm(m.w_head, m.lnf_g, m.lnf_b, nullptr, m.fu_head, m.fv_head, m.c.vocab, d, st) == hipSuccess;
+}
+
+// ------------------------------------------------------------------------------------------
+// standard speculative decoding: the autoregressive drafter
+// ------------------------------------------------------------------------------------------
+int64_t sps_step_map_bytes(int max_batch, int heads, int64_t prefix_cap) {
+    const int64_t mb = max_batch;
+    return align_up((prefix_cap + 6 * mb) * 4 + 64 + mb * 8 + mb * (int64_t)sizeof(AttnTile) + 64 + 2 * 8 * (mb + 1) * heads * 4, 256);
+}
+
+struct SpsCarve { void *kcache, *vcache; float* fold; std::vector<char*> maps; int64_t step_bytes; };
+
+int64_t carve_sps(Arena& a, SpsCarve& out, const sd_model_config& c, const Limits& lim, int max_batch, int gamma_max) {
+    const int64_t cache = (int64_t)c.n_layer * max_batch * c.n_ctx * c.n_kv_head * (c.d_model / c.n_head);
+    const int ew = c.dtype == SD_DTYPE_BF16 ? 2 : 4;
+    out.kcache = a.take<char>(cache, ew);
+    out.vcache = a.take<char>(cache, ew);
+    out.fold = a.take<float>(fold_floats(c));
+    out.step_bytes = sps_step_map_bytes(max_batch, c.n_head, lim.prefix_cap);
+    out.maps.clear();
+    out.maps.push_back(a.take<char>(lim.map_bytes));                      // catch-up rows
+    for (int k = 0; k < gamma_max; ++k) out.maps.push_back(a.take<char>(out.step_bytes));
+    return a.off;
+}
+
+bool sps_config_ok(const sd_handle* h, const sd_model_config* c) {
+    if (!config_ok(c) || c->bidirectional) return false;
+    const sd_model_config& t = h->target.c;
+    const int64_t qkv = (int64_t)c->d_model + 2 * (int64_t)c->n_kv_head * (c->d_model / c->n_head);
+    const int64_t ff = (int64_t)c->d_ff * (c->arch == SD_ARCH_LLAMA ? 2 : 1);
+    const int heads = std::max(h->target.c.n_head, h->drafter.c.n_head);
+    return c->vocab == t.vocab && c->dtype == t.dtype && c->d_model <= h->lim.dmax && qkv <= h->lim.qkvmax && ff <= h->lim.ffmax &&
+           (int64_t)h->max_batch * c->n_ctx <= h->lim.max_rows && c->n_head <= heads && h->gamma_max < c->n_ctx &&
+           (c->arch != SD_ARCH_LLAMA || t.arch == SD_ARCH_LLAMA);            // the gated-MLP scratch exists for Llama-shaped targets only
+}
+
+// Bring the autoregressive drafter's cache up to tokens [0, L - 1) of every sequence: only the rows it does not hold yet
+// (after a committed round: none, or the one row of the last accepted draft token).
+int sps_catch_up(sd_handle* h, int batch, const int32_t* prefix, const int32_t* len, int64_t n_tokens) {
+    std::vector<int32_t> start(batch);
+    bool any = false;
+    int64_t off = 0;
+    for (int b = 0; b < batch; ++b) {
+        const int c = h->sps_cached_len[b];
+        start[b] = (c >= 0 && c <= len[b] - 1 && fnv_extend(kFnvBasis, prefix + off, c) == h->sps_cached_fnv[b]) ? c : 0;
+        any = any || start[b] < len[b] - 1;
+        off += len[b];
+    }
+    if (!any) return SD_OK;
+    int rc = upload_rows(h, 4, batch, prefix, len, n_tokens, 0, 0, start.data());
+    if (rc) return rc;
+    h->prof.phase = "prefill:";
+    rc = run_layers(h, h->sps, h->sps_ms[0], nullptr);
+    if (rc) return rc;
+    off = 0;
+    for (int b = 0; b < batch; ++b) {
+        h->sps_cached_len[b] = len[b] - 1;
+        h->sps_cached_fnv[b] = fnv_extend(kFnvBasis, prefix + off, len[b] - 1);
+        off += len[b];
+    }
+    return SD_OK;
+}
+
+// Everything the gamma sequential steps need on the device before their launches: the drafter's cache, the row maps of
+// every step, the seed.
+int prepare_sps(sd_handle* h, int batch, const int32_t* prefix, const int32_t* len, int64_t n_tokens, int gamma, uint64_t seed) {
+    for (int b = 0; b < batch; ++b)
+        if (len[b] + gamma > h->sps.c.n_ctx) return fail(h, SD_ERR_SHAPE, "prefix + gamma exceeds the autoregressive drafter's context");
+    int rc = sps_catch_up(h, batch, prefix, len, n_tokens);
+    for (int k = 0; k < gamma && !rc; ++k) rc = upload_rows(h, 3, batch, prefix, len, k == 0 ? n_tokens : 0, gamma, k);
+    if (rc) return rc;
+    h->stage_seed[0] = seed;
+    SD_HIP(h, hipMemcpyAsync(h->buf.seed, h->stage_seed, 8, hipMemcpyHostToDevice, h->st));
+    return SD_OK;
+}
+
+// The gamma sequential drafter evaluations (launches only: capturable): step k scores the one new row of every
+// sequence against the drafter's cache, and its token is sampled on the device before step k + 1 embeds it.
+int enqueue_sps_draft(sd_handle* h, int batch, int gamma) {
+    Buffers& B = h->buf;
+    const Model& m = h->sps;
+    h->prof.phase = "draft:";
+    const SampleScratch ss = sampling_scratch(B.sample_scratch, (int)h->lim.rows_head, m.c.vocab);
+    for (int k = 0; k < gamma; ++k) {
+        const MapSet& rm = h->sps_ms[1 + k];
+        int rc = run_layers(h, m, rm, nullptr, batch);
+        if (rc) return rc;
+        rc = run_head(h, m, nullptr, rm.head_row0, batch, B.logits_d);
+        if (rc) return rc;
+        SD_LAUNCH(h, h->greedy ? "sps_sample(k_chunk_argmax+k_greedy_reveal)" : "sps_sample(k_row_stats+k_unmask_sample)",
+                  (h->greedy ? 1.0 : 3.0) * batch * m.ld * 4, 0,
+                  launch_sps_sample(B.logits_d, batch, gamma, m.c.vocab, k, B.seed, B.z, B.q, B.qtok, h->greedy, ss, h->st));
+    }
+    return SD_OK;
+}
+
 }  // namespace
 
 // ------------------------------------------------------------------------------------------
@@ -1113,31 +1265,11 @@ int32_t sd_create(const sd_model_config* target, const sd_model_config* drafter,
         return SD_ERR_HIP;
     }
     // Fold the LayerNorms in front of QKV and MLP-up into those contractions (bf16 models): u = W g, v = W beta + bias.
-    for (int which = 0; which < 2; ++which) {
-        Model& m = which ? h->drafter : h->target;
-        m.fold = m.c.dtype == SD_DTYPE_BF16;
-        if (!m.fold || m.c.arch != SD_ARCH_GPT2) continue;
-        float* p = which ? h->buf.fold_d : h->buf.fold_t;
-        const int qkv = m.dq + 2 * m.dkv, F = m.c.d_ff, d = m.c.d_model;
-        for (Layer& l : m.L) {
-            l.fu_qkv = p; p += align_up(qkv, 64);
-            l.fv_qkv = p; p += align_up(qkv, 64);
-            l.fu_fc = p; p += align_up(F, 64);
-            l.fv_fc = p; p += align_up(F, 64);
-            if (launch_fold_norm(l.w_qkv, l.ln1_g, l.ln1_b, l.b_qkv, l.fu_qkv, l.fv_qkv, qkv, d, static_cast<hipStream_t>(hip_stream)) != hipSuccess ||
-                launch_fold_norm(l.w_fc, l.ln2_g, l.ln2_b, l.b_fc, l.fu_fc, l.fv_fc, F, d, static_cast<hipStream_t>(hip_stream)) != hipSuccess) {
-                g_create_error = "launch of the norm-folding kernel failed";
-                delete h;
-                return SD_ERR_HIP;
-            }
-        }
-        m.fu_head = p; p += align_up(m.c.vocab, 64);
-        m.fv_head = p; p += align_up(m.c.vocab, 64);
-        if (launch_fold_norm(m.w_head, m.lnf_g, m.lnf_b, nullptr, m.fu_head, m.fv_head, m.c.vocab, d, static_cast<hipStream_t>(hip_stream)) != hipSuccess) {
-            g_create_error = "launch of the norm-folding kernel failed";
-            delete h;
-            return SD_ERR_HIP;
-        }
+    if (!fold_model(h->target, h->buf.fold_t, static_cast<hipStream_t>(hip_stream)) ||
+        !fold_model(h->drafter, h->buf.fold_d, static_cast<hipStream_t>(hip_stream))) {
+        g_create_error = "launch of the norm-folding kernel failed";
+        delete h;
+        return SD_ERR_HIP;
     }
     if (hipStreamSynchronize(static_cast<hipStream_t>(hip_stream)) != hipSuccess) {
         g_create_error = "norm folding failed";
@@ -1145,6 +1277,8 @@ int32_t sd_create(const sd_model_config* target, const sd_model_config* drafter,
         return SD_ERR_HIP;
     }
     { void* fixed = nullptr; (void)static_scratch(&fixed); }     // set-up of the allocation-free entry point on this device (it retries by itself if this failed)
+    h->target.kcache = h->buf.kcache;
+    h->target.vcache = h->buf.vcache;
     h->lim = limits_of(*target, *drafter, max_batch, gamma_max);
     h->max_batch = max_batch;
     h->gamma_max = gamma_max;
@@ -1183,6 +1317,7 @@ void sd_destroy(sd_handle* h) {
     if (h->stage_z) (void)hipHostFree(h->stage_z);
     if (h->stage_out) (void)hipHostFree(h->stage_out);
     if (h->stage_f) (void)hipHostFree(h->stage_f);
+    for (char* p : h->sps_stage) if (p) (void)hipHostFree(p);
     delete h;
 }
 
@@ -1222,6 +1357,7 @@ int32_t sd_draft(sd_handle* h, int32_t batch, const int32_t* prefix, const int32
     memcpy(draft_out, h->stage_out, cnt * 4);
     if (qtok_out) memcpy(qtok_out, h->stage_f, cnt * 4);
     if (q_dev_out) *q_dev_out = h->greedy ? nullptr : h->buf.q;      // temperature 0 produces no q
+    h->last_draft_sps = false;
     return SD_OK;
 }
 
@@ -1252,7 +1388,7 @@ int32_t sd_verify(sd_handle* h, int32_t batch, const int32_t* prefix, const int3
     if (rc) return rc;
     rc = read_back(h, token_out, h->buf.tok, batch);
     if (rc) return rc;
-    note_pending(h, batch, prefix, prefix_len, gamma, draft);
+    note_pending(h, batch, prefix, prefix_len, gamma, draft, h->last_draft_sps);
     return SD_OK;
 }
 
@@ -1313,6 +1449,17 @@ int32_t sd_commit(sd_handle* h, int32_t batch, const int32_t* n_accepted) {
         h->cached_fnv[b] = x;
         h->cached_len[b] = h->pend_len[b] + n_accepted[b];
         h->cached_hash[b] = x ^ (uint64_t)h->cached_len[b];
+    }
+    if (h->has_sps && h->pend_sps) {
+        // the autoregressive drafter's cache holds the rows of the last prefix token and of draft[0 .. gamma - 1)
+        for (int b = 0; b < batch; ++b) {
+            if (h->sps_cached_len[b] != h->pend_len[b] - 1) continue;                // not the string this round extended
+            const int keep = std::min(n_accepted[b], h->pend_gamma - 1);
+            uint64_t x = fnv_extend(h->sps_cached_fnv[b], &h->pend_tail[b], 1);
+            x = fnv_extend(x, h->pend_draft.data() + (int64_t)b * h->pend_gamma, keep);
+            h->sps_cached_fnv[b] = x;
+            h->sps_cached_len[b] = h->pend_len[b] + keep;
+        }
     }
     h->pend_batch = 0;
     return SD_OK;
@@ -1390,6 +1537,125 @@ int32_t sd_target_logits(sd_handle* h, int32_t batch, const int32_t* prefix, con
     if (rc) return rc;
     { const int rc_ = sync_stream(h); if (rc_) return rc_; }
     *logits_dev_out = h->buf.logits_t;
+    return SD_OK;
+}
+
+int64_t sd_sps_workspace_bytes(const sd_handle* h, const sd_model_config* sps) {
+    if (!h || !sps_config_ok(h, sps)) return 0;
+    Arena a(nullptr);
+    SpsCarve c;
+    return carve_sps(a, c, *sps, h->lim, h->max_batch, h->gamma_max);
+}
+
+int32_t sd_sps_attach(sd_handle* h, const sd_model_config* sps, const void* sps_w, void* workspace, int64_t workspace_bytes) {
+    if (!h) return SD_ERR_ARG;
+    if (!sps || !sps_w || !workspace) return fail(h, SD_ERR_ARG, "null argument");
+    if (h->has_sps) return fail(h, SD_ERR_STATE, "an autoregressive drafter is already attached");
+    if (!sps_config_ok(h, sps)) return fail(h, SD_ERR_ARG, "autoregressive drafter must be causal, share vocabulary and storage type with the target and fit the handle's activation buffers");
+    if ((reinterpret_cast<uintptr_t>(workspace) & 255) || (reinterpret_cast<uintptr_t>(sps_w) & 255)) return fail(h, SD_ERR_WORKSPACE, "misaligned buffer");
+    Arena a(workspace);
+    SpsCarve c;
+    if (carve_sps(a, c, *sps, h->lim, h->max_batch, h->gamma_max) > workspace_bytes) return fail(h, SD_ERR_WORKSPACE, "workspace too small");
+    if (!bind_model(h->sps, *sps, sps_w)) return fail(h, SD_ERR_ARG, "weight layout");
+    h->sps.kcache = c.kcache;
+    h->sps.vcache = c.vcache;
+    if (!fold_model(h->sps, c.fold, h->st)) return fail(h, SD_ERR_HIP, "launch of the norm-folding kernel failed");
+    SD_HIP(h, hipStreamSynchronize(h->st));
+    h->sps_map_cap = c.step_bytes;
+    h->sps_dev = c.maps;
+    h->sps_stage.assign(c.maps.size(), nullptr);
+    for (size_t i = 0; i < c.maps.size(); ++i) {
+        const hipError_t e = hipHostMalloc(reinterpret_cast<void**>(&h->sps_stage[i]), i == 0 ? h->lim.map_bytes : c.step_bytes, hipHostMallocDefault);
+        if (e != hipSuccess) {
+            for (char* p : h->sps_stage) if (p) (void)hipHostFree(p);
+            h->sps_stage.clear();
+            h->err = std::string("hipHostMalloc: ") + hipGetErrorString(e);
+            return SD_ERR_HIP;
+        }
+    }
+    h->sps_ms.assign(c.maps.size(), MapSet());
+    h->sps_shadow.assign(c.maps.size(), std::vector<char>());
+    h->sps_cached_len.assign(h->max_batch, -1);
+    h->sps_cached_fnv.assign(h->max_batch, 0);
+    h->has_sps = true;
+    return SD_OK;
+}
+
+int32_t sd_sps_draft(sd_handle* h, int32_t batch, const int32_t* prefix, const int32_t* prefix_len, int32_t gamma,
+                     uint64_t seed, int32_t* draft_out, float* qtok_out, const float** q_dev_out) {
+    int64_t n;
+    int rc = check_batch(h, batch, prefix, prefix_len, h ? h->target.c.vocab : 0, &n);
+    if (rc) return rc;
+    if (!h->has_sps) return fail(h, SD_ERR_STATE, "no autoregressive drafter attached (sd_sps_attach)");
+    if (!draft_out) return fail(h, SD_ERR_ARG, "draft_out is null");
+    rc = check_round_shapes(h, batch, prefix_len, gamma);
+    if (rc) return rc;
+    rc = prepare_sps(h, batch, prefix, prefix_len, n, gamma, seed);
+    if (rc) return rc;
+    h->steps_run = gamma;
+    rc = replay(h, shape_key(9 + (h->greedy ? 16 : 0), batch, gamma, 0, prefix_len, nullptr), [&] { return enqueue_sps_draft(h, batch, gamma); });
+    if (rc) return rc;
+    const int64_t cnt = (int64_t)batch * gamma;
+    SD_HIP(h, hipMemcpyAsync(h->stage_out, h->buf.z, cnt * 4, hipMemcpyDeviceToHost, h->st));
+    SD_HIP(h, hipMemcpyAsync(h->stage_f, h->buf.qtok, cnt * 4, hipMemcpyDeviceToHost, h->st));
+    { const int rc_ = sync_stream(h); if (rc_) return rc_; }
+    memcpy(draft_out, h->stage_out, cnt * 4);
+    if (qtok_out) memcpy(qtok_out, h->stage_f, cnt * 4);
+    if (q_dev_out) *q_dev_out = h->greedy ? nullptr : h->buf.q;
+    h->last_draft_sps = true;
+    return SD_OK;
+}
+
+int32_t sd_sps_round(sd_handle* h, int32_t batch, const int32_t* prefix, const int32_t* prefix_len, int32_t gamma,
+                     uint64_t seed, int32_t* draft_out, int32_t* n_accepted_out, int32_t* token_out) {
+    int64_t n;
+    int rc = check_batch(h, batch, prefix, prefix_len, h ? h->target.c.vocab : 0, &n);
+    if (rc) return rc;
+    if (!h->has_sps) return fail(h, SD_ERR_STATE, "no autoregressive drafter attached (sd_sps_attach)");
+    if (!draft_out || !n_accepted_out || !token_out) return fail(h, SD_ERR_ARG, "null argument");
+    rc = check_round_shapes(h, batch, prefix_len, gamma);
+    if (rc) return rc;
+    rc = prepare_sps(h, batch, prefix, prefix_len, n, gamma, seed);
+    if (rc) return rc;
+    rc = prepare_target(h, batch, prefix, prefix_len, n, gamma);
+    if (rc) return rc;
+    h->steps_run = gamma;
+    rc = replay(h, shape_key(10 + (h->greedy ? 16 : 0), batch, gamma, 0, prefix_len, nullptr), [&] {
+        int r2 = enqueue_sps_draft(h, batch, gamma);
+        if (!r2) r2 = enqueue_target(h);
+        return r2 ? r2 : enqueue_accept(h, batch, gamma, h->buf.q);
+    });
+    if (rc) return rc;
+    const int64_t cnt = (int64_t)batch * gamma;
+    int32_t* so = h->stage_out;
+    SD_HIP(h, hipMemcpyAsync(so, h->buf.z, cnt * 4, hipMemcpyDeviceToHost, h->st));
+    SD_HIP(h, hipMemcpyAsync(so + cnt, h->buf.n_acc, batch * 4, hipMemcpyDeviceToHost, h->st));
+    SD_HIP(h, hipMemcpyAsync(so + cnt + batch, h->buf.tok, batch * 4, hipMemcpyDeviceToHost, h->st));
+    { const int rc_ = sync_stream(h); if (rc_) return rc_; }
+    memcpy(draft_out, so, cnt * 4);
+    memcpy(n_accepted_out, so + cnt, batch * 4);
+    memcpy(token_out, so + cnt + batch, batch * 4);
+    note_pending(h, batch, prefix, prefix_len, gamma, draft_out, true);
+    return SD_OK;
+}
+
+int32_t sd_sps_logits(sd_handle* h, int32_t batch, const int32_t* tokens, const int32_t* seq_len, const float** logits_dev_out) {
+    int64_t n;
+    int rc = check_batch(h, batch, tokens, seq_len, h ? h->target.c.vocab : 0, &n);
+    if (rc) return rc;
+    if (!h->has_sps) return fail(h, SD_ERR_STATE, "no autoregressive drafter attached (sd_sps_attach)");
+    if (!logits_dev_out) return fail(h, SD_ERR_ARG, "logits_dev_out is null");
+    for (int b = 0; b < batch; ++b)
+        if (seq_len[b] > h->sps.c.n_ctx) return fail(h, SD_ERR_SHAPE, "sequence exceeds the autoregressive drafter's context");
+    rc = sps_catch_up(h, batch, tokens, seq_len, n);
+    if (!rc) rc = upload_rows(h, 3, batch, tokens, seq_len, n, 1, 0);
+    if (rc) return rc;
+    h->prof.phase = "";
+    rc = run_layers(h, h->sps, h->sps_ms[1], nullptr, batch);
+    if (!rc) rc = run_head(h, h->sps, nullptr, h->sps_ms[1].head_row0, batch, h->buf.logits_d);
+    if (rc) return rc;
+    { const int rc_ = sync_stream(h); if (rc_) return rc_; }
+    *logits_dev_out = h->buf.logits_d;
     return SD_OK;
 }
 

@@ -16,6 +16,7 @@ constexpr int kWave = 64;            // CDNA wavefront
 constexpr int kChunk = 1024;         // vocabulary columns handled by one workgroup of the sampling kernels
 constexpr uint32_t STREAM_DRAFT = 1; // Philox counter word 3
 constexpr uint32_t STREAM_VERIFY = 2;
+constexpr uint32_t STREAM_SPS = 3;   // token samples of the autoregressive drafter of standard speculative decoding
 
 __host__ __device__ inline int64_t align_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
 __host__ __device__ inline int vocab_pad(int v) { return (v + 255) / 256 * 256; }
@@ -226,6 +227,13 @@ hipError_t launch_unmask_sample(const float* logits, int batch, int gamma, int v
 hipError_t launch_accept_resample(const float* p_logits, const float* q, const int32_t* draft, int batch,
                                   int gamma, int vocab, const uint64_t* seed, int32_t* n_acc, int32_t* token,
                                   const SampleScratch& s, hipStream_t st);
+
+// Step k of the autoregressive drafter (standard speculative decoding): logits [batch, ld], one row per sequence;
+// x_k ~ softmax(row b) by inverse CDF with the Philox draw (position k, step 0, sequence b, STREAM_SPS) word 1;
+// z[b * gamma + k] <- x_k, q row b * gamma + k <- the softmax row, qtok[b * gamma + k] <- its probability.
+// greedy: x_k = argmax (lowest id on ties), qtok = 1, no q row.
+hipError_t launch_sps_sample(const float* logits, int batch, int gamma, int vocab, int k, const uint64_t* seed, int32_t* z,
+                             float* q, float* qtok, bool greedy, const SampleScratch& s, hipStream_t st);
 
 // Temperature 0: argmax at reveal (qtok = 1, no q row); accept iff the drafted token is the target's argmax.
 hipError_t launch_unmask_greedy(const float* logits, int batch, int gamma, int vocab, int step, const uint64_t* seed,

@@ -174,24 +174,27 @@ __global__ __launch_bounds__(kThreads) void k_unmask_sample(const float* __restr
                                                             const double* __restrict__ part_m,
                                                             const double* __restrict__ part_s,
                                                             const int32_t* __restrict__ active, int32_t* __restrict__ z,
-                                                            float* __restrict__ q, float* __restrict__ qtok) {
+                                                            float* __restrict__ q, float* __restrict__ qtok, int sps_k) {
     __shared__ double sS[kMaxChunks];
     __shared__ double sh[4];
     __shared__ int shi[4];
     __shared__ ChunkPick pick;
-    const int row = blockIdx.y, c = blockIdx.x, nch = gridDim.x;
-    if (!active[row]) return;
-    const double m = combine_chunks(part_m + (size_t)row * nch, part_s + (size_t)row * nch, nch, sS, sh);
+    // sps_k >= 0: step sps_k of the autoregressive drafter -- logits row = sequence, every row draws, with its own
+    // Philox stream, and the results go to slot (sequence, sps_k) of the [batch, gamma] outputs.
+    const int lrow = blockIdx.y, c = blockIdx.x, nch = gridDim.x;
+    const int row = sps_k >= 0 ? lrow * gamma + sps_k : lrow;
+    if (sps_k < 0 && !active[lrow]) return;
+    const double m = combine_chunks(part_m + (size_t)lrow * nch, part_s + (size_t)lrow * nch, nch, sS, sh);
     if (threadIdx.x == 0) {
-        const Philox4 r = philox4x32_10((uint32_t)(row % gamma), (uint32_t)step, (uint32_t)(row / gamma),
-                                        STREAM_DRAFT, *seed_p);
+        const Philox4 r = sps_k >= 0 ? philox4x32_10((uint32_t)sps_k, 0u, (uint32_t)lrow, STREAM_SPS, *seed_p)
+                                     : philox4x32_10((uint32_t)(row % gamma), (uint32_t)step, (uint32_t)(row / gamma), STREAM_DRAFT, *seed_p);
         pick = pick_chunk(sS, nch, uniform_f64(r.y));
     }
     __syncthreads();
     const double Z = pick.total;
     const int col0 = c * kChunk + threadIdx.x * 4;
     float l[4];
-    load4(logits + (size_t)row * ld, col0, vocab, l);
+    load4(logits + (size_t)lrow * ld, col0, vocab, l);
     double w[4];
     float qv[4];
 #pragma unroll
@@ -395,10 +398,11 @@ __device__ inline MaxAt row_best(const float* pv, const int32_t* pi, int nch, in
 // grid (rows), one wave: revealed slots take the argmax of their row.
 __global__ __launch_bounds__(64) void k_greedy_reveal(const float* __restrict__ part_v, const int32_t* __restrict__ part_i,
                                                       int nch, const int32_t* __restrict__ active,
-                                                      int32_t* __restrict__ z, float* __restrict__ qtok) {
-    const int row = blockIdx.x;
-    if (!active[row]) return;
-    const MaxAt m = row_best(part_v + (size_t)row * nch, part_i + (size_t)row * nch, nch, threadIdx.x);
+                                                      int32_t* __restrict__ z, float* __restrict__ qtok, int gamma, int sps_k) {
+    const int lrow = blockIdx.x;                                   // sps_k >= 0: see k_unmask_sample
+    if (sps_k < 0 && !active[lrow]) return;
+    const int row = sps_k >= 0 ? lrow * gamma + sps_k : lrow;
+    const MaxAt m = row_best(part_v + (size_t)lrow * nch, part_i + (size_t)lrow * nch, nch, threadIdx.x);
     if (threadIdx.x == 0) { z[row] = m.i; qtok[row] = 1.f; }
 }
 
@@ -463,7 +467,7 @@ hipError_t launch_unmask_sample(const float* logits, int batch, int gamma, int v
     const dim3 grid(nch, rows);
     launch_kernel(k_row_stats, dim3(grid), dim3(kThreads), 0, st, logits, ld, vocab, z, gamma, step, seed, s.part_m, s.part_s, s.active);
     launch_kernel(k_unmask_sample, dim3(grid), dim3(kThreads), 0, st, logits, ld, vocab, gamma, step, seed, s.part_m, s.part_s, s.active, z,
-                                               q, qtok);
+                  q, qtok, -1);
     return hipGetLastError();
 }
 
@@ -473,7 +477,23 @@ hipError_t launch_unmask_greedy(const float* logits, int batch, int gamma, int v
     float* pv = reinterpret_cast<float*>(s.part_m);          // the fp64 partial arrays are free in this mode
     int32_t* pi = reinterpret_cast<int32_t*>(s.part_s);
     launch_kernel(k_chunk_argmax, dim3(dim3(nch, rows)), dim3(kThreads), 0, st, logits, ld, vocab, z, gamma, step, seed, pv, pi, s.active);
-    launch_kernel(k_greedy_reveal, dim3(rows), dim3(64), 0, st, pv, pi, nch, s.active, z, qtok);
+    launch_kernel(k_greedy_reveal, dim3(rows), dim3(64), 0, st, pv, pi, nch, s.active, z, qtok, gamma, -1);
+    return hipGetLastError();
+}
+
+hipError_t launch_sps_sample(const float* logits, int batch, int gamma, int vocab, int k, const uint64_t* seed, int32_t* z,
+                             float* q, float* qtok, bool greedy, const SampleScratch& s, hipStream_t st) {
+    const int nch = n_chunks(vocab), ld = vocab_pad(vocab);
+    const dim3 grid(nch, batch);
+    if (greedy) {
+        float* pv = reinterpret_cast<float*>(s.part_m);
+        int32_t* pi = reinterpret_cast<int32_t*>(s.part_s);
+        launch_kernel(k_chunk_argmax, dim3(grid), dim3(kThreads), 0, st, logits, ld, vocab, nullptr, gamma, 0, nullptr, pv, pi, s.active);
+        launch_kernel(k_greedy_reveal, dim3(batch), dim3(64), 0, st, pv, pi, nch, s.active, z, qtok, gamma, k);
+        return hipGetLastError();
+    }
+    launch_kernel(k_row_stats, dim3(grid), dim3(kThreads), 0, st, logits, ld, vocab, nullptr, gamma, 0, seed, s.part_m, s.part_s, s.active);
+    launch_kernel(k_unmask_sample, dim3(grid), dim3(kThreads), 0, st, logits, ld, vocab, gamma, 0, seed, s.part_m, s.part_s, s.active, z, q, qtok, k);
     return hipGetLastError();
 }
 
