@@ -222,8 +222,8 @@ int32_t sd_accept_resample(const float *p_logits, const float *q, const int32_t 
  * hip_stream.  Shapes whose statistics do not fit, i.e. sd_sampling_scratch_bytes(batch * (gamma + 1), vocab) >
  * sd_static_scratch_bytes(), are rejected with SD_ERR_WORKSPACE (text in sd_last_error(NULL)); nothing is launched
  * then.  All calls on one GPU share that GPU's buffer: calls that overlap in time on one GPU (two streams, two
- * threads) race and give undefined results; calls on one stream, or otherwise ordered, are fine.  Nothing in the
- * buffer needs to be zero and nothing is kept between calls. */
+ * threads) race and give undefined results; calls on one stream, or otherwise ordered, are fine.  The call clears the
+ * few counters that must start at zero itself (a fill kernel, no memset); nothing is kept between calls. */
 int64_t sd_static_scratch_bytes(void);
 int32_t sd_accept_resample_static(const float *p_logits, const float *q, const int32_t *draft,
                                   int32_t batch, int32_t gamma, int32_t vocab, uint64_t seed,

@@ -322,6 +322,7 @@ struct sd_handle {
     bool last_draft_sps = false;         // the last drafting call was sd_sps_draft
     int steps_run = 0;                   // drafter forwards of the last sd_draft / sd_round
     int temb_T = 0;                      // number of steps the timestep-embedding table in the workspace was built for
+    int target_tiles = 0;                // > 0: the last target pass left per-tile arg-maxima (that many tiles per row) instead of logits
     bool head_folded = false;            // the last run_layers left x and row sums for the final normalisation (run_head folds it)
     // KV-cache state per sequence: number of cached positions and a hash of their tokens
     std::vector<int32_t> cached_len;
@@ -843,20 +844,42 @@ int run_layers(sd_handle* h, const Model& m, const MapSet& rm, const float* temb
 
 // Final norm on selected rows + LM head -> fp32 logits [n_rows, ld].  idx: the rows (NULL: rows 0 .. n_rows - 1);
 // row0: their first row when they are one contiguous run (MapSet::head_row0).
-int run_head(sd_handle* h, const Model& m, const int32_t* idx, int row0, int n_rows, float* logits) {
+// tiles_out != NULL (temperature 0, where only the arg-maxima of the rows are needed): with up to 64 rows the head
+// writes no logits at all but, per row and 32-column tile, the largest logit and its column -- values in `logits` as
+// [n_rows][tiles], columns behind them as int32 [n_rows][tiles] -- and *tiles_out = tiles; otherwise *tiles_out = 0 and
+// the logits are written as usual.
+int run_head(sd_handle* h, const Model& m, const int32_t* idx, int row0, int n_rows, float* logits, int* tiles_out = nullptr) {
     Buffers& B = h->buf;
     const sd_model_config& c = m.c;
-    if (h->head_folded && row0 >= 0) {
+    const bool ln = c.arch == SD_ARCH_GPT2;
+    const bool folded = h->head_folded && row0 >= 0;
+    NormIn ni;
+    const void* x = B.xf;
+    if (folded) {
         // the last residual epilogue left x = bf16(h gain_f) and the row sums of every row: no normalisation kernel
-        const bool ln = c.arch == SD_ARCH_GPT2;
         const int parts = (c.d_model + 31) / 32;
-        NormIn ni;
         ni.kind = ln ? 1 : 2; ni.stats = B.stats + (int64_t)row0 * parts * 2; ni.parts = parts; ni.u = ln ? m.fu_head : nullptr; ni.eps = c.norm_eps;
-        const char* x = static_cast<const char*>(B.xn) + (int64_t)row0 * c.d_model * 2;
-        return run_linear(h, c.dtype, x, m.w_head, ln ? m.fv_head : nullptr, logits, n_rows, c.vocab, c.d_model, m.ld, EPI_F32, ni);
+        x = static_cast<const char*>(B.xn) + (int64_t)row0 * c.d_model * 2;
+    } else {
+        SD_LAUNCH(h, "k_norm", (double)n_rows * c.d_model * (4 + m.ew), 0, launch_norm(c.dtype, B.h, idx, m.lnf_g, m.lnf_b, B.xf, n_rows, c.d_model, c.norm_eps, h->st));
     }
-    SD_LAUNCH(h, "k_norm", (double)n_rows * c.d_model * (4 + m.ew), 0, launch_norm(c.dtype, B.h, idx, m.lnf_g, m.lnf_b, B.xf, n_rows, c.d_model, c.norm_eps, h->st));
-    return run_linear(h, c.dtype, B.xf, m.w_head, nullptr, logits, n_rows, c.vocab, c.d_model, m.ld, EPI_F32);
+    const float* bias = folded && ln ? m.fv_head : nullptr;
+    if (tiles_out) {
+        *tiles_out = 0;
+        if (n_rows <= 64 && linear_mfma_supported(c.dtype, n_rows, c.vocab, c.d_model, m.ld)) {
+            const int tiles = (c.vocab + 31) / 32;
+            NormOut no;
+            no.am_v = logits;
+            no.am_i = reinterpret_cast<int32_t*>(logits + (int64_t)n_rows * tiles);
+            const double bytes = ((double)n_rows * c.d_model + (double)c.vocab * c.d_model) * m.ew + 8.0 * n_rows * tiles;
+            const char* name = "linear";
+            SD_LAUNCH(h, name, bytes, 2.0 * n_rows * c.vocab * c.d_model,
+                      launch_linear_stream(x, m.w_head, bias, logits, n_rows, c.vocab, c.d_model, m.ld, EPI_ARGMAX, ni, no, h->buf.split, 0, h->st, &name));
+            *tiles_out = tiles;
+            return SD_OK;
+        }
+    }
+    return run_linear(h, c.dtype, x, m.w_head, bias, logits, n_rows, c.vocab, c.d_model, m.ld, EPI_F32, ni);
 }
 
 int check_round_shapes(sd_handle* h, int batch, const int32_t* len, int gamma) {
@@ -946,9 +969,15 @@ int enqueue_draft_step(sd_handle* h, int batch, int gamma, int T, int j) {
     const SampleScratch ss = sampling_scratch(B.sample_scratch, (int)h->lim.rows_head, m.c.vocab);
     int rc = run_layers(h, m, rm, B.temb + (int64_t)(j - 1) * m.c.d_model, batch * gamma);
     if (rc) return rc;
-    rc = run_head(h, m, rm.blk, rm.head_row0, batch * gamma, B.logits_d);
+    int tiles = 0;
+    rc = run_head(h, m, rm.blk, rm.head_row0, batch * gamma, B.logits_d, h->greedy ? &tiles : nullptr);
     if (rc) return rc;
-    if (h->greedy) {
+    if (h->greedy && tiles > 0) {
+        const int rows = batch * gamma;
+        SD_LAUNCH(h, "k_greedy_reveal_tiles", 8.0 * rows / T * tiles, 0,
+                  launch_greedy_from_tiles(B.logits_d, reinterpret_cast<const int32_t*>(B.logits_d + (int64_t)rows * tiles), tiles, batch, gamma,
+                                           m.c.vocab, j, -1, B.seed, B.z, B.qtok, h->st));
+    } else if (h->greedy) {
         SD_LAUNCH(h, "unmask_greedy(k_chunk_argmax+k_greedy_reveal)", 1.0 * batch * gamma / T * m.ld * 4, 0,
                   launch_unmask_greedy(B.logits_d, batch, gamma, m.c.vocab, j, B.seed, B.z, B.qtok, ss, h->st));
     } else {
@@ -1006,23 +1035,33 @@ int prepare_target(sd_handle* h, int batch, const int32_t* prefix, const int32_t
 }
 
 // Target forward over the gamma+1 query rows (draft tokens taken from buf.z) -> buf.logits_t (capturable).
-int enqueue_target(sd_handle* h) {
+// for_round: the acceptance step follows (at temperature 0 the head may then leave per-tile arg-maxima instead of logits);
+// false for the parity hook, which wants the logits.
+int enqueue_target(sd_handle* h, bool for_round = true) {
     const MapSet& rm = h->maps[1];
     h->prof.phase = "verify:";
     const int rc = run_layers(h, h->target, rm, nullptr, rm.rows);
     if (rc) return rc;
-    return run_head(h, h->target, nullptr, rm.head_row0, rm.rows, h->buf.logits_t);
+    h->target_tiles = 0;
+    return run_head(h, h->target, nullptr, rm.head_row0, rm.rows, h->buf.logits_t, (h->greedy && for_round) ? &h->target_tiles : nullptr);
 }
 
 int enqueue_accept(sd_handle* h, int batch, int gamma, const float* q_dev) {
     h->prof.phase = "accept:";
     const SampleScratch ss = sampling_scratch(h->buf.sample_scratch, (int)h->lim.rows_head, h->target.c.vocab);
+    if (h->greedy && h->target_tiles > 0) {
+        const int rows = batch * (gamma + 1), tiles = h->target_tiles;
+        SD_LAUNCH(h, "accept_greedy(k_row_argmax_tiles+k_greedy_accept_top)", 8.0 * rows * tiles, 0,
+                  launch_accept_greedy_from_tiles(h->buf.logits_t, reinterpret_cast<const int32_t*>(h->buf.logits_t + (int64_t)rows * tiles), tiles,
+                                                  h->buf.z, batch, gamma, ss.active, h->buf.n_acc, h->buf.tok, h->st));
+        return SD_OK;
+    }
     if (h->greedy) {
         SD_LAUNCH(h, "accept_greedy(k_chunk_argmax+k_greedy_accept)", (double)batch * (gamma + 1) * h->target.ld * 4, 0,
                   launch_accept_greedy(h->buf.logits_t, h->buf.z, batch, gamma, h->target.c.vocab, h->buf.n_acc, h->buf.tok, ss, h->st));
         return SD_OK;
     }
-    SD_LAUNCH(h, "accept_resample(k_row_stats+k_accept+k_final_partial+k_final_sample)",
+    SD_LAUNCH(h, "accept_resample(k_row_stats+k_accept_final)",
               ((double)batch * (gamma + 1) + 4.0 * batch) * h->target.ld * 4, 0,
               launch_accept_resample(h->buf.logits_t, q_dev, h->buf.z, batch, gamma, h->target.c.vocab, h->buf.seed,
                                      h->buf.n_acc, h->buf.tok, ss, h->st));
@@ -1142,8 +1181,15 @@ int enqueue_sps_draft(sd_handle* h, int batch, int gamma) {
         const MapSet& rm = h->sps_ms[1 + k];
         int rc = run_layers(h, m, rm, nullptr, batch);
         if (rc) return rc;
-        rc = run_head(h, m, nullptr, rm.head_row0, batch, B.logits_d);
+        int tiles = 0;
+        rc = run_head(h, m, nullptr, rm.head_row0, batch, B.logits_d, h->greedy ? &tiles : nullptr);
         if (rc) return rc;
+        if (tiles > 0) {
+            SD_LAUNCH(h, "k_greedy_reveal_tiles", 8.0 * batch * tiles, 0,
+                      launch_greedy_from_tiles(B.logits_d, reinterpret_cast<const int32_t*>(B.logits_d + (int64_t)batch * tiles), tiles, batch, gamma,
+                                               m.c.vocab, 0, k, B.seed, B.z, B.qtok, h->st));
+            continue;
+        }
         SD_LAUNCH(h, h->greedy ? "sps_sample(k_chunk_argmax+k_greedy_reveal)" : "sps_sample(k_row_stats+k_unmask_sample)",
                   (h->greedy ? 1.0 : 3.0) * batch * m.ld * 4, 0,
                   launch_sps_sample(B.logits_d, batch, gamma, m.c.vocab, k, B.seed, B.z, B.q, B.qtok, h->greedy, ss, h->st));
@@ -1259,6 +1305,12 @@ int32_t sd_create(const sd_model_config* target, const sd_model_config* drafter,
     const int64_t need = carve(a, h->buf, *target, *drafter, max_batch, gamma_max);
     if (need > workspace_bytes) { delete h; return SD_ERR_WORKSPACE; }
     if (!bind_model(h->target, *target, target_w) || !bind_model(h->drafter, *drafter, drafter_w)) { delete h; return SD_ERR_ARG; }
+    if (launch_sampling_reset(sampling_scratch(h->buf.sample_scratch, (int)limits_of(*target, *drafter, max_batch, gamma_max).rows_head, target->vocab),
+                             (int)limits_of(*target, *drafter, max_batch, gamma_max).rows_head, static_cast<hipStream_t>(hip_stream)) != hipSuccess) {
+        g_create_error = "clearing the sampling counters failed";
+        delete h;
+        return SD_ERR_HIP;
+    }
     if (hipMemsetAsync(h->buf.split.base, 0, kSplitTicketBytes, static_cast<hipStream_t>(hip_stream)) != hipSuccess) {
         g_create_error = "clearing the split-K tickets failed";
         delete h;
@@ -1533,7 +1585,7 @@ int32_t sd_target_logits(sd_handle* h, int32_t batch, const int32_t* prefix, con
     SD_HIP(h, hipMemcpyAsync(h->buf.z, h->stage_z, cnt * 4, hipMemcpyHostToDevice, h->st));
     rc = prepare_target(h, batch, prefix, prefix_len, n, gamma);
     if (rc) return rc;
-    rc = enqueue_target(h);
+    rc = enqueue_target(h, false);
     if (rc) return rc;
     { const int rc_ = sync_stream(h); if (rc_) return rc_; }
     *logits_dev_out = h->buf.logits_t;
@@ -1731,6 +1783,7 @@ int32_t sd_accept_resample(const float* p_logits, const float* q, const int32_t*
     const SampleScratch ss = sampling_scratch(scratch, batch * (gamma + 1), vocab);
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     if (hipMemcpyAsync(ss.seed, &seed, 8, hipMemcpyHostToDevice, st) != hipSuccess) return SD_ERR_HIP;   // pageable source: staged before return
+    if (launch_sampling_reset(ss, batch * (gamma + 1), st) != hipSuccess) return SD_ERR_HIP;             // caller memory of unknown content
     return launch_accept_resample(p_logits, q, draft, batch, gamma, vocab, ss.seed, n_accepted, token, ss, st) == hipSuccess ? SD_OK : SD_ERR_HIP;
 }
 
@@ -1752,8 +1805,10 @@ int32_t sd_accept_resample_static(const float* p_logits, const float* q, const i
     if (rc) return rc;
     const SampleScratch ss = sampling_scratch(base, (int)rows, vocab);
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    // Nothing in the scratch has to start at zero: every partial, row statistic and the seed slot is written by this
-    // call before it is read.  The seed travels as a kernel argument (no staging copy).
+    // The arrival counters must start at zero (the array keeps whatever the last call, possibly an interrupted one, left):
+    // cleared by a kernel.  Everything else -- partials, row statistics, the seed slot -- is written by this call before
+    // it is read.  The seed travels as a kernel argument (no staging copy).
+    if (launch_sampling_reset(ss, (int)rows, st) != hipSuccess) return SD_ERR_HIP;
     launch_kernel(k_store_u64, dim3(1), dim3(1), 0, st, ss.seed, seed);
     if (hipGetLastError() != hipSuccess) return SD_ERR_HIP;
     return launch_accept_resample(p_logits, q, draft, batch, gamma, vocab, ss.seed, n_accepted, token, ss, st) == hipSuccess ? SD_OK : SD_ERR_HIP;

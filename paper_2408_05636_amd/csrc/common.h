@@ -25,6 +25,8 @@ __host__ __device__ inline int n_chunks(int vocab) { return (vocab + kChunk - 1)
 enum Epilogue {
     EPI_STORE = 0, EPI_GELU = 1, EPI_RESID = 2, EPI_F32 = 3,
     EPI_RESID_NORM = 4,  // kernels only: EPI_RESID with NormOut
+    EPI_ARGMAX = 7,      // no output rows at all: per row and 32-column tile the largest value and its column (NormOut::am_v / am_i;
+                         // temperature 0 needs nothing else of an LM head); the few-row streaming kernel only (launch_linear_stream)
     EPI_STORE_ROPE = 6,  // kernels only: EPI_STORE with NormOut::rope_cs (rotary embedding in the epilogue)
     EPI_SWIGLU = 5       // W = [gate rows | up rows] ([n, k], n even): y[m, n / 2] (dtype) = silu(gate part) * (up part); the few-row
                          // streaming kernel only (launch_linear_stream), callers fall back to EPI_STORE + launch_swiglu
@@ -57,6 +59,10 @@ struct NormOut {             // producer (residual epilogue): what to prepare fo
     // rotated by the angle whose (cos, sin) is rope_cs[m * rope_dh / 2 + i] (launch_rope_table).  NULL: no rotation.
     const float* rope_cs = nullptr;
     int rope_cols = 0, rope_dh = 0;
+    // EPI_ARGMAX: am_v[row * ceil(n / 32) + tile] = largest value of the row within columns 32 tile .. 32 tile + 31,
+    // am_i[...] = its column (lowest on ties).
+    float* am_v = nullptr;
+    int32_t* am_i = nullptr;
 };
 
 // Every kernel of the library is launched through launch_kernel().  Ordinarily that is a plain launch.  While a
@@ -215,11 +221,14 @@ struct SampleScratch {       // carved from one device buffer by sampling_scratc
     double* row_m;           // [batch] max of the row the final token is drawn from
     double* row_z;           // [batch] its softmax normaliser
     int32_t* active;         // [rows]
+    unsigned int* ticket;    // [rows + batch] arrival counters of the acceptance path: zero before a launch, zero again after it
     uint64_t* seed;          // Philox key of the current call (kernels read it from memory so that a
                              // captured graph can be replayed with a new seed)
 };
 int64_t sampling_scratch_bytes(int rows, int vocab);
 SampleScratch sampling_scratch(void* base, int rows, int vocab);
+// Zero the arrival counters (scratch memory of unknown content; the kernels leave them zero afterwards).
+hipError_t launch_sampling_reset(const SampleScratch& s, int rows, hipStream_t st);
 
 hipError_t launch_fill_i32(int32_t* p, int n, int v, hipStream_t st);
 hipError_t launch_unmask_sample(const float* logits, int batch, int gamma, int vocab, int step, const uint64_t* seed,
@@ -234,6 +243,14 @@ hipError_t launch_accept_resample(const float* p_logits, const float* q, const i
 // greedy: x_k = argmax (lowest id on ties), qtok = 1, no q row.
 hipError_t launch_sps_sample(const float* logits, int batch, int gamma, int vocab, int k, const uint64_t* seed, int32_t* z,
                              float* q, float* qtok, bool greedy, const SampleScratch& s, hipStream_t st);
+
+// Temperature 0 on per-tile maxima left by an LM head with EPI_ARGMAX (pv, pi: [rows][tiles]) instead of on logits:
+// the reveal step of the diffusion drafter (step >= 1), step k of the autoregressive drafter (sps_k >= 0, logits row =
+// sequence), and the acceptance (rows = batch * (gamma + 1)).
+hipError_t launch_greedy_from_tiles(const float* pv, const int32_t* pi, int tiles, int batch, int gamma, int vocab, int step, int sps_k,
+                                    const uint64_t* seed, int32_t* z, float* qtok, hipStream_t st);
+hipError_t launch_accept_greedy_from_tiles(const float* pv, const int32_t* pi, int tiles, const int32_t* draft, int batch, int gamma,
+                                           int32_t* top /* int32 [batch * (gamma + 1)] scratch */, int32_t* n_acc, int32_t* token, hipStream_t st);
 
 // Temperature 0: argmax at reveal (qtok = 1, no q row); accept iff the drafted token is the target's argmax.
 hipError_t launch_unmask_greedy(const float* logits, int batch, int gamma, int vocab, int step, const uint64_t* seed,

@@ -23,6 +23,9 @@
 //
 // Normalisations folded around the contraction work as in gemm_mfma.hip (FoldIn / FoldOut in mfma_common.hip.h).
 //
+// EPI_ARGMAX (LM heads at temperature 0): no output matrix; a wave reduces its 32 columns per row to the largest value
+// and its column (lowest column on ties) and writes one pair per row and tile.  No K split in this form.
+//
 // EPI_SWIGLU (the gated MLP of the Llama-shaped target): W holds the gate rows followed by the up rows; a workgroup
 // takes 64 gate columns and the 64 up columns that belong to them -- waves 0, 1 the gate tiles, waves 2, 3 the up
 // tiles --, the up waves hand their results over through LDS and the gate waves store silu(gate) * up.  The gate / up
@@ -43,6 +46,8 @@ struct StreamSplit {
     float* part;            // [column tile][split][MT * 16][64] fp32
     unsigned int* ticket;   // one counter per column tile, zero between launches
     int split_chunks;       // K chunks per workgroup (the last split may have fewer)
+    float* am_v;            // EPI_ARGMAX: [M][ceil(N / 32)] largest value per row and column tile ...
+    int32_t* am_i;          // ... and its column
 };
 
 template <int MT, int EPI, int NF>
@@ -325,6 +330,43 @@ __global__ __launch_bounds__(256) void k_linear_stream(const bf16_t* __restrict_
         }
     }
 
+    if constexpr (EPI == EPI_ARGMAX) {
+        // Through the wave's own staging tile (free after the loop; LDS operations of one wave execute in order): the
+        // 32 x 32 tile is written [row][column] with padded rows, then lane -> (row lane & 31, column half lane >> 5)
+        // scans 16 columns and one exchange between the halves finishes the row.
+        const int n_tiles = (N + 31) / 32;
+        float* const tl = reinterpret_cast<float*>(stage);            // 32 x 33 floats <= 4352 bytes
+#pragma unroll
+        for (int t = 0; t < MT; ++t) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int lr = 8 * (e >> 2) + (e & 3) + 4 * half;
+                float v = acc[t][e];
+                if constexpr (NF > 0) v = fmaf(ab[(32 * t + lr) * 2 + 0], v, ab[(32 * t + lr) * 2 + 1] * uv);
+                v += bv;
+                tl[lr * 33 + r] = ncol < (uint32_t)N ? v : -INFINITY;
+            }
+            float best = tl[r * 33 + 16 * half];
+            int bc = 16 * half;
+#pragma unroll
+            for (int c = 1; c < 16; ++c) {
+                const float x = tl[r * 33 + 16 * half + c];
+                if (x > best) { best = x; bc = 16 * half + c; }      // ascending columns: the lowest column wins ties
+            }
+            const float ov = __shfl_xor(best, 32, 64);
+            const int oc = __shfl_xor(bc, 32, 64);
+            if (half == 0) {
+                const bool take = ov > best;                           // the upper half only when strictly larger
+                const int row = 32 * t + r;
+                if (row < M) {
+                    sk.am_v[(size_t)row * n_tiles + tile] = take ? ov : best;
+                    sk.am_i[(size_t)row * n_tiles + tile] = n_base + (take ? oc : bc);
+                }
+            }
+        }
+        return;
+    }
+
     if constexpr (EPI == EPI_SWIGLU) {
         // The up waves park their tiles (normalisation and bias applied) in LDS, the gate waves of the same column pair
         // pick them up.  The slabs are free once every wave has left the K loop.
@@ -449,7 +491,7 @@ bool linear_stream_preferred(int m, int n, int k, bool folded) {
     return (folded && m <= 32) || (groups >= 160 && groups <= 256) || groups >= 700;
 }
 
-static std::string g_stream_names[3][6][3];
+static std::string g_stream_names[3][8][3];
 static const char* stream_name(int mt, int epi, int nfk) {
     std::string& s = g_stream_names[mt][epi][nfk];
     if (s.empty()) s = "k_linear_stream<" + std::to_string(mt) + "," + std::to_string(epi) + "," + std::to_string(nfk) + ">";
@@ -483,6 +525,7 @@ static hipError_t launch_mt(const dim3& grid, int bytes, hipStream_t st, const b
             case EPI_GELU: SD_GO(EPI_GELU, 0);
             case EPI_RESID: if (no.gain) SD_GO(EPI_RESID_NORM, 0); else SD_GO(EPI_RESID, 0);
             case EPI_SWIGLU: SD_GO(EPI_SWIGLU, 0);
+            case EPI_ARGMAX: SD_GO(EPI_ARGMAX, 0);
             default: SD_GO(EPI_F32, 0);
         }
     } else if (ni.kind == 1) {
@@ -490,6 +533,7 @@ static hipError_t launch_mt(const dim3& grid, int bytes, hipStream_t st, const b
             case EPI_STORE: SD_GO(EPI_STORE, 1);
             case EPI_GELU: SD_GO(EPI_GELU, 1);
             case EPI_F32: SD_GO(EPI_F32, 1);
+            case EPI_ARGMAX: SD_GO(EPI_ARGMAX, 1);
             default: return hipErrorInvalidValue;
         }
     } else {
@@ -498,6 +542,7 @@ static hipError_t launch_mt(const dim3& grid, int bytes, hipStream_t st, const b
             case EPI_GELU: SD_GO(EPI_GELU, 2);
             case EPI_F32: SD_GO(EPI_F32, 2);
             case EPI_SWIGLU: SD_GO(EPI_SWIGLU, 2);
+            case EPI_ARGMAX: SD_GO(EPI_ARGMAX, 2);
             default: return hipErrorInvalidValue;
         }
     }
@@ -509,12 +554,13 @@ static hipError_t launch_mt(const dim3& grid, int bytes, hipStream_t st, const b
 hipError_t launch_linear_stream(const void* x, const void* w, const float* bias, void* y, int m, int n, int k, int ldy,
                                 int epi, const NormIn& ni, const NormOut& no, const SplitWorkspace& ws, int force_split,
                                 hipStream_t st, const char** kernel_name) {
-    if (epi < 0 || (epi > 3 && epi != EPI_SWIGLU)) return hipErrorInvalidValue;
+    if (epi < 0 || (epi > 3 && epi != EPI_SWIGLU && epi != EPI_ARGMAX)) return hipErrorInvalidValue;
     StreamPlan p;
-    if (!plan_stream(m, n, k, ws, epi == EPI_SWIGLU ? 1 : force_split, &p)) return hipErrorNotSupported;
+    if (!plan_stream(m, n, k, ws, (epi == EPI_SWIGLU || epi == EPI_ARGMAX) ? 1 : force_split, &p)) return hipErrorNotSupported;
+    if (epi == EPI_ARGMAX && (p.gsplit != 1 || !no.am_v || !no.am_i || no.gain)) return hipErrorNotSupported;
     // gate / up pairs of 64 columns per workgroup, no K split, LayerNorm folds not instantiated
     if (epi == EPI_SWIGLU && (n % 128 != 0 || p.gsplit != 1 || ni.kind == 1 || no.gain)) return hipErrorNotSupported;
-    StreamSplit sk{nullptr, nullptr, p.split_chunks};
+    StreamSplit sk{nullptr, nullptr, p.split_chunks, no.am_v, no.am_i};
     if (p.gsplit > 1) {
         sk.ticket = static_cast<unsigned int*>(ws.base);
         sk.part = reinterpret_cast<float*>(static_cast<char*>(ws.base) + kSplitTicketBytes);

@@ -87,11 +87,17 @@ __device__ inline void load4(const float* row, int col, int vocab, float (&l)[4]
 
 // ---------------------------------------------------------------- chunk statistics
 // grid (n_chunks, rows).  z != NULL: drafter mode, rows that are not revealed at this step are skipped.
+// ticket != NULL (acceptance path): whichever workgroup of a row arrives last also combines the row's chunk
+// statistics into row_m[row] (maximum) and row_z[row] (sum of exp(l - maximum)), in a fixed order -- the partials travel
+// as device-scope accesses, released before the ticket is drawn and acquired by the last arrival; nobody waits.
 __global__ __launch_bounds__(kThreads) void k_row_stats(const float* __restrict__ logits, int ld, int vocab,
                                                         const int32_t* __restrict__ z, int gamma, int step,
                                                         const uint64_t* __restrict__ seed_p, double* __restrict__ part_m,
-                                                        double* __restrict__ part_s, int32_t* __restrict__ active) {
+                                                        double* __restrict__ part_s, int32_t* __restrict__ active,
+                                                        unsigned int* __restrict__ ticket, double* __restrict__ row_m,
+                                                        double* __restrict__ row_z) {
     __shared__ double sh[4];
+    __shared__ unsigned int s_last;
     const int row = blockIdx.y, c = blockIdx.x, nch = gridDim.x;
     if (z != nullptr) {
         const bool act = (z[row] == vocab) && reveal_now(row % gamma, step, row / gamma, STREAM_DRAFT, *seed_p);
@@ -105,9 +111,37 @@ __global__ __launch_bounds__(kThreads) void k_row_stats(const float* __restrict_
 #pragma unroll
     for (int i = 0; i < 4; ++i) s += exp((double)l[i] - m);   // exp(-inf) = 0 for padding columns
     s = block_sum(s, sh);
+    if (ticket == nullptr) {
+        if (threadIdx.x == 0) {
+            part_m[(size_t)row * nch + c] = m;
+            part_s[(size_t)row * nch + c] = s;
+        }
+        return;
+    }
     if (threadIdx.x == 0) {
-        part_m[(size_t)row * nch + c] = m;
-        part_s[(size_t)row * nch + c] = s;
+        __hip_atomic_store(&part_m[(size_t)row * nch + c], m, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(&part_s[(size_t)row * nch + c], s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+        s_last = __hip_atomic_fetch_add(&ticket[row], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (unsigned int)nch - 1u;
+    }
+    __syncthreads();
+    if (!s_last) return;
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    // thread t takes chunks t, t + 256, ...: a fixed assignment and a fixed reduction tree
+    double mm = -INFINITY;
+    for (int i = threadIdx.x; i < nch; i += kThreads)
+        mm = fmax(mm, __hip_atomic_load(&part_m[(size_t)row * nch + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+    mm = block_max(mm, sh);
+    double ss = 0.0;
+    for (int i = threadIdx.x; i < nch; i += kThreads)
+        ss += __hip_atomic_load(&part_s[(size_t)row * nch + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) *
+              exp(__hip_atomic_load(&part_m[(size_t)row * nch + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - mm);
+    ss = block_sum(ss, sh);
+    if (threadIdx.x == 0) {
+        row_m[row] = mm;
+        row_z[row] = ss;
+        __hip_atomic_store(&ticket[row], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);     // ready for the next launch
     }
 }
 
@@ -211,50 +245,7 @@ __global__ __launch_bounds__(kThreads) void k_unmask_sample(const float* __restr
     }
 }
 
-// ---------------------------------------------------------------- acceptance (target)
-// grid (batch).  Row statistics of P[0..gamma], the gamma acceptance tests, n = first rejection.
-__global__ __launch_bounds__(kThreads) void k_accept(const float* __restrict__ p_logits, const float* __restrict__ q,
-                                                     const int32_t* __restrict__ draft, int ld, int vocab, int gamma,
-                                                     int nch, const uint64_t* __restrict__ seed_p, const double* __restrict__ part_m,
-                                                     const double* __restrict__ part_s, int32_t* __restrict__ n_acc,
-                                                     double* __restrict__ row_m, double* __restrict__ row_z) {
-    extern __shared__ double dyn[];          // [gamma+1] maxima, [gamma+1] normalisers
-    __shared__ int shi[4];
-    double* rm = dyn;
-    double* rz = dyn + (gamma + 1);
-    const int b = blockIdx.x, lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-    for (int k = wv; k <= gamma; k += kThreads / 64) {
-        const size_t o = ((size_t)b * (gamma + 1) + k) * nch;
-        double m = -INFINITY;
-        for (int i = lane; i < nch; i += 64) m = fmax(m, part_m[o + i]);
-        m = wave_max(m);
-        double s = 0.0;
-        for (int i = lane; i < nch; i += 64) s += part_s[o + i] * exp(part_m[o + i] - m);
-        s = wave_sum(s);
-        if (lane == 0) { rm[k] = m; rz[k] = s; }
-    }
-    __syncthreads();
-    int first_reject = gamma;
-    for (int k = threadIdx.x; k < gamma; k += kThreads) {
-        const int x = draft[b * gamma + k];
-        bool ok = false;
-        if ((unsigned)x < (unsigned)vocab) {
-            const size_t prow = (size_t)b * (gamma + 1) + k, qrow = (size_t)b * gamma + k;
-            const float px = (float)(exp((double)p_logits[prow * ld + x] - rm[k]) / rz[k]);
-            const float qx = q[qrow * ld + x];
-            const Philox4 r = philox4x32_10((uint32_t)k, 0u, (uint32_t)b, STREAM_VERIFY, *seed_p);
-            ok = __fmul_rn(uniform_f32(r.x), qx) <= px;        // accept iff r q(x) <= p(x), fp32 product
-        }
-        if (!ok) first_reject = min(first_reject, k);
-    }
-    const int n = block_min_int(first_reject, shi);
-    if (threadIdx.x == 0) {
-        n_acc[b] = n;
-        row_m[b] = rm[n];
-        row_z[b] = rz[n];
-    }
-}
-
+// ---------------------------------------------------------------- acceptance + final token (target)
 // Weight of column i of the row the final token is drawn from: residual max(0, p - q) after a
 // rejection, p itself after full acceptance (or when the residual carries no mass).
 __device__ inline double final_weight(float l, float qv, double m, double Z, bool use_residual) {
@@ -262,73 +253,49 @@ __device__ inline double final_weight(float l, float qv, double m, double Z, boo
     return use_residual ? fmax(0.0, p - (double)qv) : p;
 }
 
-// grid (n_chunks, batch): chunk sums of the final-token weights.
-__global__ __launch_bounds__(kThreads) void k_final_partial(const float* __restrict__ p_logits,
-                                                            const float* __restrict__ q, int ld, int vocab, int gamma,
-                                                            const int32_t* __restrict__ n_acc,
-                                                            const double* __restrict__ row_m,
-                                                            const double* __restrict__ row_z,
-                                                            double* __restrict__ part_r) {
-    __shared__ double sh[4];
-    const int b = blockIdx.y, c = blockIdx.x, nch = gridDim.x;
-    const int n = n_acc[b];
-    const bool resid = n < gamma;
-    const int col0 = c * kChunk + threadIdx.x * 4;
-    float l[4], qv[4] = {0.f, 0.f, 0.f, 0.f};
-    load4(p_logits + ((size_t)b * (gamma + 1) + n) * ld, col0, vocab, l);
-    if (resid && col0 < ld) {
-        const float4 t = *reinterpret_cast<const float4*>(q + ((size_t)b * gamma + n) * ld + col0);
-        qv[0] = t.x; qv[1] = t.y; qv[2] = t.z; qv[3] = t.w;
-    }
-    const double m = row_m[b], Z = row_z[b];
-    double w[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) w[i] = (col0 + i < vocab) ? final_weight(l[i], qv[i], m, Z, resid) : 0.0;
-    const double s = block_sum(((w[0] + w[1]) + w[2]) + w[3], sh);
-    if (threadIdx.x == 0) part_r[(size_t)b * nch + c] = s;
-}
-
-// grid (batch): pick the chunk, then the token.
-__global__ __launch_bounds__(kThreads) void k_final_sample(const float* __restrict__ p_logits,
-                                                           const float* __restrict__ q, int ld, int vocab, int gamma,
-                                                           int nch, const uint64_t* __restrict__ seed_p, const int32_t* __restrict__ n_acc,
-                                                           const double* __restrict__ row_m,
-                                                           const double* __restrict__ row_z,
-                                                           const double* __restrict__ part_m,
-                                                           const double* __restrict__ part_s,
-                                                           const double* __restrict__ part_r,
+// grid (n_chunks, batch), after k_row_stats has left the statistics of the gamma + 1 target rows in row_m / row_z.
+//  1. Every workgroup of a sequence runs the gamma acceptance tests r_k q_k(x_k) <= p_k(x_k) (fp32 product) and takes
+//     n = the first rejection (gamma lookups: cheaper done by all than handed around).
+//  2. It sums the final-token weights of its chunk of row n -- max(0, p_n - q_n) after a rejection, p_gamma after full
+//     acceptance --, leaves the sum in part_r and draws a ticket.
+//  3. The last arrival of the sequence picks the chunk whose running sum passes u * total, then the token inside it, and
+//     writes n and the token.  Fixed orders throughout: run-to-run identical.
+__global__ __launch_bounds__(kThreads) void k_accept_final(const float* __restrict__ p_logits, const float* __restrict__ q,
+                                                           const int32_t* __restrict__ draft, int ld, int vocab, int gamma,
+                                                           const uint64_t* __restrict__ seed_p, const double* __restrict__ row_m,
+                                                           const double* __restrict__ row_z, const double* __restrict__ part_m,
+                                                           const double* __restrict__ part_s, double* __restrict__ part_r,
+                                                           unsigned int* __restrict__ ticket, int32_t* __restrict__ n_acc,
                                                            int32_t* __restrict__ token) {
     __shared__ double sS[kMaxChunks];
     __shared__ double sh[4];
     __shared__ int shi[4];
     __shared__ ChunkPick pick;
     __shared__ int s_resid;
-    const int b = blockIdx.x;
-    const int n = n_acc[b];
-    const double m = row_m[b], Z = row_z[b];
-    for (int i = threadIdx.x; i < nch; i += kThreads) sS[i] = part_r[(size_t)b * nch + i];
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        const Philox4 r = philox4x32_10((uint32_t)n, 0u, (uint32_t)b, STREAM_VERIFY, *seed_p);
-        const double u = uniform_f64(r.y);
-        int resid = n < gamma;
-        if (resid) {
-            double tot = 0.0;
-            for (int i = 0; i < nch; ++i) tot += sS[i];
-            if (!(tot > 0.0)) {      // empty residual (cannot happen in exact arithmetic): draw from p
-                resid = 0;
-                const size_t o = ((size_t)b * (gamma + 1) + n) * nch;
-                for (int i = 0; i < nch; ++i) sS[i] = part_s[o + i] * exp(part_m[o + i] - m) / Z;
-            }
+    __shared__ unsigned int s_last;
+    const int b = blockIdx.y, c = blockIdx.x, nch = gridDim.x;
+    // 1. acceptance tests
+    int first_reject = gamma;
+    for (int k = threadIdx.x; k < gamma; k += kThreads) {
+        const int x = draft[b * gamma + k];
+        bool ok = false;
+        if ((unsigned)x < (unsigned)vocab) {
+            const size_t prow = (size_t)b * (gamma + 1) + k, qrow = (size_t)b * gamma + k;
+            const float px = (float)(exp((double)p_logits[prow * ld + x] - row_m[prow]) / row_z[prow]);
+            const float qx = q[qrow * ld + x];
+            const Philox4 r = philox4x32_10((uint32_t)k, 0u, (uint32_t)b, STREAM_VERIFY, *seed_p);
+            ok = __fmul_rn(uniform_f32(r.x), qx) <= px;        // accept iff r q(x) <= p(x), fp32 product
         }
-        s_resid = resid;
-        pick = pick_chunk(sS, nch, u);
+        if (!ok) first_reject = min(first_reject, k);
     }
-    __syncthreads();
-    const bool resid = s_resid != 0;
-    const int col0 = pick.chunk * kChunk + threadIdx.x * 4;
+    const int n = block_min_int(first_reject, shi);
+    // 2. this chunk's share of the final-token weights
+    const size_t nrow = (size_t)b * (gamma + 1) + n;
+    const double m = row_m[nrow], Z = row_z[nrow];
+    bool resid = n < gamma;
+    int col0 = c * kChunk + threadIdx.x * 4;
     float l[4], qv[4] = {0.f, 0.f, 0.f, 0.f};
-    load4(p_logits + ((size_t)b * (gamma + 1) + n) * ld, col0, vocab, l);
+    load4(p_logits + nrow * ld, col0, vocab, l);
     if (resid && col0 < ld) {
         const float4 t = *reinterpret_cast<const float4*>(q + ((size_t)b * gamma + n) * ld + col0);
         qv[0] = t.x; qv[1] = t.y; qv[2] = t.z; qv[3] = t.w;
@@ -336,8 +303,56 @@ __global__ __launch_bounds__(kThreads) void k_final_sample(const float* __restri
     double w[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) w[i] = (col0 + i < vocab) ? final_weight(l[i], qv[i], m, Z, resid) : 0.0;
+    const double s = block_sum(((w[0] + w[1]) + w[2]) + w[3], sh);
+    if (threadIdx.x == 0) {
+        __hip_atomic_store(&part_r[(size_t)b * nch + c], s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+        s_last = __hip_atomic_fetch_add(&ticket[b], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (unsigned int)nch - 1u;
+    }
+    __syncthreads();
+    if (!s_last) return;
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    // 3. the last arrival draws the token
+    for (int i = threadIdx.x; i < nch; i += kThreads)
+        sS[i] = __hip_atomic_load(&part_r[(size_t)b * nch + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        __hip_atomic_store(&ticket[b], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);       // ready for the next launch
+        const Philox4 r = philox4x32_10((uint32_t)n, 0u, (uint32_t)b, STREAM_VERIFY, *seed_p);
+        const double u = uniform_f64(r.y);
+        int rs = resid ? 1 : 0;
+        if (rs) {
+            double tot = 0.0;
+            for (int i = 0; i < nch; ++i) tot += sS[i];
+            if (!(tot > 0.0)) {      // empty residual (cannot happen in exact arithmetic): draw from p
+                rs = 0;
+                const size_t o = nrow * nch;
+                for (int i = 0; i < nch; ++i) sS[i] = part_s[o + i] * exp(part_m[o + i] - m) / Z;
+            }
+        }
+        s_resid = rs;
+        pick = pick_chunk(sS, nch, u);
+        n_acc[b] = n;
+    }
+    __syncthreads();
+    resid = s_resid != 0;
+    col0 = pick.chunk * kChunk + threadIdx.x * 4;
+    qv[0] = qv[1] = qv[2] = qv[3] = 0.f;
+    load4(p_logits + nrow * ld, col0, vocab, l);
+    if (resid && col0 < ld) {
+        const float4 t = *reinterpret_cast<const float4*>(q + ((size_t)b * gamma + n) * ld + col0);
+        qv[0] = t.x; qv[1] = t.y; qv[2] = t.z; qv[3] = t.w;
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) w[i] = (col0 + i < vocab) ? final_weight(l[i], qv[i], m, Z, resid) : 0.0;
     const int v = select_in_chunk(w, col0, pick.before, pick.target, sh, shi);
     if (threadIdx.x == 0) token[b] = v;
+}
+
+__global__ void k_zero_u32(unsigned int* __restrict__ p, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0u;
 }
 
 // ---------------------------------------------------------------- temperature 0
@@ -406,6 +421,55 @@ __global__ __launch_bounds__(64) void k_greedy_reveal(const float* __restrict__ 
     if (threadIdx.x == 0) { z[row] = m.i; qtok[row] = 1.f; }
 }
 
+// Best (value, column) of a row's tiles by a whole workgroup: thread t takes tiles t, t + 256, ..., then a fixed tree.
+__device__ inline MaxAt row_best_block(const float* pv, const int32_t* pi, int nch, float* shv, int* shi) {
+    MaxAt m{-INFINITY, INT_MAX};
+    for (int i = threadIdx.x; i < nch; i += kThreads) m = better(m, MaxAt{pv[i], pi[i]});
+    m = wave_best(m);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) { shv[threadIdx.x >> 6] = m.v; shi[threadIdx.x >> 6] = m.i; }
+    __syncthreads();
+    MaxAt b{shv[0], shi[0]};
+    for (int w = 1; w < 4; ++w) b = better(b, MaxAt{shv[w], shi[w]});
+    return b;
+}
+
+// grid (rows), on per-tile maxima of all rows (an LM head with EPI_ARGMAX): the reveal decision is taken here.
+__global__ __launch_bounds__(kThreads) void k_greedy_reveal_tiles(const float* __restrict__ part_v, const int32_t* __restrict__ part_i,
+                                                                  int nch, int vocab, int gamma, int step, int sps_k,
+                                                                  const uint64_t* __restrict__ seed_p, int32_t* __restrict__ z,
+                                                                  float* __restrict__ qtok) {
+    __shared__ float shv[4];
+    __shared__ int shi[4];
+    const int lrow = blockIdx.x;
+    const int row = sps_k >= 0 ? lrow * gamma + sps_k : lrow;
+    if (sps_k < 0 && !((z[row] == vocab) && reveal_now(row % gamma, step, row / gamma, STREAM_DRAFT, *seed_p))) return;   // block-uniform
+    const MaxAt m = row_best_block(part_v + (size_t)lrow * nch, part_i + (size_t)lrow * nch, nch, shv, shi);
+    if (threadIdx.x == 0) { z[row] = m.i; qtok[row] = 1.f; }
+}
+
+// grid (gamma + 1, batch), on per-tile maxima: top[b][k] = argmax of target row k of sequence b.
+__global__ __launch_bounds__(kThreads) void k_row_argmax_tiles(const float* __restrict__ part_v, const int32_t* __restrict__ part_i,
+                                                               int nch, int32_t* __restrict__ top) {
+    __shared__ float shv[4];
+    __shared__ int shi[4];
+    const size_t row = (size_t)blockIdx.y * gridDim.x + blockIdx.x;
+    const MaxAt m = row_best_block(part_v + row * nch, part_i + row * nch, nch, shv, shi);
+    if (threadIdx.x == 0) top[row] = m.i;
+}
+
+// grid (batch), one wave: n = first drafted token that differs from its row's argmax, token = argmax of row n.
+__global__ __launch_bounds__(64) void k_greedy_accept_top(const int32_t* __restrict__ top, const int32_t* __restrict__ draft, int gamma,
+                                                          int32_t* __restrict__ n_acc, int32_t* __restrict__ token) {
+    const int b = blockIdx.x;
+    int first = gamma;
+    for (int k = threadIdx.x; k < gamma; k += 64)
+        if (draft[b * gamma + k] != top[(size_t)b * (gamma + 1) + k]) { first = k; break; }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) first = min(first, __shfl_xor(first, o, 64));
+    if (threadIdx.x == 0) { n_acc[b] = first; token[b] = top[(size_t)b * (gamma + 1) + first]; }
+}
+
 // grid (batch), one wave: n = first drafted token that is not the argmax of its target row, token = argmax of row n.
 __global__ __launch_bounds__(64) void k_greedy_accept(const float* __restrict__ part_v, const int32_t* __restrict__ part_i,
                                                       int nch, const int32_t* __restrict__ draft, int gamma,
@@ -442,6 +506,7 @@ int64_t sampling_scratch_bytes(int rows, int vocab) {
     b += align_up(rows * nch * 8, 256) * 3;   // part_m, part_s, part_r
     b += align_up((int64_t)rows * 8, 256) * 2; // row_m, row_z
     b += align_up((int64_t)rows * 4, 256);     // active
+    b += align_up((int64_t)rows * 8, 256);     // arrival counters (rows + batch <= 2 rows)
     b += 256;                                  // seed slot
     return b;
 }
@@ -457,6 +522,7 @@ SampleScratch sampling_scratch(void* base, int rows, int vocab) {
     s.row_m = reinterpret_cast<double*>(p); p += small;
     s.row_z = reinterpret_cast<double*>(p); p += small;
     s.active = reinterpret_cast<int32_t*>(p); p += align_up((int64_t)rows * 4, 256);
+    s.ticket = reinterpret_cast<unsigned int*>(p); p += align_up((int64_t)rows * 8, 256);
     s.seed = reinterpret_cast<uint64_t*>(p);
     return s;
 }
@@ -465,7 +531,7 @@ hipError_t launch_unmask_sample(const float* logits, int batch, int gamma, int v
                                 int32_t* z, float* q, float* qtok, const SampleScratch& s, hipStream_t st) {
     const int rows = batch * gamma, nch = n_chunks(vocab), ld = vocab_pad(vocab);
     const dim3 grid(nch, rows);
-    launch_kernel(k_row_stats, dim3(grid), dim3(kThreads), 0, st, logits, ld, vocab, z, gamma, step, seed, s.part_m, s.part_s, s.active);
+    launch_kernel(k_row_stats, dim3(grid), dim3(kThreads), 0, st, logits, ld, vocab, z, gamma, step, seed, s.part_m, s.part_s, s.active, nullptr, nullptr, nullptr);
     launch_kernel(k_unmask_sample, dim3(grid), dim3(kThreads), 0, st, logits, ld, vocab, gamma, step, seed, s.part_m, s.part_s, s.active, z,
                   q, qtok, -1);
     return hipGetLastError();
@@ -492,8 +558,22 @@ hipError_t launch_sps_sample(const float* logits, int batch, int gamma, int voca
         launch_kernel(k_greedy_reveal, dim3(batch), dim3(64), 0, st, pv, pi, nch, s.active, z, qtok, gamma, k);
         return hipGetLastError();
     }
-    launch_kernel(k_row_stats, dim3(grid), dim3(kThreads), 0, st, logits, ld, vocab, nullptr, gamma, 0, seed, s.part_m, s.part_s, s.active);
+    launch_kernel(k_row_stats, dim3(grid), dim3(kThreads), 0, st, logits, ld, vocab, nullptr, gamma, 0, seed, s.part_m, s.part_s, s.active, nullptr, nullptr, nullptr);
     launch_kernel(k_unmask_sample, dim3(grid), dim3(kThreads), 0, st, logits, ld, vocab, gamma, 0, seed, s.part_m, s.part_s, s.active, z, q, qtok, k);
+    return hipGetLastError();
+}
+
+hipError_t launch_greedy_from_tiles(const float* pv, const int32_t* pi, int tiles, int batch, int gamma, int vocab, int step, int sps_k,
+                                    const uint64_t* seed, int32_t* z, float* qtok, hipStream_t st) {
+    launch_kernel(k_greedy_reveal_tiles, dim3(sps_k >= 0 ? batch : batch * gamma), dim3(kThreads), 0, st, pv, pi, tiles, vocab, gamma, step, sps_k, seed, z, qtok);
+    return hipGetLastError();
+}
+
+// top: int32 [batch * (gamma + 1)] scratch
+hipError_t launch_accept_greedy_from_tiles(const float* pv, const int32_t* pi, int tiles, const int32_t* draft, int batch, int gamma,
+                                           int32_t* top, int32_t* n_acc, int32_t* token, hipStream_t st) {
+    launch_kernel(k_row_argmax_tiles, dim3(gamma + 1, batch), dim3(kThreads), 0, st, pv, pi, tiles, top);
+    launch_kernel(k_greedy_accept_top, dim3(batch), dim3(64), 0, st, top, draft, gamma, n_acc, token);
     return hipGetLastError();
 }
 
@@ -507,19 +587,21 @@ hipError_t launch_accept_greedy(const float* p_logits, const int32_t* draft, int
     return hipGetLastError();
 }
 
+hipError_t launch_sampling_reset(const SampleScratch& s, int rows, hipStream_t st) {
+    launch_kernel(k_zero_u32, dim3((2 * rows + 255) / 256), dim3(256), 0, st, s.ticket, 2 * rows);
+    return hipGetLastError();
+}
+
+// Two launches: chunk statistics whose last arrival per row leaves the row's maximum and normaliser, then the
+// acceptance tests, the final-token weights and -- by the last arrival per sequence -- the token.
 hipError_t launch_accept_resample(const float* p_logits, const float* q, const int32_t* draft, int batch,
                                   int gamma, int vocab, const uint64_t* seed, int32_t* n_acc, int32_t* token,
                                   const SampleScratch& s, hipStream_t st) {
     const int rows = batch * (gamma + 1), nch = n_chunks(vocab), ld = vocab_pad(vocab);
     launch_kernel(k_row_stats, dim3(dim3(nch, rows)), dim3(kThreads), 0, st, p_logits, ld, vocab, nullptr, gamma, 0, seed, s.part_m,
-                                                      s.part_s, s.active);
-    launch_kernel(k_accept, dim3(batch), dim3(kThreads), 2 * (gamma + 1) * sizeof(double), st, p_logits, q, draft, ld, vocab, gamma, nch,
-                                                                       seed, s.part_m, s.part_s, n_acc, s.row_m,
-                                                                       s.row_z);
-    launch_kernel(k_final_partial, dim3(dim3(nch, batch)), dim3(kThreads), 0, st, p_logits, q, ld, vocab, gamma, n_acc, s.row_m, s.row_z,
-                                                           s.part_r);
-    launch_kernel(k_final_sample, dim3(batch), dim3(kThreads), 0, st, p_logits, q, ld, vocab, gamma, nch, seed, n_acc, s.row_m, s.row_z,
-                                               s.part_m, s.part_s, s.part_r, token);
+                  s.part_s, s.active, s.ticket, s.row_m, s.row_z);
+    launch_kernel(k_accept_final, dim3(dim3(nch, batch)), dim3(kThreads), 0, st, p_logits, q, draft, ld, vocab, gamma, seed, s.row_m,
+                  s.row_z, s.part_m, s.part_s, s.part_r, s.ticket + rows, n_acc, token);
     return hipGetLastError();
 }
 
