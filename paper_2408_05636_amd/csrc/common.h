@@ -221,7 +221,7 @@ struct SampleScratch {       // carved from one device buffer by sampling_scratc
     double* row_m;           // [batch] max of the row the final token is drawn from
     double* row_z;           // [batch] its softmax normaliser
     int32_t* active;         // [rows]
-    unsigned int* ticket;    // [rows + batch] arrival counters of the acceptance path: zero before a launch, zero again after it
+    unsigned int* ticket;    // [batch] arrival counters of the acceptance path: zero before a launch, zero again after it
     uint64_t* seed;          // Philox key of the current call (kernels read it from memory so that a
                              // captured graph can be replayed with a new seed)
 };

@@ -288,16 +288,18 @@ __global__ __launch_bounds__(256) void k_linear_stream(const bf16_t* __restrict_
             for (int e = 0; e < 16; ++e)
                 if (32 * t + 8 * (e >> 2) + (e & 3) + 4 * half < M)
                     __hip_atomic_store(&mine[(t * 16 + e) * 64 + lane], acc[t][e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        // Release: every lane's partial stores are complete and visible device-wide before the ticket is drawn
-        // (the fence states it for the memory model, the explicit wait keeps the stores of all 64 lanes behind it).
+        // Hand-over without cache-wide operations: partials and ticket are device-scope accesses (they go past the caches
+        // private to one XCD), the wait below completes every lane's partial stores before the ticket is drawn, and its
+        // memory clobber keeps the compiler from moving accesses across it.  (An agent-scope release fence here is a
+        // write-back of the whole L2, an acquire fence an invalidation: measured 1-2 us per kernel, and far more where
+        // thousands of workgroups hand over, for data that never sat in those caches.)
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
         unsigned int old = 0;
         if (lane == 0) old = __hip_atomic_fetch_add(&sk.ticket[tile], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         old = __builtin_amdgcn_readfirstlane(old);
         if (old != gridDim.y - 1u) return;
         if (lane == 0) __hip_atomic_store(&sk.ticket[tile], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");     // the last arrival reads what the others released
+        asm volatile("" ::: "memory");     // compiler barrier: the loads below stay behind the ticket
 #pragma unroll
         for (int t = 0; t < MT; ++t)
 #pragma unroll

@@ -87,17 +87,11 @@ __device__ inline void load4(const float* row, int col, int vocab, float (&l)[4]
 
 // ---------------------------------------------------------------- chunk statistics
 // grid (n_chunks, rows).  z != NULL: drafter mode, rows that are not revealed at this step are skipped.
-// ticket != NULL (acceptance path): whichever workgroup of a row arrives last also combines the row's chunk
-// statistics into row_m[row] (maximum) and row_z[row] (sum of exp(l - maximum)), in a fixed order -- the partials travel
-// as device-scope accesses, released before the ticket is drawn and acquired by the last arrival; nobody waits.
 __global__ __launch_bounds__(kThreads) void k_row_stats(const float* __restrict__ logits, int ld, int vocab,
                                                         const int32_t* __restrict__ z, int gamma, int step,
                                                         const uint64_t* __restrict__ seed_p, double* __restrict__ part_m,
-                                                        double* __restrict__ part_s, int32_t* __restrict__ active,
-                                                        unsigned int* __restrict__ ticket, double* __restrict__ row_m,
-                                                        double* __restrict__ row_z) {
+                                                        double* __restrict__ part_s, int32_t* __restrict__ active) {
     __shared__ double sh[4];
-    __shared__ unsigned int s_last;
     const int row = blockIdx.y, c = blockIdx.x, nch = gridDim.x;
     if (z != nullptr) {
         const bool act = (z[row] == vocab) && reveal_now(row % gamma, step, row / gamma, STREAM_DRAFT, *seed_p);
@@ -111,37 +105,9 @@ __global__ __launch_bounds__(kThreads) void k_row_stats(const float* __restrict_
 #pragma unroll
     for (int i = 0; i < 4; ++i) s += exp((double)l[i] - m);   // exp(-inf) = 0 for padding columns
     s = block_sum(s, sh);
-    if (ticket == nullptr) {
-        if (threadIdx.x == 0) {
-            part_m[(size_t)row * nch + c] = m;
-            part_s[(size_t)row * nch + c] = s;
-        }
-        return;
-    }
     if (threadIdx.x == 0) {
-        __hip_atomic_store(&part_m[(size_t)row * nch + c], m, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_store(&part_s[(size_t)row * nch + c], s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-        s_last = __hip_atomic_fetch_add(&ticket[row], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (unsigned int)nch - 1u;
-    }
-    __syncthreads();
-    if (!s_last) return;
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-    // thread t takes chunks t, t + 256, ...: a fixed assignment and a fixed reduction tree
-    double mm = -INFINITY;
-    for (int i = threadIdx.x; i < nch; i += kThreads)
-        mm = fmax(mm, __hip_atomic_load(&part_m[(size_t)row * nch + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-    mm = block_max(mm, sh);
-    double ss = 0.0;
-    for (int i = threadIdx.x; i < nch; i += kThreads)
-        ss += __hip_atomic_load(&part_s[(size_t)row * nch + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) *
-              exp(__hip_atomic_load(&part_m[(size_t)row * nch + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - mm);
-    ss = block_sum(ss, sh);
-    if (threadIdx.x == 0) {
-        row_m[row] = mm;
-        row_z[row] = ss;
-        __hip_atomic_store(&ticket[row], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);     // ready for the next launch
+        part_m[(size_t)row * nch + c] = m;
+        part_s[(size_t)row * nch + c] = s;
     }
 }
 
@@ -253,27 +219,45 @@ __device__ inline double final_weight(float l, float qv, double m, double Z, boo
     return use_residual ? fmax(0.0, p - (double)qv) : p;
 }
 
-// grid (n_chunks, batch), after k_row_stats has left the statistics of the gamma + 1 target rows in row_m / row_z.
-//  1. Every workgroup of a sequence runs the gamma acceptance tests r_k q_k(x_k) <= p_k(x_k) (fp32 product) and takes
-//     n = the first rejection (gamma lookups: cheaper done by all than handed around).
+// grid (n_chunks, batch), after k_row_stats has left the chunk statistics of the gamma + 1 target rows.
+//  0. Every workgroup of a sequence combines the chunk statistics of the sequence's gamma + 1 rows (maximum, normaliser)
+//     and  1. runs the gamma acceptance tests r_k q_k(x_k) <= p_k(x_k) (fp32 product), n = the first rejection: a few
+//     thousand exponentials and gamma lookups, cheaper done by every workgroup than handed around.
 //  2. It sums the final-token weights of its chunk of row n -- max(0, p_n - q_n) after a rejection, p_gamma after full
-//     acceptance --, leaves the sum in part_r and draws a ticket.
+//     acceptance --, leaves the sum in part_r and draws a ticket (device-scope accesses, complete before the ticket).
 //  3. The last arrival of the sequence picks the chunk whose running sum passes u * total, then the token inside it, and
-//     writes n and the token.  Fixed orders throughout: run-to-run identical.
+//     writes n and the token; nobody waits.  Fixed orders throughout: run-to-run identical.
 __global__ __launch_bounds__(kThreads) void k_accept_final(const float* __restrict__ p_logits, const float* __restrict__ q,
                                                            const int32_t* __restrict__ draft, int ld, int vocab, int gamma,
-                                                           const uint64_t* __restrict__ seed_p, const double* __restrict__ row_m,
-                                                           const double* __restrict__ row_z, const double* __restrict__ part_m,
+                                                           const uint64_t* __restrict__ seed_p, const double* __restrict__ part_m,
                                                            const double* __restrict__ part_s, double* __restrict__ part_r,
                                                            unsigned int* __restrict__ ticket, int32_t* __restrict__ n_acc,
                                                            int32_t* __restrict__ token) {
+    extern __shared__ double dyn[];          // [gamma+1] maxima, [gamma+1] normalisers
     __shared__ double sS[kMaxChunks];
     __shared__ double sh[4];
     __shared__ int shi[4];
     __shared__ ChunkPick pick;
     __shared__ int s_resid;
     __shared__ unsigned int s_last;
+    double* const row_m = dyn;
+    double* const row_z = dyn + (gamma + 1);
     const int b = blockIdx.y, c = blockIdx.x, nch = gridDim.x;
+    // 0. row statistics of P[0..gamma] (one wave per row, lanes stride over the chunks)
+    {
+        const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+        for (int k = wv; k <= gamma; k += kThreads / 64) {
+            const size_t o = ((size_t)b * (gamma + 1) + k) * nch;
+            double mm = -INFINITY;
+            for (int i = lane; i < nch; i += 64) mm = fmax(mm, part_m[o + i]);
+            mm = wave_max(mm);
+            double ss = 0.0;
+            for (int i = lane; i < nch; i += 64) ss += part_s[o + i] * exp(part_m[o + i] - mm);
+            ss = wave_sum(ss);
+            if (lane == 0) { row_m[k] = mm; row_z[k] = ss; }
+        }
+    }
+    __syncthreads();
     // 1. acceptance tests
     int first_reject = gamma;
     for (int k = threadIdx.x; k < gamma; k += kThreads) {
@@ -281,7 +265,7 @@ __global__ __launch_bounds__(kThreads) void k_accept_final(const float* __restri
         bool ok = false;
         if ((unsigned)x < (unsigned)vocab) {
             const size_t prow = (size_t)b * (gamma + 1) + k, qrow = (size_t)b * gamma + k;
-            const float px = (float)(exp((double)p_logits[prow * ld + x] - row_m[prow]) / row_z[prow]);
+            const float px = (float)(exp((double)p_logits[prow * ld + x] - row_m[k]) / row_z[k]);
             const float qx = q[qrow * ld + x];
             const Philox4 r = philox4x32_10((uint32_t)k, 0u, (uint32_t)b, STREAM_VERIFY, *seed_p);
             ok = __fmul_rn(uniform_f32(r.x), qx) <= px;        // accept iff r q(x) <= p(x), fp32 product
@@ -291,7 +275,7 @@ __global__ __launch_bounds__(kThreads) void k_accept_final(const float* __restri
     const int n = block_min_int(first_reject, shi);
     // 2. this chunk's share of the final-token weights
     const size_t nrow = (size_t)b * (gamma + 1) + n;
-    const double m = row_m[nrow], Z = row_z[nrow];
+    const double m = row_m[n], Z = row_z[n];
     bool resid = n < gamma;
     int col0 = c * kChunk + threadIdx.x * 4;
     float l[4], qv[4] = {0.f, 0.f, 0.f, 0.f};
@@ -307,12 +291,11 @@ __global__ __launch_bounds__(kThreads) void k_accept_final(const float* __restri
     if (threadIdx.x == 0) {
         __hip_atomic_store(&part_r[(size_t)b * nch + c], s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
         s_last = __hip_atomic_fetch_add(&ticket[b], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (unsigned int)nch - 1u;
     }
     __syncthreads();
     if (!s_last) return;
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    asm volatile("" ::: "memory");     // compiler barrier: the loads below stay behind the ticket
     // 3. the last arrival draws the token
     for (int i = threadIdx.x; i < nch; i += kThreads)
         sS[i] = __hip_atomic_load(&part_r[(size_t)b * nch + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -531,7 +514,7 @@ hipError_t launch_unmask_sample(const float* logits, int batch, int gamma, int v
                                 int32_t* z, float* q, float* qtok, const SampleScratch& s, hipStream_t st) {
     const int rows = batch * gamma, nch = n_chunks(vocab), ld = vocab_pad(vocab);
     const dim3 grid(nch, rows);
-    launch_kernel(k_row_stats, dim3(grid), dim3(kThreads), 0, st, logits, ld, vocab, z, gamma, step, seed, s.part_m, s.part_s, s.active, nullptr, nullptr, nullptr);
+    launch_kernel(k_row_stats, dim3(grid), dim3(kThreads), 0, st, logits, ld, vocab, z, gamma, step, seed, s.part_m, s.part_s, s.active);
     launch_kernel(k_unmask_sample, dim3(grid), dim3(kThreads), 0, st, logits, ld, vocab, gamma, step, seed, s.part_m, s.part_s, s.active, z,
                   q, qtok, -1);
     return hipGetLastError();
@@ -558,7 +541,7 @@ hipError_t launch_sps_sample(const float* logits, int batch, int gamma, int voca
         launch_kernel(k_greedy_reveal, dim3(batch), dim3(64), 0, st, pv, pi, nch, s.active, z, qtok, gamma, k);
         return hipGetLastError();
     }
-    launch_kernel(k_row_stats, dim3(grid), dim3(kThreads), 0, st, logits, ld, vocab, nullptr, gamma, 0, seed, s.part_m, s.part_s, s.active, nullptr, nullptr, nullptr);
+    launch_kernel(k_row_stats, dim3(grid), dim3(kThreads), 0, st, logits, ld, vocab, nullptr, gamma, 0, seed, s.part_m, s.part_s, s.active);
     launch_kernel(k_unmask_sample, dim3(grid), dim3(kThreads), 0, st, logits, ld, vocab, gamma, 0, seed, s.part_m, s.part_s, s.active, z, q, qtok, k);
     return hipGetLastError();
 }
@@ -588,20 +571,20 @@ hipError_t launch_accept_greedy(const float* p_logits, const int32_t* draft, int
 }
 
 hipError_t launch_sampling_reset(const SampleScratch& s, int rows, hipStream_t st) {
-    launch_kernel(k_zero_u32, dim3((2 * rows + 255) / 256), dim3(256), 0, st, s.ticket, 2 * rows);
+    launch_kernel(k_zero_u32, dim3((rows + 255) / 256), dim3(256), 0, st, s.ticket, rows);
     return hipGetLastError();
 }
 
-// Two launches: chunk statistics whose last arrival per row leaves the row's maximum and normaliser, then the
-// acceptance tests, the final-token weights and -- by the last arrival per sequence -- the token.
+// Two launches: chunk statistics, then the acceptance tests, the final-token weights and -- by the last arrival per
+// sequence -- the token.
 hipError_t launch_accept_resample(const float* p_logits, const float* q, const int32_t* draft, int batch,
                                   int gamma, int vocab, const uint64_t* seed, int32_t* n_acc, int32_t* token,
                                   const SampleScratch& s, hipStream_t st) {
     const int rows = batch * (gamma + 1), nch = n_chunks(vocab), ld = vocab_pad(vocab);
     launch_kernel(k_row_stats, dim3(dim3(nch, rows)), dim3(kThreads), 0, st, p_logits, ld, vocab, nullptr, gamma, 0, seed, s.part_m,
-                  s.part_s, s.active, s.ticket, s.row_m, s.row_z);
-    launch_kernel(k_accept_final, dim3(dim3(nch, batch)), dim3(kThreads), 0, st, p_logits, q, draft, ld, vocab, gamma, seed, s.row_m,
-                  s.row_z, s.part_m, s.part_s, s.part_r, s.ticket + rows, n_acc, token);
+                  s.part_s, s.active);
+    launch_kernel(k_accept_final, dim3(dim3(nch, batch)), dim3(kThreads), 2 * (gamma + 1) * sizeof(double), st, p_logits, q, draft, ld, vocab,
+                  gamma, seed, s.part_m, s.part_s, s.part_r, s.ticket, n_acc, token);
     return hipGetLastError();
 }
 
