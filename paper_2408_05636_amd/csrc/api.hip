@@ -742,16 +742,25 @@ int run_layers(sd_handle* h, const Model& m, const MapSet& rm, const float* temb
     const bool head_fold = fold && head_rows > 0 && rm.head_row0 >= 0 && linear_mfma_supported(dt, head_rows, c.vocab, d, m.ld);
     h->head_folded = head_fold;
     int parts = 1;                      // partial row sums per row currently in buf.stats
-    auto fold_in = [&](const float* u) {
+    // r0: first row of the call (the row sums of row r sit at stats[r][parts][2], xn at xn[r][d])
+    auto fold_in = [&](const float* u, int r0 = 0) {
         NormIn ni;
-        ni.kind = ln ? 1 : 2; ni.stats = B.stats; ni.parts = parts; ni.u = ln ? u : nullptr; ni.eps = c.norm_eps;
+        ni.kind = ln ? 1 : 2; ni.stats = B.stats + (size_t)r0 * parts * 2; ni.parts = parts; ni.u = ln ? u : nullptr; ni.eps = c.norm_eps;
         return ni;
     };
-    auto fold_out = [&](const float* gain) {
+    auto fold_out = [&](const float* gain, int r0 = 0) {
         NormOut no;
-        no.gain = gain; no.xg = B.xn; no.stats = B.stats;
+        no.gain = gain; no.xg = static_cast<char*>(B.xn) + (size_t)r0 * d * 2; no.stats = B.stats + (size_t)r0 * parts_d * 2;
         return no;
     };
+    // Last layer of the drafter at batch 1: only the block's rows reach the LM head, and after the QKV contraction
+    // (keys and values of every row are still needed) nothing else reads the prefix rows.  Attention, attention
+    // output and MLP then run on the rows from t0 on (the 32-row tile that holds the block's first row).
+    int t0 = 0;
+    if (head_fold && !cached && rm.regular && rm.head_row0 >= 32) {
+        const int cand = rm.head_row0 / 32 * 32, n = rows - cand;
+        if (linear_mfma_supported(dt, n, d, d, d) && linear_mfma_supported(dt, n, up_w, d, up_w) && linear_mfma_supported(dt, n, d, c.d_ff, d)) t0 = cand;
+    }
     int rc;
     SD_LAUNCH(h, "k_embed", rd * (4 + ew + (fold ? 2 : 0)), 0,
               launch_embed(dt, rm.src, rm.pos, rm.tokens, B.z, m.wte, m.wpe, temb, B.h, rows, d, fold ? m.L[0].ln1_g : nullptr, B.xn, B.stats, h->st));
@@ -783,15 +792,18 @@ int run_layers(sd_handle* h, const Model& m, const MapSet& rm, const float* temb
         const bool rope_into_cache = c.arch == SD_ARCH_LLAMA && cached;     // one kernel for both
         if (c.arch == SD_ARCH_LLAMA && !rope_into_cache)
             SD_LAUNCH(h, "k_rope", 2.0 * rows * (m.dq + m.dkv) * ew, 0, launch_rope(dt, B.qkv, rm.pos, rows, c.n_head, c.n_kv_head, m.dh, c.rope_theta, h->st));
+        // r0, nr: the rows everything after the QKV contraction runs on
+        const int r0 = i + 1 == c.n_layer ? t0 : 0, nr = rows - r0;
+        auto at = [&](void* p, int64_t width, int64_t esz) { return static_cast<void*>(static_cast<char*>(p) + (int64_t)r0 * width * esz); };
         AttnArgs a;
-        a.q = B.qkv; a.q_ld = qkv_w;
+        a.q = at(B.qkv, qkv_w, m.ew); a.q_ld = qkv_w;
         a.kv_off = rm.kv_off; a.kv_len = rm.kvl;
-        a.out = B.att; a.out_ld = d;
-        a.rows = rows; a.n_head = c.n_head; a.n_kv_head = c.n_kv_head; a.d_head = m.dh; a.max_kv = rm.max_kv;
-        a.tiles = rm.tiles; a.n_tiles = rm.n_tiles;
+        a.out = at(B.att, d, m.ew); a.out_ld = d;
+        a.rows = nr; a.n_head = c.n_head; a.n_kv_head = c.n_kv_head; a.d_head = m.dh; a.max_kv = rm.max_kv;
+        a.tiles = rm.tiles; a.n_tiles = r0 ? (nr + 31) / 32 : rm.n_tiles;
         a.regular = !cached && rm.regular;
-        if (rm.grouped) { a.order = rm.order; a.n_order = rm.n_order; }      // the plain order needs no table (and no load of it)
-        a.groups = rm.groups; a.n_groups = rm.n_groups; a.group_tiles = rm.group_tiles;
+        if (rm.grouped && !r0) { a.order = rm.order; a.n_order = rm.n_order; }      // the plain order needs no table (and no load of it)
+        if (!r0) { a.groups = rm.groups; a.n_groups = rm.n_groups; a.group_tiles = rm.group_tiles; }
         if (cached) {
             if (kv_direct) {
                 // already in the cache
@@ -807,37 +819,38 @@ int run_layers(sd_handle* h, const Model& m, const MapSet& rm, const float* temb
             a.kv_ld = qkv_w;
         }
         const char* aname = "attention";
-        SD_LAUNCH(h, aname, 2.0 * rd * ew + 2.0 * rm.kv_rows * m.dkv * ew, 4.0 * rm.kv_sum * d, launch_attention(dt, a, h->st, &aname));
+        SD_LAUNCH(h, aname, 2.0 * nr * d * ew + 2.0 * rm.kv_rows * m.dkv * ew, 4.0 * (r0 ? (double)nr * rm.max_kv : (double)rm.kv_sum) * d,
+                  launch_attention(dt, a, h->st, &aname));
         // attention output: h += ..., and xn / row sums for the normalisation in front of the MLP
-        if ((rc = run_linear(h, dt, B.att, l.w_o, l.b_o, B.h, rows, d, d, d, EPI_RESID, NormIn(), fold ? fold_out(l.ln2_g) : NormOut()))) return rc;
+        if ((rc = run_linear(h, dt, at(B.att, d, m.ew), l.w_o, l.b_o, at(B.h, d, 4), nr, d, d, d, EPI_RESID, NormIn(), fold ? fold_out(l.ln2_g, r0) : NormOut()))) return rc;
         if (fold) parts = parts_d;
         if (!fold) SD_LAUNCH(h, "k_norm", rd * (4 + ew), 0, launch_norm(dt, B.h, nullptr, l.ln2_g, ln ? l.ln2_b : nullptr, B.xn, rows, d, c.norm_eps, h->st));
-        const NormIn up_in = fold ? fold_in(l.fu_fc) : NormIn();
+        const NormIn up_in = fold ? fold_in(l.fu_fc, r0) : NormIn();
         const float* up_bias = ln ? (fold ? l.fv_fc : l.b_fc) : nullptr;
         const void* down_x;
         if (ln) {
-            if ((rc = run_linear(h, dt, B.xn, l.w_fc, up_bias, B.mlp, rows, up_w, d, up_w, EPI_GELU, up_in))) return rc;
-            down_x = B.mlp;
+            if ((rc = run_linear(h, dt, at(B.xn, d, m.ew), l.w_fc, up_bias, at(B.mlp, up_w, m.ew), nr, up_w, d, up_w, EPI_GELU, up_in))) return rc;
+            down_x = at(B.mlp, up_w, m.ew);
         } else {
             // Few rows against the long gate | up stream: the gating runs in the contraction's epilogue (gate and up tiles
             // of the same columns in one workgroup), gate / up never reach memory.  Otherwise contraction, then gating kernel.
-            const bool gated = fold && rows <= 64 && up_w % 128 == 0;
+            const bool gated = fold && nr <= 64 && up_w % 128 == 0;
             if (gated) {
-                const double bytes = ((double)rows * d + (double)up_w * d) * ew + (double)rows * c.d_ff * ew;
+                const double bytes = ((double)nr * d + (double)up_w * d) * ew + (double)nr * c.d_ff * ew;
                 const char* name = "linear";
-                SD_LAUNCH(h, name, bytes, 2.0 * rows * up_w * d,
-                          launch_linear_stream(B.xn, l.w_fc, nullptr, B.act, rows, up_w, d, c.d_ff, EPI_SWIGLU, up_in, NormOut(), h->buf.split, 0, h->st, &name));
+                SD_LAUNCH(h, name, bytes, 2.0 * nr * up_w * d,
+                          launch_linear_stream(at(B.xn, d, m.ew), l.w_fc, nullptr, at(B.act, c.d_ff, m.ew), nr, up_w, d, c.d_ff, EPI_SWIGLU, up_in, NormOut(), h->buf.split, 0, h->st, &name));
             }
             if (!gated) {
-                if ((rc = run_linear(h, dt, B.xn, l.w_fc, up_bias, B.mlp, rows, up_w, d, up_w, EPI_STORE, up_in))) return rc;
-                SD_LAUNCH(h, "k_swiglu", 3.0 * rows * c.d_ff * ew, 0, launch_swiglu(dt, B.mlp, B.act, rows, c.d_ff, h->st));
+                if ((rc = run_linear(h, dt, at(B.xn, d, m.ew), l.w_fc, up_bias, at(B.mlp, up_w, m.ew), nr, up_w, d, up_w, EPI_STORE, up_in))) return rc;
+                SD_LAUNCH(h, "k_swiglu", 3.0 * nr * c.d_ff * ew, 0, launch_swiglu(dt, at(B.mlp, up_w, m.ew), at(B.act, c.d_ff, m.ew), nr, c.d_ff, h->st));
             }
-            down_x = B.act;
+            down_x = at(B.act, c.d_ff, m.ew);
         }
         // MLP down: h += ..., and xn / row sums for the first normalisation of the next layer
         const bool more = fold && i + 1 < c.n_layer;
-        if ((rc = run_linear(h, dt, down_x, l.w_proj, ln ? l.b_proj : nullptr, B.h, rows, d, c.d_ff, d, EPI_RESID, NormIn(),
-                             more ? fold_out(m.L[i + 1].ln1_g) : (head_fold ? fold_out(m.lnf_g) : NormOut())))) return rc;
+        if ((rc = run_linear(h, dt, down_x, l.w_proj, ln ? l.b_proj : nullptr, at(B.h, d, 4), nr, d, c.d_ff, d, EPI_RESID, NormIn(),
+                             more ? fold_out(m.L[i + 1].ln1_g) : (head_fold ? fold_out(m.lnf_g, r0) : NormOut())))) return rc;
     }
     return SD_OK;
 }

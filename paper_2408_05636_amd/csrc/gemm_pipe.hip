@@ -321,7 +321,11 @@ static hipError_t launch_pipe(const void* x, const bf16_t* wb, const float* bias
 // couple of thousand rows against a wide weight matrix (the drafter's QKV and MLP-up layers, the batched target's):
 // the largest tile that still gives about 150 workgroups, i.e. one round of workgroups on most of the chip.
 int linear_pipe_shape(int m, int n, int k) {
-    if (m < 192 || m > 2048 || n < 2048 || k / 64 < 5) return -1;
+    // narrow outputs, short K, around a thousand rows (the drafter's attention-output projection at a 1024-token prefix):
+    // 64 x 64 tiles, one chunk per stage (1056 x 768 x 768 with the residual / normalisation epilogue: 8.3 us against 10.4
+    // for the wave-private quadrants and 9.0 for the K-splitting few-row tiles; no gain at 544 or 4224 rows, nor at K = 3072)
+    if (n < 2048) return (m >= 800 && m <= 2048 && n >= 512 && k <= 1024 && k / 64 >= 5) ? 0 : -1;
+    if (m < 192 || m > 2048 || k / 64 < 5) return -1;
     for (int s = 2; s >= 0; --s) {
         const PipeShape& p = kPipeShapes[s];
         if ((long)((m + p.bm - 1) / p.bm) * ((n + p.bn - 1) / p.bn) >= 150)
