@@ -495,33 +495,46 @@ int upload_rows(sd_handle* h, int mode, int batch, const int32_t* tokens, const 
     char* hb = mode >= 3 ? h->sps_stage[sps_slot] : h->stage_maps[mode];
     const int64_t map_cap = mode == 3 ? h->sps_map_cap : h->lim.map_bytes;
     // Attention launch order.  Workgroups go to the 8 XCDs round-robin by linear id and every XCD has its own
-    // L2: all query tiles and query heads that read the same keys and values (one sequence, one KV head) are
-    // placed on one XCD, back to back, so that K and V are fetched into one L2 once instead of into all of
-    // them by turns.  When all keys and values fit any L2 anyway the plain order spreads the load better.
+    // L2.  Query tiles and query heads that read the same keys and values (one sequence, one KV head) are
+    // placed back to back on one XCD, so that K and V are fetched into one L2 once instead of into all of
+    // them by turns: the list of (sequence, KV head, query head, tile) in that order is cut into eight
+    // consecutive pieces of equal work (key blocks walked, plus a constant per workgroup), one per XCD --
+    // a KV head then lands in at most two L2s, and no XCD gets more than its share (dealing out whole KV
+    // heads leaves half the chip idle when 12 heads meet 8 XCDs).  When all keys and values fit any L2
+    // anyway the plain order is used.
     const int n_kv_groups = m.c.n_kv_head, q_per_kv = m.c.n_head / m.c.n_kv_head;
     std::vector<std::vector<int32_t>> per_xcd(8), grp_xcd(8);
     int group_tiles = 0;
     bool grouped_order = false;
     {
         double kv_bytes = 0;
-        for (int b = 0; b < batch; ++b) kv_bytes += 2.0 * m.ew * m.dkv * (mode == 2 || mode == 4 ? len[b] - 1 : len[b] + gamma);
+        auto kv_of = [&](int b) { return (int64_t)(mode == 2 || mode == 4 ? len[b] - 1 : len[b] + gamma); };
+        for (int b = 0; b < batch; ++b) kv_bytes += 2.0 * m.ew * m.dkv * kv_of(b);
         const bool grouped = kv_bytes > 2.0e6;
         grouped_order = grouped;
-        int64_t t0 = 0, lin = 0;
+        auto work_of = [&](int b) { return (kv_of(b) + 31) / 32 + 2; };
+        int64_t total = 0, total_grp = 0;
+        for (int b = 0; b < batch; ++b) {
+            const int64_t ntb = (rows_of(b) + 31) / 32;
+            total += work_of(b) * ntb * m.c.n_head;
+            total_grp += work_of(b) * ((ntb + 3) / 4) * m.c.n_head;
+        }
+        int64_t t0 = 0, lin = 0, done = 0, done_grp = 0;
         for (int b = 0; b < batch; ++b) {
             const int64_t rb = rows_of(b);
             const int64_t ntb = (rb + 31) / 32;
+            const int64_t wk = work_of(b);
             for (int g = 0; g < n_kv_groups; ++g)
                 for (int qh = 0; qh < q_per_kv; ++qh)
-                    for (int64_t t = 0; t < ntb; ++t, ++lin)
-                        per_xcd[grouped ? (b * n_kv_groups + g) % 8 : lin % 8].push_back((int32_t)(t0 + t) | ((g * q_per_kv + qh) << 20));
+                    for (int64_t t = 0; t < ntb; ++t, ++lin, done += wk)
+                        per_xcd[grouped ? (8 * done + 4 * wk) / total % 8 : lin % 8].push_back((int32_t)(t0 + t) | ((g * q_per_kv + qh) << 20));
             // the same work as groups of up to four consecutive tiles (they share the sequence's keys)
             for (int g = 0; g < n_kv_groups; ++g)
                 for (int qh = 0; qh < q_per_kv; ++qh)
-                    for (int64_t t = 0; t < ntb; t += 4) {
+                    for (int64_t t = 0; t < ntb; t += 4, done_grp += wk) {
                         const int n = (int)(ntb - t < 4 ? ntb - t : 4);
                         group_tiles = n > group_tiles ? n : group_tiles;
-                        grp_xcd[(b * n_kv_groups + g) % 8].push_back((int32_t)(t0 + t) | ((n - 1) << 18) | ((g * q_per_kv + qh) << 20));
+                        grp_xcd[(8 * done_grp + 4 * wk) / total_grp % 8].push_back((int32_t)(t0 + t) | ((n - 1) << 18) | ((g * q_per_kv + qh) << 20));
                     }
             t0 += ntb;
         }

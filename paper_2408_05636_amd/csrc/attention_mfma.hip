@@ -50,16 +50,22 @@ __device__ inline bf16x8 vt_operand(const u32x4* v_tile, const int* off) {
     return __builtin_bit_cast(bf16x8, both);
 }
 
-template <int DH, bool KSPLIT>
+// KW: 0 -- the waves of a workgroup take four query tiles; 4 -- the four waves share the key range of one tile.
+template <int DH, int KW>
+constexpr int attention_lds_bytes() {
+    constexpr int stage = (KW ? KW : 4) * 2 * (DH / 64) * 256 * 16;
+    constexpr int merge = KW ? (KW - 1) * (2 + DH / 32 * 16) * 64 * 4 : 0;
+    return stage > merge ? stage : merge;
+}
+template <int DH, int KW>
 __global__ __launch_bounds__(256, (DH == 64 ? 2 : 1)) void k_attention_mfma(AttnArgs a) {
+    static_assert(KW == 0 || KW == 4, "a workgroup is four waves");
+    constexpr bool KSPLIT = KW > 0;
     constexpr int NCH = DH / 64;     // 64-wide chunks of a q / k row
     constexpr int DT = DH / 32;      // 32-row tiles of O^T
     // Per wave: a K tile and a V tile of 32 keys (NCH x 4 KB each), private to the wave.  After the loop the
-    // key-splitting variant reuses the memory to merge its four partial results.
-    constexpr int kStageVecs = 4 * 2 * NCH * 256;                              // u32x4 units
-    constexpr int kMergeFloats = KSPLIT ? 3 * (2 + DT * 16) * 64 : 0;
-    constexpr int kSmemVecs = kStageVecs > (kMergeFloats + 3) / 4 ? kStageVecs : (kMergeFloats + 3) / 4;
-    __shared__ u32x4 smem[kSmemVecs];
+    // key-splitting variant reuses the memory to merge its partial results.
+    extern __shared__ u32x4 smem[];
 
     // wave-uniform values are kept in scalar registers (tile description, buffer descriptors, block counters)
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -144,7 +150,7 @@ __global__ __launch_bounds__(256, (DH == 64 ? 2 : 1)) void k_attention_mfma(Attn
     const float scale = rsqrtf((float)DH) * 1.4426950408889634f;     // scores in log2 units
 
     const int n_blocks = (kv_max + 31) / 32;
-    constexpr int kStep = KSPLIT ? 4 : 1;
+    constexpr int kStep = KSPLIT ? KW : 1;
     u32x4 kc[NCH][4], vc[NCH][4], kn[NCH][4], vn[NCH][4];
 #define SD_LOAD_BLOCK(KR, VR, KB)                                                                        \
     {                                                                                                    \
@@ -216,11 +222,12 @@ __global__ __launch_bounds__(256, (DH == 64 ? 2 : 1)) void k_attention_mfma(Attn
 #undef SD_ATTN_BLOCK
 #undef SD_LOAD_BLOCK
 
-    if constexpr (KSPLIT) {            // merge the four key ranges in a fixed order
+    if constexpr (KSPLIT) {            // merge the key ranges in a fixed order
         float* const mf = reinterpret_cast<float*>(smem);
-        float (*mrg_m)[64] = reinterpret_cast<float (*)[64]>(mf);                       // [3][64]
-        float (*mrg_l)[64] = reinterpret_cast<float (*)[64]>(mf + 3 * 64);              // [3][64]
-        float (*mrg_o)[DT * 16][64] = reinterpret_cast<float (*)[DT * 16][64]>(mf + 6 * 64);   // [3][DT*16][64]
+        constexpr int NP = KW - 1;     // partial results besides wave 0's own
+        float (*mrg_m)[64] = reinterpret_cast<float (*)[64]>(mf);                       // [NP][64]
+        float (*mrg_l)[64] = reinterpret_cast<float (*)[64]>(mf + NP * 64);             // [NP][64]
+        float (*mrg_o)[DT * 16][64] = reinterpret_cast<float (*)[DT * 16][64]>(mf + 2 * NP * 64);   // [NP][DT*16][64]
         __syncthreads();               // every wave is done with its staging tiles
         if (wave > 0) {
             mrg_m[wave - 1][lane] = m_run;
@@ -234,7 +241,7 @@ __global__ __launch_bounds__(256, (DH == 64 ? 2 : 1)) void k_attention_mfma(Attn
         if (wave > 0) return;
         float m_all = m_run;
 #pragma unroll
-        for (int w = 0; w < 3; ++w) m_all = fmaxf(m_all, mrg_m[w][lane]);
+        for (int w = 0; w < NP; ++w) m_all = fmaxf(m_all, mrg_m[w][lane]);
         const float f0 = m_run == -INFINITY ? 0.f : exp2f((m_run - m_all) * scale);
         l_run *= f0;
 #pragma unroll
@@ -242,7 +249,7 @@ __global__ __launch_bounds__(256, (DH == 64 ? 2 : 1)) void k_attention_mfma(Attn
 #pragma unroll
             for (int e = 0; e < 16; ++e) o[t][e] *= f0;
 #pragma unroll
-        for (int w = 0; w < 3; ++w) {
+        for (int w = 0; w < NP; ++w) {
             const float mw = mrg_m[w][lane];
             const float fw = mw == -INFINITY ? 0.f : exp2f((mw - m_all) * scale);
             l_run += mrg_l[w][lane] * fw;
@@ -429,6 +436,19 @@ __global__ __launch_bounds__(256, (DH == 64 ? 2 : 1)) void k_attention_group(Att
         }
 }
 
+template <int DH, int KW>
+static hipError_t launch_attention_kernel(dim3 grid, hipStream_t st, const AttnArgs& a) {
+    constexpr int kLds = attention_lds_bytes<DH, KW>();
+    static bool raised = false;                   // more than the default 64 KB of LDS: allowed once per kernel
+    if (kLds > 65536 && !raised) {
+        const hipError_t e = hipFuncSetAttribute((const void*)k_attention_mfma<DH, KW>, hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
+        if (e != hipSuccess) return e;
+        raised = true;
+    }
+    launch_kernel(k_attention_mfma<DH, KW>, grid, dim3(256), kLds, st, a);
+    return hipGetLastError();
+}
+
 bool attention_mfma_supported(int dtype, const AttnArgs& a) {
     return dtype == SD_DTYPE_BF16 && (a.d_head == 64 || a.d_head == 128) && a.tiles != nullptr && a.n_tiles > 0 &&
            a.q_ld % 8 == 0 && a.kv_ld % 8 == 0 && a.out_ld % 4 == 0 && (int64_t)a.max_kv * a.kv_ld * 2 < ((int64_t)1 << 31) &&
@@ -442,16 +462,21 @@ hipError_t launch_attention_mfma(const AttnArgs& a, hipStream_t st, const char**
         else { if (kernel_name) *kernel_name = "k_attention_group<128>"; launch_kernel(k_attention_group<128>, dim3(a.n_groups), dim3(256), 0, st, a); }
         return hipGetLastError();
     }
-    const bool ksplit = (long)a.n_tiles * a.n_head < 1024 && a.max_kv > 64;   // few tiles: the four waves share the key range of one tile
-    const dim3 grid = ksplit ? (a.order ? dim3(a.n_order, 1) : dim3(a.n_tiles, a.n_head)) : dim3((a.n_tiles + 3) / 4, a.n_head);
-    if (a.d_head == 64) {
-        if (ksplit) { if (kernel_name) *kernel_name = "k_attention_mfma<64,true>"; launch_kernel(k_attention_mfma<64, true>, dim3(grid), dim3(256), 0, st, a); }
-        else { if (kernel_name) *kernel_name = "k_attention_mfma<64,false>"; launch_kernel(k_attention_mfma<64, false>, dim3(grid), dim3(256), 0, st, a); }
-    } else {
-        if (ksplit) { if (kernel_name) *kernel_name = "k_attention_mfma<128,true>"; launch_kernel(k_attention_mfma<128, true>, dim3(grid), dim3(256), 0, st, a); }
-        else { if (kernel_name) *kernel_name = "k_attention_mfma<128,false>"; launch_kernel(k_attention_mfma<128, false>, dim3(grid), dim3(256), 0, st, a); }
+    // few tiles: the four waves of a workgroup share the key range of one tile.  (Eight waves per tile were measured too:
+    // slower -- 256 registers per lane leave one workgroup per CU, and the chip then needs two rounds of them.)
+    const int kw = (long)a.n_tiles * a.n_head < 1024 && a.max_kv > 64 ? 4 : 0;
+    const dim3 grid = kw ? (a.order ? dim3(a.n_order, 1) : dim3(a.n_tiles, a.n_head)) : dim3((a.n_tiles + 3) / 4, a.n_head);
+#define SD_GO(DH, KW)                                                                                          \
+    {                                                                                                          \
+        if (kernel_name) *kernel_name = "k_attention_mfma<" #DH "," #KW ">";                                   \
+        return launch_attention_kernel<DH, KW>(grid, st, a);                                                   \
     }
-    return hipGetLastError();
+    if (a.d_head == 64) {
+        if (kw == 4) SD_GO(64, 4) else SD_GO(64, 0)
+    } else {
+        if (kw == 4) SD_GO(128, 4) else SD_GO(128, 0)
+    }
+#undef SD_GO
 }
 
 }  // namespace sd

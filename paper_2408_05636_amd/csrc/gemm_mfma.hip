@@ -52,22 +52,11 @@ __global__ __launch_bounds__(256, (MT * NT == 1 ? 3 : 1)) void k_linear_mfma(con
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int r = lane & 31, half = lane >> 5;
     const int wm = wave % WM, wn = (wave / WM) % WN, wk = wave / (WM * WN);
-    // Workgroups are handed to the 8 XCDs round-robin by linear id, and each XCD has its own L2.  The
-    // larger operand decides the mapping.  Weights larger (few rows): column tile tn lives on XCD tn % 8
-    // with all its row tiles, launched back to back, so a panel of W is fetched into exactly one L2
-    // instead of being pulled through the fabric by several of them.  x larger (many rows): row tile tm
-    // lives on XCD tm % 8 with all its column tiles back to back, so x is streamed from HBM once (per
-    // XCD a row tile at a time) while W, which then fits an L2, is re-read from there.
-    const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
+    // Tile of this workgroup (XCD-aware order, see xcd_tile): with the weights larger (few rows) a panel of W is
+    // fetched into one L2 instead of being pulled through the fabric by several of them; with x larger (many rows) x
+    // is streamed from HBM once while W, which then fits an L2, is re-read from there.
     int tn, tm;
-    if (sk.x_stationary) {
-        tm = xcd + 8 * (local / tiles_n);
-        tn = local % tiles_n;
-    } else {
-        tn = xcd + 8 * (local / tiles_m);
-        tm = local % tiles_m;
-    }
-    if (tn >= tiles_n || tm >= tiles_m) return;         // padding workgroup of an XCD with fewer tiles
+    if (!xcd_tile(tiles_m, tiles_n, sk.x_stationary, tm, tn)) return;
     const int m_base = (tm * WM + wm) * 32 * MT;
     const int n_base = (tn * WN + wn) * 32 * NT;
     // EPI_STORE_ROPE (one column tile per wave): a tile inside the rotated columns does not take 32 consecutive W rows but
@@ -535,8 +524,7 @@ static hipError_t launch_variant(const void* x, const void* w, const float* bias
             }
         }
     }
-    // every XCD gets the id range of the fullest one
-    const dim3 grid(sk.x_stationary ? 8 * ((tiles_m + 7) / 8) * tiles_n : 8 * ((tiles_n + 7) / 8) * tiles_m, sk.gsplit);
+    const dim3 grid(xcd_grid(tiles_m, tiles_n), sk.gsplit);
     const bf16_t* wb = (const bf16_t*)w;
     const FoldIn fi{ni.stats, ni.u, ni.parts, ni.eps};
     const FoldOut fo{no.gain, static_cast<bf16_t*>(no.xg), no.stats};

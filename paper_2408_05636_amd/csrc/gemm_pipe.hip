@@ -67,17 +67,8 @@ __global__ __launch_bounds__(256) void k_linear_pipe(const void* __restrict__ Xv
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int r = lane & 31, half = lane >> 5;
     const int wm = wave % WMV, wn = wave / WMV;
-    // XCD-aware tile order (workgroups go to the 8 XCDs round-robin): the larger operand is fetched by one XCD only.
-    const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
-    int tn, tm;
-    if (x_stationary) {
-        tm = xcd + 8 * (local / tiles_n);
-        tn = local % tiles_n;
-    } else {
-        tn = xcd + 8 * (local / tiles_m);
-        tm = local % tiles_m;
-    }
-    if (tn >= tiles_n || tm >= tiles_m) return;
+    int tn, tm;                 // XCD-aware tile order: the larger operand's tiles stay in one L2
+    if (!xcd_tile(tiles_m, tiles_n, x_stationary, tm, tn)) return;
     const int m_base = tm * BM, n_base = tn * BN;
 
     const u32x4 dx = raw_descriptor(Xv, (uint32_t)M * (uint32_t)K * 2u);
@@ -288,7 +279,7 @@ static hipError_t launch_pipe(const void* x, const bf16_t* wb, const float* bias
     if (k % (64 * KC) != 0 || k / (64 * KC) < NS - 1) return hipErrorNotSupported;
     const int tiles_m = (m + BM - 1) / BM, tiles_n = (n + BN - 1) / BN;
     const int xs = (int64_t)m > (int64_t)n;
-    const int grid = xs ? 8 * ((tiles_m + 7) / 8) * tiles_n : 8 * ((tiles_n + 7) / 8) * tiles_m;
+    const int grid = xcd_grid(tiles_m, tiles_n);
     const FoldIn fi{ni.stats, ni.u, ni.parts, ni.eps};
     const FoldOut fo{no.gain, static_cast<bf16_t*>(no.xg), no.stats};
 #define SD_GO(EPI, NF) return launch_pipe_kernel<EPI, WMV, WNV, TM, TN, NS, KC, NF>(grid, st, x, wb, bias, y, m, n, k, ldy, tiles_m, tiles_n, xs, fi, fo)
@@ -317,21 +308,24 @@ static hipError_t launch_pipe(const void* x, const bf16_t* wb, const float* bias
 #undef SD_GO
 }
 
-// Tile shape for a contraction, -1: leave it to the other kernels.  The ring pays off for a few hundred to a
-// couple of thousand rows against a wide weight matrix (the drafter's QKV and MLP-up layers, the batched target's):
-// the largest tile that still gives about 150 workgroups, i.e. one round of workgroups on most of the chip.
+// Tile shape for a contraction, -1: leave it to the other kernels.  The ring pays off for a few hundred to a couple of
+// thousand rows (the drafter's layers at batch 1, the batched target pass).  Every shape moves its operands from L2 to
+// the CU at about the same 24 bytes per clock and CU (deeper rings, more chunks per stage or requesting all operand
+// fragments of a stage at once change nothing), so what counts is bytes per CU: measured with the balanced XCD order,
+// K = 768 (1600 alike), a round of 64 x 64 tiles costs about 2.5 us and a round of 128 x 128 tiles about 5.4 us on top
+// of 3.6 us per launch; 64 x 64 workgroups share a CU two at a time (64 KB of LDS), 128 x 128 ones have it alone.  So:
+// the small tile while the 256 CUs hold all of them about twice, the large one after that; 64 x 128 tiles (one wave per
+// 32 columns) win nowhere.  When the small tiles fit the chip once, two chunks per stage (fewer waits and barriers) are
+// a little faster still -- 1056 x 768 x 3072 with the residual epilogue: 16.4 us against 20.0 for the wave-private quadrants.
 int linear_pipe_shape(int m, int n, int k) {
-    // narrow outputs, short K, around a thousand rows (the drafter's attention-output projection at a 1024-token prefix):
-    // 64 x 64 tiles, one chunk per stage (1056 x 768 x 768 with the residual / normalisation epilogue: 8.3 us against 10.4
-    // for the wave-private quadrants and 9.0 for the K-splitting few-row tiles; no gain at 544 or 4224 rows, nor at K = 3072)
-    if (n < 2048) return (m >= 800 && m <= 2048 && n >= 512 && k <= 1024 && k / 64 >= 5) ? 0 : -1;
     if (m < 192 || m > 2048 || k / 64 < 5) return -1;
-    for (int s = 2; s >= 0; --s) {
-        const PipeShape& p = kPipeShapes[s];
-        if ((long)((m + p.bm - 1) / p.bm) * ((n + p.bn - 1) / p.bn) >= 150)
-            return s < 2 && k % 128 == 0 ? s + 4 : s;       // the 64-row tiles: two chunks per stage when K allows
-    }
-    return -1;
+    const long t64 = (long)((m + 63) / 64) * ((n + 63) / 64), t128 = (long)((m + 127) / 128) * ((n + 127) / 128);
+    // narrow outputs: below about a thousand rows the wave-private quadrants with their K split inside the workgroup are
+    // faster (272 x 768 x 3072: 7.0 us against 12.5)
+    if (n < 2048) return (m >= 800 && n >= 512) ? (t64 <= 256 && k % 128 == 0 ? 4 : 0) : -1;
+    const double cost64 = 2.5 * (t64 <= 256 ? 1.0 : t64 / 256.0), cost128 = 5.4 * (double)((t128 + 255) / 256);
+    if (cost128 < cost64) return 2;
+    return t64 <= 256 && k % 128 == 0 ? 4 : 0;
 }
 
 // x bf16 [m, k], w bf16 [n, k]; same shape limits as the few-row kernel (linear_mfma_supported); ni / no as there.

@@ -17,6 +17,24 @@ constexpr int kBufFlags = 0x00020000;   // raw buffer, 32-bit data format (gfx9 
 // the host), and 2 GiB plus any in-matrix offset cannot wrap around 2^32.
 constexpr uint32_t kOutOfRange = 0x80000000u;
 
+// Workgroup -> tile for the contractions.  Workgroups are handed to the 8 XCDs round-robin by linear id and every XCD has
+// its own L2, so the tiles that share the larger operand are given to one XCD, back to back: the tile list, ordered by
+// that operand's tile index first (row tile when x is the larger operand, column tile when W is), is cut into eight
+// consecutive pieces of equal length, piece i for XCD i.  A tile of the larger operand then reaches one L2 (two where a
+// cut falls inside it) and every XCD has the same number of workgroups to within one -- dealing out whole row or column
+// tiles leaves XCDs with 3 against 2 of them (17 row tiles) or 5 against 4 (33).  The grid is xcd_grid() workgroups;
+// false: a padding workgroup.
+__device__ inline bool xcd_tile(int tiles_m, int tiles_n, int x_stationary, int& tm, int& tn) {
+    const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
+    const int total = tiles_m * tiles_n;
+    const int lin = xcd * total / 8 + local;
+    if (lin >= (xcd + 1) * total / 8) return false;
+    if (x_stationary) { tm = lin / tiles_n; tn = lin - tm * tiles_n; }
+    else { tn = lin / tiles_m; tm = lin - tn * tiles_m; }
+    return true;
+}
+inline int xcd_grid(int tiles_m, int tiles_n) { return 8 * ((tiles_m * tiles_n + 7) / 8); }
+
 // Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every global load in flight,
 // which would cut a prefetch that runs ahead of the barrier down to what one compute phase can hide; a stage
 // hand-over needs the LDS writes and reads alone.
