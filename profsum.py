@@ -1,8 +1,8 @@
 """Turn rocprofv3 CSV output into the short text summaries kept under profiles/.
 
-  python -m paper_2408_05636_amd.profsum kernels <dir-with-*_kernel_stats.csv> "<command that produced it>"
-  python -m paper_2408_05636_amd.profsum traffic <fetch-dir> <write-dir> <kernel-name-substring> <copy-bytes>
-  python -m paper_2408_05636_amd.profsum counters <dir-with-*_counter_collection.csv> "<command that produced it>"
+  python profsum.py kernels <dir-with-*_kernel_stats.csv> "<command that produced it>"
+  python profsum.py traffic <fetch-dir> <write-dir> <kernel-name-substring> <copy-bytes>
+  python profsum.py counters <dir-with-*_counter_collection.csv> "<command that produced it>"
 
 `counters` prints, per kernel, the mean over its dispatches of every counter of one --pmc run (ten largest kernels
 by dispatch count x first counter).  `traffic` reads the per-dispatch FETCH_SIZE / WRITE_SIZE counters (KiB) of two --pmc runs, scales

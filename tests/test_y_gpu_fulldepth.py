@@ -8,7 +8,7 @@ tails the configurations use) and the real vocabularies -- against the pure fp64
     plus one whole round replayed by the oracle's Algorithm 1 on the GPU's logits.
 
 The bf16 bound comes from the storage model on the same inputs (tests/helpers.py); measured maxima, rms errors and the
-model's sigma are written to gpurun_out/fulldepth_errors.json when that folder exists.  These tests take minutes of
+model's sigma are written to fulldepth_errors.json in the folder that SD_TEST_OUT names, when it is set.  These tests take minutes of
 host time (fp64 forwards of 1.5 and 8 billion parameters); they print a progress line per phase.
 """
 import json
@@ -40,16 +40,16 @@ class Progress:
         line = f"[fulldepth {time.perf_counter() - _T0:7.1f}s] {self.test}: {msg}"
         with self.capsys.disabled():
             print(line, flush=True)
-        d = os.path.join(ROOT, "gpurun_out")
-        if os.path.isdir(d):
+        d = os.environ.get("SD_TEST_OUT", "")
+        if d and os.path.isdir(d):
             with open(os.path.join(d, "fulldepth_progress.log"), "a") as f:
                 f.write(line + "\n")
 
     def record(self, stats):
         self(f"{stats['what']}: logit rms {stats['logit_rms']:.3f}, max err {stats['max_err']:.4f}, rms err {stats['rms_err']:.5f}, "
              f"storage-model sigma {stats['sigma_model']:.5f}, bound {stats['tol']:.4f}")
-        d = os.path.join(ROOT, "gpurun_out")
-        if os.path.isdir(d):
+        d = os.environ.get("SD_TEST_OUT", "")
+        if d and os.path.isdir(d):
             path = os.path.join(d, "fulldepth_errors.json")
             all_ = json.load(open(path)) if os.path.exists(path) else {}
             all_[f"{self.test}/{stats['what']}"] = stats
