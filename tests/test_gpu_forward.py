@@ -104,6 +104,17 @@ def test_few_query_rows_against_a_long_cache():
     check_forwards(t, d, [930], 40, 2, seed=22, steps=[1])
 
 
+def test_drafter_at_a_long_prefix():
+    """One sequence of ~790 and ~1024 rows at 12 heads of 64 (more (tile, head) workgroups than CUs, launched in the
+    balanced XCD order; an odd and an even tile count); two layers, so that the last layer's row-restricted tail
+    (attention, attention output and MLP on the block's rows only) is compared too."""
+    w = synth.workload("gpt2s")
+    t = synth.shrink(w["target"], n_layer=1, d_model=256, n_head=4, n_kv_head=4, d_ff=512, vocab=1200, n_ctx=1100)
+    d = synth.shrink(w["drafter"], n_layer=2, vocab=1200, n_ctx=1100)
+    check_forwards(t, d, [770], 18, 2, seed=31, steps=[1])     # 788 rows: 25 tiles
+    check_forwards(t, d, [1008], 16, 2, seed=32, steps=[2])    # 1024 rows: 32 tiles
+
+
 def test_gpt2_small_full_size():
     """The benchmark workload's shapes: 12 layers, d = 768, V = 50257, prefix 256, gamma 16."""
     w = synth.workload("gpt2s")
