@@ -504,7 +504,7 @@ static hipError_t launch_variant(const void* x, const void* w, const float* bias
     // fill the chip, keeping at least two chunks per wave, within the workspace.
     SplitArgs sk{nullptr, nullptr, 1, 0, no.y1, no.y2, no.c1, no.c2, no.ld12, no.rope_cs, no.rope_cols, no.rope_dh};
     if (no.y1 && (NT != 1 || epi != EPI_STORE)) return hipErrorInvalidValue;
-    sk.x_stationary = m > n;
+    sk.x_stationary = xcd_order(m, n, tiles_n);
     if constexpr (WM * WN == 1) {
         const long tiles = (long)tiles_n * tiles_m;
         const long part_floats = ws.base ? (ws.bytes - kSplitTicketBytes) / 4 : 0;

@@ -278,7 +278,7 @@ static hipError_t launch_pipe(const void* x, const bf16_t* wb, const float* bias
     constexpr int BM = 32 * TM * WMV, BN = 32 * TN * WNV;
     if (k % (64 * KC) != 0 || k / (64 * KC) < NS - 1) return hipErrorNotSupported;
     const int tiles_m = (m + BM - 1) / BM, tiles_n = (n + BN - 1) / BN;
-    const int xs = (int64_t)m > (int64_t)n;
+    const int xs = xcd_order(m, n, tiles_n);
     const int grid = xcd_grid(tiles_m, tiles_n);
     const FoldIn fi{ni.stats, ni.u, ni.parts, ni.eps};
     const FoldOut fo{no.gain, static_cast<bf16_t*>(no.xg), no.stats};

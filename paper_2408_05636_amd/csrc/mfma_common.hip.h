@@ -22,17 +22,29 @@ constexpr uint32_t kOutOfRange = 0x80000000u;
 // that operand's tile index first (row tile when x is the larger operand, column tile when W is), is cut into eight
 // consecutive pieces of equal length, piece i for XCD i.  A tile of the larger operand then reaches one L2 (two where a
 // cut falls inside it) and every XCD has the same number of workgroups to within one -- dealing out whole row or column
-// tiles leaves XCDs with 3 against 2 of them (17 row tiles) or 5 against 4 (33).  The grid is xcd_grid() workgroups;
-// false: a padding workgroup.
+// tiles leaves XCDs with 3 against 2 of them (17 row tiles) or 5 against 4 (33).
+// x_stationary: 0 -- W is the larger operand (column tile first); 1 -- x is (row tile first); 2 -- x is larger but W is
+// not small beside it: the columns form two groups, the list is group 0 row tile by row tile, then group 1, so an XCD
+// pulls half of W and a quarter of x into its L2 instead of all of W and an eighth of x.
+// The grid is xcd_grid() workgroups; false: a padding workgroup.
 __device__ inline bool xcd_tile(int tiles_m, int tiles_n, int x_stationary, int& tm, int& tn) {
     const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
     const int total = tiles_m * tiles_n;
-    const int lin = xcd * total / 8 + local;
+    int lin = xcd * total / 8 + local;
     if (lin >= (xcd + 1) * total / 8) return false;
-    if (x_stationary) { tm = lin / tiles_n; tn = lin - tm * tiles_n; }
-    else { tn = lin / tiles_m; tm = lin - tn * tiles_m; }
+    if (x_stationary == 0) { tn = lin / tiles_m; tm = lin - tn * tiles_m; return true; }
+    int c0 = 0, w = tiles_n;
+    if (x_stationary == 2) {
+        w = tiles_n / 2;
+        if (lin >= tiles_m * w) { lin -= tiles_m * w; c0 = w; w = tiles_n - w; }
+    }
+    tm = lin / w;
+    tn = c0 + lin - tm * w;
     return true;
 }
+// How to order the tiles of an m x n x k contraction (see xcd_tile): two column groups when both operands are of a size
+// (x fetched by two groups of XCDs and W by four costs less than x once and W eight times iff x < 4 W).
+inline int xcd_order(int64_t m, int64_t n, int tiles_n) { return m > n ? (tiles_n >= 2 && m < 4 * n ? 2 : 1) : 0; }
 inline int xcd_grid(int tiles_m, int tiles_n) { return 8 * ((tiles_m * tiles_n + 7) / 8); }
 
 // Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every global load in flight,
