@@ -265,6 +265,8 @@ def run_workload(name, a, torch, binding, synth, headline):
     log(f"{name}: {ms:.3f} ms per round, {res['tokens_per_s']:.1f} tok/s, roofline {roof_us:.0f} us")
     if name == "gpt2xl" and not (headline and a.greedy):
         res["sps"] = sps_comparison(sd, synth, binding, torch, w, flat, lens, steps, warmup, res)
+    if B == 1 and name != "tiny" and not a.no_autoregressive:
+        res["autoregressive"] = autoregressive_baseline(binding, torch, pair, w, prefixes, steps, warmup, res, alpha_paper, per_round)
     if not headline:
         sd.close()
         return res, None
@@ -281,6 +283,33 @@ def run_workload(name, a, torch, binding, synth, headline):
         torch.cuda.synchronize()
     ctx = dict(sd=sd, w=w, pair=pair, prefixes=prefixes, flat=flat, lens=lens, steps=steps, warmup=warmup, tokens=r["tokens"], ms=ms)
     return res, ctx
+
+
+def autoregressive_baseline(binding, torch, pair, w, prefixes, steps, warmup, res, alpha_paper, per_round_paper):
+    """Plain autoregressive decoding with the target alone, on the same kernels: the target is attached to a second handle
+    as the one-token-per-step model of sd_sps_draft (causal, incremental KV cache), which then produces tokens one forward
+    at a time from the same prefix.  The paper's speed-ups (Tables 2, 3) are quoted against this; reported here: time per
+    token, SpecDiff's tokens/s over it at the acceptance the random-init pair happens to have, and -- context only -- at an
+    acceptance rate the paper reports for a trained pair."""
+    t, d, gamma = w["target"], w["drafter"], w["gamma"]
+    n_tok = min(gamma, 16)
+    ar = binding.SpecDiff(t, d, None, None, max_batch=1, gamma_max=n_tok, device_weights=(pair.tw, pair.dw))
+    ar.sd_sps_attach(t, device_weights=pair.tw)
+    for i in range(warmup):
+        ar.sd_sps_draft(prefixes, n_tok, 100 + i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        ar.sd_sps_draft(prefixes, n_tok, 1000 + i)
+    torch.cuda.synchronize()
+    us = (time.perf_counter() - t0) / (steps * n_tok) * 1e6
+    ar.close()
+    out = {"us_per_token": us, "tokens_per_s": 1e6 / us, "tokens_per_call": n_tok,
+           "specdiff_over_autoregressive": res["tokens_per_s"] * us * 1e-6,
+           "context_only": {"alpha": alpha_paper, "specdiff_over_autoregressive": per_round_paper / (res["round_latency_us"] / us),
+                            "paper": "speed-ups over autoregressive decoding of 3.8-7.2x (T = 2, gamma 10-20, trained pairs, 2x A100-80GB)"}}
+    log(f"autoregressive decoding with the target alone: {us:.0f} us per token; SpecDiff / autoregressive = {out['specdiff_over_autoregressive']:.2f}")
+    return out
 
 
 def sps_comparison(sd, synth, binding, torch, w, flat, lens, steps, warmup, res):
@@ -405,6 +434,7 @@ def main():
     ap.add_argument("--no-accept-micro", action="store_true", help="leave out the micro-benchmark of the accept / residual-sampling kernels")
     ap.add_argument("--no-step-skipping", action="store_true", help="leave out the extra timed pass with sd_set_step_skipping")
     ap.add_argument("--no-extras", action="store_true", help="only the headline workload, not the other configurations")
+    ap.add_argument("--no-autoregressive", action="store_true", help="leave out the autoregressive-decoding reference (target alone, one token per forward)")
     ap.add_argument("--extras", default=",".join(EXTRA_WORKLOADS), help="comma-separated workloads reported under `configs`")
     ap.add_argument("--copy-probe", action="store_true", help="also launch one 64 MiB elementwise copy kernel, torch.neg (calibrates rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)")
     a = ap.parse_args()
@@ -452,7 +482,7 @@ def main():
                 continue
             r2, _ = run_workload(name, a, torch, binding, synth, headline=False)
             configs[name] = {k: r2[k] for k in ("workload", "round_latency_us", "tokens_per_s", "alpha_hat", "mean_accepted_per_round",
-                                                 "round_roofline_us", "roofline_parts", "frac_of_round_roofline", "sps") if k in r2}
+                                                 "round_roofline_us", "roofline_parts", "frac_of_round_roofline", "sps", "autoregressive") if k in r2}
 
     out = {
         "metric": "verified tokens/s", "value": res["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": ctx["steps"],
@@ -464,6 +494,7 @@ def main():
         "acceptance": res["acceptance"],
         "round_roofline_us": res["round_roofline_us"], "roofline_parts": res["roofline_parts"],
         "frac_of_round_roofline": res["frac_of_round_roofline"],
+        "autoregressive": res.get("autoregressive"),
         "roofline": roof, "cpu_baseline": cpu, "step_skipping": skipping, "accept_micro": micro, "phases": phases,
         "graph_replay": graphs, "configs": configs, "kernels": kernels,
     }
