@@ -267,6 +267,7 @@ struct MapSet {
     int rows = 0, n_tiles = 0, max_kv = 0;
     int head_row0 = -1;                  // first of the rows the LM head reads when they are one contiguous run, else -1
     int regular = 0;                     // one sequence whose rows all see all keys (AttnArgs::regular)
+    int causal_base = -1;                // one sequence at cache row 0 whose query row q sees causal_base + q keys, else -1
     int64_t kv_row0 = -1;                // target query rows of a single sequence: the KV-cache row of row 0 (row r goes to kv_row0 + r), else -1
     bool grouped = false;                // the attention launch order groups sequences per XCD (else it is the plain order)
     double kv_sum = 0, kv_rows = 0;     // sum of kv_len over rows; distinct key rows
@@ -641,6 +642,7 @@ int upload_rows(sd_handle* h, int mode, int batch, const int32_t* tokens, const 
     ms.rows = (int)rows; ms.n_tiles = (int)n_tiles; ms.max_kv = max_kv; ms.kv_sum = kv_sum; ms.kv_rows = kv_rows;
     ms.head_row0 = (mode == 1 || mode == 3) ? 0 : (mode == 0 && batch == 1 ? len[0] : -1);   // target, autoregressive step: all rows; drafter: the block of a single sequence
     ms.regular = mode == 0 && batch == 1;
+    ms.causal_base = batch == 1 && mode == 1 ? len[0] : (batch == 1 && mode == 3 ? len[0] + k : -1);
     ms.kv_row0 = (mode == 1 || mode == 3) && batch == 1 ? len[0] - 1 + k : -1;
     ms.grouped = grouped_order;
     ms.bytes = bytes;
@@ -814,7 +816,8 @@ int run_layers(sd_handle* h, const Model& m, const MapSet& rm, const float* temb
         a.out = at(B.att, d, m.ew); a.out_ld = d;
         a.rows = nr; a.n_head = c.n_head; a.n_kv_head = c.n_kv_head; a.d_head = m.dh; a.max_kv = rm.max_kv;
         a.tiles = rm.tiles; a.n_tiles = r0 ? (nr + 31) / 32 : rm.n_tiles;
-        a.regular = !cached && rm.regular;
+        a.regular = cached ? (rm.causal_base >= 0 ? 2 : 0) : (rm.regular ? 1 : 0);
+        a.kv_base = rm.causal_base;
         if (rm.grouped && !r0) { a.order = rm.order; a.n_order = rm.n_order; }      // the plain order needs no table (and no load of it)
         if (!r0) { a.groups = rm.groups; a.n_groups = rm.n_groups; a.group_tiles = rm.group_tiles; }
         if (cached) {

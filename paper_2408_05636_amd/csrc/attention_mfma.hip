@@ -84,8 +84,10 @@ __global__ __launch_bounds__(256, (DH == 64 ? 2 : 1)) void k_attention_mfma(Attn
     // rows and the first key / value block are then requested together (two dependent round trips in all;
     // one for a regular single sequence, whose tile needs no description).
     AttnTile tl;
-    if (a.regular) {
+    if (a.regular == 1) {
         tl.row0 = 32 * tile; tl.nrows = min(32, a.rows - 32 * tile); tl.kv_max = a.max_kv; tl.kv_off = 0;
+    } else if (a.regular == 2) {          // one sequence, causal: row q sees kv_base + q keys
+        tl.row0 = 32 * tile; tl.nrows = min(32, a.rows - 32 * tile); tl.kv_max = a.kv_base + tl.row0 + tl.nrows - 1; tl.kv_off = 0;
     } else {
         tl = a.tiles[tile];
     }
@@ -97,9 +99,11 @@ __global__ __launch_bounds__(256, (DH == 64 ? 2 : 1)) void k_attention_mfma(Attn
     bf16_t* vbase = const_cast<bf16_t*>(static_cast<const bf16_t*>(a.v)) + tl.kv_off + (size_t)g * DH;
     const __amdgpu_buffer_rsrc_t rk = __builtin_amdgcn_make_buffer_rsrc(kbase, 0, kv_bytes, kBufFlags);
     const __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc(vbase, 0, kv_bytes, kBufFlags);
-    const int kvl = a.regular ? a.max_kv : a.kv_len[qrow];
+    const int kvl = a.regular == 1 ? a.max_kv : (a.regular == 2 ? a.kv_base + qrow : a.kv_len[qrow]);
     int kv_min = kvl;                                    // smallest key count among the tile's rows (wave-uniform)
-    if (!a.regular) {
+    if (a.regular == 2) {
+        kv_min = a.kv_base + row0;
+    } else if (!a.regular) {
 #pragma unroll
         for (int o_ = 32; o_ > 0; o_ >>= 1) kv_min = min(kv_min, __shfl_xor(kv_min, o_, 64));
         kv_min = __builtin_amdgcn_readfirstlane(kv_min);

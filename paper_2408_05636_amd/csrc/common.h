@@ -150,9 +150,11 @@ struct AttnArgs {
     // group_tiles: the largest n (the variant is used from 2 on).
     const int32_t* groups = nullptr;
     int n_groups = 0, group_tiles = 0;
-    // One sequence whose rows all see all max_kv keys (the drafter at batch 1): tile t is rows 32 t .. of it, key offset
-    // 0.  The kernels then take nothing from tiles / kv_off / kv_len and save the round trip for them.
+    // 1: one sequence whose rows all see all max_kv keys (the drafter at batch 1): tile t is rows 32 t .. of it, key offset
+    // 0.  2: one sequence with causal visibility (the target's query rows at batch 1): row q sees its first kv_base + q
+    // keys.  The kernels then take nothing from tiles / kv_off / kv_len and save the round trip for them.
     int regular = 0;
+    int kv_base = 0;
 };
 // Rows row0 .. row0 + nrows - 1 (<= 32, all of one sequence); kv_max = largest kv_len among them;
 // kv_off = element offset of the sequence's key row 0 (the kv_off of its rows).
