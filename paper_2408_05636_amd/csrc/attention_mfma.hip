@@ -72,11 +72,17 @@ __global__ __launch_bounds__(256, (DH == 64 ? 2 : 1)) void k_attention_mfma(Attn
     const int r = lane & 31, half = lane >> 5;
     int tile = KSPLIT ? (int)blockIdx.x : (int)blockIdx.x * 4 + wave;
     int head = blockIdx.y;
-    if (KSPLIT && a.order != nullptr) {                 // XCD-aware launch order supplied by the host
-        const int ent = a.order[blockIdx.x];
-        if (ent < 0) return;                            // padding entry (whole workgroup)
-        tile = ent & 0xFFFFF;
-        head = ent >> 20;
+    if (KSPLIT && a.order != nullptr) {                 // XCD-aware launch order
+        if (a.regular) {
+            // one sequence, tiles of (nearly) equal work: the host's order is the list (head, tile) cut into eight equal
+            // pieces -- computed here instead of fetched, which takes a dependent load off the start of the kernel
+            if (!xcd_tile(a.n_tiles, a.n_head, 0, tile, head)) return;
+        } else {
+            const int ent = a.order[blockIdx.x];
+            if (ent < 0) return;                        // padding entry (whole workgroup)
+            tile = ent & 0xFFFFF;
+            head = ent >> 20;
+        }
     }
     if (!KSPLIT && tile >= a.n_tiles) return;           // whole wave; this variant has no barriers
 
@@ -469,7 +475,8 @@ hipError_t launch_attention_mfma(const AttnArgs& a, hipStream_t st, const char**
     // few tiles: the four waves of a workgroup share the key range of one tile.  (Eight waves per tile were measured too:
     // slower -- 256 registers per lane leave one workgroup per CU, and the chip then needs two rounds of them.)
     const int kw = (long)a.n_tiles * a.n_head < 1024 && a.max_kv > 64 ? 4 : 0;
-    const dim3 grid = kw ? (a.order ? dim3(a.n_order, 1) : dim3(a.n_tiles, a.n_head)) : dim3((a.n_tiles + 3) / 4, a.n_head);
+    const dim3 grid = kw ? (a.order ? dim3(a.regular ? xcd_grid(a.n_tiles, a.n_head) : a.n_order, 1) : dim3(a.n_tiles, a.n_head))
+                         : dim3((a.n_tiles + 3) / 4, a.n_head);
 #define SD_GO(DH, KW)                                                                                          \
     {                                                                                                          \
         if (kernel_name) *kernel_name = "k_attention_mfma<" #DH "," #KW ">";                                   \
